@@ -1,0 +1,337 @@
+"""Python face of the CPU oracle (oracle/alt_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the GPU library and its binding never
+do, and it never imports them.
+
+Layouts are primitive sequences exactly as in Table 1 of the paper (split,
+reorder, fuse), with 0-based dimension numbers; `paper_seq` converts the
+paper's 1-based notation.  Convolution and matrix product are computed on
+logical NCHW / OIHW / row-major arrays; other layouts are reached through
+`layout_transform`.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "alt_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, OpenMP over the outermost
+    independent loop).  Rebuilds when the source is newer than the library."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                           "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Prim(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("k", ctypes.c_int32), ("m", ctypes.c_int32),
+                ("pad_", ctypes.c_int32), ("v", ctypes.c_int64 * 8)]
+
+
+class _Conv(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w",
+                 "pad_h", "pad_w", "dil_h", "dil_w")] + \
+               [(n, ctypes.c_int32) for n in ("in_bf16", "out_bf16", "has_bias", "relu")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.orc_layout_offset.restype = ctypes.c_int64
+        L.orc_unfold_tiles.restype = ctypes.c_int64
+        L.orc_unfold_tiles.argtypes = [ctypes.c_int64] * 3
+        L.orc_conv_out_h.restype = ctypes.c_int64
+        L.orc_conv_out_w.restype = ctypes.c_int64
+        L.orc_f32_to_bf16.restype = ctypes.c_uint16
+        L.orc_f32_to_bf16.argtypes = [ctypes.c_float]
+        _lib = L
+    return _lib
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+# ---------------------------------------------------------------- layouts ----
+
+def split(k, factors):
+    return ("split", int(k), [int(f) for f in factors])
+
+
+def reorder(perm):
+    return ("reorder", [int(p) for p in perm])
+
+
+def fuse(k, m):
+    """Fuse the m dimensions k .. k+m-1."""
+    return ("fuse", int(k), int(m))
+
+
+def paper_seq(seq):
+    """Convert a sequence written as in the paper (1-based dims; fuse given as
+    the list of dims) to this module's 0-based form."""
+    out = []
+    for p in seq:
+        if p[0] == "split":
+            out.append(split(p[1] - 1, p[2]))
+        elif p[0] == "reorder":
+            out.append(reorder([q - 1 for q in p[1]]))
+        elif p[0] == "fuse":
+            dims = list(p[1])
+            assert dims == list(range(dims[0], dims[0] + len(dims)))
+            out.append(fuse(dims[0] - 1, len(dims)))
+        else:
+            raise ValueError(p)
+    return out
+
+
+def _pack(seq):
+    arr = (_Prim * max(1, len(seq)))()
+    for i, p in enumerate(seq):
+        if p[0] == "split":
+            arr[i].kind, arr[i].k, arr[i].m = 0, p[1], len(p[2])
+            for j, f in enumerate(p[2]):
+                arr[i].v[j] = f
+        elif p[0] == "reorder":
+            arr[i].kind, arr[i].k, arr[i].m = 1, 0, len(p[1])
+            for j, f in enumerate(p[1]):
+                arr[i].v[j] = f
+        elif p[0] == "fuse":
+            arr[i].kind, arr[i].k, arr[i].m = 2, p[1], p[2]
+        else:
+            raise ValueError(p)
+    return arr, len(seq)
+
+
+def _i64(a):
+    return (ctypes.c_int64 * len(a))(*[int(x) for x in a])
+
+
+def seq_from_string(name, shape):
+    """Primitive sequence for a layout written as dimension letters, e.g.
+    logical "NCHW" stored as "NHWC" or "NCHW16c", logical "OIHW" stored as
+    "OIHW16i32o", logical "MK" stored as "KM" or "MK64m32k".  `name` is
+    "LOGICAL->PHYSICAL".  Built the way Section 4.1.1 builds N(O/o_t)HWo_t:
+    one split per blocked dimension, then one reorder."""
+    logical, physical = name.split("->")
+    toks = []                     # (letter, factor or None), physical order
+    num = ""
+    for ch in physical:
+        if ch.isdigit():
+            num += ch
+        else:
+            toks.append((ch, int(num) if num else None))
+            num = ""
+    seq = []
+    cur = [(c, None) for c in logical]      # dims after the splits so far
+    for d, c in enumerate(logical):
+        inner = [t for t in toks if t[0] == c.lower() and t[1] is not None]
+        if not inner:
+            continue
+        assert len(inner) == 1, "one blocking level per dimension"
+        f = inner[0][1]
+        pos = cur.index((c, None))
+        assert shape[d] % f == 0
+        seq.append(split(pos, [shape[d] // f, f]))
+        cur[pos:pos + 1] = [(c, None), (c.lower(), f)]
+    perm = []
+    for t in toks:
+        key = (t[0], None) if t[0].isupper() else (t[0], t[1])
+        perm.append(cur.index(key))
+    assert sorted(perm) == list(range(len(cur))), (name, perm)
+    if perm != list(range(len(cur))):
+        seq.append(reorder(perm))
+    return seq
+
+
+def layout_shape(shape, seq):
+    arr, n = _pack(seq)
+    out = (ctypes.c_int64 * 12)()
+    r = lib().orc_layout_shape(len(shape), _i64(shape), arr, n, out)
+    if r < 0:
+        raise ValueError("bad primitive sequence")
+    return tuple(out[i] for i in range(r))
+
+
+def layout_index(shape, seq, idx):
+    """(transformed index tuple, row-major offset) of one logical index."""
+    arr, n = _pack(seq)
+    out = (ctypes.c_int64 * 12)()
+    off = lib().orc_layout_offset(len(shape), _i64(shape), arr, n, _i64(idx), out)
+    if off < 0:
+        raise ValueError("bad index or primitive sequence")
+    r = len(layout_shape(shape, seq))
+    return tuple(out[i] for i in range(r)), int(off)
+
+
+def layout_offsets(shape, seq):
+    """int64 array of logical `shape`: physical offset of every element."""
+    arr, n = _pack(seq)
+    out = np.empty(int(np.prod(shape)), dtype=np.int64)
+    rc = lib().orc_layout_offsets_all(len(shape), _i64(shape), arr, n,
+                                      out.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("bad primitive sequence")
+    return out.reshape(shape)
+
+
+def layout_transform(src, shape, seq_src, seq_dst):
+    """Conversion operator.  `src` is the flat physical buffer (uint16/uint32 or
+    any 2/4-byte dtype) of a tensor of logical `shape` stored under seq_src;
+    returns the flat physical buffer under seq_dst, same dtype."""
+    src = np.ascontiguousarray(src).reshape(-1)
+    assert src.size == int(np.prod(shape))
+    dst = np.empty_like(src)
+    a, na = _pack(seq_src)
+    b, nb = _pack(seq_dst)
+    rc = lib().orc_layout_transform(src.dtype.itemsize, len(shape), _i64(shape),
+                                    a, na, src.ctypes.data_as(ctypes.c_void_p),
+                                    b, nb, dst.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("layout_transform failed")
+    return dst
+
+
+# ----------------------------------------------------------------- unfold ----
+
+def unfold_tiles(D, B, S):
+    return int(lib().orc_unfold_tiles(D, B, S))
+
+
+def unfold_1d(src, B, S):
+    src = np.ascontiguousarray(src, dtype=np.float64)
+    T = unfold_tiles(src.size, B, S)
+    dst = np.empty((T, B), dtype=np.float64)
+    lib().orc_unfold_1d(src.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(src.size),
+                        ctypes.c_int64(B), ctypes.c_int64(S),
+                        dst.ctypes.data_as(ctypes.c_void_p))
+    return dst
+
+
+def unfold_access(V, i, r, B, S, M):
+    t, w = ctypes.c_int64(), ctypes.c_int64()
+    lib().orc_unfold_access(ctypes.c_int64(V), ctypes.c_int64(i), ctypes.c_int64(r),
+                            ctypes.c_int64(B), ctypes.c_int64(S), ctypes.c_int64(M),
+                            ctypes.byref(t), ctypes.byref(w))
+    return t.value, w.value
+
+
+# ------------------------------------------------------------- conv / gemm ----
+
+def f32_to_bf16_bits(x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    f = lib().orc_f32_to_bf16
+    return np.array([f(float(v)) for v in x.reshape(-1)], dtype=np.uint16).reshape(x.shape)
+
+
+def _conv_desc(x, w, stride, pad, dil, out_bf16, bias, relu):
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C2 == C
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dil, dil) if np.isscalar(dil) else dil
+    in_bf16 = x.dtype == np.uint16
+    assert (w.dtype == np.uint16) == in_bf16
+    d = _Conv(N, C, H, W, K, R, S, sh, sw, ph, pw, dh, dw,
+              int(in_bf16), int(out_bf16), int(bias is not None), int(relu))
+    return d
+
+
+def conv2d(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, relu=False):
+    """x: (N,C,H,W), w: (K,C,R,S); float32 arrays, or uint16 arrays of bf16
+    bits.  Returns (N,K,OH,OW) float32, or uint16 bf16 bits if out_bf16."""
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    d = _conv_desc(x, w, stride, pad, dil, out_bf16, bias, relu)
+    OH, OW = int(lib().orc_conv_out_h(ctypes.byref(d))), int(lib().orc_conv_out_w(ctypes.byref(d)))
+    y = np.empty((d.N, d.K, OH, OW), dtype=np.uint16 if out_bf16 else np.float32)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    rc = lib().orc_conv2d(ctypes.byref(d), x.ctypes.data_as(ctypes.c_void_p),
+                          w.ctypes.data_as(ctypes.c_void_p),
+                          None if b is None else b.ctypes.data_as(ctypes.c_void_p),
+                          y.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("conv2d: empty output")
+    return y
+
+
+def conv2d_at(x, w, flat, stride=1, pad=0, dil=1, bias=None, relu=False):
+    """Double-precision values of the outputs with flat (N,K,OH,OW) indices
+    `flat`."""
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    d = _conv_desc(x, w, stride, pad, dil, False, bias, relu)
+    flat = np.ascontiguousarray(flat, dtype=np.int64)
+    out = np.empty(flat.size, dtype=np.float64)
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    rc = lib().orc_conv2d_at(ctypes.byref(d), x.ctypes.data_as(ctypes.c_void_p),
+                             w.ctypes.data_as(ctypes.c_void_p),
+                             None if b is None else b.ctypes.data_as(ctypes.c_void_p),
+                             flat.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(flat.size),
+                             out.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("conv2d_at failed")
+    return out
+
+
+def conv_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
+    d = _Conv(*x_shape, w_shape[0], w_shape[2], w_shape[3], stride, stride, pad, pad, dil, dil,
+              0, 0, 0, 0)
+    return (x_shape[0], w_shape[0], int(lib().orc_conv_out_h(ctypes.byref(d))),
+            int(lib().orc_conv_out_w(ctypes.byref(d))))
+
+
+def gemm(A, B, out_bf16=False):
+    """A: (batch,M,K) or (M,K); B: (batch,K,N) or (K,N); float32 or uint16 bf16
+    bits.  Returns float32 (or uint16 bf16 bits) of shape (batch,M,N)/(M,N)."""
+    A = np.ascontiguousarray(A)
+    B = np.ascontiguousarray(B)
+    squeeze = A.ndim == 2
+    if squeeze:
+        A, B = A[None], B[None]
+    batch, M, K = A.shape
+    assert B.shape[0] == batch and B.shape[1] == K
+    N = B.shape[2]
+    in_bf16 = A.dtype == np.uint16
+    assert (B.dtype == np.uint16) == in_bf16
+    C = np.empty((batch, M, N), dtype=np.uint16 if out_bf16 else np.float32)
+    lib().orc_gemm(ctypes.c_int64(batch), ctypes.c_int64(M), ctypes.c_int64(N),
+                   ctypes.c_int64(K), int(in_bf16), int(out_bf16),
+                   A.ctypes.data_as(ctypes.c_void_p), B.ctypes.data_as(ctypes.c_void_p),
+                   C.ctypes.data_as(ctypes.c_void_p))
+    return C[0] if squeeze else C
+
+
+def gemm_at(A, B, flat):
+    A = np.ascontiguousarray(A)
+    B = np.ascontiguousarray(B)
+    if A.ndim == 2:
+        A, B = A[None], B[None]
+    batch, M, K = A.shape
+    N = B.shape[2]
+    in_bf16 = A.dtype == np.uint16
+    flat = np.ascontiguousarray(flat, dtype=np.int64)
+    out = np.empty(flat.size, dtype=np.float64)
+    lib().orc_gemm_at(ctypes.c_int64(batch), ctypes.c_int64(M), ctypes.c_int64(N),
+                      ctypes.c_int64(K), int(in_bf16),
+                      A.ctypes.data_as(ctypes.c_void_p), B.ctypes.data_as(ctypes.c_void_p),
+                      flat.ctypes.data_as(ctypes.c_void_p), ctypes.c_int64(flat.size),
+                      out.ctypes.data_as(ctypes.c_void_p))
+    return out

@@ -1,0 +1,238 @@
+"""Pins for the oracle's convolution, matrix product and bf16 rounding:
+brute-force loops written here, an independently written im2col product,
+closed forms (delta kernel, all-ones), exact-arithmetic properties (linearity,
+translation, stride sub-sampling) and library routines as special cases
+(numpy matmul, torch's float64 conv2d, torch's bf16 cast).  Expected values
+never come from the oracle itself."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import (bf16_bits_to_f32, f32_to_bf16_bits, normal_f32, small_ints_f32,
+                       uniform_f32)
+
+
+def _brute_conv(x, w, stride, pad, dil=1):
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    OH = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1
+    OW = (W + 2 * pad - dil * (S - 1) - 1) // stride + 1
+    y = np.zeros((N, K, OH, OW), dtype=np.float64)
+    for n, k, oh, ow in itertools.product(range(N), range(K), range(OH), range(OW)):
+        acc = 0.0
+        for c, r, s in itertools.product(range(C), range(R), range(S)):
+            ih, iw = oh * stride - pad + r * dil, ow * stride - pad + s * dil
+            if 0 <= ih < H and 0 <= iw < W:
+                acc += float(x[n, c, ih, iw]) * float(w[k, c, r, s])
+        y[n, k, oh, ow] = acc
+    return y
+
+
+def _im2col_conv(x, w, stride, pad):
+    """Separate formulation: gather patches into a matrix, one matmul."""
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=np.float64)
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    OH = (H + 2 * pad - R) // stride + 1
+    OW = (W + 2 * pad - S) // stride + 1
+    cols = np.empty((N, OH, OW, C, R, S), dtype=np.float64)
+    for r in range(R):
+        for s in range(S):
+            cols[:, :, :, :, r, s] = xp[:, :, r:r + stride * OH:stride, s:s + stride * OW:stride].transpose(0, 2, 3, 1)
+    out = cols.reshape(N * OH * OW, C * R * S) @ w.reshape(K, C * R * S).astype(np.float64).T
+    return out.reshape(N, OH, OW, K).transpose(0, 3, 1, 2)
+
+
+@pytest.mark.parametrize("stride,pad,dil", [(1, 1, 1), (2, 1, 1), (1, 0, 1), (2, 0, 1), (1, 2, 2), (3, 2, 1)])
+def test_conv_brute_force_tiny(oracle, stride, pad, dil):
+    x = uniform_f32(1, (2, 3, 6, 7))
+    w = uniform_f32(2, (4, 3, 3, 2))
+    want = _brute_conv(x, w, stride, pad, dil)
+    got = oracle.conv2d(x, w, stride=stride, pad=pad, dil=dil)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want.astype(np.float32))
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+def test_conv_vs_im2col_and_torch(oracle, stride, pad):
+    x = normal_f32(3, (2, 5, 9, 8))
+    w = normal_f32(4, (6, 5, 3, 3), std=0.05)
+    got = oracle.conv2d(x, w, stride=stride, pad=pad).astype(np.float64)
+    alt = _im2col_conv(x, w, stride, pad)
+    lib = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                     stride=stride, padding=pad).numpy()
+    scale = np.abs(lib).max()
+    assert np.abs(got - alt).max() <= 2e-7 * scale
+    assert np.abs(got - lib).max() <= 2e-7 * scale
+
+
+def test_conv_small_config_shape(oracle):
+    # the N=1, C=16, 14x14, K=16, 3x3 case: output keeps 14x14 with pad 1
+    x = uniform_f32(0xA18, (1, 16, 14, 14))
+    w = uniform_f32(0xA19, (16, 16, 3, 3))
+    y = oracle.conv2d(x, w, stride=1, pad=1)
+    assert y.shape == (1, 16, 14, 14)
+    assert np.abs(y - _im2col_conv(x, w, 1, 1)).max() < 1e-5
+
+
+def test_conv_delta_kernel_is_identity(oracle):
+    C = 5
+    x = uniform_f32(7, (2, C, 6, 6))
+    w = np.zeros((C, C, 3, 3), dtype=np.float32)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    assert np.array_equal(oracle.conv2d(x, w, stride=1, pad=1), x)
+    # a delta off centre shifts the image: y[h, w] = x[h-1, w+1], zero outside
+    w2 = np.zeros_like(w)
+    for c in range(C):
+        w2[c, c, 0, 2] = 1.0
+    y = oracle.conv2d(x, w2, stride=1, pad=1)
+    want = np.zeros_like(x)
+    want[:, :, 1:, :-1] = x[:, :, :-1, 1:]
+    assert np.array_equal(y, want)
+
+
+def test_conv_all_ones_counts_taps(oracle):
+    C, H, W, R, S, pad = 3, 5, 6, 3, 3, 1
+    x = np.ones((1, C, H, W), dtype=np.float32)
+    w = np.ones((2, C, R, S), dtype=np.float32)
+    y = oracle.conv2d(x, w, stride=1, pad=pad)
+    for oh in range(H):
+        for ow in range(W):
+            rows = sum(0 <= oh - pad + r < H for r in range(R))
+            cols = sum(0 <= ow - pad + s < W for s in range(S))
+            assert y[0, 0, oh, ow] == C * rows * cols
+            assert y[0, 1, oh, ow] == C * rows * cols
+
+
+def test_conv_linearity_exact(oracle):
+    x1 = small_ints_f32(8, (2, 4, 7, 7))
+    x2 = small_ints_f32(9, (2, 4, 7, 7))
+    w = small_ints_f32(10, (3, 4, 3, 3))
+    a = 4.0
+    lhs = oracle.conv2d(a * x1 + x2, w, stride=1, pad=1)
+    rhs = a * oracle.conv2d(x1, w, stride=1, pad=1) + oracle.conv2d(x2, w, stride=1, pad=1)
+    assert np.array_equal(lhs, rhs)
+
+
+def test_conv_stride2_is_subsampled_stride1(oracle):
+    x = small_ints_f32(12, (1, 3, 9, 9))
+    w = small_ints_f32(13, (2, 3, 3, 3))
+    y1 = oracle.conv2d(x, w, stride=1, pad=1)
+    y2 = oracle.conv2d(x, w, stride=2, pad=1)
+    assert np.array_equal(y2, y1[:, :, ::2, ::2])
+
+
+def test_conv_translation(oracle):
+    x = small_ints_f32(14, (1, 2, 8, 8))
+    w = small_ints_f32(15, (2, 2, 3, 3))
+    xs = np.zeros_like(x)
+    xs[:, :, :, 1:] = x[:, :, :, :-1]                 # shift right by one pixel
+    y, ys = oracle.conv2d(x, w, pad=1), oracle.conv2d(xs, w, pad=1)
+    # columns whose windows never see the pixel column that fell off the right edge
+    assert np.array_equal(ys[:, :, :, 1:-1], y[:, :, :, :-2])
+
+
+def test_conv_1x1_is_matrix_product(oracle):
+    N, C, H, W, K = 2, 6, 4, 5, 3
+    x = small_ints_f32(16, (N, C, H, W))
+    w = small_ints_f32(17, (K, C, 1, 1))
+    y = oracle.conv2d(x, w)
+    A = x.transpose(0, 2, 3, 1).reshape(N * H * W, C)
+    want = (A.astype(np.float64) @ w.reshape(K, C).T.astype(np.float64)).reshape(N, H, W, K).transpose(0, 3, 1, 2)
+    assert np.array_equal(y, want.astype(np.float32))
+    # and the two oracles agree with each other through that identity
+    g = oracle.gemm(A, np.ascontiguousarray(w.reshape(K, C).T))
+    assert np.array_equal(g.reshape(N, H, W, K).transpose(0, 3, 1, 2), y)
+
+
+def test_conv_bias_relu_and_bf16(oracle):
+    x = f32_to_bf16_bits(normal_f32(18, (2, 8, 6, 6)))
+    w = f32_to_bf16_bits(normal_f32(19, (4, 8, 3, 3), std=0.05))
+    b = normal_f32(20, (4,), std=0.1)
+    xf, wf = bf16_bits_to_f32(x), bf16_bits_to_f32(w)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(xf).double(), torch.from_numpy(wf).double(),
+                                     torch.from_numpy(b).double(), padding=1).clamp_min(0).numpy()
+    y32 = oracle.conv2d(x, w, pad=1, bias=b, relu=True)
+    assert np.abs(y32 - ref).max() <= 1e-6 * np.abs(ref).max()
+    assert (y32 >= 0).all() and (y32 == 0).any()
+    y16 = oracle.conv2d(x, w, pad=1, bias=b, relu=True, out_bf16=True)
+    want16 = torch.from_numpy(y32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(y16, want16)
+
+
+def test_conv_at_matches_full(oracle):
+    x = normal_f32(21, (2, 4, 6, 6))
+    w = normal_f32(22, (5, 4, 3, 3))
+    full = _im2col_conv(x, w, 2, 1)
+    flat = np.array([0, 7, 13, full.size - 1, 29])
+    got = oracle.conv2d_at(x, w, flat, stride=2, pad=1)
+    assert np.allclose(got, full.reshape(-1)[flat], rtol=1e-12, atol=1e-12)
+
+
+# -------------------------------------------------------------------- gemm ----
+
+def test_gemm_identity_and_permutation(oracle):
+    A = uniform_f32(30, (7, 9))
+    assert np.array_equal(oracle.gemm(A, np.eye(9, dtype=np.float32)), A)
+    perm = np.array([3, 0, 8, 1, 7, 2, 6, 4, 5])
+    P = np.zeros((9, 9), dtype=np.float32)
+    P[perm, np.arange(9)] = 1.0
+    assert np.array_equal(oracle.gemm(A, P), A[:, perm])
+
+
+def test_gemm_vs_numpy_and_transpose_rule(oracle):
+    A = normal_f32(31, (13, 17))
+    B = normal_f32(32, (17, 11))
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    got = oracle.gemm(A, B)
+    assert np.array_equal(got, want.astype(np.float32)) or np.abs(got - want).max() < 1e-6
+    gt = oracle.gemm(np.ascontiguousarray(B.T), np.ascontiguousarray(A.T))
+    assert np.abs(gt.T - got).max() <= 1e-6
+
+
+def test_gemm_non_square_catches_transposed_operand(oracle):
+    A = small_ints_f32(33, (3, 5))
+    B = small_ints_f32(34, (5, 4))
+    want = np.zeros((3, 4))
+    for m, n, k in itertools.product(range(3), range(4), range(5)):
+        want[m, n] += A[m, k] * B[k, n]
+    assert np.array_equal(oracle.gemm(A, B), want.astype(np.float32))
+
+
+def test_gemm_batched_is_loop_of_singles(oracle):
+    A = normal_f32(35, (4, 6, 8))
+    B = normal_f32(36, (4, 8, 5))
+    C = oracle.gemm(A, B)
+    for b in range(4):
+        assert np.array_equal(C[b], oracle.gemm(A[b], B[b]))
+        assert np.abs(C[b] - A[b].astype(np.float64) @ B[b].astype(np.float64)).max() < 1e-6
+
+
+def test_gemm_bf16_inputs_and_at(oracle):
+    A = f32_to_bf16_bits(normal_f32(37, (9, 32), std=0.02))
+    B = f32_to_bf16_bits(normal_f32(38, (32, 6), std=0.02))
+    want = bf16_bits_to_f32(A).astype(np.float64) @ bf16_bits_to_f32(B).astype(np.float64)
+    got = oracle.gemm(A, B)
+    assert np.array_equal(got, want.astype(np.float32))
+    at = oracle.gemm_at(A, B, np.array([0, 5, 53]))
+    assert np.allclose(at, want.reshape(-1)[[0, 5, 53]], rtol=1e-13, atol=0)
+
+
+# -------------------------------------------------------------------- bf16 ----
+
+def test_bf16_rounding_matches_library_cast(oracle):
+    v = np.concatenate([normal_f32(40, (4000,)), np.array(
+        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40, -1e-40, np.inf, -np.inf],
+        dtype=np.float32)])
+    want = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.f32_to_bf16_bits(v), want)
+    assert np.array_equal(f32_to_bf16_bits(v), want)          # the input generator's rounding too
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert oracle.f32_to_bf16_bits(np.array([1.00390625], dtype=np.float32))[0] == 0x3F80
+    assert oracle.f32_to_bf16_bits(np.array([1.01171875], dtype=np.float32))[0] == 0x3F82
+    nan = oracle.f32_to_bf16_bits(np.array([np.nan], dtype=np.float32))[0]
+    assert (nan & 0x7F80) == 0x7F80 and (nan & 0x7F) != 0
