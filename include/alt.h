@@ -1,0 +1,331 @@
+/*
+ * alt.h — C ABI of the MI355X (gfx950) tensor-operator library: 2-D
+ * convolution and matrix multiplication executed under explicit tensor data
+ * layouts, the layout conversion operator, and an on-device tuner over
+ * {layout, kernel tile configuration}.
+ *
+ * The operations follow "ALT: Breaking the Wall between Graph and Operator
+ * Level Optimizations for Deep Learning Compilation" (arXiv 2210.12415);
+ * every entry point cites the passage that defines what it computes.
+ *
+ * Conventions
+ *  - Plain C.  Every call returns alt_status_t; 0 is success.  No exception
+ *    crosses the boundary.  alt_last_error(h) returns a string owned by the
+ *    handle, valid until the next call on that handle.
+ *  - "device pointer" = memory of the GPU that was current when the handle was
+ *    created.  The caller owns every tensor buffer, the workspace and the
+ *    stream.  `stream` is a hipStream_t passed as void* (NULL = default
+ *    stream).  Calls that take a stream only enqueue work on it and return;
+ *    the alt_tune_* calls synchronise.
+ *  - The library never allocates device memory: split-K partial sums live in
+ *    the caller's workspace, the tuner's scratch tensors in the caller's arena.
+ *  - Tensors are addressed through a *logical* index and a layout.  Logical
+ *    dimension order is fixed per operand: activations (N, C, H, W), weights
+ *    (O, I, H, W) = (K, C, R, S), outputs (N, K, OH, OW); matrices A (M, K),
+ *    B (K, N), C (M, N), with an optional dense outermost batch.
+ *  - Element types: ALT_F32 (IEEE binary32) and ALT_BF16 (bfloat16 bit
+ *    patterns in 16-bit words).  Products are accumulated in fp32.
+ */
+#ifndef ALT_H_
+#define ALT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default)   /* the entry points below are the library's only exports */
+#endif
+
+typedef enum {
+    ALT_OK = 0,
+    ALT_INVALID_ARG = 1,          /* null pointer, bad enum, non-positive size */
+    ALT_INVALID_LAYOUT = 2,       /* unparsable string / malformed primitive */
+    ALT_SHAPE_MISMATCH = 3,       /* layout does not tile the given shape exactly */
+    ALT_UNSUPPORTED = 4,          /* valid request no kernel covers */
+    ALT_WORKSPACE_TOO_SMALL = 5,
+    ALT_HIP_ERROR = 6,            /* a HIP runtime call failed; see alt_last_error */
+    ALT_NOT_TUNED = 7             /* cache lookup found no entry */
+} alt_status_t;
+
+typedef enum { ALT_F32 = 0, ALT_BF16 = 1 } alt_dtype_t;
+
+typedef struct alt_context *alt_handle_t;
+
+#define ALT_MAX_RANK 8            /* most logical or physical dimensions */
+#define ALT_MAX_PRIMS 8           /* longest primitive sequence kept */
+
+/* ---- layout primitives (Table 1 of the paper) --------------------------- */
+
+typedef enum { ALT_PRIM_SPLIT = 0, ALT_PRIM_REORDER = 1, ALT_PRIM_FUSE = 2 } alt_prim_kind_t;
+
+/* One primitive.  Dimension numbers are 0-based (the paper's examples count
+ * from 1).
+ *   SPLIT  : dimension `dim` becomes `count` dimensions with extents
+ *            v[0..count-1], outermost first; their product must equal the
+ *            extent being split.
+ *   REORDER: count = current rank; new dimension j is old dimension v[j].
+ *   FUSE   : dimensions dim .. dim+count-1 become one (row-major). */
+typedef struct {
+    int32_t kind;
+    int32_t dim;
+    int32_t count;
+    int32_t reserved;
+    int64_t v[ALT_MAX_RANK];
+} alt_prim_t;
+
+/* A layout: where each logical index lives in memory.  Plain data, copied by
+ * value, no pointers.
+ *
+ * Separable form (separable = 1): the physical dimensions, outermost first,
+ * are `nsub` pieces; piece j takes digit (i[sub_dim[j]] / sub_div[j]) mod
+ * sub_extent[j] of one logical index.  sub_extent = 0 means "the rest": the
+ * logical extent divided by sub_div (the outermost piece of that dimension).
+ * Pieces with the same sub_group were fused into one physical dimension.
+ * Every layout that alt_layout_parse accepts, and every split/reorder
+ * sequence, has this form.
+ *
+ * General form (separable = 0): a sequence containing a fuse that is later
+ * split across the old dimension boundaries (the N(O/4)(HW)4 example of
+ * Section 4.1.1).  Only `prims`/`shape` describe it; it is bound to that
+ * shape.  Index math and the conversion operator accept it; conv and gemm do
+ * not. */
+typedef struct {
+    int32_t ndim;                         /* logical rank */
+    int32_t nsub;                         /* number of pieces (separable form) */
+    int32_t separable;
+    int32_t nprims;                       /* > 0 only when built from primitives */
+    int32_t sub_dim[ALT_MAX_RANK];
+    int32_t sub_group[ALT_MAX_RANK];
+    int64_t sub_div[ALT_MAX_RANK];
+    int64_t sub_extent[ALT_MAX_RANK];
+    int64_t shape[ALT_MAX_RANK];          /* logical shape the primitives were given for */
+    alt_prim_t prims[ALT_MAX_PRIMS];
+} alt_layout_t;
+
+/* ---- lifecycle ----------------------------------------------------------- */
+
+/* Creates a handle bound to the current HIP device.  With no usable GPU the
+ * handle is still created (layout index math and argument checking work) and
+ * every call that would launch a kernel returns ALT_HIP_ERROR. */
+alt_status_t alt_create(alt_handle_t *out);
+alt_status_t alt_destroy(alt_handle_t h);
+const char *alt_last_error(alt_handle_t h);
+const char *alt_status_string(alt_status_t s);
+/* Library version, "major.minor". */
+const char *alt_version(void);
+
+/* ---- layouts: index math (Table 1; worked sequences of Section 4.1.1) ---- */
+
+/* Parses "LOGICAL->PHYSICAL", e.g. "NCHW->NHWC", "NCHW->NCHW16c",
+ * "OIHW->OIHW16i32o", "OIHW->OHWI", "MK->KM", "KN->KN64k32n".  Upper-case
+ * letters name logical dimensions; in PHYSICAL an upper-case letter is the
+ * outermost piece of that dimension and <factor><lower-case letter> an inner
+ * block of that extent, exactly the N(O/o_t)HWo_t notation of the paper.  The
+ * result is shape-independent. */
+alt_status_t alt_layout_parse(const char *text, alt_layout_t *out);
+
+/* Builds a layout from a primitive sequence applied to a tensor of logical
+ * `shape` (host pointers).  At most ALT_MAX_PRIMS primitives and ALT_MAX_RANK
+ * dimensions at any point of the sequence. */
+alt_status_t alt_layout_from_prims(int ndim, const int64_t *shape, const alt_prim_t *seq,
+                                   int nseq, alt_layout_t *out);
+
+/* Physical shape of a tensor of logical `shape` under `l`; out_shape must
+ * hold ALT_MAX_RANK entries.  ALT_SHAPE_MISMATCH if a block factor does not
+ * divide its dimension. */
+alt_status_t alt_layout_physical_shape(const alt_layout_t *l, const int64_t *shape,
+                                       int64_t *out_shape, int *out_rank);
+
+/* Element offset (row-major under the physical shape) of logical index `idx`. */
+alt_status_t alt_layout_offset(const alt_layout_t *l, const int64_t *shape, const int64_t *idx,
+                               int64_t *out_offset);
+
+/* Inverse map: logical index stored at physical element offset `offset`. */
+alt_status_t alt_layout_index_of(const alt_layout_t *l, const int64_t *shape, int64_t offset,
+                                 int64_t *out_idx);
+
+/* ---- layout conversion operator (Section 4.2, first way of Fig. 5) ------ */
+
+/* dst[off_dst(i)] = src[off_src(i)] for every logical index i of a tensor of
+ * logical `shape` (host pointer, `ndim` entries).  src and dst are device
+ * pointers to numel elements each and must not overlap.  Bits are moved
+ * unchanged.  Asynchronous on `stream`. */
+alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape,
+                                  const alt_layout_t *src_layout, const void *src,
+                                  const alt_layout_t *dst_layout, void *dst, void *stream);
+
+/* ---- C2D (program of Fig. 3; zero padding as in Section 4.2; fused bias and
+ *      ReLU as in Fig. 6; producer writes the consumer's layout, Section 4.2) */
+
+#define ALT_EPI_BIAS 1            /* y += bias[k], bias is fp32[K] on the device */
+#define ALT_EPI_RELU 2            /* y = max(y, 0) after the bias */
+
+typedef struct {
+    int64_t N, C, H, W;           /* input activations */
+    int64_t K, R, S;              /* output channels, kernel height, width */
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t in_dtype;             /* alt_dtype_t of x and w */
+    int32_t out_dtype;            /* alt_dtype_t of y (bf16 = fp32 sum rounded to nearest even) */
+    int32_t epilogue;             /* ALT_EPI_* flags */
+    int32_t variant;              /* kernel variant; -1 = cached tuned one, else the default */
+    alt_layout_t x_layout;        /* of logical (N, C, H, W) */
+    alt_layout_t w_layout;        /* of logical (K, C, R, S) */
+    alt_layout_t y_layout;        /* of logical (N, K, OH, OW) */
+} alt_conv_desc_t;
+
+/* y[n,k,oh,ow] = sum_{c,r,s} x[n,c,oh*stride-pad+r*dil, ow*stride-pad+s*dil] * w[k,c,r,s]
+ * (cross-correlation, zeros outside the input), OH = floor((H+2pad-dil(R-1)-1)/stride)+1.
+ * x, w, y are device pointers holding the tensors under the descriptor's
+ * layouts; `w` is what alt_pack_weights wrote (or any buffer already in
+ * w_layout).  bias may be NULL without ALT_EPI_BIAS.  `workspace` (device,
+ * ws_bytes) must be at least alt_conv2d_workspace_size for the variant used.
+ * Asynchronous on `stream`. */
+alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
+                        const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
+alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
+alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw);
+
+/* Offline weight transformation (Section 4.2: the weight tensor is a constant,
+ * so its layout is changed once, outside the timed path): dense OIHW ->
+ * d->w_layout.  Device pointers, asynchronous on `stream`. */
+alt_status_t alt_pack_weights(alt_handle_t h, const alt_conv_desc_t *d, const void *w_oihw,
+                              void *w_packed, void *stream);
+
+/* Kernel variants applicable to a descriptor (loop-tuning space of Section
+ * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and
+ * operand loader).  Variant numbers are stable within one library build. */
+alt_status_t alt_conv2d_variant_count(alt_handle_t h, const alt_conv_desc_t *d, int *count);
+alt_status_t alt_conv2d_variant_name(alt_handle_t h, const alt_conv_desc_t *d, int variant,
+                                     char *buf, size_t buflen);
+
+/* ---- GMM (Section 5.1: C = A B with per-operand layouts) ----------------- */
+
+typedef struct {
+    int64_t batch, M, N, K;       /* batch >= 1; operands of one batch entry are dense, batch outermost */
+    int32_t in_dtype, out_dtype;
+    int32_t variant;              /* -1 = cached tuned one, else the default */
+    int32_t reserved;
+    alt_layout_t a_layout;        /* of logical (M, K) */
+    alt_layout_t b_layout;        /* of logical (K, N); "KN->NK" is a transposed operand */
+    alt_layout_t c_layout;        /* of logical (M, N) */
+} alt_gemm_desc_t;
+
+/* C[b,m,n] = sum_k A[b,m,k] * B[b,k,n].  Device pointers; asynchronous. */
+alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B,
+                      void *C, void *workspace, size_t ws_bytes, void *stream);
+alt_status_t alt_gemm_workspace_size(alt_handle_t h, const alt_gemm_desc_t *d, size_t *bytes);
+alt_status_t alt_gemm_variant_count(alt_handle_t h, const alt_gemm_desc_t *d, int *count);
+alt_status_t alt_gemm_variant_name(alt_handle_t h, const alt_gemm_desc_t *d, int variant,
+                                   char *buf, size_t buflen);
+
+/* ---- joint tuning (Section 5.2: cross exploration — pick a layout, tune the
+ *      loops under it, feed the best latency back; budget counted in on-device
+ *      measurements as in Section 6) --------------------------------------- */
+
+typedef struct {
+    int32_t max_trials;           /* measurement budget; <= 0 = unlimited */
+    int32_t warmup;               /* untimed launches per measurement (default 3) */
+    int32_t reps;                 /* timed launches per measurement (default 20) */
+    int32_t layout_mask;          /* bit i enables layout candidate i; 0 = all */
+    void *arena;                  /* device scratch for the tuner's tensors */
+    size_t arena_bytes;
+    void *stream;
+} alt_tune_opts_t;
+
+#define ALT_MAX_CANDIDATES 16
+
+typedef struct {
+    int32_t trials;               /* measurements actually run */
+    int32_t n_layouts;            /* layout candidates explored */
+    float best_us;                /* latency of the winner */
+    float default_us;             /* best latency under the default layouts (NCHW/OIHW, row-major) */
+    float layout_best_us[ALT_MAX_CANDIDATES];   /* the reward of each layout: its best latency */
+    int32_t layout_best_variant[ALT_MAX_CANDIDATES];
+    char layout_name[ALT_MAX_CANDIDATES][48];
+} alt_tune_report_t;
+
+/* Required arena size for the tune calls below. */
+alt_status_t alt_tune_conv2d_arena_size(alt_handle_t h, const alt_conv_desc_t *shape, size_t *bytes);
+alt_status_t alt_tune_gemm_arena_size(alt_handle_t h, const alt_gemm_desc_t *shape, size_t *bytes);
+
+/* Explores layout candidates x kernel variants for the problem in `shape`
+ * (its layouts and variant are ignored), writes the winner (layouts + variant
+ * filled in) to best_out, remembers it in the handle's cache so that later
+ * alt_conv2d / alt_gemm calls with variant = -1 on the same problem and
+ * layouts use the tuned variant.  Synchronises. */
+alt_status_t alt_tune_conv2d(alt_handle_t h, const alt_conv_desc_t *shape, const alt_tune_opts_t *opts,
+                             alt_conv_desc_t *best_out, alt_tune_report_t *report);
+alt_status_t alt_tune_gemm(alt_handle_t h, const alt_gemm_desc_t *shape, const alt_tune_opts_t *opts,
+                           alt_gemm_desc_t *best_out, alt_tune_report_t *report);
+
+/* Loop-only stage (Section 5.2): layouts in `d` are kept, only the kernel
+ * variant is searched; the winner is written to d->variant and cached. */
+alt_status_t alt_tune_conv2d_variants(alt_handle_t h, alt_conv_desc_t *d, const alt_tune_opts_t *opts,
+                                      float *best_us, int *trials);
+
+#define ALT_MAX_CHAIN 8
+
+typedef struct {
+    int32_t nops;
+    int32_t trials;
+    alt_conv_desc_t op[ALT_MAX_CHAIN];        /* chosen layouts and variant per operator */
+    int32_t transform_before[ALT_MAX_CHAIN];  /* 1: a conversion operator feeds op i's input */
+    alt_layout_t edge_layout[ALT_MAX_CHAIN + 1]; /* layout the producer writes on edge i (edge 0 = chain input) */
+    float op_us[ALT_MAX_CHAIN];
+    float transform_us[ALT_MAX_CHAIN];
+    float total_us;                           /* planned end-to-end latency */
+    float default_total_us;                   /* same chain with NCHW on every edge */
+} alt_chain_plan_t;
+
+/* Graph-level choice for a chain of convolutions (Section 4.2, third
+ * constraint: each complex operator is tuned on its own and a conversion
+ * operator is inserted between two of them only where their layouts differ).
+ * ops[i+1] consumes ops[i]'s output; the chain input arrives in `in_layout`
+ * and the last output leaves in the layout the last operator prefers.
+ * Measures every operator under every (input, output) layout pair and every
+ * conversion, then takes the cheapest path.  Synchronises. */
+alt_status_t alt_tune_chain(alt_handle_t h, const alt_conv_desc_t *ops, int nops,
+                            const alt_layout_t *in_layout, const alt_tune_opts_t *opts,
+                            alt_chain_plan_t *plan);
+
+/* Pure planner behind alt_tune_chain (host only, no device work): given
+ * op_cost[i][a][b] = latency of operator i reading layout a and writing layout
+ * b (row-major [nops][nl][nl]), conv_cost[i][a][b] = latency of converting
+ * edge i from a to b ([nops][nl][nl], zero on the diagonal) and the layout
+ * index the chain input arrives in, returns per operator the (input, output)
+ * layout indices of the cheapest plan and its total cost. */
+alt_status_t alt_plan_chain(int nops, int nl, const float *op_cost, const float *conv_cost,
+                            int in_layout, int *out_in_idx, int *out_out_idx, float *out_total);
+
+/* Tune cache persistence: text file, one line per entry keyed by problem,
+ * dtype, layouts and the device architecture name. */
+alt_status_t alt_cache_save(alt_handle_t h, const char *path);
+alt_status_t alt_cache_load(alt_handle_t h, const char *path);
+alt_status_t alt_cache_clear(alt_handle_t h);
+
+/* ---- introspection -------------------------------------------------------- */
+
+typedef struct {
+    float copy_gbps;              /* measured large streaming copy, read+write bytes per second / 1e9 */
+    float mfma_bf16_tflops;       /* measured register-resident bf16 MFMA loop */
+    float nominal_hbm_gbps;       /* 8000 */
+    float nominal_bf16_tflops;    /* 2500 */
+    int32_t compute_units;
+    int32_t clock_mhz;
+    char arch[32];
+} alt_peaks_t;
+
+/* Measures attainable peaks on the handle's device using `arena` (device,
+ * >= 512 MiB recommended) as copy buffer.  Synchronises. */
+alt_status_t alt_get_peak(alt_handle_t h, void *arena, size_t arena_bytes, alt_peaks_t *out);
+
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALT_H_ */

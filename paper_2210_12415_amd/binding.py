@@ -1,0 +1,362 @@
+"""ctypes marshalling for libalt.so.  Function names follow include/alt.h."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "libalt.so")
+
+F32, BF16 = 0, 1
+EPI_BIAS, EPI_RELU = 1, 2
+MAX_RANK, MAX_PRIMS, MAX_CAND, MAX_CHAIN = 8, 8, 16, 8
+
+_STATUS = ["ok", "invalid argument", "invalid layout", "shape mismatch", "unsupported",
+           "workspace too small", "HIP error", "not tuned"]
+
+
+class AltError(RuntimeError):
+    def __init__(self, status, msg=""):
+        self.status = status
+        name = _STATUS[status] if 0 <= status < len(_STATUS) else str(status)
+        super().__init__("%s%s" % (name, (": " + msg) if msg else ""))
+
+
+class Prim(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("dim", ctypes.c_int32), ("count", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("v", ctypes.c_int64 * MAX_RANK)]
+
+
+def split(dim, factors):
+    p = Prim(0, dim, len(factors), 0)
+    for i, f in enumerate(factors):
+        p.v[i] = f
+    return p
+
+
+def reorder(perm):
+    p = Prim(1, 0, len(perm), 0)
+    for i, f in enumerate(perm):
+        p.v[i] = f
+    return p
+
+
+def fuse(dim, count):
+    return Prim(2, dim, count, 0)
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("ndim", ctypes.c_int32), ("nsub", ctypes.c_int32), ("separable", ctypes.c_int32),
+                ("nprims", ctypes.c_int32),
+                ("sub_dim", ctypes.c_int32 * MAX_RANK), ("sub_group", ctypes.c_int32 * MAX_RANK),
+                ("sub_div", ctypes.c_int64 * MAX_RANK), ("sub_extent", ctypes.c_int64 * MAX_RANK),
+                ("shape", ctypes.c_int64 * MAX_RANK), ("prims", Prim * MAX_PRIMS)]
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("N", "C", "H", "W", "K", "R", "S")] + \
+               [(n, ctypes.c_int32) for n in ("stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
+                                              "in_dtype", "out_dtype", "epilogue", "variant")] + \
+               [("x_layout", Layout), ("w_layout", Layout), ("y_layout", Layout)]
+
+
+class GemmDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("batch", "M", "N", "K")] + \
+               [(n, ctypes.c_int32) for n in ("in_dtype", "out_dtype", "variant", "reserved")] + \
+               [("a_layout", Layout), ("b_layout", Layout), ("c_layout", Layout)]
+
+
+class TuneOpts(ctypes.Structure):
+    _fields_ = [("max_trials", ctypes.c_int32), ("warmup", ctypes.c_int32), ("reps", ctypes.c_int32),
+                ("layout_mask", ctypes.c_int32), ("arena", ctypes.c_void_p),
+                ("arena_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p)]
+
+
+class TuneReport(ctypes.Structure):
+    _fields_ = [("trials", ctypes.c_int32), ("n_layouts", ctypes.c_int32),
+                ("best_us", ctypes.c_float), ("default_us", ctypes.c_float),
+                ("layout_best_us", ctypes.c_float * MAX_CAND),
+                ("layout_best_variant", ctypes.c_int32 * MAX_CAND),
+                ("layout_name", (ctypes.c_char * 48) * MAX_CAND)]
+
+
+class ChainPlan(ctypes.Structure):
+    _fields_ = [("nops", ctypes.c_int32), ("trials", ctypes.c_int32),
+                ("op", ConvDesc * MAX_CHAIN), ("transform_before", ctypes.c_int32 * MAX_CHAIN),
+                ("edge_layout", Layout * (MAX_CHAIN + 1)),
+                ("op_us", ctypes.c_float * MAX_CHAIN), ("transform_us", ctypes.c_float * MAX_CHAIN),
+                ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float)]
+
+
+class Peaks(ctypes.Structure):
+    _fields_ = [("copy_gbps", ctypes.c_float), ("mfma_bf16_tflops", ctypes.c_float),
+                ("nominal_hbm_gbps", ctypes.c_float), ("nominal_bf16_tflops", ctypes.c_float),
+                ("compute_units", ctypes.c_int32), ("clock_mhz", ctypes.c_int32),
+                ("arch", ctypes.c_char * 32)]
+
+
+_lib = None
+
+
+def library_path():
+    return _LIBPATH
+
+
+def lib():
+    """Loads libalt.so; raises if it has not been built (python -m
+    paper_2210_12415_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIBPATH):
+            raise AltError(6, "libalt.so is not built: run python -m paper_2210_12415_amd.build")
+        L = ctypes.CDLL(_LIBPATH)
+        L.alt_last_error.restype = ctypes.c_char_p
+        L.alt_status_string.restype = ctypes.c_char_p
+        L.alt_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def exported_symbols():
+    """Names declared in include/alt.h that the binding expects to find."""
+    return ["alt_create", "alt_destroy", "alt_last_error", "alt_status_string", "alt_version",
+            "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
+            "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
+            "alt_conv2d", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_conv2d_variant_count", "alt_conv2d_variant_name",
+            "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
+            "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
+            "alt_tune_conv2d_variants", "alt_tune_chain", "alt_plan_chain",
+            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak"]
+
+
+def version():
+    return lib().alt_version().decode()
+
+
+def _i64(a):
+    return (ctypes.c_int64 * len(a))(*[int(x) for x in a])
+
+
+def _ck(status, h=None):
+    if status != 0:
+        msg = lib().alt_last_error(h).decode() if h else ""
+        raise AltError(status, msg)
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, or the integer itself."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return ctypes.c_void_p(x.data_ptr())
+    return ctypes.c_void_p(int(x))
+
+
+def _stream(s):
+    if s is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(s, "cuda_stream"):
+        return ctypes.c_void_p(s.cuda_stream)
+    return ctypes.c_void_p(int(s))
+
+
+# ------------------------------------------------------------- layouts (host) ----
+
+def layout_parse(text):
+    out = Layout()
+    _ck(lib().alt_layout_parse(text.encode(), ctypes.byref(out)))
+    return out
+
+
+def layout_from_prims(shape, seq):
+    out = Layout()
+    arr = (Prim * max(1, len(seq)))(*seq)
+    _ck(lib().alt_layout_from_prims(len(shape), _i64(shape), arr, len(seq), ctypes.byref(out)))
+    return out
+
+
+def _as_layout(l):
+    return layout_parse(l) if isinstance(l, str) else l
+
+
+def layout_physical_shape(layout, shape):
+    out = (ctypes.c_int64 * MAX_RANK)()
+    rank = ctypes.c_int()
+    _ck(lib().alt_layout_physical_shape(ctypes.byref(_as_layout(layout)), _i64(shape), out, ctypes.byref(rank)))
+    return tuple(out[i] for i in range(rank.value))
+
+
+def layout_offset(layout, shape, idx):
+    off = ctypes.c_int64()
+    _ck(lib().alt_layout_offset(ctypes.byref(_as_layout(layout)), _i64(shape), _i64(idx), ctypes.byref(off)))
+    return off.value
+
+
+def layout_index_of(layout, shape, offset):
+    out = (ctypes.c_int64 * MAX_RANK)()
+    _ck(lib().alt_layout_index_of(ctypes.byref(_as_layout(layout)), _i64(shape), ctypes.c_int64(offset), out))
+    return tuple(out[i] for i in range(len(shape)))
+
+
+def plan_chain(op_cost, conv_cost, in_layout):
+    """op_cost, conv_cost: nested lists [nops][nl][nl] of latencies."""
+    nops, nl = len(op_cost), len(op_cost[0])
+    flat = lambda c: (ctypes.c_float * (nops * nl * nl))(*[float(v) for o in c for r in o for v in r])
+    ins, outs = (ctypes.c_int * nops)(), (ctypes.c_int * nops)()
+    total = ctypes.c_float()
+    _ck(lib().alt_plan_chain(nops, nl, flat(op_cost), flat(conv_cost), in_layout, ins, outs, ctypes.byref(total)))
+    return list(ins), list(outs), total.value
+
+
+# ------------------------------------------------------------------ descriptors ----
+
+def conv_desc(N, C, H, W, K, R, S, stride=1, pad=0, dil=1, in_dtype=BF16, out_dtype=F32,
+              epilogue=0, variant=-1, x_layout="NCHW->NCHW", w_layout="OIHW->OIHW",
+              y_layout="NCHW->NCHW"):
+    d = ConvDesc(N, C, H, W, K, R, S, stride, stride, pad, pad, dil, dil, in_dtype, out_dtype,
+                 epilogue, variant)
+    d.x_layout, d.w_layout, d.y_layout = _as_layout(x_layout), _as_layout(w_layout), _as_layout(y_layout)
+    return d
+
+
+def gemm_desc(M, N, K, batch=1, in_dtype=BF16, out_dtype=F32, variant=-1,
+              a_layout="MK->MK", b_layout="KN->KN", c_layout="MN->MN"):
+    d = GemmDesc(batch, M, N, K, in_dtype, out_dtype, variant, 0)
+    d.a_layout, d.b_layout, d.c_layout = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    return d
+
+
+# ----------------------------------------------------------------------- handle ----
+
+class Handle:
+    """One library handle on the current device."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _ck(lib().alt_create(ctypes.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().alt_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self):
+        return lib().alt_last_error(self._h).decode()
+
+    def layout_transform(self, dtype, shape, src_layout, src, dst_layout, dst, stream=None):
+        _ck(lib().alt_layout_transform(self._h, dtype, len(shape), _i64(shape),
+                                       ctypes.byref(_as_layout(src_layout)), _ptr(src),
+                                       ctypes.byref(_as_layout(dst_layout)), _ptr(dst),
+                                       _stream(stream)), self._h)
+
+    # conv
+    def conv2d(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_conv2d(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
+                             _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv2d_workspace_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_conv2d_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def conv2d_output_shape(self, d):
+        out = (ctypes.c_int64 * 4)()
+        _ck(lib().alt_conv2d_output_shape(ctypes.byref(d), out))
+        return tuple(out)
+
+    def pack_weights(self, d, w_oihw, w_packed, stream=None):
+        _ck(lib().alt_pack_weights(self._h, ctypes.byref(d), _ptr(w_oihw), _ptr(w_packed),
+                                   _stream(stream)), self._h)
+
+    def conv2d_variant_count(self, d):
+        n = ctypes.c_int()
+        _ck(lib().alt_conv2d_variant_count(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def conv2d_variant_name(self, d, variant):
+        buf = ctypes.create_string_buffer(96)
+        _ck(lib().alt_conv2d_variant_name(self._h, ctypes.byref(d), variant, buf, ctypes.c_size_t(96)), self._h)
+        return buf.value.decode()
+
+    # gemm
+    def gemm(self, d, A, B, C, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_gemm(self._h, ctypes.byref(d), _ptr(A), _ptr(B), _ptr(C), _ptr(workspace),
+                           ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def gemm_workspace_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_gemm_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def gemm_variant_count(self, d):
+        n = ctypes.c_int()
+        _ck(lib().alt_gemm_variant_count(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def gemm_variant_name(self, d, variant):
+        buf = ctypes.create_string_buffer(96)
+        _ck(lib().alt_gemm_variant_name(self._h, ctypes.byref(d), variant, buf, ctypes.c_size_t(96)), self._h)
+        return buf.value.decode()
+
+    # tuning
+    def _opts(self, arena, arena_bytes, max_trials, warmup, reps, layout_mask, stream):
+        return TuneOpts(max_trials, warmup, reps, layout_mask, _ptr(arena), arena_bytes, _stream(stream))
+
+    def tune_conv2d_arena_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_tune_conv2d_arena_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def tune_gemm_arena_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_tune_gemm_arena_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def tune_conv2d(self, d, arena, arena_bytes, max_trials=0, warmup=3, reps=20, layout_mask=0, stream=None):
+        best, rep = ConvDesc(), TuneReport()
+        o = self._opts(arena, arena_bytes, max_trials, warmup, reps, layout_mask, stream)
+        _ck(lib().alt_tune_conv2d(self._h, ctypes.byref(d), ctypes.byref(o), ctypes.byref(best),
+                                  ctypes.byref(rep)), self._h)
+        return best, rep
+
+    def tune_gemm(self, d, arena, arena_bytes, max_trials=0, warmup=3, reps=20, layout_mask=0, stream=None):
+        best, rep = GemmDesc(), TuneReport()
+        o = self._opts(arena, arena_bytes, max_trials, warmup, reps, layout_mask, stream)
+        _ck(lib().alt_tune_gemm(self._h, ctypes.byref(d), ctypes.byref(o), ctypes.byref(best),
+                                ctypes.byref(rep)), self._h)
+        return best, rep
+
+    def tune_conv2d_variants(self, d, arena, arena_bytes, max_trials=0, warmup=3, reps=20, stream=None):
+        us, trials = ctypes.c_float(), ctypes.c_int()
+        o = self._opts(arena, arena_bytes, max_trials, warmup, reps, 0, stream)
+        _ck(lib().alt_tune_conv2d_variants(self._h, ctypes.byref(d), ctypes.byref(o), ctypes.byref(us),
+                                           ctypes.byref(trials)), self._h)
+        return us.value, trials.value
+
+    def tune_chain(self, ops, in_layout, arena, arena_bytes, max_trials=0, warmup=3, reps=20, stream=None):
+        arr = (ConvDesc * len(ops))(*ops)
+        plan = ChainPlan()
+        o = self._opts(arena, arena_bytes, max_trials, warmup, reps, 0, stream)
+        _ck(lib().alt_tune_chain(self._h, arr, len(ops), ctypes.byref(_as_layout(in_layout)),
+                                 ctypes.byref(o), ctypes.byref(plan)), self._h)
+        return plan
+
+    def cache_save(self, path):
+        _ck(lib().alt_cache_save(self._h, path.encode()), self._h)
+
+    def cache_load(self, path):
+        _ck(lib().alt_cache_load(self._h, path.encode()), self._h)
+
+    def cache_clear(self):
+        _ck(lib().alt_cache_clear(self._h), self._h)
+
+    def get_peak(self, arena, arena_bytes):
+        p = Peaks()
+        _ck(lib().alt_get_peak(self._h, _ptr(arena), ctypes.c_size_t(arena_bytes), ctypes.byref(p)), self._h)
+        return p

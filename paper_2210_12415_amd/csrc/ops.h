@@ -1,0 +1,36 @@
+// Shared between ops.hip (conv/gemm entry points) and tune.cpp.
+#pragma once
+
+#include "igemm.h"
+
+namespace alt {
+
+// One conv/gemm call reduced to what the implicit-GEMM kernels need.
+struct Problem {
+    IgemmParams p;
+    int dtype;
+    bool a_vec, a_trans, b_vec, b_trans;   // loaders the operand layouts admit (gather always works)
+    bool spatial_split, spatial_ok;
+};
+
+extern const int kSplitFactors[];
+int igemm_num_splits();
+int igemm_variant_count();
+std::string igemm_variant_name(int variant);
+void igemm_analyse(Problem *pb);
+bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, IgemmParams *out, std::string *why);
+size_t igemm_workspace(const Problem &pb, int splitk);
+double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams &p);
+int igemm_default_variant(const Problem &pb);
+alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *workspace, size_t ws_bytes,
+                       hipStream_t st);
+
+alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
+                          const float *bias, void *y, Problem *pb);
+alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B, void *C,
+                          Problem *pb);
+
+alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src,
+                             const BoundLayout &ld, void *dst, hipStream_t st);
+
+}  // namespace alt

@@ -1,0 +1,445 @@
+// Host side of alt_conv2d / alt_gemm: descriptor checks, mapping of layouts to
+// the implicit-GEMM kernel's addressing, variant table, split-K reduction,
+// weight packing.
+#include <algorithm>
+#include <mutex>
+
+#include "igemm.h"
+#include "ops.h"
+
+namespace alt {
+
+// ---- kernel registry -----------------------------------------------------------
+
+static std::vector<IgemmLaunch> &registry()
+{
+    static std::vector<IgemmLaunch> v;
+    return v;
+}
+
+void igemm_register(const IgemmLaunch &l) { registry().push_back(l); }
+
+const std::vector<IgemmLaunch> &igemm_table()
+{
+    static std::once_flag once;
+    std::call_once(once, [] {
+        auto &v = registry();
+        std::sort(v.begin(), v.end(), [](const IgemmLaunch &a, const IgemmLaunch &b) {
+            return std::strcmp(a.name, b.name) < 0;
+        });
+    });
+    return registry();
+}
+
+const int kSplitFactors[] = {1, 2, 3, 4, 6, 8, 9, 12, 16, 18, 24, 36};
+static const int *const kSplits = kSplitFactors;
+constexpr int kNumSplits = 12;
+int igemm_num_splits() { return kNumSplits; }
+
+int igemm_variant_count() { return (int)igemm_table().size() * kNumSplits; }
+
+// ---- split-K reduction + epilogue ----------------------------------------------
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
+{
+    const int64_t per_batch = (int64_t)p.M * p.Nc;
+    const int64_t total = per_batch * p.batch;
+    const int ohow = p.OH * p.OW;
+    for (int64_t e = blockIdx.x * (int64_t)256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int bz = (int)(e / per_batch);
+        const int64_t r = e - bz * per_batch;
+        const int m = (int)(r / p.Nc), n = (int)(r - (int64_t)m * p.Nc);
+        float v = 0.f;
+        for (int s = 0; s < p.splitk; ++s) v += p.partial[(int64_t)s * total + e];
+        if (p.epilogue & ALT_EPI_BIAS) v += p.bias[n];
+        if (p.epilogue & ALT_EPI_RELU) v = fmaxf(v, 0.f);
+        const int img = m / ohow, rem = m - img * ohow;
+        const int oh = rem / p.OW, ow = rem - oh * p.OW;
+        const int64_t off = (int64_t)bz * p.y_bstride + dim2_off(p.yn, img) + dim2_off(p.yk, n) +
+                            dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
+        if (p.out_bf16) ((uint16_t *)p.y)[off] = f32_to_bf16_rne(v);
+        else ((float *)p.y)[off] = v;
+    }
+}
+
+// ---- eligibility of loaders ------------------------------------------------------
+
+static bool mult(int64_t v, int m) { return v % m == 0; }
+
+void igemm_analyse(Problem *pb)
+{
+    const IgemmParams &p = pb->p;
+    const int epv = pb->dtype == ALT_BF16 ? 8 : 4;
+    const int es = pb->dtype == ALT_BF16 ? 2 : 4;
+    const bool x_spatial_split = (p.xh.f < p.H) || (p.xw.f < p.W);
+    pb->spatial_split = x_spatial_split;
+    pb->spatial_ok = !x_spatial_split || (p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0);
+    // A: 16-byte loads along channels
+    pb->a_vec = p.xc.si == 1 && mult(p.xc.f, epv) && (p.xc.f >= p.C || mult(p.xc.so, epv)) &&
+                mult(p.xn.si, epv) && mult(p.xn.so, epv) && mult(p.xh.si, epv) && mult(p.xh.so, epv) &&
+                mult(p.xw.si, epv) && mult(p.xw.so, epv) && mult(p.x_bstride, epv) &&
+                ((uintptr_t)p.x % 16 == 0) && pb->spatial_ok;
+    (void)es;
+    // A: rows (GMM m) contiguous, no spatial structure
+    pb->a_trans = p.H == 1 && p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0 && p.stride_w == 1 &&
+                  p.xw.si == 1 && p.xw.f >= p.W && mult(p.M, epv) && p.xc.f >= p.C && mult(p.xc.si, epv) &&
+                  mult(p.x_bstride, epv) && ((uintptr_t)p.x % 16 == 0) && p.OW == p.M;
+    pb->b_vec = p.wi.si == 1 && mult(p.wi.f, epv) && (p.wi.f >= p.C || mult(p.wi.so, epv)) &&
+                mult(p.wo.si, epv) && mult(p.wo.so, epv) && mult(p.wr.si, epv) && mult(p.wr.so, epv) &&
+                mult(p.ws.si, epv) && mult(p.ws.so, epv) && mult(p.w_bstride, epv) &&
+                ((uintptr_t)p.w % 16 == 0);
+    pb->b_trans = p.R == 1 && p.S == 1 && p.wo.si == 1 && mult(p.wo.f, epv) &&
+                  (p.wo.f >= p.Nc || mult(p.wo.so, epv)) && mult(p.Nc, epv) && mult(p.wi.si, epv) &&
+                  mult(p.wi.so, epv) && mult(p.w_bstride, epv) && ((uintptr_t)p.w % 16 == 0);
+}
+
+static bool nests(int64_t f, int64_t C, int bk) { return f >= C ? true : (f % bk == 0 || bk % f == 0); }
+
+// Can kernel `k` with split factor `splitk` run this problem?  Fills the
+// launch-dependent fields of a copy of the parameters.
+bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, IgemmParams *out, std::string *why)
+{
+    auto no = [&](const char *m) { if (why) *why = m; return false; };
+    const IgemmParams &p0 = pb.p;
+    if (k.dtype != pb.dtype) return no("element type");
+    if (!pb.spatial_ok && (k.amode != LOAD_GATHER)) return no("blocked H/W needs R=S=1 without padding");
+    const bool uniform = p0.C % k.BK == 0 && nests(p0.xc.f, p0.C, k.BK) && nests(p0.wi.f, p0.C, k.BK);
+    if (k.amode == LOAD_VEC && !(pb.a_vec && uniform)) return no("A is not channel-contiguous in 16-byte blocks");
+    if (k.bmode == LOAD_VEC && !(pb.b_vec && uniform)) return no("B is not channel-contiguous in 16-byte blocks");
+    if (k.amode == LOAD_TRANS && !pb.a_trans) return no("A rows are not contiguous");
+    if (k.bmode == LOAD_TRANS && !pb.b_trans) return no("B rows are not contiguous");
+    if (pb.spatial_split && k.amode == LOAD_GATHER && !(p0.R == 1 && p0.S == 1 && p0.pad_h == 0 && p0.pad_w == 0))
+        return no("blocked H/W with a sliding window");
+    IgemmParams p = p0;
+    p.uniform_rs = uniform ? 1 : 0;
+    p.spatial_split = pb.spatial_split ? 1 : 0;
+    p.ksteps_total = (p.Kg + k.BK - 1) / k.BK;
+    if (splitk < 1 || splitk > p.ksteps_total) return no("split-K factor exceeds the K steps");
+    p.splitk = splitk;
+    p.ksteps_per_split = (p.ksteps_total + splitk - 1) / splitk;
+    if ((int64_t)(splitk - 1) * p.ksteps_per_split >= p.ksteps_total) return no("split-K factor leaves an empty slice");
+    p.tiles_m = (p.M + k.BM - 1) / k.BM;
+    p.tiles_n = (p.Nc + k.BN - 1) / k.BN;
+    if ((int64_t)p.batch * splitk > 65535) return no("batch x split-K exceeds the grid");
+    if (out) *out = p;
+    return true;
+}
+
+size_t igemm_workspace(const Problem &pb, int splitk)
+{
+    if (splitk <= 1) return 0;
+    return (size_t)splitk * pb.p.batch * pb.p.M * pb.p.Nc * sizeof(float);
+}
+
+// Rough relative time of one variant: rounds of workgroups over the chip x
+// (K steps x per-step cost), gather/transposing loaders penalised.  Only used
+// to pick a default and to order the tuner's trials best-first.
+double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams &p)
+{
+    (void)pb;
+    double mode_cost = 1.0;
+    if (k.amode == LOAD_GATHER) mode_cost *= 6.0;
+    if (k.bmode == LOAD_GATHER) mode_cost *= 3.0;
+    if (k.amode == LOAD_TRANS) mode_cost *= 1.5;
+    if (k.bmode == LOAD_TRANS) mode_cost *= 1.5;
+    const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
+    const double rounds = std::ceil(blocks / 512.0);
+    const double step = (double)k.BM * k.BN * k.BK / 16384.0 + 3.0 * (k.BM + k.BN) * k.BK / 8192.0 + 2.0;
+    double est = rounds * (p.ksteps_per_split * step + 20.0) * mode_cost;
+    if (p.splitk > 1) est += 30.0 + 0.00002 * p.splitk * (double)p.M * p.Nc * p.batch;
+    return est;
+}
+
+int igemm_default_variant(const Problem &pb)
+{
+    const auto &tab = igemm_table();
+    double best = 1e300;
+    int best_v = -1;
+    for (int ki = 0; ki < (int)tab.size(); ++ki)
+        for (int si = 0; si < kNumSplits; ++si) {
+            IgemmParams p;
+            if (!igemm_applicable(pb, tab[ki], kSplits[si], &p, nullptr)) continue;
+            const double est = igemm_estimate(pb, tab[ki], p);
+            if (est < best) { best = est; best_v = ki * kNumSplits + si; }
+        }
+    return best_v;
+}
+
+alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *workspace, size_t ws_bytes,
+                       hipStream_t st)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const auto &tab = igemm_table();
+    if (variant < 0 || variant >= (int)tab.size() * kNumSplits)
+        return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
+    const IgemmLaunch &k = tab[variant / kNumSplits];
+    const int splitk = kSplits[variant % kNumSplits];
+    IgemmParams p;
+    std::string why;
+    if (!igemm_applicable(pb, k, splitk, &p, &why))
+        return fail(h, ALT_UNSUPPORTED, "variant %s/splitk%d not applicable: %s", k.name, splitk, why.c_str());
+    const size_t need = igemm_workspace(pb, splitk);
+    if (need > 0) {
+        if (!workspace || ws_bytes < need)
+            return fail(h, ALT_WORKSPACE_TOO_SMALL, "split-K needs %zu workspace bytes, got %zu", need, ws_bytes);
+        p.partial = (float *)workspace;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)(p.batch * p.splitk));
+    hipError_t e = k.launch(p, grid, st);
+    if (e != hipSuccess) return fail(h, ALT_HIP_ERROR, "launch of %s failed: %s", k.name, hipGetErrorString(e));
+    if (splitk > 1) {
+        const int64_t total = (int64_t)p.M * p.Nc * p.batch;
+        unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 256 * 16);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, p);
+        ALT_CHECK_HIP(h, hipGetLastError());
+    }
+    return ALT_OK;
+}
+
+std::string igemm_variant_name(int variant)
+{
+    const auto &tab = igemm_table();
+    if (variant < 0 || variant >= (int)tab.size() * kNumSplits) return "";
+    char buf[96];
+    std::snprintf(buf, sizeof buf, "%s_k%d", tab[variant / kNumSplits].name, kSplits[variant % kNumSplits]);
+    return buf;
+}
+
+// ---- descriptor -> problem ------------------------------------------------------------
+
+static bool fits32(int64_t v) { return v >= 0 && v <= 0x7fffffff; }
+
+alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
+                          const float *bias, void *y, Problem *pb)
+{
+    if (!d) return fail(h, ALT_INVALID_ARG, "null descriptor");
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1)
+        return fail(h, ALT_INVALID_ARG, "conv2d: non-positive extent");
+    if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0 || d->dil_h < 1 || d->dil_w < 1)
+        return fail(h, ALT_INVALID_ARG, "conv2d: bad stride/pad/dilation");
+    if ((d->in_dtype != ALT_F32 && d->in_dtype != ALT_BF16) || (d->out_dtype != ALT_F32 && d->out_dtype != ALT_BF16))
+        return fail(h, ALT_INVALID_ARG, "conv2d: bad dtype");
+    if (d->epilogue & ~(ALT_EPI_BIAS | ALT_EPI_RELU)) return fail(h, ALT_INVALID_ARG, "conv2d: unknown epilogue flag");
+    const int64_t OH = (d->H + 2 * d->pad_h - d->dil_h * (d->R - 1) - 1) / d->stride_h + 1;
+    const int64_t OW = (d->W + 2 * d->pad_w - d->dil_w * (d->S - 1) - 1) / d->stride_w + 1;
+    if (d->H + 2 * d->pad_h < d->dil_h * (d->R - 1) + 1 || d->W + 2 * d->pad_w < d->dil_w * (d->S - 1) + 1)
+        return fail(h, ALT_INVALID_ARG, "conv2d: kernel larger than padded input");
+    const int64_t xs[4] = {d->N, d->C, d->H, d->W}, wsh[4] = {d->K, d->C, d->R, d->S}, ys[4] = {d->N, d->K, OH, OW};
+    BoundLayout bx, bw, by;
+    std::string err;
+    alt_status_t s;
+    if ((s = bind_layout(&d->x_layout, 4, xs, &bx, &err)) != ALT_OK) return fail(h, s, "x_layout: %s", err.c_str());
+    if ((s = bind_layout(&d->w_layout, 4, wsh, &bw, &err)) != ALT_OK) return fail(h, s, "w_layout: %s", err.c_str());
+    if ((s = bind_layout(&d->y_layout, 4, ys, &by, &err)) != ALT_OK) return fail(h, s, "y_layout: %s", err.c_str());
+    Dim2 dx[4], dw[4], dy[4];
+    if (!layout_to_dim2(bx, dx) || !layout_to_dim2(bw, dw) || !layout_to_dim2(by, dy))
+        return fail(h, ALT_UNSUPPORTED, "conv2d: layouts must be separable with at most one block level per dimension");
+    if (!fits32(d->N * OH * OW) || !fits32(d->C * d->R * d->S) || !fits32(d->K) || !fits32(bx.numel / d->N * 2))
+        return fail(h, ALT_UNSUPPORTED, "conv2d: problem too large for 32-bit tile indices");
+    std::memset(pb, 0, sizeof(*pb));
+    pb->dtype = d->in_dtype;
+    IgemmParams &p = pb->p;
+    p.x = x; p.w = w; p.bias = bias; p.y = y;
+    p.M = (int32_t)(d->N * OH * OW); p.Nc = (int32_t)d->K; p.Kg = (int32_t)(d->C * d->R * d->S);
+    p.C = (int32_t)d->C; p.H = (int32_t)d->H; p.W = (int32_t)d->W; p.R = (int32_t)d->R; p.S = (int32_t)d->S;
+    p.OH = (int32_t)OH; p.OW = (int32_t)OW;
+    p.stride_h = d->stride_h; p.stride_w = d->stride_w; p.pad_h = d->pad_h; p.pad_w = d->pad_w;
+    p.dil_h = d->dil_h; p.dil_w = d->dil_w;
+    p.batch = 1; p.splitk = 1;
+    p.epilogue = d->epilogue; p.out_bf16 = d->out_dtype == ALT_BF16;
+    p.xn = dx[0]; p.xc = dx[1]; p.xh = dx[2]; p.xw = dx[3];
+    p.wo = dw[0]; p.wi = dw[1]; p.wr = dw[2]; p.ws = dw[3];
+    p.yn = dy[0]; p.yk = dy[1]; p.yh = dy[2]; p.yw = dy[3];
+    igemm_analyse(pb);
+    return ALT_OK;
+}
+
+alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B, void *C,
+                          Problem *pb)
+{
+    if (!d) return fail(h, ALT_INVALID_ARG, "null descriptor");
+    if (d->batch < 1 || d->M < 1 || d->N < 1 || d->K < 1) return fail(h, ALT_INVALID_ARG, "gemm: non-positive extent");
+    if ((d->in_dtype != ALT_F32 && d->in_dtype != ALT_BF16) || (d->out_dtype != ALT_F32 && d->out_dtype != ALT_BF16))
+        return fail(h, ALT_INVALID_ARG, "gemm: bad dtype");
+    const int64_t as[2] = {d->M, d->K}, bs[2] = {d->K, d->N}, cs[2] = {d->M, d->N};
+    BoundLayout ba, bb, bc;
+    std::string err;
+    alt_status_t s;
+    if ((s = bind_layout(&d->a_layout, 2, as, &ba, &err)) != ALT_OK) return fail(h, s, "a_layout: %s", err.c_str());
+    if ((s = bind_layout(&d->b_layout, 2, bs, &bb, &err)) != ALT_OK) return fail(h, s, "b_layout: %s", err.c_str());
+    if ((s = bind_layout(&d->c_layout, 2, cs, &bc, &err)) != ALT_OK) return fail(h, s, "c_layout: %s", err.c_str());
+    Dim2 da[2], db[2], dc[2];
+    if (!layout_to_dim2(ba, da) || !layout_to_dim2(bb, db) || !layout_to_dim2(bc, dc))
+        return fail(h, ALT_UNSUPPORTED, "gemm: layouts must be separable with at most one block level per dimension");
+    if (!fits32(d->M) || !fits32(d->N) || !fits32(d->K))
+        return fail(h, ALT_UNSUPPORTED, "gemm: problem too large for 32-bit tile indices");
+    std::memset(pb, 0, sizeof(*pb));
+    pb->dtype = d->in_dtype;
+    IgemmParams &p = pb->p;
+    const Dim2 one = {1, 0, 0, 0};
+    p.x = A; p.w = B; p.y = C; p.bias = nullptr;
+    p.M = (int32_t)d->M; p.Nc = (int32_t)d->N; p.Kg = (int32_t)d->K;
+    p.C = (int32_t)d->K; p.H = 1; p.W = (int32_t)d->M; p.R = 1; p.S = 1; p.OH = 1; p.OW = (int32_t)d->M;
+    p.stride_h = p.stride_w = 1; p.dil_h = p.dil_w = 1;
+    p.batch = (int32_t)d->batch; p.splitk = 1;
+    p.out_bf16 = d->out_dtype == ALT_BF16;
+    p.x_bstride = d->M * d->K; p.w_bstride = d->K * d->N; p.y_bstride = d->M * d->N;
+    p.xn = one; p.xc = da[1]; p.xh = one; p.xw = da[0];
+    p.wo = db[1]; p.wi = db[0]; p.wr = one; p.ws = one;
+    p.yn = one; p.yk = dc[1]; p.yh = one; p.yw = dc[0];
+    igemm_analyse(pb);
+    return ALT_OK;
+}
+
+}  // namespace alt
+
+using namespace alt;
+
+extern "C" {
+
+alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out)
+{
+    if (!d || !out) return ALT_INVALID_ARG;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1) return ALT_INVALID_ARG;
+    out[0] = d->N;
+    out[1] = d->K;
+    out[2] = (d->H + 2 * d->pad_h - d->dil_h * (d->R - 1) - 1) / d->stride_h + 1;
+    out[3] = (d->W + 2 * d->pad_w - d->dil_w * (d->S - 1) - 1) / d->stride_w + 1;
+    return (out[2] < 1 || out[3] < 1) ? ALT_INVALID_ARG : ALT_OK;
+}
+
+static int pick_variant(alt_handle_t h, const Problem &pb, int requested, const std::string &key)
+{
+    if (requested >= 0) return requested;
+    auto it = h->cache.find(key);
+    if (it != h->cache.end()) {
+        // a cached entry is only trusted if it still applies (pointers may be aligned differently)
+        const auto &tab = igemm_table();
+        int v = it->second.variant;
+        if (v >= 0 && v < (int)tab.size() * kNumSplits &&
+            igemm_applicable(pb, tab[v / kNumSplits], kSplits[v % kNumSplits], nullptr, nullptr))
+            return v;
+    }
+    return igemm_default_variant(pb);
+}
+
+alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
+                        void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !x || !w || !y) return fail(h, ALT_INVALID_ARG, "alt_conv2d: null argument");
+    if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv2d: bias flag without bias");
+    Problem pb;
+    alt_status_t s = conv_problem(h, d, x, w, bias, y, &pb);
+    if (s != ALT_OK) return s;
+    int v = pick_variant(h, pb, d->variant, conv_key(h, d));
+    if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_conv2d: no kernel variant applies");
+    return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem pb;
+    // alignment of real pointers is unknown here: assume 16-byte aligned buffers
+    alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
+    if (s != ALT_OK) return s;
+    int v = pick_variant(h, pb, d->variant, conv_key(h, d));
+    if (v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
+    *bytes = igemm_workspace(pb, kSplits[v % kNumSplits]);
+    return ALT_OK;
+}
+
+alt_status_t alt_conv2d_variant_count(alt_handle_t h, const alt_conv_desc_t *d, int *count)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !count) return fail(h, ALT_INVALID_ARG, "null argument");
+    *count = igemm_variant_count();
+    return ALT_OK;
+}
+
+alt_status_t alt_conv2d_variant_name(alt_handle_t h, const alt_conv_desc_t *d, int variant, char *buf, size_t buflen)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !buf || buflen == 0) return fail(h, ALT_INVALID_ARG, "null argument");
+    std::string n = igemm_variant_name(variant);
+    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
+    std::snprintf(buf, buflen, "%s", n.c_str());
+    Problem pb;
+    alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
+    if (s != ALT_OK) return s;
+    std::string why;
+    const auto &tab = igemm_table();
+    if (!igemm_applicable(pb, tab[variant / kNumSplits], kSplits[variant % kNumSplits], nullptr, &why))
+        return fail(h, ALT_UNSUPPORTED, "%s: %s", n.c_str(), why.c_str());
+    return ALT_OK;
+}
+
+alt_status_t alt_pack_weights(alt_handle_t h, const alt_conv_desc_t *d, const void *w_oihw, void *w_packed, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !w_oihw || !w_packed) return fail(h, ALT_INVALID_ARG, "alt_pack_weights: null argument");
+    const int64_t wsh[4] = {d->K, d->C, d->R, d->S};
+    alt_layout_t plain;
+    alt_layout_parse("OIHW->OIHW", &plain);
+    BoundLayout bs, bd;
+    std::string err;
+    alt_status_t s;
+    if ((s = bind_layout(&plain, 4, wsh, &bs, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+    if ((s = bind_layout(&d->w_layout, 4, wsh, &bd, &err)) != ALT_OK) return fail(h, s, "w_layout: %s", err.c_str());
+    return transform_bound(h, (int)dtype_size(d->in_dtype), bs, w_oihw, bd, w_packed, (hipStream_t)stream);
+}
+
+alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B, void *C,
+                      void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !A || !B || !C) return fail(h, ALT_INVALID_ARG, "alt_gemm: null argument");
+    Problem pb;
+    alt_status_t s = gemm_problem(h, d, A, B, C, &pb);
+    if (s != ALT_OK) return s;
+    int v = pick_variant(h, pb, d->variant, gemm_key(h, d));
+    if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_gemm: no kernel variant applies");
+    return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+alt_status_t alt_gemm_workspace_size(alt_handle_t h, const alt_gemm_desc_t *d, size_t *bytes)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem pb;
+    alt_status_t s = gemm_problem(h, d, (void *)16, (void *)16, (void *)16, &pb);
+    if (s != ALT_OK) return s;
+    int v = pick_variant(h, pb, d->variant, gemm_key(h, d));
+    if (v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
+    *bytes = igemm_workspace(pb, kSplits[v % kNumSplits]);
+    return ALT_OK;
+}
+
+alt_status_t alt_gemm_variant_count(alt_handle_t h, const alt_gemm_desc_t *d, int *count)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !count) return fail(h, ALT_INVALID_ARG, "null argument");
+    *count = igemm_variant_count();
+    return ALT_OK;
+}
+
+alt_status_t alt_gemm_variant_name(alt_handle_t h, const alt_gemm_desc_t *d, int variant, char *buf, size_t buflen)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !buf || buflen == 0) return fail(h, ALT_INVALID_ARG, "null argument");
+    std::string n = igemm_variant_name(variant);
+    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
+    std::snprintf(buf, buflen, "%s", n.c_str());
+    Problem pb;
+    alt_status_t s = gemm_problem(h, d, (void *)16, (void *)16, (void *)16, &pb);
+    if (s != ALT_OK) return s;
+    std::string why;
+    const auto &tab = igemm_table();
+    if (!igemm_applicable(pb, tab[variant / kNumSplits], kSplits[variant % kNumSplits], nullptr, &why))
+        return fail(h, ALT_UNSUPPORTED, "%s: %s", n.c_str(), why.c_str());
+    return ALT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,344 @@
+// Layout conversion operator (Section 4.2 of the paper): an element copy
+// under two index maps.  Both maps are split+reorder sequences, so after
+// cutting every logical dimension at the union of both layouts' block
+// boundaries the conversion is a strided permutation of a small number of
+// "pieces", each with a source and a destination stride.  Three kernels:
+//   rows      – the memory-contiguous piece is the same on both sides:
+//               contiguous runs are copied with vector loads and stores;
+//   transpose – it differs: a 2-D tile (source-contiguous piece x
+//               destination-contiguous piece) goes through LDS so that both
+//               the global reads and the global writes are coalesced;
+//   general   – anything else (blocks that do not nest, sequences with a
+//               non-separable fuse): one thread per logical element.
+#include <algorithm>
+
+#include "common.h"
+#include "layout_eval.h"
+
+namespace alt {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxOuter = 7;
+
+struct Piece {
+    int64_t ext, ss, ds;
+};
+
+struct PermuteParams {
+    const void *src;
+    void *dst;
+    int32_t n_outer;
+    int32_t TA, TB, LD;
+    int64_t outer_ext[kMaxOuter], outer_ss[kMaxOuter], outer_ds[kMaxOuter];
+    int64_t ext_a, ext_b;     // extents of the two tile pieces
+    int64_t ss_b, ds_b;       // strides of piece b (ds_b = 1 in the transpose kernel)
+    int64_t ss_a, ds_a;       // strides of piece a (ss_a = 1 always; ds_a = 1 in the rows kernel)
+    int64_t tiles_a, tiles_b;
+};
+
+template <int BYTES> struct Word;
+template <> struct Word<2> { using type = uint16_t; };
+template <> struct Word<4> { using type = uint32_t; };
+template <> struct Word<8> { using type = uint2; };
+template <> struct Word<16> { using type = uint4; };
+
+// Block -> (outer indices, tile origin).  Uniform per block.
+__device__ inline void locate_tile(const PermuteParams &p, int64_t &src_base, int64_t &dst_base,
+                                   int64_t &a0, int64_t &b0)
+{
+    int64_t t = blockIdx.x;
+    int64_t ta = t % p.tiles_a; t /= p.tiles_a;
+    int64_t tb = t % p.tiles_b; t /= p.tiles_b;
+    a0 = ta * p.TA;
+    b0 = tb * p.TB;
+    src_base = a0 * p.ss_a + b0 * p.ss_b;
+    dst_base = a0 * p.ds_a + b0 * p.ds_b;
+    for (int d = p.n_outer - 1; d >= 0; --d) {
+        int64_t i = t % p.outer_ext[d];
+        t /= p.outer_ext[d];
+        src_base += i * p.outer_ss[d];
+        dst_base += i * p.outer_ds[d];
+    }
+}
+
+// Piece a is contiguous on both sides: copy TB runs of TA elements.
+template <int ELSZ, int VBYTES>
+__global__ __launch_bounds__(kThreads) void permute_rows_kernel(PermuteParams p)
+{
+    using V = typename Word<VBYTES>::type;
+    constexpr int VL = VBYTES / ELSZ;
+    int64_t sb, db, a0, b0;
+    locate_tile(p, sb, db, a0, b0);
+    const int ta = (int)min((int64_t)p.TA, p.ext_a - a0);
+    const int tb = (int)min((int64_t)p.TB, p.ext_b - b0);
+    const int ra = ta / VL;                         // vectors per run (host guarantees divisibility)
+    const char *src = (const char *)p.src;
+    char *dst = (char *)p.dst;
+    for (int v = threadIdx.x; v < ra * tb; v += kThreads) {
+        int ib = v / ra, ia = (v - ib * ra) * VL;
+        V w = *(const V *)(src + (sb + ib * p.ss_b + ia) * ELSZ);
+        *(V *)(dst + (db + ib * p.ds_b + ia) * ELSZ) = w;
+    }
+}
+
+// Piece a is contiguous in the source, piece b in the destination.
+template <int ELSZ, int LBYTES, int SBYTES>
+__global__ __launch_bounds__(kThreads) void permute_transpose_kernel(PermuteParams p)
+{
+    using E = typename Word<ELSZ>::type;
+    using VLd = typename Word<LBYTES>::type;
+    using VSt = typename Word<SBYTES>::type;
+    constexpr int VL = LBYTES / ELSZ, VS = SBYTES / ELSZ;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    E *tile = (E *)smem_raw;                        // [TB][LD], element (ib, ia) at ib*LD + ia
+    int64_t sb, db, a0, b0;
+    locate_tile(p, sb, db, a0, b0);
+    const int ta = (int)min((int64_t)p.TA, p.ext_a - a0);
+    const int tb = (int)min((int64_t)p.TB, p.ext_b - b0);
+    const int LD = p.LD;
+    const char *src = (const char *)p.src;
+    char *dst = (char *)p.dst;
+    {
+        const int ra = ta / VL;
+        for (int v = threadIdx.x; v < ra * tb; v += kThreads) {
+            int ib = v / ra, ia = (v - ib * ra) * VL;
+            VLd w = *(const VLd *)(src + (sb + ib * p.ss_b + ia) * ELSZ);
+            const E *e = (const E *)&w;
+#pragma unroll
+            for (int j = 0; j < VL; ++j) tile[ib * LD + ia + j] = e[j];
+        }
+    }
+    __syncthreads();
+    {
+        const int rb = tb / VS;
+        for (int v = threadIdx.x; v < rb * ta; v += kThreads) {
+            int ia = v / rb, ib = (v - ia * rb) * VS;
+            VSt w;
+            E *e = (E *)&w;
+#pragma unroll
+            for (int j = 0; j < VS; ++j) e[j] = tile[(ib + j) * LD + ia];
+            *(VSt *)(dst + (db + ia * p.ds_a + ib) * ELSZ) = w;
+        }
+    }
+}
+
+struct GeneralParams {
+    const void *src;
+    void *dst;
+    BoundLayout ls, ld;
+};
+
+template <int ELSZ>
+__global__ __launch_bounds__(kThreads) void permute_general_kernel(GeneralParams p)
+{
+    using E = typename Word<ELSZ>::type;
+    const int64_t n = p.ls.numel;
+    for (int64_t e = blockIdx.x * (int64_t)kThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kThreads) {
+        int64_t idx[ALT_MAX_RANK];
+        int64_t r = e;
+        for (int d = p.ls.ndim - 1; d >= 0; --d) { idx[d] = r % p.ls.shape[d]; r /= p.ls.shape[d]; }
+        ((E *)p.dst)[eval_offset(p.ld, idx)] = ((const E *)p.src)[eval_offset(p.ls, idx)];
+    }
+}
+
+// Cuts every logical dimension at the union of both layouts' boundaries.
+// Returns false when the boundaries do not nest (e.g. blocks of 12 and 8).
+bool refine(const BoundLayout &s, const BoundLayout &d, std::vector<Piece> *out)
+{
+    for (int dim = 0; dim < s.ndim; ++dim) {
+        std::vector<int64_t> cuts;
+        for (int j = 0; j < s.nsub; ++j) if (s.atom[j].dim == dim) cuts.push_back(s.atom[j].div);
+        for (int j = 0; j < d.nsub; ++j) if (d.atom[j].dim == dim) cuts.push_back(d.atom[j].div);
+        cuts.push_back(s.shape[dim]);
+        std::sort(cuts.begin(), cuts.end());
+        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+        for (size_t c = 0; c + 1 < cuts.size(); ++c) {
+            int64_t lo = cuts[c], hi = cuts[c + 1];
+            if (hi % lo != 0) return false;
+            Piece pc{hi / lo, -1, -1};
+            for (int j = 0; j < s.nsub; ++j) {
+                const Atom &a = s.atom[j];
+                if (a.dim == dim && a.div <= lo && lo < a.div * a.ext) {
+                    if (lo % a.div != 0 || (a.div * a.ext) % hi != 0) return false;
+                    pc.ss = a.stride * (lo / a.div);
+                }
+            }
+            for (int j = 0; j < d.nsub; ++j) {
+                const Atom &a = d.atom[j];
+                if (a.dim == dim && a.div <= lo && lo < a.div * a.ext) {
+                    if (lo % a.div != 0 || (a.div * a.ext) % hi != 0) return false;
+                    pc.ds = a.stride * (lo / a.div);
+                }
+            }
+            if (pc.ss < 0 || pc.ds < 0) return false;
+            if (pc.ext > 1) out->push_back(pc);
+        }
+    }
+    // destination order, then merge neighbours that are contiguous on both sides
+    std::sort(out->begin(), out->end(), [](const Piece &x, const Piece &y) { return x.ds > y.ds; });
+    std::vector<Piece> m;
+    for (const Piece &pc : *out) {
+        if (!m.empty() && m.back().ds == pc.ds * pc.ext && m.back().ss == pc.ss * pc.ext) {
+            m.back().ext *= pc.ext;
+            m.back().ss = pc.ss;
+            m.back().ds = pc.ds;
+        } else {
+            m.push_back(pc);
+        }
+    }
+    out->swap(m);
+    return true;
+}
+
+int pick_vector_bytes(int elsz, int64_t run, const std::vector<int64_t> &strides, const void *ptr)
+{
+    for (int vb : {16, 8}) {
+        if (vb <= elsz) break;
+        int vl = vb / elsz;
+        bool ok = run % vl == 0 && ((uintptr_t)ptr % vb) == 0;
+        for (int64_t st : strides) ok = ok && (st % vl == 0);
+        if (ok) return vb;
+    }
+    return elsz;
+}
+
+template <int ELSZ>
+void launch_rows(int vb, const PermuteParams &p, dim3 grid, hipStream_t st)
+{
+    if (vb == 16) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 16>), grid, dim3(kThreads), 0, st, p);
+    else if (vb == 8) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 8>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((permute_rows_kernel<ELSZ, ELSZ>), grid, dim3(kThreads), 0, st, p);
+}
+
+template <int ELSZ, int LB>
+void launch_transpose_s(int sb, const PermuteParams &p, dim3 grid, size_t lds, hipStream_t st)
+{
+    if (sb == 16) hipLaunchKernelGGL((permute_transpose_kernel<ELSZ, LB, 16>), grid, dim3(kThreads), lds, st, p);
+    else if (sb == 8) hipLaunchKernelGGL((permute_transpose_kernel<ELSZ, LB, 8>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((permute_transpose_kernel<ELSZ, LB, ELSZ>), grid, dim3(kThreads), lds, st, p);
+}
+
+template <int ELSZ>
+void launch_transpose(int lb, int sb, const PermuteParams &p, dim3 grid, size_t lds, hipStream_t st)
+{
+    if (lb == 16) launch_transpose_s<ELSZ, 16>(sb, p, grid, lds, st);
+    else if (lb == 8) launch_transpose_s<ELSZ, 8>(sb, p, grid, lds, st);
+    else launch_transpose_s<ELSZ, ELSZ>(sb, p, grid, lds, st);
+}
+
+}  // namespace
+
+// Shared with conv.hip (weight packing) and the tuner.
+alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src,
+                             const BoundLayout &ld, void *dst, hipStream_t st)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const int64_t numel = ls.numel;
+    std::vector<Piece> pcs;
+    bool permutable = ls.separable && ld.separable && refine(ls, ld, &pcs) && (int)pcs.size() <= kMaxOuter + 2;
+    if (permutable && numel >= ((int64_t)1 << 40)) permutable = false;
+    if (!permutable) {
+        GeneralParams gp;
+        gp.src = src; gp.dst = dst; gp.ls = ls; gp.ld = ld;
+        int64_t blocks = std::min<int64_t>((numel + kThreads - 1) / kThreads, 256 * 32);
+        if (elsz == 2) hipLaunchKernelGGL(permute_general_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), 0, st, gp);
+        else hipLaunchKernelGGL(permute_general_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), 0, st, gp);
+        ALT_CHECK_HIP(h, hipGetLastError());
+        return ALT_OK;
+    }
+    if (pcs.size() <= 1) {                       // same placement: plain copy
+        ALT_CHECK_HIP(h, hipMemcpyAsync(dst, src, (size_t)numel * elsz, hipMemcpyDeviceToDevice, st));
+        return ALT_OK;
+    }
+    // pieces are in destination order: the last one has ds = 1
+    int ib = (int)pcs.size() - 1, ia = -1;
+    for (int j = 0; j < (int)pcs.size(); ++j) if (pcs[j].ss == 1) ia = j;
+    if (ia < 0 || pcs[ib].ds != 1) return fail(h, ALT_UNSUPPORTED, "internal: no unit-stride piece");
+
+    PermuteParams p;
+    std::memset(&p, 0, sizeof p);
+    p.src = src; p.dst = dst;
+    const bool rows = ia == ib;
+    if (rows) ib = (int)pcs.size() - 2;          // tile over the run and the next destination piece
+    const Piece A = pcs[ia], B = pcs[ib];
+    p.ext_a = A.ext; p.ext_b = B.ext;
+    p.ss_a = A.ss; p.ds_a = A.ds; p.ss_b = B.ss; p.ds_b = B.ds;
+    for (int j = 0; j < (int)pcs.size(); ++j) {
+        if (j == ia || j == ib) continue;
+        p.outer_ext[p.n_outer] = pcs[j].ext;
+        p.outer_ss[p.n_outer] = pcs[j].ss;
+        p.outer_ds[p.n_outer] = pcs[j].ds;
+        ++p.n_outer;
+    }
+    std::vector<int64_t> sstr, dstr;
+    for (int j = 0; j < (int)pcs.size(); ++j) {
+        if (j != ia) sstr.push_back(pcs[j].ss);
+        if (j != (rows ? ia : ib)) dstr.push_back(pcs[j].ds);
+    }
+    constexpr int64_t kTileElems = 4096;
+    if (rows) {
+        int vb = std::min(pick_vector_bytes(elsz, A.ext, sstr, src), pick_vector_bytes(elsz, A.ext, dstr, dst));
+        int vl = vb / elsz;
+        int64_t TA = std::min<int64_t>(A.ext, kTileElems);
+        TA -= TA % vl;
+        if (TA == 0) TA = vl;
+        int64_t TB = std::max<int64_t>(1, std::min<int64_t>(B.ext, kTileElems / TA));
+        p.TA = (int)TA; p.TB = (int)TB;
+        p.tiles_a = (A.ext + TA - 1) / TA;
+        p.tiles_b = (B.ext + TB - 1) / TB;
+        int64_t blocks = p.tiles_a * p.tiles_b;
+        for (int d = 0; d < p.n_outer; ++d) blocks *= p.outer_ext[d];
+        if (blocks > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "tensor too large for one launch");
+        if (elsz == 2) launch_rows<2>(vb, p, dim3((unsigned)blocks), st);
+        else launch_rows<4>(vb, p, dim3((unsigned)blocks), st);
+    } else {
+        int lb = pick_vector_bytes(elsz, A.ext, sstr, src);
+        int sb = pick_vector_bytes(elsz, B.ext, dstr, dst);
+        int vl = lb / elsz, vs = sb / elsz;
+        int64_t TA = std::min<int64_t>(A.ext, 64), TB = std::min<int64_t>(B.ext, 64);
+        if (TA < 64) TB = std::min<int64_t>(B.ext, kTileElems / TA);
+        else if (TB < 64) TA = std::min<int64_t>(A.ext, kTileElems / TB);
+        TA -= TA % vl; if (TA == 0) TA = vl;
+        TB -= TB % vs; if (TB == 0) TB = vs;
+        p.TA = (int)TA; p.TB = (int)TB;
+        p.LD = (int)TA | 1;                      // odd row pitch: conflict-free column reads
+        p.tiles_a = (A.ext + TA - 1) / TA;
+        p.tiles_b = (B.ext + TB - 1) / TB;
+        int64_t blocks = p.tiles_a * p.tiles_b;
+        for (int d = 0; d < p.n_outer; ++d) blocks *= p.outer_ext[d];
+        if (blocks > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "tensor too large for one launch");
+        size_t lds = (size_t)p.LD * p.TB * elsz;
+        if (elsz == 2) launch_transpose<2>(lb, sb, p, dim3((unsigned)blocks), lds, st);
+        else launch_transpose<4>(lb, sb, p, dim3((unsigned)blocks), lds, st);
+    }
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+}  // namespace alt
+
+using namespace alt;
+
+extern "C" alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape,
+                                             const alt_layout_t *src_layout, const void *src,
+                                             const alt_layout_t *dst_layout, void *dst, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!shape || !src_layout || !dst_layout || !src || !dst)
+        return fail(h, ALT_INVALID_ARG, "alt_layout_transform: null argument");
+    if (dtype != ALT_F32 && dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_layout_transform: bad dtype");
+    if (src == dst) return fail(h, ALT_INVALID_ARG, "alt_layout_transform: src and dst must not overlap");
+    BoundLayout ls, ld;
+    std::string err;
+    alt_status_t s = bind_layout(src_layout, ndim, shape, &ls, &err);
+    if (s != ALT_OK) return fail(h, s, "source layout: %s", err.c_str());
+    s = bind_layout(dst_layout, ndim, shape, &ld, &err);
+    if (s != ALT_OK) return fail(h, s, "destination layout: %s", err.c_str());
+    const size_t bytes = (size_t)ls.numel * dtype_size(dtype);
+    const char *a = (const char *)src, *b = (const char *)dst;
+    if ((a < b + bytes) && (b < a + bytes))
+        return fail(h, ALT_INVALID_ARG, "alt_layout_transform: src and dst must not overlap");
+    return transform_bound(h, (int)dtype_size(dtype), ls, src, ld, dst, (hipStream_t)stream);
+}

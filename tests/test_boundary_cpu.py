@@ -1,0 +1,153 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, its layout index math agrees with the oracle bit for bit, its
+chain planner finds known shortest paths, and argument errors come back as
+status codes.  No kernel is launched."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2210_12415_amd as alt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "alt.h")).read()
+    declared = set(re.findall(r"\b(alt_[a-z0-9_]+)\s*\(", header))
+    declared -= {"alt_context"}
+    lib = alt.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(alt.exported_symbols())
+    assert alt.version() == "0.1"
+
+
+LAYOUTS = [("NCHW->NCHW", (2, 8, 3, 5)), ("NCHW->NHWC", (2, 8, 3, 5)), ("NCHW->NCHW4c", (2, 8, 3, 5)),
+           ("NCHW->HWNC", (2, 8, 3, 5)), ("NCHW->NCHW2c4c", (1, 16, 2, 3)), ("OIHW->OIHW4i2o", (4, 8, 3, 3)),
+           ("OIHW->OIHW2o4i", (4, 8, 3, 3)), ("OIHW->OHWI", (4, 8, 3, 3)), ("MK->KM", (6, 10)),
+           ("MK->MK3m5k", (6, 10)), ("KN->NK2n5k", (10, 6))]
+
+
+@pytest.mark.parametrize("name,shape", LAYOUTS)
+def test_layout_offsets_match_oracle(oracle, name, shape):
+    L = alt.layout_parse(name)
+    if name == "NCHW->NCHW2c4c":
+        seq = [oracle.split(1, [shape[1] // 8, 2, 4]), oracle.reorder([0, 1, 4, 5, 2, 3])]
+    else:
+        seq = oracle.seq_from_string(name, shape)
+    want = oracle.layout_offsets(shape, seq)
+    assert alt.layout_physical_shape(L, shape) == oracle.layout_shape(shape, seq)
+    for idx in itertools.product(*map(range, shape)):
+        off = alt.layout_offset(L, shape, idx)
+        assert off == want[idx]
+        assert alt.layout_index_of(L, shape, off) == idx
+
+
+def test_layout_from_primitive_sequences(oracle):
+    # the paper's two worked sequences (Section 4.1.1), 0-based
+    N, O, H, W, ot = 2, 32, 3, 5, 16
+    L = alt.layout_from_prims((N, O, H, W), [alt.split(1, [O // ot, ot]), alt.reorder([0, 1, 3, 4, 2])])
+    assert L.separable == 1
+    want = oracle.layout_offsets((N, O, H, W), oracle.seq_from_string("NCHW->NCHW16c", (N, O, H, W)))
+    for idx in itertools.product(range(N), range(O), range(H), range(W)):
+        assert alt.layout_offset(L, (N, O, H, W), idx) == want[idx]
+    N, H, W, O = 2, 3, 5, 8
+    shape = (N, H, W, O)
+    L2 = alt.layout_from_prims(shape, [alt.fuse(1, 3), alt.split(1, [O // 4, 4, H * W]), alt.reorder([0, 1, 3, 2])])
+    assert L2.separable == 0                      # the fuse is cut across the old dimensions
+    seq = [oracle.fuse(1, 3), oracle.split(1, [O // 4, 4, H * W]), oracle.reorder([0, 1, 3, 2])]
+    want = oracle.layout_offsets(shape, seq)
+    assert alt.layout_physical_shape(L2, shape) == (N, O // 4, H * W, 4)
+    for idx in itertools.product(*map(range, shape)):
+        off = alt.layout_offset(L2, shape, idx)
+        assert off == want[idx]
+        assert alt.layout_index_of(L2, shape, off) == idx
+    # fuse then split back along the old boundaries stays separable
+    L3 = alt.layout_from_prims((2, 6, 4), [alt.fuse(1, 2), alt.split(1, [3, 8]), alt.reorder([1, 0, 2])])
+    assert L3.separable == 1
+    seq3 = [oracle.fuse(1, 2), oracle.split(1, [3, 8]), oracle.reorder([1, 0, 2])]
+    want3 = oracle.layout_offsets((2, 6, 4), seq3)
+    for idx in itertools.product(range(2), range(6), range(4)):
+        assert alt.layout_offset(L3, (2, 6, 4), idx) == want3[idx]
+
+
+def test_layout_errors():
+    for bad in ["NCHW", "NCHW->", "NCHW->NCH", "NCHW->NCHWW", "NCHW->NCHW16", "NCHW->NCHWc", "NCHW->NCHW0c",
+                "nchw->NCHW", "NCHW->NCHX", "NNHW->NNHW", "NCHW->16NCHW"]:
+        with pytest.raises(alt.AltError) as e:
+            alt.layout_parse(bad)
+        assert e.value.status == 2, bad
+    L = alt.layout_parse("NCHW->NCHW16c")
+    with pytest.raises(alt.AltError) as e:
+        alt.layout_offset(L, (1, 24, 2, 2), (0, 0, 0, 0))       # 16 does not divide 24
+    assert e.value.status == 3
+    with pytest.raises(alt.AltError) as e:
+        alt.layout_offset(L, (1, 32, 2, 2), (0, 32, 0, 0))      # index out of range
+    assert e.value.status == 1
+    with pytest.raises(alt.AltError) as e:
+        alt.layout_from_prims((2, 10), [alt.split(1, [3, 4])])  # factors do not multiply to the extent
+    assert e.value.status == 3
+    with pytest.raises(alt.AltError) as e:
+        alt.layout_from_prims((2, 10), [alt.reorder([0, 0])])
+    assert e.value.status == 2
+
+
+def test_plan_chain_known_shortest_paths():
+    inf = float("inf")
+    # two layouts; op0 is fast only when writing layout 1, op1 only when reading layout 1
+    op = [[[10, 4], [10, 4]], [[9, 9], [3, 3]]]
+    cv = [[[0, 1], [1, 0]], [[0, 1], [1, 0]]]
+    ins, outs, total = alt.plan_chain(op, cv, 0)
+    assert (ins, outs, total) == ([0, 1], [1, 0], 7.0)            # producer writes the consumer's layout
+    # an expensive conversion keeps everything in the input layout
+    cv2 = [[[0, 100], [100, 0]], [[0, 100], [100, 0]]]
+    op2 = [[[10, 50], [1, 1]], [[9, 9], [3, 3]]]
+    ins, outs, total = alt.plan_chain(op2, cv2, 0)
+    assert (ins, outs, total) == ([0, 0], [0, 0], 19.0)
+    # a cheap conversion is inserted exactly where layouts differ
+    op3 = [[[10, inf], [inf, 2]]]
+    cv3 = [[[0, 3], [3, 0]]]
+    ins, outs, total = alt.plan_chain(op3, cv3, 0)
+    assert (ins, outs, total) == ([1], [1], 5.0)
+    # brute force on a random 3-op, 3-layout table
+    rng = np.random.RandomState(0)
+    opc = rng.uniform(1, 10, (3, 3, 3)).astype(np.float32)
+    cvc = rng.uniform(0.5, 3, (3, 3, 3)).astype(np.float32)
+    best = inf
+    for a in itertools.product(range(3), repeat=3):
+        for b in itertools.product(range(3), repeat=3):
+            prev, c = 1, 0.0
+            for i in range(3):
+                c += (0.0 if prev == a[i] else float(cvc[i][prev][a[i]])) + float(opc[i][a[i]][b[i]])
+                prev = b[i]
+            best = min(best, c)
+    _, _, total = alt.plan_chain(opc.tolist(), cvc.tolist(), 1)
+    assert abs(total - best) < 1e-4
+
+
+def test_calls_without_gpu_fail_loudly_not_silently():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    h = alt.Handle()
+    d = alt.conv_desc(1, 16, 8, 8, 16, 3, 3, pad=1, in_dtype=alt.F32)
+    assert h.conv2d_output_shape(d) == (1, 16, 8, 8)
+    with pytest.raises(alt.AltError) as e:
+        import ctypes
+        alt.lib().alt_conv2d  # symbol exists
+        h.conv2d(d, 16, 16, 16, stream=0)
+    assert e.value.status == 6
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform(alt.F32, (2, 4), "MK->MK", 16, "MK->KM", 4096, stream=0)
+    assert e.value.status == 6
+    # argument errors are reported before any device work
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform(alt.F32, (2, 4), "MK->MK", 16, "MK->KM", 16, stream=0)
+    assert e.value.status == 1
+    bad = alt.conv_desc(1, 24, 8, 8, 16, 3, 3, pad=1, x_layout="NCHW->NCHW16c")
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(bad, 16, 16, 16, stream=0)
+    assert e.value.status == 3

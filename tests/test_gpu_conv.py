@@ -1,0 +1,203 @@
+"""GPU parity: alt_conv2d against the oracle.  Operands are put into their
+layouts by the oracle's conversion operator; results are brought back to
+logical NCHW the same way, so the library's own transform is not trusted
+here.  Integer-valued inputs make every summation order exact, so those
+cases must match bit for bit under every kernel variant."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_12415_amd as alt
+from workloads import (RESNET_LAYERS, SMALL_CONV, bf16_bits_to_f32, f32_to_bf16_bits, normal_f32,
+                       small_ints_f32, uniform_f32)
+
+from gpu_util import TOL, applicable_variants, canary_dev, canary_ok, dev, from_layout, host, rel_err, to_layout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def h():
+    return alt.Handle()
+
+
+def run_conv(h, x, w, cfg, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False, variant=-1,
+             use_pack=False):
+    """x (N,C,H,W), w (K,C,R,S): float32 or uint16 bf16 bits, logical.  Returns
+    the logical NKPQ result and the variant's name."""
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
+    d = alt.conv_desc(N, C, H, W, K, R, S, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1),
+                      in_dtype=in_dtype, out_dtype=out_dtype, epilogue=epi, variant=variant,
+                      x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+    oshape = h.conv2d_output_shape(d)
+    xd = dev(to_layout(x, "NCHW", xl))
+    if use_pack:
+        wd = torch.empty_like(dev(w.reshape(-1)))
+        h.pack_weights(d, dev(w.reshape(-1)), wd)
+    else:
+        wd = dev(to_layout(w, "OIHW", wl))
+    ydt = np.float32 if out_dtype == alt.F32 else np.uint16
+    n_out = int(np.prod(oshape))
+    whole, yd = canary_dev(n_out, ydt)
+    ws_bytes = 36 * n_out * 4
+    ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device="cuda")
+    bd = dev(bias) if bias is not None else None
+    h.conv2d(d, xd, wd, yd, bias=bd, workspace=ws, ws_bytes=ws_bytes)
+    got = host(yd, ydt)
+    assert canary_ok(whole, n_out), "wrote outside y"
+    return from_layout(got, oshape, "NCHW", yl), d
+
+
+LAYOUT_SETS = [("NCHW", "OIHW", "NCHW"), ("NHWC", "OHWI", "NHWC"), ("NCHW16c", "OIHW16o16i", "NCHW16c"),
+               ("NHWC", "OIHW16i16o", "NCHW"), ("NCHW8c", "OHWI", "NHWC"), ("NCHW", "OHWI", "NCHW16c"),
+               ("NCHW32c", "OIHW32o32i", "NCHW32c")]
+
+
+def test_small_fp32_config_nchw_and_nhwc(h):
+    c = SMALL_CONV
+    x = uniform_f32(0xA17 + 1, (c["N"], c["C"], c["H"], c["W"]))
+    w = uniform_f32(0xA17 + 101, (c["K"], c["C"], c["R"], c["S"]))
+    ref = oracle.conv2d(x, w, stride=c["stride"], pad=c["pad"])
+    for xl, wl, yl in [("NCHW", "OIHW", "NCHW"), ("NHWC", "OHWI", "NHWC"), ("NHWC", "OIHW", "NCHW"),
+                       ("NCHW", "OHWI", "NHWC")]:
+        got, _ = run_conv(h, x, w, c, xl, wl, yl, alt.F32)
+        assert rel_err(got, ref) <= TOL[alt.F32], (xl, wl, yl, rel_err(got, ref))
+
+
+@pytest.mark.parametrize("layouts", LAYOUT_SETS)
+@pytest.mark.parametrize("in_dtype", [alt.BF16, alt.F32])
+def test_exact_integers_every_variant(h, layouts, in_dtype):
+    """|sum| < 2^24, so fp32 accumulation is exact in any order: every tile
+    shape, split-K factor and loader must reproduce the oracle bit for bit."""
+    xl, wl, yl = layouts
+    cfg = dict(stride=1, pad=1)
+    x = small_ints_f32(11, (3, 32, 9, 10))          # M = 270: several tiles and a ragged tail
+    w = small_ints_f32(12, (96, 32, 3, 3))          # N_g = 96: ragged against 64- and 128-wide tiles
+    ref = oracle.conv2d(x, w, stride=1, pad=1)
+    if in_dtype == alt.BF16:
+        x, w = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    d0 = alt.conv_desc(3, 32, 9, 10, 96, 3, 3, stride=1, pad=1, in_dtype=in_dtype,
+                       x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+    variants = applicable_variants(h, d0)
+    assert variants, "no variant applies"
+    for v, name in variants:
+        got, _ = run_conv(h, x, w, cfg, xl, wl, yl, in_dtype, variant=v)
+        assert np.array_equal(got, ref), name
+
+
+@pytest.mark.parametrize("cfg", [dict(stride=2, pad=1), dict(stride=1, pad=0), dict(stride=2, pad=0),
+                                 dict(stride=1, pad=2, dil=2), dict(stride=3, pad=1)])
+@pytest.mark.parametrize("layouts", LAYOUT_SETS[:4])
+def test_exact_integers_strides_and_padding(h, cfg, layouts):
+    xl, wl, yl = layouts
+    x = small_ints_f32(21, (2, 16, 11, 13))
+    w = small_ints_f32(22, (32, 16, 3, 3))
+    ref = oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1))
+    got, _ = run_conv(h, f32_to_bf16_bits(x), f32_to_bf16_bits(w), cfg, xl, wl, yl, alt.BF16)
+    assert np.array_equal(got, ref)
+
+
+def test_odd_channel_counts_and_kernels(h):
+    """C = 3 (first-layer shape), 5x5 and 1x7 kernels, K not a multiple of 8:
+    only the gather loaders apply; still exact."""
+    for (C, K, R, S, pad) in [(3, 10, 7, 7, 3), (5, 7, 1, 7, 0), (20, 24, 5, 5, 2)]:
+        x = small_ints_f32(31, (2, C, 12, 15), -2, 2)
+        w = small_ints_f32(32, (K, C, R, S), -2, 2)
+        ref = oracle.conv2d(x, w, stride=2, pad=pad)
+        for xl, wl, yl in [("NCHW", "OIHW", "NCHW"), ("NHWC", "OHWI", "NHWC")]:
+            got, _ = run_conv(h, f32_to_bf16_bits(x), f32_to_bf16_bits(w), dict(stride=2, pad=pad), xl, wl, yl,
+                              alt.BF16)
+            assert np.array_equal(got, ref), (C, K, R, S, xl)
+
+
+@pytest.mark.parametrize("layouts", LAYOUT_SETS[:3])
+def test_bias_relu_and_bf16_output(h, layouts):
+    xl, wl, yl = layouts
+    x = f32_to_bf16_bits(normal_f32(41, (2, 64, 14, 14)))
+    w = f32_to_bf16_bits(normal_f32(42, (64, 64, 3, 3), std=0.05))
+    b = normal_f32(43, (64,), std=0.1)
+    cfg = dict(stride=1, pad=1)
+    ref = oracle.conv2d(x, w, stride=1, pad=1, bias=b, relu=True)
+    got, _ = run_conv(h, x, w, cfg, xl, wl, yl, alt.BF16, bias=b, relu=True)
+    assert rel_err(got, ref) <= TOL[alt.BF16]
+    assert (got >= 0).all() and (got == 0).any()
+    got16, _ = run_conv(h, x, w, cfg, xl, wl, yl, alt.BF16, out_dtype=alt.BF16, bias=b, relu=True)
+    ref16 = oracle.conv2d(x, w, stride=1, pad=1, bias=b, relu=True, out_bf16=True)
+    # the two fp32 sums differ by rounding order, so the bf16 results may differ by one ulp
+    diff = np.abs(got16.astype(np.int32) - ref16.astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).mean() < 0.02
+    assert rel_err(bf16_bits_to_f32(got16), ref) <= TOL[alt.BF16]
+
+
+def test_pack_weights_matches_oracle_layout(h):
+    w = f32_to_bf16_bits(normal_f32(51, (64, 32, 3, 3)))
+    for wl in ["OHWI", "OIHW16o16i", "OIHW16i32o", "OIHW"]:
+        d = alt.conv_desc(1, 32, 8, 8, 64, 3, 3, pad=1, w_layout="OIHW->" + wl)
+        out = torch.empty_like(dev(w.reshape(-1)))
+        if wl == "OIHW":
+            out2 = torch.empty_like(out)
+            h.pack_weights(d, dev(w.reshape(-1)), out2)
+            assert np.array_equal(host(out2, np.uint16), w.reshape(-1))
+            continue
+        h.pack_weights(d, dev(w.reshape(-1)), out)
+        assert np.array_equal(host(out, np.uint16), to_layout(w, "OIHW", wl))
+
+
+@pytest.mark.parametrize("layer", RESNET_LAYERS, ids=[l["name"] for l in RESNET_LAYERS])
+@pytest.mark.parametrize("batch", [1, 16])
+def test_resnet_layers_sampled(h, layer, batch):
+    """Full benchmark shapes in the layouts and default variants the benchmark
+    launches; 4000 sampled outputs are computed one by one by the oracle."""
+    c = layer
+    x = f32_to_bf16_bits(normal_f32(0xA17 + 2, (batch, c["C"], c["H"], c["W"])))
+    w = f32_to_bf16_bits(normal_f32(0xA17 + 102, (c["K"], c["C"], c["R"], c["S"]), std=0.05))
+    oshape = oracle.conv_out_shape(x.shape, w.shape, c["stride"], c["pad"])
+    n_out = int(np.prod(oshape))
+    rng = np.random.RandomState(5)
+    flat = np.unique(np.concatenate([rng.randint(0, n_out, 4000), [0, n_out - 1]]))
+    ref = oracle.conv2d_at(x, w, flat, stride=c["stride"], pad=c["pad"])
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    for xl, wl, yl in [("NHWC", "OHWI", "NHWC"), ("NCHW16c", "OIHW16o16i", "NCHW16c"), ("NCHW", "OIHW", "NCHW")]:
+        d = alt.conv_desc(batch, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
+                          x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+        # inputs under the layout: through the library's transform here (checked bit-exact elsewhere),
+        # because the oracle's per-element transform of 3M elements per case would dominate the run
+        xd, wd = torch.empty_like(dev(x.reshape(-1))), torch.empty_like(dev(w.reshape(-1)))
+        h.layout_transform(alt.BF16, x.shape, "NCHW->NCHW", dev(x.reshape(-1)), "NCHW->" + xl, xd)
+        h.pack_weights(d, dev(w.reshape(-1)), wd)
+        yd = torch.empty(n_out, dtype=torch.float32, device="cuda")
+        ws_bytes = h.conv2d_workspace_size(d)
+        ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
+        h.conv2d(d, xd, wd, yd, workspace=ws, ws_bytes=ws_bytes)
+        ylog = torch.empty_like(yd)
+        h.layout_transform(alt.F32, oshape, "NCHW->" + yl, yd, "NCHW->NCHW", ylog)
+        got = host(ylog, np.float32)[flat].astype(np.float64)
+        err = float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+        assert err <= TOL[alt.BF16], (xl, err)
+        assert err <= 1e-4, (xl, err)          # fp32 accumulation of exact bf16 products is far tighter
+
+
+def test_conv_errors(h):
+    a = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    d = alt.conv_desc(1, 24, 8, 8, 16, 3, 3, pad=1, x_layout="NCHW->NCHW16c")
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(d, a, a, a)
+    assert e.value.status == 3
+    d = alt.conv_desc(1, 16, 8, 8, 16, 3, 3, pad=1, epilogue=alt.EPI_BIAS)
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(d, a, a, a)                    # bias flag without a bias pointer
+    assert e.value.status == 1
+    d = alt.conv_desc(1, 16, 2, 2, 16, 5, 5, pad=0)
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(d, a, a, a)                    # kernel larger than the input
+    assert e.value.status == 1
+    d = alt.conv_desc(2, 32, 9, 10, 96, 3, 3, pad=1, in_dtype=alt.BF16,
+                      x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+    split_variants = [v for v, n in applicable_variants(h, d) if not n.endswith("_k1")]
+    d.variant = split_variants[0]
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(d, a, a, a, workspace=None, ws_bytes=0)
+    assert e.value.status == 5

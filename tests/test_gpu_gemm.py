@@ -1,0 +1,110 @@
+"""GPU parity: alt_gemm against the oracle's triple loop."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_12415_amd as alt
+from workloads import BERT_GEMMS, BERT_QKT, f32_to_bf16_bits, normal_f32, small_ints_f32
+
+from gpu_util import TOL, applicable_variants, canary_dev, canary_ok, dev, from_layout, host, rel_err, to_layout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def h():
+    return alt.Handle()
+
+
+def run_gemm(h, A, B, al, bl, cl, in_dtype, out_dtype=alt.F32, variant=-1):
+    """A (batch,M,K), B (batch,K,N) logical.  Returns logical (batch,M,N)."""
+    batch, M, K = A.shape
+    N = B.shape[2]
+    d = alt.gemm_desc(M, N, K, batch=batch, in_dtype=in_dtype, out_dtype=out_dtype, variant=variant,
+                      a_layout="MK->" + al, b_layout="KN->" + bl, c_layout="MN->" + cl)
+    Ap = np.concatenate([to_layout(A[b], "MK", al) for b in range(batch)])
+    Bp = np.concatenate([to_layout(B[b], "KN", bl) for b in range(batch)])
+    cdt = np.float32 if out_dtype == alt.F32 else np.uint16
+    whole, Cd = canary_dev(batch * M * N, cdt)
+    ws_bytes = 36 * batch * M * N * 4
+    ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device="cuda")
+    h.gemm(d, dev(Ap), dev(Bp), Cd, workspace=ws, ws_bytes=ws_bytes)
+    got = host(Cd, cdt)
+    assert canary_ok(whole, batch * M * N)
+    return np.stack([from_layout(got[b * M * N:(b + 1) * M * N], (M, N), "MN", cl) for b in range(batch)]), d
+
+
+GEMM_LAYOUTS = [("MK", "KN", "MN"), ("MK", "NK", "MN"), ("KM", "KN", "MN"), ("KM", "NK", "NM"),
+                ("MK32m16k", "NK32n16k", "MN"), ("MK", "KN16k32n", "MN16m8n"), ("MK", "NK64n32k", "MN")]
+
+
+@pytest.mark.parametrize("layouts", GEMM_LAYOUTS)
+@pytest.mark.parametrize("in_dtype", [alt.BF16, alt.F32])
+def test_exact_integers_every_variant(h, layouts, in_dtype):
+    al, bl, cl = layouts
+    batch, M, K, N = 2, 160, 96, 192
+    A = small_ints_f32(61, (batch, M, K))
+    B = small_ints_f32(62, (batch, K, N))
+    ref = oracle.gemm(A, B)
+    if in_dtype == alt.BF16:
+        A, B = f32_to_bf16_bits(A), f32_to_bf16_bits(B)
+    d0 = alt.gemm_desc(M, N, K, batch=batch, in_dtype=in_dtype, a_layout="MK->" + al, b_layout="KN->" + bl,
+                       c_layout="MN->" + cl)
+    variants = applicable_variants(h, d0, "gemm")
+    assert variants
+    for v, name in variants:
+        got, _ = run_gemm(h, A, B, al, bl, cl, in_dtype, variant=v)
+        assert np.array_equal(got, ref), name
+
+
+def test_ragged_sizes(h):
+    for (M, K, N) in [(1, 8, 8), (37, 40, 24), (130, 72, 200), (64, 4608, 64)]:
+        A = small_ints_f32(63, (1, M, K), -2, 2)
+        B = small_ints_f32(64, (1, K, N), -2, 2)
+        ref = oracle.gemm(A, B)
+        for al, bl in [("MK", "KN"), ("MK", "NK")]:
+            got, _ = run_gemm(h, f32_to_bf16_bits(A), f32_to_bf16_bits(B), al, bl, "MN", alt.BF16)
+            assert np.array_equal(got, ref), (M, K, N, al, bl)
+    # K not a multiple of 8: only the gather loaders can run it
+    A = small_ints_f32(65, (1, 20, 13))
+    B = small_ints_f32(66, (1, 13, 9))
+    got, _ = run_gemm(h, f32_to_bf16_bits(A), f32_to_bf16_bits(B), "MK", "KN", "MN", alt.BF16)
+    assert np.array_equal(got, oracle.gemm(A, B))
+
+
+def test_tolerance_fp32_and_bf16_out(h):
+    A = normal_f32(67, (1, 256, 768), std=0.02)
+    B = normal_f32(68, (1, 768, 192), std=0.02)
+    ref = oracle.gemm(A, B)
+    got, _ = run_gemm(h, A, B, "MK", "KN", "MN", alt.F32)
+    assert rel_err(got, ref) <= TOL[alt.F32]
+    Ab, Bb = f32_to_bf16_bits(A), f32_to_bf16_bits(B)
+    ref = oracle.gemm(Ab, Bb)
+    got, _ = run_gemm(h, Ab, Bb, "MK", "NK", "MN", alt.BF16)
+    assert rel_err(got, ref) <= 1e-4
+    got16, _ = run_gemm(h, Ab, Bb, "MK", "NK", "MN", alt.BF16, out_dtype=alt.BF16)
+    ref16 = oracle.gemm(Ab, Bb, out_bf16=True)
+    diff = np.abs(got16.astype(np.int32) - ref16.astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).mean() < 0.02
+
+
+@pytest.mark.parametrize("g", BERT_GEMMS + [BERT_QKT], ids=[g["name"] for g in BERT_GEMMS + [BERT_QKT]])
+def test_bert_shapes_sampled(h, g):
+    batch, M, K, N = g["batch"], g["M"], g["K"], g["N"]
+    A = f32_to_bf16_bits(normal_f32(0xA17 + 4, (batch, M, K), std=0.02))
+    B = f32_to_bf16_bits(normal_f32(0xA17 + 104, (batch, K, N), std=0.02))
+    rng = np.random.RandomState(9)
+    flat = np.unique(np.concatenate([rng.randint(0, batch * M * N, 3000), [0, batch * M * N - 1]]))
+    ref = oracle.gemm_at(A, B, flat)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    for bl in ["KN", "NK"]:
+        d = alt.gemm_desc(M, N, K, batch=batch, b_layout="KN->" + bl)
+        Bp = B if bl == "KN" else np.ascontiguousarray(B.transpose(0, 2, 1))
+        Cd = torch.empty(batch * M * N, dtype=torch.float32, device="cuda")
+        ws_bytes = h.gemm_workspace_size(d)
+        ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
+        h.gemm(d, dev(A.reshape(-1)), dev(Bp.reshape(-1)), Cd, workspace=ws, ws_bytes=ws_bytes)
+        got = host(Cd, np.float32)[flat].astype(np.float64)
+        err = float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+        assert err <= 1e-4, (bl, err)

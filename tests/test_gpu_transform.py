@@ -1,0 +1,119 @@
+"""GPU parity: alt_layout_transform against the oracle's conversion operator,
+bit for bit, on small ragged shapes (every kernel path), on the full
+benchmark shapes, and on general primitive sequences."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_12415_amd as alt
+from workloads import TRANSFORM_SHAPES, special_bit_patterns
+
+from gpu_util import canary_dev, canary_ok, dev, host
+
+pytestmark = pytest.mark.gpu
+
+NP = {alt.F32: np.uint32, alt.BF16: np.uint16}
+
+
+@pytest.fixture(scope="module")
+def h():
+    return alt.Handle()
+
+
+def _run(h, dtype, shape, src_name, dst_name, seed=1):
+    logical = src_name.split("->")[0]
+    bits = 32 if dtype == alt.F32 else 16
+    data = special_bit_patterns(seed, shape, bits).reshape(-1)       # the physical source buffer
+    s_seq = oracle.seq_from_string(src_name, shape)
+    d_seq = oracle.seq_from_string(logical + "->" + dst_name.split("->")[1], shape)
+    want = oracle.layout_transform(data, shape, s_seq, d_seq)
+    src = dev(data)
+    whole, dst = canary_dev(data.size, NP[dtype])
+    h.layout_transform(dtype, shape, src_name, src, dst_name, dst)
+    got = host(dst, NP[dtype])
+    assert canary_ok(whole, data.size), "wrote outside the destination"
+    assert np.array_equal(got, want), (src_name, dst_name, shape)
+
+
+PAIRS4 = [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
+          ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW16c", "NCHW->NCHW"),
+          ("NCHW->NCHW", "NCHW->NCHW32c"), ("NCHW->NHWC", "NCHW->NCHW16c"),
+          ("NCHW->NCHW16c", "NCHW->NHWC"), ("NCHW->NCHW16c", "NCHW->NCHW32c"),
+          ("NCHW->NCHW32c", "NCHW->NCHW8c"), ("NCHW->NCHW", "NCHW->HWNC"),
+          ("NCHW->NHWC", "NCHW->NHWC"), ("NCHW->CNHW", "NCHW->NCHW4c")]
+SMALL4 = [(2, 32, 5, 7), (3, 64, 14, 14), (1, 32, 1, 1), (2, 96, 7, 7), (1, 32, 9, 40)]
+
+
+@pytest.mark.parametrize("dtype", [alt.F32, alt.BF16])
+@pytest.mark.parametrize("shape", SMALL4)
+@pytest.mark.parametrize("pair", PAIRS4)
+def test_transform_small(h, dtype, shape, pair):
+    _run(h, dtype, shape, pair[0], pair[1])
+
+
+@pytest.mark.parametrize("dtype", [alt.F32, alt.BF16])
+@pytest.mark.parametrize("shape", TRANSFORM_SHAPES)
+@pytest.mark.parametrize("pair", [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
+                                  ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW", "NCHW->NCHW32c")])
+def test_transform_benchmark_shapes(h, dtype, shape, pair):
+    _run(h, dtype, shape, pair[0], pair[1], seed=7)
+
+
+@pytest.mark.parametrize("dtype", [alt.F32, alt.BF16])
+def test_transform_weights_and_matrices(h, dtype):
+    _run(h, dtype, (64, 32, 3, 3), "OIHW->OIHW", "OIHW->OHWI")
+    _run(h, dtype, (64, 32, 3, 3), "OIHW->OIHW", "OIHW->OIHW16o16i")
+    _run(h, dtype, (64, 32, 3, 3), "OIHW->OIHW", "OIHW->OIHW16i32o")
+    _run(h, dtype, (48, 24, 1, 1), "OIHW->OIHW8i4o", "OIHW->OIHW12o8i")      # blocks that do not nest
+    _run(h, dtype, (100, 72), "MK->MK", "MK->KM")
+    _run(h, dtype, (128, 96), "MK->MK", "MK->MK32m16k")
+    _run(h, dtype, (96, 128), "KN->KN", "KN->NK64n32k")
+    _run(h, dtype, (7, 13), "MK->MK", "MK->KM")
+
+
+@pytest.mark.parametrize("dtype", [alt.F32, alt.BF16])
+def test_transform_general_sequences(h, dtype):
+    """Sequences with a fuse cut across the old dimensions (Section 4.1.1's
+    N(O/4)(HW)4 example) go through the per-element kernel."""
+    N, H, W, O = 2, 3, 5, 8
+    shape = (N, H, W, O)
+    bits = 32 if dtype == alt.F32 else 16
+    data = special_bit_patterns(3, shape, bits).reshape(-1)
+    oseq = [oracle.fuse(1, 3), oracle.split(1, [O // 4, 4, H * W]), oracle.reorder([0, 1, 3, 2])]
+    L = alt.layout_from_prims(shape, [alt.fuse(1, 3), alt.split(1, [O // 4, 4, H * W]), alt.reorder([0, 1, 3, 2])])
+    plain = alt.layout_parse("NHWO->NHWO")
+    want = oracle.layout_transform(data, shape, [], oseq)
+    dst = torch.empty_like(dev(data))
+    h.layout_transform(dtype, shape, plain, dev(data), L, dst)
+    assert np.array_equal(host(dst, NP[dtype]), want)
+    back = torch.empty_like(dst)
+    h.layout_transform(dtype, shape, L, dst, plain, back)
+    assert np.array_equal(host(back, NP[dtype]), data)
+
+
+def test_transform_round_trip_and_composition(h):
+    shape = (4, 64, 14, 14)
+    data = special_bit_patterns(5, shape, 16).reshape(-1)
+    a, b, c = dev(data), torch.empty_like(dev(data)), torch.empty_like(dev(data))
+    d = torch.empty_like(a)
+    h.layout_transform(alt.BF16, shape, "NCHW->NCHW", a, "NCHW->NHWC", b)
+    h.layout_transform(alt.BF16, shape, "NCHW->NHWC", b, "NCHW->NCHW16c", c)
+    h.layout_transform(alt.BF16, shape, "NCHW->NCHW", a, "NCHW->NCHW16c", d)
+    assert torch.equal(c, d)
+    h.layout_transform(alt.BF16, shape, "NCHW->NCHW16c", c, "NCHW->NCHW", b)
+    assert np.array_equal(host(b, np.uint16), data)
+
+
+def test_transform_errors(h):
+    a = torch.zeros(64, dtype=torch.float32, device="cuda")
+    b = torch.zeros(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform(alt.F32, (1, 24, 1, 1), "NCHW->NCHW", a, "NCHW->NCHW16c", b)
+    assert e.value.status == 3
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform(alt.F32, (2, 4, 2, 4), "NCHW->NCHW", a, "NCHW->NHWC", a)
+    assert e.value.status == 1
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform(7, (2, 4, 2, 4), "NCHW->NCHW", a, "NCHW->NHWC", b)
+    assert e.value.status == 1
