@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv2d / gemm / layout_transform path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one pass over the five ResNet-50-style convolution layers at batch
+16 (bf16 inputs, fp32 accumulation on the matrix cores, fp32 output), each
+under the layouts and kernel variant the tuner picked, inputs already resident
+in HBM in the tuned layout (the producer writes the consumer's layout; weights
+are packed once, offline).  `value` is the layers' nominal FLOPs per step over
+the measured time per step.  The same run also reports, under "extra", the
+per-layer figures, the layout conversion operator on the activation shapes
+(GB/s), the BERT-shaped matrix products, the batch-1 layers, the three-layer
+chain and the tuner's best-vs-default-layout ratios.  Prints one JSON line.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--quick", action="store_true", help="skip the extra sections")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2210_12415_amd as alt
+    from workloads import (RESNET_LAYERS, TRANSFORM_SHAPES, BERT_GEMMS, BERT_QKT, CHAIN_LAYERS,
+                           conv_flops, conv_out_hw, f32_to_bf16_bits, normal_f32)
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    alt.lib()                                   # fails loudly if libalt.so is missing
+    dev = torch.device("cuda:0")
+    h = alt.Handle()
+    stream = torch.cuda.current_stream()
+
+    def dbuf(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    arena = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+
+    def timed(fn, reps, warm=5):
+        """Average microseconds per call over `reps` back-to-back calls (HIP
+        events on the launch stream)."""
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1000.0 / reps
+
+    def median_timed(fn, reps, batches=5):
+        return float(np.median([timed(fn, reps) for _ in range(batches)]))
+
+    # ------------------------------------------------------------ conv layers ----
+    def prepare_layers(batch, out_dtype, budget):
+        """Tunes each layer, then lays out its operands for the tuned layouts."""
+        layers = []
+        for li, L in enumerate(RESNET_LAYERS):
+            shape = alt.conv_desc(batch, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"],
+                                  pad=L["pad"], in_dtype=alt.BF16, out_dtype=out_dtype)
+            best, rep = h.tune_conv2d(shape, arena, arena.numel(), max_trials=budget, warmup=3, reps=30)
+            x = f32_to_bf16_bits(normal_f32(0xA17 + 2 + li, (batch, L["C"], L["H"], L["W"])))
+            w = f32_to_bf16_bits(normal_f32(0xA17 + 102 + li, (L["K"], L["C"], L["R"], L["S"]), std=0.05))
+            x_nchw, w_oihw = dbuf(x.reshape(-1)), dbuf(w.reshape(-1))
+            xd, wd = torch.empty_like(x_nchw), torch.empty_like(w_oihw)
+            h.layout_transform(alt.BF16, x.shape, "NCHW->NCHW", x_nchw, best.x_layout, xd)
+            h.pack_weights(best, w_oihw, wd)
+            oh, ow = conv_out_hw(L["H"], L["W"], L["R"], L["S"], L["stride"], L["pad"])
+            n_out = batch * L["K"] * oh * ow
+            yd = torch.empty(n_out, dtype=torch.float32 if out_dtype == alt.F32 else torch.int16, device=dev)
+            ws_bytes = h.conv2d_workspace_size(best)
+            ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+            names = [rep.layout_name[i].value.decode() for i in range(rep.n_layouts)]
+            lus = [rep.layout_best_us[i] for i in range(rep.n_layouts)]
+            layers.append(dict(L=L, desc=best, x=xd, w=wd, y=yd, ws=ws, ws_bytes=ws_bytes, x_nchw=x_nchw,
+                               flops=conv_flops(batch, **L), rep=rep,
+                               layout=names[int(np.argmin(lus))], variant=h.conv2d_variant_name(best, best.variant),
+                               layout_us=dict(zip(names, [round(float(u), 2) for u in lus])),
+                               trials=rep.trials, default_us=float(rep.default_us), best_us=float(rep.best_us),
+                               bytes=(x.size + w.size) * 2 + n_out * (4 if out_dtype == alt.F32 else 2)))
+        return layers
+
+    def run_layer(l):
+        h.conv2d(l["desc"], l["x"], l["w"], l["y"], workspace=l["ws"], ws_bytes=l["ws_bytes"], stream=stream)
+
+    layers = prepare_layers(16, alt.F32, 0)
+    torch.cuda.synchronize()
+
+    def step():
+        for l in layers:
+            run_layer(l)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1000.0
+    ms_per_step = wall_ms / args.steps
+    dev_ms_per_step = e0.elapsed_time(e1) / args.steps
+    step_flops = sum(l["flops"] for l in layers)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-layer kernel durations, live, on the launch stream
+    per_layer = []
+    for l in layers:
+        us = median_timed(lambda l=l: run_layer(l), 200)
+        l["us"] = us
+        per_layer.append(dict(layer=l["L"]["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
+                              tflops=round(l["flops"] / us / 1e6, 1),
+                              frac_mfma_peak=round(l["flops"] / us / 1e6 / PEAK_BF16_TFLOPS, 4),
+                              compulsory_GBps=round(l["bytes"] / us / 1e3, 1),
+                              tuner_trials=l["trials"], default_layout_us=round(l["default_us"], 2),
+                              tuned_us=round(l["best_us"], 2),
+                              speedup_vs_default_layout=round(l["default_us"] / l["best_us"], 2),
+                              layout_us=l["layout_us"]))
+    dom = max(layers, key=lambda l: l["us"])
+    achieved = dom["flops"] / dom["us"] / 1e6
+    roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    kernel="igemm_kernel<%s>" % dom["variant"], layer=dom["L"]["name"],
+                    us_per_launch=round(dom["us"], 3), flops_per_launch=dom["flops"])
+
+    extra = dict(per_layer_b16=per_layer, device_ms_per_step=round(dev_ms_per_step, 4))
+
+    if not args.quick:
+        # -------------------------------------------------- conversion operator ----
+        tr = []
+        for shp in TRANSFORM_SHAPES:
+            numel = int(np.prod(shp))
+            for dt, tdt, es in [(alt.F32, torch.float32, 4), (alt.BF16, torch.int16, 2)]:
+                # a ring of distinct buffers larger than the last-level cache, so every launch streams from HBM
+                nring = max(2, int(math.ceil((768 << 20) / (numel * es * 2))))
+                srcs = [torch.randn(numel, device=dev).to(tdt) if tdt == torch.float32 else
+                        torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev) for _ in range(nring)]
+                dsts = [torch.empty(numel, dtype=tdt, device=dev) for _ in range(nring)]
+                for a, b in [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
+                             ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW", "NCHW->NCHW32c")]:
+                    la, lb = alt.layout_parse(a), alt.layout_parse(b)
+                    state = dict(i=0)
+
+                    def f():
+                        i = state["i"] = (state["i"] + 1) % nring
+                        h.layout_transform(dt, shp, la, srcs[i], lb, dsts[i], stream=stream)
+
+                    us_cold = median_timed(f, 4 * nring, batches=3)
+                    us_warm = median_timed(lambda: h.layout_transform(dt, shp, la, srcs[0], lb, dsts[0], stream=stream), 100, 3)
+                    gb = 2.0 * numel * es / 1e9
+                    tr.append(dict(shape=list(shp), dtype="f32" if dt == alt.F32 else "bf16",
+                                   src=a.split(">")[1], dst=b.split(">")[1], us_hbm=round(us_cold, 2),
+                                   GBps_hbm=round(gb / (us_cold * 1e-6), 1),
+                                   frac_hbm_peak=round(gb / (us_cold * 1e-6) / PEAK_HBM_GBPS, 4),
+                                   us_cache_resident=round(us_warm, 2), GBps_cache_resident=round(gb / (us_warm * 1e-6), 1)))
+                del srcs, dsts
+        extra["layout_transform"] = tr
+        # scaled beyond the configs: 16x the batch, to show the kernel away from launch overhead
+        big = (256, 64, 56, 56)
+        numel = int(np.prod(big))
+        s0 = torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev)
+        s1 = torch.empty_like(s0)
+        us = median_timed(lambda: h.layout_transform(alt.BF16, big, "NCHW->NCHW", s0, "NCHW->NHWC", s1, stream=stream), 20, 3)
+        extra["layout_transform_scaled_256x64x56x56_bf16_nchw_to_nhwc"] = dict(
+            us=round(us, 1), GBps=round(2.0 * numel * 2 / 1e9 / (us * 1e-6), 1),
+            frac_hbm_peak=round(2.0 * numel * 2 / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4))
+        del s0, s1
+
+        # ------------------------------------------------------------------ gemm ----
+        gm = []
+        for g in BERT_GEMMS + [BERT_QKT]:
+            d0 = alt.gemm_desc(g["M"], g["N"], g["K"], batch=g["batch"], in_dtype=alt.BF16, out_dtype=alt.F32)
+            best, rep = h.tune_gemm(d0, arena, arena.numel(), max_trials=0, warmup=3, reps=30)
+            A = torch.randint(-200, 200, (g["batch"] * g["M"] * g["K"],), dtype=torch.int16, device=dev)
+            B = torch.randint(-200, 200, (g["batch"] * g["K"] * g["N"],), dtype=torch.int16, device=dev)
+            Cd = torch.empty(g["batch"] * g["M"] * g["N"], dtype=torch.float32, device=dev)
+            wsb = h.gemm_workspace_size(best)
+            ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+            us = median_timed(lambda: h.gemm(best, A, B, Cd, workspace=ws, ws_bytes=wsb, stream=stream), 200)
+            fl = 2.0 * g["batch"] * g["M"] * g["N"] * g["K"]
+            names = [rep.layout_name[i].value.decode() for i in range(rep.n_layouts)]
+            lus = [float(rep.layout_best_us[i]) for i in range(rep.n_layouts)]
+            gm.append(dict(gemm=g["name"], M=g["M"], N=g["N"], K=g["K"], batch=g["batch"],
+                           layout=names[int(np.argmin(lus))], variant=h.gemm_variant_name(best, best.variant),
+                           us=round(us, 3), tflops=round(fl / us / 1e6, 1),
+                           frac_mfma_peak=round(fl / us / 1e6 / PEAK_BF16_TFLOPS, 4),
+                           default_layout_us=round(float(rep.default_us), 2), tuned_us=round(float(rep.best_us), 2),
+                           speedup_vs_default_layout=round(float(rep.default_us) / float(rep.best_us), 2),
+                           tuner_trials=rep.trials, layout_us=dict(zip(names, [round(u, 2) for u in lus]))))
+        extra["gemm_bert"] = gm
+
+        # ------------------------------------------------------- batch-1 layers ----
+        l1 = prepare_layers(1, alt.F32, 0)
+        b1 = []
+        for l in l1:
+            us = median_timed(lambda l=l: run_layer(l), 200)
+            b1.append(dict(layer=l["L"]["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
+                           tflops=round(l["flops"] / us / 1e6, 2),
+                           speedup_vs_default_layout=round(l["default_us"] / l["best_us"], 2)))
+        extra["per_layer_b1"] = b1
+        del l1
+
+        # ---------------------------------------- scaled: 16x batch, bf16 output ----
+        scaled = []
+        for L in RESNET_LAYERS[:1] + RESNET_LAYERS[2:3]:
+            batch = 256
+            shape = alt.conv_desc(batch, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"],
+                                  pad=L["pad"], in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                  x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+            xs = torch.randint(-200, 200, (batch * L["C"] * L["H"] * L["W"],), dtype=torch.int16, device=dev)
+            wsd = torch.randint(-200, 200, (L["K"] * L["C"] * L["R"] * L["S"],), dtype=torch.int16, device=dev)
+            oh, ow = conv_out_hw(L["H"], L["W"], L["R"], L["S"], L["stride"], L["pad"])
+            ys = torch.empty(batch * L["K"] * oh * ow, dtype=torch.int16, device=dev)
+            us_best, _ = h.tune_conv2d_variants(shape, arena, arena.numel(), max_trials=24, warmup=2, reps=10)
+            us = median_timed(lambda: h.conv2d(shape, xs, wsd, ys, workspace=arena, ws_bytes=arena.numel(), stream=stream), 20, 3)
+            fl = conv_flops(batch, **L)
+            scaled.append(dict(layer=L["name"], batch=batch, variant=h.conv2d_variant_name(shape, shape.variant),
+                               us=round(us, 1), tflops=round(fl / us / 1e6, 1),
+                               frac_mfma_peak=round(fl / us / 1e6 / PEAK_BF16_TFLOPS, 4)))
+            del xs, wsd, ys
+        extra["conv_scaled_batch256_nhwc_bf16out"] = scaled
+
+        # ------------------------------------------------------------------ chain ----
+        ops = [alt.conv_desc(16, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
+                             in_dtype=alt.BF16, out_dtype=alt.BF16,
+                             epilogue=(alt.EPI_BIAS if c["bias"] else 0) | (alt.EPI_RELU if c["relu"] else 0))
+               for c in CHAIN_LAYERS]
+        plan = h.tune_chain(ops, "NCHW->NCHW", arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        extra["chain"] = dict(planned_total_us=round(float(plan.total_us), 2),
+                              all_nchw_total_us=round(float(plan.default_total_us), 2),
+                              speedup_vs_all_nchw=round(float(plan.default_total_us) / float(plan.total_us), 2),
+                              transforms_inserted=[int(plan.transform_before[i]) for i in range(plan.nops)],
+                              op_us=[round(float(plan.op_us[i]), 2) for i in range(plan.nops)],
+                              transform_us=[round(float(plan.transform_us[i]), 2) for i in range(plan.nops)],
+                              variants=[h.conv2d_variant_name(plan.op[i], plan.op[i].variant) for i in range(plan.nops)],
+                              measurements=plan.trials)
+
+        pk = h.get_peak(arena, arena.numel())
+        extra["attainable"] = dict(copy_GBps=round(float(pk.copy_gbps), 1),
+                                   mfma_bf16_TFLOPs=round(float(pk.mfma_bf16_tflops), 1),
+                                   compute_units=pk.compute_units, clock_mhz=pk.clock_mhz,
+                                   arch=pk.arch.decode())
+
+    # ------------------------------------------------------------ cpu baseline ----
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        t_total, f_total = 0.0, 0.0
+        for li, L in enumerate(RESNET_LAYERS):
+            x = f32_to_bf16_bits(normal_f32(0xA17 + 2 + li, (1, L["C"], L["H"], L["W"])))
+            w = f32_to_bf16_bits(normal_f32(0xA17 + 102 + li, (L["K"], L["C"], L["R"], L["S"]), std=0.05))
+            t0 = time.perf_counter()
+            oracle.conv2d(x, w, stride=L["stride"], pad=L["pad"])
+            t_total += time.perf_counter() - t0
+            f_total += conv_flops(1, **L)
+        cpu = dict(value=round(f_total / t_total / 1e12, 6), unit="TFLOP/s", cores=oracle.num_threads(),
+                   kind="oracle", sample="the five layers at batch 1 (1/16 of one step), one pass, %.2f s" % t_total)
+
+    out = dict(metric="conv2d/GEMM TFLOP/s (% bf16 MFMA peak); layout_transform GB/s (% HBM)",
+               value=round(value, 2), unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload="ResNet-50-style conv layers (C64 56x56 3x3, C128 28x28 3x3, C256 14x14 3x3, "
+                                    "C512 7x7 3x3, C256->64 56x56 1x1), batch 16, bf16 in / fp32 accumulate / fp32 out, "
+                                    "tuned layout per layer, inputs resident in the tuned layout",
+                           flops_per_step=step_flops, frac_bf16_mfma_peak=round(value / PEAK_BF16_TFLOPS, 4)),
+               roofline=roofline, cpu_baseline=cpu, extra=extra)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

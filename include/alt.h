@@ -181,7 +181,11 @@ typedef struct {
  * x, w, y are device pointers holding the tensors under the descriptor's
  * layouts; `w` is what alt_pack_weights wrote (or any buffer already in
  * w_layout).  bias may be NULL without ALT_EPI_BIAS.  `workspace` (device,
- * ws_bytes) must be at least alt_conv2d_workspace_size for the variant used.
+ * ws_bytes) holds split-K partial sums.  With variant = -1 the library only
+ * picks variants whose partial sums fit the workspace given (none is needed
+ * without split-K, so NULL/0 always works); alt_conv2d_workspace_size reports
+ * what the preferred variant would like.  An explicitly requested variant
+ * whose needs exceed ws_bytes fails with ALT_WORKSPACE_TOO_SMALL.
  * Asynchronous on `stream`. */
 alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
                         const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);

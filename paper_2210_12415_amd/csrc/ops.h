@@ -21,7 +21,7 @@ void igemm_analyse(Problem *pb);
 bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, IgemmParams *out, std::string *why);
 size_t igemm_workspace(const Problem &pb, int splitk);
 double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams &p);
-int igemm_default_variant(const Problem &pb);
+int igemm_default_variant(const Problem &pb, size_t ws_limit);
 alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *workspace, size_t ws_bytes,
                        hipStream_t st);
 

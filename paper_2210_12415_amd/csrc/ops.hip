@@ -150,7 +150,7 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
     return est;
 }
 
-int igemm_default_variant(const Problem &pb)
+int igemm_default_variant(const Problem &pb, size_t ws_limit)
 {
     const auto &tab = igemm_table();
     double best = 1e300;
@@ -159,6 +159,7 @@ int igemm_default_variant(const Problem &pb)
         for (int si = 0; si < kNumSplits; ++si) {
             IgemmParams p;
             if (!igemm_applicable(pb, tab[ki], kSplits[si], &p, nullptr)) continue;
+            if (igemm_workspace(pb, kSplits[si]) > ws_limit) continue;
             const double est = igemm_estimate(pb, tab[ki], p);
             if (est < best) { best = est; best_v = ki * kNumSplits + si; }
         }
@@ -308,7 +309,10 @@ alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out)
     return (out[2] < 1 || out[3] < 1) ? ALT_INVALID_ARG : ALT_OK;
 }
 
-static int pick_variant(alt_handle_t h, const Problem &pb, int requested, const std::string &key)
+// variant = -1: the cached tuned variant if it applies and its split-K partial
+// sums fit the workspace the caller brought, else the best-estimate variant
+// that fits.
+static int pick_variant(alt_handle_t h, const Problem &pb, int requested, const std::string &key, size_t ws_limit)
 {
     if (requested >= 0) return requested;
     auto it = h->cache.find(key);
@@ -317,10 +321,11 @@ static int pick_variant(alt_handle_t h, const Problem &pb, int requested, const 
         const auto &tab = igemm_table();
         int v = it->second.variant;
         if (v >= 0 && v < (int)tab.size() * kNumSplits &&
-            igemm_applicable(pb, tab[v / kNumSplits], kSplits[v % kNumSplits], nullptr, nullptr))
+            igemm_applicable(pb, tab[v / kNumSplits], kSplits[v % kNumSplits], nullptr, nullptr) &&
+            igemm_workspace(pb, kSplits[v % kNumSplits]) <= ws_limit)
             return v;
     }
-    return igemm_default_variant(pb);
+    return igemm_default_variant(pb, ws_limit);
 }
 
 alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
@@ -332,7 +337,7 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
     Problem pb;
     alt_status_t s = conv_problem(h, d, x, w, bias, y, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, conv_key(h, d));
+    int v = pick_variant(h, pb, d->variant, conv_key(h, d), workspace ? ws_bytes : 0);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_conv2d: no kernel variant applies");
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
 }
@@ -345,7 +350,7 @@ alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d,
     // alignment of real pointers is unknown here: assume 16-byte aligned buffers
     alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, conv_key(h, d));
+    int v = pick_variant(h, pb, d->variant, conv_key(h, d), (size_t)-1);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
     *bytes = igemm_workspace(pb, kSplits[v % kNumSplits]);
     return ALT_OK;
@@ -399,7 +404,7 @@ alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, c
     Problem pb;
     alt_status_t s = gemm_problem(h, d, A, B, C, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, gemm_key(h, d));
+    int v = pick_variant(h, pb, d->variant, gemm_key(h, d), workspace ? ws_bytes : 0);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_gemm: no kernel variant applies");
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
 }
@@ -411,7 +416,7 @@ alt_status_t alt_gemm_workspace_size(alt_handle_t h, const alt_gemm_desc_t *d, s
     Problem pb;
     alt_status_t s = gemm_problem(h, d, (void *)16, (void *)16, (void *)16, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, gemm_key(h, d));
+    int v = pick_variant(h, pb, d->variant, gemm_key(h, d), (size_t)-1);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
     *bytes = igemm_workspace(pb, kSplits[v % kNumSplits]);
     return ALT_OK;
