@@ -3,7 +3,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIBPATH = os.path.join(_HERE, "libalt.so")
+_LIBPATH = os.environ.get("ALT_LIBRARY", os.path.join(_HERE, "libalt.so"))   # ALT_LIBRARY: developer builds
 
 F32, BF16 = 0, 1
 EPI_BIAS, EPI_RELU = 1, 2

@@ -46,11 +46,41 @@ alt_status_t bind_layout(const alt_layout_t *l, int ndim, const int64_t *shape, 
 // Two-level strided addressing of one logical dimension:
 // off(i) = (i / f) * so + (i % f) * si.  An unsplit dimension has f = extent
 // (so unused).  Everything conv/gemm kernels need to know about a layout.
+// Division by a runtime constant without a divide: for 0 <= n < 2^31 and
+// d >= 2, n / d == umulhi(n, mul) >> shift with mul = ceil(2^(32+shift) / d),
+// shift = ceil(log2 d) - 1 (the rounding error n * (mul*d - 2^(32+shift)) stays
+// below 2^(32+shift)); d == 1 is passed through.
+struct FastDiv {
+    uint32_t d, mul, shift, pad_;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f{d, 0, 0, 0};
+    if (d <= 1) return f;
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;                       // ceil(log2 d)
+    const unsigned p = 31 + l;
+    f.mul = (uint32_t)((((uint64_t)1 << p) + d - 1) / d);     // < 2^32
+    f.shift = p - 32;
+    return f;
+}
+
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return f.d <= 1 ? n : (__umulhi(n, f.mul) >> f.shift);
+#else
+    return f.d <= 1 ? n : (uint32_t)(((uint64_t)n * f.mul) >> 32) >> f.shift;
+#endif
+}
+
 struct Dim2 {
     int32_t f;
     int32_t pad_;
     int64_t so;
     int64_t si;
+    FastDiv fd;        // of f
 };
 
 // Reduces a bound separable layout to one Dim2 per logical dimension; fails if

@@ -8,9 +8,12 @@
 // "B" operand (weights) in LDS, both stored [row][k] with k contiguous,
 // because every 32x32 MFMA lane consumes 8 (bf16) or 4 (fp32) consecutive k
 // of one row.  LDS rows are padded by 16 bytes so that the 16-byte operand
-// reads of a wavefront fall on distinct banks.  Global loads of step t+1 are
-// issued before the MFMAs of step t and written to the other LDS stage
-// afterwards (register prefetch + double buffering, one barrier per step).
+// reads of a wavefront fall on distinct banks.  Global loads run PF steps
+// ahead of the MFMAs: the loads of step t+PF are issued before the MFMAs of
+// step t into a register slot of their own, and the registers of step t+1 go
+// to the other LDS stage after them (register prefetch of depth PF + LDS double
+// buffering, one barrier per step).  With few workgroups per CU the load
+// latency is what a step costs, so PF > 1 is what keeps the matrix cores fed.
 //
 // How an operand tile is fetched depends on its layout (the point of the
 // paper: the loop nest follows the layout):
@@ -45,6 +48,10 @@ struct IgemmParams {
     int32_t uniform_rs;       // C % BK == 0: one (r, s) per K step
     int32_t spatial_split;    // H or W of x is blocked (only with R = S = 1, no padding)
     int64_t x_bstride, w_bstride, y_bstride;
+    uint32_t x_bytes, w_bytes;   // size of one batch entry of each operand (vector loaders: < 2 GiB)
+    uint32_t y_bytes;            // size of one batch entry of the output, 0 if it does not fit 31 bits
+    uint32_t pad0_;
+    FastDiv fd_ohow, fd_ow, fd_c, fd_s, fd_nc;   // divisions by OH*OW, OW, C, S, Nc
     Dim2 xn, xc, xh, xw;      // activations (N, C, H, W)
     Dim2 wo, wi, wr, ws;      // weights (O, I, R, S)
     Dim2 yn, yk, yh, yw;      // output (N, K, OH, OW)
@@ -58,11 +65,38 @@ struct KEntry {               // one K step: what is uniform over the tile
 constexpr int kIgemmThreads = 256;
 constexpr int kKTab = 256;    // K steps whose KEntry is kept in LDS at a time
 
+// Offset of index i (0 <= i < extent) of one logical dimension.
 __device__ __forceinline__ int64_t dim2_off(const Dim2 &d, int32_t i)
 {
-    if (i < d.f && i >= 0) return (int64_t)i * d.si;
-    int32_t q = i / d.f;
+    const int32_t q = (int32_t)fast_div((uint32_t)i, d.fd);
     return (int64_t)q * d.so + (int64_t)(i - q * d.f) * d.si;
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also
+// carries a workgroup-scope release fence, which drains every outstanding
+// global load (s_waitcnt vmcnt(0)) and so would cancel the register prefetch;
+// here only this wave's LDS operations are waited for before the barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// 16-byte load through a buffer descriptor: an offset at or beyond the
+// descriptor's size returns zeros, which is how padding taps and rows outside
+// the tile are filled without a branch or a select on the loaded data.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOutOfRange = 0x80000000u;
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off)
+{
+    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Same in 32 bits, for tensors known to be smaller than 2^31 elements.
+__device__ __forceinline__ int32_t dim2_off32(const Dim2 &d, int32_t i)
+{
+    const int32_t q = (int32_t)fast_div((uint32_t)i, d.fd);
+    return q * (int32_t)d.so + (i - q * d.f) * (int32_t)d.si;
 }
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -97,12 +131,13 @@ __device__ __forceinline__ void mma_tile(floatx16_t &acc, const uint4 &a, const 
     for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], acc, 0, 0, 0);
 }
 
+// fp32 -> bf16, round to nearest even, NaN kept quiet; selects instead of a branch.
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
-    uint32_t w = __builtin_bit_cast(uint32_t, f);
-    if ((w & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((w >> 16) | 0x40u);
-    w += 0x7fffu + ((w >> 16) & 1u);
-    return (uint16_t)(w >> 16);
+    const uint32_t w = __builtin_bit_cast(uint32_t, f);
+    const uint32_t rounded = (w + 0x7fffu + ((w >> 16) & 1u)) >> 16;
+    const uint32_t quiet = (w >> 16) | 0x40u;
+    return (uint16_t)(((w & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);
 }
 
 // 8x8 transpose of 16-bit elements held as 8 uint4 rows (in place).
@@ -132,7 +167,144 @@ __device__ __forceinline__ void transpose4x4_b32(uint4 *r)
     for (int i = 0; i < 4; ++i) r[i] = make_uint4(in[0][i], in[1][i], in[2][i], in[3][i]);
 }
 
-template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE>
+// Writes one workgroup's accumulators: to y under its layout with bias, ReLU
+// and the output conversion fused (the consumer's layout is written directly),
+// or to the split-K partial-sum buffer.  Row offsets of the tile go through
+// LDS (`scratch`, BM entries of 8 bytes; the operand stages are free by now);
+// the column offset is per lane.  All waves must have passed their last LDS
+// read.  When the destination spans less than 2 GiB the stores go through a
+// buffer descriptor with 32-bit offsets and rows/columns outside the problem
+// get an out-of-range offset, which the hardware drops: no branch per element.
+template <int BM, int TM, int TN, int WTM, int WTN>
+__device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t (&acc)[TM][TN], void *scratch,
+                                               int m0, int n0, int wm, int wn, int split, int bz)
+{
+    const int t = threadIdx.x, lane = t & 63;
+    const int ohow = p.OH * p.OW;
+    const bool to_partial = p.splitk > 1;
+    const bool narrow = to_partial || p.y_bytes != 0;
+    if (narrow) {
+        int32_t *rowoff = (int32_t *)scratch;
+        for (int r = t; r < BM; r += kIgemmThreads) {
+            const int m = m0 + r;
+            int32_t off = -1;                              // row outside M
+            if (m < p.M) {
+                if (to_partial) {
+                    off = m * p.Nc;
+                } else {
+                    const int img = (int)fast_div(m, p.fd_ohow), rem = m - img * ohow;
+                    const int oh = (int)fast_div(rem, p.fd_ow), ow = rem - oh * p.OW;
+                    off = dim2_off32(p.yn, img) + dim2_off32(p.yh, oh) + dim2_off32(p.yw, ow);
+                }
+            }
+            rowoff[r] = off;
+        }
+        lds_barrier();
+        const int esz = to_partial ? 4 : (p.out_bf16 ? 2 : 4);
+        const char *dst = to_partial
+            ? (const char *)(p.partial + ((int64_t)split * p.batch + bz) * (int64_t)p.M * p.Nc)
+            : (const char *)p.y + (int64_t)bz * p.y_bstride * esz;
+        const uint32_t dst_bytes = to_partial ? (uint32_t)p.M * p.Nc * 4u : p.y_bytes;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)dst, 0, (int)dst_bytes, 0x00020000);
+        // the 16 rows of a 32x32 accumulator tile a lane holds: 4 groups of 4 consecutive rows
+        int32_t ro[TM][16];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int4 v = *(const int4 *)(rowoff + wm * WTM + i * 32 + 8 * g + 4 * (lane >> 5));
+                ro[i][4 * g + 0] = v.x; ro[i][4 * g + 1] = v.y; ro[i][4 * g + 2] = v.z; ro[i][4 * g + 3] = v.w;
+            }
+        // straight-line store loops (no branch per element, so the compiler's
+        // wait-count bookkeeping never makes a store wait for the one before it)
+        const float relu_floor = (p.epilogue & ALT_EPI_RELU) ? 0.f : -INFINITY;
+        const int mode = to_partial ? 0 : (p.out_bf16 ? 2 : 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+            const bool n_ok = n < p.Nc;
+            const int32_t coff = n_ok ? (to_partial ? n : dim2_off32(p.yk, n)) : 0;
+            const float bv = (n_ok && !to_partial && (p.epilogue & ALT_EPI_BIAS)) ? p.bias[n] : 0.f;
+            uint32_t voff[TM][16];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    voff[i][e] = (n_ok && ro[i][e] >= 0) ? (uint32_t)(ro[i][e] + coff) * (uint32_t)esz : kOutOfRange;
+            if (mode == 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float v = acc[i][j][e];      // (a vector element is not a bit_cast operand)
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, (int)voff[i][e], 0, 0);
+                    }
+            } else if (mode == 1) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float v = fmaxf(acc[i][j][e] + bv, relu_floor);
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, (int)voff[i][e], 0, 0);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float v = fmaxf(acc[i][j][e] + bv, relu_floor);
+                        __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(v), rsrc, (int)voff[i][e], 0, 0);
+                    }
+            }
+        }
+        return;
+    }
+    // outputs of 2 GiB and more: 64-bit addresses, one guarded store per element
+    int64_t *rowoff = (int64_t *)scratch;
+    for (int r = t; r < BM; r += kIgemmThreads) {
+        const int m = m0 + r;
+        int64_t off = -1;
+        if (m < p.M) {
+            const int img = (int)fast_div(m, p.fd_ohow), rem = m - img * ohow;
+            const int oh = (int)fast_div(rem, p.fd_ow), ow = rem - oh * p.OW;
+            off = dim2_off(p.yn, img) + dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
+        }
+        rowoff[r] = off;
+    }
+    lds_barrier();
+    char *yb = (char *)p.y + (int64_t)bz * p.y_bstride * (p.out_bf16 ? 2 : 4);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+        if (n >= p.Nc) continue;
+        const int64_t coff = dim2_off(p.yk, n);
+        const float bv = (p.epilogue & ALT_EPI_BIAS) ? p.bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int r = wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int64_t ro = rowoff[r];
+                if (ro < 0) continue;
+                float v = acc[i][j][e] + bv;
+                if (p.epilogue & ALT_EPI_RELU) v = fmaxf(v, 0.f);
+                if (p.out_bf16) ((uint16_t *)yb)[ro + coff] = f32_to_bf16_rne(v);
+                else ((float *)yb)[ro + coff] = v;
+            }
+    }
+}
+
+// Consecutive logical tiles stay on one XCD (workgroup ids are dealt round-robin
+// to the 8 XCDs), n-tiles of one m-tile adjacent, so the activation rows they
+// share are served by the same L2.
+__device__ __forceinline__ int igemm_logical_tile(int ntiles)
+{
+    const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const int q = ntiles >> 3, rem = ntiles & 7;
+    return xcd * q + min(xcd, rem) + slot;
+}
+
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE, int PF>
 __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams p)
 {
     using TR = ElemTraits<T>;
@@ -167,16 +339,8 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- which tile: consecutive logical tiles stay on one XCD (ids are dealt
-    // round-robin to the 8 XCDs), n-tiles of one m-tile adjacent, so the
-    // activation rows they share are served by the same L2
     const int ntiles = p.tiles_m * p.tiles_n;
-    int logical;
-    {
-        const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
-        const int q = ntiles >> 3, rem = ntiles & 7;
-        logical = xcd * q + min(xcd, rem) + slot;
-    }
+    const int logical = igemm_logical_tile(ntiles);
     const int nt = logical % p.tiles_n, mt = logical / p.tiles_n;
     const int m0 = mt * BM, n0 = nt * BN;
     const int split = blockIdx.y % p.splitk, bz = blockIdx.y / p.splitk;
@@ -185,6 +349,9 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
 
     const char *xb = (const char *)p.x + (int64_t)bz * p.x_bstride * ES;
     const char *wb = (const char *)p.w + (int64_t)bz * p.w_bstride * ES;
+    // raw buffer descriptors (stride 0, 32-bit data format) over one batch entry of each operand
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)xb, 0, (int)p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)wb, 0, (int)p.w_bytes, 0x00020000);
 
     // ---- per-thread row bases --------------------------------------------------
     constexpr int NRA = AMODE == LOAD_VEC ? NVA : 1;
@@ -198,8 +365,8 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     auto decode_a_row = [&](int row, int64_t &base, int32_t &ih0, int32_t &iw0) {
         const int m = m0 + row;
         if (m < p.M) {
-            const int img = m / ohow, rem = m - img * ohow;
-            const int oh = rem / p.OW, ow = rem - oh * p.OW;
+            const int img = (int)fast_div(m, p.fd_ohow), rem = m - img * ohow;
+            const int oh = (int)fast_div(rem, p.fd_ow), ow = rem - oh * p.OW;
             ih0 = oh * p.stride_h - p.pad_h;
             iw0 = ow * p.stride_w - p.pad_w;
             base = dim2_off(p.xn, img);
@@ -248,8 +415,8 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     auto fill_ktab = [&](int first) {
         for (int j = t; j < kKTab && first + j < nk; j += kIgemmThreads) {
             const int k0 = (kbeg + first + j) * BK;
-            const int rs = k0 / p.C, c0 = k0 - rs * p.C;
-            const int r = rs / p.S, s = rs - r * p.S;
+            const int rs = (int)fast_div(k0, p.fd_c), c0 = k0 - rs * p.C;
+            const int r = (int)fast_div(rs, p.fd_s), s = rs - r * p.S;
             KEntry e;
             e.dh = r * p.dil_h;
             e.dw = s * p.dil_w;
@@ -262,7 +429,7 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     // ---- operand fetch: global -> registers ------------------------------------
     constexpr int NA_REG = AMODE == LOAD_VEC ? NVA : AMODE == LOAD_GATHER ? (NGA * ES + 15) / 16 : NQA * EPV;
     constexpr int NB_REG = BMODE == LOAD_VEC ? NVB : BMODE == LOAD_GATHER ? (NGB * ES + 15) / 16 : NQB * EPV;
-    uint4 a_reg[NA_REG], b_reg[NB_REG];
+    uint4 a_regs[PF][NA_REG], b_regs[PF][NB_REG];     // PF K steps of operand data in flight
 
     auto gather_one = [&](const char *basep, int64_t rowbase, int32_t ih0, int32_t iw0, bool rowok,
                           int kk, int kstep, const KEntry &e, bool is_a) -> E {
@@ -278,8 +445,8 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
         } else {
             const int k = (kbeg + kstep) * BK + kk;
             if (k < p.Kg) {
-                const int rs = k / p.C, c = k - rs * p.C;
-                const int r = rs / p.S, s = rs - r * p.S;
+                const int rs = (int)fast_div(k, p.fd_c), c = k - rs * p.C;
+                const int r = (int)fast_div(rs, p.fd_s), s = rs - r * p.S;
                 if (is_a) {
                     const int ih = ih0 + r * p.dil_h, iw = iw0 + s * p.dil_w;
                     if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W) {
@@ -296,14 +463,14 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
         return v;
     };
 
-    auto fetch = [&](int kstep) {
+    auto fetch = [&](int kstep, uint4 *a_reg, uint4 *b_reg) {
         const KEntry e = ktab[kstep % kKTab];
         if constexpr (AMODE == LOAD_VEC) {
 #pragma unroll
             for (int i = 0; i < NVA; ++i) {
                 const bool ok = (unsigned)(a_ih0[i] + e.dh) < (unsigned)p.H &&
                                 (unsigned)(a_iw0[i] + e.dw) < (unsigned)p.W;
-                a_reg[i] = ok ? *(const uint4 *)(xb + (a_base[i] + e.a_off) * ES) : make_uint4(0, 0, 0, 0);
+                a_reg[i] = buffer_load16(x_rsrc, ok ? (uint32_t)((a_base[i] + e.a_off) * ES) : kOutOfRange);
             }
         } else if constexpr (AMODE == LOAD_GATHER) {
             E *dst = (E *)a_reg;
@@ -330,7 +497,7 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
         if constexpr (BMODE == LOAD_VEC) {
 #pragma unroll
             for (int i = 0; i < NVB; ++i)
-                b_reg[i] = b_ok[i] ? *(const uint4 *)(wb + (b_base[i] + e.b_off) * ES) : make_uint4(0, 0, 0, 0);
+                b_reg[i] = buffer_load16(w_rsrc, b_ok[i] ? (uint32_t)((b_base[i] + e.b_off) * ES) : kOutOfRange);
         } else if constexpr (BMODE == LOAD_GATHER) {
             E *dst = (E *)b_reg;
             constexpr int KSTR = kIgemmThreads / BN;
@@ -355,7 +522,7 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     };
 
     // ---- registers -> LDS stage --------------------------------------------------
-    auto stash = [&](int stage) {
+    auto stash = [&](int stage, const uint4 *a_reg, const uint4 *b_reg) {
         E *as = As + stage * BM * LDA;
         E *bs = Bs + stage * BN * LDB;
         if constexpr (AMODE == LOAD_VEC) {
@@ -421,101 +588,65 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
 
     if (nk > 0) {
         fill_ktab(0);
-        __syncthreads();
-        fetch(0);
-        stash(0);
-        __syncthreads();
-        for (int ks = 0; ks < nk; ++ks) {
-            const bool more = ks + 1 < nk;
-            if (more) {
-                if ((ks + 1) % kKTab == 0) {       // next window of the K-step table
-                    __syncthreads();
-                    fill_ktab(ks + 1);
-                    __syncthreads();
+        lds_barrier();
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (j < nk) fetch(j, a_regs[j], b_regs[j]);
+        stash(0, a_regs[0], b_regs[0]);
+        lds_barrier();
+        for (int ks0 = 0; ks0 < nk; ks0 += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                const int ks = ks0 + j;
+                if (ks >= nk) break;
+                const int nf = ks + PF;            // its data goes into the register slot step ks just left
+                if (nf < nk) {
+                    if (nf % kKTab == 0) {         // next window of the K-step table
+                        lds_barrier();
+                        fill_ktab(nf);
+                        lds_barrier();
+                    }
+                    fetch(nf, a_regs[j], b_regs[j]);
                 }
-                fetch(ks + 1);
+                const E *as = As + (ks & 1) * BM * LDA + (wm * WTM + (lane & 31)) * LDA + (lane >> 5) * EPV;
+                const E *bs = Bs + (ks & 1) * BN * LDB + (wn * WTN + (lane & 31)) * LDB + (lane >> 5) * EPV;
+#pragma unroll
+                for (int kc = 0; kc < BK / KC; ++kc) {
+                    uint4 af[TM], bf[TN];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) af[i] = *(const uint4 *)(as + i * 32 * LDA + kc * KC);
+#pragma unroll
+                    for (int jn = 0; jn < TN; ++jn) bf[jn] = *(const uint4 *)(bs + jn * 32 * LDB + kc * KC);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int jn = 0; jn < TN; ++jn) mma_tile(acc[i][jn], af[i], bf[jn], T{});
+                }
+                if (ks + 1 < nk) stash((ks + 1) & 1, a_regs[(j + 1) % PF], b_regs[(j + 1) % PF]);
+                lds_barrier();
             }
-            const E *as = As + (ks & 1) * BM * LDA + (wm * WTM + (lane & 31)) * LDA + (lane >> 5) * EPV;
-            const E *bs = Bs + (ks & 1) * BN * LDB + (wn * WTN + (lane & 31)) * LDB + (lane >> 5) * EPV;
-#pragma unroll
-            for (int kc = 0; kc < BK / KC; ++kc) {
-                uint4 af[TM], bf[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) af[i] = *(const uint4 *)(as + i * 32 * LDA + kc * KC);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) bf[j] = *(const uint4 *)(bs + j * 32 * LDB + kc * KC);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) mma_tile(acc[i][j], af[i], bf[j], T{});
-            }
-            if (more) stash((ks + 1) & 1);
-            __syncthreads();
         }
     }
 
-    // ---- epilogue ---------------------------------------------------------------------
-    // Row offsets of this tile under the output layout go through LDS (the
-    // stages are free now); the column offset is per lane.
-    int64_t *rowoff = (int64_t *)smem_u4;          // [BM], -1 = row outside M
-    const bool to_partial = p.splitk > 1;
-    for (int r = t; r < BM; r += kIgemmThreads) {
-        const int m = m0 + r;
-        int64_t off = -1;
-        if (m < p.M) {
-            if (to_partial) {
-                off = (int64_t)m * p.Nc;
-            } else {
-                const int img = m / ohow, rem = m - img * ohow;
-                const int oh = rem / p.OW, ow = rem - oh * p.OW;
-                off = dim2_off(p.yn, img) + dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
-            }
-        }
-        rowoff[r] = off;
-    }
-    __syncthreads();
-    float *part = p.partial + ((int64_t)split * p.batch + bz) * (int64_t)p.M * p.Nc;
-    char *yb = (char *)p.y + (int64_t)bz * p.y_bstride * (p.out_bf16 ? 2 : 4);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-        if (n >= p.Nc) continue;
-        const int64_t coff = to_partial ? n : dim2_off(p.yk, n);
-        const float bv = (!to_partial && (p.epilogue & ALT_EPI_BIAS)) ? p.bias[n] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int r = wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                const int64_t ro = rowoff[r];
-                if (ro < 0) continue;
-                float v = acc[i][j][e];
-                if (to_partial) {
-                    part[ro + coff] = v;
-                } else {
-                    v += bv;
-                    if (p.epilogue & ALT_EPI_RELU) v = fmaxf(v, 0.f);
-                    if (p.out_bf16) ((uint16_t *)yb)[ro + coff] = f32_to_bf16_rne(v);
-                    else ((float *)yb)[ro + coff] = v;
-                }
-            }
-    }
+    igemm_epilogue<BM, TM, TN, WTM, WTN>(p, acc, (void *)smem_u4, m0, n0, wm, wn, split, bz);
 }
 
 // Launch of one instantiation; defined in the igemm_*.hip files.
 struct IgemmLaunch {
     const char *name;
     int dtype, BM, BN, BK, amode, bmode;
+    int prefetch;             // register pipeline: K steps of loads in flight; DMA pipeline: LDS stages - 1
+    int dma;                  // 1 = operands go global -> LDS directly (igemm_dma.h)
     size_t lds_bytes;
     hipError_t (*launch)(const IgemmParams &p, dim3 grid, hipStream_t st);
 };
 
-template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE>
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE, int PF>
 hipError_t igemm_launch(const IgemmParams &p, dim3 grid, hipStream_t st)
 {
     using TR = ElemTraits<T>;
     constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + TR::EPV) * TR::SIZE + kKTab * sizeof(KEntry);
-    auto kern = igemm_kernel<T, BM, BN, BK, WGM, WGN, AMODE, BMODE>;
+    auto kern = igemm_kernel<T, BM, BN, BK, WGM, WGN, AMODE, BMODE, PF>;
     static bool attr_set = false;
     if (!attr_set && lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

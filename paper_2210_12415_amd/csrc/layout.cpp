@@ -137,13 +137,15 @@ bool layout_to_dim2(const BoundLayout &b, Dim2 *out)
             if (a.div == 1) inner = &a; else outer = &a;
         }
         if (n > 2) return false;
-        if (n == 0) { out[d].f = 1; out[d].so = 0; out[d].si = 0; continue; }
+        out[d].pad_ = 0;
+        if (n == 0) { out[d].f = 1; out[d].so = 0; out[d].si = 0; out[d].fd = make_fastdiv(1); continue; }
         if (n == 1) {
             // the chain of divisors starts at 1, so a lone non-unit piece is the whole dimension
             const Atom *a = inner ? inner : outer;
             out[d].f = (int32_t)b.shape[d];
             out[d].so = 0;
             out[d].si = a->stride;
+            out[d].fd = make_fastdiv((uint32_t)out[d].f);
             continue;
         }
         if (!inner || !outer || outer->div != inner->ext) return false;
@@ -151,6 +153,7 @@ bool layout_to_dim2(const BoundLayout &b, Dim2 *out)
         out[d].f = (int32_t)inner->ext;
         out[d].si = inner->stride;
         out[d].so = outer->stride;
+        out[d].fd = make_fastdiv((uint32_t)out[d].f);
     }
     return true;
 }

@@ -11,6 +11,7 @@ struct Problem {
     int dtype;
     bool a_vec, a_trans, b_vec, b_trans;   // loaders the operand layouts admit (gather always works)
     bool spatial_split, spatial_ok;
+    int64_t x_elems, w_elems;              // elements of one batch entry of each operand
 };
 
 extern const int kSplitFactors[];

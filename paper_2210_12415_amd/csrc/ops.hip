@@ -46,15 +46,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
     const int64_t total = per_batch * p.batch;
     const int ohow = p.OH * p.OW;
     for (int64_t e = blockIdx.x * (int64_t)256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int bz = (int)(e / per_batch);
+        const int bz = p.batch == 1 ? 0 : (int)(e / per_batch);
         const int64_t r = e - bz * per_batch;
-        const int m = (int)(r / p.Nc), n = (int)(r - (int64_t)m * p.Nc);
+        const int m = (int)fast_div((uint32_t)r, p.fd_nc), n = (int)(r - (int64_t)m * p.Nc);
         float v = 0.f;
         for (int s = 0; s < p.splitk; ++s) v += p.partial[(int64_t)s * total + e];
         if (p.epilogue & ALT_EPI_BIAS) v += p.bias[n];
         if (p.epilogue & ALT_EPI_RELU) v = fmaxf(v, 0.f);
-        const int img = m / ohow, rem = m - img * ohow;
-        const int oh = rem / p.OW, ow = rem - oh * p.OW;
+        const int img = (int)fast_div(m, p.fd_ohow), rem = m - img * ohow;
+        const int oh = (int)fast_div(rem, p.fd_ow), ow = rem - oh * p.OW;
         const int64_t off = (int64_t)bz * p.y_bstride + dim2_off(p.yn, img) + dim2_off(p.yk, n) +
                             dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
         if (p.out_bf16) ((uint16_t *)p.y)[off] = f32_to_bf16_rne(v);
@@ -78,8 +78,7 @@ void igemm_analyse(Problem *pb)
     pb->a_vec = p.xc.si == 1 && mult(p.xc.f, epv) && (p.xc.f >= p.C || mult(p.xc.so, epv)) &&
                 mult(p.xn.si, epv) && mult(p.xn.so, epv) && mult(p.xh.si, epv) && mult(p.xh.so, epv) &&
                 mult(p.xw.si, epv) && mult(p.xw.so, epv) && mult(p.x_bstride, epv) &&
-                ((uintptr_t)p.x % 16 == 0) && pb->spatial_ok;
-    (void)es;
+                ((uintptr_t)p.x % 16 == 0) && pb->spatial_ok && pb->x_elems * es < 0x7fffffff;
     // A: rows (GMM m) contiguous, no spatial structure
     pb->a_trans = p.H == 1 && p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0 && p.stride_w == 1 &&
                   p.xw.si == 1 && p.xw.f >= p.W && mult(p.M, epv) && p.xc.f >= p.C && mult(p.xc.si, epv) &&
@@ -87,7 +86,7 @@ void igemm_analyse(Problem *pb)
     pb->b_vec = p.wi.si == 1 && mult(p.wi.f, epv) && (p.wi.f >= p.C || mult(p.wi.so, epv)) &&
                 mult(p.wo.si, epv) && mult(p.wo.so, epv) && mult(p.wr.si, epv) && mult(p.wr.so, epv) &&
                 mult(p.ws.si, epv) && mult(p.ws.so, epv) && mult(p.w_bstride, epv) &&
-                ((uintptr_t)p.w % 16 == 0);
+                ((uintptr_t)p.w % 16 == 0) && pb->w_elems * es < 0x7fffffff;
     pb->b_trans = p.R == 1 && p.S == 1 && p.wo.si == 1 && mult(p.wo.f, epv) &&
                   (p.wo.f >= p.Nc || mult(p.wo.so, epv)) && mult(p.Nc, epv) && mult(p.wi.si, epv) &&
                   mult(p.wi.so, epv) && mult(p.w_bstride, epv) && ((uintptr_t)p.w % 16 == 0);
@@ -111,10 +110,16 @@ bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, Igemm
     if (pb.spatial_split && k.amode == LOAD_GATHER && !(p0.R == 1 && p0.S == 1 && p0.pad_h == 0 && p0.pad_w == 0))
         return no("blocked H/W with a sliding window");
     IgemmParams p = p0;
+    p.fd_ohow = make_fastdiv((uint32_t)(p.OH * p.OW));
+    p.fd_ow = make_fastdiv((uint32_t)p.OW);
+    p.fd_c = make_fastdiv((uint32_t)p.C);
+    p.fd_s = make_fastdiv((uint32_t)p.S);
+    p.fd_nc = make_fastdiv((uint32_t)p.Nc);
     p.uniform_rs = uniform ? 1 : 0;
     p.spatial_split = pb.spatial_split ? 1 : 0;
     p.ksteps_total = (p.Kg + k.BK - 1) / k.BK;
     if (splitk < 1 || splitk > p.ksteps_total) return no("split-K factor exceeds the K steps");
+    if (splitk > 1 && (int64_t)p.M * p.Nc * 4 >= 0x7fffffff) return no("output too large for the split-K reduction");
     p.splitk = splitk;
     p.ksteps_per_split = (p.ksteps_total + splitk - 1) / splitk;
     if ((int64_t)(splitk - 1) * p.ksteps_per_split >= p.ksteps_total) return no("split-K factor leaves an empty slice");
@@ -142,6 +147,7 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
     if (k.bmode == LOAD_GATHER) mode_cost *= 3.0;
     if (k.amode == LOAD_TRANS) mode_cost *= 1.5;
     if (k.bmode == LOAD_TRANS) mode_cost *= 1.5;
+    if (k.prefetch > 1) mode_cost *= 0.8;
     const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
     const double rounds = std::ceil(blocks / 512.0);
     const double step = (double)k.BM * k.BN * k.BK / 16384.0 + 3.0 * (k.BM + k.BN) * k.BK / 8192.0 + 2.0;
@@ -180,6 +186,9 @@ alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *wor
     if (!igemm_applicable(pb, k, splitk, &p, &why))
         return fail(h, ALT_UNSUPPORTED, "variant %s/splitk%d not applicable: %s", k.name, splitk, why.c_str());
     const size_t need = igemm_workspace(pb, splitk);
+#ifdef ALT_PHASE_TIMING
+    if (need == 0 && workspace) p.partial = (float *)workspace;
+#endif
     if (need > 0) {
         if (!workspace || ws_bytes < need)
             return fail(h, ALT_WORKSPACE_TOO_SMALL, "split-K needs %zu workspace bytes, got %zu", need, ws_bytes);
@@ -251,6 +260,14 @@ alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *
     p.xn = dx[0]; p.xc = dx[1]; p.xh = dx[2]; p.xw = dx[3];
     p.wo = dw[0]; p.wi = dw[1]; p.wr = dw[2]; p.ws = dw[3];
     p.yn = dy[0]; p.yk = dy[1]; p.yh = dy[2]; p.yw = dy[3];
+    pb->x_elems = bx.numel;
+    pb->w_elems = bw.numel;
+    {
+        const int64_t yb = by.numel * (int64_t)dtype_size(d->out_dtype);
+        p.y_bytes = yb < 0x7fffffff ? (uint32_t)yb : 0;
+    }
+    p.x_bytes = (uint32_t)std::min<int64_t>(bx.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
+    p.w_bytes = (uint32_t)std::min<int64_t>(bw.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
     igemm_analyse(pb);
     return ALT_OK;
 }
@@ -277,7 +294,7 @@ alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *
     std::memset(pb, 0, sizeof(*pb));
     pb->dtype = d->in_dtype;
     IgemmParams &p = pb->p;
-    const Dim2 one = {1, 0, 0, 0};
+    const Dim2 one = {1, 0, 0, 0, make_fastdiv(1)};
     p.x = A; p.w = B; p.y = C; p.bias = nullptr;
     p.M = (int32_t)d->M; p.Nc = (int32_t)d->N; p.Kg = (int32_t)d->K;
     p.C = (int32_t)d->K; p.H = 1; p.W = (int32_t)d->M; p.R = 1; p.S = 1; p.OH = 1; p.OW = (int32_t)d->M;
@@ -288,6 +305,14 @@ alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *
     p.xn = one; p.xc = da[1]; p.xh = one; p.xw = da[0];
     p.wo = db[1]; p.wi = db[0]; p.wr = one; p.ws = one;
     p.yn = one; p.yk = dc[1]; p.yh = one; p.yw = dc[0];
+    pb->x_elems = ba.numel;
+    pb->w_elems = bb.numel;
+    {
+        const int64_t yb = bc.numel * (int64_t)dtype_size(d->out_dtype);
+        p.y_bytes = yb < 0x7fffffff ? (uint32_t)yb : 0;
+    }
+    p.x_bytes = (uint32_t)std::min<int64_t>(ba.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
+    p.w_bytes = (uint32_t)std::min<int64_t>(bb.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
     igemm_analyse(pb);
     return ALT_OK;
 }

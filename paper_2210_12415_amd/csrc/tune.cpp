@@ -106,6 +106,13 @@ alt_status_t measure(alt_handle_t h, Timer &tm, hipStream_t st, int warmup, int 
     return ALT_OK;
 }
 
+// ALT_VERBOSE=1 in the environment prints every trial to stderr.
+bool verbose()
+{
+    static const bool v = std::getenv("ALT_VERBOSE") != nullptr;
+    return v;
+}
+
 struct Trial {
     int variant;
     double est;
@@ -201,6 +208,7 @@ alt_status_t tune_variants_conv(alt_handle_t h, const alt_conv_desc_t *d, const 
         s = measure(h, tm, st, warmup, reps, [&] { return igemm_run(h, pb, t.variant, ws, ws_bytes, st); }, &us);
         if (s != ALT_OK) return s;
         ++done;
+        if (verbose()) std::fprintf(stderr, "[alt tune] %-28s %9.2f us\n", igemm_variant_name(t.variant).c_str(), us);
         if (us < *best_us) { *best_us = us; *best_variant = t.variant; }
     }
     *trials += done;
@@ -331,6 +339,7 @@ alt_status_t alt_tune_conv2d(alt_handle_t h, const alt_conv_desc_t *shape, const
         if ((s = alt_pack_weights(h, &d, w0, w1, st)) != ALT_OK) return s;
         float us = INFINITY;
         int v = -1;
+        if (verbose()) std::fprintf(stderr, "[alt tune] layout %s\n", cc.name);
         s = tune_variants_conv(h, &d, x1, w1, bias, y, ws, ws_bytes, st, tm, opt_warmup(opts), opt_reps(opts),
                                per_layout, &rep.trials, &us, &v);
         if (s != ALT_OK) return s;
