@@ -175,7 +175,7 @@ __device__ __forceinline__ void transpose4x4_b32(uint4 *r)
 // read.  When the destination spans less than 2 GiB the stores go through a
 // buffer descriptor with 32-bit offsets and rows/columns outside the problem
 // get an out-of-range offset, which the hardware drops: no branch per element.
-template <int BM, int TM, int TN, int WTM, int WTN>
+template <int BM, int TM, int TN, int WTM, int WTN, int NT = kIgemmThreads>
 __device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t (&acc)[TM][TN], void *scratch,
                                                int m0, int n0, int wm, int wn, int split, int bz)
 {
@@ -185,7 +185,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t 
     const bool narrow = to_partial || p.y_bytes != 0;
     if (narrow) {
         int32_t *rowoff = (int32_t *)scratch;
-        for (int r = t; r < BM; r += kIgemmThreads) {
+        for (int r = t; r < BM; r += NT) {
             const int m = m0 + r;
             int32_t off = -1;                              // row outside M
             if (m < p.M) {
@@ -261,7 +261,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t 
     }
     // outputs of 2 GiB and more: 64-bit addresses, one guarded store per element
     int64_t *rowoff = (int64_t *)scratch;
-    for (int r = t; r < BM; r += kIgemmThreads) {
+    for (int r = t; r < BM; r += NT) {
         const int m = m0 + r;
         int64_t off = -1;
         if (m < p.M) {

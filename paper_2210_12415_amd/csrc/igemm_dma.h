@@ -32,15 +32,17 @@ struct KEntry32 {             // per K step, byte-offset arithmetic in 32 bits (
 
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
-// One wave-wide 16-byte-per-lane load into LDS at byte address `lds` (+ 16 * lane).
+// One wave-wide 16-byte-per-lane load into LDS at byte address `lds` (+ 16 * lane);
+// `lds` must be wave-uniform (it is moved to M0).
 __device__ __forceinline__ void dma_load16(i32x4_t rsrc, uint32_t voff, uint32_t lds)
 {
-    const uint32_t lds_uniform = __builtin_amdgcn_readfirstlane(lds);
+    // (the compiler drops the readfirstlane where it already knows the value to be scalar)
+    const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds);
     asm volatile("s_mov_b32 m0, %0\n\t"
                  "s_nop 0\n\t"
                  "buffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
-                 : "s"(lds_uniform), "v"(voff), "s"(rsrc)
+                 : "s"(lds_s), "v"(voff), "s"(rsrc)
                  : "memory");
 }
 
@@ -72,7 +74,7 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void *base, uint32_t bytes)
 #endif
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int NS>
-__global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmParams p)
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmParams p)
 {
 #ifdef ALT_PHASE_TIMING
     uint64_t stamps[5] = {0, 0, 0, 0, 0};
@@ -81,26 +83,30 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
     using TR = ElemTraits<T>;
     constexpr int EPV = TR::EPV;
     constexpr int ES = TR::SIZE;
+    constexpr int NW = WGM * WGN;                          // wavefronts per workgroup (4 or 8)
+    constexpr int NT = 64 * NW;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int KC = 2 * EPV;
+    constexpr int NKC = BK / KC;                           // MFMA k-chunks per step
     constexpr int CPR = BK / EPV;                          // 16-byte chunks per tile row
     constexpr int SWZ_DIV = CPR >= 16 ? 1 : 16 / CPR;      // rows that share one swizzle value
     constexpr int A_STAGE = BM * BK * ES, B_STAGE = BN * BK * ES;      // bytes
-    constexpr int NLA = A_STAGE / 1024 / 4, NLB = B_STAGE / 1024 / 4;  // wave-loads per wave per stage
+    constexpr int NLA = A_STAGE / 1024 / NW, NLB = B_STAGE / 1024 / NW;  // wave-loads per wave per stage
     constexpr int LPS = NLA + NLB;
-    static_assert(WGM * WGN == 4 && WTM % 32 == 0 && WTN % 32 == 0 && BK % KC == 0, "tile shape");
-    static_assert(A_STAGE % 4096 == 0 && B_STAGE % 4096 == 0, "a stage is a whole number of wave-loads per wave");
+    constexpr int LPK = (LPS + NKC - 1) / NKC;             // wave-loads issued per k-chunk
+    static_assert((NW == 4 || NW == 8 || NW == 16) && WTM % 32 == 0 && WTN % 32 == 0 && BK % KC == 0, "tile shape");
+    static_assert(A_STAGE % (1024 * NW) == 0 && B_STAGE % (1024 * NW) == 0, "a stage is a whole number of wave-loads per wave");
     static_assert(NS >= 2 && (NS - 2) * LPS < 64, "pipeline depth against the vmcnt range");
     static_assert(CPR >= 2 && (CPR & (CPR - 1)) == 0 && CPR <= 16, "chunks per row");
 
     extern __shared__ uint4 smem_u4[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem_u4;
-    const uint32_t ldsA = lds0, ldsB = lds0 + NS * A_STAGE;
     KEntry32 *ktab = (KEntry32 *)((char *)smem_u4 + NS * (A_STAGE + B_STAGE));
 
     const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);          // scalar: LDS destinations stay in SGPRs
     const int wm = wave / WGN, wn = wave % WGN;
     const int logical = igemm_logical_tile(p.tiles_m * p.tiles_n);
     const int nt = logical % p.tiles_n, mt = logical / p.tiles_n;
@@ -111,15 +117,17 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
 
     const i32x4_t x_rsrc = make_rsrc((const char *)p.x + (int64_t)bz * p.x_bstride * ES, p.x_bytes);
     const i32x4_t w_rsrc = make_rsrc((const char *)p.w + (int64_t)bz * p.w_bstride * ES, p.w_bytes);
+    // LDS byte addresses of this wave's first wave-load of stage 0
+    const uint32_t ldsA = lds0 + wave * 1024, ldsB = lds0 + NS * A_STAGE + wave * 1024;
 
-    // ---- what each lane fetches: LDS slot s = (i*4 + wave)*64 + lane holds chunk
+    // ---- what each lane fetches: LDS slot s = (i*NW + wave)*64 + lane holds chunk
     // (s % CPR) ^ swz(row) of tile row s / CPR
     int32_t a_base[NLA], a_ih0[NLA], a_iw0[NLA];
     int32_t b_base[NLB];
     const int ohow = p.OH * p.OW;
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
-        const int s = (i * 4 + wave) * 64 + lane;
+        const int s = (i * NW + wave) * 64 + lane;
         const int row = s / CPR, c = (s % CPR) ^ ((row / SWZ_DIV) % CPR);
         const int m = m0 + row;
         if (m < p.M) {
@@ -137,14 +145,14 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
-        const int s = (i * 4 + wave) * 64 + lane;
+        const int s = (i * NW + wave) * 64 + lane;
         const int row = s / CPR, c = (s % CPR) ^ ((row / SWZ_DIV) % CPR);
         const int n = n0 + row;
         b_base[i] = n < p.Nc ? dim2_off32(p.wo, n) + dim2_off32(p.wi, c * EPV) : -1;
     }
 
     auto fill_ktab = [&](int first) {
-        for (int j = t; j < kKTab && first + j < nk; j += kIgemmThreads) {
+        for (int j = t; j < kKTab && first + j < nk; j += NT) {
             const int k0 = (kbeg + first + j) * BK;
             const int rs = (int)fast_div(k0, p.fd_c), c0 = k0 - rs * p.C;
             const int r = (int)fast_div(rs, p.fd_s), s = rs - r * p.S;
@@ -157,19 +165,22 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
         }
     };
 
-    // Issues the loads of K step `kstep` into stage `stage`.
-    auto issue = [&](int kstep, int stage) {
-        const KEntry32 e = ktab[kstep % kKTab];
+    // Issues wave-loads [first, last) of the K step described by table entry e into stage
+    // `stage`; loads 0..NLA-1 are the A tile, NLA..LPS-1 the B tile.
+    auto issue = [&](const KEntry32 &e, int stage, int first, int last) {
 #pragma unroll
-        for (int i = 0; i < NLA; ++i) {
-            const bool ok = (unsigned)(a_ih0[i] + e.dh) < (unsigned)p.H && (unsigned)(a_iw0[i] + e.dw) < (unsigned)p.W;
-            const uint32_t voff = ok ? (uint32_t)(a_base[i] + e.a_off) * ES : kOutOfRange;
-            dma_load16(x_rsrc, voff, ldsA + stage * A_STAGE + (i * 4 + wave) * 1024);
-        }
-#pragma unroll
-        for (int i = 0; i < NLB; ++i) {
-            const uint32_t voff = b_base[i] >= 0 ? (uint32_t)(b_base[i] + e.b_off) * ES : kOutOfRange;
-            dma_load16(w_rsrc, voff, ldsB + stage * B_STAGE + (i * 4 + wave) * 1024);
+        for (int l = 0; l < LPS; ++l) {
+            if (l < first || l >= last) continue;
+            if (l < NLA) {
+                const int i = l;
+                const bool ok = (unsigned)(a_ih0[i] + e.dh) < (unsigned)p.H && (unsigned)(a_iw0[i] + e.dw) < (unsigned)p.W;
+                const uint32_t voff = ok ? (uint32_t)(a_base[i] + e.a_off) * ES : kOutOfRange;
+                dma_load16(x_rsrc, voff, ldsA + stage * A_STAGE + i * (NW * 1024));
+            } else {
+                const int i = l - NLA;
+                const uint32_t voff = b_base[i] >= 0 ? (uint32_t)(b_base[i] + e.b_off) * ES : kOutOfRange;
+                dma_load16(w_rsrc, voff, ldsB + stage * B_STAGE + i * (NW * 1024));
+            }
         }
     };
 
@@ -181,22 +192,27 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // operand read addresses: row base and swizzle term per 32-row MFMA tile
-    uint32_t a_row[TM], a_swz[TM], b_row[TN], b_swz[TN];
+    // operand read addresses inside a stage, per 32-row MFMA tile and k-chunk (loop
+    // invariant; the stage offset is a compile-time addend of the unrolled step)
+    const char *a_rd[TM][NKC], *b_rd[TN][NKC];
+    {
+        const uint32_t khalf = (lane >> 5) * 16;
+        const char *lds_base = (const char *)smem_u4;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int r = wm * WTM + i * 32 + (lane & 31);
-        a_row[i] = r * (CPR * 16);
-        a_swz[i] = ((r / SWZ_DIV) % CPR) * 16;
-    }
+        for (int i = 0; i < TM; ++i) {
+            const int r = wm * WTM + i * 32 + (lane & 31);
+            const uint32_t swz = ((r / SWZ_DIV) % CPR) * 16;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int r = wn * WTN + j * 32 + (lane & 31);
-        b_row[j] = r * (CPR * 16);
-        b_swz[j] = ((r / SWZ_DIV) % CPR) * 16;
+            for (int kc = 0; kc < NKC; ++kc) a_rd[i][kc] = lds_base + r * (CPR * 16) + ((kc * 32 + khalf) ^ swz);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int r = wn * WTN + j * 32 + (lane & 31);
+            const uint32_t swz = ((r / SWZ_DIV) % CPR) * 16;
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = lds_base + NS * A_STAGE + r * (CPR * 16) + ((kc * 32 + khalf) ^ swz);
+        }
     }
-    const uint32_t khalf = (lane >> 5) * 16;
-    const char *lds_base = (const char *)smem_u4;
 
     if (nk > 0) {
         fill_ktab(0);
@@ -204,9 +220,9 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
         ALT_STAMP(1);
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
-            if (s < nk) issue(s, s);
-        int stage = 0;                                 // stage of step ks
-        for (int ks = 0; ks < nk; ++ks) {
+            if (s < nk) issue(ktab[s], s, 0, LPS);
+        // One K step; `st`, the stage of step ks, is a compile-time constant at every call site.
+        auto do_step = [&](int ks, int st) {
             // step ks has landed once at most the loads of the later steps in flight remain
             if (ks + NS - 2 < nk) wait_vmcnt<(NS - 2) * LPS>();
             else wait_vmcnt<0>();
@@ -215,34 +231,48 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_dma_kernel(const IgemmPar
             if (ks == 0) ALT_STAMP(2);
 #endif
             const int nf = ks + NS - 1;
-            if (nf < nk) {
-                if (nf % kKTab == 0) {                 // next window of the K-step table
-                    fill_ktab(nf);
-                    lds_barrier();
-                }
-                issue(nf, stage == 0 ? NS - 1 : stage - 1);
+            const bool more = nf < nk;
+            if (more && nf % kKTab == 0) {             // next window of the K-step table
+                fill_ktab(nf);
+                lds_barrier();
             }
-            const char *as = lds_base + stage * A_STAGE;
-            const char *bs = lds_base + NS * A_STAGE + stage * B_STAGE;
+            const KEntry32 e = ktab[(more ? nf : ks) % kKTab];
+            const int fstage = (st + NS - 1) % NS;
+            // operand fragments one k-chunk ahead of the MFMAs that use them, and the
+            // next stage's loads spread between the MFMA groups, so that a wavefront
+            // alone on its SIMD still overlaps LDS reads, load issue and matrix math
+            uint4 af[2][TM], bf[2][TN];
 #pragma unroll
-            for (int kc = 0; kc < BK / KC; ++kc) {
-                uint4 af[TM], bf[TN];
-                const uint32_t kpos = kc * 32 + khalf;         // byte position of the logical chunk in its row
+            for (int i = 0; i < TM; ++i) af[0][i] = *(const uint4 *)(a_rd[i][0] + st * A_STAGE);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) af[i] = *(const uint4 *)(as + a_row[i] + (kpos ^ a_swz[i]));
+            for (int j = 0; j < TN; ++j) bf[0][j] = *(const uint4 *)(b_rd[j][0] + st * B_STAGE);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bf[j] = *(const uint4 *)(bs + b_row[j] + (kpos ^ b_swz[j]));
+            for (int kc = 0; kc < NKC; ++kc) {
+                if (kc + 1 < NKC) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) af[(kc + 1) & 1][i] = *(const uint4 *)(a_rd[i][kc + 1 < NKC ? kc + 1 : 0] + st * A_STAGE);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) bf[(kc + 1) & 1][j] = *(const uint4 *)(b_rd[j][kc + 1 < NKC ? kc + 1 : 0] + st * B_STAGE);
+                }
+                if (more) issue(e, fstage, kc * LPK, (kc + 1) * LPK);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) mma_tile(acc[i][j], af[i], bf[j], T{});
+                    for (int j = 0; j < TN; ++j) mma_tile(acc[i][j], af[kc & 1][i], bf[kc & 1][j], T{});
             }
-            stage = stage + 1 == NS ? 0 : stage + 1;
+        };
+        int ks0 = 0;
+        for (; ks0 + NS <= nk; ks0 += NS) {            // whole rounds over the stages, no exit inside
+#pragma unroll
+            for (int st = 0; st < NS; ++st) do_step(ks0 + st, st);
         }
+#pragma unroll
+        for (int st = 0; st < NS - 1; ++st)            // the last, partial round
+            if (ks0 + st < nk) do_step(ks0 + st, st);
         lds_barrier();                                 // last reads done before the stages are reused
     }
     ALT_STAMP(3);
-    igemm_epilogue<BM, TM, TN, WTM, WTN>(p, acc, (void *)smem_u4, m0, n0, wm, wn, split, bz);
+    igemm_epilogue<BM, TM, TN, WTM, WTN, NT>(p, acc, (void *)smem_u4, m0, n0, wm, wn, split, bz);
 #ifdef ALT_PHASE_TIMING
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ALT_STAMP(4);
@@ -264,6 +294,7 @@ constexpr size_t igemm_dma_lds_bytes()
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int NS>
 hipError_t igemm_dma_launch(const IgemmParams &p, dim3 grid, hipStream_t st)
 {
+    constexpr int NT = 64 * WGM * WGN;
     constexpr size_t lds = igemm_dma_lds_bytes<T, BM, BN, BK, NS>();
     static_assert(lds <= 160 * 1024, "LDS per workgroup");
     auto kern = igemm_dma_kernel<T, BM, BN, BK, WGM, WGN, NS>;
@@ -273,7 +304,7 @@ hipError_t igemm_dma_launch(const IgemmParams &p, dim3 grid, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(kIgemmThreads), lds, st, p);
+    hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p);
     return hipGetLastError();
 }
 
