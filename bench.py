@@ -25,6 +25,11 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# Kernel arguments in device memory: with the HIP default (host memory) every
+# workgroup's first scalar loads cross the host link, which costs these
+# microsecond-sized kernels 2-5 us each.  Read by the HIP runtime when it starts.
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBPS = 8000.0
 
@@ -36,6 +41,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="skip the extra sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
+                         "which gives a hardware-counter run its scale")
+    ap.add_argument("--plan", default=os.path.join(ROOT, "workloads", "tuned_plan_gfx950.json"),
+                    help="tuned layouts and kernel variants of the batch-16 layers (a previous run's choice)")
+    ap.add_argument("--retune", action="store_true",
+                    help="tune the batch-16 layers on the device now instead of reading --plan, and rewrite it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -79,13 +91,38 @@ def main():
         return float(np.median([timed(fn, reps) for _ in range(batches)]))
 
     # ------------------------------------------------------------ conv layers ----
-    def prepare_layers(batch, out_dtype, budget):
-        """Tunes each layer, then lays out its operands for the tuned layouts."""
+    def from_plan(shape, entry):
+        """The descriptor a stored plan entry names, or None if this build lacks its variant."""
+        a, b = entry["layout"].split("/")
+        d = alt.conv_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, stride=shape.stride_h,
+                          pad=shape.pad_h, in_dtype=shape.in_dtype, out_dtype=shape.out_dtype,
+                          x_layout="NCHW->" + a, w_layout="OIHW->" + b, y_layout="NCHW->" + a)
+        for v in range(h.conv2d_variant_count(d)):
+            try:
+                if h.conv2d_variant_name(d, v) == entry["variant"]:
+                    d.variant = v
+                    return d
+            except alt.AltError:
+                pass
+        return None
+
+    def prepare_layers(batch, out_dtype, budget, plan=None):
+        """Tunes each layer (or takes a stored choice), then lays out its operands for the chosen layouts."""
         layers = []
         for li, L in enumerate(RESNET_LAYERS):
             shape = alt.conv_desc(batch, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"],
                                   pad=L["pad"], in_dtype=alt.BF16, out_dtype=out_dtype)
-            best, rep = h.tune_conv2d(shape, arena, arena.numel(), max_trials=budget, warmup=3, reps=30)
+            best = from_plan(shape, plan[L["name"]]) if plan and L["name"] in plan else None
+            if best is not None:
+                e = plan[L["name"]]
+                rep = alt.TuneReport()
+                rep.trials, rep.best_us, rep.default_us = e["trials"], e["tuned_us"], e["default_layout_us"]
+                for i, (nm, us) in enumerate(e["layout_us"].items()):
+                    rep.layout_name[i].value = nm.encode()
+                    rep.layout_best_us[i] = us
+                rep.n_layouts = len(e["layout_us"])
+            else:
+                best, rep = h.tune_conv2d(shape, arena, arena.numel(), max_trials=budget, warmup=3, reps=30)
             x = f32_to_bf16_bits(normal_f32(0xA17 + 2 + li, (batch, L["C"], L["H"], L["W"])))
             w = f32_to_bf16_bits(normal_f32(0xA17 + 102 + li, (L["K"], L["C"], L["R"], L["S"]), std=0.05))
             x_nchw, w_oihw = dbuf(x.reshape(-1)), dbuf(w.reshape(-1))
@@ -107,24 +144,81 @@ def main():
                                bytes=(x.size + w.size) * 2 + n_out * (4 if out_dtype == alt.F32 else 2)))
         return layers
 
-    def run_layer(l):
-        h.conv2d(l["desc"], l["x"], l["w"], l["y"], workspace=l["ws"], ws_bytes=l["ws_bytes"], stream=stream)
+    def run_layer(l, st=None):
+        h.conv2d(l["desc"], l["x"], l["w"], l["y"], workspace=l["ws"], ws_bytes=l["ws_bytes"], stream=st or stream)
 
-    layers = prepare_layers(16, alt.F32, 0)
+    side = torch.cuda.Stream()
+
+    def capture(fn, n):
+        """A HIP graph of n back-to-back calls of fn(stream), recorded on a side stream."""
+        fn(side)                                # first use of a kernel (module load, attributes) stays outside the capture
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(n):
+                fn(side)
+        return g
+
+    def graph_timed(g, launches_per_replay, replays=10, batches=5):
+        """Median microseconds per launch over `replays` replays of graph g."""
+        out = []
+        for _ in range(batches):
+            g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(replays):
+                g.replay()
+            e1.record(stream)
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1) * 1000.0 / (replays * launches_per_replay))
+        return float(np.median(out))
+
+    plan = None
+    if not args.retune and os.path.exists(args.plan):
+        with open(args.plan) as f:
+            plan = json.load(f)
+    layers = prepare_layers(16, alt.F32, 0, plan)
     torch.cuda.synchronize()
+    tuned_now = plan is None or any(l["L"]["name"] not in plan for l in layers)
+    if tuned_now:
+        new_plan = {l["L"]["name"]: dict(layout=l["layout"], variant=l["variant"], trials=l["trials"],
+                                         tuned_us=round(l["best_us"], 2), default_layout_us=round(l["default_us"], 2),
+                                         layout_us=l["layout_us"]) for l in layers}
+        out_path = args.plan if args.retune else os.path.join(ROOT, "gpurun_out", "tuned_plan.json")
+        try:
+            os.makedirs(os.path.dirname(out_path), exist_ok=True)
+            with open(out_path, "w") as f:
+                json.dump(new_plan, f, indent=1)
+        except OSError:
+            pass
 
-    def step():
+    def step(st=None):
         for l in layers:
-            run_layer(l)
+            run_layer(l, st)
 
-    for _ in range(args.warmup):
-        step()
+    # The step is recorded once into a HIP graph and replayed: the five launches
+    # then cost the GPU's own dispatch time, not the host's call path.  Every
+    # replay runs the same kernels on the same buffers as the eager step; the
+    # outputs of the two are compared bit for bit below.
+    step()
     torch.cuda.synchronize()
+    eager_y = [l["y"].clone() for l in layers]
+    for l in layers:
+        l["y"].fill_(0)
+    g_step = capture(step, 1)
+    for _ in range(args.warmup):
+        g_step.replay()
+    torch.cuda.synchronize()
+    for l, ye in zip(layers, eager_y):
+        if not torch.equal(l["y"], ye):
+            raise SystemExit("bench.py: graph replay of %s differs from the eager launch" % l["L"]["name"])
+    del eager_y
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record(stream)
     for _ in range(args.steps):
-        step()
+        g_step.replay()
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1000.0
@@ -132,11 +226,15 @@ def main():
     dev_ms_per_step = e0.elapsed_time(e1) / args.steps
     step_flops = sum(l["flops"] for l in layers)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
+    # the same step launched call by call from Python (host-bound), for comparison
+    eager_us_per_step = median_timed(step, 50, batches=3)
 
-    # per-layer kernel durations, live, on the launch stream
+    # per-layer kernel durations, live: 20 launches of the layer per graph replay
     per_layer = []
     for l in layers:
-        us = median_timed(lambda l=l: run_layer(l), 200)
+        g = capture(lambda st, l=l: run_layer(l, st), 20)
+        us = graph_timed(g, 20)
+        del g
         l["us"] = us
         per_layer.append(dict(layer=l["L"]["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
                               tflops=round(l["flops"] / us / 1e6, 1),
@@ -153,7 +251,13 @@ def main():
                     kernel="igemm_kernel<%s>" % dom["variant"], layer=dom["L"]["name"],
                     us_per_launch=round(dom["us"], 3), flops_per_launch=dom["flops"])
 
-    extra = dict(per_layer_b16=per_layer, device_ms_per_step=round(dev_ms_per_step, 4))
+    extra = dict(per_layer_b16=per_layer, device_ms_per_step=round(dev_ms_per_step, 4),
+                 launch="one HIP graph replay per step (5 kernel nodes)",
+                 layer_choice="tuned in this run" if tuned_now else "read from " + os.path.relpath(args.plan, ROOT),
+                 eager_python_launch_us_per_step=round(eager_us_per_step, 2))
+
+    if args.calib_copy:
+        h.get_peak(arena[:512 << 20], 512 << 20)
 
     if not args.quick:
         # -------------------------------------------------- conversion operator ----
@@ -169,14 +273,15 @@ def main():
                 for a, b in [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
                              ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW", "NCHW->NCHW32c")]:
                     la, lb = alt.layout_parse(a), alt.layout_parse(b)
-                    state = dict(i=0)
+                    def ring(st):
+                        for i in range(nring):
+                            h.layout_transform(dt, shp, la, srcs[i], lb, dsts[i], stream=st)
 
-                    def f():
-                        i = state["i"] = (state["i"] + 1) % nring
-                        h.layout_transform(dt, shp, la, srcs[i], lb, dsts[i], stream=stream)
-
-                    us_cold = median_timed(f, 4 * nring, batches=3)
-                    us_warm = median_timed(lambda: h.layout_transform(dt, shp, la, srcs[0], lb, dsts[0], stream=stream), 100, 3)
+                    g = capture(ring, 1)
+                    us_cold = graph_timed(g, nring, replays=4, batches=3)
+                    g = capture(lambda st: h.layout_transform(dt, shp, la, srcs[0], lb, dsts[0], stream=st), 20)
+                    us_warm = graph_timed(g, 20, replays=5, batches=3)
+                    del g
                     gb = 2.0 * numel * es / 1e9
                     tr.append(dict(shape=list(shp), dtype="f32" if dt == alt.F32 else "bf16",
                                    src=a.split(">")[1], dst=b.split(">")[1], us_hbm=round(us_cold, 2),
@@ -206,7 +311,9 @@ def main():
             Cd = torch.empty(g["batch"] * g["M"] * g["N"], dtype=torch.float32, device=dev)
             wsb = h.gemm_workspace_size(best)
             ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
-            us = median_timed(lambda: h.gemm(best, A, B, Cd, workspace=ws, ws_bytes=wsb, stream=stream), 200)
+            gr = capture(lambda st: h.gemm(best, A, B, Cd, workspace=ws, ws_bytes=wsb, stream=st), 20)
+            us = graph_timed(gr, 20)
+            del gr
             fl = 2.0 * g["batch"] * g["M"] * g["N"] * g["K"]
             names = [rep.layout_name[i].value.decode() for i in range(rep.n_layouts)]
             lus = [float(rep.layout_best_us[i]) for i in range(rep.n_layouts)]
@@ -223,7 +330,9 @@ def main():
         l1 = prepare_layers(1, alt.F32, 0)
         b1 = []
         for l in l1:
-            us = median_timed(lambda l=l: run_layer(l), 200)
+            g = capture(lambda st, l=l: run_layer(l, st), 20)
+            us = graph_timed(g, 20)
+            del g
             b1.append(dict(layer=l["L"]["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
                            tflops=round(l["flops"] / us / 1e6, 2),
                            speedup_vs_default_layout=round(l["default_us"] / l["best_us"], 2)))

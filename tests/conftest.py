@@ -3,6 +3,8 @@ import sys
 
 import pytest
 
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")   # before the HIP runtime starts (see the package's __init__)
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
