@@ -1,0 +1,119 @@
+// Host side of the patch-resident direct convolution (dconv.h): which problems
+// it covers, its launch parameters, and the arrival counters of its fused
+// split-K reduction.
+#include <atomic>
+
+#include "dconv.h"
+#include "ops.h"
+
+namespace alt {
+
+namespace {
+
+// Arrival counters of the fused split-K reduction: zero when the module is
+// loaded, and every launch leaves them zero again.  kDconvSlots sets are
+// handed out round-robin so that launches in flight on different streams do
+// not share one (more than kDconvSlots overlapping split-K launches would).
+__device__ __align__(256) uint32_t g_dconv_counters[kDconvSlots * kDconvMaxTiles];
+
+constexpr int kMaxDevices = 16;
+uint32_t *g_counter_ptr[kMaxDevices];
+std::atomic<unsigned> g_next_slot{0};
+
+bool dense(const Dim2 &d, int64_t extent, int64_t stride)
+{
+    return extent == 1 || (d.f >= extent && d.si == stride);
+}
+
+}  // namespace
+
+// Device address of the counters on the current device (looked up once per device).
+hipError_t dconv_counters(uint32_t **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_counter_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_dconv_counters));
+        if (e != hipSuccess) return e;
+        g_counter_ptr[dev] = (uint32_t *)ptr;
+    }
+    *out = g_counter_ptr[dev];
+    return hipSuccess;
+}
+
+// Fills the launch parameters of direct kernel `k` for `pb` split into `splitk`
+// channel slices, or says why the kernel does not cover the problem.
+bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes, std::string *why)
+{
+    auto no = [&](const char *m) { if (why) *why = m; return false; };
+    const IgemmParams &p = pb.p;
+    if (pb.dtype != ALT_BF16) return no("direct kernel is bf16 only");
+    if (p.batch != 1) return no("direct kernel takes no batch");
+    if (p.stride_h != 1 || p.stride_w != 1 || p.dil_h != 1 || p.dil_w != 1) return no("direct kernel needs stride 1, dilation 1");
+    if (2 * p.pad_h != p.R - 1 || 2 * p.pad_w != p.S - 1) return no("direct kernel needs same-size padding");
+    if (p.OH != p.H || p.OW != p.W) return no("direct kernel needs output size = input size");
+    const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, R = p.R, S = p.S, N = p.M / (H * W);
+    if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
+        return no("activations are not dense NHWC");
+    if (!(dense(p.wi, C, 1) && dense(p.ws, S, C) && dense(p.wr, R, S * C) && dense(p.wo, K, R * S * C)))
+        return no("weights are not dense OHWI");
+    if (!(dense(p.yk, K, 1) && dense(p.yw, W, K) && dense(p.yh, H, W * K) && dense(p.yn, N, H * W * K)))
+        return no("output is not dense NHWC");
+    if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16) return no("operands are not 16-byte aligned");
+    if (splitk < 1 || C % splitk) return no("split factor does not divide the channels");
+    const int64_t Cs = C / splitk;
+    if (Cs % 64 || (Cs & (Cs - 1)) || Cs > 512) return no("channels per slice must be 64, 128, 256 or 512");
+    if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
+        return no("operand of 2 GiB or more");
+    if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
+    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, (int)Cs, p.W, p.pad_h, p.pad_w);
+    if (lds > 160 * 1024) return no("patch does not fit LDS");
+    const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
+    if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
+    if ((int64_t)tiles_m * tiles_n * splitk > 0x7fffffff) return no("grid too large");
+    if (!out) return true;
+    DconvParams d;
+    std::memset(&d, 0, sizeof d);
+    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
+    d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
+    d.partial_bytes = (uint32_t)((int64_t)p.M * K * 4);
+    d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = (int32_t)Cs;
+    d.H = p.H; d.W = p.W; d.R = p.R; d.S = p.S; d.pad_h = p.pad_h; d.pad_w = p.pad_w;
+    d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = splitk;
+    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
+    d.d_hw = make_div32((uint32_t)(p.H * p.W));
+    d.d_w = make_div32((uint32_t)p.W);
+    d.d_tm = make_div32((uint32_t)tiles_m);
+    d.d_tn = make_div32((uint32_t)tiles_n);
+    int l2 = 0;
+    while ((8 << l2) < Cs) ++l2;
+    d.log2_cpp = l2;
+    // 16 consecutive pixels must spread over the 256 bytes the LDS serves per
+    // cycle: 128-byte pixels pair up (pixel / 2 picks the chunk position), wider ones do not
+    d.swz_shift = Cs == 64 ? 1 : 0;
+    d.swz_mask = Cs == 64 ? 7 : 15;
+    d.ncc = (int32_t)(Cs / 64);
+    *out = d;
+    *lds_bytes = lds;
+    return true;
+}
+
+hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st)
+{
+    if (d.splitk > 1) {
+        uint32_t *base = nullptr;
+        hipError_t e = dconv_counters(&base);
+        if (e != hipSuccess) return e;
+        d.counters = base + (size_t)(g_next_slot.fetch_add(1) % kDconvSlots) * kDconvMaxTiles;
+        d.partial = partial;
+    }
+#ifdef ALT_PHASE_TIMING
+    if (d.splitk == 1) d.partial = partial;    // developer builds: workgroup timestamps go to the workspace
+#endif
+    return k.launch_direct(d, lds, st);
+}
+
+}  // namespace alt

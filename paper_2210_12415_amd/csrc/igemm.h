@@ -631,7 +631,9 @@ __global__ __launch_bounds__(kIgemmThreads) void igemm_kernel(const IgemmParams 
     igemm_epilogue<BM, TM, TN, WTM, WTN>(p, acc, (void *)smem_u4, m0, n0, wm, wn, split, bz);
 }
 
-// Launch of one instantiation; defined in the igemm_*.hip files.
+struct DconvParams;           // dconv.h
+
+// Launch of one instantiation; defined in the igemm_*.hip and dconv_*.hip files.
 struct IgemmLaunch {
     const char *name;
     int dtype, BM, BN, BK, amode, bmode;
@@ -639,6 +641,9 @@ struct IgemmLaunch {
     int dma;                  // 1 = operands go global -> LDS directly (igemm_dma.h)
     size_t lds_bytes;
     hipError_t (*launch)(const IgemmParams &p, dim3 grid, hipStream_t st);
+    // set instead of `launch` for the patch-resident direct convolution (dconv.h),
+    // which splits K over channel slices and reduces them inside the same launch
+    hipError_t (*launch_direct)(const DconvParams &p, size_t lds_bytes, hipStream_t st) = nullptr;
 };
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE, int PF>

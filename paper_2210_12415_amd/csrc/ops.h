@@ -1,7 +1,7 @@
 // Shared between ops.hip (conv/gemm entry points) and tune.cpp.
 #pragma once
 
-#include "igemm.h"
+#include "dconv.h"
 
 namespace alt {
 
@@ -25,6 +25,11 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
 int igemm_default_variant(const Problem &pb, size_t ws_limit);
 alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *workspace, size_t ws_bytes,
                        hipStream_t st);
+
+// dconv.hip
+bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes,
+                 std::string *why);
+hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st);
 
 alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
                           const float *bias, void *y, Problem *pb);

@@ -101,6 +101,19 @@ bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, Igemm
     auto no = [&](const char *m) { if (why) *why = m; return false; };
     const IgemmParams &p0 = pb.p;
     if (k.dtype != pb.dtype) return no("element type");
+    if (k.launch_direct) {
+        if (!dconv_setup(pb, k, splitk, nullptr, nullptr, why)) return false;
+        if (out) {
+            IgemmParams p = p0;
+            p.splitk = splitk;
+            p.ksteps_total = p.R * p.S * (p.C / 64);
+            p.ksteps_per_split = p.ksteps_total / splitk;
+            p.tiles_m = (p.M + k.BM - 1) / k.BM;
+            p.tiles_n = (p.Nc + k.BN - 1) / k.BN;
+            *out = p;
+        }
+        return true;
+    }
     if (!pb.spatial_ok && (k.amode != LOAD_GATHER)) return no("blocked H/W needs R=S=1 without padding");
     const bool uniform = p0.C % k.BK == 0 && nests(p0.xc.f, p0.C, k.BK) && nests(p0.wi.f, p0.C, k.BK);
     if (k.amode == LOAD_VEC && !(pb.a_vec && uniform)) return no("A is not channel-contiguous in 16-byte blocks");
@@ -148,11 +161,12 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
     if (k.amode == LOAD_TRANS) mode_cost *= 1.5;
     if (k.bmode == LOAD_TRANS) mode_cost *= 1.5;
     if (k.prefetch > 1) mode_cost *= 0.8;
+    if (k.launch_direct) mode_cost *= 0.5;
     const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
     const double rounds = std::ceil(blocks / 512.0);
     const double step = (double)k.BM * k.BN * k.BK / 16384.0 + 3.0 * (k.BM + k.BN) * k.BK / 8192.0 + 2.0;
     double est = rounds * (p.ksteps_per_split * step + 20.0) * mode_cost;
-    if (p.splitk > 1) est += 30.0 + 0.00002 * p.splitk * (double)p.M * p.Nc * p.batch;
+    if (p.splitk > 1) est += (k.launch_direct ? 5.0 : 30.0) + 0.00002 * p.splitk * (double)p.M * p.Nc * p.batch;
     return est;
 }
 
@@ -186,6 +200,17 @@ alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *wor
     if (!igemm_applicable(pb, k, splitk, &p, &why))
         return fail(h, ALT_UNSUPPORTED, "variant %s/splitk%d not applicable: %s", k.name, splitk, why.c_str());
     const size_t need = igemm_workspace(pb, splitk);
+    if (k.launch_direct) {
+        if (need > 0 && (!workspace || ws_bytes < need))
+            return fail(h, ALT_WORKSPACE_TOO_SMALL, "split-K needs %zu workspace bytes, got %zu", need, ws_bytes);
+        DconvParams dp;
+        size_t lds = 0;
+        if (!dconv_setup(pb, k, splitk, &dp, &lds, &why))
+            return fail(h, ALT_UNSUPPORTED, "variant %s/splitk%d not applicable: %s", k.name, splitk, why.c_str());
+        hipError_t e = dconv_run(k, dp, lds, (float *)workspace, st);
+        if (e != hipSuccess) return fail(h, ALT_HIP_ERROR, "launch of %s failed: %s", k.name, hipGetErrorString(e));
+        return ALT_OK;
+    }
 #ifdef ALT_PHASE_TIMING
     if (need == 0 && workspace) p.partial = (float *)workspace;
 #endif

@@ -88,6 +88,47 @@ def test_exact_integers_every_variant(h, layouts, in_dtype):
         assert np.array_equal(got, ref), name
 
 
+DIRECT_CASES = [
+    # (N, C, H, W, K, R, S, pad_h == pad_w or (pad_h, pad_w))
+    dict(N=3, C=128, H=9, W=10, K=96, R=3, S=3, pad=1),      # tiles straddle image boundaries, ragged M and K
+    dict(N=2, C=64, H=20, W=17, K=64, R=3, S=3, pad=1),      # 128-byte patch pixels (the paired swizzle)
+    dict(N=2, C=256, H=13, W=6, K=160, R=1, S=1, pad=0),     # 1x1: no halo, up to four channel slices
+    dict(N=1, C=64, H=11, W=12, K=32, R=5, S=5, pad=2),      # two-pixel halo, K below one tile
+    dict(N=5, C=512, H=3, W=3, K=64, R=3, S=3, pad=1),       # images smaller than the halo of a tile
+]
+
+
+@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"]))
+def test_direct_kernel_exact_integers_every_variant(h, case):
+    """The patch-resident direct kernels (NHWC / OHWI / NHWC, same-size padding):
+    every tile shape, pipeline depth and channel-slice count, bit for bit; fp32
+    and bf16 output, bias and ReLU through the fused split-K tail as well."""
+    c = case
+    x = small_ints_f32(61, (c["N"], c["C"], c["H"], c["W"]), -3, 3)
+    w = small_ints_f32(62, (c["K"], c["C"], c["R"], c["S"]), -3, 3)
+    b = small_ints_f32(63, (c["K"],), -50, 50)
+    cfg = dict(stride=1, pad=c["pad"])
+    ref = oracle.conv2d(x, w, stride=1, pad=c["pad"])
+    ref_br = oracle.conv2d(x, w, stride=1, pad=c["pad"], bias=b, relu=True)
+    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=1, pad=c["pad"],
+                       in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+    variants = [(v, n) for v, n in applicable_variants(h, d0) if "direct" in n]
+    assert len(variants) >= 30, "direct kernels should cover this case"
+    assert any(not n.endswith("_k1") for _, n in variants) or c["C"] == 64
+    for v, name in variants:
+        got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, variant=v)
+        assert np.array_equal(got, ref), name
+    # the epilogue variants on a few kernels, split and unsplit
+    picks = [variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
+    for v, name in picks:
+        got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, bias=b, relu=True, variant=v)
+        assert np.array_equal(got, ref_br), name
+        got16, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, out_dtype=alt.BF16, bias=b, relu=True,
+                            variant=v)
+        assert np.array_equal(got16, f32_to_bf16_bits(ref_br)), name
+
+
 @pytest.mark.parametrize("cfg", [dict(stride=2, pad=1), dict(stride=1, pad=0), dict(stride=2, pad=0),
                                  dict(stride=1, pad=2, dil=2), dict(stride=3, pad=1)])
 @pytest.mark.parametrize("layouts", LAYOUT_SETS[:4])
