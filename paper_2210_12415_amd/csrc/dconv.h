@@ -15,7 +15,7 @@
 //
 // Covers: bf16, stride 1, dilation 1, "same" padding (2*pad = R-1, S-1; so 1x1
 // pad 0 too), activations NHWC, weights OHWI, output NHWC (fp32 or bf16), all
-// dense, channels a multiple of 64 per split.  The linear pixel index of the
+// dense, channels a multiple of 64 per split, output channels a multiple of 4.  The linear pixel index of the
 // input is then the linear index of the output pixel plus a per-tap constant,
 // across image boundaries too, which is what makes the patch one contiguous
 // range of input pixels.
@@ -65,6 +65,8 @@ struct DconvParams {
     int32_t ncc;                  // Cs / 64: K steps per tap
 };
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 constexpr int kDconvOutBf16 = 4;
 constexpr int kAgentScope = 16;          // cache-policy operand of buffer loads/stores: sc1 = device (agent) scope
 constexpr int kDconvMaxTiles = 4096;     // output tiles a split-K launch may have (one counter each)
@@ -84,7 +86,29 @@ __device__ __forceinline__ void dma_load16_s(i32x4_t rsrc, uint32_t voff, uint32
                  : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
+// LDS operand read whose completion the compiler does not track: the data is
+// only valid after lds_wait<N>() on the same registers.
+__device__ __forceinline__ void lds_read16_async(u32x4_t &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
+}
+
+// Waits until at most N LDS operations of this wave are outstanding and ties
+// the given fragment registers to that point (no use can move above it).
+template <int N, int NA, int NB>
+__device__ __forceinline__ void lds_wait(u32x4_t (&a)[NA], u32x4_t (&b)[NB])
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a[0]) : "n"(N) : "memory");
+#pragma unroll
+    for (int i = 1; i < NA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+// KR > 0: the filter is KR x KR with KR known at compile time (1 and 3 are
+// instantiated): the taps are unrolled and their patch addresses precomputed.
+// KR = 0: any filter size, taps walked at run time.
+template <int BM, int BN, int WGM, int WGN, int NS, int KR>
 __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
@@ -99,7 +123,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     constexpr int NLB = B_STAGE / 1024 / NW;               // wave-loads per wave per stage
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile");
     static_assert(B_STAGE % (1024 * NW) == 0 && NLB >= 1, "a weight stage is a whole number of wave-loads per wave");
-    static_assert(NS >= 2 && (NS - 1) * NLB < 48, "pipeline depth against the vmcnt range");
+    static_assert(NS >= 3 && (NS - 1) * NLB < 48, "pipeline depth");
+    static_assert(TM + TN <= 15, "fragment reads in flight against the lgkmcnt range");
 
     extern __shared__ uint4 smem_u4[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem_u4;    // weight stages first, then the patch
@@ -122,24 +147,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     const i32x4_t w_rsrc = make_rsrc(p.w, p.w_bytes);
 
     // ---- the patch: input pixels [m0 - halo, m0 + BM + halo), Cs channels of this slice --------
+    // 16-byte slot s of the patch region holds chunk (s % cpp) ^ swz(pixel) of pixel s / cpp.
     const int halo = p.pad_h * p.W + p.pad_w;
     const int np = BM + 2 * halo;
     const int log2_pitch = p.log2_cpp + 4;                 // bytes per patch pixel = Cs * 2
-    const int nslots = np << p.log2_cpp;                   // 16-byte slots
-    const int nwl = (nslots + 63) >> 6;                    // wave-loads (the region is padded to whole ones)
+    const int nwl = ((np << p.log2_cpp) + 63) >> 6;        // wave-loads (the region is padded to whole ones)
     const int pz = (nwl << 10) >> log2_pitch;              // index of the all-zero pixel row behind the patch
     {
-        const int cmask = (1 << p.log2_cpp) - 1;
+        const int ppw = 64 >> p.log2_cpp;                  // pixels per wave-load (Cs <= 512)
+        const int lpx = lane >> p.log2_cpp, cpos = lane & ((1 << p.log2_cpp) - 1);
         const int g0 = m0 - halo;
-        for (int j = wave; j < nwl; j += NW) {
-            const int sidx = j * 64 + lane;
-            const int px = sidx >> p.log2_cpp, cpos = sidx & cmask;
+        const uint32_t lane_off = (uint32_t)(split * p.Cs) * 2u;
+        auto load_one = [&](int j) {
+            const int px = j * ppw + lpx;
             const int q = cpos ^ ((px >> p.swz_shift) & p.swz_mask);
             const int g = g0 + px;
-            const bool ok = sidx < nslots && (unsigned)g < (unsigned)p.M;
-            const uint32_t voff = ok ? (uint32_t)(g * p.C + split * p.Cs + q * 8) * 2u : kOutOfRange;
+            const bool ok = px < np && (unsigned)g < (unsigned)p.M;
+            const uint32_t voff = ok ? (uint32_t)(g * p.C) * 2u + lane_off + (uint32_t)q * 16u : kOutOfRange;
             dma_load16(x_rsrc, voff, patch0 + j * 1024);
+        };
+        int j = wave;
+        for (; j + 3 * NW < nwl; j += 4 * NW) {            // four at a time: independent address chains
+            load_one(j); load_one(j + NW); load_one(j + 2 * NW); load_one(j + 3 * NW);
         }
+        for (; j < nwl; j += NW) load_one(j);
         if (t < (1 << p.log2_cpp)) ((uint4 *)((char *)smem_u4 + NS * B_STAGE + (pz << log2_pitch)))[t] = make_uint4(0, 0, 0, 0);
     }
 
@@ -156,19 +187,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     const uint32_t ldsB = lds0 + wave * 1024;
     const int nsteps = p.R * p.S * p.ncc;
     // load cursor: byte offset of K step `lstep` inside a weight row, (tap, chunk) walked chunk fastest
-    int lstep = 0, lcc = 0;
+    int lstep = 0, lcc = 0, lstage = 0;
     uint32_t lsoff = 0;
     auto issue_b = [&]() {
-        const int stage = lstep % NS;
 #pragma unroll
-        for (int i = 0; i < NLB; ++i) dma_load16_s(w_rsrc, b_voff[i], lsoff, ldsB + stage * B_STAGE + i * (NW * 1024));
+        for (int i = 0; i < NLB; ++i) dma_load16_s(w_rsrc, b_voff[i], lsoff, ldsB + lstage * B_STAGE + i * (NW * 1024));
         ++lstep;
-        if (++lcc == p.ncc) { lcc = 0; lsoff += (uint32_t)(p.C - p.Cs) * 2u; }
-        lsoff += BK * 2;
+        lstage = lstage + 1 == NS ? 0 : lstage + 1;
+        // next K step's offset inside a weight row; past the last step it stays where it is
+        const bool more = lstep < nsteps;
+        const bool wrap = lcc + 1 == p.ncc;
+        lsoff += more ? (uint32_t)(BK * 2) + (wrap ? (uint32_t)(p.C - p.Cs) * 2u : 0u) : 0u;
+        lcc = more ? (wrap ? 0 : lcc + 1) : lcc;
     };
+    // NS - 1 stages in flight from here on (past the last step: repeats of it, never read)
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < nsteps) issue_b();
+    for (int s = 0; s < NS - 1; ++s) issue_b();
 
     // ---- per-lane rows of the MFMA tiles ---------------------------------------------------------
     int32_t row_px[TM], row_oh[TM], row_ow[TM];
@@ -187,14 +221,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
             row_ow[i] = -(1 << 20);
         }
     }
-    // weight operand addresses inside a stage (byte offsets from lds0), per n tile and k chunk
+    // weight operand addresses inside stage 0 (LDS byte addresses), per n tile and k chunk
     uint32_t b_rd[TN][NKC];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int r = wn * WTN + j * 32 + (lane & 31);
         const uint32_t swz = ((r >> 1) & 7) * 16;
 #pragma unroll
-        for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = r * 128 + ((kc * 32 + (lane >> 5) * 16) ^ swz);
+        for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = lds0 + r * 128 + ((kc * 32 + (lane >> 5) * 16) ^ swz);
     }
 
     floatx16_t acc[TM][TN];
@@ -205,85 +239,238 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const char *lds_base = (const char *)smem_u4;
-    const char *patch_base = lds_base + NS * B_STAGE;
     const uint32_t khalf = (lane >> 5) * 16;
 
+    // Where the MFMA row tiles of one K step read: patch row and swizzle under the
+    // step's tap (rows whose tap falls outside the image use the zero row), the
+    // channel offset inside the pixel and the weight stage.
+    struct StepAddr {
+        uint32_t a_row[TM], a_swz[TM], c_off, st_off;
+    };
+    auto set_tap = [&](StepAddr &sa, int r, int s) {
+        const int shift = (r - p.pad_h) * p.W + (s - p.pad_w);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const bool ok = (unsigned)(row_oh[i] + r - p.pad_h) < (unsigned)p.H &&
+                            (unsigned)(row_ow[i] + s - p.pad_w) < (unsigned)p.W;
+            const int px = ok ? row_px[i] + shift : pz;
+            sa.a_row[i] = patch0 + ((uint32_t)px << log2_pitch);
+            sa.a_swz[i] = (uint32_t)((px >> p.swz_shift) & p.swz_mask) << 4;
+        }
+    };
+    // Operand reads run D k-chunks ahead of the MFMAs that use them, each k-chunk in a
+    // register buffer of its own (kc % NKC): with one wave per SIMD the LDS latency
+    // under load (several hundred cycles) is only covered by that many MFMA groups.
+    constexpr int D = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
+    static_assert(D < NKC, "look-ahead stays within the next step");
+    u32x4_t af[NKC][TM], bf[NKC][TN];
+    auto read_frags = [&](int kc, const StepAddr &sa) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], sa.a_row[i] + ((sa.c_off + kc * 32) ^ sa.a_swz[i]));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rd[j][kc] + sa.st_off);
+    };
+
     ALT_STAMP(1);
-    // ---- main loop: taps outer, 64-channel chunks inner; one barrier per K step ---------------------
-    int step = 0;
-    for (int r = 0; r < p.R; ++r) {
-        for (int s = 0; s < p.S; ++s) {
-            const int shift = (r - p.pad_h) * p.W + (s - p.pad_w);
-            uint32_t a_row[TM], a_swz[TM];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const bool ok = (unsigned)(row_oh[i] + r - p.pad_h) < (unsigned)p.H &&
-                                (unsigned)(row_ow[i] + s - p.pad_w) < (unsigned)p.W;
-                const int px = ok ? row_px[i] + shift : pz;
-                a_row[i] = (uint32_t)px << log2_pitch;
-                a_swz[i] = (uint32_t)((px >> p.swz_shift) & p.swz_mask) << 4;
-            }
-            for (int cc = 0; cc < p.ncc; ++cc, ++step) {
-                if (step + NS - 2 < nsteps) wait_vmcnt<(NS - 2) * NLB>();
-                else wait_vmcnt<0>();
-                lds_barrier();                 // step's weights (and at step 0 the patch) are in LDS; step-1 is consumed
 #ifdef ALT_PHASE_TIMING
-                if (step == 0) ALT_STAMP(2);
+    const uint64_t core_clk0 = __builtin_amdgcn_s_memtime();
 #endif
-                if (lstep < nsteps) issue_b();
-                const uint32_t st_off = (uint32_t)(step % NS) * B_STAGE;
-                const uint32_t c_off = (uint32_t)cc * (BK * 2) + khalf;
-                uint4 af[2][TM], bf[2][TN];
+    // ---- main loop -------------------------------------------------------------------------------------
+    // K steps walk the taps, 64-channel chunks of the slice innermost.  Step t's weights
+    // sit in stage t % NS.  At the barrier that opens step t every wave has its share of
+    // stage t+1 landed, so after it stages t and t+1 are complete for everybody and the
+    // look-ahead reads may run into step t+1 before the next barrier.  The same barrier
+    // says stage t-1 is consumed, and its refill (step t+NS-1) is issued after it.
+    //
+    // A wave issues in order, so whatever sits between two MFMA groups delays the
+    // second one unless it can run in the first one's shadow.  The body of a step is
+    // therefore one straight basic block: the bookkeeping of the next step (tap, row
+    // addresses) uses selects, not branches, and stands after the first MFMA group; past
+    // the last step the weight refills and look-ahead reads repeat the last step's
+    // addresses (loaded, never used) instead of being skipped.
+    if constexpr (KR > 0) {
+        // Patch rows and swizzles of every tap, computed while the patch is still in flight.
+        constexpr int RS = KR * KR;
+        uint32_t t_row[RS][TM], t_swz[RS][TM];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) af[0][i] = *(const uint4 *)(patch_base + a_row[i] + (c_off ^ a_swz[i]));
+        for (int tap = 0; tap < RS; ++tap) {
+            StepAddr sa;
+            set_tap(sa, tap / KR, tap % KR);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bf[0][j] = *(const uint4 *)(lds_base + st_off + b_rd[j][0]);
+            for (int i = 0; i < TM; ++i) { t_row[tap][i] = sa.a_row[i]; t_swz[tap][i] = sa.a_swz[i]; }
+        }
+        wait_vmcnt<(NS - 2) * NLB>();                      // the patch and stage 0
+        lds_barrier();
+        ALT_STAMP(2);
+        uint32_t st_off = 0;                               // stage of the current step (byte offset)
+        uint32_t c_off = khalf;                            // channel offset of the current step inside a pixel
+        auto reads = [&](int kc, const uint32_t (&row)[TM], const uint32_t (&swz)[TM], uint32_t co, uint32_t so) {
 #pragma unroll
-                for (int kc = 0; kc < NKC; ++kc) {
-                    if (kc + 1 < NKC) {
+            for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], row[i] + ((co + kc * 32) ^ swz[i]));
 #pragma unroll
-                        for (int i = 0; i < TM; ++i)
-                            af[(kc + 1) & 1][i] = *(const uint4 *)(patch_base + a_row[i] + ((c_off + (kc + 1) * 32) ^ a_swz[i]));
+            for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rd[j][kc] + so);
+        };
 #pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            bf[(kc + 1) & 1][j] = *(const uint4 *)(lds_base + st_off + b_rd[j][kc + 1 < NKC ? kc + 1 : 0]);
-                    }
+        for (int kc = 0; kc < D; ++kc) reads(kc, t_row[0], t_swz[0], c_off, st_off);
+        // One K step under tap `tap`; its look-ahead reads run into the step at
+        // (nrow, nswz, n_c_off): the same tap's next channel chunk, or the next tap.
+        auto step_body = [&](const uint32_t (&row)[TM], const uint32_t (&swz)[TM], const uint32_t (&nrow)[TM],
+                             const uint32_t (&nswz)[TM], uint32_t n_c_off, bool more) {
+            wait_vmcnt<(NS - 3) * NLB>();                  // stage step+1 has landed (this wave's share)
+            asm volatile("s_barrier" ::: "memory");
+            issue_b();
+            const uint32_t st1 = st_off + B_STAGE == NS * B_STAGE ? 0 : st_off + B_STAGE;
+            const uint32_t n_st_off = more ? st1 : st_off;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+            for (int kc = 0; kc < NKC; ++kc) {
+                if (kc + D < NKC) reads(kc + D, row, swz, c_off, st_off);
+                else reads(kc + D - NKC, nrow, nswz, n_c_off, n_st_off);
+                lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) mma_tile(acc[i][j], af[kc & 1][i], bf[kc & 1][j], bf16_tag{});
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
+                                                                            __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                                                                            acc[i][j], 0, 0, 0);
+            }
+            st_off = n_st_off;
+            c_off = n_c_off;
+        };
+#pragma unroll
+        for (int tap = 0; tap < RS; ++tap) {
+            for (int cc = 0; cc + 1 < p.ncc; ++cc)         // all but the tap's last chunk: the next step stays under this tap
+                step_body(t_row[tap], t_swz[tap], t_row[tap], t_swz[tap], c_off + BK * 2, true);
+            const int ntap = tap + 1 < RS ? tap + 1 : tap;       // past the last step: reads that are never used
+            step_body(t_row[tap], t_swz[tap], t_row[ntap], t_swz[ntap], tap + 1 < RS ? khalf : c_off, tap + 1 < RS);
+        }
+    } else {
+        int r = 0, s = 0, cc = 0;
+        StepAddr cur, nxt;
+        set_tap(cur, 0, 0);
+        cur.c_off = khalf;
+        cur.st_off = 0;
+        wait_vmcnt<(NS - 2) * NLB>();                          // the patch and stage 0
+        lds_barrier();
+        ALT_STAMP(2);
+    #pragma unroll
+        for (int kc = 0; kc < D; ++kc) read_frags(kc, cur);
+        for (int step = 0; step < nsteps; ++step) {
+            wait_vmcnt<(NS - 3) * NLB>();                      // stage step+1 has landed (this wave's share)
+    #ifdef ALT_PHASE_TIMING
+            if (!(p.flags & 512))
+    #endif
+            asm volatile("s_barrier" ::: "memory");
+    #ifdef ALT_PHASE_TIMING
+            if (!(p.flags & 256))
+    #endif
+            issue_b();
+    #pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) {
+    #ifdef ALT_PHASE_TIMING
+                if (!(p.flags & 1024)) {
+    #endif
+                if (kc + D < NKC) read_frags(kc + D, cur);
+                else read_frags(kc + D - NKC, nxt);
+                lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
+    #ifdef ALT_PHASE_TIMING
+                }
+    #endif
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
+                                                                            __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                                                                            acc[i][j], 0, 0, 0);
+                if (kc == 0) {
+                    // where step + 1 reads (after the last step: where this one does)
+                    const bool more = step + 1 < nsteps;
+                    const bool wrap_c = cc + 1 == p.ncc;
+                    const bool wrap_s = wrap_c && s + 1 == p.S;
+                    cc = more ? (wrap_c ? 0 : cc + 1) : cc;
+                    s = more && wrap_c ? (wrap_s ? 0 : s + 1) : s;
+                    r = more && wrap_s ? r + 1 : r;
+                    set_tap(nxt, r, s);
+                    nxt.c_off = khalf + (uint32_t)cc * (BK * 2);
+                    const uint32_t st1 = cur.st_off + B_STAGE == NS * B_STAGE ? 0 : cur.st_off + B_STAGE;
+                    nxt.st_off = more ? st1 : cur.st_off;
                 }
             }
+            cur = nxt;
         }
     }
-
+    wait_vmcnt<0>();                                       // the refills past the last step
+    // The look-ahead reads past the last step are never used, but they still land in
+    // their registers some hundred cycles after they were issued: the registers must
+    // stay reserved until then, so they are tied to a wait here like any other read.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[kc][i]));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bf[kc][j]));
+    }
     ALT_STAMP(3);
-    // ---- split-K: publish the partial tile; the last slice to arrive sums all slices ------------------
+#ifdef ALT_PHASE_TIMING
+    const uint64_t core_clk1 = __builtin_amdgcn_s_memtime();
+#endif
+
+    // ---- the wave's tile goes through LDS to row-major order -----------------------------------------
+    // Accumulator register e of lane l is element (8*(e/4) + 4*(l/32) + e%4, l%32) of a 32x32
+    // tile: consecutive lanes hold consecutive channels of one pixel, one dword each.
+    // Stores of one dword per lane run at a quarter of the rate of 16-byte ones, so each
+    // wave transposes through a private LDS region ([WTM][WTN + 8] floats: the pitch
+    // keeps both the dword writes and the 16-byte reads conflict-free) and then handles
+    // four consecutive channels per lane.
+    constexpr int SP = WTN + 8;                            // staging pitch in floats
+    constexpr int CPRW = WTN / 4;                          // 16-byte chunks per staged row
+    constexpr int RPI = 64 / CPRW;                         // rows per wave-wide access
+    __syncthreads();                                       // every wave is done with the stages and the patch
+#ifdef ALT_PHASE_TIMING
+    uint64_t epi_clk[3];
+    epi_clk[0] = __builtin_amdgcn_s_memtime();
+#endif
+    float *stg = (float *)smem_u4 + wave * (WTM * SP);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stg[(i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][e];
+    // (a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
+#ifdef ALT_PHASE_TIMING
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    epi_clk[1] = __builtin_amdgcn_s_memtime();
+#endif
+    const int cl = lane % CPRW, rl = lane / CPRW;          // this lane's chunk and row inside an access
+    const int n = n0 + wn * WTN + cl * 4;
+    const bool n_ok = n < p.Nc;                            // Nc % 4 == 0
+    const int mrow0 = m0 + wm * WTM + rl;
     const int tile = mt * p.tiles_n + nt;
+
     if (p.splitk > 1) {
+        // publish the partial tile; the last slice to arrive sums all slices in slice order
         const __amdgpu_buffer_rsrc_t pr = __builtin_amdgcn_make_buffer_rsrc(
             (void *)((char *)p.partial + (size_t)split * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                    const uint32_t off = (m < p.M && n < p.Nc) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-                    const float v = acc[i][j][e];
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), pr, (int)off, 0, kAgentScope);
-                }
-            }
+        for (int it = 0; it < WTM / RPI; ++it) {
+            const int m = mrow0 + it * RPI;
+            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
+            const u32x4_t v = {__builtin_bit_cast(uint32_t, f.x), __builtin_bit_cast(uint32_t, f.y),
+                               __builtin_bit_cast(uint32_t, f.z), __builtin_bit_cast(uint32_t, f.w)};
+            const uint32_t off = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
+            __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, kAgentScope);
+        }
         // The partial sums were stored with device (agent) scope, i.e. written through to
         // memory all XCDs share; once the stores are acknowledged they are visible to
         // device-scope loads anywhere.  That is the release half; a full device-scope
         // fence would write back the whole L2 and costs tens of microseconds here.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        uint32_t *flag = (uint32_t *)smem_u4;  // the weight stages are free now
+        uint32_t *flag = (uint32_t *)smem_u4 + NW * (WTM * SP);
         if (t == 0) {
             const uint32_t old = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             *flag = old == (uint32_t)(p.splitk - 1);
@@ -292,55 +479,53 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         __syncthreads();
         if (*flag == 0) return;
         // acquire half: the loads below have device scope and so do not hit stale cache lines
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-        for (int sl = 0; sl < p.splitk; ++sl) {
-            const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)((char *)p.partial + (size_t)sl * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                        const uint32_t off = (m < p.M && n < p.Nc) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-                        const uint32_t bits = __builtin_amdgcn_raw_buffer_load_b32(sr, (int)off, 0, kAgentScope);
-                        acc[i][j][e] += __builtin_bit_cast(float, bits);
-                    }
-                }
-        }
     }
 
-    // ---- epilogue: bias, ReLU, rounding, NHWC store ---------------------------------------------------------
     const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)p.y_bytes, 0x00020000);
     const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
     const bool out_bf16 = p.flags & kDconvOutBf16;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (n_ok && (p.flags & ALT_EPI_BIAS)) {
+        const float4 b4 = *(const float4 *)(p.bias + n);
+        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
+    }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-        const bool n_ok = n < p.Nc;
-        const float bv = (n_ok && (p.flags & ALT_EPI_BIAS)) ? p.bias[n] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                const uint32_t idx = (uint32_t)(m * p.Nc + n);
-                const bool ok = n_ok && m < p.M;
-                const float v = fmaxf(acc[i][j][e] + bv, relu_floor);
-                if (out_bf16)
-                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(v), yr, (int)(ok ? idx * 2u : kOutOfRange), 0, 0);
-                else
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), yr, (int)(ok ? idx * 4u : kOutOfRange), 0, 0);
+    for (int it = 0; it < WTM / RPI; ++it) {
+        const int m = mrow0 + it * RPI;
+        const bool ok = n_ok && m < p.M;
+        const uint32_t idx = (uint32_t)(m * p.Nc + n);
+        float v[4];
+        if (p.splitk > 1) {
+            // (summed as whole vectors: element-wise float views of the loaded vector are
+            // miscompiled into a single-dword load by this toolchain)
+            f32x4_t vs = {0.f, 0.f, 0.f, 0.f};
+            for (int sl = 0; sl < p.splitk; ++sl) {
+                const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)((char *)p.partial + (size_t)sl * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
+                const u32x4_t w4 = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(ok ? idx * 4u : kOutOfRange), 0, kAgentScope);
+                vs += __builtin_bit_cast(f32x4_t, w4);
             }
+            v[0] = vs[0]; v[1] = vs[1]; v[2] = vs[2]; v[3] = vs[3];
+        } else {
+            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
+            v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = fmaxf(v[q] + bv[q], relu_floor);
+        if (out_bf16) {
+            const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+            const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+            typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+            u32x2_t o = {lo, hi};
+            __builtin_amdgcn_raw_buffer_store_b64(o, yr, (int)(ok ? idx * 2u : kOutOfRange), 0, 0);
+        } else {
+            u32x4_t o = {__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
+                         __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(o, yr, (int)(ok ? idx * 4u : kOutOfRange), 0, 0);
+        }
     }
 #ifdef ALT_PHASE_TIMING
+    epi_clk[2] = __builtin_amdgcn_s_memtime();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ALT_STAMP(4);
     if (threadIdx.x == 0 && p.partial && p.splitk == 1) {
@@ -348,24 +533,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         for (int i = 0; i < 5; ++i) out[i] = stamps[i];
         out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
         out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
+        out[7] = core_clk1 - core_clk0;                                // core clocks spent in the main loop
+        out[4] = stamps[4] | ((epi_clk[1] - epi_clk[0]) << 48);         // top 16 bits: clocks barrier -> staged
+        out[3] = stamps[3] | ((epi_clk[2] - epi_clk[1]) << 48);         // clocks staged -> stores issued
+        out[2] = stamps[2] | ((epi_clk[0] - core_clk1) << 48);          // clocks main loop end -> past the barrier
     }
 #endif
 }
 
 // LDS bytes of one workgroup: weight stages, the patch rounded up to whole
 // wave-loads, the all-zero row.
-inline size_t dconv_lds_bytes(int BM, int BN, int NS, int Cs, int W, int pad_h, int pad_w)
+inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int Cs, int W, int pad_h, int pad_w)
 {
     const size_t pitch = (size_t)Cs * 2;
     const size_t np = (size_t)BM + 2 * ((size_t)pad_h * W + pad_w);
     const size_t patch = (np * pitch + 1023) / 1024 * 1024;
-    return (size_t)NS * BN * 128 + patch + pitch;
+    const size_t main_loop = (size_t)NS * BN * 128 + patch + pitch;
+    // output staging: [BM][BN + 8 floats per wave column] + the split-K flag
+    const size_t staging = (size_t)BM * (BN + 8 * waves_n) * 4 + 16;
+    return main_loop > staging ? main_loop : staging;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
-hipError_t dconv_launch(const DconvParams &p, size_t lds, hipStream_t st)
+template <int BM, int BN, int WGM, int WGN, int NS, int KR>
+hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    auto kern = dconv_kernel<BM, BN, WGM, WGN, NS>;
+    auto kern = dconv_kernel<BM, BN, WGM, WGN, NS, KR>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -376,10 +568,13 @@ hipError_t dconv_launch(const DconvParams &p, size_t lds, hipStream_t st)
     return hipGetLastError();
 }
 
-struct DconvLaunch {
-    const char *name;
-    int BM, BN, NS, waves;
-    hipError_t (*launch)(const DconvParams &p, size_t lds, hipStream_t st);
-};
+// 1x1 and 3x3 filters have kernels with unrolled taps; other sizes walk the taps at run time.
+template <int BM, int BN, int WGM, int WGN, int NS>
+hipError_t dconv_launch(const DconvParams &p, size_t lds, hipStream_t st)
+{
+    if (p.R == 3 && p.S == 3) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3>(p, lds, st);
+    if (p.R == 1 && p.S == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1>(p, lds, st);
+    return dconv_launch_kr<BM, BN, WGM, WGN, NS, 0>(p, lds, st);
+}
 
 }  // namespace alt

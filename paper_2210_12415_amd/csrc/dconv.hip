@@ -69,7 +69,9 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
         return no("operand of 2 GiB or more");
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
-    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, (int)Cs, p.W, p.pad_h, p.pad_w);
+    if (K % 4 || (uintptr_t)p.y % 16 || ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 16))
+        return no("direct kernel stores four output channels at a time");
+    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, (int)Cs, p.W, p.pad_h, p.pad_w);
     if (lds > 160 * 1024) return no("patch does not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
@@ -112,6 +114,7 @@ hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *par
     }
 #ifdef ALT_PHASE_TIMING
     if (d.splitk == 1) d.partial = partial;    // developer builds: workgroup timestamps go to the workspace
+    if (const char *e = std::getenv("ALT_EXPERIMENT")) d.flags |= std::atoi(e);   // 256: no weight loads, 512: no barrier, 1024: no LDS reads
 #endif
     return k.launch_direct(d, lds, st);
 }

@@ -1,4 +1,4 @@
-// Instantiations of the patch-resident direct convolution: smaller wavefront tiles.
+// Instantiations of the patch-resident direct convolution: 128x64 tiles.
 #include "dconv.h"
 
 namespace alt {
@@ -8,27 +8,15 @@ namespace {
     const bool reg_dconv_##BM##x##BN##_w##WGM##x##WGN##_s##NS =                                                  \
         (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_direct_w" #WGM "x" #WGN "_s" #NS, ALT_BF16, BM, BN,  \
                                     64, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,                               \
-                                    &dconv_launch<BM, BN, WGM, WGN, NS>}),                                       \
+                                    &dconv_launch<BM, BN, WGM, WGN, NS>, WGM, WGN}),                             \
          true)
 
-ALT_DCONV(128, 64, 4, 1, 2);
+ALT_DCONV(128, 64, 2, 1, 3);
+ALT_DCONV(128, 64, 2, 1, 5);
 ALT_DCONV(128, 64, 4, 1, 3);
-ALT_DCONV(128, 64, 4, 1, 4);
-ALT_DCONV(256, 64, 8, 1, 2);
-ALT_DCONV(256, 64, 8, 1, 3);
-ALT_DCONV(256, 64, 8, 1, 4);
-ALT_DCONV(64, 64, 2, 2, 2);
-ALT_DCONV(64, 64, 2, 2, 3);
-ALT_DCONV(64, 64, 2, 2, 4);
-ALT_DCONV(128, 64, 4, 2, 2);
+ALT_DCONV(128, 64, 4, 1, 5);
 ALT_DCONV(128, 64, 4, 2, 3);
-ALT_DCONV(128, 64, 4, 2, 4);
-ALT_DCONV(64, 64, 2, 1, 2);
-ALT_DCONV(64, 64, 2, 1, 3);
-ALT_DCONV(64, 64, 2, 1, 4);
-ALT_DCONV(128, 128, 4, 2, 2);
-ALT_DCONV(128, 128, 4, 2, 3);
-ALT_DCONV(128, 128, 4, 2, 4);
+ALT_DCONV(128, 64, 4, 2, 5);
 
 }  // namespace
 }  // namespace alt

@@ -644,6 +644,7 @@ struct IgemmLaunch {
     // set instead of `launch` for the patch-resident direct convolution (dconv.h),
     // which splits K over channel slices and reduces them inside the same launch
     hipError_t (*launch_direct)(const DconvParams &p, size_t lds_bytes, hipStream_t st) = nullptr;
+    int wgm = 0, wgn = 0;     // wave grid of a direct kernel
 };
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE, int PF>

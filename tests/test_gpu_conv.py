@@ -114,7 +114,7 @@ def test_direct_kernel_exact_integers_every_variant(h, case):
     d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=1, pad=c["pad"],
                        in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
     variants = [(v, n) for v, n in applicable_variants(h, d0) if "direct" in n]
-    assert len(variants) >= 30, "direct kernels should cover this case"
+    assert len(variants) >= 20, "direct kernels should cover this case"
     assert any(not n.endswith("_k1") for _, n in variants) or c["C"] == 64
     for v, name in variants:
         got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, variant=v)
