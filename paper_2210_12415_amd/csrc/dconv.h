@@ -105,10 +105,11 @@ __device__ __forceinline__ void lds_wait(u32x4_t (&a)[NA], u32x4_t (&b)[NB])
     for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
 }
 
-// KR > 0: the filter is KR x KR with KR known at compile time (1 and 3 are
-// instantiated): the taps are unrolled and their patch addresses precomputed.
-// KR = 0: any filter size, taps walked at run time.
-template <int BM, int BN, int WGM, int WGN, int NS, int KR>
+// KR > 0: the filter is KR x KR and the slice has NCC 64-channel chunks, both known at
+// compile time: all K steps are unrolled into straight-line code (no loop-carried
+// register shuffling, every operand address precomputed).  KR = 0: any filter size and
+// slice width, taps and chunks walked at run time.
+template <int BM, int BN, int WGM, int WGN, int NS, int KR, int NCC>
 __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
@@ -185,7 +186,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         b_voff[i] = n < p.Nc ? (uint32_t)(n * rsc + split * p.Cs + c * 8) * 2u : kOutOfRange;
     }
     const uint32_t ldsB = lds0 + wave * 1024;
-    const int nsteps = p.R * p.S * p.ncc;
+    const int ncc = NCC > 0 ? NCC : p.ncc;                 // 64-channel chunks of the slice
+    const int nsteps = KR > 0 ? KR * KR * NCC : p.R * p.S * p.ncc;
     // load cursor: byte offset of K step `lstep` inside a weight row, (tap, chunk) walked chunk fastest
     int lstep = 0, lcc = 0, lstage = 0;
     uint32_t lsoff = 0;
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         lstage = lstage + 1 == NS ? 0 : lstage + 1;
         // next K step's offset inside a weight row; past the last step it stays where it is
         const bool more = lstep < nsteps;
-        const bool wrap = lcc + 1 == p.ncc;
+        const bool wrap = lcc + 1 == ncc;
         lsoff += more ? (uint32_t)(BK * 2) + (wrap ? (uint32_t)(p.C - p.Cs) * 2u : 0u) : 0u;
         lcc = more ? (wrap ? 0 : lcc + 1) : lcc;
     };
@@ -289,8 +291,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     // the last step the weight refills and look-ahead reads repeat the last step's
     // addresses (loaded, never used) instead of being skipped.
     if constexpr (KR > 0) {
-        // Patch rows and swizzles of every tap, computed while the patch is still in flight.
-        constexpr int RS = KR * KR;
+        // Patch rows and swizzles of every tap, the channel offsets of every k chunk and the
+        // weight operand addresses in every stage, computed while the patch is still in flight.
+        constexpr int RS = KR * KR, NSTEPS = RS * NCC;
         uint32_t t_row[RS][TM], t_swz[RS][TM];
 #pragma unroll
         for (int tap = 0; tap < RS; ++tap) {
@@ -299,32 +302,40 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #pragma unroll
             for (int i = 0; i < TM; ++i) { t_row[tap][i] = sa.a_row[i]; t_swz[tap][i] = sa.a_swz[i]; }
         }
+        uint32_t k_off[NCC][NKC];
+#pragma unroll
+        for (int cc = 0; cc < NCC; ++cc)
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) k_off[cc][kc] = khalf + cc * (BK * 2) + kc * 32;
+        uint32_t b_rds[NS][TN][NKC];
+#pragma unroll
+        for (int st = 0; st < NS; ++st)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int kc = 0; kc < NKC; ++kc) b_rds[st][j][kc] = b_rd[j][kc] + st * B_STAGE;
         wait_vmcnt<(NS - 2) * NLB>();                      // the patch and stage 0
         lds_barrier();
         ALT_STAMP(2);
-        uint32_t st_off = 0;                               // stage of the current step (byte offset)
-        uint32_t c_off = khalf;                            // channel offset of the current step inside a pixel
-        auto reads = [&](int kc, const uint32_t (&row)[TM], const uint32_t (&swz)[TM], uint32_t co, uint32_t so) {
+        // reads of k chunk g (counted over all steps); past the last step they repeat it (never used)
+        auto reads = [&](int g) {
+            const int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC;
+            const int tap = step / NCC, cc = step % NCC, st = step % NS;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], row[i] + ((co + kc * 32) ^ swz[i]));
+            for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], t_row[tap][i] + (k_off[cc][kc] ^ t_swz[tap][i]));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rd[j][kc] + so);
+            for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rds[st][j][kc]);
         };
 #pragma unroll
-        for (int kc = 0; kc < D; ++kc) reads(kc, t_row[0], t_swz[0], c_off, st_off);
-        // One K step under tap `tap`; its look-ahead reads run into the step at
-        // (nrow, nswz, n_c_off): the same tap's next channel chunk, or the next tap.
-        auto step_body = [&](const uint32_t (&row)[TM], const uint32_t (&swz)[TM], const uint32_t (&nrow)[TM],
-                             const uint32_t (&nswz)[TM], uint32_t n_c_off, bool more) {
+        for (int g = 0; g < D; ++g) reads(g);
+#pragma unroll
+        for (int step = 0; step < NSTEPS; ++step) {
             wait_vmcnt<(NS - 3) * NLB>();                  // stage step+1 has landed (this wave's share)
             asm volatile("s_barrier" ::: "memory");
             issue_b();
-            const uint32_t st1 = st_off + B_STAGE == NS * B_STAGE ? 0 : st_off + B_STAGE;
-            const uint32_t n_st_off = more ? st1 : st_off;
 #pragma unroll
             for (int kc = 0; kc < NKC; ++kc) {
-                if (kc + D < NKC) reads(kc + D, row, swz, c_off, st_off);
-                else reads(kc + D - NKC, nrow, nswz, n_c_off, n_st_off);
+                reads(step * NKC + kc + D);
                 lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -334,15 +345,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
                                                                             __builtin_bit_cast(bf16x8_t, bf[kc][j]),
                                                                             acc[i][j], 0, 0, 0);
             }
-            st_off = n_st_off;
-            c_off = n_c_off;
-        };
-#pragma unroll
-        for (int tap = 0; tap < RS; ++tap) {
-            for (int cc = 0; cc + 1 < p.ncc; ++cc)         // all but the tap's last chunk: the next step stays under this tap
-                step_body(t_row[tap], t_swz[tap], t_row[tap], t_swz[tap], c_off + BK * 2, true);
-            const int ntap = tap + 1 < RS ? tap + 1 : tap;       // past the last step: reads that are never used
-            step_body(t_row[tap], t_swz[tap], t_row[ntap], t_swz[ntap], tap + 1 < RS ? khalf : c_off, tap + 1 < RS);
         }
     } else {
         int r = 0, s = 0, cc = 0;
@@ -489,29 +491,43 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         const float4 b4 = *(const float4 *)(p.bias + n);
         bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
     }
+    constexpr int NIT = WTM / RPI;                         // wave-wide accesses per wave tile
+    f32x4_t vs[NIT];
+    if (p.splitk > 1) {
+        // Sum of the slices in slice order.  All loads of a slice are issued before any of
+        // them is consumed (one dependent load per access would cost a device-scope memory
+        // round trip each).  Whole-vector adds: element-wise float views of a loaded
+        // vector are miscompiled into a single-dword load by this toolchain.
 #pragma unroll
-    for (int it = 0; it < WTM / RPI; ++it) {
+        for (int it = 0; it < NIT; ++it) vs[it] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        for (int sl = 0; sl < p.splitk; ++sl) {
+            const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)((char *)p.partial + (size_t)sl * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
+            u32x4_t w4[NIT];
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int m = mrow0 + it * RPI;
+                const uint32_t off = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
+                w4[it] = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)off, 0, kAgentScope);
+            }
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) vs[it] += __builtin_bit_cast(f32x4_t, w4[it]);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
+            vs[it] = (f32x4_t){f.x, f.y, f.z, f.w};
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
         const int m = mrow0 + it * RPI;
         const bool ok = n_ok && m < p.M;
         const uint32_t idx = (uint32_t)(m * p.Nc + n);
         float v[4];
-        if (p.splitk > 1) {
-            // (summed as whole vectors: element-wise float views of the loaded vector are
-            // miscompiled into a single-dword load by this toolchain)
-            f32x4_t vs = {0.f, 0.f, 0.f, 0.f};
-            for (int sl = 0; sl < p.splitk; ++sl) {
-                const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
-                    (void *)((char *)p.partial + (size_t)sl * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
-                const u32x4_t w4 = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(ok ? idx * 4u : kOutOfRange), 0, kAgentScope);
-                vs += __builtin_bit_cast(f32x4_t, w4);
-            }
-            v[0] = vs[0]; v[1] = vs[1]; v[2] = vs[2]; v[3] = vs[3];
-        } else {
-            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
-            v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
-        }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = fmaxf(v[q] + bv[q], relu_floor);
+        for (int q = 0; q < 4; ++q) v[q] = fmaxf(vs[it][q] + bv[q], relu_floor);
         if (out_bf16) {
             const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
             const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
@@ -554,10 +570,10 @@ inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int Cs, int W
     return main_loop > staging ? main_loop : staging;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, int KR>
+template <int BM, int BN, int WGM, int WGN, int NS, int KR, int NCC>
 hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    auto kern = dconv_kernel<BM, BN, WGM, WGN, NS, KR>;
+    auto kern = dconv_kernel<BM, BN, WGM, WGN, NS, KR, NCC>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -568,13 +584,21 @@ hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
     return hipGetLastError();
 }
 
-// 1x1 and 3x3 filters have kernels with unrolled taps; other sizes walk the taps at run time.
+// 1x1 filters over up to 512 channels per slice and 3x3 filters over 64 or 128 have
+// fully unrolled kernels; everything else walks taps and chunks at run time.
 template <int BM, int BN, int WGM, int WGN, int NS>
 hipError_t dconv_launch(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    if (p.R == 3 && p.S == 3) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3>(p, lds, st);
-    if (p.R == 1 && p.S == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1>(p, lds, st);
-    return dconv_launch_kr<BM, BN, WGM, WGN, NS, 0>(p, lds, st);
+    if (p.R == 3 && p.S == 3) {
+        if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3, 1>(p, lds, st);
+        if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3, 2>(p, lds, st);
+    } else if (p.R == 1 && p.S == 1) {
+        if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 1>(p, lds, st);
+        if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 2>(p, lds, st);
+        if (p.ncc == 4) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 4>(p, lds, st);
+        if (p.ncc == 8) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 8>(p, lds, st);
+    }
+    return dconv_launch_kr<BM, BN, WGM, WGN, NS, 0, 0>(p, lds, st);
 }
 
 }  // namespace alt
