@@ -500,18 +500,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         // vector are miscompiled into a single-dword load by this toolchain.
 #pragma unroll
         for (int it = 0; it < NIT; ++it) vs[it] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        for (int sl = 0; sl < p.splitk; ++sl) {
-            const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)((char *)p.partial + (size_t)sl * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
-            u32x4_t w4[NIT];
+        // G slices (up to 32 loads) are in flight at a time: a device-scope load takes over a
+        // microsecond, so slices fetched one after the other would cost that much each
+        constexpr int G = NIT >= 32 ? 1 : 32 / NIT;
+        uint32_t offs[NIT];
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int m = mrow0 + it * RPI;
-                const uint32_t off = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-                w4[it] = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)off, 0, kAgentScope);
+        for (int it = 0; it < NIT; ++it) {
+            const int m = mrow0 + it * RPI;
+            offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
+        }
+        for (int sl0 = 0; sl0 < p.splitk; sl0 += G) {
+            u32x4_t w4[G][NIT];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                // slices past the last one read with a zero-sized descriptor: all zeros
+                const bool live = sl0 + g < p.splitk;
+                const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)((char *)p.partial + (size_t)(live ? sl0 + g : 0) * p.partial_bytes), 0,
+                    live ? (int)p.partial_bytes : 0, 0x00020000);
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) w4[g][it] = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kAgentScope);
             }
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) vs[it] += __builtin_bit_cast(f32x4_t, w4[it]);
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) vs[it] += __builtin_bit_cast(f32x4_t, w4[g][it]);
         }
     } else {
 #pragma unroll
@@ -544,8 +557,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     epi_clk[2] = __builtin_amdgcn_s_memtime();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ALT_STAMP(4);
-    if (threadIdx.x == 0 && p.partial && p.splitk == 1) {
-        uint64_t *out = (uint64_t *)p.partial + (size_t)blockIdx.x * 8;
+    if (threadIdx.x == 0 && p.partial) {
+        // (developer builds) timestamps behind the partial sums; with split-K only the reducing workgroups get here
+        uint64_t *out = (uint64_t *)((char *)p.partial + (p.splitk > 1 ? (size_t)p.splitk * p.partial_bytes : 0)) + (size_t)blockIdx.x * 8;
         for (int i = 0; i < 5; ++i) out[i] = stamps[i];
         out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
         out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
