@@ -260,6 +260,21 @@ class Handle:
         _ck(lib().alt_conv2d(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
                              _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
 
+    def conv2d_prepared(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        """The same call as conv2d with its arguments marshalled once: returns a
+        function of no arguments that launches it (for loops that repeat one call)."""
+        fn = lib().alt_conv2d
+        args = (self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(workspace),
+                ctypes.c_size_t(ws_bytes), _stream(stream))
+        keep = (d, x, w, y, bias, workspace)
+
+        def run():
+            status = fn(*args)
+            if status != 0:
+                _ck(status, self._h)
+            return keep is None
+        return run
+
     def conv2d_workspace_size(self, d):
         n = ctypes.c_size_t()
         _ck(lib().alt_conv2d_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)

@@ -48,6 +48,7 @@ alt_status_t alt_create(alt_handle_t *out)
 alt_status_t alt_destroy(alt_handle_t h)
 {
     if (!h) return ALT_INVALID_ARG;
+    alt::launch_memo_free(h);
     delete h;
     return ALT_OK;
 }

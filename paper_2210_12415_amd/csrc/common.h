@@ -104,6 +104,8 @@ struct alt_context {
     std::string arch;
     std::string last_error;
     std::map<std::string, alt::TuneEntry> cache;   // key -> tuned variant
+    unsigned cache_gen = 0;                        // bumped whenever `cache` changes
+    struct alt_launch_memo *memo = nullptr;        // ops.hip: recent descriptors reduced to launch parameters
 };
 
 namespace alt {
@@ -118,6 +120,8 @@ alt_status_t fail(alt_handle_t h, alt_status_t s, const char *fmt, ...);
     } while (0)
 
 inline size_t dtype_size(int dt) { return dt == ALT_BF16 ? 2 : 4; }
+
+void launch_memo_free(alt_handle_t h);       // ops.hip
 
 // Cache keys (tune.cpp)
 std::string conv_key(alt_handle_t h, const alt_conv_desc_t *d);

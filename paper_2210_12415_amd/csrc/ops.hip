@@ -359,6 +359,67 @@ alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out)
     return (out[2] < 1 || out[3] < 1) ? ALT_INVALID_ARG : ALT_OK;
 }
 
+// ---- launch memo -------------------------------------------------------------------
+// Turning a descriptor into launch parameters (three layouts bound, loaders analysed,
+// with variant = -1 every kernel estimated) costs far more host time than the launch
+// itself, and callers repeat the same few descriptors.  The handle remembers the last
+// descriptors byte for byte, with what else the result depends on: 16-byte alignment
+// of the buffers, the workspace size, the tune cache's generation.
+
+struct MemoEntry {
+    std::vector<unsigned char> desc;
+    unsigned sig, gen;
+    size_t ws_limit;
+    Problem pb;
+    int variant;
+};
+
+}  // extern "C"
+
+struct alt_launch_memo {
+    std::vector<MemoEntry> entries;
+    size_t next = 0;
+};
+
+namespace alt {
+void launch_memo_free(alt_handle_t h)
+{
+    delete h->memo;
+    h->memo = nullptr;
+}
+}  // namespace alt
+
+extern "C" {
+
+static unsigned align_sig(const void *a, const void *b, const void *c, const void *d)
+{
+    return (unsigned)(((uintptr_t)a & 15) | (((uintptr_t)b & 15) << 4) | (((uintptr_t)c & 15) << 8) |
+                      (((uintptr_t)d & 15) << 12) | ((c ? 1u : 0u) << 16));
+}
+
+static MemoEntry *memo_find(alt_handle_t h, const void *desc, size_t bytes, unsigned sig, size_t ws_limit)
+{
+    if (!h->memo) return nullptr;
+    for (MemoEntry &e : h->memo->entries)
+        if (e.sig == sig && e.gen == h->cache_gen && e.ws_limit == ws_limit && e.desc.size() == bytes &&
+            std::memcmp(e.desc.data(), desc, bytes) == 0)
+            return &e;
+    return nullptr;
+}
+
+static void memo_store(alt_handle_t h, const void *desc, size_t bytes, unsigned sig, size_t ws_limit, const Problem &pb,
+                       int variant)
+{
+    constexpr size_t kMemoEntries = 32;
+    if (!h->memo) h->memo = new alt_launch_memo();
+    MemoEntry e;
+    e.desc.assign((const unsigned char *)desc, (const unsigned char *)desc + bytes);
+    e.sig = sig; e.gen = h->cache_gen; e.ws_limit = ws_limit; e.pb = pb; e.variant = variant;
+    auto &v = h->memo->entries;
+    if (v.size() < kMemoEntries) v.push_back(std::move(e));
+    else { v[h->memo->next] = std::move(e); h->memo->next = (h->memo->next + 1) % kMemoEntries; }
+}
+
 // variant = -1: the cached tuned variant if it applies and its split-K partial
 // sums fit the workspace the caller brought, else the best-estimate variant
 // that fits.
@@ -384,11 +445,18 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
     if (!h) return ALT_INVALID_ARG;
     if (!d || !x || !w || !y) return fail(h, ALT_INVALID_ARG, "alt_conv2d: null argument");
     if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv2d: bias flag without bias");
+    const size_t ws_limit = workspace ? ws_bytes : 0;
+    const unsigned sig = align_sig(x, w, bias, y);
+    if (MemoEntry *m = memo_find(h, d, sizeof *d, sig, ws_limit)) {
+        m->pb.p.x = x; m->pb.p.w = w; m->pb.p.bias = bias; m->pb.p.y = y;
+        return igemm_run(h, m->pb, m->variant, workspace, ws_bytes, (hipStream_t)stream);
+    }
     Problem pb;
     alt_status_t s = conv_problem(h, d, x, w, bias, y, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, conv_key(h, d), workspace ? ws_bytes : 0);
+    int v = pick_variant(h, pb, d->variant, d->variant >= 0 ? std::string() : conv_key(h, d), ws_limit);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_conv2d: no kernel variant applies");
+    memo_store(h, d, sizeof *d, sig, ws_limit, pb, v);
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
 }
 
@@ -451,11 +519,18 @@ alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, c
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !A || !B || !C) return fail(h, ALT_INVALID_ARG, "alt_gemm: null argument");
+    const size_t ws_limit = workspace ? ws_bytes : 0;
+    const unsigned sig = align_sig(A, B, nullptr, C);
+    if (MemoEntry *m = memo_find(h, d, sizeof *d, sig, ws_limit)) {
+        m->pb.p.x = A; m->pb.p.w = B; m->pb.p.y = C;
+        return igemm_run(h, m->pb, m->variant, workspace, ws_bytes, (hipStream_t)stream);
+    }
     Problem pb;
     alt_status_t s = gemm_problem(h, d, A, B, C, &pb);
     if (s != ALT_OK) return s;
-    int v = pick_variant(h, pb, d->variant, gemm_key(h, d), workspace ? ws_bytes : 0);
+    int v = pick_variant(h, pb, d->variant, d->variant >= 0 ? std::string() : gemm_key(h, d), ws_limit);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_gemm: no kernel variant applies");
+    memo_store(h, d, sizeof *d, sig, ws_limit, pb, v);
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
 }
 

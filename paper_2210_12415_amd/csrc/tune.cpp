@@ -271,6 +271,7 @@ alt_status_t alt_tune_conv2d_variants(alt_handle_t h, alt_conv_desc_t *d, const 
     if (best_v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
     d->variant = -1;
     h->cache[conv_key(h, d)] = TuneEntry{best_v, *best_us};
+    ++h->cache_gen;
     d->variant = best_v;
     return ALT_OK;
 }
@@ -382,6 +383,7 @@ alt_status_t alt_tune_conv2d(alt_handle_t h, const alt_conv_desc_t *shape, const
         k.variant = -1;
         h->cache[conv_key(h, &k)] = TuneEntry{descs[ci].variant, rep.layout_best_us[ci]};
     }
+    ++h->cache_gen;
     *best_out = descs[best_c];
     if (report) *report = rep;
     return ALT_OK;
@@ -478,6 +480,7 @@ alt_status_t alt_tune_gemm(alt_handle_t h, const alt_gemm_desc_t *shape, const a
             alt_gemm_desc_t k = d;
             k.variant = -1;
             h->cache[gemm_key(h, &k)] = TuneEntry{bv, best};
+            ++h->cache_gen;
         }
     }
     if (best_c < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies under any layout");
@@ -625,6 +628,7 @@ alt_status_t alt_tune_chain(alt_handle_t h, const alt_conv_desc_t *ops, int nops
                 op_cost[((size_t)i * nl + a) * nl + b] = us;
                 op_var[((size_t)i * nl + a) * nl + b] = v;
                 h->cache[conv_key(h, &d)] = TuneEntry{v, us};
+                ++h->cache_gen;
             }
         }
     }
@@ -683,6 +687,7 @@ alt_status_t alt_cache_load(alt_handle_t h, const char *path)
         if (it == by_name.end()) continue;             // a variant this build does not have
         h->cache[line.substr(0, t1)] = TuneEntry{it->second, (float)std::atof(line.c_str() + t2 + 1)};
     }
+    ++h->cache_gen;
     return ALT_OK;
 }
 
@@ -690,6 +695,7 @@ alt_status_t alt_cache_clear(alt_handle_t h)
 {
     if (!h) return ALT_INVALID_ARG;
     h->cache.clear();
+    ++h->cache_gen;
     return ALT_OK;
 }
 

@@ -219,6 +219,19 @@ def test_resnet_layers_sampled(h, layer, batch):
         err = float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
         assert err <= TOL[alt.BF16], (xl, err)
         assert err <= 1e-4, (xl, err)          # fp32 accumulation of exact bf16 products is far tighter
+        if xl == "NHWC":
+            # bf16 output (what the benchmark's headline step writes): the fp32 sum rounded once
+            d16 = alt.conv_desc(batch, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
+                                out_dtype=alt.BF16, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+            y16 = torch.empty(n_out, dtype=torch.int16, device="cuda")
+            ws_bytes = h.conv2d_workspace_size(d16)
+            ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
+            h.conv2d(d16, xd, wd, y16, workspace=ws, ws_bytes=ws_bytes)
+            y16log = torch.empty_like(y16)
+            h.layout_transform(alt.BF16, oshape, "NCHW->" + yl, y16, "NCHW->NCHW", y16log)
+            got16 = bf16_bits_to_f32(host(y16log, np.uint16)[flat]).astype(np.float64)
+            err16 = float(np.max(np.abs(got16 - ref) / (np.abs(ref) + rms)))
+            assert err16 <= 2.0 ** -8, (xl, err16)       # half an ulp of bf16 on top of the fp32 sum
 
 
 def test_conv_errors(h):
