@@ -1,5 +1,5 @@
 // Handle lifecycle, error reporting.
-#include "common.h"
+#include "ops.h"
 
 namespace alt {
 
@@ -41,6 +41,7 @@ alt_status_t alt_create(alt_handle_t *out)
         (void)hipGetLastError();
     }
     if (!c->has_gpu) c->arch = "none";
+    else (void)alt::dconv_round_robin_xcds();      // probes the device once
     *out = c;
     return ALT_OK;
 }

@@ -63,12 +63,15 @@ struct DconvParams {
     int32_t log2_cpp;             // log2(Cs / 8): 16-byte chunks per patch pixel
     int32_t swz_shift, swz_mask;  // patch swizzle: chunk position = chunk ^ ((pixel >> swz_shift) & swz_mask)
     int32_t ncc;                  // Cs / 64: K steps per tap
+    int32_t xcd_local;            // split-K: the slices of a tile run on one XCD and meet in its L2
+    Div32 d_sk;                   // division by splitk
 };
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kDconvOutBf16 = 4;
 constexpr int kAgentScope = 16;          // cache-policy operand of buffer loads/stores: sc1 = device (agent) scope
+constexpr int kBypassL1 = 1;             // sc0: served by the XCD's L2, never by the CU's own L1
 constexpr int kDconvMaxTiles = 4096;     // output tiles a split-K launch may have (one counter each)
 constexpr int kDconvSlots = 8;           // counter sets, handed to launches round-robin
 
@@ -135,13 +138,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // workgroup -> (m tile, n tile, channel slice); consecutive logical ids share an XCD
-    const int ntot = p.tiles_m * p.tiles_n * p.splitk;
-    const int logical = igemm_logical_tile(ntot);
-    const int rest = (int)div32((uint32_t)logical, p.d_tm);
-    const int mt = logical - rest * p.tiles_m;
-    const int split = (int)div32((uint32_t)rest, p.d_tn);
-    const int nt = rest - split * p.tiles_n;
+    // workgroup -> (m tile, n tile, channel slice)
+    int mt, nt, split;
+    if (p.xcd_local) {
+        // Workgroup ids are dealt round-robin to the 8 XCDs, so ids that agree modulo 8 share an
+        // XCD and its L2: the slices of one tile are given such ids (the host has checked the
+        // dealing order on this device), tiles go round the XCDs, the grid is padded to whole rounds.
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int tl = (int)div32((uint32_t)slot, p.d_sk);
+        split = slot - tl * p.splitk;
+        const int tile_id = tl * 8 + xcd;
+        if (tile_id >= p.tiles_m * p.tiles_n) return;
+        nt = (int)div32((uint32_t)tile_id, p.d_tm);
+        mt = tile_id - nt * p.tiles_m;
+    } else {
+        // consecutive logical ids share an XCD
+        const int ntot = p.tiles_m * p.tiles_n * p.splitk;
+        const int logical = igemm_logical_tile(ntot);
+        const int rest = (int)div32((uint32_t)logical, p.d_tm);
+        mt = logical - rest * p.tiles_m;
+        split = (int)div32((uint32_t)rest, p.d_tn);
+        nt = rest - split * p.tiles_n;
+    }
     const int m0 = mt * BM, n0 = nt * BN;
 
     const i32x4_t x_rsrc = make_rsrc(p.x, p.x_bytes);
@@ -464,23 +482,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
             const u32x4_t v = {__builtin_bit_cast(uint32_t, f.x), __builtin_bit_cast(uint32_t, f.y),
                                __builtin_bit_cast(uint32_t, f.z), __builtin_bit_cast(uint32_t, f.w)};
             const uint32_t off = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-            __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, kAgentScope);
+            if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, kAgentScope);
         }
-        // The partial sums were stored with device (agent) scope, i.e. written through to
-        // memory all XCDs share; once the stores are acknowledged they are visible to
-        // device-scope loads anywhere.  That is the release half; a full device-scope
-        // fence would write back the whole L2 and costs tens of microseconds here.
+        // Release half.  Across XCDs: the partial sums were stored with device (agent) scope,
+        // i.e. written through to memory all XCDs share; once the stores are acknowledged
+        // they are visible to device-scope loads anywhere (a full device-scope fence would
+        // write back the whole L2 and costs tens of microseconds here).  Within one XCD:
+        // plain stores are acknowledged by the XCD's L2, which every CU of the XCD reads.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem_u4 + NW * (WTM * SP);
         if (t == 0) {
-            const uint32_t old = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (the XCD-local counter is an atomic executed in that XCD's L2: no device-scope bits)
+            const uint32_t old = p.xcd_local
+                ? __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
+                : __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             *flag = old == (uint32_t)(p.splitk - 1);
-            if (*flag) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            if (*flag) {                           // ready for the next launch
+                if (p.xcd_local) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                else __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         __syncthreads();
         if (*flag == 0) return;
-        // acquire half: the loads below have device scope and so do not hit stale cache lines
+        // acquire half: the loads below have device scope (or bypass the CU's L1) and so do not hit stale cache lines
     }
 
     const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)p.y_bytes, 0x00020000);
@@ -519,7 +545,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
                     (void *)((char *)p.partial + (size_t)(live ? sl0 + g : 0) * p.partial_bytes), 0,
                     live ? (int)p.partial_bytes : 0, 0x00020000);
 #pragma unroll
-                for (int it = 0; it < NIT; ++it) w4[g][it] = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kAgentScope);
+                for (int it = 0; it < NIT; ++it)
+                    w4[g][it] = p.xcd_local ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kBypassL1)
+                                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kAgentScope);
             }
 #pragma unroll
             for (int g = 0; g < G; ++g)
@@ -594,7 +622,9 @@ hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(p.tiles_m * p.tiles_n * p.splitk)), dim3(64 * WGM * WGN), lds, st, p);
+    const int tiles = p.tiles_m * p.tiles_n;
+    const unsigned grid = p.xcd_local ? (unsigned)((tiles + 7) / 8 * 8 * p.splitk) : (unsigned)(tiles * p.splitk);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WGM * WGN), lds, st, p);
     return hipGetLastError();
 }
 

@@ -18,6 +18,13 @@ __device__ __align__(256) uint32_t g_dconv_counters[kDconvSlots * kDconvMaxTiles
 
 constexpr int kMaxDevices = 16;
 uint32_t *g_counter_ptr[kMaxDevices];
+int g_round_robin[kMaxDevices];      // 0 = not probed, 1 = workgroup ids go round the XCDs in order, -1 = they do not
+
+// Each workgroup reports the XCD it runs on.
+__global__ void xcd_probe_kernel(uint32_t *out)
+{
+    if (threadIdx.x == 0) out[blockIdx.x] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20)) & 0xf;   // XCC_ID
+}
 std::atomic<unsigned> g_next_slot{0};
 
 bool dense(const Dim2 &d, int64_t extent, int64_t stride)
@@ -42,6 +49,35 @@ hipError_t dconv_counters(uint32_t **out)
     }
     *out = g_counter_ptr[dev];
     return hipSuccess;
+}
+
+// Whether workgroup i of a launch runs on the same XCD as every workgroup j with
+// j = i (mod 8), which lets the slices of a split-K tile meet in one L2.  Probed once per
+// device with a small launch whose workgroups report their XCD, using the counter array
+// as scratch (it is zeroed again); synchronises, so it runs when a handle is created.
+bool dconv_round_robin_xcds()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (g_round_robin[dev] != 0) return g_round_robin[dev] > 0;
+    g_round_robin[dev] = -1;
+    if (const char *e = std::getenv("ALT_SPLITK_SCOPE"))
+        if (std::strcmp(e, "device") == 0) return false;
+    uint32_t *buf = nullptr;
+    if (dconv_counters(&buf) != hipSuccess) return false;
+    constexpr int kBlocks = 1024;
+    static_assert(kBlocks <= kDconvSlots * kDconvMaxTiles, "probe scratch");
+    uint32_t host[kBlocks];
+    bool ok = true;
+    for (int rep = 0; rep < 3 && ok; ++rep) {
+        hipLaunchKernelGGL(xcd_probe_kernel, dim3(kBlocks), dim3(64), 0, 0, buf);
+        if (hipMemcpy(host, buf, sizeof host, hipMemcpyDeviceToHost) != hipSuccess) { ok = false; break; }
+        for (int b = 8; b < kBlocks; ++b) ok = ok && host[b] == host[b & 7];
+    }
+    (void)hipMemset(buf, 0, sizeof host);
+    (void)hipDeviceSynchronize();
+    if (ok) g_round_robin[dev] = 1;
+    return ok;
 }
 
 // Fills the launch parameters of direct kernel `k` for `pb` split into `splitk`
@@ -98,6 +134,12 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     d.swz_shift = Cs == 64 ? 1 : 0;
     d.swz_mask = Cs == 64 ? 7 : 15;
     d.ncc = (int32_t)(Cs / 64);
+    d.d_sk = make_div32((uint32_t)splitk);
+    {
+        int dev = 0;
+        d.xcd_local = splitk > 1 && hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices &&
+                      g_round_robin[dev] > 0 && (int64_t)(tiles_m * tiles_n + 7) / 8 * 8 * splitk <= 0x7fffffff;
+    }
     *out = d;
     *lds_bytes = lds;
     return true;
