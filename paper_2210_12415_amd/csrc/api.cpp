@@ -50,6 +50,7 @@ alt_status_t alt_destroy(alt_handle_t h)
 {
     if (!h) return ALT_INVALID_ARG;
     alt::launch_memo_free(h);
+    alt::transform_memo_free(h);
     delete h;
     return ALT_OK;
 }

@@ -106,6 +106,7 @@ struct alt_context {
     std::map<std::string, alt::TuneEntry> cache;   // key -> tuned variant
     unsigned cache_gen = 0;                        // bumped whenever `cache` changes
     struct alt_launch_memo *memo = nullptr;        // ops.hip: recent descriptors reduced to launch parameters
+    struct alt_transform_memo *tmemo = nullptr;    // transform.hip: recent conversions reduced to launch plans
 };
 
 namespace alt {
@@ -122,6 +123,7 @@ alt_status_t fail(alt_handle_t h, alt_status_t s, const char *fmt, ...);
 inline size_t dtype_size(int dt) { return dt == ALT_BF16 ? 2 : 4; }
 
 void launch_memo_free(alt_handle_t h);       // ops.hip
+void transform_memo_free(alt_handle_t h);    // transform.hip
 
 // Cache keys (tune.cpp)
 std::string conv_key(alt_handle_t h, const alt_conv_desc_t *d);

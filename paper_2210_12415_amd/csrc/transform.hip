@@ -44,22 +44,32 @@ template <> struct Word<4> { using type = uint32_t; };
 template <> struct Word<8> { using type = uint2; };
 template <> struct Word<16> { using type = uint4; };
 
-// Block -> (outer indices, tile origin).  Uniform per block.
+// Block -> (outer indices, tile origin).  Uniform per block.  The block count and
+// every extent fit 32 bits (checked by the host): 32-bit divisions, which cost a
+// fraction of 64-bit ones, and these few dozen instructions are on every block's
+// critical path before its first load.
 __device__ inline void locate_tile(const PermuteParams &p, int64_t &src_base, int64_t &dst_base,
                                    int64_t &a0, int64_t &b0)
 {
-    int64_t t = blockIdx.x;
-    int64_t ta = t % p.tiles_a; t /= p.tiles_a;
-    int64_t tb = t % p.tiles_b; t /= p.tiles_b;
-    a0 = ta * p.TA;
-    b0 = tb * p.TB;
+    uint32_t t = blockIdx.x;
+    const uint32_t tiles_a = (uint32_t)p.tiles_a, tiles_b = (uint32_t)p.tiles_b;
+    uint32_t q = t / tiles_a;
+    const uint32_t ta = t - q * tiles_a;
+    t = q;
+    q = t / tiles_b;
+    const uint32_t tb = t - q * tiles_b;
+    t = q;
+    a0 = (int64_t)ta * p.TA;
+    b0 = (int64_t)tb * p.TB;
     src_base = a0 * p.ss_a + b0 * p.ss_b;
     dst_base = a0 * p.ds_a + b0 * p.ds_b;
     for (int d = p.n_outer - 1; d >= 0; --d) {
-        int64_t i = t % p.outer_ext[d];
-        t /= p.outer_ext[d];
-        src_base += i * p.outer_ss[d];
-        dst_base += i * p.outer_ds[d];
+        const uint32_t e = (uint32_t)p.outer_ext[d];
+        q = t / e;
+        const uint32_t i = t - q * e;
+        t = q;
+        src_base += (int64_t)i * p.outer_ss[d];
+        dst_base += (int64_t)i * p.outer_ds[d];
     }
 }
 
@@ -228,28 +238,36 @@ void launch_transpose(int lb, int sb, const PermuteParams &p, dim3 grid, size_t 
     else launch_transpose_s<ELSZ, ELSZ>(sb, p, grid, lds, st);
 }
 
-}  // namespace
 
-// Shared with conv.hip (weight packing) and the tuner.
-alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src,
-                             const BoundLayout &ld, void *dst, hipStream_t st)
+// What one conversion launches: the kernel, its parameters and its grid.  Depends on the
+// two bound layouts, the element size and the 16-byte alignment of the two buffers only.
+struct TransformPlan {
+    enum Kind { COPY, GENERAL, ROWS, TRANSPOSE } kind;
+    int elsz, vb, lb, sb;
+    unsigned blocks;
+    size_t lds, bytes;
+    PermuteParams p;
+    GeneralParams gp;
+};
+
+alt_status_t plan_transform(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src, const BoundLayout &ld,
+                            void *dst, TransformPlan *out)
 {
-    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    TransformPlan &t = *out;
+    t.elsz = elsz;
     const int64_t numel = ls.numel;
+    t.bytes = (size_t)numel * elsz;
     std::vector<Piece> pcs;
     bool permutable = ls.separable && ld.separable && refine(ls, ld, &pcs) && (int)pcs.size() <= kMaxOuter + 2;
     if (permutable && numel >= ((int64_t)1 << 40)) permutable = false;
     if (!permutable) {
-        GeneralParams gp;
-        gp.src = src; gp.dst = dst; gp.ls = ls; gp.ld = ld;
-        int64_t blocks = std::min<int64_t>((numel + kThreads - 1) / kThreads, 256 * 32);
-        if (elsz == 2) hipLaunchKernelGGL(permute_general_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), 0, st, gp);
-        else hipLaunchKernelGGL(permute_general_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), 0, st, gp);
-        ALT_CHECK_HIP(h, hipGetLastError());
+        t.kind = TransformPlan::GENERAL;
+        t.gp.src = src; t.gp.dst = dst; t.gp.ls = ls; t.gp.ld = ld;
+        t.blocks = (unsigned)std::min<int64_t>((numel + kThreads - 1) / kThreads, 256 * 32);
         return ALT_OK;
     }
     if (pcs.size() <= 1) {                       // same placement: plain copy
-        ALT_CHECK_HIP(h, hipMemcpyAsync(dst, src, (size_t)numel * elsz, hipMemcpyDeviceToDevice, st));
+        t.kind = TransformPlan::COPY;
         return ALT_OK;
     }
     // pieces are in destination order: the last one has ds = 1
@@ -257,7 +275,7 @@ alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, co
     for (int j = 0; j < (int)pcs.size(); ++j) if (pcs[j].ss == 1) ia = j;
     if (ia < 0 || pcs[ib].ds != 1) return fail(h, ALT_UNSUPPORTED, "internal: no unit-stride piece");
 
-    PermuteParams p;
+    PermuteParams &p = t.p;
     std::memset(&p, 0, sizeof p);
     p.src = src; p.dst = dst;
     const bool rows = ia == ib;
@@ -278,9 +296,11 @@ alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, co
         if (j != (rows ? ia : ib)) dstr.push_back(pcs[j].ds);
     }
     constexpr int64_t kTileElems = 4096;
+    int64_t blocks = 0;
     if (rows) {
-        int vb = std::min(pick_vector_bytes(elsz, A.ext, sstr, src), pick_vector_bytes(elsz, A.ext, dstr, dst));
-        int vl = vb / elsz;
+        t.kind = TransformPlan::ROWS;
+        t.vb = std::min(pick_vector_bytes(elsz, A.ext, sstr, src), pick_vector_bytes(elsz, A.ext, dstr, dst));
+        int vl = t.vb / elsz;
         int64_t TA = std::min<int64_t>(A.ext, kTileElems);
         TA -= TA % vl;
         if (TA == 0) TA = vl;
@@ -288,15 +308,13 @@ alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, co
         p.TA = (int)TA; p.TB = (int)TB;
         p.tiles_a = (A.ext + TA - 1) / TA;
         p.tiles_b = (B.ext + TB - 1) / TB;
-        int64_t blocks = p.tiles_a * p.tiles_b;
-        for (int d = 0; d < p.n_outer; ++d) blocks *= p.outer_ext[d];
-        if (blocks > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "tensor too large for one launch");
-        if (elsz == 2) launch_rows<2>(vb, p, dim3((unsigned)blocks), st);
-        else launch_rows<4>(vb, p, dim3((unsigned)blocks), st);
+        blocks = p.tiles_a * p.tiles_b;
+        t.lds = 0;
     } else {
-        int lb = pick_vector_bytes(elsz, A.ext, sstr, src);
-        int sb = pick_vector_bytes(elsz, B.ext, dstr, dst);
-        int vl = lb / elsz, vs = sb / elsz;
+        t.kind = TransformPlan::TRANSPOSE;
+        t.lb = pick_vector_bytes(elsz, A.ext, sstr, src);
+        t.sb = pick_vector_bytes(elsz, B.ext, dstr, dst);
+        int vl = t.lb / elsz, vs = t.sb / elsz;
         int64_t TA = std::min<int64_t>(A.ext, 64), TB = std::min<int64_t>(B.ext, 64);
         if (TA < 64) TB = std::min<int64_t>(B.ext, kTileElems / TA);
         else if (TB < 64) TA = std::min<int64_t>(A.ext, kTileElems / TB);
@@ -306,17 +324,77 @@ alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, co
         p.LD = (int)TA | 1;                      // odd row pitch: conflict-free column reads
         p.tiles_a = (A.ext + TA - 1) / TA;
         p.tiles_b = (B.ext + TB - 1) / TB;
-        int64_t blocks = p.tiles_a * p.tiles_b;
-        for (int d = 0; d < p.n_outer; ++d) blocks *= p.outer_ext[d];
-        if (blocks > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "tensor too large for one launch");
-        size_t lds = (size_t)p.LD * p.TB * elsz;
-        if (elsz == 2) launch_transpose<2>(lb, sb, p, dim3((unsigned)blocks), lds, st);
-        else launch_transpose<4>(lb, sb, p, dim3((unsigned)blocks), lds, st);
+        blocks = p.tiles_a * p.tiles_b;
+        t.lds = (size_t)p.LD * p.TB * elsz;
+    }
+    for (int d = 0; d < p.n_outer; ++d) blocks *= p.outer_ext[d];
+    if (blocks > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "tensor too large for one launch");
+    t.blocks = (unsigned)blocks;
+    return ALT_OK;
+}
+
+alt_status_t run_transform(alt_handle_t h, TransformPlan &t, const void *src, void *dst, hipStream_t st)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    switch (t.kind) {
+        case TransformPlan::COPY:
+            ALT_CHECK_HIP(h, hipMemcpyAsync(dst, src, t.bytes, hipMemcpyDeviceToDevice, st));
+            return ALT_OK;
+        case TransformPlan::GENERAL:
+            t.gp.src = src; t.gp.dst = dst;
+            if (t.elsz == 2) hipLaunchKernelGGL(permute_general_kernel<2>, dim3(t.blocks), dim3(kThreads), 0, st, t.gp);
+            else hipLaunchKernelGGL(permute_general_kernel<4>, dim3(t.blocks), dim3(kThreads), 0, st, t.gp);
+            break;
+        case TransformPlan::ROWS:
+            t.p.src = src; t.p.dst = dst;
+            if (t.elsz == 2) launch_rows<2>(t.vb, t.p, dim3(t.blocks), st);
+            else launch_rows<4>(t.vb, t.p, dim3(t.blocks), st);
+            break;
+        case TransformPlan::TRANSPOSE:
+            t.p.src = src; t.p.dst = dst;
+            if (t.elsz == 2) launch_transpose<2>(t.lb, t.sb, t.p, dim3(t.blocks), t.lds, st);
+            else launch_transpose<4>(t.lb, t.sb, t.p, dim3(t.blocks), t.lds, st);
+            break;
     }
     ALT_CHECK_HIP(h, hipGetLastError());
     return ALT_OK;
 }
 
+}  // namespace
+
+// Shared with ops.hip (weight packing) and the tuner.
+alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src,
+                             const BoundLayout &ld, void *dst, hipStream_t st)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    TransformPlan t;
+    alt_status_t s = plan_transform(h, elsz, ls, src, ld, dst, &t);
+    if (s != ALT_OK) return s;
+    return run_transform(h, t, src, dst, st);
+}
+
+}  // namespace alt
+
+// Recent alt_layout_transform calls reduced to launch plans (the planning costs several
+// microseconds of host time, more than most of these conversions take on the device).
+struct alt_transform_memo {
+    struct Entry {
+        int dtype, ndim;
+        unsigned sig;
+        int64_t shape[ALT_MAX_RANK];
+        alt_layout_t src, dst;
+        alt::TransformPlan plan;
+    };
+    std::vector<Entry> entries;
+    size_t next = 0;
+};
+
+namespace alt {
+void transform_memo_free(alt_handle_t h)
+{
+    delete h->tmemo;
+    h->tmemo = nullptr;
+}
 }  // namespace alt
 
 using namespace alt;
@@ -330,6 +408,21 @@ extern "C" alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, 
         return fail(h, ALT_INVALID_ARG, "alt_layout_transform: null argument");
     if (dtype != ALT_F32 && dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_layout_transform: bad dtype");
     if (src == dst) return fail(h, ALT_INVALID_ARG, "alt_layout_transform: src and dst must not overlap");
+    if (ndim < 1 || ndim > ALT_MAX_RANK) return fail(h, ALT_INVALID_ARG, "alt_layout_transform: bad rank");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const unsigned sig = (unsigned)(((uintptr_t)src & 15) | (((uintptr_t)dst & 15) << 4));
+    if (h->tmemo) {
+        for (auto &e : h->tmemo->entries)
+            if (e.dtype == (int)dtype && e.ndim == ndim && e.sig == sig &&
+                std::memcmp(e.shape, shape, sizeof(int64_t) * ndim) == 0 &&
+                std::memcmp(&e.src, src_layout, sizeof(alt_layout_t)) == 0 &&
+                std::memcmp(&e.dst, dst_layout, sizeof(alt_layout_t)) == 0) {
+                const char *a = (const char *)src, *b = (const char *)dst;
+                if ((a < b + e.plan.bytes) && (b < a + e.plan.bytes))
+                    return fail(h, ALT_INVALID_ARG, "alt_layout_transform: src and dst must not overlap");
+                return run_transform(h, e.plan, src, dst, (hipStream_t)stream);
+            }
+    }
     BoundLayout ls, ld;
     std::string err;
     alt_status_t s = bind_layout(src_layout, ndim, shape, &ls, &err);
@@ -340,5 +433,19 @@ extern "C" alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, 
     const char *a = (const char *)src, *b = (const char *)dst;
     if ((a < b + bytes) && (b < a + bytes))
         return fail(h, ALT_INVALID_ARG, "alt_layout_transform: src and dst must not overlap");
-    return transform_bound(h, (int)dtype_size(dtype), ls, src, ld, dst, (hipStream_t)stream);
+    alt_transform_memo::Entry e;
+    e.dtype = (int)dtype; e.ndim = ndim; e.sig = sig;
+    std::memset(e.shape, 0, sizeof e.shape);
+    std::memcpy(e.shape, shape, sizeof(int64_t) * ndim);
+    e.src = *src_layout; e.dst = *dst_layout;
+    s = plan_transform(h, (int)dtype_size(dtype), ls, src, ld, dst, &e.plan);
+    if (s != ALT_OK) return s;
+    s = run_transform(h, e.plan, src, dst, (hipStream_t)stream);
+    if (s != ALT_OK) return s;
+    constexpr size_t kEntries = 32;
+    if (!h->tmemo) h->tmemo = new alt_transform_memo();
+    auto &v = h->tmemo->entries;
+    if (v.size() < kEntries) v.push_back(e);
+    else { v[h->tmemo->next] = e; h->tmemo->next = (h->tmemo->next + 1) % kEntries; }
+    return ALT_OK;
 }
