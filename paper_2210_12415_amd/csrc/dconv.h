@@ -62,7 +62,8 @@ struct DconvParams {
     Div32 d_hw, d_w, d_tm, d_tn;  // divisions by H*W, W, tiles_m, tiles_n
     int32_t log2_cpp;             // log2(Cs / 8): 16-byte chunks per patch pixel
     int32_t swz_shift, swz_mask;  // patch swizzle: chunk position = chunk ^ ((pixel >> swz_shift) & swz_mask)
-    int32_t ncc;                  // Cs / 64: K steps per tap
+    int32_t ncc;                  // K steps per tap: (Cs / K groups) / channels per K step
+    int32_t bk;                   // channels per K step: 64, or 32 for narrow K groups
     int32_t xcd_local;            // split-K: the slices of a tile run on one XCD and meet in its L2
     Div32 d_sk;                   // division by splitk
 };
@@ -108,35 +109,46 @@ __device__ __forceinline__ void lds_wait(u32x4_t (&a)[NA], u32x4_t (&b)[NB])
     for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
 }
 
-// KR > 0: the filter is KR x KR and the slice has NCC 64-channel chunks, both known at
+// The workgroup has KW groups of WGM x WGN waves.  Each group computes the whole BM x BN
+// tile over its own 1/KW of the slice's channels (all taps), with a weight ring of its
+// own; the groups' tiles are summed through LDS at the end.  This puts two waves on every
+// SIMD of a CU even when the tile only has room for a few large wave tiles, which is
+// what hides the operand-read latency (large wave tiles keep the LDS traffic per MFMA low).
+//
+// KR > 0: the filter is KR x KR and a group's channels are NCC chunks of BK, both known at
 // compile time: all K steps are unrolled into straight-line code (no loop-carried
 // register shuffling, every operand address precomputed).  KR = 0: any filter size and
 // slice width, taps and chunks walked at run time.
-template <int BM, int BN, int WGM, int WGN, int NS, int KR, int NCC>
-__global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams p)
+template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK, int KR, int NCC>
+__global__ __launch_bounds__(64 * WGM * WGN * KW) void dconv_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
     uint64_t stamps[5] = {0, 0, 0, 0, 0};
 #endif
     ALT_STAMP(0);
-    constexpr int NW = WGM * WGN;
+    constexpr int NWG = WGM * WGN, NW = NWG * KW;          // waves per group, per workgroup
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int BK = 64, NKC = BK / 16;
-    constexpr int B_STAGE = BN * BK * 2;                   // bytes of one weight stage: [BN][8 chunks of 16 B]
-    constexpr int NLB = B_STAGE / 1024 / NW;               // wave-loads per wave per stage
+    constexpr int NKC = BK / 16;
+    constexpr int CPR = BK / 8;                            // 16-byte chunks per weight row of a stage
+    constexpr int RP = 256 / (BK * 2);                     // weight rows per 256 bytes of LDS
+    constexpr int B_STAGE = BN * BK * 2;                   // bytes of one weight stage: [BN][CPR chunks of 16 B]
+    constexpr int B_RING = NS * B_STAGE;                   // one group's stages
+    constexpr int NLB = B_STAGE / 1024 / NWG;              // wave-loads per wave per stage
+    static_assert(BK == 64 || BK == 32, "K step");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile");
-    static_assert(B_STAGE % (1024 * NW) == 0 && NLB >= 1, "a weight stage is a whole number of wave-loads per wave");
+    static_assert(B_STAGE % (1024 * NWG) == 0 && NLB >= 1, "a weight stage is a whole number of wave-loads per wave");
     static_assert(NS >= 3 && (NS - 1) * NLB < 48, "pipeline depth");
     static_assert(TM + TN <= 15, "fragment reads in flight against the lgkmcnt range");
 
     extern __shared__ uint4 smem_u4[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem_u4;    // weight stages first, then the patch
-    const uint32_t patch0 = lds0 + NS * B_STAGE;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem_u4;    // the groups' weight rings first, then the patch
+    const uint32_t patch0 = lds0 + KW * B_RING;
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
+    const int kg = wave / NWG, wq = wave % NWG;            // K group, wave inside the group
+    const int wm = wq / WGN, wn = wq % WGN;
 
     // workgroup -> (m tile, n tile, channel slice)
     int mt, nt, split;
@@ -190,34 +202,38 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
             load_one(j); load_one(j + NW); load_one(j + 2 * NW); load_one(j + 3 * NW);
         }
         for (; j < nwl; j += NW) load_one(j);
-        if (t < (1 << p.log2_cpp)) ((uint4 *)((char *)smem_u4 + NS * B_STAGE + (pz << log2_pitch)))[t] = make_uint4(0, 0, 0, 0);
+        if (t < (1 << p.log2_cpp)) ((uint4 *)((char *)smem_u4 + KW * B_RING + (pz << log2_pitch)))[t] = make_uint4(0, 0, 0, 0);
     }
 
-    // ---- weights: slot s = (i*NW + wave)*64 + lane of a stage holds chunk (s % 8) ^ swz(row) of row s / 8
+    // ---- weights: slot s = (i*NWG + wq)*64 + lane of a stage holds chunk (s % CPR) ^ swz(row) of row s / CPR
+    // (rows that share LDS banks, RP apart, get different chunk orders)
+    const int ncc = NCC > 0 ? NCC : p.ncc;                 // BK-channel chunks of the group
+    const int csg = ncc * BK;                              // channels of the group
+    const uint32_t kg_off = (uint32_t)(kg * csg) * 2u;     // the group's first channel inside a patch pixel, bytes
     uint32_t b_voff[NLB];
     const int rsc = p.R * p.S * p.C;
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
-        const int s = (i * NW + wave) * 64 + lane;
-        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
+        const int s = (i * NWG + wq) * 64 + lane;
+        const int row = s / CPR, c = (s % CPR) ^ ((row / RP) & (CPR - 1));
         const int n = n0 + row;
-        b_voff[i] = n < p.Nc ? (uint32_t)(n * rsc + split * p.Cs + c * 8) * 2u : kOutOfRange;
+        b_voff[i] = n < p.Nc ? (uint32_t)(n * rsc + split * p.Cs + kg * csg + c * 8) * 2u : kOutOfRange;
     }
-    const uint32_t ldsB = lds0 + wave * 1024;
-    const int ncc = NCC > 0 ? NCC : p.ncc;                 // 64-channel chunks of the slice
+    const uint32_t ring0 = lds0 + kg * B_RING;
+    const uint32_t ldsB = ring0 + wq * 1024;
     const int nsteps = KR > 0 ? KR * KR * NCC : p.R * p.S * p.ncc;
     // load cursor: byte offset of K step `lstep` inside a weight row, (tap, chunk) walked chunk fastest
     int lstep = 0, lcc = 0, lstage = 0;
     uint32_t lsoff = 0;
     auto issue_b = [&]() {
 #pragma unroll
-        for (int i = 0; i < NLB; ++i) dma_load16_s(w_rsrc, b_voff[i], lsoff, ldsB + lstage * B_STAGE + i * (NW * 1024));
+        for (int i = 0; i < NLB; ++i) dma_load16_s(w_rsrc, b_voff[i], lsoff, ldsB + lstage * B_STAGE + i * (NWG * 1024));
         ++lstep;
         lstage = lstage + 1 == NS ? 0 : lstage + 1;
         // next K step's offset inside a weight row; past the last step it stays where it is
         const bool more = lstep < nsteps;
         const bool wrap = lcc + 1 == ncc;
-        lsoff += more ? (uint32_t)(BK * 2) + (wrap ? (uint32_t)(p.C - p.Cs) * 2u : 0u) : 0u;
+        lsoff += more ? (uint32_t)(BK * 2) + (wrap ? (uint32_t)(p.C - csg) * 2u : 0u) : 0u;
         lcc = more ? (wrap ? 0 : lcc + 1) : lcc;
     };
     // NS - 1 stages in flight from here on (past the last step: repeats of it, never read)
@@ -246,9 +262,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int r = wn * WTN + j * 32 + (lane & 31);
-        const uint32_t swz = ((r >> 1) & 7) * 16;
+        const uint32_t swz = ((r / RP) & (CPR - 1)) * 16;
 #pragma unroll
-        for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = lds0 + r * 128 + ((kc * 32 + (lane >> 5) * 16) ^ swz);
+        for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = ring0 + r * (BK * 2) + ((kc * 32 + (lane >> 5) * 16) ^ swz);
     }
 
     floatx16_t acc[TM][TN];
@@ -259,7 +275,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const uint32_t khalf = (lane >> 5) * 16;
+    const uint32_t khalf = (lane >> 5) * 16 + kg_off;      // this lane's first byte inside a patch pixel
 
     // Where the MFMA row tiles of one K step read: patch row and swizzle under the
     // step's tap (rows whose tap falls outside the image use the zero row), the
@@ -281,9 +297,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     // Operand reads run D k-chunks ahead of the MFMAs that use them, each k-chunk in a
     // register buffer of its own (kc % NKC): with one wave per SIMD the LDS latency
     // under load (several hundred cycles) is only covered by that many MFMA groups.
-    constexpr int D = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
-    static_assert(D < NKC, "look-ahead stays within the next step");
-    u32x4_t af[NKC][TM], bf[NKC][TN];
+    constexpr int D0 = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
+    constexpr int D = D0 < NKC ? D0 : NKC;
+    constexpr int NBUF = 4;                                // k chunk g (counted over all steps) uses buffer g % NBUF
+    static_assert(D <= NKC && D < NBUF && NBUF % NKC == 0, "look-ahead stays within the next step");
+    u32x4_t af[NBUF][TM], bf[NBUF][TN];
     auto read_frags = [&](int kc, const StepAddr &sa) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], sa.a_row[i] + ((sa.c_off + kc * 32) ^ sa.a_swz[i]));
@@ -337,34 +355,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         ALT_STAMP(2);
         // reads of k chunk g (counted over all steps); past the last step they repeat it (never used)
         auto reads = [&](int g) {
-            const int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC;
+            const int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC, buf = g % NBUF;
             const int tap = step / NCC, cc = step % NCC, st = step % NS;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], t_row[tap][i] + (k_off[cc][kc] ^ t_swz[tap][i]));
+            for (int i = 0; i < TM; ++i) lds_read16_async(af[buf][i], t_row[tap][i] + (k_off[cc][kc] ^ t_swz[tap][i]));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rds[st][j][kc]);
+            for (int j = 0; j < TN; ++j) lds_read16_async(bf[buf][j], b_rds[st][j][kc]);
         };
 #pragma unroll
         for (int g = 0; g < D; ++g) reads(g);
 #pragma unroll
         for (int step = 0; step < NSTEPS; ++step) {
             wait_vmcnt<(NS - 3) * NLB>();                  // stage step+1 has landed (this wave's share)
-            asm volatile("s_barrier" ::: "memory");
+            if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");   // (a one-wave group loads its ring alone)
             issue_b();
 #pragma unroll
             for (int kc = 0; kc < NKC; ++kc) {
+                const int buf = (step * NKC + kc) % NBUF;
                 reads(step * NKC + kc + D);
-                lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
+                lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
-                                                                            __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                            __builtin_bit_cast(bf16x8_t, bf[buf][j]),
                                                                             acc[i][j], 0, 0, 0);
             }
         }
     } else {
+        static_assert(KR > 0 || NKC == NBUF, "the run-time path takes 64-channel steps");
         int r = 0, s = 0, cc = 0;
         StepAddr cur, nxt;
         set_tap(cur, 0, 0);
@@ -380,7 +400,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     #ifdef ALT_PHASE_TIMING
             if (!(p.flags & 512))
     #endif
-            asm volatile("s_barrier" ::: "memory");
+            if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");
     #ifdef ALT_PHASE_TIMING
             if (!(p.flags & 256))
     #endif
@@ -406,7 +426,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
                 if (kc == 0) {
                     // where step + 1 reads (after the last step: where this one does)
                     const bool more = step + 1 < nsteps;
-                    const bool wrap_c = cc + 1 == p.ncc;
+                    const bool wrap_c = cc + 1 == ncc;
                     const bool wrap_s = wrap_c && s + 1 == p.S;
                     cc = more ? (wrap_c ? 0 : cc + 1) : cc;
                     s = more && wrap_c ? (wrap_s ? 0 : s + 1) : s;
@@ -426,7 +446,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     // stay reserved until then, so they are tied to a wait here like any other read.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int kc = 0; kc < NKC; ++kc) {
+    for (int kc = 0; kc < NBUF; ++kc) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[kc][i]));
 #pragma unroll
@@ -447,6 +467,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     constexpr int SP = WTN + 8;                            // staging pitch in floats
     constexpr int CPRW = WTN / 4;                          // 16-byte chunks per staged row
     constexpr int RPI = 64 / CPRW;                         // rows per wave-wide access
+    constexpr int NIT = WTM / RPI / KW;                    // wave-wide accesses per wave: its 1/KW of the wave tile's rows
+    static_assert(WTM % (RPI * KW) == 0, "the K groups share the rows of a wave tile evenly");
     __syncthreads();                                       // every wave is done with the stages and the patch
 #ifdef ALT_PHASE_TIMING
     uint64_t epi_clk[3];
@@ -460,7 +482,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 stg[(i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][e];
-    // (a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
+    // (with one K group a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
+    if constexpr (KW > 1) __syncthreads();
 #ifdef ALT_PHASE_TIMING
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     epi_clk[1] = __builtin_amdgcn_s_memtime();
@@ -468,22 +491,43 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
     const int cl = lane % CPRW, rl = lane / CPRW;          // this lane's chunk and row inside an access
     const int n = n0 + wn * WTN + cl * 4;
     const bool n_ok = n < p.Nc;                            // Nc % 4 == 0
-    const int mrow0 = m0 + wm * WTM + rl;
+    const int rrow0 = kg * (NIT * RPI) + rl;               // first row of this lane inside the wave tile
+    const int mrow0 = m0 + wm * WTM + rrow0;
     const int tile = mt * p.tiles_n + nt;
+
+    // The wave's share of the tile, summed over the K groups in group order.
+    f32x4_t vs[NIT];
+    {
+        const float *src = (const float *)smem_u4 + wq * (WTM * SP) + rrow0 * SP + cl * 4;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const float4 f = *(const float4 *)(src + it * RPI * SP);
+            vs[it] = (f32x4_t){f.x, f.y, f.z, f.w};
+        }
+#pragma unroll
+        for (int g = 1; g < KW; ++g)
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const float4 f = *(const float4 *)(src + g * (NWG * WTM * SP) + it * RPI * SP);
+                vs[it] += (f32x4_t){f.x, f.y, f.z, f.w};
+            }
+    }
+    uint32_t offs[NIT];                                    // element offsets in the output (and a partial-sum plane)
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int m = mrow0 + it * RPI;
+        offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) : kOutOfRange / 4u;
+    }
 
     if (p.splitk > 1) {
         // publish the partial tile; the last slice to arrive sums all slices in slice order
         const __amdgpu_buffer_rsrc_t pr = __builtin_amdgcn_make_buffer_rsrc(
             (void *)((char *)p.partial + (size_t)split * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
 #pragma unroll
-        for (int it = 0; it < WTM / RPI; ++it) {
-            const int m = mrow0 + it * RPI;
-            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
-            const u32x4_t v = {__builtin_bit_cast(uint32_t, f.x), __builtin_bit_cast(uint32_t, f.y),
-                               __builtin_bit_cast(uint32_t, f.z), __builtin_bit_cast(uint32_t, f.w)};
-            const uint32_t off = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-            if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, 0);
-            else __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)off, 0, kAgentScope);
+        for (int it = 0; it < NIT; ++it) {
+            const u32x4_t v = __builtin_bit_cast(u32x4_t, vs[it]);
+            if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)(offs[it] * 4u), 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)(offs[it] * 4u), 0, kAgentScope);
         }
         // Release half.  Across XCDs: the partial sums were stored with device (agent) scope,
         // i.e. written through to memory all XCDs share; once the stores are acknowledged
@@ -507,19 +551,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         __syncthreads();
         if (*flag == 0) return;
         // acquire half: the loads below have device scope (or bypass the CU's L1) and so do not hit stale cache lines
-    }
 
-    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)p.y_bytes, 0x00020000);
-    const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
-    const bool out_bf16 = p.flags & kDconvOutBf16;
-    float bv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (n_ok && (p.flags & ALT_EPI_BIAS)) {
-        const float4 b4 = *(const float4 *)(p.bias + n);
-        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
-    }
-    constexpr int NIT = WTM / RPI;                         // wave-wide accesses per wave tile
-    f32x4_t vs[NIT];
-    if (p.splitk > 1) {
         // Sum of the slices in slice order.  All loads of a slice are issued before any of
         // them is consumed (one dependent load per access would cost a device-scope memory
         // round trip each).  Whole-vector adds: element-wise float views of a loaded
@@ -529,12 +561,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
         // G slices (up to 32 loads) are in flight at a time: a device-scope load takes over a
         // microsecond, so slices fetched one after the other would cost that much each
         constexpr int G = NIT >= 32 ? 1 : 32 / NIT;
-        uint32_t offs[NIT];
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int m = mrow0 + it * RPI;
-            offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) * 4u : kOutOfRange;
-        }
         for (int sl0 = 0; sl0 < p.splitk; sl0 += G) {
             u32x4_t w4[G][NIT];
 #pragma unroll
@@ -546,26 +572,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
                     live ? (int)p.partial_bytes : 0, 0x00020000);
 #pragma unroll
                 for (int it = 0; it < NIT; ++it)
-                    w4[g][it] = p.xcd_local ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kBypassL1)
-                                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)offs[it], 0, kAgentScope);
+                    w4[g][it] = p.xcd_local ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), 0, kBypassL1)
+                                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), 0, kAgentScope);
             }
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int it = 0; it < NIT; ++it) vs[it] += __builtin_bit_cast(f32x4_t, w4[g][it]);
         }
-    } else {
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const float4 f = *(const float4 *)(stg + (rl + it * RPI) * SP + cl * 4);
-            vs[it] = (f32x4_t){f.x, f.y, f.z, f.w};
-        }
+    }
+
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)p.y_bytes, 0x00020000);
+    const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
+    const bool out_bf16 = p.flags & kDconvOutBf16;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (n_ok && (p.flags & ALT_EPI_BIAS)) {
+        const float4 b4 = *(const float4 *)(p.bias + n);
+        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
     }
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int m = mrow0 + it * RPI;
-        const bool ok = n_ok && m < p.M;
-        const uint32_t idx = (uint32_t)(m * p.Nc + n);
+        const bool ok = offs[it] != kOutOfRange / 4u;
         float v[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[q] = fmaxf(vs[it][q] + bv[q], relu_floor);
@@ -574,11 +601,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
             const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
             typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
             u32x2_t o = {lo, hi};
-            __builtin_amdgcn_raw_buffer_store_b64(o, yr, (int)(ok ? idx * 2u : kOutOfRange), 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(o, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
         } else {
             u32x4_t o = {__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
                          __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
-            __builtin_amdgcn_raw_buffer_store_b128(o, yr, (int)(ok ? idx * 4u : kOutOfRange), 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(o, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0);
         }
     }
 #ifdef ALT_PHASE_TIMING
@@ -599,23 +626,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void dconv_kernel(const DconvParams
 #endif
 }
 
-// LDS bytes of one workgroup: weight stages, the patch rounded up to whole
-// wave-loads, the all-zero row.
-inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int Cs, int W, int pad_h, int pad_w)
+// LDS bytes of one workgroup: the K groups' weight rings, the patch rounded up to
+// whole wave-loads, the all-zero row.
+inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, int W, int pad_h, int pad_w)
 {
     const size_t pitch = (size_t)Cs * 2;
     const size_t np = (size_t)BM + 2 * ((size_t)pad_h * W + pad_w);
     const size_t patch = (np * pitch + 1023) / 1024 * 1024;
-    const size_t main_loop = (size_t)NS * BN * 128 + patch + pitch;
-    // output staging: [BM][BN + 8 floats per wave column] + the split-K flag
-    const size_t staging = (size_t)BM * (BN + 8 * waves_n) * 4 + 16;
+    const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + patch + pitch;
+    // output staging: per K group [BM][BN + 8 floats per wave column], + the split-K flag
+    const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
     return main_loop > staging ? main_loop : staging;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, int KR, int NCC>
+template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK, int KR, int NCC>
 hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    auto kern = dconv_kernel<BM, BN, WGM, WGN, NS, KR, NCC>;
+    auto kern = dconv_kernel<BM, BN, WGM, WGN, KW, NS, BK, KR, NCC>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -624,25 +651,35 @@ hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
     }
     const int tiles = p.tiles_m * p.tiles_n;
     const unsigned grid = p.xcd_local ? (unsigned)((tiles + 7) / 8 * 8 * p.splitk) : (unsigned)(tiles * p.splitk);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WGM * WGN), lds, st, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WGM * WGN * KW), lds, st, p);
     return hipGetLastError();
 }
 
-// 1x1 filters over up to 512 channels per slice and 3x3 filters over 64 or 128 have
-// fully unrolled kernels; everything else walks taps and chunks at run time.
-template <int BM, int BN, int WGM, int WGN, int NS>
+// 1x1 filters over up to 512 channels per K group and 3x3 filters over 64 or 128 have
+// fully unrolled kernels; everything else walks taps and chunks at run time.  Kernels
+// with 32-channel K steps (BK = 32: smaller weight stages) exist for 3x3 filters over
+// 32 or 64 channels per K group.
+template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK>
 hipError_t dconv_launch(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    if (p.R == 3 && p.S == 3) {
-        if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3, 1>(p, lds, st);
-        if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 3, 2>(p, lds, st);
-    } else if (p.R == 1 && p.S == 1) {
-        if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 1>(p, lds, st);
-        if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 2>(p, lds, st);
-        if (p.ncc == 4) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 4>(p, lds, st);
-        if (p.ncc == 8) return dconv_launch_kr<BM, BN, WGM, WGN, NS, 1, 8>(p, lds, st);
+    if (p.bk != BK) return hipErrorInvalidValue;
+    if constexpr (BK == 32) {
+        if (p.R == 3 && p.S == 3 && p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 32, 3, 1>(p, lds, st);
+        if (p.R == 3 && p.S == 3 && p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 32, 3, 2>(p, lds, st);
+        return hipErrorInvalidValue;
+    } else {
+        if (p.R == 3 && p.S == 3) {
+            if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 3, 1>(p, lds, st);
+            if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 3, 2>(p, lds, st);
+        } else if (p.R == 1 && p.S == 1) {
+            if (p.ncc == 1) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 1, 1>(p, lds, st);
+            if (p.ncc == 2) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 1, 2>(p, lds, st);
+            if (p.ncc == 4) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 1, 4>(p, lds, st);
+            if constexpr (KW == 1)
+                if (p.ncc == 8) return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 1, 8>(p, lds, st);
+        }
+        return dconv_launch_kr<BM, BN, WGM, WGN, KW, NS, 64, 0, 0>(p, lds, st);
     }
-    return dconv_launch_kr<BM, BN, WGM, WGN, NS, 0, 0>(p, lds, st);
 }
 
 }  // namespace alt

@@ -102,12 +102,19 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if (splitk < 1 || C % splitk) return no("split factor does not divide the channels");
     const int64_t Cs = C / splitk;
     if (Cs % 64 || (Cs & (Cs - 1)) || Cs > 512) return no("channels per slice must be 64, 128, 256 or 512");
+    // K groups: each takes Cs / kw channels, in steps of k.BK (64, or 32: built for 3x3 filters over
+    // 32 or 64 channels per group)
+    const int kw = k.kw, bk = k.BK;
+    if (Cs % kw) return no("K groups do not divide the slice");
+    const int64_t Csg = Cs / kw;
+    if (Csg % bk) return no("too few channels per K group");
+    if (bk == 32 && !(R == 3 && S == 3 && Csg <= 64)) return no("32-channel K steps are built for 3x3 filters over 32 or 64 channels per group");
     if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
         return no("operand of 2 GiB or more");
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
     if (K % 4 || (uintptr_t)p.y % 16 || ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 16))
         return no("direct kernel stores four output channels at a time");
-    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, (int)Cs, p.W, p.pad_h, p.pad_w);
+    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs, p.W, p.pad_h, p.pad_w);
     if (lds > 160 * 1024) return no("patch does not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
@@ -133,7 +140,8 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     // cycle: 128-byte pixels pair up (pixel / 2 picks the chunk position), wider ones do not
     d.swz_shift = Cs == 64 ? 1 : 0;
     d.swz_mask = Cs == 64 ? 7 : 15;
-    d.ncc = (int32_t)(Cs / 64);
+    d.ncc = (int32_t)(Csg / bk);
+    d.bk = bk;
     d.d_sk = make_div32((uint32_t)splitk);
     {
         int dev = 0;

@@ -4,12 +4,7 @@
 namespace alt {
 namespace {
 
-#define ALT_DCONV(BM, BN, WGM, WGN, NS)                                                                          \
-    const bool reg_dconv_##BM##x##BN##_w##WGM##x##WGN##_s##NS =                                                  \
-        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_direct_w" #WGM "x" #WGN "_s" #NS, ALT_BF16, BM, BN,  \
-                                    64, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,                               \
-                                    &dconv_launch<BM, BN, WGM, WGN, NS>, WGM, WGN}),                             \
-         true)
+#include "dconv_reg.h"
 
 ALT_DCONV(128, 128, 2, 2, 3);
 ALT_DCONV(128, 128, 2, 2, 5);

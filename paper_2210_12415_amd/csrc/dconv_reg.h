@@ -1,0 +1,19 @@
+// Registration of one direct-convolution tile configuration with the kernel table.
+#pragma once
+#include "dconv.h"
+
+// BM x BN output tile, WGM x WGN waves, NS weight stages
+#define ALT_DCONV(BM, BN, WGM, WGN, NS)                                                                          \
+    const bool reg_dconv_##BM##x##BN##_w##WGM##x##WGN##_s##NS =                                                  \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_direct_w" #WGM "x" #WGN "_s" #NS, ALT_BF16, BM, BN,  \
+                                    64, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,                               \
+                                    &dconv_launch<BM, BN, WGM, WGN, 1, NS, 64>, WGM, WGN, 1}),                   \
+         true)
+
+// the same with KW K groups of WGM x WGN waves each and K steps of BK channels
+#define ALT_DCONV_KW(BM, BN, WGM, WGN, KW, NS, BK)                                                               \
+    const bool reg_dconv_##BM##x##BN##_w##WGM##x##WGN##x##KW##_s##NS##_b##BK =                                   \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x" #BK "_direct_w" #WGM "x" #WGN "x" #KW "_s" #NS,       \
+                                    ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
+                                    &dconv_launch<BM, BN, WGM, WGN, KW, NS, BK>, WGM, WGN, KW}),                 \
+         true)

@@ -3,6 +3,8 @@ layouts by the oracle's conversion operator; results are brought back to
 logical NCHW the same way, so the library's own transform is not trusted
 here.  Integer-valued inputs make every summation order exact, so those
 cases must match bit for bit under every kernel variant."""
+import re
+
 import numpy as np
 import pytest
 import torch
@@ -95,6 +97,7 @@ DIRECT_CASES = [
     dict(N=2, C=256, H=13, W=6, K=160, R=1, S=1, pad=0),     # 1x1: no halo, up to four channel slices
     dict(N=1, C=64, H=11, W=12, K=32, R=5, S=5, pad=2),      # two-pixel halo, K below one tile
     dict(N=5, C=512, H=3, W=3, K=64, R=3, S=3, pad=1),       # images smaller than the halo of a tile
+    dict(N=1, C=128, H=8, W=9, K=72, R=5, S=5, pad=2),       # run-time tap walk with K groups
 ]
 
 
@@ -119,8 +122,12 @@ def test_direct_kernel_exact_integers_every_variant(h, case):
     for v, name in variants:
         got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, variant=v)
         assert np.array_equal(got, ref), name
-    # the epilogue variants on a few kernels, split and unsplit
-    picks = [variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
+    # kernels whose waves form several K groups (name: w<rows>x<cols>x<groups>)
+    grouped = [vn for vn in variants if re.search(r"_w\d+x\d+x\d+_", vn[1])]
+    assert grouped or c["C"] == 64
+    # the epilogue variants on a few kernels, split and unsplit, with and without K groups
+    picks = ([variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
+             + grouped[:2] + [vn for vn in grouped if not vn[1].endswith("_k1")][:2])
     for v, name in picks:
         got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, bias=b, relu=True, variant=v)
         assert np.array_equal(got, ref_br), name
