@@ -27,6 +27,8 @@
 // second kernel is launched.
 #pragma once
 
+#include <utility>
+
 #include "igemm_dma.h"
 
 namespace alt {
@@ -66,6 +68,9 @@ struct DconvParams {
     int32_t bk;                   // channels per K step: 64, or 32 for narrow K groups
     int32_t xcd_local;            // split-K: the slices of a tile run on one XCD and meet in its L2
     Div32 d_sk;                   // division by splitk
+    // streaming kernel (dstream.h) only: batch entries and the byte strides between them
+    int32_t batch, pad1_;
+    int64_t x_bstride, w_bstride, y_bstride;
 };
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -97,6 +102,26 @@ __device__ __forceinline__ void lds_read16_async(u32x4_t &dst, uint32_t addr)
     asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr) : "memory");
 }
 
+// The same with a compile-time byte offset (an instruction field up to 65535, an add beyond).
+template <int OFF>
+__device__ __forceinline__ void lds_read16_async_at(u32x4_t &dst, uint32_t addr)
+{
+    if constexpr (OFF >= 0 && OFF < 65536) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    else lds_read16_async(dst, addr + (uint32_t)OFF);
+}
+
+// f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>), in order.
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // Waits until at most N LDS operations of this wave are outstanding and ties
 // the given fragment registers to that point (no use can move above it).
 template <int N, int NA, int NB>
@@ -107,6 +132,223 @@ __device__ __forceinline__ void lds_wait(u32x4_t (&a)[NA], u32x4_t (&b)[NB])
     for (int i = 1; i < NA; ++i) asm volatile("" : "+v"(a[i]));
 #pragma unroll
     for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+// Second half of the epilogue.  The waves' tiles are staged in LDS ([WTM][SP] floats per
+// wave); each lane handles CW consecutive columns (4, or 8 for bf16 output so that its
+// store is still 16 bytes wide: stores run at a rate set by the bytes per lane).
+template <int BM, int BN, int WGM, int WGN, int KW, int CW>
+__device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 *smem_u4, int t, int lane, int kg, int wq,
+                                                    int wm, int wn, int m0, int n0, int mt, int nt, int split, char *y)
+{
+    constexpr int NWG = WGM * WGN, NW = NWG * KW;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int SP = WTN + 8;                            // staging pitch in floats
+    constexpr int V = CW / 4;                              // 16-byte pieces per lane per access
+    constexpr int CPRW = WTN / CW;                         // lanes per staged row
+    constexpr int RPI = 64 / CPRW;                         // rows per wave-wide access
+    constexpr int NIT = WTM / RPI / KW;                    // wave-wide accesses per wave: its 1/KW of the wave tile's rows
+    static_assert(NIT >= 1 && WTM % (RPI * KW) == 0, "the K groups share the rows of a wave tile evenly");
+    const int cl = lane % CPRW, rl = lane / CPRW;          // this lane's column group and row inside an access
+    const int n = n0 + wn * WTN + cl * CW;
+    const bool n_ok = n < p.Nc;                            // Nc % CW == 0
+    const int rrow0 = kg * (NIT * RPI) + rl;               // first row of this lane inside the wave tile
+    const int mrow0 = m0 + wm * WTM + rrow0;
+    const int tile = mt * p.tiles_n + nt;
+
+    // The wave's share of the tile, summed over the K groups in group order.
+    f32x4_t vs[NIT][V];
+    {
+        const float *src = (const float *)smem_u4 + wq * (WTM * SP) + rrow0 * SP + cl * CW;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float4 f = *(const float4 *)(src + it * RPI * SP + v * 4);
+                vs[it][v] = (f32x4_t){f.x, f.y, f.z, f.w};
+            }
+#pragma unroll
+        for (int g = 1; g < KW; ++g)
+#pragma unroll
+            for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const float4 f = *(const float4 *)(src + g * (NWG * WTM * SP) + it * RPI * SP + v * 4);
+                    vs[it][v] += (f32x4_t){f.x, f.y, f.z, f.w};
+                }
+    }
+    uint32_t offs[NIT];                                    // element offsets in the output (and a partial-sum plane)
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int m = mrow0 + it * RPI;
+        offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) : kOutOfRange / 4u;
+    }
+
+    if (p.splitk > 1) {
+        // publish the partial tile; the last slice to arrive sums all slices in slice order
+        const __amdgpu_buffer_rsrc_t pr = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((char *)p.partial + (size_t)split * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const u32x4_t w = __builtin_bit_cast(u32x4_t, vs[it][v]);
+                if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(w, pr, (int)(offs[it] * 4u), v * 16, 0);
+                else __builtin_amdgcn_raw_buffer_store_b128(w, pr, (int)(offs[it] * 4u), v * 16, kAgentScope);
+            }
+        // Release half.  Across XCDs: the partial sums were stored with device (agent) scope,
+        // i.e. written through to memory all XCDs share; once the stores are acknowledged
+        // they are visible to device-scope loads anywhere (a full device-scope fence would
+        // write back the whole L2 and costs tens of microseconds here).  Within one XCD:
+        // plain stores are acknowledged by the XCD's L2, which every CU of the XCD reads.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        uint32_t *flag = (uint32_t *)smem_u4 + NW * (WTM * SP);
+        if (t == 0) {
+            // (the XCD-local counter is an atomic executed in that XCD's L2: no device-scope bits)
+            const uint32_t old = p.xcd_local
+                ? __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
+                : __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = old == (uint32_t)(p.splitk - 1);
+            if (*flag) {                           // ready for the next launch
+                if (p.xcd_local) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                else __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+        if (*flag == 0) return false;                   // another workgroup finishes this tile
+        // acquire half: the loads below have device scope (or bypass the CU's L1) and so do not hit stale cache lines
+
+        // Sum of the slices in slice order.  All loads of a slice are issued before any of
+        // them is consumed (one dependent load per access would cost a device-scope memory
+        // round trip each).  Whole-vector adds: element-wise float views of a loaded
+        // vector are miscompiled into a single-dword load by this toolchain.
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int v = 0; v < V; ++v) vs[it][v] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        // G slices (up to 32 loads) are in flight at a time: a device-scope load takes over a
+        // microsecond, so slices fetched one after the other would cost that much each
+        constexpr int G = NIT * V >= 32 ? 1 : 32 / (NIT * V);
+        for (int sl0 = 0; sl0 < p.splitk; sl0 += G) {
+            u32x4_t w4[G][NIT][V];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                // slices past the last one read with a zero-sized descriptor: all zeros
+                const bool live = sl0 + g < p.splitk;
+                const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)((char *)p.partial + (size_t)(live ? sl0 + g : 0) * p.partial_bytes), 0,
+                    live ? (int)p.partial_bytes : 0, 0x00020000);
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        w4[g][it][v] = p.xcd_local
+                            ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), v * 16, kBypassL1)
+                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), v * 16, kAgentScope);
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) vs[it][v] += __builtin_bit_cast(f32x4_t, w4[g][it][v]);
+        }
+    }
+
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)p.y_bytes, 0x00020000);
+    const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
+    const bool out_bf16 = p.flags & kDconvOutBf16;
+    float bv[CW];
+#pragma unroll
+    for (int q = 0; q < CW; ++q) bv[q] = 0.f;
+    if (n_ok && (p.flags & ALT_EPI_BIAS)) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float4 b4 = *(const float4 *)(p.bias + n + v * 4);
+            bv[v * 4 + 0] = b4.x; bv[v * 4 + 1] = b4.y; bv[v * 4 + 2] = b4.z; bv[v * 4 + 3] = b4.w;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const bool ok = offs[it] != kOutOfRange / 4u;
+        float o[CW];
+#pragma unroll
+        for (int q = 0; q < CW; ++q) o[q] = fmaxf(vs[it][q / 4][q % 4] + bv[q], relu_floor);
+        if (CW == 8 || out_bf16) {                         // (eight columns per lane are only used for bf16 output)
+            uint32_t w[CW / 2];
+#pragma unroll
+            for (int q = 0; q < CW / 2; ++q)
+                w[q] = (uint32_t)f32_to_bf16_rne(o[2 * q]) | ((uint32_t)f32_to_bf16_rne(o[2 * q + 1]) << 16);
+            if constexpr (CW == 8) {
+                u32x4_t ov = {w[0], w[1], w[2], w[3]};
+                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+            } else {
+                typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+                u32x2_t ov = {w[0], w[1]};
+                __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+            }
+        } else {
+            u32x4_t ov = {__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                          __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0);
+        }
+    }
+    return true;
+}
+
+// The end of a tile kernel: every wave holds a WTM x WTN accumulator tile (wave (wm, wn) of
+// K group kg; wq = its index inside the group); the K groups are summed, then either
+// the finished tile is stored (bias, ReLU, fp32 or bf16) or, with split-K, the partial
+// tile is published and the last slice to arrive sums all slices.  y = the output of this
+// batch entry.  Uses the whole LDS allocation from its start (callers are done with it: the
+// function opens with a barrier).  Returns false in workgroups that leave the tile to
+// another slice's workgroup.
+template <int BM, int BN, int WGM, int WGN, int KW>
+__device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                               uint4 *smem_u4, int t, int lane, int wave, int kg, int wq, int wm, int wn,
+                                               int m0, int n0, int mt, int nt, int split, char *y, uint64_t *epi_clk)
+{
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    // ---- the wave's tile goes through LDS to row-major order -----------------------------------------
+    // Accumulator register e of lane l is element (8*(e/4) + 4*(l/32) + e%4, l%32) of a 32x32
+    // tile: consecutive lanes hold consecutive channels of one pixel, one dword each.
+    // Stores of one dword per lane run at a quarter of the rate of 16-byte ones, so each
+    // wave transposes through a private LDS region ([WTM][WTN + 8] floats: the pitch
+    // keeps both the dword writes and the 16-byte reads conflict-free) and then handles
+    // four or eight consecutive channels per lane.
+    constexpr int SP = WTN + 8;                            // staging pitch in floats
+    __syncthreads();                                       // every wave is done with the stages and the patch
+#ifdef ALT_PHASE_TIMING
+    epi_clk[0] = __builtin_amdgcn_s_memtime();
+#endif
+    float *stg = (float *)smem_u4 + wave * (WTM * SP);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stg[(i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][e];
+    // (with one K group a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
+    if constexpr (KW > 1) __syncthreads();
+#ifdef ALT_PHASE_TIMING
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    epi_clk[1] = __builtin_amdgcn_s_memtime();
+#endif
+    bool mine;
+    constexpr bool kWideFits = WTM % ((64 / (WTN / 8)) * KW) == 0;     // eight columns per lane divide the tile evenly
+    if (kWideFits && (p.flags & kDconvOutBf16) && p.Nc % 8 == 0) {
+        if constexpr (kWideFits)
+            mine = dconv_epilogue_tail<BM, BN, WGM, WGN, KW, 8>(p, smem_u4, t, lane, kg, wq, wm, wn, m0, n0, mt, nt, split, y);
+    } else {
+        mine = dconv_epilogue_tail<BM, BN, WGM, WGN, KW, 4>(p, smem_u4, t, lane, kg, wq, wm, wn, m0, n0, mt, nt, split, y);
+    }
+#ifdef ALT_PHASE_TIMING
+    epi_clk[2] = __builtin_amdgcn_s_memtime();
+#endif
+    return mine;
 }
 
 // The workgroup has KW groups of WGM x WGN waves.  Each group computes the whole BM x BN
@@ -457,159 +699,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dconv_kernel(const DconvP
     const uint64_t core_clk1 = __builtin_amdgcn_s_memtime();
 #endif
 
-    // ---- the wave's tile goes through LDS to row-major order -----------------------------------------
-    // Accumulator register e of lane l is element (8*(e/4) + 4*(l/32) + e%4, l%32) of a 32x32
-    // tile: consecutive lanes hold consecutive channels of one pixel, one dword each.
-    // Stores of one dword per lane run at a quarter of the rate of 16-byte ones, so each
-    // wave transposes through a private LDS region ([WTM][WTN + 8] floats: the pitch
-    // keeps both the dword writes and the 16-byte reads conflict-free) and then handles
-    // four consecutive channels per lane.
-    constexpr int SP = WTN + 8;                            // staging pitch in floats
-    constexpr int CPRW = WTN / 4;                          // 16-byte chunks per staged row
-    constexpr int RPI = 64 / CPRW;                         // rows per wave-wide access
-    constexpr int NIT = WTM / RPI / KW;                    // wave-wide accesses per wave: its 1/KW of the wave tile's rows
-    static_assert(WTM % (RPI * KW) == 0, "the K groups share the rows of a wave tile evenly");
-    __syncthreads();                                       // every wave is done with the stages and the patch
+    uint64_t epi_clk[3] = {0, 0, 0};
+    if (!dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
+                                              (char *)p.y, epi_clk))
+        return;
 #ifdef ALT_PHASE_TIMING
-    uint64_t epi_clk[3];
-    epi_clk[0] = __builtin_amdgcn_s_memtime();
-#endif
-    float *stg = (float *)smem_u4 + wave * (WTM * SP);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stg[(i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][e];
-    // (with one K group a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
-    if constexpr (KW > 1) __syncthreads();
-#ifdef ALT_PHASE_TIMING
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    epi_clk[1] = __builtin_amdgcn_s_memtime();
-#endif
-    const int cl = lane % CPRW, rl = lane / CPRW;          // this lane's chunk and row inside an access
-    const int n = n0 + wn * WTN + cl * 4;
-    const bool n_ok = n < p.Nc;                            // Nc % 4 == 0
-    const int rrow0 = kg * (NIT * RPI) + rl;               // first row of this lane inside the wave tile
-    const int mrow0 = m0 + wm * WTM + rrow0;
-    const int tile = mt * p.tiles_n + nt;
-
-    // The wave's share of the tile, summed over the K groups in group order.
-    f32x4_t vs[NIT];
-    {
-        const float *src = (const float *)smem_u4 + wq * (WTM * SP) + rrow0 * SP + cl * 4;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const float4 f = *(const float4 *)(src + it * RPI * SP);
-            vs[it] = (f32x4_t){f.x, f.y, f.z, f.w};
-        }
-#pragma unroll
-        for (int g = 1; g < KW; ++g)
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const float4 f = *(const float4 *)(src + g * (NWG * WTM * SP) + it * RPI * SP);
-                vs[it] += (f32x4_t){f.x, f.y, f.z, f.w};
-            }
-    }
-    uint32_t offs[NIT];                                    // element offsets in the output (and a partial-sum plane)
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int m = mrow0 + it * RPI;
-        offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) : kOutOfRange / 4u;
-    }
-
-    if (p.splitk > 1) {
-        // publish the partial tile; the last slice to arrive sums all slices in slice order
-        const __amdgpu_buffer_rsrc_t pr = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)((char *)p.partial + (size_t)split * p.partial_bytes), 0, (int)p.partial_bytes, 0x00020000);
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const u32x4_t v = __builtin_bit_cast(u32x4_t, vs[it]);
-            if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)(offs[it] * 4u), 0, 0);
-            else __builtin_amdgcn_raw_buffer_store_b128(v, pr, (int)(offs[it] * 4u), 0, kAgentScope);
-        }
-        // Release half.  Across XCDs: the partial sums were stored with device (agent) scope,
-        // i.e. written through to memory all XCDs share; once the stores are acknowledged
-        // they are visible to device-scope loads anywhere (a full device-scope fence would
-        // write back the whole L2 and costs tens of microseconds here).  Within one XCD:
-        // plain stores are acknowledged by the XCD's L2, which every CU of the XCD reads.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        uint32_t *flag = (uint32_t *)smem_u4 + NW * (WTM * SP);
-        if (t == 0) {
-            // (the XCD-local counter is an atomic executed in that XCD's L2: no device-scope bits)
-            const uint32_t old = p.xcd_local
-                ? __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
-                : __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            *flag = old == (uint32_t)(p.splitk - 1);
-            if (*flag) {                           // ready for the next launch
-                if (p.xcd_local) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                else __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        __syncthreads();
-        if (*flag == 0) return;
-        // acquire half: the loads below have device scope (or bypass the CU's L1) and so do not hit stale cache lines
-
-        // Sum of the slices in slice order.  All loads of a slice are issued before any of
-        // them is consumed (one dependent load per access would cost a device-scope memory
-        // round trip each).  Whole-vector adds: element-wise float views of a loaded
-        // vector are miscompiled into a single-dword load by this toolchain.
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) vs[it] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        // G slices (up to 32 loads) are in flight at a time: a device-scope load takes over a
-        // microsecond, so slices fetched one after the other would cost that much each
-        constexpr int G = NIT >= 32 ? 1 : 32 / NIT;
-        for (int sl0 = 0; sl0 < p.splitk; sl0 += G) {
-            u32x4_t w4[G][NIT];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                // slices past the last one read with a zero-sized descriptor: all zeros
-                const bool live = sl0 + g < p.splitk;
-                const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
-                    (void *)((char *)p.partial + (size_t)(live ? sl0 + g : 0) * p.partial_bytes), 0,
-                    live ? (int)p.partial_bytes : 0, 0x00020000);
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-                    w4[g][it] = p.xcd_local ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), 0, kBypassL1)
-                                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), 0, kAgentScope);
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int it = 0; it < NIT; ++it) vs[it] += __builtin_bit_cast(f32x4_t, w4[g][it]);
-        }
-    }
-
-    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)p.y_bytes, 0x00020000);
-    const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
-    const bool out_bf16 = p.flags & kDconvOutBf16;
-    float bv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (n_ok && (p.flags & ALT_EPI_BIAS)) {
-        const float4 b4 = *(const float4 *)(p.bias + n);
-        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
-    }
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const bool ok = offs[it] != kOutOfRange / 4u;
-        float v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = fmaxf(vs[it][q] + bv[q], relu_floor);
-        if (out_bf16) {
-            const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-            const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
-            typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-            u32x2_t o = {lo, hi};
-            __builtin_amdgcn_raw_buffer_store_b64(o, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
-        } else {
-            u32x4_t o = {__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
-                         __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
-            __builtin_amdgcn_raw_buffer_store_b128(o, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0);
-        }
-    }
-#ifdef ALT_PHASE_TIMING
-    epi_clk[2] = __builtin_amdgcn_s_memtime();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ALT_STAMP(4);
     if (threadIdx.x == 0 && p.partial) {

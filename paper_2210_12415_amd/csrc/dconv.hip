@@ -3,7 +3,7 @@
 // split-K reduction.
 #include <atomic>
 
-#include "dconv.h"
+#include "dstream.h"
 #include "ops.h"
 
 namespace alt {
@@ -80,10 +80,73 @@ bool dconv_round_robin_xcds()
     return ok;
 }
 
+// The same for a streaming kernel (dstream.h): 1x1 filters, stride 1, no padding (a GEMM
+// is lowered to that), any number of channels that splits into 64-channel steps.
+static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes,
+                          std::string *why)
+{
+    auto no = [&](const char *m) { if (why) *why = m; return false; };
+    const IgemmParams &p = pb.p;
+    if (pb.dtype != ALT_BF16) return no("streaming kernel is bf16 only");
+    if (p.R != 1 || p.S != 1 || p.stride_h != 1 || p.stride_w != 1 || p.pad_h != 0 || p.pad_w != 0)
+        return no("streaming kernel needs a 1x1 filter, stride 1, no padding");
+    if (p.OH != p.H || p.OW != p.W) return no("streaming kernel needs output size = input size");
+    const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, N = p.M / (H * W);
+    if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
+        return no("A is not dense with K contiguous");
+    if (!(dense(p.wi, C, 1) && dense(p.wo, K, C))) return no("B is not dense with K contiguous");
+    if (!(dense(p.yk, K, 1) && dense(p.yw, W, K) && dense(p.yh, H, W * K) && dense(p.yn, N, H * W * K)))
+        return no("output is not dense with N contiguous");
+    const int64_t osz = p.out_bf16 ? 2 : 4;
+    if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16 || (uintptr_t)p.y % 16) return no("operands are not 16-byte aligned");
+    if (p.batch > 1 && ((p.x_bstride * 2) % 16 || (p.w_bstride * 2) % 16 || (p.y_bstride * osz) % 16))
+        return no("batch entries are not 16-byte aligned");
+    if (p.batch > 65535) return no("too many batch entries for one launch");
+    if (splitk < 1 || (splitk > 1 && p.batch > 1)) return no("split-K is not built for batched problems");
+    if (C % ((int64_t)64 * splitk * k.kw)) return no("K does not split into 64-wide steps per slice and K group");
+    if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
+        return no("operand of 2 GiB or more");
+    if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
+    if (K % 4 || (p.epilogue & ALT_EPI_BIAS && (uintptr_t)p.bias % 16)) return no("streaming kernel stores four output columns at a time");
+    const size_t lds = dstream_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, k.kw);
+    if (lds > 160 * 1024) return no("stages do not fit LDS");
+    const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
+    if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
+    if ((int64_t)tiles_m * tiles_n * splitk > 0x7fffffff) return no("grid too large");
+    if (!out) return true;
+    DconvParams d;
+    std::memset(&d, 0, sizeof d);
+    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
+    d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
+    d.partial_bytes = (uint32_t)((int64_t)p.M * K * 4);
+    d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = (int32_t)(C / splitk);
+    d.H = p.H; d.W = p.W; d.R = 1; d.S = 1;
+    d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = splitk;
+    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
+    d.d_hw = make_div32((uint32_t)(p.H * p.W));
+    d.d_w = make_div32((uint32_t)p.W);
+    d.d_tm = make_div32((uint32_t)tiles_m);
+    d.d_tn = make_div32((uint32_t)tiles_n);
+    d.ncc = (int32_t)(C / splitk / k.kw / 64);
+    d.bk = 64;
+    d.d_sk = make_div32((uint32_t)splitk);
+    d.batch = p.batch;
+    d.x_bstride = p.x_bstride * 2; d.w_bstride = p.w_bstride * 2; d.y_bstride = p.y_bstride * osz;
+    {
+        int dev = 0;
+        d.xcd_local = splitk > 1 && hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices &&
+                      g_round_robin[dev] > 0 && (int64_t)(tiles_m * tiles_n + 7) / 8 * 8 * splitk <= 0x7fffffff;
+    }
+    *out = d;
+    *lds_bytes = lds;
+    return true;
+}
+
 // Fills the launch parameters of direct kernel `k` for `pb` split into `splitk`
 // channel slices, or says why the kernel does not cover the problem.
 bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes, std::string *why)
 {
+    if (k.stream) return dstream_setup(pb, k, splitk, out, lds_bytes, why);
     auto no = [&](const char *m) { if (why) *why = m; return false; };
     const IgemmParams &p = pb.p;
     if (pb.dtype != ALT_BF16) return no("direct kernel is bf16 only");

@@ -1,6 +1,6 @@
 // Registration of one direct-convolution tile configuration with the kernel table.
 #pragma once
-#include "dconv.h"
+#include "dstream.h"
 
 // BM x BN output tile, WGM x WGN waves, NS weight stages
 #define ALT_DCONV(BM, BN, WGM, WGN, NS)                                                                          \
@@ -16,4 +16,12 @@
         (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x" #BK "_direct_w" #WGM "x" #WGN "x" #KW "_s" #NS,       \
                                     ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
                                     &dconv_launch<BM, BN, WGM, WGN, KW, NS, BK>, WGM, WGN, KW}),                 \
+         true)
+
+// streaming kernel (dstream.h): BM x BN tile, KW K groups of WGM x WGN waves, NS stages
+#define ALT_DSTREAM(BM, BN, WGM, WGN, KW, NS)                                                                    \
+    const bool reg_dstream_##BM##x##BN##_w##WGM##x##WGN##x##KW##_s##NS =                                         \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_stream_w" #WGM "x" #WGN "x" #KW "_s" #NS,            \
+                                    ALT_BF16, BM, BN, 64, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
+                                    &dstream_launch<BM, BN, WGM, WGN, KW, NS>, WGM, WGN, KW, 1}),                \
          true)

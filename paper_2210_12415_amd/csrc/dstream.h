@@ -1,0 +1,241 @@
+// Streaming GEMM kernel for bf16 on gfx950: C[M][N] = A[M][K] * B[N][K]^T with both
+// operands K-contiguous (the GMM template with A as MK and B as NK, and equally a 1x1
+// stride-1 convolution over NHWC activations with OHWI weights), fp32 accumulation.
+//
+// Both operand tiles of a K step go from global memory straight into a ring of LDS
+// stages (no registers in between); everything else is the machinery of the direct
+// convolution (dconv.h): asynchronous fragment reads that run ahead of the MFMAs,
+// K groups inside the workgroup, the fused split-K tail, the shared epilogue.
+#pragma once
+
+#include "dconv.h"
+
+namespace alt {
+
+// KW groups of WGM x WGN waves; group kg handles channels [kg, kg + 1) * Cs / KW of the
+// workgroup's slice in steps of 64, through a ring of NS stages of its own.
+template <int BM, int BN, int WGM, int WGN, int KW, int NS>
+__global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const DconvParams p)
+{
+#ifdef ALT_PHASE_TIMING
+    uint64_t stamps[5] = {0, 0, 0, 0, 0};
+#endif
+    ALT_STAMP(0);
+    constexpr int NWG = WGM * WGN;                         // waves per K group
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int BK = 64, NKC = BK / 16;
+    constexpr int A_STAGE = BM * BK * 2, B_STAGE = BN * BK * 2;     // bytes: [rows][8 chunks of 16 B]
+    constexpr int STAGE = A_STAGE + B_STAGE;
+    constexpr int RING = NS * STAGE;
+    constexpr int NLA = A_STAGE / 1024 / NWG, NLB = B_STAGE / 1024 / NWG;   // wave-loads per wave per stage
+    constexpr int LPS = NLA + NLB;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile");
+    static_assert(A_STAGE % (1024 * NWG) == 0 && B_STAGE % (1024 * NWG) == 0 && NLA >= 1 && NLB >= 1,
+                  "a stage is a whole number of wave-loads per wave");
+    static_assert(NS >= 3 && (NS - 1) * LPS < 60, "pipeline depth against the vmcnt range");
+    static_assert(TM + TN <= 15, "fragment reads in flight against the lgkmcnt range");
+
+    extern __shared__ uint4 smem_u4[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem_u4;
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int kg = wave / NWG, wq = wave % NWG;
+    const int wm = wq / WGN, wn = wq % WGN;
+
+    // workgroup -> (m tile, n tile, channel slice), as in the direct convolution
+    int mt, nt, split;
+    if (p.xcd_local) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int tl = (int)div32((uint32_t)slot, p.d_sk);
+        split = slot - tl * p.splitk;
+        const int tile_id = tl * 8 + xcd;
+        if (tile_id >= p.tiles_m * p.tiles_n) return;
+        nt = (int)div32((uint32_t)tile_id, p.d_tm);
+        mt = tile_id - nt * p.tiles_m;
+    } else {
+        const int ntot = p.tiles_m * p.tiles_n * p.splitk;
+        const int logical = igemm_logical_tile(ntot);
+        const int rest = (int)div32((uint32_t)logical, p.d_tm);
+        mt = logical - rest * p.tiles_m;
+        split = (int)div32((uint32_t)rest, p.d_tn);
+        nt = rest - split * p.tiles_n;
+    }
+    const int m0 = mt * BM, n0 = nt * BN;
+    const int bz = blockIdx.y;                             // batch entry
+
+    const i32x4_t x_rsrc = make_rsrc((const char *)p.x + (int64_t)bz * p.x_bstride, p.x_bytes);
+    const i32x4_t w_rsrc = make_rsrc((const char *)p.w + (int64_t)bz * p.w_bstride, p.w_bytes);
+
+    // ---- loads: slot s = (i*NWG + wq)*64 + lane of an operand's stage holds chunk (s % 8) ^ swz(row) of row s / 8
+    const int nk = p.ncc;                                  // K steps of a group
+    const uint32_t k_off0 = (uint32_t)(split * p.Cs + kg * (nk * BK)) * 2u;
+    uint32_t a_voff[NLA], b_voff[NLB];
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+        const int s = (i * NWG + wq) * 64 + lane;
+        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
+        const int m = m0 + row;
+        a_voff[i] = m < p.M ? (uint32_t)(m * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
+    }
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) {
+        const int s = (i * NWG + wq) * 64 + lane;
+        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
+        const int n = n0 + row;
+        b_voff[i] = n < p.Nc ? (uint32_t)(n * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
+    }
+    const uint32_t ring0 = lds0 + kg * RING;
+    const uint32_t ldsW = ring0 + wq * 1024;
+    // load cursor: K step `lstep` goes to stage `lstage`; past the last step the last one is
+    // loaded again (into stages nobody reads any more), which keeps the load count per step fixed
+    int lstep = 0, lstage = 0;
+    auto issue_stage = [&]() {
+        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * (BK * 2);
+        const uint32_t dst = ldsW + lstage * STAGE;
+#pragma unroll
+        for (int i = 0; i < NLA; ++i) dma_load16_s(x_rsrc, a_voff[i], soff, dst + i * (NWG * 1024));
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) dma_load16_s(w_rsrc, b_voff[i], soff, dst + A_STAGE + i * (NWG * 1024));
+        ++lstep;
+        lstage = lstage + 1 == NS ? 0 : lstage + 1;
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_stage();
+
+    // ---- operand addresses of this lane in stage 0: row (lane % 32) of each 32-row MFMA tile, k half (lane / 32)
+    uint32_t a_rd[TM][NKC], b_rd[TN][NKC];
+    {
+        const uint32_t khalf = (lane >> 5) * 16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int r = wm * WTM + i * 32 + (lane & 31);
+            const uint32_t swz = ((r >> 1) & 7) * 16;
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) a_rd[i][kc] = ring0 + r * 128 + ((kc * 32 + khalf) ^ swz);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int r = wn * WTN + j * 32 + (lane & 31);
+            const uint32_t swz = ((r >> 1) & 7) * 16;
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = ring0 + A_STAGE + r * 128 + ((kc * 32 + khalf) ^ swz);
+        }
+    }
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // Operand reads run D k-chunks ahead of the MFMAs that use them, k chunk g (counted
+    // over all steps) in register buffer g % NKC.
+    constexpr int D = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
+    static_assert(D < NKC, "look-ahead stays within the next step");
+    u32x4_t af[NKC][TM], bf[NKC][TN];
+    // reads of k chunk kc of the step in stage ST
+    auto reads = [&](auto ST, int kc) {
+        constexpr int off = decltype(ST)::value * STAGE;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) lds_read16_async_at<off>(af[kc][i], a_rd[i][kc]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) lds_read16_async_at<off>(bf[kc][j], b_rd[j][kc]);
+    };
+
+    ALT_STAMP(1);
+    wait_vmcnt<(NS - 2) * LPS>();                          // stage 0 (this wave's share)
+    lds_barrier();
+    ALT_STAMP(2);
+#pragma unroll
+    for (int kc = 0; kc < D; ++kc) reads(std::integral_constant<int, 0>{}, kc);
+
+    // One K step in stage st.  At its barrier every wave has its share of the next stage
+    // landed, so both are complete for everybody afterwards and the look-ahead may run into
+    // the next stage; the barrier also says the previous stage is consumed, and its refill
+    // is issued right after it.  Past the last step the look-ahead reads whatever the
+    // repeated loads left in the next stage (never used).
+    auto do_step = [&](auto ST) {
+        constexpr int st = decltype(ST)::value;
+        using Next = std::integral_constant<int, (st + 1 == NS ? 0 : st + 1)>;
+        wait_vmcnt<(NS - 3) * LPS>();
+        if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");
+        issue_stage();
+#pragma unroll
+        for (int kc = 0; kc < NKC; ++kc) {
+            if (kc + D < NKC) reads(ST, kc + D);
+            else reads(Next{}, kc + D - NKC);
+            lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
+                                                                        __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                                                                        acc[i][j], 0, 0, 0);
+        }
+    };
+    int ks0 = 0;
+    for (; ks0 + NS <= nk; ks0 += NS)                      // whole rounds over the stages, no exit inside
+        static_for<NS>(do_step);
+    static_for<NS - 1>([&](auto ST) {                      // the last, partial round
+        if (ks0 + decltype(ST)::value < nk) do_step(ST);
+    });
+
+    wait_vmcnt<0>();                                       // the repeated loads past the last step
+    // the look-ahead reads past the last step still land in their registers: tie them to a wait
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[kc][i]));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bf[kc][j]));
+    }
+    ALT_STAMP(3);
+
+    uint64_t epi_clk[3] = {0, 0, 0};
+    if (!dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
+                                              (char *)p.y + (int64_t)bz * p.y_bstride, epi_clk))
+        return;
+#ifdef ALT_PHASE_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    ALT_STAMP(4);
+    if (threadIdx.x == 0 && p.partial && gridDim.y == 1) {
+        uint64_t *out = (uint64_t *)((char *)p.partial + (p.splitk > 1 ? (size_t)p.splitk * p.partial_bytes : 0)) + (size_t)blockIdx.x * 8;
+        for (int i = 0; i < 5; ++i) out[i] = stamps[i];
+        out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
+        out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
+        out[7] = 0;
+    }
+#endif
+}
+
+// LDS bytes of one workgroup: the K groups' operand rings, or the output staging.
+inline size_t dstream_lds_bytes(int BM, int BN, int NS, int waves_n, int kw)
+{
+    const size_t main_loop = (size_t)kw * NS * (BM + BN) * 128;
+    const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
+    return main_loop > staging ? main_loop : staging;
+}
+
+template <int BM, int BN, int WGM, int WGN, int KW, int NS>
+hipError_t dstream_launch(const DconvParams &p, size_t lds, hipStream_t st)
+{
+    auto kern = dstream_kernel<BM, BN, WGM, WGN, KW, NS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles = p.tiles_m * p.tiles_n;
+    const unsigned grid = p.xcd_local ? (unsigned)((tiles + 7) / 8 * 8 * p.splitk) : (unsigned)(tiles * p.splitk);
+    hipLaunchKernelGGL(kern, dim3(grid, (unsigned)p.batch), dim3(64 * WGM * WGN * KW), lds, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace alt

@@ -1,0 +1,16 @@
+// Instantiations of the streaming GEMM kernel: large tiles.
+#include "dconv_reg.h"
+
+namespace alt {
+namespace {
+
+ALT_DSTREAM(256, 128, 4, 2, 1, 3);
+ALT_DSTREAM(128, 256, 2, 4, 1, 3);
+ALT_DSTREAM(128, 128, 2, 2, 1, 3);
+ALT_DSTREAM(128, 128, 2, 2, 1, 4);
+ALT_DSTREAM(128, 128, 4, 2, 1, 4);
+ALT_DSTREAM(256, 64, 4, 1, 1, 3);
+ALT_DSTREAM(256, 64, 4, 1, 1, 4);
+
+}  // namespace
+}  // namespace alt

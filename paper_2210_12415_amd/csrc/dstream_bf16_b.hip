@@ -1,0 +1,15 @@
+// Instantiations of the streaming GEMM kernel: small tiles and K groups.
+#include "dconv_reg.h"
+
+namespace alt {
+namespace {
+
+ALT_DSTREAM(128, 64, 2, 1, 1, 4);
+ALT_DSTREAM(128, 64, 4, 1, 1, 4);
+ALT_DSTREAM(128, 64, 2, 1, 2, 3);
+ALT_DSTREAM(64, 128, 1, 2, 2, 3);
+ALT_DSTREAM(64, 64, 2, 2, 1, 4);
+ALT_DSTREAM(256, 64, 8, 1, 1, 3);
+
+}  // namespace
+}  // namespace alt
