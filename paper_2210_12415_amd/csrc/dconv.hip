@@ -103,12 +103,12 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
         return no("batch entries are not 16-byte aligned");
     if (p.batch > 65535) return no("too many batch entries for one launch");
     if (splitk < 1 || (splitk > 1 && p.batch > 1)) return no("split-K is not built for batched problems");
-    if (C % ((int64_t)64 * splitk * k.kw)) return no("K does not split into 64-wide steps per slice and K group");
+    if (C % ((int64_t)k.BK * splitk * k.kw)) return no("K does not split into whole steps per slice and K group");
     if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
         return no("operand of 2 GiB or more");
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
     if (K % 4 || (p.epilogue & ALT_EPI_BIAS && (uintptr_t)p.bias % 16)) return no("streaming kernel stores four output columns at a time");
-    const size_t lds = dstream_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, k.kw);
+    const size_t lds = dstream_lds_bytes(k.BM, k.BN, k.BK, k.prefetch + 1, k.wgn, k.kw);
     if (lds > 160 * 1024) return no("stages do not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
@@ -127,8 +127,8 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     d.d_w = make_div32((uint32_t)p.W);
     d.d_tm = make_div32((uint32_t)tiles_m);
     d.d_tn = make_div32((uint32_t)tiles_n);
-    d.ncc = (int32_t)(C / splitk / k.kw / 64);
-    d.bk = 64;
+    d.ncc = (int32_t)(C / splitk / k.kw / k.BK);
+    d.bk = k.BK;
     d.d_sk = make_div32((uint32_t)splitk);
     d.batch = p.batch;
     d.x_bstride = p.x_bstride * 2; d.w_bstride = p.w_bstride * 2; d.y_bstride = p.y_bstride * osz;

@@ -18,10 +18,10 @@
                                     &dconv_launch<BM, BN, WGM, WGN, KW, NS, BK>, WGM, WGN, KW}),                 \
          true)
 
-// streaming kernel (dstream.h): BM x BN tile, KW K groups of WGM x WGN waves, NS stages
-#define ALT_DSTREAM(BM, BN, WGM, WGN, KW, NS)                                                                    \
-    const bool reg_dstream_##BM##x##BN##_w##WGM##x##WGN##x##KW##_s##NS =                                         \
-        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_stream_w" #WGM "x" #WGN "x" #KW "_s" #NS,            \
-                                    ALT_BF16, BM, BN, 64, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
-                                    &dstream_launch<BM, BN, WGM, WGN, KW, NS>, WGM, WGN, KW, 1}),                \
+// streaming kernel (dstream.h): BM x BN tile, KW K groups of WGM x WGN waves, NS stages of BK channels
+#define ALT_DSTREAM(BM, BN, WGM, WGN, KW, NS, BK)                                                                \
+    const bool reg_dstream_##BM##x##BN##x##BK##_w##WGM##x##WGN##x##KW##_s##NS =                                  \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x" #BK "_stream_w" #WGM "x" #WGN "x" #KW "_s" #NS,       \
+                                    ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
+                                    &dstream_launch<BM, BN, WGM, WGN, KW, NS, BK>, WGM, WGN, KW, 1}),            \
          true)

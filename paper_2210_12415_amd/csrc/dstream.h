@@ -13,8 +13,10 @@
 namespace alt {
 
 // KW groups of WGM x WGN waves; group kg handles channels [kg, kg + 1) * Cs / KW of the
-// workgroup's slice in steps of 64, through a ring of NS stages of its own.
-template <int BM, int BN, int WGM, int WGN, int KW, int NS>
+// workgroup's slice in steps of BK (64 or 32), through a ring of NS stages of its own.
+// While a step computes, NS - 2 later stages are in flight: deep rings of small stages
+// (BK = 32) cover the load latency with the same LDS as shallow rings of large ones.
+template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK>
 __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
@@ -24,8 +26,10 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
     constexpr int NWG = WGM * WGN;                         // waves per K group
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int BK = 64, NKC = BK / 16;
-    constexpr int A_STAGE = BM * BK * 2, B_STAGE = BN * BK * 2;     // bytes: [rows][8 chunks of 16 B]
+    constexpr int NKC = BK / 16;
+    constexpr int CPR = BK / 8;                            // 16-byte chunks per tile row of a stage
+    constexpr int RP = 256 / (BK * 2);                     // tile rows per 256 bytes of LDS
+    constexpr int A_STAGE = BM * BK * 2, B_STAGE = BN * BK * 2;     // bytes: [rows][CPR chunks of 16 B]
     constexpr int STAGE = A_STAGE + B_STAGE;
     constexpr int RING = NS * STAGE;
     constexpr int NLA = A_STAGE / 1024 / NWG, NLB = B_STAGE / 1024 / NWG;   // wave-loads per wave per stage
@@ -33,7 +37,9 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile");
     static_assert(A_STAGE % (1024 * NWG) == 0 && B_STAGE % (1024 * NWG) == 0 && NLA >= 1 && NLB >= 1,
                   "a stage is a whole number of wave-loads per wave");
+    static_assert(BK == 64 || BK == 32, "K step");
     static_assert(NS >= 3 && (NS - 1) * LPS < 60, "pipeline depth against the vmcnt range");
+    static_assert((NS * NKC) % 4 == 0, "a round over the stages is a whole number of fragment-buffer cycles");
     static_assert(TM + TN <= 15, "fragment reads in flight against the lgkmcnt range");
 
     extern __shared__ uint4 smem_u4[];
@@ -68,21 +74,22 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
     const i32x4_t x_rsrc = make_rsrc((const char *)p.x + (int64_t)bz * p.x_bstride, p.x_bytes);
     const i32x4_t w_rsrc = make_rsrc((const char *)p.w + (int64_t)bz * p.w_bstride, p.w_bytes);
 
-    // ---- loads: slot s = (i*NWG + wq)*64 + lane of an operand's stage holds chunk (s % 8) ^ swz(row) of row s / 8
+    // ---- loads: slot s = (i*NWG + wq)*64 + lane of an operand's stage holds chunk (s % CPR) ^ swz(row) of
+    // row s / CPR (rows that share LDS banks, RP apart, get different chunk orders)
     const int nk = p.ncc;                                  // K steps of a group
     const uint32_t k_off0 = (uint32_t)(split * p.Cs + kg * (nk * BK)) * 2u;
     uint32_t a_voff[NLA], b_voff[NLB];
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
         const int s = (i * NWG + wq) * 64 + lane;
-        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
+        const int row = s / CPR, c = (s % CPR) ^ ((row / RP) & (CPR - 1));
         const int m = m0 + row;
         a_voff[i] = m < p.M ? (uint32_t)(m * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
         const int s = (i * NWG + wq) * 64 + lane;
-        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
+        const int row = s / CPR, c = (s % CPR) ^ ((row / RP) & (CPR - 1));
         const int n = n0 + row;
         b_voff[i] = n < p.Nc ? (uint32_t)(n * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
     }
@@ -111,16 +118,16 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int r = wm * WTM + i * 32 + (lane & 31);
-            const uint32_t swz = ((r >> 1) & 7) * 16;
+            const uint32_t swz = ((r / RP) & (CPR - 1)) * 16;
 #pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) a_rd[i][kc] = ring0 + r * 128 + ((kc * 32 + khalf) ^ swz);
+            for (int kc = 0; kc < NKC; ++kc) a_rd[i][kc] = ring0 + r * (BK * 2) + ((kc * 32 + khalf) ^ swz);
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int r = wn * WTN + j * 32 + (lane & 31);
-            const uint32_t swz = ((r >> 1) & 7) * 16;
+            const uint32_t swz = ((r / RP) & (CPR - 1)) * 16;
 #pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = ring0 + A_STAGE + r * 128 + ((kc * 32 + khalf) ^ swz);
+            for (int kc = 0; kc < NKC; ++kc) b_rd[j][kc] = ring0 + A_STAGE + r * (BK * 2) + ((kc * 32 + khalf) ^ swz);
         }
     }
 
@@ -132,26 +139,28 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // Operand reads run D k-chunks ahead of the MFMAs that use them, k chunk g (counted
-    // over all steps) in register buffer g % NKC.
-    constexpr int D = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
-    static_assert(D < NKC, "look-ahead stays within the next step");
-    u32x4_t af[NKC][TM], bf[NKC][TN];
-    // reads of k chunk kc of the step in stage ST
-    auto reads = [&](auto ST, int kc) {
-        constexpr int off = decltype(ST)::value * STAGE;
+    // Operand reads run D k-chunks ahead of the MFMAs that use them; k chunk g (counted
+    // from the start of a round over the stages) uses register buffer g % NBUF.
+    constexpr int D0 = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
+    constexpr int D = D0 < NKC ? D0 : NKC;                 // the look-ahead stays within the next step
+    constexpr int NBUF = 4;
+    static_assert(D < NBUF && NBUF % NKC == 0, "fragment buffers");
+    u32x4_t af[NBUF][TM], bf[NBUF][TN];
+    // reads of k chunk G of a round (G / NKC = stage, wrapping into the next round's first stage)
+    auto reads = [&](auto GI) {
+        constexpr int g = decltype(GI)::value;
+        constexpr int st = (g / NKC) % NS, kc = g % NKC, buf = g % NBUF, off = st * STAGE;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) lds_read16_async_at<off>(af[kc][i], a_rd[i][kc]);
+        for (int i = 0; i < TM; ++i) lds_read16_async_at<off>(af[buf][i], a_rd[i][kc]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) lds_read16_async_at<off>(bf[kc][j], b_rd[j][kc]);
+        for (int j = 0; j < TN; ++j) lds_read16_async_at<off>(bf[buf][j], b_rd[j][kc]);
     };
 
     ALT_STAMP(1);
     wait_vmcnt<(NS - 2) * LPS>();                          // stage 0 (this wave's share)
     lds_barrier();
     ALT_STAMP(2);
-#pragma unroll
-    for (int kc = 0; kc < D; ++kc) reads(std::integral_constant<int, 0>{}, kc);
+    static_for<D>(reads);
 
     // One K step in stage st.  At its barrier every wave has its share of the next stage
     // landed, so both are complete for everybody afterwards and the look-ahead may run into
@@ -160,23 +169,21 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
     // repeated loads left in the next stage (never used).
     auto do_step = [&](auto ST) {
         constexpr int st = decltype(ST)::value;
-        using Next = std::integral_constant<int, (st + 1 == NS ? 0 : st + 1)>;
         wait_vmcnt<(NS - 3) * LPS>();
         if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");
         issue_stage();
-#pragma unroll
-        for (int kc = 0; kc < NKC; ++kc) {
-            if (kc + D < NKC) reads(ST, kc + D);
-            else reads(Next{}, kc + D - NKC);
-            lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
+        static_for<NKC>([&](auto KC) {
+            constexpr int g = st * NKC + decltype(KC)::value, buf = g % NBUF;
+            reads(std::integral_constant<int, g + D>{});
+            lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
-                                                                        __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                        __builtin_bit_cast(bf16x8_t, bf[buf][j]),
                                                                         acc[i][j], 0, 0, 0);
-        }
+        });
     };
     int ks0 = 0;
     for (; ks0 + NS <= nk; ks0 += NS)                      // whole rounds over the stages, no exit inside
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
     // the look-ahead reads past the last step still land in their registers: tie them to a wait
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int kc = 0; kc < NKC; ++kc) {
+    for (int kc = 0; kc < NBUF; ++kc) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[kc][i]));
 #pragma unroll
@@ -215,17 +222,18 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const Dcon
 }
 
 // LDS bytes of one workgroup: the K groups' operand rings, or the output staging.
-inline size_t dstream_lds_bytes(int BM, int BN, int NS, int waves_n, int kw)
+inline size_t dstream_lds_bytes(int BM, int BN, int bk, int NS, int waves_n, int kw)
 {
-    const size_t main_loop = (size_t)kw * NS * (BM + BN) * 128;
+    const size_t main_loop = (size_t)kw * NS * (BM + BN) * bk * 2;
     const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
     return main_loop > staging ? main_loop : staging;
 }
 
-template <int BM, int BN, int WGM, int WGN, int KW, int NS>
+template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK>
 hipError_t dstream_launch(const DconvParams &p, size_t lds, hipStream_t st)
 {
-    auto kern = dstream_kernel<BM, BN, WGM, WGN, KW, NS>;
+    if (p.bk != BK) return hipErrorInvalidValue;
+    auto kern = dstream_kernel<BM, BN, WGM, WGN, KW, NS, BK>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

@@ -4,13 +4,16 @@
 namespace alt {
 namespace {
 
-ALT_DSTREAM(256, 128, 4, 2, 1, 3);
-ALT_DSTREAM(128, 256, 2, 4, 1, 3);
-ALT_DSTREAM(128, 128, 2, 2, 1, 3);
-ALT_DSTREAM(128, 128, 2, 2, 1, 4);
-ALT_DSTREAM(128, 128, 4, 2, 1, 4);
-ALT_DSTREAM(256, 64, 4, 1, 1, 3);
-ALT_DSTREAM(256, 64, 4, 1, 1, 4);
+ALT_DSTREAM(256, 128, 4, 2, 1, 3, 64);
+ALT_DSTREAM(256, 128, 2, 2, 1, 3, 64);
+ALT_DSTREAM(128, 256, 2, 2, 1, 3, 64);
+ALT_DSTREAM(256, 128, 4, 2, 1, 6, 32);
+ALT_DSTREAM(128, 256, 2, 4, 1, 6, 32);
+ALT_DSTREAM(128, 128, 2, 2, 1, 4, 64);
+ALT_DSTREAM(128, 128, 4, 2, 1, 4, 64);
+ALT_DSTREAM(128, 128, 4, 2, 1, 8, 32);
+ALT_DSTREAM(256, 64, 4, 1, 1, 4, 64);
+ALT_DSTREAM(256, 64, 4, 1, 1, 8, 32);
 
 }  // namespace
 }  // namespace alt
