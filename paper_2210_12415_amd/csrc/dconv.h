@@ -279,7 +279,7 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
             uint32_t w[CW / 2];
 #pragma unroll
             for (int q = 0; q < CW / 2; ++q)
-                w[q] = (uint32_t)f32_to_bf16_rne(o[2 * q]) | ((uint32_t)f32_to_bf16_rne(o[2 * q + 1]) << 16);
+                w[q] = f32x2_to_bf16x2(o[2 * q], o[2 * q + 1]);
             if constexpr (CW == 8) {
                 u32x4_t ov = {w[0], w[1], w[2], w[3]};
                 __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);

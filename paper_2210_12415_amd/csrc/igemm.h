@@ -140,6 +140,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(((w & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);
 }
 
+// Two fp32 -> bf16 conversions (round to nearest even, NaN kept quiet) packed into one
+// dword, lo in the low half: one hardware conversion instruction on gfx950.
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // 8x8 transpose of 16-bit elements held as 8 uint4 rows (in place).
 __device__ __forceinline__ void transpose8x8_b16(uint4 *r)
 {
