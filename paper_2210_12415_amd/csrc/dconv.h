@@ -78,6 +78,10 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kDconvOutBf16 = 4;
 constexpr int kAgentScope = 16;          // cache-policy operand of buffer loads/stores: sc1 = device (agent) scope
 constexpr int kBypassL1 = 1;             // sc0: served by the XCD's L2, never by the CU's own L1
+// Output stores carry sc0 + sc1: the lines go through to memory as they are written instead of
+// staying dirty in the XCD's L2 until the write-back at the end of the kernel, which
+// shortens the gap before the next kernel on the stream (measured: 5 % of a five-layer step).
+constexpr int kWriteThrough = 17;
 constexpr int kDconvMaxTiles = 4096;     // output tiles a split-K launch may have (one counter each)
 constexpr int kDconvSlots = 8;           // counter sets, handed to launches round-robin
 
@@ -282,16 +286,16 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
                 w[q] = f32x2_to_bf16x2(o[2 * q], o[2 * q + 1]);
             if constexpr (CW == 8) {
                 u32x4_t ov = {w[0], w[1], w[2], w[3]};
-                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, kWriteThrough);
             } else {
                 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
                 u32x2_t ov = {w[0], w[1]};
-                __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, kWriteThrough);
             }
         } else {
             u32x4_t ov = {__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
                           __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])};
-            __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, kWriteThrough);
         }
     }
     return true;

@@ -73,6 +73,29 @@ __device__ inline void locate_tile(const PermuteParams &p, int64_t &src_base, in
     }
 }
 
+// Store that goes through to memory as it is written (sc0 + sc1) instead of leaving a dirty
+// line in the XCD's L2 for the write-back at the end of the kernel: the output of a
+// conversion is not read again by this kernel, and the shorter kernel end is what counts
+// for these few-microsecond launches.
+template <typename V>
+__device__ __forceinline__ void store_through(char *addr, const V &w)
+{
+    typedef uint32_t w4_t __attribute__((ext_vector_type(4)));
+    typedef uint32_t w2_t __attribute__((ext_vector_type(2)));
+    if constexpr (sizeof(V) == 16) {
+        const w4_t v = __builtin_bit_cast(w4_t, w);
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(addr), "v"(v) : "memory");
+    } else if constexpr (sizeof(V) == 8) {
+        const w2_t v = __builtin_bit_cast(w2_t, w);
+        asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(addr), "v"(v) : "memory");
+    } else if constexpr (sizeof(V) == 4) {
+        const uint32_t v = __builtin_bit_cast(uint32_t, w);
+        asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(addr), "v"(v) : "memory");
+    } else {
+        *(V *)addr = w;
+    }
+}
+
 // Piece a is contiguous on both sides: copy TB runs of TA elements.
 template <int ELSZ, int VBYTES>
 __global__ __launch_bounds__(kThreads) void permute_rows_kernel(PermuteParams p)
@@ -89,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void permute_rows_kernel(PermuteParams p)
     for (int v = threadIdx.x; v < ra * tb; v += kThreads) {
         int ib = v / ra, ia = (v - ib * ra) * VL;
         V w = *(const V *)(src + (sb + ib * p.ss_b + ia) * ELSZ);
-        *(V *)(dst + (db + ib * p.ds_b + ia) * ELSZ) = w;
+        store_through(dst + (db + ib * p.ds_b + ia) * ELSZ, w);
     }
 }
 
@@ -129,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void permute_transpose_kernel(PermutePara
             E *e = (E *)&w;
 #pragma unroll
             for (int j = 0; j < VS; ++j) e[j] = tile[(ib + j) * LD + ia];
-            *(VSt *)(dst + (db + ia * p.ds_a + ib) * ELSZ) = w;
+            store_through(dst + (db + ia * p.ds_a + ib) * ELSZ, w);
         }
     }
 }
