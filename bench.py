@@ -263,6 +263,42 @@ def main():
         res["per_layer"] = per_layer
         return res
 
+    def load_traffic():
+        """HBM bytes per launch from a stored pair of hardware-counter runs
+        (workloads/traffic_from_rocprof.py writes the file), or None."""
+        path = os.path.join(ROOT, "workloads", "measured_traffic_gfx950.json")
+        if not os.path.exists(path):
+            return None
+        with open(path) as f:
+            return json.load(f)
+
+    def kernel_traffic(doc, layer, batch):
+        """The stored traffic of the kernel instantiation and grid this layer launches."""
+        import re
+        if not doc:
+            return None
+        L, name = layer["L"], layer["variant"]
+        m = re.match(r"bf16_(\d+)x(\d+)x(\d+)_(direct|stream)_w(\d+)x(\d+)(?:x(\d+))?_s(\d+)_k(\d+)$", name)
+        if not m:
+            return None
+        BM, BN, BK, kind, wgm, wgn, kw, ns, sk = (int(g) if g and g.isdigit() else g for g in m.groups())
+        kw = kw or 1
+        oh, ow = conv_out_hw(L["H"], L["W"], L["R"], L["S"], L["stride"], L["pad"])
+        tiles = -(-(batch * oh * ow) // BM) * -(-L["K"] // BN)
+        if sk > 1:
+            tiles = -(-tiles // 8) * 8
+        grid = tiles * sk * 64 * wgm * wgn * kw
+        ncc = L["C"] // sk // kw // BK
+        if kind == "direct":
+            kr = L["R"] if (L["R"] == L["S"] and ((L["R"] == 3 and ncc in (1, 2)) or (L["R"] == 1 and ncc in (1, 2, 4, 8)))) else 0
+            key = "dconv_kernel<%d, %d, %d, %d, %d, %d, %d, %d, %d>|%d" % (BM, BN, wgm, wgn, kw, ns, BK, kr, ncc if kr else 0, grid)
+        else:
+            key = "dstream_kernel<%d, %d, %d, %d, %d, %d, %d>|%d" % (BM, BN, wgm, wgn, kw, ns, BK, grid)
+        e = doc["kernels"].get(key)
+        if not e or "fetch_bytes" not in e or "write_bytes" not in e:
+            return None
+        return dict(fetch_bytes=e["fetch_bytes"], write_bytes=e["write_bytes"])
+
     # headline: bf16 in, fp32 accumulate, bf16 out (the layer's output feeds a bf16 layer)
     layers = load_layers(alt.BF16, "bf16_out")
     head = measure_step(layers)
@@ -272,8 +308,15 @@ def main():
     per_layer = head["per_layer"]
     dom = max(layers, key=lambda l: l["us"])
     achieved = dom["flops"] / dom["us"] / 1e6
+    traffic_doc = load_traffic()
+    for l, pl in zip(layers, per_layer):
+        tr = kernel_traffic(traffic_doc, l, 16)
+        if tr:
+            pl["hbm_bytes_per_launch"] = tr
+    dom_tr = kernel_traffic(traffic_doc, dom, 16)
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=(dom_tr["fetch_bytes"] + dom_tr["write_bytes"]) if dom_tr else None,
                     kernel=dom["variant"], layer=dom["L"]["name"],
                     us_per_launch=round(dom["us"], 3), flops_per_launch=dom["flops"])
 
