@@ -461,6 +461,36 @@ def main():
                               variants=[h.conv2d_variant_name(plan.op[i], plan.op[i].variant) for i in range(plan.nops)],
                               measurements=plan.trials)
 
+        # ------------------------------------------------- residual block (graph) ----
+        # conv3x3+bias+ReLU -> conv3x3+bias -> + block input -> ReLU, 64 channels, 56x56, batch 16, bf16 tensors:
+        # layouts propagate through the sum, the block input has two consumers
+        def phys(l):
+            return "".join("NCHW"[l.sub_dim[j]] if l.sub_extent[j] == 0 else "%d%s" % (l.sub_extent[j], "nchw"[l.sub_dim[j]])
+                           for j in range(l.nsub))
+        mk = lambda relu: alt.conv_desc(16, 64, 56, 56, 64, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                        epilogue=alt.EPI_BIAS | (alt.EPI_RELU if relu else 0))
+        blk = [alt.graph_node(alt.NODE_CONV, 0, conv=mk(True)), alt.graph_node(alt.NODE_CONV, 1, conv=mk(False)),
+               alt.graph_node(alt.NODE_ADD, 2, 0, relu=1)]
+        gp = h.tune_graph(blk, "NCHW->NCHW", arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        numel = 16 * 64 * 56 * 56
+        ea = torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev)
+        eb = torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev)
+        ey = torch.empty_like(ea)
+        gr = capture(lambda st: h.eltwise_add(alt.BF16, numel, ea, eb, ey, relu=True, stream=st), 20)
+        add_us = graph_timed(gr, 20)
+        del gr, ea, eb, ey
+        extra["residual_block"] = dict(
+            planned_total_us=round(float(gp.total_us), 2), all_nchw_total_us=round(float(gp.default_total_us), 2),
+            speedup_vs_all_nchw=round(float(gp.default_total_us) / float(gp.total_us), 2),
+            tensor_layouts=[phys(gp.tensor_layout[t]) for t in range(4)],
+            conversions=[[int(gp.convert[i][j]) for j in range(2)] for i in range(3)],
+            conversion_us=[[round(float(gp.convert_us[i][j]), 2) for j in range(2)] for i in range(3)],
+            node_us=[round(float(gp.node_us[i]), 2) for i in range(3)],
+            variants=[h.conv2d_variant_name(gp.conv[i], gp.conv[i].variant) for i in range(2)],
+            measurements=gp.trials,
+            add_relu_us=round(add_us, 2), add_relu_GBps=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6), 1),
+            add_relu_frac_hbm_peak=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6) / PEAK_HBM_GBPS, 4))
+
         pk = h.get_peak(arena, arena.numel())
         extra["attainable"] = dict(copy_GBps=round(float(pk.copy_gbps), 1),
                                    mfma_bf16_TFLOPs=round(float(pk.mfma_bf16_tflops), 1),

@@ -304,6 +304,66 @@ alt_status_t alt_tune_chain(alt_handle_t h, const alt_conv_desc_t *ops, int nops
 alt_status_t alt_plan_chain(int nops, int nl, const float *op_cost, const float *conv_cost,
                             int in_layout, int *out_in_idx, int *out_out_idx, float *out_total);
 
+/* ---- graphs of operators: layout propagation (Section 4.2) ---------------- */
+
+/* y[i] = a[i] + b[i] (b may be null: y = a), then max(., 0) if relu != 0, for
+ * numel elements of `dtype`.  bf16: the exact sum rounded once to nearest even.
+ * An element-wise operator takes the layout of its producer (Section 4.2), so
+ * the three device buffers are flat and share one layout; y may alias a or b.
+ * 16-byte aligned buffers.  Asynchronous on `stream`. */
+alt_status_t alt_eltwise_add(alt_handle_t h, alt_dtype_t dtype, int64_t numel, const void *a, const void *b,
+                             void *y, int relu, void *stream);
+
+#define ALT_MAX_GRAPH 8
+#define ALT_NODE_CONV 0
+#define ALT_NODE_ADD 1
+
+typedef struct {
+    int32_t kind;             /* ALT_NODE_CONV or ALT_NODE_ADD */
+    int32_t in0, in1;         /* tensors read: 0 = the graph input, i + 1 = the output of node i (earlier nodes
+                                 only); in1 is ignored for ALT_NODE_CONV */
+    int32_t relu;             /* ALT_NODE_ADD: ReLU after the sum (a convolution's is in its epilogue flags) */
+    alt_conv_desc_t conv;     /* ALT_NODE_CONV: shape, types, stride, padding, epilogue; layouts and variant ignored */
+} alt_graph_node_t;
+
+typedef struct {
+    int32_t nnodes, trials;
+    alt_conv_desc_t conv[ALT_MAX_GRAPH];            /* ALT_NODE_CONV nodes: chosen layouts and variant */
+    alt_layout_t tensor_layout[ALT_MAX_GRAPH + 1];  /* layout tensor t is stored in (0 = the graph input) */
+    alt_layout_t read_layout[ALT_MAX_GRAPH][2];     /* layout node i reads its input j in */
+    int32_t convert[ALT_MAX_GRAPH][2];              /* 1: a conversion operator feeds input j of node i */
+    float convert_us[ALT_MAX_GRAPH][2];
+    float node_us[ALT_MAX_GRAPH];
+    float total_us;                                 /* planned latency of the graph */
+    float default_total_us;                         /* the same graph with NCHW on every tensor */
+} alt_graph_plan_t;
+
+/* Layout choice for a small graph of convolutions and element-wise sums, e.g.
+ * a residual block (Section 4.2: layouts propagate from the complex operators
+ * through the simple ones; a tensor with several consumers is stored once, in
+ * its producer's layout, and a conversion operator is inserted in front of each
+ * consumer that reads another layout).  An ALT_NODE_ADD reads both inputs and
+ * writes its output in one layout.  nodes[i] may only read the graph input and
+ * outputs of nodes before it; the last node's output is the graph's.  Measures
+ * every convolution under every (input, output) layout pair, every conversion
+ * of every consumed tensor and every sum, then takes the cheapest assignment.
+ * Synchronises. */
+alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int nnodes,
+                            const alt_layout_t *in_layout, const alt_tune_opts_t *opts,
+                            alt_graph_plan_t *plan);
+
+/* Pure planner behind alt_tune_graph (host only).  kind/in0/in1: as in
+ * alt_graph_node_t, per node.  op_cost[i][a][b] ([nnodes][nl][nl], convolutions
+ * only): latency reading layout a, writing layout b.  conv_cost[t][a][b]
+ * ([nnodes + 1][nl][nl]): latency of converting tensor t from a to b (the
+ * diagonal is taken as zero).  add_cost[i]: latency of sum node i.  Infinite
+ * entries mark impossible combinations.  Returns the stored layout index of
+ * every tensor ([nnodes + 1], entry 0 = in_layout), the layout index every
+ * node reads each input in ([nnodes][2], -1 for unused) and the total. */
+alt_status_t alt_plan_graph(int nnodes, const int32_t *kind, const int32_t *in0, const int32_t *in1, int nl,
+                            const float *op_cost, const float *conv_cost, const float *add_cost, int in_layout,
+                            int32_t *tensor_layout, int32_t *read_layout, float *total);
+
 /* Tune cache persistence: text file, one line per entry keyed by problem,
  * dtype, layouts and the device architecture name. */
 alt_status_t alt_cache_save(alt_handle_t h, const char *path);

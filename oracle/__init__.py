@@ -291,6 +291,36 @@ def conv2d_at(x, w, flat, stride=1, pad=0, dil=1, bias=None, relu=False):
     return out
 
 
+def bf16_bits_to_f64(b):
+    """uint16 bf16 bit patterns -> float64 values (exact)."""
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def eltwise_add(a, b=None, relu=False):
+    """Element-wise operator of a graph (Section 4.2: simple operators take the
+    layout of their producer, so this works on arrays of any shape in any one
+    layout).  y = a + b (b may be None: y = a), then max(y, 0) if relu.
+    float32 arrays: IEEE single-precision addition.  uint16 arrays of bf16
+    bits: the exact sum rounded once to bf16, to nearest even."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        s = bf16_bits_to_f64(a)
+        if b is not None:
+            s = s + bf16_bits_to_f64(b)            # exact: both fit 8 significant bits
+        if relu:
+            s = np.maximum(s, 0.0)
+        # float32 holds the sum exactly unless the exponents are > 16 apart, and then the
+        # smaller term is far below half a bf16 step of the larger: one rounding either way
+        return f32_to_bf16_bits(s.astype(np.float32))
+    s = a.astype(np.float32)
+    if b is not None:
+        s = (s + np.asarray(b, dtype=np.float32)).astype(np.float32)
+    if relu:
+        s = np.maximum(s, np.float32(0))
+    return s
+
+
 def conv_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
     d = _Conv(*x_shape, w_shape[0], w_shape[2], w_shape[3], stride, stride, pad, pad, dil, dil,
               0, 0, 0, 0)

@@ -86,6 +86,23 @@ class ChainPlan(ctypes.Structure):
                 ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float)]
 
 
+MAX_GRAPH = 8
+NODE_CONV, NODE_ADD = 0, 1
+
+
+class GraphNode(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("in0", ctypes.c_int32), ("in1", ctypes.c_int32),
+                ("relu", ctypes.c_int32), ("conv", ConvDesc)]
+
+
+class GraphPlan(ctypes.Structure):
+    _fields_ = [("nnodes", ctypes.c_int32), ("trials", ctypes.c_int32),
+                ("conv", ConvDesc * MAX_GRAPH), ("tensor_layout", Layout * (MAX_GRAPH + 1)),
+                ("read_layout", (Layout * 2) * MAX_GRAPH), ("convert", (ctypes.c_int32 * 2) * MAX_GRAPH),
+                ("convert_us", (ctypes.c_float * 2) * MAX_GRAPH), ("node_us", ctypes.c_float * MAX_GRAPH),
+                ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float)]
+
+
 class Peaks(ctypes.Structure):
     _fields_ = [("copy_gbps", ctypes.c_float), ("mfma_bf16_tflops", ctypes.c_float),
                 ("nominal_hbm_gbps", ctypes.c_float), ("nominal_bf16_tflops", ctypes.c_float),
@@ -125,6 +142,7 @@ def exported_symbols():
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_chain", "alt_plan_chain",
+            "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph",
             "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak"]
 
 
@@ -206,6 +224,27 @@ def plan_chain(op_cost, conv_cost, in_layout):
     total = ctypes.c_float()
     _ck(lib().alt_plan_chain(nops, nl, flat(op_cost), flat(conv_cost), in_layout, ins, outs, ctypes.byref(total)))
     return list(ins), list(outs), total.value
+
+
+def plan_graph(kind, in0, in1, op_cost, conv_cost, add_cost, in_layout):
+    """kind/in0/in1: per node; op_cost [nnodes][nl][nl], conv_cost [nnodes+1][nl][nl],
+    add_cost [nnodes].  Returns (stored layout per tensor, read layouts per node, total)."""
+    n, nl = len(kind), len(op_cost[0])
+    i32 = lambda a: (ctypes.c_int32 * len(a))(*[int(v) for v in a])
+    flat = lambda c, m: (ctypes.c_float * (m * nl * nl))(*[float(v) for o in c for r in o for v in r])
+    tl, rl = (ctypes.c_int32 * (n + 1))(), (ctypes.c_int32 * (2 * n))()
+    total = ctypes.c_float()
+    _ck(lib().alt_plan_graph(n, i32(kind), i32(in0), i32(in1), nl, flat(op_cost, n), flat(conv_cost, n + 1),
+                             (ctypes.c_float * n)(*[float(v) for v in add_cost]), in_layout, tl, rl,
+                             ctypes.byref(total)))
+    return list(tl), [list(rl[2 * i:2 * i + 2]) for i in range(n)], total.value
+
+
+def graph_node(kind, in0, in1=0, relu=0, conv=None):
+    nd = GraphNode(kind, in0, in1, relu)
+    if conv is not None:
+        nd.conv = conv
+    return nd
 
 
 # ------------------------------------------------------------------ descriptors ----
@@ -359,6 +398,18 @@ class Handle:
         plan = ChainPlan()
         o = self._opts(arena, arena_bytes, max_trials, warmup, reps, 0, stream)
         _ck(lib().alt_tune_chain(self._h, arr, len(ops), ctypes.byref(_as_layout(in_layout)),
+                                 ctypes.byref(o), ctypes.byref(plan)), self._h)
+        return plan
+
+    def eltwise_add(self, dtype, numel, a, b, y, relu=False, stream=None):
+        _ck(lib().alt_eltwise_add(self._h, dtype, ctypes.c_int64(numel), _ptr(a), _ptr(b), _ptr(y), int(bool(relu)),
+                                  _stream(stream)), self._h)
+
+    def tune_graph(self, nodes, in_layout, arena, arena_bytes, max_trials=0, warmup=3, reps=20, stream=None):
+        arr = (GraphNode * len(nodes))(*nodes)
+        plan = GraphPlan()
+        o = self._opts(arena, arena_bytes, max_trials, warmup, reps, 0, stream)
+        _ck(lib().alt_tune_graph(self._h, arr, len(nodes), ctypes.byref(_as_layout(in_layout)),
                                  ctypes.byref(o), ctypes.byref(plan)), self._h)
         return plan
 

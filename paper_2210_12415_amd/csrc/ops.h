@@ -32,6 +32,10 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
 bool dconv_round_robin_xcds();
 hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st);
 
+// eltwise.hip
+alt_status_t eltwise_add(alt_handle_t h, int dtype, int64_t numel, const void *a, const void *b, void *y, int relu,
+                         hipStream_t st);
+
 alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
                           const float *bias, void *y, Problem *pb);
 alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B, void *C,

@@ -659,6 +659,252 @@ alt_status_t alt_tune_chain(alt_handle_t h, const alt_conv_desc_t *ops, int nops
     return ALT_OK;
 }
 
+// ---- graphs: layout propagation through element-wise operators (Section 4.2) -------------
+
+alt_status_t alt_plan_graph(int nnodes, const int32_t *kind, const int32_t *in0, const int32_t *in1, int nl,
+                            const float *op_cost, const float *conv_cost, const float *add_cost, int in_layout,
+                            int32_t *tensor_layout, int32_t *read_layout, float *total)
+{
+    if (!kind || !in0 || !in1 || !op_cost || !conv_cost || !add_cost || !tensor_layout || !read_layout || !total)
+        return ALT_INVALID_ARG;
+    if (nnodes < 1 || nnodes > ALT_MAX_GRAPH || nl < 1 || nl > ALT_MAX_CANDIDATES || in_layout < 0 || in_layout >= nl)
+        return ALT_INVALID_ARG;
+    for (int i = 0; i < nnodes; ++i) {
+        if (kind[i] != ALT_NODE_CONV && kind[i] != ALT_NODE_ADD) return ALT_INVALID_ARG;
+        if (in0[i] < 0 || in0[i] > i) return ALT_INVALID_ARG;
+        if (kind[i] == ALT_NODE_ADD && (in1[i] < 0 || in1[i] > i)) return ALT_INVALID_ARG;
+    }
+    auto OC = [&](int i, int a, int b) { return (double)op_cost[((size_t)i * nl + a) * nl + b]; };
+    auto CC = [&](int t, int a, int b) { return a == b ? 0.0 : (double)conv_cost[((size_t)t * nl + a) * nl + b]; };
+    // Every assignment of a stored layout to the node outputs (tensor 0 is given).  With the
+    // stored layouts fixed the nodes are independent: a convolution picks the cheapest layout to
+    // read (conversion + kernel), a sum reads both inputs in the layout it writes.
+    std::vector<int> s(nnodes + 1, 0), rd(nnodes * 2, -1), best_s, best_rd;
+    s[0] = in_layout;
+    double best = INFINITY;
+    long long combos = 1;
+    for (int i = 0; i < nnodes; ++i) combos *= nl;
+    for (long long c = 0; c < combos; ++c) {
+        long long r = c;
+        for (int i = 0; i < nnodes; ++i) { s[i + 1] = (int)(r % nl); r /= nl; }
+        double tot = 0.0;
+        for (int i = 0; i < nnodes && tot < best; ++i) {
+            const int out = s[i + 1];
+            if (kind[i] == ALT_NODE_CONV) {
+                double m = INFINITY;
+                int arg = -1;
+                for (int a = 0; a < nl; ++a) {
+                    const double v = CC(in0[i], s[in0[i]], a) + OC(i, a, out);
+                    if (v < m) { m = v; arg = a; }
+                }
+                rd[i * 2] = arg; rd[i * 2 + 1] = -1;
+                tot += m;
+            } else {
+                rd[i * 2] = out; rd[i * 2 + 1] = out;
+                tot += (double)add_cost[i] + CC(in0[i], s[in0[i]], out) + CC(in1[i], s[in1[i]], out);
+            }
+        }
+        if (tot < best) { best = tot; best_s = s; best_rd = rd; }
+    }
+    if (!(best < INFINITY)) return ALT_UNSUPPORTED;
+    for (int t = 0; t <= nnodes; ++t) tensor_layout[t] = best_s[t];
+    for (int i = 0; i < nnodes * 2; ++i) read_layout[i] = best_rd[i];
+    *total = (float)best;
+    return ALT_OK;
+}
+
+alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int nnodes, const alt_layout_t *in_layout,
+                            const alt_tune_opts_t *opts, alt_graph_plan_t *plan)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!nodes || !in_layout || !opts || !plan) return fail(h, ALT_INVALID_ARG, "null argument");
+    if (nnodes < 1 || nnodes > ALT_MAX_GRAPH) return fail(h, ALT_INVALID_ARG, "graph size out of range");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    if (!opts->arena) return fail(h, ALT_INVALID_ARG, "tuning needs an arena");
+    hipStream_t st = (hipStream_t)opts->stream;
+    const int nl = kNumEdgeLayouts;
+    std::memset(plan, 0, sizeof *plan);
+
+    // shape and element type of every tensor
+    struct Tensor { int64_t shape[4]; int dtype; bool known, consumed; };
+    std::vector<Tensor> T(nnodes + 1);
+    for (auto &t : T) { t.known = false; t.consumed = false; }
+    auto same = [](const Tensor &a, const int64_t *sh, int dt) {
+        return a.shape[0] == sh[0] && a.shape[1] == sh[1] && a.shape[2] == sh[2] && a.shape[3] == sh[3] && a.dtype == dt;
+    };
+    for (int i = 0; i < nnodes; ++i) {
+        const alt_graph_node_t &nd = nodes[i];
+        if (nd.kind != ALT_NODE_CONV && nd.kind != ALT_NODE_ADD) return fail(h, ALT_INVALID_ARG, "node %d: bad kind", i);
+        if (nd.in0 < 0 || nd.in0 > i || (nd.kind == ALT_NODE_ADD && (nd.in1 < 0 || nd.in1 > i)))
+            return fail(h, ALT_INVALID_ARG, "node %d reads a tensor that is not produced before it", i);
+        if (nd.kind == ALT_NODE_CONV) {
+            const int64_t xs[4] = {nd.conv.N, nd.conv.C, nd.conv.H, nd.conv.W};
+            int64_t o[4];
+            if (alt_conv2d_output_shape(&nd.conv, o) != ALT_OK) return fail(h, ALT_INVALID_ARG, "node %d: bad shape", i);
+            Tensor &in = T[nd.in0];
+            if (!in.known) { std::memcpy(in.shape, xs, sizeof xs); in.dtype = nd.conv.in_dtype; in.known = true; }
+            else if (!same(in, xs, nd.conv.in_dtype)) return fail(h, ALT_SHAPE_MISMATCH, "node %d does not fit the tensor it reads", i);
+            in.consumed = true;
+            std::memcpy(T[i + 1].shape, o, sizeof o);
+            T[i + 1].dtype = nd.conv.out_dtype;
+            T[i + 1].known = true;
+        } else {
+            Tensor &a = T[nd.in0], &b = T[nd.in1];
+            if (!a.known && b.known) a = b;
+            if (!b.known && a.known) { const bool c = b.consumed; b = a; b.consumed = c; }
+            if (!a.known || !same(a, b.shape, b.dtype)) return fail(h, ALT_SHAPE_MISMATCH, "node %d adds tensors of different shape or type", i);
+            a.consumed = b.consumed = true;
+            T[i + 1] = a;
+            T[i + 1].consumed = false;
+        }
+    }
+    alt_layout_t L[kNumEdgeLayouts];
+    for (int j = 0; j < nl; ++j) alt_layout_parse(kEdgeLayouts[j], &L[j]);
+    int in_idx = -1;
+    for (int j = 0; j < nl; ++j)
+        if (layout_text(&L[j]) == layout_text(in_layout)) in_idx = j;
+    if (in_idx < 0) return fail(h, ALT_UNSUPPORTED, "graph input layout is not one of the planner's layouts");
+
+    size_t max_t = 0, max_w = 16, max_ws = 0;
+    int64_t max_k = 1;
+    for (auto &t : T) max_t = std::max<size_t>(max_t, (size_t)(t.shape[0] * t.shape[1] * t.shape[2] * t.shape[3]) * dtype_size((alt_dtype_t)t.dtype));
+    for (int i = 0; i < nnodes; ++i)
+        if (nodes[i].kind == ALT_NODE_CONV) {
+            max_w = std::max(max_w, conv_bytes_w(&nodes[i].conv));
+            max_ws = std::max(max_ws, std::min<size_t>(conv_ws_budget(&nodes[i].conv), (size_t)64 << 20));
+            max_k = std::max(max_k, nodes[i].conv.K);
+        }
+    Arena ar{(char *)opts->arena, opts->arena_bytes, 0};
+    void *x0 = ar.take(max_t), *x1 = ar.take(max_t), *w0 = ar.take(max_w), *w1 = ar.take(max_w), *y = ar.take(max_t);
+    float *bias = (float *)ar.take((size_t)max_k * 4);
+    if (!x0 || !x1 || !w0 || !w1 || !y || !bias) return fail(h, ALT_WORKSPACE_TOO_SMALL, "arena too small for the graph");
+    size_t ws_bytes = std::min(max_ws, ar.size - ((ar.used + 255) & ~(size_t)255));
+    void *ws = ar.take(ws_bytes);
+    if (!ws) ws_bytes = 0;
+    Timer tm;
+    if (!tm.ok) return fail(h, ALT_HIP_ERROR, "cannot create events");
+    alt_status_t s;
+    if ((s = fill_random(h, x0, max_t, 1, T[0].dtype, st)) != ALT_OK) return s;
+    if ((s = fill_random(h, x1, max_t, 4, T[0].dtype, st)) != ALT_OK) return s;
+    if ((s = fill_random(h, w0, max_w, 2, T[0].dtype, st)) != ALT_OK) return s;
+    if ((s = fill_random(h, bias, (size_t)max_k * 4, 3, ALT_F32, st)) != ALT_OK) return s;
+
+    std::vector<float> op_cost((size_t)nnodes * nl * nl, INFINITY), conv_cost((size_t)(nnodes + 1) * nl * nl, INFINITY);
+    std::vector<float> add_cost(nnodes, 0.f);
+    std::vector<int> op_var((size_t)nnodes * nl * nl, -1);
+    int nconv = 0;
+    for (int i = 0; i < nnodes; ++i) nconv += nodes[i].kind == ALT_NODE_CONV;
+    const int per_pair = opts->max_trials > 0 ? std::max(1, opts->max_trials / (std::max(nconv, 1) * nl * nl)) : 8;
+    alt_layout_t plain_x;
+    alt_layout_parse("NCHW->NCHW", &plain_x);
+    std::string err;
+    // conversions of every consumed tensor
+    for (int t = 0; t <= nnodes; ++t) {
+        if (!T[t].consumed) continue;
+        const int esz = (int)dtype_size((alt_dtype_t)T[t].dtype);
+        for (int a = 0; a < nl; ++a) {
+            if (kEdgeBlock[a] && T[t].shape[1] % kEdgeBlock[a]) continue;
+            conv_cost[((size_t)t * nl + a) * nl + a] = 0.f;
+            BoundLayout ba;
+            if ((s = bind_layout(&L[a], 4, T[t].shape, &ba, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+            for (int b = 0; b < nl; ++b) {
+                if (a == b || (kEdgeBlock[b] && T[t].shape[1] % kEdgeBlock[b])) continue;
+                BoundLayout bb;
+                if ((s = bind_layout(&L[b], 4, T[t].shape, &bb, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+                float us = 0.f;
+                s = measure(h, tm, st, opt_warmup(opts), opt_reps(opts), [&] { return transform_bound(h, esz, ba, x0, bb, y, st); }, &us);
+                if (s != ALT_OK) return s;
+                ++plan->trials;
+                conv_cost[((size_t)t * nl + a) * nl + b] = us;
+            }
+        }
+    }
+    for (int i = 0; i < nnodes; ++i) {
+        if (nodes[i].kind == ALT_NODE_ADD) {
+            const Tensor &t = T[i + 1];
+            const int64_t numel = t.shape[0] * t.shape[1] * t.shape[2] * t.shape[3];
+            float us = 0.f;
+            s = measure(h, tm, st, opt_warmup(opts), opt_reps(opts), [&] { return eltwise_add(h, t.dtype, numel, x0, x1, y, nodes[i].relu, st); }, &us);
+            if (s != ALT_OK) return s;
+            ++plan->trials;
+            add_cost[i] = us;
+            continue;
+        }
+        const alt_conv_desc_t &op = nodes[i].conv;
+        const int64_t xs[4] = {op.N, op.C, op.H, op.W};
+        for (int a = 0; a < nl; ++a) {
+            if (kEdgeBlock[a] && op.C % kEdgeBlock[a]) continue;
+            BoundLayout bs, bd;
+            if ((s = bind_layout(&plain_x, 4, xs, &bs, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+            if ((s = bind_layout(&L[a], 4, xs, &bd, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+            if ((s = transform_bound(h, (int)dtype_size(op.in_dtype), bs, x0, bd, x1, st)) != ALT_OK) return s;
+            for (int b = 0; b < nl; ++b) {
+                if (kEdgeBlock[b] && op.K % kEdgeBlock[b]) continue;
+                alt_conv_desc_t d = op;
+                d.variant = -1;
+                d.x_layout = L[a];
+                d.y_layout = L[b];
+                alt_layout_parse(kEdgeWeights[a], &d.w_layout);
+                if ((s = alt_pack_weights(h, &d, w0, w1, st)) != ALT_OK) return s;
+                float us = INFINITY;
+                int v = -1;
+                s = tune_variants_conv(h, &d, x1, w1, bias, y, ws, ws_bytes, st, tm, opt_warmup(opts), opt_reps(opts),
+                                       per_pair, &plan->trials, &us, &v);
+                if (s != ALT_OK) return s;
+                if (v < 0) continue;
+                op_cost[((size_t)i * nl + a) * nl + b] = us;
+                op_var[((size_t)i * nl + a) * nl + b] = v;
+                h->cache[conv_key(h, &d)] = TuneEntry{v, us};
+                ++h->cache_gen;
+            }
+        }
+    }
+    std::vector<int32_t> kind(nnodes), i0(nnodes), i1(nnodes), tl(nnodes + 1), rl(nnodes * 2);
+    for (int i = 0; i < nnodes; ++i) { kind[i] = nodes[i].kind; i0[i] = nodes[i].in0; i1[i] = nodes[i].kind == ALT_NODE_ADD ? nodes[i].in1 : 0; }
+    float total = 0.f;
+    s = alt_plan_graph(nnodes, kind.data(), i0.data(), i1.data(), nl, op_cost.data(), conv_cost.data(), add_cost.data(), in_idx,
+                       tl.data(), rl.data(), &total);
+    if (s != ALT_OK) return fail(h, s, "no feasible plan");
+    plan->nnodes = nnodes;
+    plan->total_us = total;
+    for (int t = 0; t <= nnodes; ++t) plan->tensor_layout[t] = L[tl[t]];
+    auto CC = [&](int t, int a, int b) { return a == b ? 0.f : conv_cost[((size_t)t * nl + a) * nl + b]; };
+    double dflt = 0.0;
+    for (int i = 0; i < nnodes; ++i) {
+        const int nin = nodes[i].kind == ALT_NODE_ADD ? 2 : 1;
+        for (int j = 0; j < nin; ++j) {
+            const int t = j == 0 ? i0[i] : i1[i];
+            const int r = rl[i * 2 + j];
+            plan->read_layout[i][j] = L[r];
+            plan->convert[i][j] = r != tl[t];
+            plan->convert_us[i][j] = CC(t, tl[t], r);
+        }
+        if (nodes[i].kind == ALT_NODE_CONV) {
+            const int a = rl[i * 2], b = tl[i + 1];
+            alt_conv_desc_t d = nodes[i].conv;
+            d.x_layout = L[a];
+            d.y_layout = L[b];
+            alt_layout_parse(kEdgeWeights[a], &d.w_layout);
+            d.variant = op_var[((size_t)i * nl + a) * nl + b];
+            plan->conv[i] = d;
+            plan->node_us[i] = op_cost[((size_t)i * nl + a) * nl + b];
+            dflt += op_cost[((size_t)i * nl + 0) * nl + 0];
+        } else {
+            plan->node_us[i] = add_cost[i];
+            dflt += add_cost[i];
+        }
+    }
+    if (in_idx != 0) {
+        // the all-NCHW graph converts the input once per consumer that reads it
+        for (int i = 0; i < nnodes; ++i) {
+            if (i0[i] == 0) dflt += CC(0, in_idx, 0);
+            if (nodes[i].kind == ALT_NODE_ADD && i1[i] == 0) dflt += CC(0, in_idx, 0);
+        }
+    }
+    plan->default_total_us = (float)dflt;
+    return ALT_OK;
+}
+
 alt_status_t alt_cache_save(alt_handle_t h, const char *path)
 {
     if (!h) return ALT_INVALID_ARG;

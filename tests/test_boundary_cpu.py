@@ -128,6 +128,60 @@ def test_plan_chain_known_shortest_paths():
     assert abs(total - best) < 1e-4
 
 
+def test_plan_graph_residual_block_rules():
+    """Layout propagation over a residual block (conv, conv, add of the block input):
+    the sum reads both inputs in the layout it writes, a tensor with two consumers is
+    stored once, conversions appear exactly on the edges whose layouts differ."""
+    inf = float("inf")
+    K, A = alt.NODE_CONV, alt.NODE_ADD
+    kind, in0, in1 = [K, K, A], [0, 1, 2], [0, 0, 0]
+    zero = [[0, 0], [0, 0]]
+    # convolutions are fast only in layout 1; conversions cost 2; the input arrives in layout 0
+    op = [[[20, 20], [20, 5]], [[20, 20], [20, 5]], zero]
+    cv = [[[0, 2], [2, 0]], [[0, 2], [2, 0]], [[0, 3], [3, 0]], [[0, 2], [2, 0]]]
+    tl, rl, total = alt.plan_graph(kind, in0, in1, op, cv, [0, 0, 1.0], 0)
+    # input converted once per consumer that reads layout 1: conv0 (2) and the sum (2; converting
+    # the second convolution's output instead would cost 3)
+    assert tl == [0, 1, 1, 1] and rl == [[1, -1], [1, -1], [1, 1]] and total == 2 + 5 + 5 + 2 + 1
+    # expensive conversions: everything stays in the input layout
+    cvx = [[[0, 100], [100, 0]]] * 4
+    tl, rl, total = alt.plan_graph(kind, in0, in1, op, cvx, [0, 0, 1.0], 0)
+    assert tl == [0, 0, 0, 0] and rl == [[0, -1], [0, -1], [0, 0]] and total == 41.0
+    # the input already in layout 1: no conversion anywhere
+    tl, rl, total = alt.plan_graph(kind, in0, in1, op, cv, [0, 0, 1.0], 1)
+    assert tl == [1, 1, 1, 1] and total == 11.0
+    # impossible combinations are never chosen
+    op_inf = [[[inf, inf], [inf, 5]], [[inf, 7], [inf, inf]], zero]
+    tl, rl, total = alt.plan_graph(kind, in0, in1, op_inf, cv, [0, 0, 1.0], 0)
+    assert rl[0][0] == 1 and tl[1] == 1 and rl[1][0] == 0 and tl[2] == 1
+    # brute force over every assignment on random tables, three layouts, two-consumer tensors
+    rng = np.random.RandomState(3)
+    kind, in0, in1 = [K, K, A, K, A], [0, 1, 2, 3, 4], [0, 0, 0, 0, 1]
+    n, nl = 5, 3
+    opc = rng.uniform(1, 10, (n, nl, nl)).astype(np.float32)
+    cvc = rng.uniform(0.5, 4, (n + 1, nl, nl)).astype(np.float32)
+    addc = rng.uniform(0.5, 2, n).astype(np.float32)
+    cc = lambda t, a, b: 0.0 if a == b else float(cvc[t][a][b])
+    best = inf
+    for s in itertools.product(range(nl), repeat=n):
+        st = (2,) + s
+        tot = 0.0
+        for i in range(n):
+            if kind[i] == K:
+                tot += min(cc(in0[i], st[in0[i]], a) + float(opc[i][a][st[i + 1]]) for a in range(nl))
+            else:
+                tot += float(addc[i]) + cc(in0[i], st[in0[i]], st[i + 1]) + cc(in1[i], st[in1[i]], st[i + 1])
+        best = min(best, tot)
+    tl, rl, total = alt.plan_graph(kind, in0, in1, opc.tolist(), cvc.tolist(), addc.tolist(), 2)
+    assert abs(total - best) < 1e-3
+    for i in range(n):
+        if kind[i] == A:
+            assert rl[i] == [tl[i + 1], tl[i + 1]]       # element-wise: output in the layout it reads
+    # malformed graphs are refused
+    with pytest.raises(alt.AltError):
+        alt.plan_graph([K], [1], [0], [zero], [zero, zero], [0], 0)     # reads its own output
+
+
 def test_calls_without_gpu_fail_loudly_not_silently():
     import torch
     if torch.cuda.is_available():

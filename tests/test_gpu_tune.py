@@ -141,3 +141,88 @@ def test_chain_plan_executes_to_oracle_result(h, arena):
     got = from_layout(host(cur, np.uint16), cur_shape, "NCHW", _phys_name(plan.op[2].y_layout, "NCHW"))
     # bf16 rounding between layers: compare values, allow the ulp-level differences rounding order causes
     assert rel_err(bf16_bits_to_f32(got), bf16_bits_to_f32(ref)) <= TOL[alt.BF16]
+
+
+def run_graph_plan(h, plan, nodes, x, weights, biases, arena, in_layout="NCHW->NCHW"):
+    """Executes a graph plan through the library: conversions where the plan has them,
+    convolutions in their chosen layouts, sums on flat buffers.  Returns the last
+    tensor (device, bf16 bits), its logical shape and its layout."""
+    tensors = [(dev(x.reshape(-1)), x.shape)]
+    for i, nd in enumerate(nodes):
+        ins = []
+        for j in range(2 if nd.kind == alt.NODE_ADD else 1):
+            t = nd.in0 if j == 0 else nd.in1
+            buf, shape = tensors[t]
+            if plan.convert[i][j]:
+                nxt = torch.empty_like(buf)
+                h.layout_transform(alt.BF16, shape, plan.tensor_layout[t], buf, plan.read_layout[i][j], nxt)
+                buf = nxt
+            ins.append((buf, shape))
+        if nd.kind == alt.NODE_CONV:
+            d = plan.conv[i]
+            wd = torch.empty_like(dev(weights[i].reshape(-1)))
+            h.pack_weights(d, dev(weights[i].reshape(-1)), wd)
+            oshape = h.conv2d_output_shape(d)
+            y = torch.empty(int(np.prod(oshape)), dtype=torch.int16, device="cuda")
+            h.conv2d(d, ins[0][0], wd, y, bias=dev(biases[i]) if biases[i] is not None else None, workspace=arena,
+                     ws_bytes=arena.numel())
+            tensors.append((y, oshape))
+        else:
+            y = torch.empty_like(ins[0][0])
+            h.eltwise_add(alt.BF16, y.numel(), ins[0][0], ins[1][0], y, relu=bool(nd.relu))
+            tensors.append((y, ins[0][1]))
+    return tensors[-1][0], tensors[-1][1], plan.tensor_layout[len(nodes)]
+
+
+def test_residual_block_plan_executes_to_oracle_result(h, arena):
+    """A ResNet basic block (conv3x3+bias+ReLU -> conv3x3+bias -> + block input -> ReLU), bf16
+    tensors: layouts propagate through the sum, the block input has two consumers."""
+    N, C, H = 2, 64, 28
+    mk = lambda relu: alt.conv_desc(N, C, H, H, C, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                    epilogue=alt.EPI_BIAS | (alt.EPI_RELU if relu else 0))
+    nodes = [alt.graph_node(alt.NODE_CONV, 0, conv=mk(True)), alt.graph_node(alt.NODE_CONV, 1, conv=mk(False)),
+             alt.graph_node(alt.NODE_ADD, 2, 0, relu=1)]
+    plan = h.tune_graph(nodes, "NCHW->NCHW", arena, arena.numel(), max_trials=0, warmup=2, reps=5)
+    assert plan.nnodes == 3 and plan.total_us <= plan.default_total_us * 1.0001
+    name = lambda l: _phys_name(l, "NCHW")
+    # the sum reads both inputs and writes its output in one layout
+    assert name(plan.read_layout[2][0]) == name(plan.read_layout[2][1]) == name(plan.tensor_layout[3])
+    # conversions exactly where the stored layout differs from the one read
+    for i, nd in enumerate(nodes):
+        for j in range(2 if nd.kind == alt.NODE_ADD else 1):
+            t = nd.in0 if j == 0 else nd.in1
+            assert bool(plan.convert[i][j]) == (name(plan.tensor_layout[t]) != name(plan.read_layout[i][j]))
+    for i in (0, 1):
+        assert name(plan.conv[i].x_layout) == name(plan.read_layout[i][0])
+        assert name(plan.conv[i].y_layout) == name(plan.tensor_layout[i + 1])
+    # the direct kernels make channel-contiguous layouts the choice for these convolutions
+    assert name(plan.conv[0].x_layout) != "NCHW"
+    x = f32_to_bf16_bits(normal_f32(181, (N, C, H, H)))
+    ws = [f32_to_bf16_bits(normal_f32(182 + i, (C, C, 3, 3), std=0.05)) for i in range(2)] + [None]
+    bs = [normal_f32(190 + i, (C,), std=0.1) for i in range(2)] + [None]
+    t1 = oracle.conv2d(x, ws[0], stride=1, pad=1, bias=bs[0], relu=True, out_bf16=True)
+    t2 = oracle.conv2d(t1, ws[1], stride=1, pad=1, bias=bs[1], relu=False, out_bf16=True)
+    ref = oracle.eltwise_add(t2, x, relu=True)
+    out, oshape, olayout = run_graph_plan(h, plan, nodes, x, ws, bs, arena)
+    got = from_layout(host(out, np.uint16), oshape, "NCHW", name(olayout))
+    assert rel_err(bf16_bits_to_f32(got), bf16_bits_to_f32(ref)) <= TOL[alt.BF16]
+    assert (bf16_bits_to_f32(got) >= 0).all()
+
+
+@pytest.mark.parametrize("dtype", [alt.BF16, alt.F32])
+def test_eltwise_add_bit_exact(h, dtype):
+    """y = a + b, relu(a + b), relu(a); whole vectors, ragged tails, one element, none."""
+    for numel in [0, 1, 7, 8, 1000, 64 * 56 * 56 + 3]:
+        a = normal_f32(201, (max(numel, 1),))[:numel]
+        b = normal_f32(202, (max(numel, 1),), std=2.0)[:numel]
+        if dtype == alt.BF16:
+            a, b = f32_to_bf16_bits(a), f32_to_bf16_bits(b)
+        npdt = np.uint16 if dtype == alt.BF16 else np.float32
+        tdt = torch.int16 if dtype == alt.BF16 else torch.float32
+        pad = lambda v: dev(np.concatenate([v, np.zeros(16, dtype=npdt)]))      # 16-byte aligned, never empty
+        for bb, relu in [(b, False), (b, True), (None, True)]:
+            y = torch.full((numel + 16,), 77, dtype=tdt, device="cuda")
+            h.eltwise_add(dtype, numel, pad(a), None if bb is None else pad(bb), y, relu=relu)
+            got = host(y, npdt)
+            assert np.array_equal(got[:numel], oracle.eltwise_add(a, bb, relu=relu)), (numel, relu)
+            assert (host(y, npdt)[numel:] == host(torch.full((16,), 77, dtype=tdt), npdt)).all()   # nothing past the end

@@ -236,3 +236,77 @@ def test_bf16_rounding_matches_library_cast(oracle):
     assert oracle.f32_to_bf16_bits(np.array([1.01171875], dtype=np.float32))[0] == 0x3F82
     nan = oracle.f32_to_bf16_bits(np.array([np.nan], dtype=np.float32))[0]
     assert (nan & 0x7F80) == 0x7F80 and (nan & 0x7F) != 0
+
+
+def _bf16_exact(bits):
+    """bf16 bit pattern -> exact Fraction."""
+    from fractions import Fraction
+    bits = int(bits)
+    sign = -1 if bits >> 15 else 1
+    e, m = (bits >> 7) & 0xff, bits & 0x7f
+    if e == 0:
+        return sign * Fraction(m, 1 << 7) * Fraction(2) ** (-126)
+    return sign * (1 + Fraction(m, 1 << 7)) * Fraction(2) ** (e - 127)
+
+
+def _round_to_bf16_exact(q):
+    """Nearest bf16 (ties to even) of an exact rational, by search over the two neighbours."""
+    from fractions import Fraction
+    if q == 0:
+        return 0
+    sign = 0x8000 if q < 0 else 0
+    a = abs(q)
+    lo, hi = 0, 0x7f7f                      # finite positive patterns are ordered like their values
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if _bf16_exact(mid) <= a:
+            lo = mid
+        else:
+            hi = mid
+    dl, dh = a - _bf16_exact(lo), _bf16_exact(hi) - a
+    pick = lo if dl < dh or (dl == dh and lo % 2 == 0) else hi
+    return sign | pick
+
+
+def test_eltwise_add_bf16_is_one_exact_rounding(oracle):
+    """Pin: exact rational arithmetic on every pair of a few hundred patterns that
+    include wide exponent gaps, ties, cancellation and subnormals."""
+    rng = np.random.RandomState(5)
+    pats = set(rng.randint(0x0080, 0x7f00, 40).tolist())
+    pats |= {0x0000, 0x8000, 0x0001, 0x007f, 0x0080, 0x3f80, 0x3f81, 0x3fff, 0x4000, 0x3b80, 0x3380, 0x2f80, 0x2b80,
+             0x2380, 0x1f80, 0x7f7f, 0x7f00, 0x3f00, 0x3e80}
+    pats |= {p | 0x8000 for p in list(pats)[:20]}
+    pats = sorted(pats)
+    a = np.array([p for p in pats for _ in pats], dtype=np.uint16)
+    b = np.array([q for _ in pats for q in pats], dtype=np.uint16)
+    got = oracle.eltwise_add(a, b)
+    for i in range(a.size):
+        q = _bf16_exact(a[i]) + _bf16_exact(b[i])
+        if abs(q) >= _bf16_exact(0x7f7f) + (_bf16_exact(0x7f7f) - _bf16_exact(0x7f7e)) / 2:
+            continue                         # overflows to infinity
+        want = _round_to_bf16_exact(q)
+        if q == 0:
+            assert got[i] & 0x7fff == 0
+        else:
+            assert got[i] == want, (hex(a[i]), hex(b[i]), hex(got[i]), hex(want))
+
+
+def test_eltwise_add_closed_forms(oracle):
+    x = uniform_f32(91, (3, 5, 7))
+    y = uniform_f32(92, (3, 5, 7))
+    z = np.zeros_like(x)
+    assert np.array_equal(oracle.eltwise_add(x, z), x)                      # a + 0 = a
+    assert np.array_equal(oracle.eltwise_add(x, None), x)
+    assert np.array_equal(oracle.eltwise_add(x, y), oracle.eltwise_add(y, x))   # commutative
+    assert np.array_equal(oracle.eltwise_add(x, y), (x.astype(np.float64) + y).astype(np.float32))  # one fp32 rounding
+    r = oracle.eltwise_add(x, y, relu=True)
+    assert (r >= 0).all() and np.array_equal(r, np.maximum(oracle.eltwise_add(x, y), 0))
+    assert np.array_equal(oracle.eltwise_add(x, -x), z)                     # exact cancellation
+    xb = f32_to_bf16_bits(x)
+    assert np.array_equal(oracle.eltwise_add(xb, None), xb)                 # bf16 identity keeps the bits
+    nb = f32_to_bf16_bits(-np.abs(x))
+    assert (oracle.eltwise_add(nb, None, relu=True) & 0x7fff == 0).all()     # relu of negatives is zero
+    # torch's bf16 addition (fp32 add, one rounding) as a library special case
+    yb = f32_to_bf16_bits(y)
+    t = (torch.from_numpy(bf16_bits_to_f32(xb)).bfloat16() + torch.from_numpy(bf16_bits_to_f32(yb)).bfloat16())
+    assert np.array_equal(oracle.eltwise_add(xb, yb), f32_to_bf16_bits(t.float().numpy()))
