@@ -341,8 +341,10 @@ typedef struct {
 /* Layout choice for a small graph of convolutions and element-wise sums, e.g.
  * a residual block (Section 4.2: layouts propagate from the complex operators
  * through the simple ones; a tensor with several consumers is stored once, in
- * its producer's layout, and a conversion operator is inserted in front of each
- * consumer that reads another layout).  An ALT_NODE_ADD reads both inputs and
+ * its producer's layout, and a conversion operator is inserted in front of the
+ * consumers that read another layout, one per target layout: consumers that
+ * read the same converted copy share it, and convert_us is zero for all but the
+ * first of them).  An ALT_NODE_ADD reads both inputs and
  * writes its output in one layout.  nodes[i] may only read the graph input and
  * outputs of nodes before it; the last node's output is the graph's.  Measures
  * every convolution under every (input, output) layout pair, every conversion
@@ -356,7 +358,8 @@ alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int n
  * alt_graph_node_t, per node.  op_cost[i][a][b] ([nnodes][nl][nl], convolutions
  * only): latency reading layout a, writing layout b.  conv_cost[t][a][b]
  * ([nnodes + 1][nl][nl]): latency of converting tensor t from a to b (the
- * diagonal is taken as zero).  add_cost[i]: latency of sum node i.  Infinite
+ * diagonal is taken as zero; a tensor converted to one layout for several
+ * consumers is charged once).  add_cost[i]: latency of sum node i.  Infinite
  * entries mark impossible combinations.  Returns the stored layout index of
  * every tensor ([nnodes + 1], entry 0 = in_layout), the layout index every
  * node reads each input in ([nnodes][2], -1 for unused) and the total. */

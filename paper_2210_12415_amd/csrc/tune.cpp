@@ -676,32 +676,53 @@ alt_status_t alt_plan_graph(int nnodes, const int32_t *kind, const int32_t *in0,
     }
     auto OC = [&](int i, int a, int b) { return (double)op_cost[((size_t)i * nl + a) * nl + b]; };
     auto CC = [&](int t, int a, int b) { return a == b ? 0.0 : (double)conv_cost[((size_t)t * nl + a) * nl + b]; };
-    // Every assignment of a stored layout to the node outputs (tensor 0 is given).  With the
-    // stored layouts fixed the nodes are independent: a convolution picks the cheapest layout to
-    // read (conversion + kernel), a sum reads both inputs in the layout it writes.
-    std::vector<int> s(nnodes + 1, 0), rd(nnodes * 2, -1), best_s, best_rd;
+    // Every assignment of a stored layout to the node outputs (tensor 0 is given) and of a layout
+    // each convolution reads; a sum reads both inputs in the layout it writes.  A tensor converted
+    // to one layout is paid for once, however many consumers read that copy.  Beyond 2^24
+    // assignments the convolutions' read layouts are no longer enumerated but picked greedily in
+    // node order (cheapest conversion + kernel given the copies already made).
+    std::vector<int> s(nnodes + 1, 0), rd(nnodes * 2, -1), best_s, best_rd, conv_nodes;
+    for (int i = 0; i < nnodes; ++i)
+        if (kind[i] == ALT_NODE_CONV) conv_nodes.push_back(i);
     s[0] = in_layout;
     double best = INFINITY;
+    double space = 1.0;
+    for (int i = 0; i < nnodes + (int)conv_nodes.size(); ++i) space *= nl;
+    const bool exact = space <= (double)(1 << 24);
+    const int nvar = nnodes + (exact ? (int)conv_nodes.size() : 0);
     long long combos = 1;
-    for (int i = 0; i < nnodes; ++i) combos *= nl;
+    for (int i = 0; i < nvar; ++i) combos *= nl;
+    std::vector<int> want(nnodes, -1);
     for (long long c = 0; c < combos; ++c) {
         long long r = c;
         for (int i = 0; i < nnodes; ++i) { s[i + 1] = (int)(r % nl); r /= nl; }
+        if (exact)
+            for (int i : conv_nodes) { want[i] = (int)(r % nl); r /= nl; }
         double tot = 0.0;
+        unsigned paid[ALT_MAX_GRAPH + 1] = {0};
+        auto convert = [&](int t, int to) {
+            if (s[t] == to || (paid[t] >> to & 1u)) return 0.0;
+            return CC(t, s[t], to);
+        };
         for (int i = 0; i < nnodes && tot < best; ++i) {
             const int out = s[i + 1];
             if (kind[i] == ALT_NODE_CONV) {
                 double m = INFINITY;
                 int arg = -1;
                 for (int a = 0; a < nl; ++a) {
-                    const double v = CC(in0[i], s[in0[i]], a) + OC(i, a, out);
+                    if (exact && a != want[i]) continue;
+                    const double v = convert(in0[i], a) + OC(i, a, out);
                     if (v < m) { m = v; arg = a; }
                 }
+                if (arg >= 0) paid[in0[i]] |= 1u << arg;
                 rd[i * 2] = arg; rd[i * 2 + 1] = -1;
                 tot += m;
             } else {
                 rd[i * 2] = out; rd[i * 2 + 1] = out;
-                tot += (double)add_cost[i] + CC(in0[i], s[in0[i]], out) + CC(in1[i], s[in1[i]], out);
+                tot += (double)add_cost[i] + convert(in0[i], out);
+                paid[in0[i]] |= 1u << out;
+                tot += convert(in1[i], out);
+                paid[in1[i]] |= 1u << out;
             }
         }
         if (tot < best) { best = tot; best_s = s; best_rd = rd; }
@@ -877,7 +898,14 @@ alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int n
             const int r = rl[i * 2 + j];
             plan->read_layout[i][j] = L[r];
             plan->convert[i][j] = r != tl[t];
-            plan->convert_us[i][j] = CC(t, tl[t], r);
+            bool shared = false;                 // an earlier consumer already has this copy made
+            for (int i2 = 0; i2 <= i && !shared; ++i2)
+                for (int j2 = 0; j2 < 2 && !shared; ++j2) {
+                    if (i2 == i && j2 >= j) break;
+                    const bool reads = j2 == 0 ? i0[i2] == t : (nodes[i2].kind == ALT_NODE_ADD && i1[i2] == t);
+                    shared = reads && rl[i2 * 2 + j2] == r;
+                }
+            plan->convert_us[i][j] = shared ? 0.f : CC(t, tl[t], r);
         }
         if (nodes[i].kind == ALT_NODE_CONV) {
             const int a = rl[i * 2], b = tl[i + 1];
@@ -894,13 +922,7 @@ alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int n
             dflt += add_cost[i];
         }
     }
-    if (in_idx != 0) {
-        // the all-NCHW graph converts the input once per consumer that reads it
-        for (int i = 0; i < nnodes; ++i) {
-            if (i0[i] == 0) dflt += CC(0, in_idx, 0);
-            if (nodes[i].kind == ALT_NODE_ADD && i1[i] == 0) dflt += CC(0, in_idx, 0);
-        }
-    }
+    if (in_idx != 0) dflt += CC(0, in_idx, 0);     // the all-NCHW graph converts its input once
     plan->default_total_us = (float)dflt;
     return ALT_OK;
 }

@@ -140,9 +140,8 @@ def test_plan_graph_residual_block_rules():
     op = [[[20, 20], [20, 5]], [[20, 20], [20, 5]], zero]
     cv = [[[0, 2], [2, 0]], [[0, 2], [2, 0]], [[0, 3], [3, 0]], [[0, 2], [2, 0]]]
     tl, rl, total = alt.plan_graph(kind, in0, in1, op, cv, [0, 0, 1.0], 0)
-    # input converted once per consumer that reads layout 1: conv0 (2) and the sum (2; converting
-    # the second convolution's output instead would cost 3)
-    assert tl == [0, 1, 1, 1] and rl == [[1, -1], [1, -1], [1, 1]] and total == 2 + 5 + 5 + 2 + 1
+    # the input is converted to layout 1 once and that copy serves both conv0 and the sum
+    assert tl == [0, 1, 1, 1] and rl == [[1, -1], [1, -1], [1, 1]] and total == 2 + 5 + 5 + 1
     # expensive conversions: everything stays in the input layout
     cvx = [[[0, 100], [100, 0]]] * 4
     tl, rl, total = alt.plan_graph(kind, in0, in1, op, cvx, [0, 0, 1.0], 0)
@@ -163,15 +162,25 @@ def test_plan_graph_residual_block_rules():
     addc = rng.uniform(0.5, 2, n).astype(np.float32)
     cc = lambda t, a, b: 0.0 if a == b else float(cvc[t][a][b])
     best = inf
+    # (every stored layout and every layout each convolution reads; a copy of a tensor in one
+    # layout is paid for once)
+    convs = [i for i in range(n) if kind[i] == K]
     for s in itertools.product(range(nl), repeat=n):
         st = (2,) + s
-        tot = 0.0
-        for i in range(n):
-            if kind[i] == K:
-                tot += min(cc(in0[i], st[in0[i]], a) + float(opc[i][a][st[i + 1]]) for a in range(nl))
-            else:
-                tot += float(addc[i]) + cc(in0[i], st[in0[i]], st[i + 1]) + cc(in1[i], st[in1[i]], st[i + 1])
-        best = min(best, tot)
+        for reads in itertools.product(range(nl), repeat=len(convs)):
+            made, tot = set(), 0.0
+            def conv_to(t, b):
+                if st[t] == b or (t, b) in made:
+                    return 0.0
+                made.add((t, b))
+                return float(cvc[t][st[t]][b])
+            for i in range(n):
+                if kind[i] == K:
+                    a = reads[convs.index(i)]
+                    tot += conv_to(in0[i], a) + float(opc[i][a][st[i + 1]])
+                else:
+                    tot += float(addc[i]) + conv_to(in0[i], st[i + 1]) + conv_to(in1[i], st[i + 1])
+            best = min(best, tot)
     tl, rl, total = alt.plan_graph(kind, in0, in1, opc.tolist(), cvc.tolist(), addc.tolist(), 2)
     assert abs(total - best) < 1e-3
     for i in range(n):

@@ -148,15 +148,21 @@ def run_graph_plan(h, plan, nodes, x, weights, biases, arena, in_layout="NCHW->N
     convolutions in their chosen layouts, sums on flat buffers.  Returns the last
     tensor (device, bf16 bits), its logical shape and its layout."""
     tensors = [(dev(x.reshape(-1)), x.shape)]
+    copies = {}                                   # (tensor, layout) -> converted copy, shared by its consumers
     for i, nd in enumerate(nodes):
         ins = []
         for j in range(2 if nd.kind == alt.NODE_ADD else 1):
             t = nd.in0 if j == 0 else nd.in1
             buf, shape = tensors[t]
             if plan.convert[i][j]:
-                nxt = torch.empty_like(buf)
-                h.layout_transform(alt.BF16, shape, plan.tensor_layout[t], buf, plan.read_layout[i][j], nxt)
-                buf = nxt
+                key = (t, _phys_name(plan.read_layout[i][j], "NCHW"))
+                if key not in copies:
+                    assert plan.convert_us[i][j] > 0
+                    copies[key] = torch.empty_like(buf)
+                    h.layout_transform(alt.BF16, shape, plan.tensor_layout[t], buf, plan.read_layout[i][j], copies[key])
+                else:
+                    assert plan.convert_us[i][j] == 0      # charged once
+                buf = copies[key]
             ins.append((buf, shape))
         if nd.kind == alt.NODE_CONV:
             d = plan.conv[i]
