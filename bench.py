@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="skip the extra sections")
+    ap.add_argument("--sections", default="all",
+                    help="comma-separated extra sections to run besides the headline step: f32, transforms, gemm, b1, "
+                         "scaled, chain, graph, peaks (default all; --quick runs none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
@@ -61,6 +64,13 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
+    all_sections = ("f32", "transforms", "gemm", "b1", "scaled", "chain", "graph", "peaks")
+    chosen = set(all_sections) if args.sections == "all" else set(x for x in args.sections.split(",") if x)
+    if chosen - set(all_sections):
+        raise SystemExit("bench.py: unknown section(s) %s" % ", ".join(sorted(chosen - set(all_sections))))
+
+    def want(name):
+        return not args.quick and name in chosen
     alt.lib()                                   # fails loudly if libalt.so is missing
     dev = torch.device("cuda:0")
     h = alt.Handle()
@@ -324,7 +334,7 @@ def main():
                  graph_replay_ms_per_step=round(head["graph_ms_per_step"], 5),
                  stream_launch_ms_per_step=round(head["stream_ms_per_step"], 5))
 
-    if not args.quick:
+    if want("f32"):
         # the same step with fp32 output (twice the output bytes)
         l32 = load_layers(alt.F32, "f32_out")
         r32 = measure_step(l32)
@@ -346,7 +356,7 @@ def main():
     if args.calib_copy:
         h.get_peak(arena[:512 << 20], 512 << 20)
 
-    if not args.quick:
+    if want("transforms"):
         # -------------------------------------------------- conversion operator ----
         tr = []
         for shp in TRANSFORM_SHAPES:
@@ -388,6 +398,7 @@ def main():
             frac_hbm_peak=round(2.0 * numel * 2 / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4))
         del s0, s1
 
+    if want("gemm"):
         # ------------------------------------------------------------------ gemm ----
         gm = []
         for g in BERT_GEMMS + [BERT_QKT]:
@@ -413,6 +424,7 @@ def main():
                            tuner_trials=rep.trials, layout_us=dict(zip(names, [round(u, 2) for u in lus]))))
         extra["gemm_bert"] = gm
 
+    if want("b1"):
         # ------------------------------------------------------- batch-1 layers ----
         l1 = prepare_layers(1, alt.F32, 0)
         b1 = []
@@ -426,6 +438,7 @@ def main():
         extra["per_layer_b1"] = b1
         del l1
 
+    if want("scaled"):
         # ---------------------------------------- scaled: 16x batch, bf16 output ----
         scaled = []
         for L in RESNET_LAYERS[:1] + RESNET_LAYERS[2:3]:
@@ -446,6 +459,7 @@ def main():
             del xs, wsd, ys
         extra["conv_scaled_batch256_nhwc_bf16out"] = scaled
 
+    if want("chain"):
         # ------------------------------------------------------------------ chain ----
         ops = [alt.conv_desc(16, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
                              in_dtype=alt.BF16, out_dtype=alt.BF16,
@@ -461,6 +475,7 @@ def main():
                               variants=[h.conv2d_variant_name(plan.op[i], plan.op[i].variant) for i in range(plan.nops)],
                               measurements=plan.trials)
 
+    if want("graph"):
         # ------------------------------------------------- residual block (graph) ----
         # conv3x3+bias+ReLU -> conv3x3+bias -> + block input -> ReLU, 64 channels, 56x56, batch 16, bf16 tensors:
         # layouts propagate through the sum, the block input has two consumers
@@ -491,6 +506,7 @@ def main():
             add_relu_us=round(add_us, 2), add_relu_GBps=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6), 1),
             add_relu_frac_hbm_peak=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6) / PEAK_HBM_GBPS, 4))
 
+    if want("peaks"):
         pk = h.get_peak(arena, arena.numel())
         extra["attainable"] = dict(copy_GBps=round(float(pk.copy_gbps), 1),
                                    mfma_bf16_TFLOPs=round(float(pk.mfma_bf16_tflops), 1),
