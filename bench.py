@@ -397,6 +397,19 @@ def main():
             us=round(us, 1), GBps=round(2.0 * numel * 2 / 1e9 / (us * 1e-6), 1),
             frac_hbm_peak=round(2.0 * numel * 2 / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4))
         del s0, s1
+        # the unfold primitive (overlapped tiles of 14 + 2 rows along H of an NHWC tensor, Section 4.1.2): expands the data
+        ushape = (16, 56, 56, 64)
+        oshape = alt.unfold_shape(ushape, 1, 16, 14)
+        u0 = torch.randint(-30000, 30000, (int(np.prod(ushape)),), dtype=torch.int16, device=dev)
+        u1 = torch.empty(int(np.prod(oshape)), dtype=torch.int16, device=dev)
+        gr = capture(lambda st: h.unfold(alt.BF16, ushape, 1, 16, 14, u0, u1, stream=st), 20)
+        us = graph_timed(gr, 20)
+        del gr
+        moved = (u0.numel() + u1.numel()) * 2
+        extra["unfold_16x56x56x64_bf16_H_tiles_of_16_every_14"] = dict(
+            out_shape=list(oshape), us=round(us, 2), GBps=round(moved / 1e9 / (us * 1e-6), 1),
+            frac_hbm_peak=round(moved / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4), note="cache-resident buffers")
+        del u0, u1
 
     if want("gemm"):
         # ------------------------------------------------------------------ gemm ----

@@ -304,6 +304,23 @@ alt_status_t alt_tune_chain(alt_handle_t h, const alt_conv_desc_t *ops, int nops
 alt_status_t alt_plan_chain(int nops, int nl, const float *op_cost, const float *conv_cost,
                             int in_layout, int *out_in_idx, int *out_out_idx, float *out_total);
 
+/* ---- unfold primitive: overlapped tiling (Section 4.1.2, Eq. 1) ---------- */
+
+/* Shape after unfolding dimension `dim` of `shape` (ndim entries, ndim <
+ * ALT_MAX_RANK) into tiles of B elements every S elements: the dimension is
+ * replaced by (T, B) with T = ceil((D - B) / S) + 1 (1 if D <= B); out_shape
+ * gets ndim + 1 entries.  Host only. */
+alt_status_t alt_unfold_shape(int ndim, const int64_t *shape, int dim, int64_t B, int64_t S, int64_t *out_shape);
+
+/* dst[..., t, b, ...] = src[..., t*S + b, ...] over a row-major tensor of
+ * `shape`, zero bits where t*S + b runs past the dimension (the last tile of a
+ * non-dividing tiling).  This is the conversion that materialises the
+ * overlapped-tile layout of a convolution input: it expands the data by about
+ * B / S.  src and dst are device buffers that do not overlap; bits are moved
+ * unchanged.  Asynchronous on `stream`. */
+alt_status_t alt_unfold(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape, int dim, int64_t B,
+                        int64_t S, const void *src, void *dst, void *stream);
+
 /* ---- graphs of operators: layout propagation (Section 4.2) ---------------- */
 
 /* y[i] = a[i] + b[i] (b may be null: y = a), then max(., 0) if relu != 0, for

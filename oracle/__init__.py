@@ -224,6 +224,22 @@ def unfold_1d(src, B, S):
     return dst
 
 
+def unfold(x, dim, B, S):
+    """The unfold primitive (Section 4.1.2) on dimension `dim` of an array: every
+    1-D line along `dim` goes through unfold_1d.  Values pass through float64
+    (exact for float32 and for integers below 2^53); returns float64 of shape
+    x.shape[:dim] + (T, B) + x.shape[dim+1:]."""
+    x = np.asarray(x)
+    moved = np.moveaxis(x, dim, -1)
+    lines = moved.reshape(-1, x.shape[dim])
+    T = unfold_tiles(x.shape[dim], B, S)
+    out = np.empty((lines.shape[0], T, B), dtype=np.float64)
+    for j in range(lines.shape[0]):
+        out[j] = unfold_1d(lines[j], B, S)
+    out = out.reshape(moved.shape[:-1] + (T, B))
+    return np.moveaxis(np.moveaxis(out, -2, dim), -1, dim + 1)
+
+
 def unfold_access(V, i, r, B, S, M):
     t, w = ctypes.c_int64(), ctypes.c_int64()
     lib().orc_unfold_access(ctypes.c_int64(V), ctypes.c_int64(i), ctypes.c_int64(r),

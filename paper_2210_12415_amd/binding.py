@@ -142,7 +142,7 @@ def exported_symbols():
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_chain", "alt_plan_chain",
-            "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph",
+            "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
             "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak"]
 
 
@@ -224,6 +224,12 @@ def plan_chain(op_cost, conv_cost, in_layout):
     total = ctypes.c_float()
     _ck(lib().alt_plan_chain(nops, nl, flat(op_cost), flat(conv_cost), in_layout, ins, outs, ctypes.byref(total)))
     return list(ins), list(outs), total.value
+
+
+def unfold_shape(shape, dim, B, S):
+    out = (ctypes.c_int64 * (len(shape) + 1))()
+    _ck(lib().alt_unfold_shape(len(shape), _i64(shape), dim, ctypes.c_int64(B), ctypes.c_int64(S), out))
+    return tuple(out)
 
 
 def plan_graph(kind, in0, in1, op_cost, conv_cost, add_cost, in_layout):
@@ -400,6 +406,10 @@ class Handle:
         _ck(lib().alt_tune_chain(self._h, arr, len(ops), ctypes.byref(_as_layout(in_layout)),
                                  ctypes.byref(o), ctypes.byref(plan)), self._h)
         return plan
+
+    def unfold(self, dtype, shape, dim, B, S, src, dst, stream=None):
+        _ck(lib().alt_unfold(self._h, dtype, len(shape), _i64(shape), dim, ctypes.c_int64(B), ctypes.c_int64(S),
+                             _ptr(src), _ptr(dst), _stream(stream)), self._h)
 
     def eltwise_add(self, dtype, numel, a, b, y, relu=False, stream=None):
         _ck(lib().alt_eltwise_add(self._h, dtype, ctypes.c_int64(numel), _ptr(a), _ptr(b), _ptr(y), int(bool(relu)),

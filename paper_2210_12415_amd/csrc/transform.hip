@@ -176,6 +176,29 @@ __global__ __launch_bounds__(kThreads) void permute_general_kernel(GeneralParams
     }
 }
 
+// The unfold primitive on one dimension of a row-major tensor seen as [outer][D][inner]:
+// dst[o][t][b][i] = src[o][t*S + b][i], zero where t*S + b >= D.  One thread per VB-byte
+// piece of the inner run (VB = 16 when the run allows, else the element size).
+template <int VB>
+__global__ __launch_bounds__(kThreads) void unfold_kernel(const char *src, char *dst, int64_t total, uint32_t vec_inner,
+                                                          uint32_t B, uint32_t T, int64_t D, int64_t S)
+{
+    using V = typename Word<VB>::type;
+    for (int64_t v = blockIdx.x * (int64_t)kThreads + threadIdx.x; v < total; v += (int64_t)gridDim.x * kThreads) {
+        const int64_t q = v / vec_inner;
+        const uint32_t i = (uint32_t)(v - q * vec_inner);
+        const int64_t q2 = q / B;
+        const uint32_t b = (uint32_t)(q - q2 * B);
+        const int64_t o = q2 / T;
+        const uint32_t t = (uint32_t)(q2 - o * T);
+        const int64_t e = (int64_t)t * S + b;
+        V w;
+        std::memset(&w, 0, sizeof w);
+        if (e < D) w = *(const V *)(src + ((o * D + e) * vec_inner + i) * VB);
+        store_through(dst + v * VB, w);
+    }
+}
+
 // Cuts every logical dimension at the union of both layouts' boundaries.
 // Returns false when the boundaries do not nest (e.g. blocks of 12 and 8).
 bool refine(const BoundLayout &s, const BoundLayout &d, std::vector<Piece> *out)
@@ -470,5 +493,51 @@ extern "C" alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, 
     auto &v = h->tmemo->entries;
     if (v.size() < kEntries) v.push_back(e);
     else { v[h->tmemo->next] = e; h->tmemo->next = (h->tmemo->next + 1) % kEntries; }
+    return ALT_OK;
+}
+
+extern "C" alt_status_t alt_unfold_shape(int ndim, const int64_t *shape, int dim, int64_t B, int64_t S, int64_t *out_shape)
+{
+    if (!shape || !out_shape || ndim < 1 || ndim >= ALT_MAX_RANK || dim < 0 || dim >= ndim || B < 1 || S < 1) return ALT_INVALID_ARG;
+    for (int d = 0; d < ndim; ++d)
+        if (shape[d] < 1) return ALT_INVALID_ARG;
+    const int64_t D = shape[dim], num = D - B;
+    const int64_t T = (num <= 0 ? 0 : (num + S - 1) / S) + 1;
+    for (int d = 0, o = 0; d < ndim; ++d) {
+        if (d == dim) { out_shape[o++] = T; out_shape[o++] = B; }
+        else out_shape[o++] = shape[d];
+    }
+    return ALT_OK;
+}
+
+extern "C" alt_status_t alt_unfold(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape, int dim, int64_t B,
+                                   int64_t S, const void *src, void *dst, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (dtype != ALT_F32 && dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_unfold: bad dtype");
+    int64_t os[ALT_MAX_RANK];
+    if (alt_unfold_shape(ndim, shape, dim, B, S, os) != ALT_OK) return fail(h, ALT_INVALID_ARG, "alt_unfold: bad shape, dimension, tile size or stride");
+    if (!src || !dst) return fail(h, ALT_INVALID_ARG, "alt_unfold: null buffer");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const int64_t esz = (int64_t)dtype_size(dtype);
+    int64_t outer = 1, inner = 1;
+    for (int d = 0; d < dim; ++d) outer *= shape[d];
+    for (int d = dim + 1; d < ndim; ++d) inner *= shape[d];
+    const int64_t D = shape[dim], T = os[dim];
+    if (B > 0x7fffffff || T > 0x7fffffff || inner * esz > 0x7fffffff) return fail(h, ALT_UNSUPPORTED, "alt_unfold: extent too large");
+    const int64_t out_bytes = outer * T * B * inner * esz, in_bytes = outer * D * inner * esz;
+    const char *a = (const char *)src;
+    char *b = (char *)dst;
+    if (a < b + out_bytes && b < a + in_bytes) return fail(h, ALT_INVALID_ARG, "alt_unfold: src and dst must not overlap");
+    const bool wide = (inner * esz) % 16 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0;
+    const int vb = wide ? 16 : (int)esz;
+    const uint32_t vec_inner = (uint32_t)(inner * esz / vb);
+    const int64_t total = outer * T * B * vec_inner;
+    const unsigned blocks = (unsigned)std::min<int64_t>((total + kThreads - 1) / kThreads, 256 * 32);
+    hipStream_t st = (hipStream_t)stream;
+    if (vb == 16) hipLaunchKernelGGL(unfold_kernel<16>, dim3(blocks), dim3(kThreads), 0, st, a, b, total, vec_inner, (uint32_t)B, (uint32_t)T, D, S);
+    else if (vb == 4) hipLaunchKernelGGL(unfold_kernel<4>, dim3(blocks), dim3(kThreads), 0, st, a, b, total, vec_inner, (uint32_t)B, (uint32_t)T, D, S);
+    else hipLaunchKernelGGL(unfold_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, a, b, total, vec_inner, (uint32_t)B, (uint32_t)T, D, S);
+    ALT_CHECK_HIP(h, hipGetLastError());
     return ALT_OK;
 }

@@ -117,3 +117,50 @@ def test_transform_errors(h):
     with pytest.raises(alt.AltError) as e:
         h.layout_transform(7, (2, 4, 2, 4), "NCHW->NCHW", a, "NCHW->NHWC", b)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("case", [((3, 12, 8), 1, 4, 2), ((2, 3, 10), 2, 6, 4), ((9, 5), 0, 3, 3), ((2, 11, 3), 1, 4, 3),
+                                  ((4, 6), 1, 8, 2), ((2, 8, 20, 24), 2, 6, 4), ((2, 8, 20, 24), 3, 10, 8)],
+                         ids=lambda c: "x".join(map(str, c[0])) + "_d%d_B%d_S%d" % c[1:])
+@pytest.mark.parametrize("dtype", [alt.BF16, alt.F32])
+def test_unfold_bit_exact(h, case, dtype):
+    """The unfold primitive on the device against the oracle's: tiles overlap by B - S, the
+    ragged last tile is zero-filled, nothing is written past the output."""
+    shape, dim, B, S = case
+    numel = int(np.prod(shape))
+    ids = np.arange(1, numel + 1, dtype=np.int64).reshape(shape)        # distinct, non-zero, exact in float64
+    want = oracle.unfold(ids, dim, B, S).astype(np.int64)
+    oshape = alt.unfold_shape(shape, dim, B, S)
+    assert tuple(want.shape) == oshape
+    npdt = np.uint16 if dtype == alt.BF16 else np.uint32
+    src = special_bit_patterns(31, shape, 16 if dtype == alt.BF16 else 32)   # NaN payloads, -0, denormals, random bits
+    expect = np.where(want > 0, src.reshape(-1)[np.maximum(want, 1) - 1], 0).astype(npdt)
+    n_out = int(np.prod(oshape))
+    whole, dst = canary_dev(n_out, npdt)
+    h.unfold(dtype, shape, dim, B, S, dev(src.reshape(-1)), dst)
+    got = host(dst, npdt)[:n_out].reshape(oshape)
+    assert np.array_equal(got, expect)
+    assert canary_ok(whole, n_out)
+    # Eq. 1 of the paper on the data: element V*i + r of the dimension is at (tile, within)
+    if (shape[dim] - B) % S == 0 and B >= 3:
+        M, V = 3, 1
+        per_tile = (B - M) // V + 1
+        if S == V * per_tile:
+            line = np.moveaxis(src, dim, -1).reshape(-1, shape[dim])[0]
+            unf = np.moveaxis(np.moveaxis(got, dim + 1, -1), dim, -2).reshape(-1, oshape[dim], B)[0]
+            for i in range((shape[dim] - M) // V + 1):
+                for r in range(M):
+                    t, w = oracle.unfold_access(V, i, r, B, S, M)
+                    assert unf[t][w] == line[V * i + r]
+
+
+def test_unfold_rejects_bad_arguments(h):
+    a = torch.zeros(64, dtype=torch.float32, device="cuda")
+    b = torch.zeros(256, dtype=torch.float32, device="cuda")
+    for shape, dim, B, S in [((4, 4), 2, 2, 1), ((4, 4), 0, 0, 1), ((4, 4), 0, 2, 0)]:
+        with pytest.raises(alt.AltError) as e:
+            h.unfold(alt.F32, shape, dim, B, S, a, b)
+        assert e.value.status == 1
+    with pytest.raises(alt.AltError) as e:
+        h.unfold(alt.F32, (4, 4), 0, 2, 1, a, a)                         # overlapping buffers
+    assert e.value.status == 1

@@ -227,3 +227,22 @@ def test_transform_gemm_operand_is_matrix_transpose(oracle):
     A = uniform_f32(5, (6, 10))
     got = oracle.layout_transform(A, (6, 10), [], oracle.seq_from_string("MK->KM", (6, 10)))
     assert np.array_equal(got.reshape(10, 6), A.T)
+
+
+def test_unfold_nd_against_sliding_windows(oracle):
+    """N-D unfold against numpy's sliding windows (written independently of the oracle):
+    tile t of a dimension is the window starting at t*S; the ragged last tile is zero-filled."""
+    rng = np.random.RandomState(11)
+    for shape, dim, B, S in [((3, 12, 4), 1, 4, 2), ((2, 3, 10), 2, 6, 4), ((9, 5), 0, 3, 3), ((2, 11, 3), 1, 4, 3),
+                             ((4, 6), 1, 8, 2)]:
+        x = rng.randint(-1000, 1000, shape).astype(np.float64)
+        got = oracle.unfold(x, dim, B, S)
+        D = shape[dim]
+        T = 1 if D <= B else -(-(D - B) // S) + 1
+        padded = np.concatenate([x, np.zeros(shape[:dim] + ((T - 1) * S + B - D,) + shape[dim + 1:])], axis=dim) \
+            if (T - 1) * S + B > D else x
+        win = np.lib.stride_tricks.sliding_window_view(padded, B, axis=dim)      # window axis goes last
+        win = np.take(win, np.arange(T) * S, axis=dim)
+        want = np.moveaxis(win, -1, dim + 1)
+        assert got.shape == shape[:dim] + (T, B) + shape[dim + 1:]
+        assert np.array_equal(got, want)
