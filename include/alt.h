@@ -174,10 +174,19 @@ typedef struct {
     alt_layout_t x_layout;        /* of logical (N, C, H, W) */
     alt_layout_t w_layout;        /* of logical (K, C, R, S) */
     alt_layout_t y_layout;        /* of logical (N, K, OH, OW) */
+    int32_t groups;               /* 0 or 1: ordinary; g > 1: output channel k reads only the C/g input channels of
+                                     group k / (K/g) (C and K multiples of g), w is logical (K, C/g, R, S);
+                                     g = C = K is the depth-wise convolution */
+    int32_t reserved;             /* 0 */
 } alt_conv_desc_t;
 
 /* y[n,k,oh,ow] = sum_{c,r,s} x[n,c,oh*stride-pad+r*dil, ow*stride-pad+s*dil] * w[k,c,r,s]
  * (cross-correlation, zeros outside the input), OH = floor((H+2pad-dil(R-1)-1)/stride)+1.
+ * With groups = g > 1 (the group-wise and depth-wise C2D of Section 6.1) c runs over the
+ * C/g channels of k's group: x channel (k / (K/g)) * (C/g) + c.  Grouped problems run on
+ * the implicit-GEMM kernels with one group per grid plane (channel blocks of a blocked
+ * layout must not straddle groups); depth-wise ones on kernels of their own, which have no
+ * variants: the tuner and alt_conv2d_variant_* do not take them.
  * x, w, y are device pointers holding the tensors under the descriptor's
  * layouts; `w` is what alt_pack_weights wrote (or any buffer already in
  * w_layout).  bias may be NULL without ALT_EPI_BIAS.  `workspace` (device,

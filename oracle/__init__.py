@@ -270,9 +270,22 @@ def _conv_desc(x, w, stride, pad, dil, out_bf16, bias, relu):
     return d
 
 
-def conv2d(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, relu=False):
-    """x: (N,C,H,W), w: (K,C,R,S); float32 arrays, or uint16 arrays of bf16
-    bits.  Returns (N,K,OH,OW) float32, or uint16 bf16 bits if out_bf16."""
+def conv2d(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, relu=False, groups=1):
+    """x: (N,C,H,W), w: (K,C/groups,R,S); float32 arrays, or uint16 arrays of bf16
+    bits.  Returns (N,K,OH,OW) float32, or uint16 bf16 bits if out_bf16.
+    groups > 1 (the group-wise and depth-wise C2D of Section 6.1): output
+    channels [g*K/groups, (g+1)*K/groups) are the convolution of input channels
+    [g*C/groups, (g+1)*C/groups) with their own filters, i.e. `groups`
+    independent convolutions side by side, which is how it is computed here."""
+    if groups > 1:
+        C, K = x.shape[1], w.shape[0]
+        if C % groups or K % groups or w.shape[1] != C // groups:
+            raise ValueError("conv2d: groups must divide C and K, w is (K, C/groups, R, S)")
+        cg, kg = C // groups, K // groups
+        parts = [conv2d(x[:, g * cg:(g + 1) * cg], w[g * kg:(g + 1) * kg], stride, pad, dil, out_bf16,
+                        None if bias is None else np.asarray(bias)[g * kg:(g + 1) * kg], relu)
+                 for g in range(groups)]
+        return np.concatenate(parts, axis=1)
     x = np.ascontiguousarray(x)
     w = np.ascontiguousarray(w)
     d = _conv_desc(x, w, stride, pad, dil, out_bf16, bias, relu)

@@ -55,7 +55,8 @@ class ConvDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("N", "C", "H", "W", "K", "R", "S")] + \
                [(n, ctypes.c_int32) for n in ("stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
                                               "in_dtype", "out_dtype", "epilogue", "variant")] + \
-               [("x_layout", Layout), ("w_layout", Layout), ("y_layout", Layout)]
+               [("x_layout", Layout), ("w_layout", Layout), ("y_layout", Layout),
+                ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class GemmDesc(ctypes.Structure):
@@ -257,10 +258,11 @@ def graph_node(kind, in0, in1=0, relu=0, conv=None):
 
 def conv_desc(N, C, H, W, K, R, S, stride=1, pad=0, dil=1, in_dtype=BF16, out_dtype=F32,
               epilogue=0, variant=-1, x_layout="NCHW->NCHW", w_layout="OIHW->OIHW",
-              y_layout="NCHW->NCHW"):
+              y_layout="NCHW->NCHW", groups=1):
     d = ConvDesc(N, C, H, W, K, R, S, stride, stride, pad, pad, dil, dil, in_dtype, out_dtype,
                  epilogue, variant)
     d.x_layout, d.w_layout, d.y_layout = _as_layout(x_layout), _as_layout(w_layout), _as_layout(y_layout)
+    d.groups = groups
     return d
 
 

@@ -1,0 +1,163 @@
+// Depth-wise 2-D convolution (one filter per channel: groups = C = K), the
+// memory-bound member of the C2D family of Section 6.1 of the paper:
+//   y[n,c,oh,ow] = sum_{r,s} x[n,c,oh*stride-pad+r*dil, ow*stride-pad+s*dil] * w[c,0,r,s]
+// fp32 accumulation over the taps in (r, s) order, then bias, ReLU and the
+// output rounding.  There is no reduction over channels, so nothing for the
+// matrix cores to do: the kernels are a gather over the filter window, and
+// the data layout decides how wide the accesses are.
+//
+//  * vector kernel: bf16 tensors whose channel is contiguous in runs of at
+//    least eight on activations, weights and output (NHWC or NCHW[x]c with
+//    channel-last weights): a thread owns eight channels of one output pixel,
+//    every access is 16 bytes;
+//  * element kernel: any separable layout; a thread owns one output element,
+//    threads run along the output's contiguous dimension.
+#include <hip/hip_runtime.h>
+
+#include "igemm.h"
+#include "ops.h"
+
+namespace alt {
+namespace {
+
+constexpr int kDwThreads = 256;
+
+struct DwParams {
+    const void *x, *w;
+    const float *bias;
+    void *y;
+    int32_t N, C, H, W, R, S, OH, OW;
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t epilogue, in_bf16, out_bf16, chan_fast;
+    Dim2 xn, xc, xh, xw, wo, wr, ws, yn, yk, yh, yw;
+};
+
+__device__ __forceinline__ float load_elem(const void *p, int64_t off, int bf16)
+{
+    if (bf16) return __builtin_bit_cast(float, (uint32_t)((const uint16_t *)p)[off] << 16);
+    return ((const float *)p)[off];
+}
+
+__global__ __launch_bounds__(kDwThreads) void dwconv_elem_kernel(const DwParams p)
+{
+    const int64_t total = (int64_t)p.N * p.C * p.OH * p.OW;
+    for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
+        int n, c, oh, ow;
+        int64_t r = e;
+        if (p.chan_fast) {
+            c = (int)(r % p.C); r /= p.C;
+            ow = (int)(r % p.OW); r /= p.OW;
+            oh = (int)(r % p.OH); n = (int)(r / p.OH);
+        } else {
+            ow = (int)(r % p.OW); r /= p.OW;
+            oh = (int)(r % p.OH); r /= p.OH;
+            c = (int)(r % p.C); n = (int)(r / p.C);
+        }
+        const int64_t xb = dim2_off(p.xn, n) + dim2_off(p.xc, c), wb = dim2_off(p.wo, c);
+        float acc = 0.f;
+        for (int fr = 0; fr < p.R; ++fr) {
+            const int ih = oh * p.stride_h - p.pad_h + fr * p.dil_h;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            for (int fs = 0; fs < p.S; ++fs) {
+                const int iw = ow * p.stride_w - p.pad_w + fs * p.dil_w;
+                if ((unsigned)iw >= (unsigned)p.W) continue;
+                acc += load_elem(p.x, xb + dim2_off(p.xh, ih) + dim2_off(p.xw, iw), p.in_bf16) *
+                       load_elem(p.w, wb + dim2_off(p.wr, fr) + dim2_off(p.ws, fs), p.in_bf16);
+            }
+        }
+        if (p.epilogue & ALT_EPI_BIAS) acc += p.bias[c];
+        if (p.epilogue & ALT_EPI_RELU) acc = fmaxf(acc, 0.f);
+        const int64_t yo = dim2_off(p.yn, n) + dim2_off(p.yk, c) + dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
+        if (p.out_bf16) ((uint16_t *)p.y)[yo] = f32_to_bf16_rne(acc);
+        else ((float *)p.y)[yo] = acc;
+    }
+}
+
+// bf16 in and out, eight consecutive channels per thread (one 16-byte access per tensor and tap).
+__global__ __launch_bounds__(kDwThreads) void dwconv_vec8_kernel(const DwParams p)
+{
+    typedef uint32_t w4_t __attribute__((ext_vector_type(4)));
+    typedef float f4_t __attribute__((ext_vector_type(4)));
+    const int C8 = p.C >> 3;
+    const int64_t total = (int64_t)p.N * p.OH * p.OW * C8;
+    for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
+        int64_t r = e;
+        const int c = (int)(r % C8) * 8; r /= C8;
+        const int ow = (int)(r % p.OW); r /= p.OW;
+        const int oh = (int)(r % p.OH);
+        const int n = (int)(r / p.OH);
+        const int64_t xb = dim2_off(p.xn, n) + dim2_off(p.xc, c), wb = dim2_off(p.wo, c);
+        // even channels of each pair in lo, odd ones in hi (whole-vector arithmetic throughout)
+        f4_t lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+        for (int fr = 0; fr < p.R; ++fr) {
+            const int ih = oh * p.stride_h - p.pad_h + fr * p.dil_h;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            for (int fs = 0; fs < p.S; ++fs) {
+                const int iw = ow * p.stride_w - p.pad_w + fs * p.dil_w;
+                if ((unsigned)iw >= (unsigned)p.W) continue;
+                const w4_t xv = *(const w4_t *)((const uint16_t *)p.x + xb + dim2_off(p.xh, ih) + dim2_off(p.xw, iw));
+                const w4_t wv = *(const w4_t *)((const uint16_t *)p.w + wb + dim2_off(p.wr, fr) + dim2_off(p.ws, fs));
+                lo += __builtin_bit_cast(f4_t, xv << 16) * __builtin_bit_cast(f4_t, wv << 16);
+                hi += __builtin_bit_cast(f4_t, xv & 0xffff0000u) * __builtin_bit_cast(f4_t, wv & 0xffff0000u);
+            }
+        }
+        if (p.epilogue & ALT_EPI_BIAS) {
+            const f4_t b0 = *(const f4_t *)(p.bias + c), b1 = *(const f4_t *)(p.bias + c + 4);
+            lo += __builtin_shufflevector(b0, b1, 0, 2, 4, 6);
+            hi += __builtin_shufflevector(b0, b1, 1, 3, 5, 7);
+        }
+        if (p.epilogue & ALT_EPI_RELU) {
+            lo = __builtin_elementwise_max(lo, (f4_t){0.f, 0.f, 0.f, 0.f});
+            hi = __builtin_elementwise_max(hi, (f4_t){0.f, 0.f, 0.f, 0.f});
+        }
+        w4_t out;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q] = f32x2_to_bf16x2(lo[q], hi[q]);
+        const int64_t yo = dim2_off(p.yn, n) + dim2_off(p.yk, c) + dim2_off(p.yh, oh) + dim2_off(p.yw, ow);
+        *(w4_t *)((uint16_t *)p.y + yo) = out;
+    }
+}
+
+// eight consecutive channels from a multiple of eight are one contiguous, 16-byte aligned run
+bool chan_runs_of_8(const Dim2 &c, int64_t C, const Dim2 *others, int n_others)
+{
+    const int64_t run = c.f >= C ? C : c.f;
+    if (c.si != 1 || run % 8 || C % 8) return false;
+    if (c.f < C && c.so % 8) return false;
+    for (int i = 0; i < n_others; ++i)
+        if (others[i].so % 8 || others[i].si % 8) return false;
+    return true;
+}
+
+}  // namespace
+
+// pb is the problem of one group (C = K = 1 per group, batch = channels) as conv_problem fills it for
+// a depth-wise descriptor; x/w/y Dim2 entries describe the whole tensors.
+alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t C, hipStream_t st)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const IgemmParams &q = pb.p;
+    DwParams p;
+    std::memset(&p, 0, sizeof p);
+    p.x = q.x; p.w = q.w; p.bias = q.bias; p.y = q.y;
+    p.N = (int32_t)N; p.C = (int32_t)C; p.H = q.H; p.W = q.W; p.R = q.R; p.S = q.S; p.OH = q.OH; p.OW = q.OW;
+    p.stride_h = q.stride_h; p.stride_w = q.stride_w; p.pad_h = q.pad_h; p.pad_w = q.pad_w;
+    p.dil_h = q.dil_h; p.dil_w = q.dil_w;
+    p.epilogue = q.epilogue; p.in_bf16 = pb.dtype == ALT_BF16; p.out_bf16 = q.out_bf16;
+    p.xn = q.xn; p.xc = q.xc; p.xh = q.xh; p.xw = q.xw;
+    p.wo = q.wo; p.wr = q.wr; p.ws = q.ws;
+    p.yn = q.yn; p.yk = q.yk; p.yh = q.yh; p.yw = q.yw;
+    p.chan_fast = q.yk.si == 1;
+    const Dim2 xo[3] = {q.xn, q.xh, q.xw}, wo_[2] = {q.wr, q.ws}, yo[3] = {q.yn, q.yh, q.yw};
+    const bool vec = p.in_bf16 && p.out_bf16 && chan_runs_of_8(q.xc, C, xo, 3) && chan_runs_of_8(q.wo, C, wo_, 2) &&
+                     chan_runs_of_8(q.yk, C, yo, 3) && (uintptr_t)q.x % 16 == 0 && (uintptr_t)q.w % 16 == 0 &&
+                     (uintptr_t)q.y % 16 == 0 && (!(q.epilogue & ALT_EPI_BIAS) || (uintptr_t)q.bias % 16 == 0);
+    const int64_t work = N * q.OH * q.OW * (vec ? C / 8 : C);
+    const unsigned blocks = (unsigned)std::min<int64_t>((work + kDwThreads - 1) / kDwThreads, 256 * 64);
+    if (vec) hipLaunchKernelGGL(dwconv_vec8_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else hipLaunchKernelGGL(dwconv_elem_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+}  // namespace alt

@@ -50,7 +50,7 @@ struct IgemmParams {
     int64_t x_bstride, w_bstride, y_bstride;
     uint32_t x_bytes, w_bytes;   // size of one batch entry of each operand (vector loaders: < 2 GiB)
     uint32_t y_bytes;            // size of one batch entry of the output, 0 if it does not fit 31 bits
-    uint32_t pad0_;
+    int32_t bias_bstride;        // elements between the bias vectors of consecutive batch entries (groups)
     FastDiv fd_ohow, fd_ow, fd_c, fd_s, fd_nc;   // divisions by OH*OW, OW, C, S, Nc
     Dim2 xn, xc, xh, xw;      // activations (N, C, H, W)
     Dim2 wo, wi, wr, ws;      // weights (O, I, R, S)
@@ -234,7 +234,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t 
             const int n = n0 + wn * WTN + j * 32 + (lane & 31);
             const bool n_ok = n < p.Nc;
             const int32_t coff = n_ok ? (to_partial ? n : dim2_off32(p.yk, n)) : 0;
-            const float bv = (n_ok && !to_partial && (p.epilogue & ALT_EPI_BIAS)) ? p.bias[n] : 0.f;
+            const float bv = (n_ok && !to_partial && (p.epilogue & ALT_EPI_BIAS)) ? p.bias[bz * p.bias_bstride + n] : 0.f;
             uint32_t voff[TM][16];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -288,7 +288,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmParams &p, floatx16_t 
         const int n = n0 + wn * WTN + j * 32 + (lane & 31);
         if (n >= p.Nc) continue;
         const int64_t coff = dim2_off(p.yk, n);
-        const float bv = (p.epilogue & ALT_EPI_BIAS) ? p.bias[n] : 0.f;
+        const float bv = (p.epilogue & ALT_EPI_BIAS) ? p.bias[bz * p.bias_bstride + n] : 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll

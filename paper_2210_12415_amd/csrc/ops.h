@@ -12,6 +12,8 @@ struct Problem {
     bool a_vec, a_trans, b_vec, b_trans;   // loaders the operand layouts admit (gather always works)
     bool spatial_split, spatial_ok;
     int64_t x_elems, w_elems;              // elements of one batch entry of each operand
+    int64_t groups;                        // convolution groups (1 for ordinary problems and products)
+    bool depthwise;                        // groups = C = K: runs on dwconv.hip, p describes the whole tensors
 };
 
 extern const int kSplitFactors[];
@@ -31,6 +33,9 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
                  std::string *why);
 bool dconv_round_robin_xcds();
 hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st);
+
+// dwconv.hip
+alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t C, hipStream_t st);
 
 // eltwise.hip
 alt_status_t eltwise_add(alt_handle_t h, int dtype, int64_t numel, const void *a, const void *b, void *y, int relu,

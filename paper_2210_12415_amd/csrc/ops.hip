@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
         const int m = (int)fast_div((uint32_t)r, p.fd_nc), n = (int)(r - (int64_t)m * p.Nc);
         float v = 0.f;
         for (int s = 0; s < p.splitk; ++s) v += p.partial[(int64_t)s * total + e];
-        if (p.epilogue & ALT_EPI_BIAS) v += p.bias[n];
+        if (p.epilogue & ALT_EPI_BIAS) v += p.bias[bz * p.bias_bstride + n];
         if (p.epilogue & ALT_EPI_RELU) v = fmaxf(v, 0.f);
         const int img = (int)fast_div(m, p.fd_ohow), rem = m - img * ohow;
         const int oh = (int)fast_div(rem, p.fd_ow), ow = rem - oh * p.OW;
@@ -259,7 +259,10 @@ alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *
     const int64_t OW = (d->W + 2 * d->pad_w - d->dil_w * (d->S - 1) - 1) / d->stride_w + 1;
     if (d->H + 2 * d->pad_h < d->dil_h * (d->R - 1) + 1 || d->W + 2 * d->pad_w < d->dil_w * (d->S - 1) + 1)
         return fail(h, ALT_INVALID_ARG, "conv2d: kernel larger than padded input");
-    const int64_t xs[4] = {d->N, d->C, d->H, d->W}, wsh[4] = {d->K, d->C, d->R, d->S}, ys[4] = {d->N, d->K, OH, OW};
+    const int64_t G = d->groups > 1 ? d->groups : 1;
+    if (d->groups < 0 || d->C % G || d->K % G) return fail(h, ALT_INVALID_ARG, "conv2d: groups must divide C and K");
+    const int64_t Cg = d->C / G, Kg = d->K / G;
+    const int64_t xs[4] = {d->N, d->C, d->H, d->W}, wsh[4] = {d->K, Cg, d->R, d->S}, ys[4] = {d->N, d->K, OH, OW};
     BoundLayout bx, bw, by;
     std::string err;
     alt_status_t s;
@@ -273,6 +276,8 @@ alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *
         return fail(h, ALT_UNSUPPORTED, "conv2d: problem too large for 32-bit tile indices");
     std::memset(pb, 0, sizeof(*pb));
     pb->dtype = d->in_dtype;
+    pb->groups = G;
+    pb->depthwise = G > 1 && Cg == 1 && Kg == 1;
     IgemmParams &p = pb->p;
     p.x = x; p.w = w; p.bias = bias; p.y = y;
     p.M = (int32_t)(d->N * OH * OW); p.Nc = (int32_t)d->K; p.Kg = (int32_t)(d->C * d->R * d->S);
@@ -293,6 +298,23 @@ alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *
     }
     p.x_bytes = (uint32_t)std::min<int64_t>(bx.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
     p.w_bytes = (uint32_t)std::min<int64_t>(bw.numel * (int64_t)dtype_size(d->in_dtype), 0x7fffffff);
+    if (G > 1 && !pb->depthwise) {
+        // One group per batch entry of the implicit-GEMM kernels: the group's channels start a fixed
+        // number of elements further on in each tensor, which needs whole channel blocks per group.
+        auto group_step = [](const Dim2 &c, int64_t extent, int64_t per_group, int64_t *step) {
+            if (c.f >= extent) { *step = per_group * c.si; return true; }
+            if (per_group % c.f) return false;
+            *step = per_group / c.f * c.so;
+            return true;
+        };
+        int64_t sx, sw, sy;
+        if (!group_step(p.xc, d->C, Cg, &sx) || !group_step(p.wo, d->K, Kg, &sw) || !group_step(p.yk, d->K, Kg, &sy))
+            return fail(h, ALT_UNSUPPORTED, "conv2d: a channel block of a layout straddles two groups");
+        p.C = (int32_t)Cg; p.Nc = (int32_t)Kg; p.Kg = (int32_t)(Cg * d->R * d->S);
+        p.batch = (int32_t)G;
+        p.x_bstride = sx; p.w_bstride = sw; p.y_bstride = sy;
+        p.bias_bstride = (int32_t)Kg;
+    }
     igemm_analyse(pb);
     return ALT_OK;
 }
@@ -454,6 +476,7 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
     Problem pb;
     alt_status_t s = conv_problem(h, d, x, w, bias, y, &pb);
     if (s != ALT_OK) return s;
+    if (pb.depthwise) return depthwise_run(h, pb, d->N, d->C, (hipStream_t)stream);
     int v = pick_variant(h, pb, d->variant, d->variant >= 0 ? std::string() : conv_key(h, d), ws_limit);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_conv2d: no kernel variant applies");
     memo_store(h, d, sizeof *d, sig, ws_limit, pb, v);
@@ -468,6 +491,7 @@ alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d,
     // alignment of real pointers is unknown here: assume 16-byte aligned buffers
     alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
     if (s != ALT_OK) return s;
+    if (pb.depthwise) { *bytes = 0; return ALT_OK; }
     int v = pick_variant(h, pb, d->variant, conv_key(h, d), (size_t)-1);
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
     *bytes = igemm_workspace(pb, kSplits[v % kNumSplits]);
@@ -492,6 +516,7 @@ alt_status_t alt_conv2d_variant_name(alt_handle_t h, const alt_conv_desc_t *d, i
     Problem pb;
     alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
     if (s != ALT_OK) return s;
+    if (pb.depthwise) return fail(h, ALT_UNSUPPORTED, "depth-wise convolutions have no kernel variants");
     std::string why;
     const auto &tab = igemm_table();
     if (!igemm_applicable(pb, tab[variant / kNumSplits], kSplits[variant % kNumSplits], nullptr, &why))
@@ -503,7 +528,9 @@ alt_status_t alt_pack_weights(alt_handle_t h, const alt_conv_desc_t *d, const vo
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !w_oihw || !w_packed) return fail(h, ALT_INVALID_ARG, "alt_pack_weights: null argument");
-    const int64_t wsh[4] = {d->K, d->C, d->R, d->S};
+    const int64_t G = d->groups > 1 ? d->groups : 1;
+    if (d->C % G) return fail(h, ALT_INVALID_ARG, "alt_pack_weights: groups must divide C");
+    const int64_t wsh[4] = {d->K, d->C / G, d->R, d->S};
     alt_layout_t plain;
     alt_layout_parse("OIHW->OIHW", &plain);
     BoundLayout bs, bd;

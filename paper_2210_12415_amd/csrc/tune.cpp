@@ -20,7 +20,8 @@ std::string conv_key(alt_handle_t h, const alt_conv_desc_t *d)
     std::ostringstream o;
     o << "conv|" << h->arch << "|" << d->N << "," << d->C << "," << d->H << "," << d->W << "," << d->K << ","
       << d->R << "," << d->S << "|" << d->stride_h << "," << d->stride_w << "," << d->pad_h << "," << d->pad_w
-      << "," << d->dil_h << "," << d->dil_w << "|" << d->in_dtype << "," << d->out_dtype << "," << d->epilogue
+      << "," << d->dil_h << "," << d->dil_w << "," << (d->groups > 1 ? d->groups : 1) << "|" << d->in_dtype << ","
+      << d->out_dtype << "," << d->epilogue
       << "|" << layout_text(&d->x_layout) << "|" << layout_text(&d->w_layout) << "|" << layout_text(&d->y_layout);
     return o.str();
 }
@@ -175,7 +176,10 @@ int opt_warmup(const alt_tune_opts_t *o) { return o->warmup > 0 ? o->warmup : 3;
 int opt_reps(const alt_tune_opts_t *o) { return o->reps > 0 ? o->reps : 20; }
 
 size_t conv_bytes_x(const alt_conv_desc_t *d) { return (size_t)d->N * d->C * d->H * d->W * dtype_size(d->in_dtype); }
-size_t conv_bytes_w(const alt_conv_desc_t *d) { return (size_t)d->K * d->C * d->R * d->S * dtype_size(d->in_dtype); }
+size_t conv_bytes_w(const alt_conv_desc_t *d)
+{
+    return (size_t)d->K * (d->C / (d->groups > 1 ? d->groups : 1)) * d->R * d->S * dtype_size(d->in_dtype);
+}
 size_t conv_bytes_y(const alt_conv_desc_t *d)
 {
     int64_t o[4];

@@ -25,7 +25,7 @@ def h():
 
 
 def run_conv(h, x, w, cfg, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False, variant=-1,
-             use_pack=False):
+             use_pack=False, groups=1):
     """x (N,C,H,W), w (K,C,R,S): float32 or uint16 bf16 bits, logical.  Returns
     the logical NKPQ result and the variant's name."""
     N, C, H, W = x.shape
@@ -33,7 +33,7 @@ def run_conv(h, x, w, cfg, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, r
     epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
     d = alt.conv_desc(N, C, H, W, K, R, S, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1),
                       in_dtype=in_dtype, out_dtype=out_dtype, epilogue=epi, variant=variant,
-                      x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+                      x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl, groups=groups)
     oshape = h.conv2d_output_shape(d)
     xd = dev(to_layout(x, "NCHW", xl))
     if use_pack:
@@ -262,3 +262,83 @@ def test_conv_errors(h):
     with pytest.raises(alt.AltError) as e:
         h.conv2d(d, a, a, a, workspace=None, ws_bytes=0)
     assert e.value.status == 5
+
+
+GROUPED_LAYOUTS = [("NCHW", "OIHW", "NCHW"), ("NHWC", "OHWI", "NHWC"), ("NCHW8c", "OIHW8o8i", "NCHW8c"),
+                   ("NHWC", "OIHW", "NCHW")]
+
+
+@pytest.mark.parametrize("layouts", GROUPED_LAYOUTS, ids=lambda l: "_".join(l))
+@pytest.mark.parametrize("in_dtype", [alt.BF16, alt.F32])
+def test_grouped_conv_exact_integers(h, layouts, in_dtype):
+    """Group-wise C2D (Section 6.1): groups run as grid planes of the implicit-GEMM kernels;
+    bias per group, ragged tiles, stride and dilation, bit for bit."""
+    xl, wl, yl = layouts
+    for (N, C, K, G, R, cfg) in [(2, 32, 48, 2, 3, dict(stride=1, pad=1)), (1, 64, 64, 4, 3, dict(stride=2, pad=1)),
+                                 (2, 16, 32, 2, 1, dict(stride=1, pad=0)), (1, 48, 24, 3, 3, dict(stride=1, pad=2, dil=2))]:
+        x = small_ints_f32(301, (N, C, 11, 9), -3, 3)
+        w = small_ints_f32(302, (K, C // G, R, R), -3, 3)
+        b = small_ints_f32(303, (K,), -20, 20)
+        ref = oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), groups=G, bias=b, relu=True)
+        xi, wi = (f32_to_bf16_bits(x), f32_to_bf16_bits(w)) if in_dtype == alt.BF16 else (x, w)
+        got, _ = run_conv(h, xi, wi, cfg, xl, wl, yl, in_dtype, bias=b, relu=True, groups=G)
+        assert np.array_equal(got, ref), (N, C, K, G, R, cfg)
+        got, _ = run_conv(h, xi, wi, cfg, xl, wl, yl, in_dtype, bias=b, relu=True, groups=G, use_pack=True)
+        assert np.array_equal(got, ref), "packed weights"
+    # every applicable variant on one case, split-K included
+    x = small_ints_f32(304, (2, 32, 10, 10), -3, 3)
+    w = small_ints_f32(305, (32, 8, 3, 3), -3, 3)
+    ref = oracle.conv2d(x, w, stride=1, pad=1, groups=4)
+    xi, wi = (f32_to_bf16_bits(x), f32_to_bf16_bits(w)) if in_dtype == alt.BF16 else (x, w)
+    d0 = alt.conv_desc(2, 32, 10, 10, 32, 3, 3, stride=1, pad=1, in_dtype=in_dtype, x_layout="NCHW->" + xl,
+                       w_layout="OIHW->" + wl, y_layout="NCHW->" + yl, groups=4)
+    variants = applicable_variants(h, d0)
+    assert variants and not any("direct" in n or "stream" in n for _, n in variants)
+    for v, name in variants:
+        got, _ = run_conv(h, xi, wi, dict(stride=1, pad=1), xl, wl, yl, in_dtype, groups=4, variant=v)
+        assert np.array_equal(got, ref), name
+
+
+def test_grouped_conv_rejects_blocks_that_straddle_groups(h):
+    d = alt.conv_desc(1, 32, 8, 8, 32, 3, 3, pad=1, x_layout="NCHW->NCHW16c", groups=4)     # 8 channels per group
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(d, 16, 16, 16, stream=0)
+    assert e.value.status == 4
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d(alt.conv_desc(1, 30, 8, 8, 32, 3, 3, pad=1, groups=4), 16, 16, 16, stream=0)
+    assert e.value.status == 1
+
+
+DW_LAYOUTS = [("NCHW", "OIHW", "NCHW"), ("NHWC", "HWIO", "NHWC"), ("NCHW16c", "OIHW16o", "NCHW16c"),
+              ("NHWC", "OIHW", "NCHW"), ("NCHW8c", "HWIO", "NHWC")]
+
+
+@pytest.mark.parametrize("layouts", DW_LAYOUTS, ids=lambda l: "_".join(l))
+@pytest.mark.parametrize("in_dtype", [alt.BF16, alt.F32])
+def test_depthwise_conv_exact_integers(h, layouts, in_dtype):
+    """Depth-wise C2D (groups = C = K): the vector kernel (channel-contiguous bf16) and the
+    element kernel (everything else), stride, dilation, bias, ReLU, both output types."""
+    xl, wl, yl = layouts
+    for (N, C, H, W, R, cfg) in [(2, 32, 13, 11, 3, dict(stride=1, pad=1)), (1, 48, 9, 14, 3, dict(stride=2, pad=1)),
+                                 (2, 16, 10, 10, 5, dict(stride=1, pad=4, dil=2)), (3, 64, 7, 7, 3, dict(stride=1, pad=0))]:
+        x = small_ints_f32(311, (N, C, H, W), -3, 3)
+        w = small_ints_f32(312, (C, 1, R, R), -3, 3)
+        b = small_ints_f32(313, (C,), -20, 20)
+        ref = oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), groups=C, bias=b, relu=True)
+        xi, wi = (f32_to_bf16_bits(x), f32_to_bf16_bits(w)) if in_dtype == alt.BF16 else (x, w)
+        got, _ = run_conv(h, xi, wi, cfg, xl, wl, yl, in_dtype, bias=b, relu=True, groups=C)
+        assert np.array_equal(got, ref), (N, C, H, W, R, cfg)
+        if in_dtype == alt.BF16:
+            got16, _ = run_conv(h, xi, wi, cfg, xl, wl, yl, in_dtype, out_dtype=alt.BF16, bias=b, relu=True, groups=C)
+            assert np.array_equal(got16, f32_to_bf16_bits(ref)), "bf16 out"
+        got, _ = run_conv(h, xi, wi, cfg, xl, wl, yl, in_dtype, groups=C)
+        assert np.array_equal(got, oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), groups=C))
+
+
+def test_depthwise_conv_tolerance(h):
+    x = f32_to_bf16_bits(normal_f32(321, (2, 64, 28, 28)))
+    w = f32_to_bf16_bits(normal_f32(322, (64, 1, 3, 3), std=0.3))
+    ref = oracle.conv2d(x, w, stride=1, pad=1, groups=64)
+    for xl, wl, yl in [("NHWC", "HWIO", "NHWC"), ("NCHW", "OIHW", "NCHW")]:
+        got, _ = run_conv(h, x, w, dict(stride=1, pad=1), xl, wl, yl, alt.BF16, groups=64)
+        assert rel_err(got, ref) <= 1e-5      # nine exact products summed in fp32

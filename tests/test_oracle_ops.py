@@ -310,3 +310,37 @@ def test_eltwise_add_closed_forms(oracle):
     yb = f32_to_bf16_bits(y)
     t = (torch.from_numpy(bf16_bits_to_f32(xb)).bfloat16() + torch.from_numpy(bf16_bits_to_f32(yb)).bfloat16())
     assert np.array_equal(oracle.eltwise_add(xb, yb), f32_to_bf16_bits(t.float().numpy()))
+
+
+def test_grouped_conv_is_block_diagonal_dense_conv(oracle):
+    """Pins for groups > 1: equal to the dense convolution whose weights are zero outside the
+    group blocks, to torch's float64 grouped conv2d (library special case), and, depth-wise,
+    to a per-channel brute-force loop."""
+    rng = np.random.RandomState(13)
+    for (N, C, K, G, R, stride, pad, dil) in [(2, 8, 12, 4, 3, 1, 1, 1), (1, 6, 6, 2, 3, 2, 1, 1), (2, 5, 5, 5, 3, 1, 1, 2),
+                                              (1, 4, 8, 4, 1, 1, 0, 1)]:
+        x = rng.randint(-3, 4, (N, C, 9, 7)).astype(np.float32)
+        w = rng.randint(-3, 4, (K, C // G, R, R)).astype(np.float32)
+        b = rng.randint(-5, 6, K).astype(np.float32)
+        got = oracle.conv2d(x, w, stride=stride, pad=pad, dil=dil, groups=G, bias=b, relu=True)
+        dense = np.zeros((K, C, R, R), dtype=np.float32)
+        cg, kg = C // G, K // G
+        for g in range(G):
+            dense[g * kg:(g + 1) * kg, g * cg:(g + 1) * cg] = w[g * kg:(g + 1) * kg]
+        assert np.array_equal(got, oracle.conv2d(x, dense, stride=stride, pad=pad, dil=dil, bias=b, relu=True))
+        t = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                       torch.from_numpy(b).double(), stride, pad, dil, G).clamp_min(0)
+        assert np.array_equal(got.astype(np.float64), t.numpy())
+    # depth-wise against loops written here
+    x = rng.randint(-3, 4, (1, 3, 5, 6)).astype(np.float32)
+    w = rng.randint(-3, 4, (3, 1, 3, 3)).astype(np.float32)
+    got = oracle.conv2d(x, w, stride=1, pad=1, groups=3)
+    for c, oh, ow in itertools.product(range(3), range(5), range(6)):
+        acc = 0.0
+        for r, s in itertools.product(range(3), range(3)):
+            ih, iw = oh - 1 + r, ow - 1 + s
+            if 0 <= ih < 5 and 0 <= iw < 6:
+                acc += float(x[0, c, ih, iw]) * float(w[c, 0, r, s])
+        assert got[0, c, oh, ow] == acc
+    with pytest.raises(ValueError):
+        oracle.conv2d(x, w, groups=2)
