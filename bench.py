@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="skip the extra sections")
     ap.add_argument("--sections", default="all",
                     help="comma-separated extra sections to run besides the headline step: f32, transforms, gemm, b1, "
-                         "scaled, chain, graph, peaks (default all; --quick runs none)")
+                         "scaled, chain, graph, groups, peaks (default all; --quick runs none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
@@ -64,7 +64,7 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
-    all_sections = ("f32", "transforms", "gemm", "b1", "scaled", "chain", "graph", "peaks")
+    all_sections = ("f32", "transforms", "gemm", "b1", "scaled", "chain", "graph", "groups", "peaks")
     chosen = set(all_sections) if args.sections == "all" else set(x for x in args.sections.split(",") if x)
     if chosen - set(all_sections):
         raise SystemExit("bench.py: unknown section(s) %s" % ", ".join(sorted(chosen - set(all_sections))))
@@ -518,6 +518,44 @@ def main():
             measurements=gp.trials,
             add_relu_us=round(add_us, 2), add_relu_GBps=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6), 1),
             add_relu_frac_hbm_peak=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6) / PEAK_HBM_GBPS, 4))
+
+    if want("groups"):
+        # --------------------------- depth-wise and group-wise convolution ----
+        # MobileNet-V2-shaped depth-wise 3x3 layers, bf16 in and out, under three layout choices: memory-bound, so the
+        # figure is GB/s over the compulsory bytes (activations in, activations out, weights)
+        dw = []
+        for (C, HW, stride) in [(144, 56, 1), (384, 28, 1), (96, 112, 2)]:
+            per = {}
+            for xl, wl in [("NCHW", "OIHW"), ("NHWC", "HWIO"), ("NCHW16c", "OIHW16o")]:
+                d = alt.conv_desc(16, C, HW, HW, C, 3, 3, stride=stride, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                  epilogue=alt.EPI_BIAS | alt.EPI_RELU, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
+                                  y_layout="NCHW->" + xl, groups=C)
+                osh = h.conv2d_output_shape(d)
+                xb = torch.randint(-30000, 30000, (16 * C * HW * HW,), dtype=torch.int16, device=dev)
+                wb = torch.randint(-30000, 30000, (C * 9,), dtype=torch.int16, device=dev)
+                bb = torch.zeros(C, dtype=torch.float32, device=dev)
+                yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)
+                gr = capture(lambda st: h.conv2d(d, xb, wb, yb, bias=bb, stream=st), 20)
+                us = graph_timed(gr, 20)
+                del gr
+                nbytes = (xb.numel() + yb.numel() + wb.numel()) * 2
+                per[xl] = dict(us=round(us, 2), GBps=round(nbytes / 1e9 / (us * 1e-6), 1),
+                               frac_hbm_peak=round(nbytes / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4))
+                del xb, wb, yb
+            best = min(per, key=lambda k: per[k]["us"])
+            dw.append(dict(layer="dw3x3_c%d_%dx%d_s%d" % (C, HW, HW, stride), batch=16, per_layout=per, best_layout=best,
+                           speedup_vs_nchw=round(per["NCHW"]["us"] / per[best]["us"], 2)))
+        extra["depthwise_b16"] = dw
+        # a ResNeXt-shaped grouped 3x3 layer (128 channels in 4 groups, 28x28), tuned like the other layers
+        gshape = alt.conv_desc(16, 128, 28, 28, 128, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16, groups=4)
+        gbest, grep_ = h.tune_conv2d(gshape, arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        gfl = 2.0 * 16 * 128 * 28 * 28 * 32 * 9
+        gnames = [grep_.layout_name[i].value.decode() for i in range(grep_.n_layouts)]
+        extra["grouped_c128_g4_28x28_b16"] = dict(
+            variant=h.conv2d_variant_name(gbest, gbest.variant), layout=gnames[int(np.argmin([grep_.layout_best_us[i] for i in range(grep_.n_layouts)]))],
+            tuned_us=round(float(grep_.best_us), 2), default_layout_us=round(float(grep_.default_us), 2),
+            tflops=round(gfl / float(grep_.best_us) / 1e6, 1), trials=grep_.trials,
+            layout_us=dict(zip(gnames, [round(float(grep_.layout_best_us[i]), 2) for i in range(grep_.n_layouts)])))
 
     if want("peaks"):
         pk = h.get_peak(arena, arena.numel())

@@ -10,6 +10,7 @@
 //    least eight on activations, weights and output (NHWC or NCHW[x]c with
 //    channel-last weights): a thread owns eight channels of one output pixel,
 //    every access is 16 bytes;
+//    (3x3 filters without dilation get a register-tiled version of it);
 //  * element kernel: any separable layout; a thread owns one output element,
 //    threads run along the output's contiguous dimension.
 #include <hip/hip_runtime.h>
@@ -43,26 +44,43 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_elem_kernel(const DwParams 
     const int64_t total = (int64_t)p.N * p.C * p.OH * p.OW;
     for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
         int n, c, oh, ow;
-        int64_t r = e;
-        if (p.chan_fast) {
-            c = (int)(r % p.C); r /= p.C;
-            ow = (int)(r % p.OW); r /= p.OW;
-            oh = (int)(r % p.OH); n = (int)(r / p.OH);
+        if (total <= 0x7fffffff) {                  // 32-bit divisions cost a fraction of 64-bit ones
+            uint32_t r = (uint32_t)e;
+            if (p.chan_fast) {
+                c = (int)(r % (uint32_t)p.C); r /= (uint32_t)p.C;
+                ow = (int)(r % (uint32_t)p.OW); r /= (uint32_t)p.OW;
+                oh = (int)(r % (uint32_t)p.OH); n = (int)(r / (uint32_t)p.OH);
+            } else {
+                ow = (int)(r % (uint32_t)p.OW); r /= (uint32_t)p.OW;
+                oh = (int)(r % (uint32_t)p.OH); r /= (uint32_t)p.OH;
+                c = (int)(r % (uint32_t)p.C); n = (int)(r / (uint32_t)p.C);
+            }
         } else {
-            ow = (int)(r % p.OW); r /= p.OW;
-            oh = (int)(r % p.OH); r /= p.OH;
-            c = (int)(r % p.C); n = (int)(r / p.C);
+            int64_t r = e;
+            if (p.chan_fast) {
+                c = (int)(r % p.C); r /= p.C;
+                ow = (int)(r % p.OW); r /= p.OW;
+                oh = (int)(r % p.OH); n = (int)(r / p.OH);
+            } else {
+                ow = (int)(r % p.OW); r /= p.OW;
+                oh = (int)(r % p.OH); r /= p.OH;
+                c = (int)(r % p.C); n = (int)(r / p.C);
+            }
         }
         const int64_t xb = dim2_off(p.xn, n) + dim2_off(p.xc, c), wb = dim2_off(p.wo, c);
         float acc = 0.f;
+        // (H, W, R and S are rarely blocked: then an offset is a multiply, not a division)
+        const bool lin = p.xh.f >= p.H && p.xw.f >= p.W && p.wr.f >= p.R && p.ws.f >= p.S;
         for (int fr = 0; fr < p.R; ++fr) {
             const int ih = oh * p.stride_h - p.pad_h + fr * p.dil_h;
             if ((unsigned)ih >= (unsigned)p.H) continue;
+            const int64_t xr = xb + (lin ? ih * p.xh.si : dim2_off(p.xh, ih));
+            const int64_t wr = wb + (lin ? fr * p.wr.si : dim2_off(p.wr, fr));
             for (int fs = 0; fs < p.S; ++fs) {
                 const int iw = ow * p.stride_w - p.pad_w + fs * p.dil_w;
                 if ((unsigned)iw >= (unsigned)p.W) continue;
-                acc += load_elem(p.x, xb + dim2_off(p.xh, ih) + dim2_off(p.xw, iw), p.in_bf16) *
-                       load_elem(p.w, wb + dim2_off(p.wr, fr) + dim2_off(p.ws, fs), p.in_bf16);
+                acc += load_elem(p.x, xr + (lin ? iw * p.xw.si : dim2_off(p.xw, iw)), p.in_bf16) *
+                       load_elem(p.w, wr + (lin ? fs * p.ws.si : dim2_off(p.ws, fs)), p.in_bf16);
             }
         }
         if (p.epilogue & ALT_EPI_BIAS) acc += p.bias[c];
@@ -118,6 +136,81 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_vec8_kernel(const DwParams 
     }
 }
 
+// The common case of the vector kernel: 3x3 filter, dilation 1, H and W not blocked.  A thread
+// owns eight channels of TW consecutive output pixels of one row: the nine weight vectors are
+// loaded once, and neighbouring outputs share the input columns of their windows, so a thread
+// makes 3 * ((TW - 1) * STRIDE + 3) + 9 loads for TW outputs instead of 18 per output.
+template <int STRIDE, int TW>
+__global__ __launch_bounds__(kDwThreads) void dwconv_vec8_3x3_kernel(const DwParams p)
+{
+    typedef uint32_t w4_t __attribute__((ext_vector_type(4)));
+    typedef float f4_t __attribute__((ext_vector_type(4)));
+    constexpr int NCOL = (TW - 1) * STRIDE + 3;
+    const int C8 = p.C >> 3, OWB = (p.OW + TW - 1) / TW;
+    const int64_t total = (int64_t)p.N * p.OH * OWB * C8;
+    const int64_t sxh = p.xh.si, sxw = p.xw.si, syh = p.yh.si, syw = p.yw.si;
+    for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
+        int64_t r = e;
+        const int c = (int)(r % C8) * 8; r /= C8;
+        const int ow0 = (int)(r % OWB) * TW; r /= OWB;
+        const int oh = (int)(r % p.OH);
+        const int n = (int)(r / p.OH);
+        const uint16_t *xb = (const uint16_t *)p.x + dim2_off(p.xn, n) + dim2_off(p.xc, c);
+        const uint16_t *wb = (const uint16_t *)p.w + dim2_off(p.wo, c);
+        f4_t wlo[9], whi[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const w4_t wv = *(const w4_t *)(wb + dim2_off(p.wr, t / 3) + dim2_off(p.ws, t % 3));
+            wlo[t] = __builtin_bit_cast(f4_t, wv << 16);
+            whi[t] = __builtin_bit_cast(f4_t, wv & 0xffff0000u);
+        }
+        f4_t lo[TW], hi[TW];
+#pragma unroll
+        for (int j = 0; j < TW; ++j) { lo[j] = (f4_t){0.f, 0.f, 0.f, 0.f}; hi[j] = (f4_t){0.f, 0.f, 0.f, 0.f}; }
+        const int ih0 = oh * STRIDE - p.pad_h, iw0 = ow0 * STRIDE - p.pad_w;
+#pragma unroll
+        for (int fr = 0; fr < 3; ++fr) {
+            const int ih = ih0 + fr;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            const uint16_t *row = xb + ih * sxh;
+            f4_t xlo[NCOL], xhi[NCOL];
+#pragma unroll
+            for (int q = 0; q < NCOL; ++q) {
+                const int iw = iw0 + q;
+                w4_t xv = {0u, 0u, 0u, 0u};
+                if ((unsigned)iw < (unsigned)p.W) xv = *(const w4_t *)(row + iw * sxw);
+                xlo[q] = __builtin_bit_cast(f4_t, xv << 16);
+                xhi[q] = __builtin_bit_cast(f4_t, xv & 0xffff0000u);
+            }
+#pragma unroll
+            for (int j = 0; j < TW; ++j)
+#pragma unroll
+                for (int fs = 0; fs < 3; ++fs) {
+                    lo[j] += xlo[j * STRIDE + fs] * wlo[fr * 3 + fs];
+                    hi[j] += xhi[j * STRIDE + fs] * whi[fr * 3 + fs];
+                }
+        }
+        f4_t blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
+        if (p.epilogue & ALT_EPI_BIAS) {
+            const f4_t b0 = *(const f4_t *)(p.bias + c), b1 = *(const f4_t *)(p.bias + c + 4);
+            blo = __builtin_shufflevector(b0, b1, 0, 2, 4, 6);
+            bhi = __builtin_shufflevector(b0, b1, 1, 3, 5, 7);
+        }
+        const float floor_ = (p.epilogue & ALT_EPI_RELU) ? 0.f : -INFINITY;
+        uint16_t *yb = (uint16_t *)p.y + dim2_off(p.yn, n) + dim2_off(p.yk, c) + oh * syh;
+#pragma unroll
+        for (int j = 0; j < TW; ++j) {
+            if (ow0 + j >= p.OW) break;
+            const f4_t a = __builtin_elementwise_max(lo[j] + blo, (f4_t){floor_, floor_, floor_, floor_});
+            const f4_t b = __builtin_elementwise_max(hi[j] + bhi, (f4_t){floor_, floor_, floor_, floor_});
+            w4_t out;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) out[q] = f32x2_to_bf16x2(a[q], b[q]);
+            *(w4_t *)(yb + (ow0 + j) * syw) = out;
+        }
+    }
+}
+
 // eight consecutive channels from a multiple of eight are one contiguous, 16-byte aligned run
 bool chan_runs_of_8(const Dim2 &c, int64_t C, const Dim2 *others, int n_others)
 {
@@ -152,9 +245,15 @@ alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t
     const bool vec = p.in_bf16 && p.out_bf16 && chan_runs_of_8(q.xc, C, xo, 3) && chan_runs_of_8(q.wo, C, wo_, 2) &&
                      chan_runs_of_8(q.yk, C, yo, 3) && (uintptr_t)q.x % 16 == 0 && (uintptr_t)q.w % 16 == 0 &&
                      (uintptr_t)q.y % 16 == 0 && (!(q.epilogue & ALT_EPI_BIAS) || (uintptr_t)q.bias % 16 == 0);
-    const int64_t work = N * q.OH * q.OW * (vec ? C / 8 : C);
+    constexpr int kTW = 4;
+    const bool k3x3 = vec && q.R == 3 && q.S == 3 && q.dil_h == 1 && q.dil_w == 1 && q.stride_h == q.stride_w &&
+                      (q.stride_h == 1 || q.stride_h == 2) && q.xh.f >= q.H && q.xw.f >= q.W && q.yh.f >= q.OH &&
+                      q.yw.f >= q.OW;
+    const int64_t work = k3x3 ? N * q.OH * ((q.OW + kTW - 1) / kTW) * (C / 8) : N * q.OH * q.OW * (vec ? C / 8 : C);
     const unsigned blocks = (unsigned)std::min<int64_t>((work + kDwThreads - 1) / kDwThreads, 256 * 64);
-    if (vec) hipLaunchKernelGGL(dwconv_vec8_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    if (k3x3 && q.stride_h == 1) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<1, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (k3x3) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<2, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (vec) hipLaunchKernelGGL(dwconv_vec8_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
     else hipLaunchKernelGGL(dwconv_elem_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
     ALT_CHECK_HIP(h, hipGetLastError());
     return ALT_OK;

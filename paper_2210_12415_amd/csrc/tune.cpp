@@ -315,7 +315,9 @@ alt_status_t alt_tune_conv2d(alt_handle_t h, const alt_conv_desc_t *shape, const
     for (int c = 0; c < kNumConvCands; ++c) {
         if (opts->layout_mask && !(opts->layout_mask & (1 << c))) continue;
         int b = kConvCands[c].block;
-        if (b && (shape->C % b || shape->K % b)) continue;
+        // channel blocks must divide the channels, of one group for group-wise problems
+        const int64_t G = shape->groups > 1 ? shape->groups : 1;
+        if (b && ((shape->C / G) % b || (shape->K / G) % b)) continue;
         cands.push_back(c);
     }
     if (cands.empty()) return fail(h, ALT_INVALID_ARG, "layout_mask leaves no candidate");
