@@ -15,10 +15,16 @@
 //
 // Covers: bf16, stride 1, dilation 1, "same" padding (2*pad = R-1, S-1; so 1x1
 // pad 0 too), activations NHWC, weights OHWI, output NHWC (fp32 or bf16), all
-// dense, channels a multiple of 64 per split, output channels a multiple of 4.  The linear pixel index of the
-// input is then the linear index of the output pixel plus a per-tap constant,
-// across image boundaries too, which is what makes the patch one contiguous
-// range of input pixels.
+// dense, 64, 128, 256 or 512 channels per split, output channels a multiple of 4.
+// The linear pixel index of the input is then the linear index of the output
+// pixel plus a per-tap constant, across image boundaries too, which is what
+// makes the patch one contiguous range of input pixels.
+//
+// K groups: the waves of a workgroup may form several groups that split the
+// slice's channels between them, each with a weight ring of its own; their
+// tiles are summed through LDS before the epilogue (see dconv_kernel).  This
+// file also holds what the streaming kernel of dstream.h shares with this one:
+// the parameter block, the asynchronous LDS reads and the epilogue.
 //
 // Split-K: grid slices over channel groups (Cs channels each) compute partial
 // sums; each writes its fp32 partial tile to the workspace and the last slice

@@ -1,6 +1,6 @@
-// Host side of the patch-resident direct convolution (dconv.h): which problems
-// it covers, its launch parameters, and the arrival counters of its fused
-// split-K reduction.
+// Host side of the patch-resident direct convolution (dconv.h) and of the
+// streaming kernel (dstream.h): which problems each covers, their launch
+// parameters, and the arrival counters of the fused split-K reduction.
 #include <atomic>
 
 #include "dstream.h"
