@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="skip the extra sections")
     ap.add_argument("--sections", default="all",
                     help="comma-separated extra sections to run besides the headline step: f32, transforms, gemm, b1, "
-                         "scaled, chain, graph, groups, peaks (default all; --quick runs none)")
+                         "scaled, chain, graph, groups, budget, peaks (default all; --quick runs none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
@@ -64,7 +64,7 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
-    all_sections = ("f32", "transforms", "gemm", "b1", "scaled", "chain", "graph", "groups", "peaks")
+    all_sections = ("f32", "transforms", "gemm", "b1", "scaled", "chain", "graph", "groups", "budget", "peaks")
     chosen = set(all_sections) if args.sections == "all" else set(x for x in args.sections.split(",") if x)
     if chosen - set(all_sections):
         raise SystemExit("bench.py: unknown section(s) %s" % ", ".join(sorted(chosen - set(all_sections))))
@@ -556,6 +556,25 @@ def main():
             tuned_us=round(float(grep_.best_us), 2), default_layout_us=round(float(grep_.default_us), 2),
             tflops=round(gfl / float(grep_.best_us) / 1e6, 1), trials=grep_.trials,
             layout_us=dict(zip(gnames, [round(float(grep_.layout_best_us[i]), 2) for i in range(grep_.n_layouts)])))
+
+    if want("budget"):
+        # ------------------------------- budgeted search against the full one ----
+        # the tuner with 48 measurements per layer (variants ranked by the cost estimate, measured best first)
+        # against the exhaustive search over the same space
+        bud = []
+        for L in RESNET_LAYERS:
+            shape = alt.conv_desc(16, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"], pad=L["pad"],
+                                  in_dtype=alt.BF16, out_dtype=alt.BF16)
+            res = {}
+            for name, budget in (("48", 48), ("all", 0)):
+                h.cache_clear()
+                bbest, brep = h.tune_conv2d(shape, arena, arena.numel(), max_trials=budget, warmup=3, reps=20)
+                res[name] = dict(us=round(float(brep.best_us), 2), trials=brep.trials,
+                                 variant=h.conv2d_variant_name(bbest, bbest.variant))
+            bud.append(dict(layer=L["name"], budget_48=res["48"], exhaustive=res["all"],
+                            ratio=round(res["48"]["us"] / res["all"]["us"], 3)))
+        h.cache_clear()
+        extra["budgeted_search_b16"] = bud
 
     if want("peaks"):
         pk = h.get_peak(arena, arena.numel())

@@ -155,6 +155,27 @@ size_t igemm_workspace(const Problem &pb, int splitk)
 double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams &p)
 {
     (void)pb;
+    if (k.launch_direct && k.stream) {
+        // Streaming kernel: all K groups take one K step each in the larger of their matrix-core
+        // time (at the efficiency these kernels reach: less with fewer than eight waves) and the
+        // time to bring their operand tiles into LDS (about 45 bytes per clock per CU), plus a
+        // fixed part; a workgroup adds a prologue and an epilogue; as many workgroups share a CU
+        // as their LDS allows.  Clocks at 2.2 GHz, scaled to the unit of the estimate below
+        // (about 45 per microsecond).
+        const int waves = k.kw * k.wgm * k.wgn;
+        const double lds = (double)k.kw * (k.prefetch + 1) * (k.BM + k.BN) * k.BK * 2;
+        const double stage = (double)k.kw * k.BM * (k.BN + 8.0 * k.wgn) * 4;
+        const int per_cu = std::max(1, (int)(160.0 * 1024 / std::max(lds, stage)));
+        const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
+        const double rounds = std::ceil(blocks / (256.0 * per_cu));
+        const double steps = (double)p.C / p.splitk / k.kw / k.BK;
+        const double mfma = (double)k.kw * k.BM * k.BN * k.BK / 16384.0 * 8.0 * (waves >= 8 ? 1.7 : 2.0);
+        const double bytes = (double)k.kw * (k.BM + k.BN) * k.BK * 2 / 45.0;
+        const double clk = rounds * (steps * (std::max(mfma, bytes) + 120.0) + 6000.0);
+        // (halved like the direct kernels' estimate below: wherever one of these kernels applies it
+        // has beaten the implicit-GEMM kernels, whose estimate is optimistic)
+        return 0.5 * (clk / 2200.0 * 45.0 + (p.splitk > 1 ? 140.0 : 0.0));
+    }
     double mode_cost = 1.0;
     if (k.amode == LOAD_GATHER) mode_cost *= 6.0;
     if (k.bmode == LOAD_GATHER) mode_cost *= 3.0;
@@ -165,7 +186,7 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
     const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
     const double rounds = std::ceil(blocks / 512.0);
     const double step = (double)k.BM * k.BN * k.BK / 16384.0 + 3.0 * (k.BM + k.BN) * k.BK / 8192.0 + 2.0;
-    double est = rounds * (p.ksteps_per_split * step + 20.0) * mode_cost;
+    double est = rounds * (p.ksteps_per_split * step + 60.0) * mode_cost;
     if (p.splitk > 1) est += (k.launch_direct ? 5.0 : 30.0) + 0.00002 * p.splitk * (double)p.M * p.Nc * p.batch;
     return est;
 }
