@@ -241,6 +241,52 @@ def test_resnet_layers_sampled(h, layer, batch):
             assert err16 <= 2.0 ** -8, (xl, err16)       # half an ulp of bf16 on top of the fp32 sum
 
 
+def _plan_entries():
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "workloads", "tuned_plan_gfx950.json")
+    with open(path) as f:
+        plan = json.load(f)
+    return [(key, name, e) for key in ("bf16_out", "f32_out") for name, e in plan.get(key, {}).items()]
+
+
+@pytest.mark.parametrize("entry", _plan_entries(), ids=lambda e: "%s-%s" % (e[0], e[1]))
+def test_bench_plan_kernels_sampled(h, entry):
+    """The layout and kernel variant bench.py launches for each batch-16 layer (the stored plan),
+    at full size: 4000 sampled outputs against the oracle's one-by-one values."""
+    key, lname, e = entry
+    c = next(l for l in RESNET_LAYERS if l["name"] == lname)
+    xl, wl = e["layout"].split("/")
+    out_dtype = alt.BF16 if key == "bf16_out" else alt.F32
+    d = alt.conv_desc(16, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
+                      in_dtype=alt.BF16, out_dtype=out_dtype, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
+                      y_layout="NCHW->" + xl)
+    byname = {n: v for v, n in applicable_variants(h, d)}
+    assert e["variant"] in byname, "the stored plan names a variant this build does not have: re-run bench.py --retune"
+    d.variant = byname[e["variant"]]
+    x = f32_to_bf16_bits(normal_f32(0xA17 + 2, (16, c["C"], c["H"], c["W"])))
+    w = f32_to_bf16_bits(normal_f32(0xA17 + 102, (c["K"], c["C"], c["R"], c["S"]), std=0.05))
+    oshape = oracle.conv_out_shape(x.shape, w.shape, c["stride"], c["pad"])
+    n_out = int(np.prod(oshape))
+    flat = np.unique(np.concatenate([np.random.RandomState(6).randint(0, n_out, 4000), [0, n_out - 1]]))
+    ref = oracle.conv2d_at(x, w, flat, stride=c["stride"], pad=c["pad"])
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    xd, wd = torch.empty_like(dev(x.reshape(-1))), torch.empty_like(dev(w.reshape(-1)))
+    h.layout_transform(alt.BF16, x.shape, "NCHW->NCHW", dev(x.reshape(-1)), "NCHW->" + xl, xd)
+    h.pack_weights(d, dev(w.reshape(-1)), wd)
+    tdt, ndt, adt = (torch.int16, np.uint16, alt.BF16) if out_dtype == alt.BF16 else (torch.float32, np.float32, alt.F32)
+    yd = torch.empty(n_out, dtype=tdt, device="cuda")
+    ws_bytes = h.conv2d_workspace_size(d)
+    ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device="cuda")
+    h.conv2d(d, xd, wd, yd, workspace=ws, ws_bytes=ws_bytes)
+    ylog = torch.empty_like(yd)
+    h.layout_transform(adt, oshape, "NCHW->" + xl, yd, "NCHW->NCHW", ylog)
+    got = host(ylog, ndt)[flat]
+    got = (bf16_bits_to_f32(got) if out_dtype == alt.BF16 else got).astype(np.float64)
+    err = float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+    assert err <= (2.0 ** -8 if out_dtype == alt.BF16 else 1e-4), err
+
+
 def test_conv_errors(h):
     a = torch.zeros(4096, dtype=torch.float32, device="cuda")
     d = alt.conv_desc(1, 24, 8, 8, 16, 3, 3, pad=1, x_layout="NCHW->NCHW16c")
