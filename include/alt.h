@@ -199,6 +199,28 @@ typedef struct {
 alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
                         const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
+
+/* One alt_conv2d call's arguments, for alt_conv2d_multi. */
+typedef struct {
+    const alt_conv_desc_t *d;
+    const void *x, *w;
+    const float *bias;
+    void *y;
+    void *workspace;
+    size_t ws_bytes;
+    void *stream;
+} alt_conv_call_t;
+
+/* Issues n convolutions that do not depend on one another (operators of a computational
+ * graph with no path between them, Section 2.2's graph view; e.g. a residual block's
+ * projection shortcut beside its main branch), the i-th exactly as
+ * alt_conv2d(h, calls[i].d, ...) on calls[i].stream.  Calls given different streams may
+ * run on the GPU at the same time, so a kernel that cannot fill the chip alone shares it
+ * and one call's start-up overlaps another's tail; ordering between the streams is the
+ * caller's (events or stream synchronisation).  The outputs and workspaces must not
+ * overlap.  Stops at the first call that fails and returns its status; the calls before
+ * it stay issued. */
+alt_status_t alt_conv2d_multi(alt_handle_t h, const alt_conv_call_t *calls, int32_t n);
 alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw);
 
 /* Offline weight transformation (Section 4.2: the weight tensor is a constant,

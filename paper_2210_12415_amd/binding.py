@@ -87,6 +87,12 @@ class ChainPlan(ctypes.Structure):
                 ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float)]
 
 
+class ConvCall(ctypes.Structure):
+    _fields_ = [("d", ctypes.POINTER(ConvDesc)), ("x", ctypes.c_void_p), ("w", ctypes.c_void_p),
+                ("bias", ctypes.c_void_p), ("y", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p)]
+
+
 MAX_GRAPH = 8
 NODE_CONV, NODE_ADD = 0, 1
 
@@ -138,7 +144,7 @@ def exported_symbols():
     return ["alt_create", "alt_destroy", "alt_last_error", "alt_status_string", "alt_version",
             "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
-            "alt_conv2d", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_conv2d", "alt_conv2d_multi", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
@@ -321,6 +327,32 @@ class Handle:
                 _ck(status, self._h)
             return keep is None
         return run
+
+    def conv2d_multi_prepared(self, calls):
+        """alt_conv2d_multi over `calls`, a list of dicts with the keyword arguments of
+        conv2d (d, x, w, y and optionally bias, workspace, ws_bytes, stream), marshalled
+        once: returns a function of no arguments that issues them all."""
+        n = len(calls)
+        arr = (ConvCall * n)()
+        keep = []
+        for i, c in enumerate(calls):
+            arr[i].d = ctypes.pointer(c["d"])
+            for k in ("x", "w", "bias", "y", "workspace"):
+                setattr(arr[i], k, _ptr(c.get(k)))
+            arr[i].ws_bytes = int(c.get("ws_bytes", 0))
+            arr[i].stream = _stream(c.get("stream"))
+            keep.append(c)
+        fn, hh, nn = lib().alt_conv2d_multi, self._h, ctypes.c_int32(n)
+
+        def run():
+            status = fn(hh, arr, nn)
+            if status != 0:
+                _ck(status, hh)
+            return keep is None
+        return run
+
+    def conv2d_multi(self, calls):
+        self.conv2d_multi_prepared(calls)()
 
     def conv2d_workspace_size(self, d):
         n = ctypes.c_size_t()

@@ -504,6 +504,18 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
 }
 
+alt_status_t alt_conv2d_multi(alt_handle_t h, const alt_conv_call_t *calls, int32_t n)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (n < 0 || (n > 0 && !calls)) return fail(h, ALT_INVALID_ARG, "alt_conv2d_multi: bad call list");
+    for (int32_t i = 0; i < n; ++i) {
+        const alt_conv_call_t &c = calls[i];
+        alt_status_t s = alt_conv2d(h, c.d, c.x, c.w, c.bias, c.y, c.workspace, c.ws_bytes, c.stream);
+        if (s != ALT_OK) return s;
+    }
+    return ALT_OK;
+}
+
 alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes)
 {
     if (!h) return ALT_INVALID_ARG;

@@ -388,3 +388,46 @@ def test_depthwise_conv_tolerance(h):
     for xl, wl, yl in [("NHWC", "HWIO", "NHWC"), ("NCHW", "OIHW", "NCHW")]:
         got, _ = run_conv(h, x, w, dict(stride=1, pad=1), xl, wl, yl, alt.BF16, groups=64)
         assert rel_err(got, ref) <= 1e-5      # nine exact products summed in fp32
+
+
+def test_conv2d_multi_on_separate_streams_exact_integers(h):
+    """Independent convolutions issued by one alt_conv2d_multi call, each on a stream of its
+    own, several rounds back to back (a direct kernel, a streaming 1x1 one, a split-K one that
+    takes a counter slot, and the generic kernel): every output bit for bit the oracle's."""
+    cases = [(2, 64, 12, 12, 64, 3, dict(stride=1, pad=1), "NHWC", "OHWI"),
+             (2, 128, 10, 10, 64, 1, dict(stride=1, pad=0), "NHWC", "OHWI"),
+             (1, 128, 7, 7, 128, 3, dict(stride=1, pad=1), "NHWC", "OHWI"),
+             (2, 24, 9, 9, 40, 3, dict(stride=2, pad=1), "NCHW", "OIHW")]
+    streams = [torch.cuda.Stream() for _ in cases]
+    calls, refs, outs = [], [], []
+    for i, (N, C, H, W, K, R, cfg, xl, wl) in enumerate(cases):
+        x = small_ints_f32(401 + i, (N, C, H, W), -3, 3)
+        w = small_ints_f32(451 + i, (K, C, R, R), -3, 3)
+        refs.append(oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"]))
+        d = alt.conv_desc(N, C, H, W, K, R, R, stride=cfg["stride"], pad=cfg["pad"], in_dtype=alt.BF16,
+                          x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
+        if i == 2:
+            split = [v for v, n in applicable_variants(h, d) if not n.endswith("_k1")]
+            assert split
+            d.variant = split[0]
+        oshape = h.conv2d_output_shape(d)
+        n_out = int(np.prod(oshape))
+        whole, yd = canary_dev(n_out, np.float32)
+        ws = torch.empty(36 * n_out, dtype=torch.float32, device="cuda")
+        calls.append(dict(d=d, x=dev(to_layout(f32_to_bf16_bits(x), "NCHW", xl)), w=dev(to_layout(f32_to_bf16_bits(w), "OIHW", wl)),
+                          y=yd, workspace=ws, ws_bytes=ws.numel() * 4, stream=streams[i]))
+        outs.append((whole, yd, n_out, oshape, xl))
+    torch.cuda.synchronize()
+    run = h.conv2d_multi_prepared(calls)
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    for (whole, yd, n_out, oshape, yl), ref in zip(outs, refs):
+        assert canary_ok(whole, n_out), "wrote outside y"
+        assert np.array_equal(from_layout(host(yd, np.float32), oshape, "NCHW", yl), ref)
+    # a failing call stops the list with its status
+    bad = dict(calls[1]); bad["d"] = alt.conv_desc(1, 24, 8, 8, 16, 3, 3, pad=1, x_layout="NCHW->NCHW16c")
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_multi([calls[0], bad, calls[2]])
+    assert e.value.status == 3
+    torch.cuda.synchronize()
