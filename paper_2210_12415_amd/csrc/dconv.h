@@ -371,8 +371,18 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
 // compile time: all K steps are unrolled into straight-line code (no loop-carried
 // register shuffling, every operand address precomputed).  KR = 0: any filter size and
 // slice width, taps and chunks walked at run time.
+// Waves per SIMD the register allocation must leave room for (512 registers per lane and
+// SIMD, accumulators included).  Left alone the compiler keeps every precomputed operand
+// address live and ends near 180 + accumulators, i.e. one or two waves per SIMD whatever
+// the LDS footprint; workgroups of up to four waves are asked for three waves per SIMD when
+// their accumulators are 32 registers and two when they are 64 (a dozen address registers
+// then live in scratch and are reloaded once per filter tap).
+#ifndef ALT_DCONV_MIN_WAVES
+#define ALT_DCONV_MIN_WAVES(acc_regs, nw) ((nw) <= 4 ? ((acc_regs) <= 32 ? 3 : 2) : 1)
+#endif
 template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK, int KR, int NCC>
-__global__ __launch_bounds__(64 * WGM * WGN * KW) void dconv_kernel(const DconvParams p)
+__global__ __launch_bounds__(64 * WGM * WGN * KW, ALT_DCONV_MIN_WAVES((BM / WGM) * (BN / WGN) / 64, WGM * WGN * KW))
+void dconv_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
     uint64_t stamps[5] = {0, 0, 0, 0, 0};
