@@ -69,7 +69,7 @@ struct DconvParams {
     int32_t tiles_m, tiles_n, splitk, flags;             // flags: ALT_EPI_BIAS | ALT_EPI_RELU | 4 (bf16 output)
     Div32 d_hw, d_w, d_tm, d_tn;  // divisions by H*W, W, tiles_m, tiles_n
     int32_t log2_cpp;             // log2(Cs / 8): 16-byte chunks per patch pixel
-    int32_t swz_shift, swz_mask;  // patch swizzle: chunk position = chunk ^ ((pixel >> swz_shift) & swz_mask)
+    Div32 d_slots;                // division by Cs / 8 + 1, the 16-byte slots of a patch pixel in LDS
     int32_t ncc;                  // K steps per tap: (Cs / K groups) / channels per K step
     int32_t bk;                   // channels per K step: 64, or 32 for narrow K groups
     int32_t xcd_local;            // split-K: the slices of a tile run on one XCD and meet in its L2
@@ -237,9 +237,11 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
         for (int it = 0; it < NIT; ++it)
 #pragma unroll
             for (int v = 0; v < V; ++v) vs[it][v] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        // G slices (up to 32 loads) are in flight at a time: a device-scope load takes over a
-        // microsecond, so slices fetched one after the other would cost that much each
-        constexpr int G = NIT * V >= 32 ? 1 : 32 / (NIT * V);
+        // G slices (up to 16 loads) are in flight at a time: a device-scope load takes over a
+        // microsecond, so slices fetched one after the other would cost that much each.  (Not
+        // more: these registers, not the main loop's, would then set the kernel's register
+        // count and with it the waves a SIMD can hold.)
+        constexpr int G = NIT * V >= 16 ? 1 : 16 / (NIT * V);
         for (int sl0 = 0; sl0 < p.splitk; sl0 += G) {
             u32x4_t w4[G][NIT][V];
 #pragma unroll
@@ -361,6 +363,16 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
     return mine;
 }
 
+// Waves per SIMD the register allocation must leave room for (a SIMD has 512 registers per
+// lane, accumulators included).  Without a bound the allocator spreads the accumulators
+// over the second register file and takes what it likes: one wave per SIMD for 64x64 wave
+// tiles.  Workgroups of up to four waves are held to three waves per SIMD when their
+// accumulators are 32 registers and to two when they are 64, which the main loops fit
+// without spilling.
+#ifndef ALT_DCONV_MIN_WAVES
+#define ALT_DCONV_MIN_WAVES(acc_regs, nw) ((nw) <= 4 ? ((acc_regs) <= 32 ? 3 : (acc_regs) <= 64 ? 2 : 1) : 1)
+#endif
+
 // The workgroup has KW groups of WGM x WGN waves.  Each group computes the whole BM x BN
 // tile over its own 1/KW of the slice's channels (all taps), with a weight ring of its
 // own; the groups' tiles are summed through LDS at the end.  This puts two waves on every
@@ -371,15 +383,6 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
 // compile time: all K steps are unrolled into straight-line code (no loop-carried
 // register shuffling, every operand address precomputed).  KR = 0: any filter size and
 // slice width, taps and chunks walked at run time.
-// Waves per SIMD the register allocation must leave room for (512 registers per lane and
-// SIMD, accumulators included).  Left alone the compiler keeps every precomputed operand
-// address live and ends near 180 + accumulators, i.e. one or two waves per SIMD whatever
-// the LDS footprint; workgroups of up to four waves are asked for three waves per SIMD when
-// their accumulators are 32 registers and two when they are 64 (a dozen address registers
-// then live in scratch and are reloaded once per filter tap).
-#ifndef ALT_DCONV_MIN_WAVES
-#define ALT_DCONV_MIN_WAVES(acc_regs, nw) ((nw) <= 4 ? ((acc_regs) <= 32 ? 3 : 2) : 1)
-#endif
 template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK, int KR, int NCC>
 __global__ __launch_bounds__(64 * WGM * WGN * KW, ALT_DCONV_MIN_WAVES((BM / WGM) * (BN / WGN) / 64, WGM * WGN * KW))
 void dconv_kernel(const DconvParams p)
@@ -440,23 +443,26 @@ void dconv_kernel(const DconvParams p)
     const i32x4_t w_rsrc = make_rsrc(p.w, p.w_bytes);
 
     // ---- the patch: input pixels [m0 - halo, m0 + BM + halo), Cs channels of this slice --------
-    // 16-byte slot s of the patch region holds chunk (s % cpp) ^ swz(pixel) of pixel s / cpp.
+    // A patch pixel takes Cs * 2 + 16 bytes of LDS: its chunks in order, then one unused
+    // 16-byte slot.  The odd pitch spreads 16 consecutive pixels over all banks (so the
+    // operand reads of an MFMA row tile do not collide) while a pixel's address stays
+    // affine in its index: a filter tap is then one add per row tile and the chunk inside
+    // the pixel an instruction offset, with no per-read address arithmetic.
     const int halo = p.pad_h * p.W + p.pad_w;
     const int np = BM + 2 * halo;
-    const int log2_pitch = p.log2_cpp + 4;                 // bytes per patch pixel = Cs * 2
-    const int nwl = ((np << p.log2_cpp) + 63) >> 6;        // wave-loads (the region is padded to whole ones)
-    const int pz = (nwl << 10) >> log2_pitch;              // index of the all-zero pixel row behind the patch
+    const int spp = (1 << p.log2_cpp) + 1;                 // 16-byte slots per patch pixel
+    const int pitch_b = spp * 16;
+    const int nwl = (np * spp + 63) >> 6;                  // wave-loads (the region is padded to whole ones)
+    const int pz = (int)div32((uint32_t)((nwl << 6) + spp - 1), p.d_slots);   // the all-zero pixel row behind the patch
     {
-        const int ppw = 64 >> p.log2_cpp;                  // pixels per wave-load (Cs <= 512)
-        const int lpx = lane >> p.log2_cpp, cpos = lane & ((1 << p.log2_cpp) - 1);
         const int g0 = m0 - halo;
         const uint32_t lane_off = (uint32_t)(split * p.Cs) * 2u;
         auto load_one = [&](int j) {
-            const int px = j * ppw + lpx;
-            const int q = cpos ^ ((px >> p.swz_shift) & p.swz_mask);
+            const int slot = j * 64 + lane;
+            const int px = (int)div32((uint32_t)slot, p.d_slots), c = slot - px * spp;
             const int g = g0 + px;
-            const bool ok = px < np && (unsigned)g < (unsigned)p.M;
-            const uint32_t voff = ok ? (uint32_t)(g * p.C) * 2u + lane_off + (uint32_t)q * 16u : kOutOfRange;
+            const bool ok = c < spp - 1 && px < np && (unsigned)g < (unsigned)p.M;
+            const uint32_t voff = ok ? (uint32_t)(g * p.C) * 2u + lane_off + (uint32_t)c * 16u : kOutOfRange;
             dma_load16(x_rsrc, voff, patch0 + j * 1024);
         };
         int j = wave;
@@ -464,7 +470,7 @@ void dconv_kernel(const DconvParams p)
             load_one(j); load_one(j + NW); load_one(j + 2 * NW); load_one(j + 3 * NW);
         }
         for (; j < nwl; j += NW) load_one(j);
-        if (t < (1 << p.log2_cpp)) ((uint4 *)((char *)smem_u4 + KW * B_RING + (pz << log2_pitch)))[t] = make_uint4(0, 0, 0, 0);
+        if (t < spp - 1) ((uint4 *)((char *)smem_u4 + KW * B_RING + pz * pitch_b))[t] = make_uint4(0, 0, 0, 0);
     }
 
     // ---- weights: slot s = (i*NWG + wq)*64 + lane of a stage holds chunk (s % CPR) ^ swz(row) of row s / CPR
@@ -539,11 +545,11 @@ void dconv_kernel(const DconvParams p)
 
     const uint32_t khalf = (lane >> 5) * 16 + kg_off;      // this lane's first byte inside a patch pixel
 
-    // Where the MFMA row tiles of one K step read: patch row and swizzle under the
-    // step's tap (rows whose tap falls outside the image use the zero row), the
-    // channel offset inside the pixel and the weight stage.
+    // Where the MFMA row tiles of one K step read: the patch row under the step's tap (rows
+    // whose tap falls outside the image use the zero row) at this lane's channel half,
+    // the channel offset inside the pixel and the weight stage.
     struct StepAddr {
-        uint32_t a_row[TM], a_swz[TM], c_off, st_off;
+        uint32_t a_row[TM], c_off, st_off;
     };
     auto set_tap = [&](StepAddr &sa, int r, int s) {
         const int shift = (r - p.pad_h) * p.W + (s - p.pad_w);
@@ -552,8 +558,7 @@ void dconv_kernel(const DconvParams p)
             const bool ok = (unsigned)(row_oh[i] + r - p.pad_h) < (unsigned)p.H &&
                             (unsigned)(row_ow[i] + s - p.pad_w) < (unsigned)p.W;
             const int px = ok ? row_px[i] + shift : pz;
-            sa.a_row[i] = patch0 + ((uint32_t)px << log2_pitch);
-            sa.a_swz[i] = (uint32_t)((px >> p.swz_shift) & p.swz_mask) << 4;
+            sa.a_row[i] = patch0 + (uint32_t)(px * pitch_b) + khalf;
         }
     };
     // Operand reads run D k-chunks ahead of the MFMAs that use them, each k-chunk in a
@@ -566,7 +571,7 @@ void dconv_kernel(const DconvParams p)
     u32x4_t af[NBUF][TM], bf[NBUF][TN];
     auto read_frags = [&](int kc, const StepAddr &sa) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], sa.a_row[i] + ((sa.c_off + kc * 32) ^ sa.a_swz[i]));
+        for (int i = 0; i < TM; ++i) lds_read16_async(af[kc][i], sa.a_row[i] + (sa.c_off + kc * 32));
 #pragma unroll
         for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rd[j][kc] + sa.st_off);
     };
@@ -589,52 +594,40 @@ void dconv_kernel(const DconvParams p)
     // the last step the weight refills and look-ahead reads repeat the last step's
     // addresses (loaded, never used) instead of being skipped.
     if constexpr (KR > 0) {
-        // Patch rows and swizzles of every tap, the channel offsets of every k chunk and the
-        // weight operand addresses in every stage, computed while the patch is still in flight.
+        // Patch rows of every tap, computed while the patch is still in flight; the channel
+        // offset of a k chunk and the weight stage are instruction offsets.
         constexpr int RS = KR * KR, NSTEPS = RS * NCC;
-        uint32_t t_row[RS][TM], t_swz[RS][TM];
+        uint32_t t_row[RS][TM];
 #pragma unroll
         for (int tap = 0; tap < RS; ++tap) {
             StepAddr sa;
             set_tap(sa, tap / KR, tap % KR);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) { t_row[tap][i] = sa.a_row[i]; t_swz[tap][i] = sa.a_swz[i]; }
+            for (int i = 0; i < TM; ++i) t_row[tap][i] = sa.a_row[i];
         }
-        uint32_t k_off[NCC][NKC];
-#pragma unroll
-        for (int cc = 0; cc < NCC; ++cc)
-#pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) k_off[cc][kc] = khalf + cc * (BK * 2) + kc * 32;
-        uint32_t b_rds[NS][TN][NKC];
-#pragma unroll
-        for (int st = 0; st < NS; ++st)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int kc = 0; kc < NKC; ++kc) b_rds[st][j][kc] = b_rd[j][kc] + st * B_STAGE;
         wait_vmcnt<(NS - 2) * NLB>();                      // the patch and stage 0
         lds_barrier();
         ALT_STAMP(2);
         // reads of k chunk g (counted over all steps); past the last step they repeat it (never used)
-        auto reads = [&](int g) {
-            const int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC, buf = g % NBUF;
-            const int tap = step / NCC, cc = step % NCC, st = step % NS;
+        auto reads = [&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            constexpr int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC, buf = g % NBUF;
+            constexpr int tap = step / NCC, cc = step % NCC, st = step % NS;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) lds_read16_async(af[buf][i], t_row[tap][i] + (k_off[cc][kc] ^ t_swz[tap][i]));
+            for (int i = 0; i < TM; ++i) lds_read16_async_at<cc * (BK * 2) + kc * 32>(af[buf][i], t_row[tap][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) lds_read16_async(bf[buf][j], b_rds[st][j][kc]);
+            for (int j = 0; j < TN; ++j) lds_read16_async_at<st * B_STAGE>(bf[buf][j], b_rd[j][kc]);
         };
-#pragma unroll
-        for (int g = 0; g < D; ++g) reads(g);
-#pragma unroll
-        for (int step = 0; step < NSTEPS; ++step) {
+        static_for<D>([&](auto gc) { reads(gc); });
+        static_for<NSTEPS>([&](auto sc) {
+            constexpr int step = decltype(sc)::value;
             wait_vmcnt<(NS - 3) * NLB>();                  // stage step+1 has landed (this wave's share)
             if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");   // (a one-wave group loads its ring alone)
             issue_b();
-#pragma unroll
-            for (int kc = 0; kc < NKC; ++kc) {
-                const int buf = (step * NKC + kc) % NBUF;
-                reads(step * NKC + kc + D);
+            static_for<NKC>([&](auto kcc) {
+                constexpr int kc = decltype(kcc)::value;
+                constexpr int buf = (step * NKC + kc) % NBUF;
+                reads(std::integral_constant<int, step * NKC + kc + D>{});
                 lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -643,14 +636,14 @@ void dconv_kernel(const DconvParams p)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[buf][i]),
                                                                             __builtin_bit_cast(bf16x8_t, bf[buf][j]),
                                                                             acc[i][j], 0, 0, 0);
-            }
-        }
+            });
+        });
     } else {
         static_assert(KR > 0 || NKC == NBUF, "the run-time path takes 64-channel steps");
         int r = 0, s = 0, cc = 0;
         StepAddr cur, nxt;
         set_tap(cur, 0, 0);
-        cur.c_off = khalf;
+        cur.c_off = 0;
         cur.st_off = 0;
         wait_vmcnt<(NS - 2) * NLB>();                          // the patch and stage 0
         lds_barrier();
@@ -694,7 +687,7 @@ void dconv_kernel(const DconvParams p)
                     s = more && wrap_c ? (wrap_s ? 0 : s + 1) : s;
                     r = more && wrap_s ? r + 1 : r;
                     set_tap(nxt, r, s);
-                    nxt.c_off = khalf + (uint32_t)cc * (BK * 2);
+                    nxt.c_off = (uint32_t)cc * (BK * 2);
                     const uint32_t st1 = cur.st_off + B_STAGE == NS * B_STAGE ? 0 : cur.st_off + B_STAGE;
                     nxt.st_off = more ? st1 : cur.st_off;
                 }
@@ -744,10 +737,11 @@ void dconv_kernel(const DconvParams p)
 // whole wave-loads, the all-zero row.
 inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, int W, int pad_h, int pad_w)
 {
-    const size_t pitch = (size_t)Cs * 2;
+    const size_t spp = (size_t)Cs / 8 + 1;                 // 16-byte slots per patch pixel (one unused)
     const size_t np = (size_t)BM + 2 * ((size_t)pad_h * W + pad_w);
-    const size_t patch = (np * pitch + 1023) / 1024 * 1024;
-    const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + patch + pitch;
+    const size_t nwl = (np * spp + 63) / 64;
+    const size_t pz = (nwl * 64 + spp - 1) / spp;          // the zero row sits behind the whole wave-loads
+    const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + (pz + 1) * spp * 16;
     // output staging: per K group [BM][BN + 8 floats per wave column], + the split-K flag
     const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
     return main_loop > staging ? main_loop : staging;

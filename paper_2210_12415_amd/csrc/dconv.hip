@@ -199,10 +199,7 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     int l2 = 0;
     while ((8 << l2) < Cs) ++l2;
     d.log2_cpp = l2;
-    // 16 consecutive pixels must spread over the 256 bytes the LDS serves per
-    // cycle: 128-byte pixels pair up (pixel / 2 picks the chunk position), wider ones do not
-    d.swz_shift = Cs == 64 ? 1 : 0;
-    d.swz_mask = Cs == 64 ? 7 : 15;
+    d.d_slots = make_div32((uint32_t)(Cs / 8 + 1));
     d.ncc = (int32_t)(Csg / bk);
     d.bk = bk;
     d.d_sk = make_div32((uint32_t)splitk);

@@ -17,7 +17,8 @@ namespace alt {
 // While a step computes, NS - 2 later stages are in flight: deep rings of small stages
 // (BK = 32) cover the load latency with the same LDS as shallow rings of large ones.
 template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK>
-__global__ __launch_bounds__(64 * WGM * WGN * KW) void dstream_kernel(const DconvParams p)
+__global__ __launch_bounds__(64 * WGM * WGN * KW, ALT_DCONV_MIN_WAVES((BM / WGM) * (BN / WGN) / 64, WGM * WGN * KW))
+void dstream_kernel(const DconvParams p)
 {
 #ifdef ALT_PHASE_TIMING
     uint64_t stamps[5] = {0, 0, 0, 0, 0};
