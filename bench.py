@@ -330,6 +330,7 @@ def main():
             multi = multi_step(layers, descs)
             for l in layers:
                 l["y"].fill_(0)
+            torch.cuda.synchronize()                # the fills run on the default stream, the step on streams of its own
             for _ in range(args.warmup):
                 multi()
             torch.cuda.synchronize()
