@@ -247,7 +247,13 @@ def _plan_entries():
     path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "workloads", "tuned_plan_gfx950.json")
     with open(path) as f:
         plan = json.load(f)
-    return [(key, name, e) for key in ("bf16_out", "f32_out") for name, e in plan.get(key, {}).items()]
+    out = [(key, name, e) for key in ("bf16_out", "f32_out") for name, e in plan.get(key, {}).items()]
+    # the variants chosen jointly for the five-stream step: same layouts as bf16_out, another kernel
+    for name, variant in plan.get("bf16_out_concurrent", {}).items():
+        base = plan.get("bf16_out", {}).get(name)
+        if base and base["variant"] != variant:
+            out.append(("bf16_out_concurrent", name, dict(base, variant=variant)))
+    return out
 
 
 @pytest.mark.parametrize("entry", _plan_entries(), ids=lambda e: "%s-%s" % (e[0], e[1]))
@@ -257,7 +263,7 @@ def test_bench_plan_kernels_sampled(h, entry):
     key, lname, e = entry
     c = next(l for l in RESNET_LAYERS if l["name"] == lname)
     xl, wl = e["layout"].split("/")
-    out_dtype = alt.BF16 if key == "bf16_out" else alt.F32
+    out_dtype = alt.F32 if key == "f32_out" else alt.BF16
     d = alt.conv_desc(16, c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=c["stride"], pad=c["pad"],
                       in_dtype=alt.BF16, out_dtype=out_dtype, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
                       y_layout="NCHW->" + xl)
@@ -431,3 +437,25 @@ def test_conv2d_multi_on_separate_streams_exact_integers(h):
         h.conv2d_multi([calls[0], bad, calls[2]])
     assert e.value.status == 3
     torch.cuda.synchronize()
+
+
+def test_conv1d_is_conv2d_with_unit_height(h):
+    """A 1-D convolution (the C1D of Section 6.1) is the C2D with H = R = 1: strided, padded and
+    dilated cases under channels-last and channel-blocked layouts, bit for bit."""
+    for (N, C, L, K, S, cfg) in [(2, 32, 50, 48, 3, dict(stride=1, pad=1)), (1, 64, 33, 32, 5, dict(stride=2, pad=2)),
+                                 (3, 16, 40, 32, 3, dict(stride=1, pad=2, dil=2))]:
+        x = small_ints_f32(501, (N, C, 1, L), -3, 3)
+        w = small_ints_f32(502, (K, C, 1, S), -3, 3)
+        ref = oracle.conv2d(x, w, stride=(1, cfg["stride"]), pad=(0, cfg["pad"]), dil=(1, cfg.get("dil", 1)))
+        for xl, wl in [("NHWC", "OHWI"), ("NCHW16c", "OIHW16o16i"), ("NCHW", "OIHW")]:
+            d = alt.conv_desc(N, C, 1, L, K, 1, S, in_dtype=alt.BF16, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
+                              y_layout="NCHW->" + xl)
+            d.stride_h, d.stride_w, d.pad_h, d.pad_w = 1, cfg["stride"], 0, cfg["pad"]
+            d.dil_h, d.dil_w = 1, cfg.get("dil", 1)
+            oshape = h.conv2d_output_shape(d)
+            assert tuple(oshape) == ref.shape
+            n_out = int(np.prod(oshape))
+            whole, yd = canary_dev(n_out, np.float32)
+            h.conv2d(d, dev(to_layout(f32_to_bf16_bits(x), "NCHW", xl)), dev(to_layout(f32_to_bf16_bits(w), "OIHW", wl)), yd)
+            assert canary_ok(whole, n_out)
+            assert np.array_equal(from_layout(host(yd, np.float32), oshape, "NCHW", xl), ref), (N, C, L, K, S, cfg, xl)

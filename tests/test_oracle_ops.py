@@ -344,3 +344,20 @@ def test_grouped_conv_is_block_diagonal_dense_conv(oracle):
         assert got[0, c, oh, ow] == acc
     with pytest.raises(ValueError):
         oracle.conv2d(x, w, groups=2)
+
+
+def test_conv_unit_height_is_numpy_correlate(oracle):
+    """H = R = 1 reduces the C2D to a 1-D cross-correlation per channel pair: numpy's own
+    correlate, summed over input channels (integers, so exact), with per-axis stride,
+    padding and dilation on the width alone."""
+    x = small_ints_f32(71, (2, 3, 1, 23), -4, 4)
+    w = small_ints_f32(72, (4, 3, 1, 5), -4, 4)
+    for stride, pad, dil in [(1, 0, 1), (2, 3, 1), (1, 4, 2), (3, 2, 2)]:
+        got = oracle.conv2d(x, w, stride=(1, stride), pad=(0, pad), dil=(1, dil))
+        xp = np.pad(x[:, :, 0, :], ((0, 0), (0, 0), (pad, pad))).astype(np.float64)
+        wd = np.zeros((4, 3, (5 - 1) * dil + 1))
+        wd[:, :, ::dil] = w[:, :, 0, :]
+        ref = np.stack([np.stack([sum(np.correlate(xp[n, c], wd[k, c], "valid") for c in range(3))[::stride]
+                                  for k in range(4)]) for n in range(2)])
+        assert got.shape == (2, 4, 1, ref.shape[-1])
+        assert np.array_equal(got[:, :, 0, :].astype(np.float64), ref), (stride, pad, dil)
