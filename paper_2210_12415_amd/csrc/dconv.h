@@ -153,7 +153,7 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
 {
     constexpr int NWG = WGM * WGN, NW = NWG * KW;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
-    constexpr int SP = WTN + 8;                            // staging pitch in floats
+    constexpr int SP = WTN + 4;                            // staging pitch in floats
     constexpr int V = CW / 4;                              // 16-byte pieces per lane per access
     constexpr int CPRW = WTN / CW;                         // lanes per staged row
     constexpr int RPI = 64 / CPRW;                         // rows per wave-wide access
@@ -324,13 +324,15 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     // ---- the wave's tile goes through LDS to row-major order -----------------------------------------
-    // Accumulator register e of lane l is element (8*(e/4) + 4*(l/32) + e%4, l%32) of a 32x32
-    // tile: consecutive lanes hold consecutive channels of one pixel, one dword each.
-    // Stores of one dword per lane run at a quarter of the rate of 16-byte ones, so each
-    // wave transposes through a private LDS region ([WTM][WTN + 8] floats: the pitch
-    // keeps both the dword writes and the 16-byte reads conflict-free) and then handles
-    // four or eight consecutive channels per lane.
-    constexpr int SP = WTN + 8;                            // staging pitch in floats
+    // The MFMAs take the weights as their first operand, so accumulator register e of lane l is
+    // element (pixel l%32, channel 8*(e/4) + 4*(l/32) + e%4) of a 32x32 tile: four consecutive
+    // channels of one pixel per register quad, but consecutive lanes on different pixels, and
+    // stores whose lanes are 2*Nc bytes apart run at a fraction of the rate of contiguous
+    // 16-byte ones.  So each wave transposes through a private LDS region ([WTM][WTN + 4]
+    // floats, written 16 bytes at a time; the pitch keeps those writes and the 16-byte reads
+    // of eight columns per lane conflict-free) and then handles four or eight consecutive
+    // channels per lane, consecutive lanes side by side.
+    constexpr int SP = WTN + 4;                            // staging pitch in floats
     __syncthreads();                                       // every wave is done with the stages and the patch
 #ifdef ALT_PHASE_TIMING
     epi_clk[0] = __builtin_amdgcn_s_memtime();
@@ -341,8 +343,9 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stg[(i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][e];
+            for (int q = 0; q < 4; ++q)
+                *(float4 *)(stg + (i * 32 + (lane & 31)) * SP + j * 32 + 8 * q + 4 * (lane >> 5)) =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     // (with one K group a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
     if constexpr (KW > 1) __syncthreads();
 #ifdef ALT_PHASE_TIMING
@@ -633,8 +636,8 @@ void dconv_kernel(const DconvParams p)
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[buf][i]),
-                                                                            __builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                            __builtin_bit_cast(bf16x8_t, af[buf][i]),
                                                                             acc[i][j], 0, 0, 0);
             });
         });
@@ -675,8 +678,8 @@ void dconv_kernel(const DconvParams p)
                 for (int i = 0; i < TM; ++i)
     #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[kc][i]),
-                                                                            __builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[kc][j]),
+                                                                            __builtin_bit_cast(bf16x8_t, af[kc][i]),
                                                                             acc[i][j], 0, 0, 0);
                 if (kc == 0) {
                     // where step + 1 reads (after the last step: where this one does)

@@ -181,8 +181,8 @@ void dstream_kernel(const DconvParams p)
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[buf][i]),
-                                                                        __builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                        __builtin_bit_cast(bf16x8_t, af[buf][i]),
                                                                         acc[i][j], 0, 0, 0);
         });
     };
