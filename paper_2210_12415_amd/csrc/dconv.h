@@ -655,25 +655,13 @@ void dconv_kernel(const DconvParams p)
         for (int kc = 0; kc < D; ++kc) read_frags(kc, cur);
         for (int step = 0; step < nsteps; ++step) {
             wait_vmcnt<(NS - 3) * NLB>();                      // stage step+1 has landed (this wave's share)
-    #ifdef ALT_PHASE_TIMING
-            if (!(p.flags & 512))
-    #endif
             if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");
-    #ifdef ALT_PHASE_TIMING
-            if (!(p.flags & 256))
-    #endif
             issue_b();
     #pragma unroll
             for (int kc = 0; kc < NKC; ++kc) {
-    #ifdef ALT_PHASE_TIMING
-                if (!(p.flags & 1024)) {
-    #endif
                 if (kc + D < NKC) read_frags(kc + D, cur);
                 else read_frags(kc + D - NKC, nxt);
                 lds_wait<D * (TM + TN)>(af[kc], bf[kc]);
-    #ifdef ALT_PHASE_TIMING
-                }
-    #endif
     #pragma unroll
                 for (int i = 0; i < TM; ++i)
     #pragma unroll

@@ -224,7 +224,6 @@ hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *par
     }
 #ifdef ALT_PHASE_TIMING
     if (d.splitk == 1) d.partial = partial;    // developer builds: workgroup timestamps go to the workspace
-    if (const char *e = std::getenv("ALT_EXPERIMENT")) d.flags |= std::atoi(e);   // 256: no weight loads, 512: no barrier, 1024: no LDS reads
 #endif
     return k.launch_direct(d, lds, st);
 }
