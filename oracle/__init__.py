@@ -350,6 +350,50 @@ def eltwise_add(a, b=None, relu=False):
     return s
 
 
+def conv2d_transpose_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
+    """(N, K, OH, OW) of the transposed C2D: OH = (H-1)*stride - 2*pad + dil*(R-1) + 1."""
+    N, C, H, W = x_shape
+    C2, K, R, S = w_shape
+    assert C2 == C
+    return (N, K, (H - 1) * stride - 2 * pad + dil * (R - 1) + 1, (W - 1) * stride - 2 * pad + dil * (S - 1) + 1)
+
+
+def conv2d_transpose(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, relu=False):
+    """Transposed C2D (the T2D of Section 6.1's operator list): the adjoint of the
+    C2D that maps K channels to C with the same filter, written out as a scatter:
+
+        y[n, k, ih*stride - pad + r*dil, iw*stride - pad + s*dil] += x[n, c, ih, iw] * w[c, k, r, s]
+
+    over all (n, c, ih, iw, k, r, s) whose target lies inside the output.  x: (N,C,H,W),
+    w: (C,K,R,S), float32 or uint16 bf16 bits; sums in float64, one rounding to float32
+    (then bias, ReLU, and a second rounding to bf16 bits if out_bf16).  Pure numpy: one
+    channel contraction per filter tap, added into a strided view of the uncropped
+    output."""
+    x = np.asarray(x)
+    w = np.asarray(w)
+    xf = bf16_bits_to_f64(x) if x.dtype == np.uint16 else x.astype(np.float64)
+    wf = bf16_bits_to_f64(w) if w.dtype == np.uint16 else w.astype(np.float64)
+    N, C, H, W = xf.shape
+    C2, K, R, S = wf.shape
+    if C2 != C:
+        raise ValueError("conv2d_transpose: w is (C, K, R, S)")
+    _, _, OH, OW = conv2d_transpose_out_shape(xf.shape, wf.shape, stride, pad, dil)
+    if OH < 1 or OW < 1:
+        raise ValueError("conv2d_transpose: empty output")
+    FH, FW = (H - 1) * stride + dil * (R - 1) + 1, (W - 1) * stride + dil * (S - 1) + 1
+    full = np.zeros((N, K, FH, FW), dtype=np.float64)
+    for r in range(R):
+        for s in range(S):
+            full[:, :, r * dil:r * dil + (H - 1) * stride + 1:stride,
+                 s * dil:s * dil + (W - 1) * stride + 1:stride] += np.einsum("nchw,ck->nkhw", xf, wf[:, :, r, s])
+    y = full[:, :, pad:pad + OH, pad:pad + OW].astype(np.float32)
+    if bias is not None:
+        y = (y + np.asarray(bias, dtype=np.float32).reshape(1, K, 1, 1)).astype(np.float32)
+    if relu:
+        y = np.maximum(y, np.float32(0))
+    return f32_to_bf16_bits(y) if out_bf16 else y
+
+
 def conv_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
     d = _Conv(*x_shape, w_shape[0], w_shape[2], w_shape[3], stride, stride, pad, pad, dil, dil,
               0, 0, 0, 0)

@@ -361,3 +361,51 @@ def test_conv_unit_height_is_numpy_correlate(oracle):
                                   for k in range(4)]) for n in range(2)])
         assert got.shape == (2, 4, 1, ref.shape[-1])
         assert np.array_equal(got[:, :, 0, :].astype(np.float64), ref), (stride, pad, dil)
+
+
+@pytest.mark.parametrize("stride,pad,dil", [(1, 0, 1), (1, 1, 1), (2, 1, 1), (2, 0, 1), (3, 2, 2), (2, 2, 2)])
+def test_conv_transpose_vs_library_routine(oracle, stride, pad, dil):
+    """Against torch's conv_transpose2d in float64 (same weight convention (C, K, R, S))."""
+    x = normal_f32(81, (2, 5, 6, 7)).astype(np.float64).astype(np.float32)
+    w = normal_f32(82, (5, 3, 3, 4))
+    got = oracle.conv2d_transpose(x, w, stride=stride, pad=pad, dil=dil)
+    ref = torch.nn.functional.conv_transpose2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                               stride=stride, padding=pad, dilation=dil).numpy()
+    assert got.shape == ref.shape == oracle.conv2d_transpose_out_shape(x.shape, w.shape, stride, pad, dil)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+
+
+@pytest.mark.parametrize("stride,pad,dil", [(1, 1, 1), (2, 1, 1), (2, 0, 2), (3, 1, 1)])
+def test_conv_transpose_is_the_adjoint_of_conv(oracle, stride, pad, dil):
+    """<conv(a, w), b> == <a, conv_transpose(b, w)> for every a, b: with small integers both
+    sides are exact.  The filter (K, C, R, S) of the forward C2D is the (in = K, out = C, R, S)
+    filter of its adjoint."""
+    # input extents that the strided windows cover exactly, so that the adjoint returns a's own shape
+    H, W = stride * 4 + dil * 2 + 1 - 2 * pad, stride * 3 + dil * 2 + 1 - 2 * pad
+    a = small_ints_f32(91, (2, 4, H, W), -3, 3)
+    w = small_ints_f32(92, (6, 4, 3, 3), -3, 3)
+    fwd = oracle.conv2d(a, w, stride=stride, pad=pad, dil=dil)
+    b = small_ints_f32(93, fwd.shape, -3, 3)
+    back = oracle.conv2d_transpose(b, w, stride=stride, pad=pad, dil=dil)
+    assert back.shape == a.shape
+    lhs = float(np.sum(fwd.astype(np.float64) * b))
+    rhs = float(np.sum(a.astype(np.float64) * back))
+    assert lhs == rhs
+
+
+def test_conv_transpose_stride1_is_conv_with_flipped_filter(oracle):
+    x = small_ints_f32(95, (2, 3, 7, 6), -4, 4)
+    w = small_ints_f32(96, (3, 5, 3, 2), -4, 4)
+    got = oracle.conv2d_transpose(x, w, stride=1, pad=0)
+    wf = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+    ref = oracle.conv2d(x, wf, stride=1, pad=(2, 1))
+    assert np.array_equal(got, ref)
+    # one input pixel scatters one copy of the filter
+    d = np.zeros((1, 1, 4, 4), dtype=np.float32)
+    d[0, 0, 1, 2] = 2.0
+    k = small_ints_f32(97, (1, 1, 3, 3), -4, 4)
+    y = oracle.conv2d_transpose(d, k, stride=2, pad=0)
+    assert y.shape == (1, 1, 9, 9)
+    exp = np.zeros((9, 9), dtype=np.float32)
+    exp[2:5, 4:7] = 2.0 * k[0, 0]
+    assert np.array_equal(y[0, 0], exp)
