@@ -671,6 +671,27 @@ def main():
             tflops=round(gfl / float(grep_.best_us) / 1e6, 1), trials=grep_.trials,
             layout_us=dict(zip(gnames, [round(float(grep_.layout_best_us[i]), 2) for i in range(grep_.n_layouts)])))
 
+        # a decoder-style transposed convolution (128 -> 64 channels, 4x4, stride 2, 28x28 -> 56x56, batch 16):
+        # zero insertion + the forward kernels, per activation layout
+        t2d = {}
+        tfl = 2.0 * 16 * 128 * 64 * 16 * 28 * 28              # nominal: every input pixel meets every filter tap
+        for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
+            d = alt.conv_desc(16, 128, 28, 28, 64, 4, 4, stride=2, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                              x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
+            osh = h.conv2d_transpose_output_shape(d)
+            xb = torch.randint(-200, 200, (16 * 128 * 28 * 28,), dtype=torch.int16, device=dev)
+            wb = torch.randint(-200, 200, (128 * 64 * 16,), dtype=torch.int16, device=dev)
+            yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)
+            wsb = h.conv2d_transpose_workspace_size(d)
+            wsd = torch.empty(wsb + 16, dtype=torch.uint8, device=dev)
+            gr = capture(lambda st: h.conv2d_transpose(d, xb, wb, yb, workspace=wsd, ws_bytes=wsb, stream=st), 20)
+            us = graph_timed(gr, 20)
+            del gr, xb, wb, yb, wsd
+            t2d[xl] = dict(us=round(us, 2), nominal_tflops=round(tfl / us / 1e6, 1))
+        extra["conv_transpose_c128_k64_4x4_s2_28x28_b16"] = dict(
+            per_layout=t2d, speedup_vs_nchw=round(t2d["NCHW"]["us"] / min(v["us"] for v in t2d.values()), 2),
+            note="two launches per call (input expansion, forward kernel with default variant choice)")
+
     if want("budget"):
         # ------------------------------- budgeted search against the full one ----
         # the tuner with 48 measurements per layer (variants ranked by the cost estimate, measured best first)

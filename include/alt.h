@@ -229,6 +229,28 @@ alt_status_t alt_conv2d_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw
 alt_status_t alt_pack_weights(alt_handle_t h, const alt_conv_desc_t *d, const void *w_oihw,
                               void *w_packed, void *stream);
 
+/* Transposed 2-D convolution (T2D in the operator list of Section 6.1), the adjoint of the
+ * C2D that maps K channels to C with the same filter:
+ *   y[n,k,ih*stride-pad+r*dil, iw*stride-pad+s*dil] += x[n,c,ih,iw] * w[c,k,r,s],
+ *   OH = (H-1)*stride - 2*pad + dil*(R-1) + 1 (likewise OW); needs pad <= dil*(R-1), groups = 1.
+ * The descriptor's N,C,H,W describe x, K the output channels, R,S,stride,pad,dil the
+ * transposed operator; x_layout and y_layout are the layouts of x and y, w_layout the layout
+ * of the equivalent forward filter w'[k,c,r,s] = w[c,k,R-1-r,S-1-s] (logical (K,C,R,S)), which
+ * alt_pack_weights_transpose writes once, offline, from the dense (C,K,R,S) filter.
+ * It runs as the equivalent forward convolution: x with stride-1 zeros between its pixels
+ * (written into the workspace under x_layout by a kernel of its own; skipped for stride 1)
+ * convolved with w' at stride 1 and padding dil*(R-1)-pad by alt_conv2d's kernels (variant,
+ * epilogue, dtypes and tuning cache as for alt_conv2d).  `workspace` (device) holds the
+ * expanded input followed by what alt_conv2d wants; alt_conv2d_transpose_workspace_size
+ * reports the sum, and less than the expanded input's size fails with
+ * ALT_WORKSPACE_TOO_SMALL.  Asynchronous on `stream`. */
+alt_status_t alt_conv2d_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w_packed,
+                                  const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
+alt_status_t alt_conv2d_transpose_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
+alt_status_t alt_conv2d_transpose_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw);
+alt_status_t alt_pack_weights_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *w_ckrs,
+                                        void *w_packed, void *stream);
+
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and
  * operand loader).  Variant numbers are stable within one library build. */

@@ -144,7 +144,8 @@ def exported_symbols():
     return ["alt_create", "alt_destroy", "alt_last_error", "alt_status_string", "alt_version",
             "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
-            "alt_conv2d", "alt_conv2d_multi", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_conv2d", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
+            "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
@@ -363,6 +364,24 @@ class Handle:
         out = (ctypes.c_int64 * 4)()
         _ck(lib().alt_conv2d_output_shape(ctypes.byref(d), out))
         return tuple(out)
+
+    def conv2d_transpose(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_conv2d_transpose(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
+                                       _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv2d_transpose_workspace_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_conv2d_transpose_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def conv2d_transpose_output_shape(self, d):
+        out = (ctypes.c_int64 * 4)()
+        _ck(lib().alt_conv2d_transpose_output_shape(ctypes.byref(d), out))
+        return tuple(out)
+
+    def pack_weights_transpose(self, d, w_ckrs, w_packed, stream=None):
+        _ck(lib().alt_pack_weights_transpose(self._h, ctypes.byref(d), _ptr(w_ckrs), _ptr(w_packed),
+                                             _stream(stream)), self._h)
 
     def pack_weights(self, d, w_oihw, w_packed, stream=None):
         _ck(lib().alt_pack_weights(self._h, ctypes.byref(d), _ptr(w_oihw), _ptr(w_packed),

@@ -1,0 +1,288 @@
+// Transposed 2-D convolution (T2D in the operator list of Section 6.1 of the paper) on the
+// forward convolution kernels.  The scatter
+//   y[n,k,ih*stride-pad+r*dil, iw*stride-pad+s*dil] += x[n,c,ih,iw] * w[c,k,r,s]
+// is the gather of a stride-1 convolution over x with stride-1 zeros between its pixels,
+// with the filter mirrored in both directions, its channel dimensions exchanged, and
+// padding dil*(R-1)-pad.  Two small kernels prepare the operands under their layouts (the
+// filter once, offline: it is a constant like any other weight tensor, Section 4.2; the
+// expanded input per call, into the workspace), then alt_conv2d does the work.
+#include <hip/hip_runtime.h>
+
+#include <string>
+
+#include "common.h"
+#include "layout_eval.h"
+#include "ops.h"
+
+namespace alt {
+namespace {
+
+constexpr int kT2dThreads = 256;
+
+template <int ELSZ> struct Elem;
+template <> struct Elem<2> { using type = uint16_t; };
+template <> struct Elem<4> { using type = uint32_t; };
+template <int BYTES> struct Word;
+template <> struct Word<2> { using type = uint16_t; };
+template <> struct Word<4> { using type = uint32_t; };
+template <> struct Word<16> { using type = uint4; };
+
+struct SpreadParams {
+    const void *src;
+    void *dst;
+    BoundLayout ls, ld;           // x over (N,C,H,W); the expanded tensor over (N,C,(H-1)*sh+1,(W-1)*sw+1)
+    int32_t sh, sw;
+};
+
+// One thread per element of the expanded tensor: x's element where both spatial indices are
+// multiples of the stride, zero elsewhere.
+template <int ELSZ>
+__global__ __launch_bounds__(kT2dThreads) void t2d_spread_kernel(SpreadParams p)
+{
+    using E = typename Elem<ELSZ>::type;
+    const int64_t n = p.ld.numel;
+    for (int64_t e = blockIdx.x * (int64_t)kT2dThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kT2dThreads) {
+        int64_t idx[ALT_MAX_RANK];
+        int64_t r = e;
+        for (int d = 3; d >= 0; --d) { idx[d] = r % p.ld.shape[d]; r /= p.ld.shape[d]; }
+        const int64_t out = eval_offset(p.ld, idx);
+        E v = 0;
+        if (idx[2] % p.sh == 0 && idx[3] % p.sw == 0) {
+            idx[2] /= p.sh;
+            idx[3] /= p.sw;
+            v = ((const E *)p.src)[eval_offset(p.ls, idx)];
+        }
+        ((E *)p.dst)[out] = v;
+    }
+}
+
+// The same for separable layouts with fewer than 2^31 elements, walked in the order of the
+// expanded tensor's memory: a thread owns VEC consecutive elements there (one element, or
+// 16 bytes of a channel run when both layouts end in the same contiguous channel block),
+// recovers their logical index from the offset digit by digit and gathers from x.  All
+// index arithmetic is 32-bit with divisions by multiplication.
+struct FastAtom {
+    uint32_t dim, div, ext, stride;
+    FastDiv by_div, by_ext, by_stride;
+};
+struct FastLayout {
+    int32_t n, pad_;
+    FastAtom a[ALT_MAX_RANK];
+};
+struct SpreadFastParams {
+    const void *src;
+    void *dst;
+    FastLayout ls, ld;
+    FastDiv by_sh, by_sw;
+    uint32_t nvec, pad_;
+};
+
+__device__ __forceinline__ uint32_t fast_mod(uint32_t n, const FastDiv &f) { return n - fast_div(n, f) * f.d; }
+
+template <int ELSZ, int VEC>
+__global__ __launch_bounds__(kT2dThreads) void t2d_spread_fast_kernel(SpreadFastParams p)
+{
+    using V = typename Word<ELSZ * VEC>::type;
+    for (uint32_t v = blockIdx.x * kT2dThreads + threadIdx.x; v < p.nvec; v += gridDim.x * kT2dThreads) {
+        const uint32_t o = v * VEC;
+        uint32_t idx[4] = {0, 0, 0, 0};
+        for (int j = 0; j < p.ld.n; ++j) {
+            const FastAtom &a = p.ld.a[j];
+            idx[a.dim] += fast_mod(fast_div(o, a.by_stride), a.by_ext) * a.div;
+        }
+        const uint32_t qh = fast_div(idx[2], p.by_sh), qw = fast_div(idx[3], p.by_sw);
+        V w;
+        __builtin_memset(&w, 0, sizeof w);
+        if (qh * p.by_sh.d == idx[2] && qw * p.by_sw.d == idx[3]) {
+            idx[2] = qh;
+            idx[3] = qw;
+            uint32_t so = 0;
+            for (int j = 0; j < p.ls.n; ++j) {
+                const FastAtom &a = p.ls.a[j];
+                so += fast_mod(fast_div(idx[a.dim], a.by_div), a.by_ext) * a.stride;
+            }
+            w = *(const V *)((const char *)p.src + (size_t)so * ELSZ);
+        }
+        *(V *)((char *)p.dst + (size_t)o * ELSZ) = w;
+    }
+}
+
+bool fast_layout(const BoundLayout &b, FastLayout *out)
+{
+    if (!b.separable || b.ndim != 4 || b.numel >= ((int64_t)1 << 31) || b.nsub > ALT_MAX_RANK) return false;
+    out->n = b.nsub;
+    out->pad_ = 0;
+    for (int j = 0; j < b.nsub; ++j) {
+        const Atom &a = b.atom[j];
+        if (a.div >= ((int64_t)1 << 31) || a.ext >= ((int64_t)1 << 31) || a.stride >= ((int64_t)1 << 31) || a.stride < 1) return false;
+        FastAtom &f = out->a[j];
+        f.dim = (uint32_t)a.dim; f.div = (uint32_t)a.div; f.ext = (uint32_t)a.ext; f.stride = (uint32_t)a.stride;
+        f.by_div = make_fastdiv(f.div); f.by_ext = make_fastdiv(f.ext); f.by_stride = make_fastdiv(f.stride);
+    }
+    return true;
+}
+
+// Elements per thread: eight (16 bytes of bf16) or four (of fp32) when both layouts end in
+// the same contiguous channel piece whose extent is a multiple of that, else one.
+int spread_vec(const BoundLayout &ls, const BoundLayout &ld, int elsz, const void *src, const void *dst)
+{
+    const int want = 16 / elsz;
+    const Atom *is = nullptr, *id = nullptr;
+    for (int j = 0; j < ls.nsub; ++j) if (ls.atom[j].stride == 1) is = &ls.atom[j];
+    for (int j = 0; j < ld.nsub; ++j) if (ld.atom[j].stride == 1) id = &ld.atom[j];
+    if (!is || !id || is->dim != 1 || id->dim != 1 || is->div != 1 || id->div != 1 || is->ext != id->ext) return 1;
+    if (is->ext % want || (uintptr_t)src % 16 || (uintptr_t)dst % 16) return 1;
+    return want;
+}
+
+struct FlipParams {
+    const void *src;              // dense (C,K,R,S)
+    void *dst;
+    BoundLayout ld;               // the forward filter (K,C,R,S) under w_layout
+};
+
+// w'[k,c,r,s] = w[c,k,R-1-r,S-1-s], one thread per element.
+template <int ELSZ>
+__global__ __launch_bounds__(kT2dThreads) void t2d_flip_kernel(FlipParams p)
+{
+    using E = typename Elem<ELSZ>::type;
+    const int64_t n = p.ld.numel;
+    const int64_t K = p.ld.shape[0], C = p.ld.shape[1], R = p.ld.shape[2], S = p.ld.shape[3];
+    for (int64_t e = blockIdx.x * (int64_t)kT2dThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kT2dThreads) {
+        int64_t idx[ALT_MAX_RANK];
+        int64_t r = e;
+        for (int d = 3; d >= 0; --d) { idx[d] = r % p.ld.shape[d]; r /= p.ld.shape[d]; }
+        const int64_t src = ((idx[1] * K + idx[0]) * R + (R - 1 - idx[2])) * S + (S - 1 - idx[3]);
+        (void)C;
+        ((E *)p.dst)[eval_offset(p.ld, idx)] = ((const E *)p.src)[src];
+    }
+}
+
+unsigned blocks_for(int64_t n)
+{
+    const int64_t b = (n + kT2dThreads - 1) / kT2dThreads;
+    return (unsigned)(b < 1 ? 1 : b > 256 * 64 ? 256 * 64 : b);
+}
+
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+// The equivalent forward problem of a transposed-convolution descriptor.
+alt_status_t forward_desc(alt_handle_t h, const alt_conv_desc_t *d, alt_conv_desc_t *f)
+{
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1)
+        return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: extents must be positive");
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1 || d->pad_h < 0 || d->pad_w < 0)
+        return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: bad stride, padding or dilation");
+    if (d->groups > 1) return fail(h, ALT_UNSUPPORTED, "alt_conv2d_transpose: groups are not supported");
+    if (d->pad_h > d->dil_h * (d->R - 1) || d->pad_w > d->dil_w * (d->S - 1))
+        return fail(h, ALT_UNSUPPORTED, "alt_conv2d_transpose: padding beyond dil*(R-1) is not supported");
+    *f = *d;
+    f->H = (d->H - 1) * d->stride_h + 1;
+    f->W = (d->W - 1) * d->stride_w + 1;
+    f->stride_h = f->stride_w = 1;
+    f->pad_h = d->dil_h * (int32_t)(d->R - 1) - d->pad_h;
+    f->pad_w = d->dil_w * (int32_t)(d->S - 1) - d->pad_w;
+    return ALT_OK;
+}
+
+}  // namespace
+}  // namespace alt
+
+using namespace alt;
+
+extern "C" alt_status_t alt_conv2d_transpose_output_shape(const alt_conv_desc_t *d, int64_t *out)
+{
+    if (!d || !out) return ALT_INVALID_ARG;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1) return ALT_INVALID_ARG;
+    out[0] = d->N;
+    out[1] = d->K;
+    out[2] = (d->H - 1) * d->stride_h - 2 * d->pad_h + d->dil_h * (d->R - 1) + 1;
+    out[3] = (d->W - 1) * d->stride_w - 2 * d->pad_w + d->dil_w * (d->S - 1) + 1;
+    return (out[2] < 1 || out[3] < 1) ? ALT_INVALID_ARG : ALT_OK;
+}
+
+extern "C" alt_status_t alt_conv2d_transpose_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
+    alt_conv_desc_t f;
+    alt_status_t s = forward_desc(h, d, &f);
+    if (s != ALT_OK) return s;
+    size_t conv_ws = 0;
+    if ((s = alt_conv2d_workspace_size(h, &f, &conv_ws)) != ALT_OK) return s;
+    const bool spread = d->stride_h > 1 || d->stride_w > 1;
+    *bytes = (spread ? round256((size_t)(f.N * f.C * f.H * f.W) * dtype_size(d->in_dtype)) : 0) + conv_ws;
+    return ALT_OK;
+}
+
+extern "C" alt_status_t alt_pack_weights_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *w_ckrs,
+                                                   void *w_packed, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !w_ckrs || !w_packed) return fail(h, ALT_INVALID_ARG, "alt_pack_weights_transpose: null argument");
+    if (d->in_dtype != ALT_F32 && d->in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_pack_weights_transpose: bad dtype");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const int64_t wsh[4] = {d->K, d->C, d->R, d->S};
+    FlipParams p;
+    std::string err;
+    alt_status_t s = bind_layout(&d->w_layout, 4, wsh, &p.ld, &err);
+    if (s != ALT_OK) return fail(h, s, "w_layout: %s", err.c_str());
+    p.src = w_ckrs;
+    p.dst = w_packed;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype_size(d->in_dtype) == 2) hipLaunchKernelGGL(t2d_flip_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kT2dThreads), 0, st, p);
+    else hipLaunchKernelGGL(t2d_flip_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kT2dThreads), 0, st, p);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+extern "C" alt_status_t alt_conv2d_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w_packed,
+                                             const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !x || !w_packed || !y) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: null argument");
+    if (d->in_dtype != ALT_F32 && d->in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: bad dtype");
+    alt_conv_desc_t f;
+    alt_status_t s = forward_desc(h, d, &f);
+    if (s != ALT_OK) return s;
+    if (d->stride_h == 1 && d->stride_w == 1)
+        return alt_conv2d(h, &f, x, w_packed, bias, y, workspace, ws_bytes, stream);
+
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const size_t xe_bytes = round256((size_t)(f.N * f.C * f.H * f.W) * dtype_size(d->in_dtype));
+    if (!workspace || ws_bytes < xe_bytes)
+        return fail(h, ALT_WORKSPACE_TOO_SMALL, "alt_conv2d_transpose: the workspace must hold the expanded input (%zu bytes)", xe_bytes);
+    if ((uintptr_t)workspace % 16) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: workspace must be 16-byte aligned");
+    SpreadParams p;
+    const int64_t xs[4] = {d->N, d->C, d->H, d->W}, es[4] = {f.N, f.C, f.H, f.W};
+    std::string err;
+    if ((s = bind_layout(&d->x_layout, 4, xs, &p.ls, &err)) != ALT_OK) return fail(h, s, "x_layout: %s", err.c_str());
+    if ((s = bind_layout(&d->x_layout, 4, es, &p.ld, &err)) != ALT_OK) return fail(h, s, "x_layout (expanded input): %s", err.c_str());
+    p.src = x;
+    p.dst = workspace;
+    p.sh = d->stride_h;
+    p.sw = d->stride_w;
+    hipStream_t st = (hipStream_t)stream;
+    const int elsz = (int)dtype_size(d->in_dtype);
+    SpreadFastParams q;
+    if (fast_layout(p.ls, &q.ls) && fast_layout(p.ld, &q.ld)) {
+        const int vec = spread_vec(p.ls, p.ld, elsz, x, workspace);
+        q.src = x;
+        q.dst = workspace;
+        q.by_sh = make_fastdiv((uint32_t)d->stride_h);
+        q.by_sw = make_fastdiv((uint32_t)d->stride_w);
+        q.nvec = (uint32_t)(p.ld.numel / vec);
+        q.pad_ = 0;
+        const dim3 grid(blocks_for(q.nvec)), block(kT2dThreads);
+        if (elsz == 2 && vec == 8) hipLaunchKernelGGL((t2d_spread_fast_kernel<2, 8>), grid, block, 0, st, q);
+        else if (elsz == 2) hipLaunchKernelGGL((t2d_spread_fast_kernel<2, 1>), grid, block, 0, st, q);
+        else if (vec == 4) hipLaunchKernelGGL((t2d_spread_fast_kernel<4, 4>), grid, block, 0, st, q);
+        else hipLaunchKernelGGL((t2d_spread_fast_kernel<4, 1>), grid, block, 0, st, q);
+    } else if (elsz == 2) {
+        hipLaunchKernelGGL(t2d_spread_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kT2dThreads), 0, st, p);
+    } else {
+        hipLaunchKernelGGL(t2d_spread_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kT2dThreads), 0, st, p);
+    }
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return alt_conv2d(h, &f, workspace, w_packed, bias, y, (char *)workspace + xe_bytes, ws_bytes - xe_bytes, stream);
+}

@@ -459,3 +459,73 @@ def test_conv1d_is_conv2d_with_unit_height(h):
             h.conv2d(d, dev(to_layout(f32_to_bf16_bits(x), "NCHW", xl)), dev(to_layout(f32_to_bf16_bits(w), "OIHW", wl)), yd)
             assert canary_ok(whole, n_out)
             assert np.array_equal(from_layout(host(yd, np.float32), oshape, "NCHW", xl), ref), (N, C, L, K, S, cfg, xl)
+
+
+T2D_LAYOUTS = [("NCHW", "OIHW", "NCHW"), ("NHWC", "OHWI", "NHWC"), ("NCHW16c", "OIHW16o16i", "NCHW16c"), ("NHWC", "OHWI", "NCHW")]
+
+
+def run_conv_transpose(h, x, w, cfg, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False):
+    """x (N,C,H,W), w (C,K,R,S) logical; returns the logical (N,K,OH,OW) result."""
+    N, C, H, W = x.shape
+    _, K, R, S = w.shape
+    epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
+    d = alt.conv_desc(N, C, H, W, K, R, S, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), in_dtype=in_dtype,
+                      out_dtype=out_dtype, epilogue=epi, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+    oshape = h.conv2d_transpose_output_shape(d)
+    wd = torch.empty_like(dev(w.reshape(-1)))
+    h.pack_weights_transpose(d, dev(w.reshape(-1)), wd)
+    ydt = np.float32 if out_dtype == alt.F32 else np.uint16
+    n_out = int(np.prod(oshape))
+    whole, yd = canary_dev(n_out, ydt)
+    ws_bytes = h.conv2d_transpose_workspace_size(d) + 36 * n_out * 4
+    ws = torch.empty(ws_bytes // 4 + 4, dtype=torch.float32, device="cuda")
+    h.conv2d_transpose(d, dev(to_layout(x, "NCHW", xl)), wd, yd, bias=dev(bias) if bias is not None else None,
+                       workspace=ws, ws_bytes=ws_bytes)
+    got = host(yd, ydt)
+    assert canary_ok(whole, n_out), "wrote outside y"
+    return from_layout(got, oshape, "NCHW", yl), d
+
+
+@pytest.mark.parametrize("layouts", T2D_LAYOUTS, ids=lambda l: "_".join(l))
+@pytest.mark.parametrize("in_dtype", [alt.BF16, alt.F32])
+def test_conv_transpose_exact_integers(h, layouts, in_dtype):
+    """Transposed C2D (Section 6.1's T2D): zero insertion, mirrored filter and the forward kernels,
+    bit for bit against the oracle's scatter definition: strides 1-3, padding up to dil*(R-1),
+    dilation, ragged sizes, bias and ReLU."""
+    xl, wl, yl = layouts
+    for (N, C, H, W, K, R, S, cfg) in [(2, 32, 7, 9, 48, 3, 3, dict(stride=2, pad=1)), (1, 64, 5, 6, 32, 3, 3, dict(stride=1, pad=1)),
+                                       (2, 16, 6, 5, 32, 4, 4, dict(stride=2, pad=1)), (1, 32, 4, 7, 16, 3, 2, dict(stride=3, pad=0)),
+                                       (2, 16, 8, 5, 16, 3, 3, dict(stride=2, pad=2, dil=2))]:
+        x = small_ints_f32(601, (N, C, H, W), -3, 3)
+        w = small_ints_f32(602, (C, K, R, S), -3, 3)
+        b = small_ints_f32(603, (K,), -20, 20)
+        ref = oracle.conv2d_transpose(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), bias=b, relu=True)
+        xi, wi = (f32_to_bf16_bits(x), f32_to_bf16_bits(w)) if in_dtype == alt.BF16 else (x, w)
+        got, _ = run_conv_transpose(h, xi, wi, cfg, xl, wl, yl, in_dtype, bias=b, relu=True)
+        assert got.shape == ref.shape
+        assert np.array_equal(got, ref), (N, C, H, W, K, R, S, cfg)
+
+
+def test_conv_transpose_tolerance_and_errors(h):
+    """A decoder-style layer (C=128 -> K=64, 4x4, stride 2, 28x28 -> 56x56, batch 4) with normal
+    inputs, bf16 in and out, against the oracle within the bf16 bound; then the error paths."""
+    x = f32_to_bf16_bits(normal_f32(611, (4, 128, 28, 28)))
+    w = f32_to_bf16_bits(normal_f32(612, (128, 64, 4, 4), std=0.05))
+    ref = bf16_bits_to_f32(oracle.conv2d_transpose(x, w, stride=2, pad=1, out_bf16=True)).astype(np.float64)
+    got, d = run_conv_transpose(h, x, w, dict(stride=2, pad=1), "NHWC", "OHWI", "NHWC", alt.BF16, out_dtype=alt.BF16)
+    assert got.shape == (4, 64, 56, 56)
+    got = bf16_bits_to_f32(got).astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    assert float(np.max(np.abs(got - ref) / (np.abs(ref) + rms))) <= 2.0 ** -7
+    a = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose(d, a, a, a, workspace=a, ws_bytes=1024)          # expanded input does not fit
+    assert e.value.status == 5
+    bad = alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=3)
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose(bad, a, a, a, workspace=a, ws_bytes=a.numel() * 4)   # padding beyond dil*(R-1)
+    assert e.value.status == 4
+    bad = alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=1, groups=2)
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose(bad, a, a, a, workspace=a, ws_bytes=a.numel() * 4)
+    assert e.value.status == 4
