@@ -250,7 +250,7 @@ def _plan_entries():
     out = [(key, name, e) for key in ("bf16_out", "f32_out") for name, e in plan.get(key, {}).items()]
     # the variants chosen jointly for the five-stream step: same layouts as bf16_out, another kernel
     for name, variant in plan.get("bf16_out_concurrent", {}).items():
-        base = plan.get("bf16_out", {}).get(name)
+        base = plan.get("bf16_out", {}).get(name)      # (the entry "issue_order" is not a layer)
         if base and base["variant"] != variant:
             out.append(("bf16_out_concurrent", name, dict(base, variant=variant)))
     return out
