@@ -214,3 +214,26 @@ def test_calls_without_gpu_fail_loudly_not_silently():
     with pytest.raises(alt.AltError) as e:
         h.conv2d(bad, 16, 16, 16, stream=0)
     assert e.value.status == 3
+
+
+def test_conv_transpose_host_side(oracle):
+    """Output shape of the transposed C2D against the oracle's, argument checks that need no
+    device, and the multi-call entry's handling of an empty or bad list."""
+    for (H, W, R, S, stride, pad, dil) in [(7, 9, 3, 3, 2, 1, 1), (5, 6, 4, 4, 2, 1, 1), (4, 7, 3, 2, 3, 0, 1), (8, 5, 3, 3, 2, 2, 2)]:
+        d = alt.conv_desc(2, 16, H, W, 32, R, S, stride=stride, pad=pad, dil=dil)
+        h = alt.Handle()
+        assert h.conv2d_transpose_output_shape(d) == oracle.conv2d_transpose_out_shape((2, 16, H, W), (16, 32, R, S), stride, pad, dil)
+    h = alt.Handle()
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose(alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=3), 16, 16, 16, workspace=16, ws_bytes=1 << 20, stream=0)
+    assert e.value.status == 4                                      # padding beyond dil*(R-1)
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose(alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=1, groups=2), 16, 16, 16, workspace=16, ws_bytes=1 << 20, stream=0)
+    assert e.value.status == 4
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_transpose_workspace_size(alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=0, pad=1))
+    assert e.value.status == 1
+    h.conv2d_multi([])                                              # nothing to issue: fine
+    import ctypes
+    assert alt.lib().alt_conv2d_multi(h._h, None, ctypes.c_int32(2)) == 1
+    assert alt.lib().alt_conv2d_multi(h._h, None, ctypes.c_int32(-1)) == 1
