@@ -218,80 +218,18 @@ def main():
         return h.conv2d_multi_prepared([calls[i] for i in (order or range(len(calls)))])
 
     def co_tune(layers):
-        """Kernel variants for the five-stream launch, chosen jointly.  Tuned one at a time
-        each layer gets the variant that is fastest alone on an idle chip; launched together
-        the layers share compute units, LDS and L2, and a variant that leaves room for a
-        neighbour's workgroups can make the step faster although it is slower alone.  The
-        search is the cross exploration of Section 5.2 with the step as the cost: per layer
-        the candidates are the variants within 2x of its best alone (split-K ones aside:
-        their workspace is not provisioned here), and rounds of coordinate descent replace
-        one layer's variant at a time whenever the measured step time drops; last, the order
-        in which the one call issues the five launches is chosen the same way."""
+        """Kernel variants and issue order for the five-stream launch, chosen jointly by
+        alt_tune_conv2d_multi (coordinate descent on the measured time of the whole step)."""
         import copy
-
-        def step_us(descs, steps, order=None):
-            run = multi_step(layers, descs, order)
-            for _ in range(10):
-                run()
-            torch.cuda.synchronize()
-            out = []
-            for _ in range(3):
-                t0 = time.perf_counter()
-                for _ in range(steps):
-                    run()
-                torch.cuda.synchronize()
-                out.append((time.perf_counter() - t0) * 1e6 / steps)
-            return sorted(out)[1]
-
-        cands = []
-        for l in layers:
-            mine = []
-            for v in range(h.conv2d_variant_count(l["desc"])):
-                try:
-                    name = h.conv2d_variant_name(l["desc"], v)
-                except alt.AltError:
-                    continue
-                if not name.endswith("_k1"):
-                    continue
-                d = copy.copy(l["desc"])
-                d.variant = v
-                try:
-                    g = capture(lambda st, d=d: h.conv2d(d, l["x"], l["w"], l["y"], workspace=l["ws"],
-                                                         ws_bytes=l["ws_bytes"], stream=st), 20)
-                except alt.AltError:
-                    continue
-                mine.append((graph_timed(g, 20, replays=4, batches=3), d))
-                del g
-            mine.sort(key=lambda c: c[0])
-            cands.append([d for us, d in mine if us <= 2.0 * mine[0][0]][:40])
-        choice = [l["desc"] for l in layers]
-        best = step_us(choice, 300)
-        measurements = 1
-        for _ in range(3):
-            improved = False
-            for i in range(len(layers)):
-                for d in cands[i]:
-                    if d.variant == choice[i].variant:
-                        continue
-                    trial = list(choice)
-                    trial[i] = d
-                    measurements += 1
-                    if step_us(trial, 150) < best * 0.985:
-                        us = step_us(trial, 300)           # confirm before taking it
-                        if us < best * 0.99:
-                            best, choice, improved = us, trial, True
-            if not improved:
-                break
-        # then the order in which the call issues them (the streams stay with their layers)
-        import itertools
-        order = list(range(len(layers)))
-        for perm in itertools.permutations(range(len(layers))):
-            measurements += 1
-            if step_us(choice, 100, list(perm)) < best * 0.985:
-                us = step_us(choice, 300, list(perm))
-                if us < best * 0.99:
-                    best, order = us, list(perm)
-        return choice, order, measurements
+        calls = [dict(d=l["desc"], x=l["x"], w=l["w"], y=l["y"], workspace=l["ws"], ws_bytes=l["ws_bytes"], stream=lanes[i])
+                 for i, l in enumerate(layers)]
+        variants, order, _, measurements = h.tune_conv2d_multi(calls)
+        descs = []
+        for l, v in zip(layers, variants):
+            d = copy.copy(l["desc"])
+            d.variant = v
+            descs.append(d)
+        return descs, order, measurements
 
     def measure_step(layers, co_descs=None, co_order=None):
         """Times the step over `layers` as one HIP graph replayed args.steps times, then each layer on its own."""

@@ -323,6 +323,26 @@ alt_status_t alt_tune_gemm(alt_handle_t h, const alt_gemm_desc_t *shape, const a
 alt_status_t alt_tune_conv2d_variants(alt_handle_t h, alt_conv_desc_t *d, const alt_tune_opts_t *opts,
                                       float *best_us, int *trials);
 
+/* Loop-only stage for n independent convolutions that alt_conv2d_multi launches together
+ * (n <= ALT_MAX_MULTI).  Tuned one at a time each problem gets the variant that is fastest
+ * alone on an idle chip; launched together they share compute units, LDS and L2, and a
+ * variant that leaves room for a neighbour's workgroups can make the whole launch faster
+ * though it is slower alone.  So the cost here is the measured time of one alt_conv2d_multi
+ * step (Section 5.2's cross exploration with the launch as the unit): every problem's
+ * variants are first timed alone on its stream (at most opts->max_trials each when > 0; those
+ * within 2x of its best stay candidates, split-K ones only if calls[i].workspace holds their
+ * partial sums), then rounds of coordinate descent replace one problem's variant at a time
+ * while the step gets faster, and last the order in which the step issues the calls is chosen
+ * the same way (all orders for n <= 5).  The layouts in calls[i].d are kept.  Writes the chosen
+ * variant of call i to variants[i], the issue order (indices into calls) to order[0..n), the
+ * step time to *step_us and the number of step measurements to *measurements (either may be
+ * NULL).  Uses the callers' buffers and streams: the outputs are overwritten.  Depth-wise
+ * problems have no variants and are refused.  opts->arena is not used.  Synchronises. */
+#define ALT_MAX_MULTI 8
+alt_status_t alt_tune_conv2d_multi(alt_handle_t h, const alt_conv_call_t *calls, int32_t n,
+                                   const alt_tune_opts_t *opts, int32_t *variants, int32_t *order,
+                                   float *step_us, int32_t *measurements);
+
 #define ALT_MAX_CHAIN 8
 
 typedef struct {

@@ -149,7 +149,7 @@ def exported_symbols():
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
-            "alt_tune_conv2d_variants", "alt_tune_chain", "alt_plan_chain",
+            "alt_tune_conv2d_variants", "alt_tune_conv2d_multi", "alt_tune_chain", "alt_plan_chain",
             "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
             "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak"]
 
@@ -329,20 +329,25 @@ class Handle:
             return keep is None
         return run
 
-    def conv2d_multi_prepared(self, calls):
-        """alt_conv2d_multi over `calls`, a list of dicts with the keyword arguments of
-        conv2d (d, x, w, y and optionally bias, workspace, ws_bytes, stream), marshalled
-        once: returns a function of no arguments that issues them all."""
+    @staticmethod
+    def _call_array(calls):
         n = len(calls)
         arr = (ConvCall * n)()
-        keep = []
         for i, c in enumerate(calls):
             arr[i].d = ctypes.pointer(c["d"])
             for k in ("x", "w", "bias", "y", "workspace"):
                 setattr(arr[i], k, _ptr(c.get(k)))
             arr[i].ws_bytes = int(c.get("ws_bytes", 0))
             arr[i].stream = _stream(c.get("stream"))
-            keep.append(c)
+        return arr
+
+    def conv2d_multi_prepared(self, calls):
+        """alt_conv2d_multi over `calls`, a list of dicts with the keyword arguments of
+        conv2d (d, x, w, y and optionally bias, workspace, ws_bytes, stream), marshalled
+        once: returns a function of no arguments that issues them all."""
+        n = len(calls)
+        arr = self._call_array(calls)
+        keep = list(calls)
         fn, hh, nn = lib().alt_conv2d_multi, self._h, ctypes.c_int32(n)
 
         def run():
@@ -451,6 +456,18 @@ class Handle:
         _ck(lib().alt_tune_conv2d_variants(self._h, ctypes.byref(d), ctypes.byref(o), ctypes.byref(us),
                                            ctypes.byref(trials)), self._h)
         return us.value, trials.value
+
+    def tune_conv2d_multi(self, calls, max_trials=0, warmup=3, reps=20):
+        """alt_tune_conv2d_multi over `calls` (as for conv2d_multi): returns (variants, order,
+        step_us, measurements)."""
+        n = len(calls)
+        arr = self._call_array(calls)
+        variants, order = (ctypes.c_int32 * n)(), (ctypes.c_int32 * n)()
+        us, meas = ctypes.c_float(), ctypes.c_int32()
+        o = TuneOpts(max_trials, warmup, reps, 0, None, 0, None)
+        _ck(lib().alt_tune_conv2d_multi(self._h, arr, ctypes.c_int32(n), ctypes.byref(o), variants, order,
+                                        ctypes.byref(us), ctypes.byref(meas)), self._h)
+        return list(variants), list(order), us.value, meas.value
 
     def tune_chain(self, ops, in_layout, arena, arena_bytes, max_trials=0, warmup=3, reps=20, stream=None):
         arr = (ConvDesc * len(ops))(*ops)

@@ -7,6 +7,7 @@
 // measurement; the budget counts measurements (Section 6).  Also the tune
 // cache and the chain planner.
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <fstream>
 #include <sstream>
@@ -930,6 +931,123 @@ alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int n
     }
     if (in_idx != 0) dflt += CC(0, in_idx, 0);     // the all-NCHW graph converts its input once
     plan->default_total_us = (float)dflt;
+    return ALT_OK;
+}
+
+alt_status_t alt_tune_conv2d_multi(alt_handle_t h, const alt_conv_call_t *calls, int32_t n, const alt_tune_opts_t *opts,
+                                   int32_t *variants, int32_t *order, float *step_us, int32_t *measurements)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!calls || !opts || !variants || !order || n < 1 || n > ALT_MAX_MULTI)
+        return fail(h, ALT_INVALID_ARG, "alt_tune_conv2d_multi: bad arguments");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    Timer tm;
+    if (!tm.ok) return fail(h, ALT_HIP_ERROR, "hipEventCreate failed");
+    const int warmup = opt_warmup(opts), reps = opt_reps(opts);
+
+    struct Cand { int variant; float us; };
+    std::vector<Problem> pb(n);
+    std::vector<std::vector<Cand>> cands(n);
+    std::vector<int> choice(n);
+    for (int i = 0; i < n; ++i) {
+        const alt_conv_call_t &c = calls[i];
+        if (!c.d || !c.x || !c.w || !c.y) return fail(h, ALT_INVALID_ARG, "alt_tune_conv2d_multi: null argument in call %d", i);
+        alt_status_t s = conv_problem(h, c.d, c.x, c.w, c.bias, c.y, &pb[i]);
+        if (s != ALT_OK) return s;
+        if (pb[i].depthwise) return fail(h, ALT_UNSUPPORTED, "alt_tune_conv2d_multi: call %d is depth-wise (no variants)", i);
+        const size_t ws_limit = c.workspace ? c.ws_bytes : 0;
+        int done = 0;
+        for (const Trial &t : ordered_variants(pb[i], ws_limit)) {
+            if (opts->max_trials > 0 && done >= opts->max_trials) break;
+            float us = 0.f;
+            s = measure(h, tm, (hipStream_t)c.stream, warmup, reps,
+                        [&] { return igemm_run(h, pb[i], t.variant, c.workspace, ws_limit, (hipStream_t)c.stream); }, &us);
+            if (s != ALT_OK) return s;
+            ++done;
+            cands[i].push_back({t.variant, us});
+        }
+        if (cands[i].empty()) return fail(h, ALT_UNSUPPORTED, "alt_tune_conv2d_multi: no kernel variant applies to call %d", i);
+        std::sort(cands[i].begin(), cands[i].end(), [](const Cand &a, const Cand &b) { return a.us < b.us; });
+        size_t keep = 0;
+        while (keep < cands[i].size() && keep < 40 && cands[i][keep].us <= 2.f * cands[i][0].us) ++keep;
+        cands[i].resize(keep);
+        choice[i] = cands[i][0].variant;
+        // a variant the caller asked for starts the search if it is among the candidates
+        for (const Cand &k : cands[i])
+            if (k.variant == c.d->variant) choice[i] = k.variant;
+    }
+
+    std::vector<int> ord(n);
+    for (int i = 0; i < n; ++i) ord[i] = i;
+    auto sync_all = [&]() -> alt_status_t {
+        for (int i = 0; i < n; ++i) ALT_CHECK_HIP(h, hipStreamSynchronize((hipStream_t)calls[i].stream));
+        return ALT_OK;
+    };
+    // microseconds per step of the launch under `var` issued in order `o`: median of three runs of `steps`
+    auto step_time = [&](const std::vector<int> &var, const std::vector<int> &o, int steps, float *us) -> alt_status_t {
+        auto one = [&]() -> alt_status_t {
+            for (int k = 0; k < n; ++k) {
+                const alt_conv_call_t &c = calls[o[k]];
+                alt_status_t s = igemm_run(h, pb[o[k]], var[o[k]], c.workspace, c.workspace ? c.ws_bytes : 0, (hipStream_t)c.stream);
+                if (s != ALT_OK) return s;
+            }
+            return ALT_OK;
+        };
+        alt_status_t s;
+        for (int w = 0; w < 10; ++w)
+            if ((s = one()) != ALT_OK) return s;
+        if ((s = sync_all()) != ALT_OK) return s;
+        float t[3];
+        for (int r = 0; r < 3; ++r) {
+            const auto t0 = std::chrono::steady_clock::now();
+            for (int k = 0; k < steps; ++k)
+                if ((s = one()) != ALT_OK) return s;
+            if ((s = sync_all()) != ALT_OK) return s;
+            t[r] = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count() / steps;
+        }
+        std::sort(t, t + 3);
+        *us = t[1];
+        return ALT_OK;
+    };
+
+    int nmeas = 0;
+    float best = 0.f;
+    alt_status_t s = step_time(choice, ord, 300, &best);
+    if (s != ALT_OK) return s;
+    ++nmeas;
+    for (int round = 0; round < 3; ++round) {
+        bool improved = false;
+        for (int i = 0; i < n; ++i)
+            for (const Cand &k : cands[i]) {
+                if (k.variant == choice[i]) continue;
+                std::vector<int> trial = choice;
+                trial[i] = k.variant;
+                float us = 0.f;
+                if ((s = step_time(trial, ord, 150, &us)) != ALT_OK) return s;
+                ++nmeas;
+                if (us >= best * 0.985f) continue;
+                if ((s = step_time(trial, ord, 300, &us)) != ALT_OK) return s;   // confirm before taking it
+                ++nmeas;
+                if (us < best * 0.99f) { best = us; choice = trial; improved = true; }
+            }
+        if (!improved) break;
+    }
+    if (n <= 5) {
+        std::vector<int> perm = ord, best_ord = ord;
+        while (std::next_permutation(perm.begin(), perm.end())) {
+            float us = 0.f;
+            if ((s = step_time(choice, perm, 100, &us)) != ALT_OK) return s;
+            ++nmeas;
+            if (us >= best * 0.985f) continue;
+            if ((s = step_time(choice, perm, 300, &us)) != ALT_OK) return s;
+            ++nmeas;
+            if (us < best * 0.99f) { best = us; best_ord = perm; }
+        }
+        ord = best_ord;
+    }
+    for (int i = 0; i < n; ++i) { variants[i] = choice[i]; order[i] = ord[i]; }
+    if (step_us) *step_us = best;
+    if (measurements) *measurements = nmeas;
     return ALT_OK;
 }
 

@@ -232,3 +232,46 @@ def test_eltwise_add_bit_exact(h, dtype):
             got = host(y, npdt)
             assert np.array_equal(got[:numel], oracle.eltwise_add(a, bb, relu=relu)), (numel, relu)
             assert (host(y, npdt)[numel:] == host(torch.full((16,), 77, dtype=tdt), npdt)).all()   # nothing past the end
+
+
+def test_tune_conv2d_multi_returns_a_valid_launch(h):
+    """Joint choice for three independent convolutions on three streams: the variants apply,
+    the order is a permutation, and the launch under them gives the oracle's integers."""
+    import copy
+    import oracle
+    from workloads import small_ints_f32, f32_to_bf16_bits
+    from gpu_util import dev, host, to_layout, from_layout
+    cases = [(2, 64, 12, 12, 64, 3, dict(stride=1, pad=1)), (2, 128, 10, 10, 64, 1, dict(stride=1, pad=0)),
+             (1, 128, 7, 7, 128, 3, dict(stride=1, pad=1))]
+    streams = [torch.cuda.Stream() for _ in cases]
+    calls, refs, outs = [], [], []
+    for i, (N, C, H, W, K, R, cfg) in enumerate(cases):
+        x = small_ints_f32(701 + i, (N, C, H, W), -3, 3)
+        w = small_ints_f32(751 + i, (K, C, R, R), -3, 3)
+        refs.append(oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"]))
+        d = alt.conv_desc(N, C, H, W, K, R, R, stride=cfg["stride"], pad=cfg["pad"], in_dtype=alt.BF16,
+                          x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+        oshape = h.conv2d_output_shape(d)
+        yd = torch.zeros(int(np.prod(oshape)), dtype=torch.float32, device="cuda")
+        calls.append(dict(d=d, x=dev(to_layout(f32_to_bf16_bits(x), "NCHW", "NHWC")), w=dev(to_layout(f32_to_bf16_bits(w), "OIHW", "OHWI")),
+                          y=yd, stream=streams[i]))
+        outs.append((yd, oshape))
+    torch.cuda.synchronize()
+    variants, order, step_us, meas = h.tune_conv2d_multi(calls, max_trials=12, warmup=1, reps=3)
+    assert sorted(order) == [0, 1, 2] and step_us > 0 and meas >= 1
+    tuned = []
+    for c, v in zip(calls, variants):
+        d = copy.copy(c["d"])
+        d.variant = v
+        assert h.conv2d_variant_name(d, v)                     # raises if the variant does not apply
+        tuned.append(dict(c, d=d))
+    for yd, _ in outs:
+        yd.zero_()
+    torch.cuda.synchronize()
+    h.conv2d_multi([tuned[i] for i in order])
+    torch.cuda.synchronize()
+    for (yd, oshape), ref in zip(outs, refs):
+        assert np.array_equal(from_layout(host(yd, np.float32), oshape, "NCHW", "NHWC"), ref)
+    with pytest.raises(alt.AltError) as e:
+        h.tune_conv2d_multi([])
+    assert e.value.status == 1
