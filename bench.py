@@ -486,6 +486,41 @@ def main():
             out_shape=list(oshape), us=round(us, 2), GBps=round(moved / 1e9 / (us * 1e-6), 1),
             frac_hbm_peak=round(moved / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4), note="cache-resident buffers")
         del u0, u1
+        # the spatially tiled C2D template (Section 5.1) with the tiles materialised: a 58x58x64 input unfolded
+        # into 16x16-pixel tiles (14 + 2 along H and W), convolved tile by tile without padding, against the direct
+        # kernel, which keeps the same overlapped tile in LDS and never writes it out
+        N_, C_, H_, K_, ht = 16, 64, 58, 64, 14
+        TH, BH = (H_ - 2) // ht, ht + 2
+        xs = torch.randint(-200, 200, (N_ * H_ * H_ * C_,), dtype=torch.int16, device=dev)
+        wsd2 = torch.randint(-200, 200, (K_ * C_ * 9,), dtype=torch.int16, device=dev)
+        s1 = alt.unfold_shape((N_, H_, H_, C_), 1, BH, ht)
+        s2 = alt.unfold_shape(s1, 3, BH, ht)
+        t1 = torch.empty(int(np.prod(s1)), dtype=torch.int16, device=dev)
+        t2 = torch.empty(int(np.prod(s2)), dtype=torch.int16, device=dev)
+        t3 = torch.empty_like(t2)
+        ident, swap = alt.layout_from_prims(s2, []), alt.layout_from_prims(s2, [alt.reorder([0, 1, 3, 2, 4, 5])])
+        dt = alt.conv_desc(N_ * TH * TH, C_, BH, BH, K_, 3, 3, stride=1, pad=0, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                           x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+        yt = torch.empty(N_ * TH * TH * ht * ht * K_, dtype=torch.int16, device=dev)
+
+        def tiled(st):
+            h.unfold(alt.BF16, (N_, H_, H_, C_), 1, BH, ht, xs, t1, stream=st)
+            h.unfold(alt.BF16, s1, 3, BH, ht, t1, t2, stream=st)
+            h.layout_transform(alt.BF16, s2, ident, t2, swap, t3, stream=st)
+            h.conv2d(dt, t3, wsd2, yt, stream=st)
+        gr = capture(tiled, 5)
+        us_all = graph_timed(gr, 5)
+        del gr
+        gr = capture(lambda st: h.conv2d(dt, t3, wsd2, yt, stream=st), 20)
+        us_conv = graph_timed(gr, 20)
+        del gr
+        direct = next(l for l in layers if l["L"]["name"] == "c64_56_3x3")
+        extra["conv_on_unfolded_tiles_c64_56x56_b16"] = dict(
+            tiles=[N_ * TH * TH, BH, BH, C_], unfold_reorder_and_conv_us=round(us_all, 2), tile_conv_alone_us=round(us_conv, 2),
+            direct_kernel_us=round(direct["us"], 2),
+            note="the tile convolution runs on the implicit-GEMM kernels (default variant); the direct kernel's "
+                 "figure is the same layer with same-size padding")
+        del xs, wsd2, t1, t2, t3, yt
 
     if want("gemm"):
         # ------------------------------------------------------------------ gemm ----

@@ -529,3 +529,40 @@ def test_conv_transpose_tolerance_and_errors(h):
     with pytest.raises(alt.AltError) as e:
         h.conv2d_transpose(bad, a, a, a, workspace=a, ws_bytes=a.numel() * 4)
     assert e.value.status == 4
+
+
+def test_conv_on_the_unfolded_layout(h):
+    """The spatially tiled C2D template of Section 5.1 on the device: the input unfolded along H
+    and W into overlapped tiles of (h_t + R - 1) x (w_t + S - 1) pixels (Section 4.1.2; two
+    alt_unfold calls and one reorder), convolved tile by tile with no padding (the tiles are
+    the batch), gives the output directly in the layout N (H/h_t) (W/w_t) h_t w_t O.  Bit for
+    bit the oracle's un-tiled convolution, for NHWC tiles and bf16 integers."""
+    N, C, H, W, K, R, S, ht, wt = 2, 32, 30, 23, 48, 3, 4, 7, 5
+    OH, OW = H - R + 1, W - S + 1
+    assert OH % ht == 0 and OW % wt == 0
+    TH, TW, BH, BW = OH // ht, OW // wt, ht + R - 1, wt + S - 1
+    x = small_ints_f32(801, (N, C, H, W), -3, 3)
+    w = small_ints_f32(802, (K, C, R, S), -3, 3)
+    ref = oracle.conv2d(x, w, stride=1, pad=0)                                   # (N, K, OH, OW)
+    xb = dev(to_layout(f32_to_bf16_bits(x), "NCHW", "NHWC"))                      # (N, H, W, C)
+    s1 = alt.unfold_shape((N, H, W, C), 1, BH, ht)
+    assert s1 == (N, TH, BH, W, C)
+    u1 = torch.empty(int(np.prod(s1)), dtype=torch.int16, device="cuda")
+    h.unfold(alt.BF16, (N, H, W, C), 1, BH, ht, xb, u1)
+    s2 = alt.unfold_shape(s1, 3, BW, wt)
+    assert s2 == (N, TH, BH, TW, BW, C)
+    u2 = torch.empty(int(np.prod(s2)), dtype=torch.int16, device="cuda")
+    h.unfold(alt.BF16, s1, 3, BW, wt, u1, u2)
+    tiles = torch.empty_like(u2)                                                  # (N, TH, TW, BH, BW, C)
+    h.layout_transform(alt.BF16, s2, alt.layout_from_prims(s2, []), u2,
+                       alt.layout_from_prims(s2, [alt.reorder([0, 1, 3, 2, 4, 5])]), tiles)
+    d = alt.conv_desc(N * TH * TW, C, BH, BW, K, R, S, stride=1, pad=0, in_dtype=alt.BF16,
+                      x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+    assert h.conv2d_output_shape(d) == (N * TH * TW, K, ht, wt)
+    n_out = N * TH * TW * ht * wt * K
+    whole, yd = canary_dev(n_out, np.float32)
+    h.conv2d(d, tiles, dev(to_layout(f32_to_bf16_bits(w), "OIHW", "OHWI")), yd)
+    assert canary_ok(whole, n_out)
+    got = host(yd, np.float32).reshape(N, TH, TW, ht, wt, K)
+    want = ref.reshape(N, K, TH, ht, TW, wt).transpose(0, 2, 4, 3, 5, 1)
+    assert np.array_equal(got, want)
