@@ -140,8 +140,11 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_vec8_kernel(const DwParams 
 // owns eight channels of TW consecutive output pixels of one row: the nine weight vectors are
 // loaded once, and neighbouring outputs share the input columns of their windows, so a thread
 // makes 3 * ((TW - 1) * STRIDE + 3) + 9 loads for TW outputs instead of 18 per output.
+// (At stride 1 the register count is held to four waves per SIMD: the benchmark layers are 3.4
+// waves per SIMD of work, so every thread is then resident at once; at stride 2 the nine input
+// columns of a row do not fit that budget without spilling.)
 template <int STRIDE, int TW>
-__global__ __launch_bounds__(kDwThreads) void dwconv_vec8_3x3_kernel(const DwParams p)
+__global__ __launch_bounds__(kDwThreads, STRIDE == 1 ? 4 : 3) void dwconv_vec8_3x3_kernel(const DwParams p)
 {
     typedef uint32_t w4_t __attribute__((ext_vector_type(4)));
     typedef float f4_t __attribute__((ext_vector_type(4)));
@@ -150,20 +153,25 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_vec8_3x3_kernel(const DwPar
     const int64_t total = (int64_t)p.N * p.OH * OWB * C8;
     const int64_t sxh = p.xh.si, sxw = p.xw.si, syh = p.yh.si, syw = p.yw.si;
     for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
-        int64_t r = e;
-        const int c = (int)(r % C8) * 8; r /= C8;
-        const int ow0 = (int)(r % OWB) * TW; r /= OWB;
-        const int oh = (int)(r % p.OH);
-        const int n = (int)(r / p.OH);
+        int c, ow0, oh, n;
+        if (total <= 0x7fffffff) {                  // 32-bit divisions cost a fraction of 64-bit ones
+            uint32_t r = (uint32_t)e;
+            c = (int)(r % (uint32_t)C8) * 8; r /= (uint32_t)C8;
+            ow0 = (int)(r % (uint32_t)OWB) * TW; r /= (uint32_t)OWB;
+            oh = (int)(r % (uint32_t)p.OH);
+            n = (int)(r / (uint32_t)p.OH);
+        } else {
+            int64_t r = e;
+            c = (int)(r % C8) * 8; r /= C8;
+            ow0 = (int)(r % OWB) * TW; r /= OWB;
+            oh = (int)(r % p.OH);
+            n = (int)(r / p.OH);
+        }
         const uint16_t *xb = (const uint16_t *)p.x + dim2_off(p.xn, n) + dim2_off(p.xc, c);
         const uint16_t *wb = (const uint16_t *)p.w + dim2_off(p.wo, c);
-        f4_t wlo[9], whi[9];
+        w4_t wv[9];                                 // kept packed: unpacked where used, half the registers
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const w4_t wv = *(const w4_t *)(wb + dim2_off(p.wr, t / 3) + dim2_off(p.ws, t % 3));
-            wlo[t] = __builtin_bit_cast(f4_t, wv << 16);
-            whi[t] = __builtin_bit_cast(f4_t, wv & 0xffff0000u);
-        }
+        for (int t = 0; t < 9; ++t) wv[t] = *(const w4_t *)(wb + dim2_off(p.wr, t / 3) + dim2_off(p.ws, t % 3));
         f4_t lo[TW], hi[TW];
 #pragma unroll
         for (int j = 0; j < TW; ++j) { lo[j] = (f4_t){0.f, 0.f, 0.f, 0.f}; hi[j] = (f4_t){0.f, 0.f, 0.f, 0.f}; }
@@ -183,12 +191,15 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_vec8_3x3_kernel(const DwPar
                 xhi[q] = __builtin_bit_cast(f4_t, xv & 0xffff0000u);
             }
 #pragma unroll
-            for (int j = 0; j < TW; ++j)
+            for (int fs = 0; fs < 3; ++fs) {
+                const f4_t wl = __builtin_bit_cast(f4_t, wv[fr * 3 + fs] << 16);
+                const f4_t wh = __builtin_bit_cast(f4_t, wv[fr * 3 + fs] & 0xffff0000u);
 #pragma unroll
-                for (int fs = 0; fs < 3; ++fs) {
-                    lo[j] += xlo[j * STRIDE + fs] * wlo[fr * 3 + fs];
-                    hi[j] += xhi[j * STRIDE + fs] * whi[fr * 3 + fs];
+                for (int j = 0; j < TW; ++j) {
+                    lo[j] += xlo[j * STRIDE + fs] * wl;
+                    hi[j] += xhi[j * STRIDE + fs] * wh;
                 }
+            }
         }
         f4_t blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
         if (p.epilogue & ALT_EPI_BIAS) {

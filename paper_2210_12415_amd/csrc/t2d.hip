@@ -147,13 +147,12 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_flip_kernel(FlipParams p)
 {
     using E = typename Elem<ELSZ>::type;
     const int64_t n = p.ld.numel;
-    const int64_t K = p.ld.shape[0], C = p.ld.shape[1], R = p.ld.shape[2], S = p.ld.shape[3];
+    const int64_t K = p.ld.shape[0], R = p.ld.shape[2], S = p.ld.shape[3];
     for (int64_t e = blockIdx.x * (int64_t)kT2dThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kT2dThreads) {
         int64_t idx[ALT_MAX_RANK];
         int64_t r = e;
         for (int d = 3; d >= 0; --d) { idx[d] = r % p.ld.shape[d]; r /= p.ld.shape[d]; }
         const int64_t src = ((idx[1] * K + idx[0]) * R + (R - 1 - idx[2])) * S + (S - 1 - idx[3]);
-        (void)C;
         ((E *)p.dst)[eval_offset(p.ld, idx)] = ((const E *)p.src)[src];
     }
 }
