@@ -394,6 +394,36 @@ def conv2d_transpose(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, re
     return f32_to_bf16_bits(y) if out_bf16 else y
 
 
+def conv3d(x, w, stride=1, pad=0):
+    """3-D convolution (the C3D of Section 6.1's operator list) from its definition:
+
+        y[n, k, od, oh, ow] = sum_{c,t,r,s} x[n, c, od*stride - pad + t, oh*stride - pad + r, ow*stride - pad + s] * w[k, c, t, r, s]
+
+    with zeros outside the input.  x: (N,C,D,H,W), w: (K,C,T,R,S), float32 or uint16 bf16
+    bits; sums in float64, one rounding to float32.  Pure numpy: one channel contraction
+    per filter tap over a strided view of the zero-padded input."""
+    x = np.asarray(x)
+    w = np.asarray(w)
+    xf = bf16_bits_to_f64(x) if x.dtype == np.uint16 else x.astype(np.float64)
+    wf = bf16_bits_to_f64(w) if w.dtype == np.uint16 else w.astype(np.float64)
+    N, C, D, H, W = xf.shape
+    K, C2, T, R, S = wf.shape
+    if C2 != C:
+        raise ValueError("conv3d: w is (K, C, T, R, S)")
+    OD, OH, OW = (D + 2 * pad - T) // stride + 1, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if min(OD, OH, OW) < 1:
+        raise ValueError("conv3d: empty output")
+    xp = np.pad(xf, ((0, 0), (0, 0), (pad, pad), (pad, pad), (pad, pad)))
+    y = np.zeros((N, K, OD, OH, OW), dtype=np.float64)
+    for t in range(T):
+        for r in range(R):
+            for s_ in range(S):
+                win = xp[:, :, t:t + (OD - 1) * stride + 1:stride, r:r + (OH - 1) * stride + 1:stride,
+                         s_:s_ + (OW - 1) * stride + 1:stride]
+                y += np.einsum("ncdhw,kc->nkdhw", win, wf[:, :, t, r, s_])
+    return y.astype(np.float32)
+
+
 def conv_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
     d = _Conv(*x_shape, w_shape[0], w_shape[2], w_shape[3], stride, stride, pad, pad, dil, dil,
               0, 0, 0, 0)

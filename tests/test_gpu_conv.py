@@ -566,3 +566,39 @@ def test_conv_on_the_unfolded_layout(h):
     got = host(yd, np.float32).reshape(N, TH, TW, ht, wt, K)
     want = ref.reshape(N, K, TH, ht, TW, wt).transpose(0, 2, 4, 3, 5, 1)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+def test_conv3d_by_unfolding_the_depth(h, stride, pad):
+    """The C3D of Section 6.1 out of the layout primitives and the C2D kernels: unfolding the
+    depth (tiles of T slices every `stride`, Section 4.1.2) and moving the tile index next to
+    the channels turns the T depth taps into T*C input channels of a 2-D convolution whose
+    batch is (n, od); the result is the NDHWC output.  Depth is zero-padded up front (a
+    copy into a larger buffer); bf16 integers, bit for bit the oracle's 3-D definition."""
+    N, C, D, H, W, K, T, R, S = 2, 16, 7, 9, 8, 32, 3, 3, 3
+    x = small_ints_f32(901, (N, C, D, H, W), -3, 3)
+    w = small_ints_f32(902, (K, C, T, R, S), -3, 3)
+    ref = oracle.conv3d(x, w, stride=stride, pad=pad)                               # (N, K, OD, OH, OW)
+    OD = ref.shape[2]
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad), (0, 0), (0, 0)))                      # depth padding only
+    Dp = D + 2 * pad
+    x_ndhwc = dev(f32_to_bf16_bits(np.ascontiguousarray(xp.transpose(0, 2, 3, 4, 1))).reshape(-1))
+    s1 = alt.unfold_shape((N, Dp, H, W, C), 1, T, stride)
+    assert s1 == (N, OD, T, H, W, C)
+    u = torch.empty(int(np.prod(s1)), dtype=torch.int16, device="cuda")
+    h.unfold(alt.BF16, (N, Dp, H, W, C), 1, T, stride, x_ndhwc, u)
+    xc = torch.empty_like(u)                                                         # (N, OD, H, W, T, C)
+    h.layout_transform(alt.BF16, s1, alt.layout_from_prims(s1, []), u,
+                       alt.layout_from_prims(s1, [alt.reorder([0, 1, 3, 4, 2, 5])]), xc)
+    # the filter is a constant: (K, C, T, R, S) -> OHWI over the T*C channels, tap index t slowest
+    w2 = np.ascontiguousarray(w.transpose(0, 3, 4, 2, 1)).reshape(K, R, S, T * C)
+    d = alt.conv_desc(N * OD, T * C, H, W, K, R, S, stride=stride, pad=pad, in_dtype=alt.BF16,
+                      x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+    oshape = h.conv2d_output_shape(d)
+    assert oshape == (N * OD, K, ref.shape[3], ref.shape[4])
+    n_out = int(np.prod(oshape))
+    whole, yd = canary_dev(n_out, np.float32)
+    h.conv2d(d, xc, dev(f32_to_bf16_bits(w2).reshape(-1)), yd)
+    assert canary_ok(whole, n_out)
+    got = host(yd, np.float32).reshape(N, OD, ref.shape[3], ref.shape[4], K).transpose(0, 4, 1, 2, 3)
+    assert np.array_equal(got, ref)

@@ -409,3 +409,19 @@ def test_conv_transpose_stride1_is_conv_with_flipped_filter(oracle):
     exp = np.zeros((9, 9), dtype=np.float32)
     exp[2:5, 4:7] = 2.0 * k[0, 0]
     assert np.array_equal(y[0, 0], exp)
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 0), (1, 1), (2, 1), (2, 0)])
+def test_conv3d_vs_library_routine_and_2d_special_case(oracle, stride, pad):
+    """Against torch's conv3d in float64; with a depth of one tap and one slice it is the C2D."""
+    x = normal_f32(101, (2, 3, 6, 7, 5))
+    w = normal_f32(102, (4, 3, 3, 2, 3))
+    got = oracle.conv3d(x, w, stride=stride, pad=pad)
+    ref = torch.nn.functional.conv3d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), stride=stride, padding=pad).numpy()
+    assert got.shape == ref.shape
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+    xi = small_ints_f32(103, (2, 3, 1, 7, 5), -4, 4)
+    wi = small_ints_f32(104, (4, 3, 1, 3, 3), -4, 4)
+    if pad == 0:
+        assert np.array_equal(oracle.conv3d(xi, wi, stride=stride, pad=0)[:, :, 0],
+                              oracle.conv2d(xi[:, :, 0], wi[:, :, 0], stride=stride, pad=0))
