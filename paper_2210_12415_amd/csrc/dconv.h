@@ -13,12 +13,15 @@
 // the weights stream through a ring of LDS stages (direct-to-LDS loads as in
 // igemm_dma.h).
 //
-// Covers: bf16, stride 1, dilation 1, "same" padding (2*pad = R-1, S-1; so 1x1
-// pad 0 too), activations NHWC, weights OHWI, output NHWC (fp32 or bf16), all
-// dense, 64, 128, 256 or 512 channels per split, output channels a multiple of 4.
-// The linear pixel index of the input is then the linear index of the output
-// pixel plus a per-tap constant, across image boundaries too, which is what
-// makes the patch one contiguous range of input pixels.
+// Covers: bf16, stride 1 or 2 (image sizes a multiple of the stride), dilation 1,
+// "same" padding (2*pad = R-1, S-1; so 1x1 pad 0 too), activations NHWC,
+// weights OHWI, output NHWC (fp32 or bf16), all dense, 64, 128, 256 or 512
+// channels per split, output channels a multiple of 4.  The input pixel under
+// an output pixel then grows monotonically with the output's linear index,
+// across rows and images too (at stride 1 the two indices are equal), so the
+// pixels a tile touches are one contiguous range of the input: the patch.  At
+// stride 2 that range is four times the tile plus a row, which leaves room
+// for 64- and 128-pixel tiles only.
 //
 // K groups: the waves of a workgroup may form several groups that split the
 // slice's channels between them, each with a weight ring of its own; their
@@ -67,7 +70,7 @@ struct DconvParams {
     int32_t M, Nc, C, Cs;         // Cs = C / splitk channels per slice
     int32_t H, W, R, S, pad_h, pad_w;
     int32_t tiles_m, tiles_n, splitk, flags;             // flags: ALT_EPI_BIAS | ALT_EPI_RELU | 4 (bf16 output)
-    Div32 d_hw, d_w, d_tm, d_tn;  // divisions by H*W, W, tiles_m, tiles_n
+    Div32 d_hw, d_w, d_tm, d_tn;  // divisions by OH*OW, OW, tiles_m, tiles_n
     int32_t log2_cpp;             // log2(Cs / 8): 16-byte chunks per patch pixel
     Div32 d_slots;                // division by Cs / 8 + 1, the 16-byte slots of a patch pixel in LDS
     int32_t ncc;                  // K steps per tap: (Cs / K groups) / channels per K step
@@ -77,6 +80,9 @@ struct DconvParams {
     // streaming kernel (dstream.h) only: batch entries and the byte strides between them
     int32_t batch, pad1_;
     int64_t x_bstride, w_bstride, y_bstride;
+    // direct kernel only: output image size and stride (H, W above are the input's; M counts
+    // output pixels), and the number of input pixels
+    int32_t OH, OW, stride, in_px;
 };
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -451,20 +457,29 @@ void dconv_kernel(const DconvParams p)
     // operand reads of an MFMA row tile do not collide) while a pixel's address stays
     // affine in its index: a filter tap is then one add per row tile and the chunk inside
     // the pixel an instruction offset, with no per-read address arithmetic.
+    // Output pixel m of image img at (oh, ow) sits over input pixel img*H*W + oh*stride*W + ow*stride
+    // (its tap (pad_h, pad_w)); the tile's patch runs from the first row's to the last row's.
     const int halo = p.pad_h * p.W + p.pad_w;
-    const int np = BM + 2 * halo;
+    const int ohw = p.OH * p.OW;
+    auto anchor = [&](int m) {
+        const int img = (int)div32((uint32_t)m, p.d_hw), rem = m - img * ohw;
+        const int oh = (int)div32((uint32_t)rem, p.d_w), ow = rem - oh * p.OW;
+        return img * (p.H * p.W) + (oh * p.W + ow) * p.stride;
+    };
+    const int a0 = anchor(m0);
+    const int np = anchor(min(m0 + BM, p.M) - 1) - a0 + 1 + 2 * halo;
     const int spp = (1 << p.log2_cpp) + 1;                 // 16-byte slots per patch pixel
     const int pitch_b = spp * 16;
     const int nwl = (np * spp + 63) >> 6;                  // wave-loads (the region is padded to whole ones)
     const int pz = (int)div32((uint32_t)((nwl << 6) + spp - 1), p.d_slots);   // the all-zero pixel row behind the patch
     {
-        const int g0 = m0 - halo;
+        const int g0 = a0 - halo;
         const uint32_t lane_off = (uint32_t)(split * p.Cs) * 2u;
         auto load_one = [&](int j) {
             const int slot = j * 64 + lane;
             const int px = (int)div32((uint32_t)slot, p.d_slots), c = slot - px * spp;
             const int g = g0 + px;
-            const bool ok = c < spp - 1 && px < np && (unsigned)g < (unsigned)p.M;
+            const bool ok = c < spp - 1 && px < np && (unsigned)g < (unsigned)p.in_px;
             const uint32_t voff = ok ? (uint32_t)(g * p.C) * 2u + lane_off + (uint32_t)c * 16u : kOutOfRange;
             dma_load16(x_rsrc, voff, patch0 + j * 1024);
         };
@@ -512,20 +527,21 @@ void dconv_kernel(const DconvParams p)
     for (int s = 0; s < NS - 1; ++s) issue_b();
 
     // ---- per-lane rows of the MFMA tiles ---------------------------------------------------------
-    int32_t row_px[TM], row_oh[TM], row_ow[TM];
-    const int hw = p.H * p.W;
+    int32_t row_px[TM], row_oh[TM], row_ow[TM];           // patch pixel under tap (pad_h, pad_w); its input row and column
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int r = wm * WTM + i * 32 + (lane & 31);
         const int m = m0 + r;
-        row_px[i] = r + halo;                              // patch pixel under the centre tap
         if (m < p.M) {
-            const int img = (int)div32((uint32_t)m, p.d_hw), rem = m - img * hw;
-            row_oh[i] = (int)div32((uint32_t)rem, p.d_w);
-            row_ow[i] = rem - row_oh[i] * p.W;
+            const int img = (int)div32((uint32_t)m, p.d_hw), rem = m - img * ohw;
+            const int oh = (int)div32((uint32_t)rem, p.d_w), ow = rem - oh * p.OW;
+            row_oh[i] = oh * p.stride;
+            row_ow[i] = ow * p.stride;
+            row_px[i] = img * (p.H * p.W) + row_oh[i] * p.W + row_ow[i] - a0 + halo;
         } else {
             row_oh[i] = -(1 << 20);
             row_ow[i] = -(1 << 20);
+            row_px[i] = 0;
         }
     }
     // weight operand addresses inside stage 0 (LDS byte addresses), per n tile and k chunk
@@ -726,10 +742,14 @@ void dconv_kernel(const DconvParams p)
 
 // LDS bytes of one workgroup: the K groups' weight rings, the patch rounded up to
 // whole wave-loads, the all-zero row.
-inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, int W, int pad_h, int pad_w)
+inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, int W, int pad_h, int pad_w,
+                              int stride)
 {
     const size_t spp = (size_t)Cs / 8 + 1;                 // 16-byte slots per patch pixel (one unused)
-    const size_t np = (size_t)BM + 2 * ((size_t)pad_h * W + pad_w);
+    // BM consecutive output pixels sit over at most stride^2 * BM input pixels, plus one step
+    // from an output row (or image) to the next
+    const size_t span = stride == 1 ? (size_t)BM : (size_t)stride * stride * BM + (size_t)stride * W;
+    const size_t np = span + 2 * ((size_t)pad_h * W + pad_w);
     const size_t nwl = (np * spp + 63) / 64;
     const size_t pz = (nwl * 64 + spp - 1) / spp;          // the zero row sits behind the whole wave-loads
     const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + (pz + 1) * spp * 16;

@@ -151,15 +151,17 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     const IgemmParams &p = pb.p;
     if (pb.dtype != ALT_BF16) return no("direct kernel is bf16 only");
     if (p.batch != 1) return no("direct kernel takes no batch");
-    if (p.stride_h != 1 || p.stride_w != 1 || p.dil_h != 1 || p.dil_w != 1) return no("direct kernel needs stride 1, dilation 1");
+    if (p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2) || p.dil_h != 1 || p.dil_w != 1)
+        return no("direct kernel needs stride 1 or 2, dilation 1");
     if (2 * p.pad_h != p.R - 1 || 2 * p.pad_w != p.S - 1) return no("direct kernel needs same-size padding");
-    if (p.OH != p.H || p.OW != p.W) return no("direct kernel needs output size = input size");
-    const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, R = p.R, S = p.S, N = p.M / (H * W);
+    const int st_ = p.stride_h;
+    if (p.H % st_ || p.W % st_ || p.OH != p.H / st_ || p.OW != p.W / st_) return no("direct kernel needs output size = input size / stride");
+    const int64_t C = p.C, H = p.H, W = p.W, OH = p.OH, OW = p.OW, K = p.Nc, R = p.R, S = p.S, N = p.M / (OH * OW);
     if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
         return no("activations are not dense NHWC");
     if (!(dense(p.wi, C, 1) && dense(p.ws, S, C) && dense(p.wr, R, S * C) && dense(p.wo, K, R * S * C)))
         return no("weights are not dense OHWI");
-    if (!(dense(p.yk, K, 1) && dense(p.yw, W, K) && dense(p.yh, H, W * K) && dense(p.yn, N, H * W * K)))
+    if (!(dense(p.yk, K, 1) && dense(p.yw, OW, K) && dense(p.yh, OH, OW * K) && dense(p.yn, N, OH * OW * K)))
         return no("output is not dense NHWC");
     if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16) return no("operands are not 16-byte aligned");
     if (splitk < 1 || C % splitk) return no("split factor does not divide the channels");
@@ -177,7 +179,7 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
     if (K % 4 || (uintptr_t)p.y % 16 || ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 16))
         return no("direct kernel stores four output channels at a time");
-    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs, p.W, p.pad_h, p.pad_w);
+    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs, p.W, p.pad_h, p.pad_w, st_);
     if (lds > 160 * 1024) return no("patch does not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
@@ -192,8 +194,11 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     d.H = p.H; d.W = p.W; d.R = p.R; d.S = p.S; d.pad_h = p.pad_h; d.pad_w = p.pad_w;
     d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = splitk;
     d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
-    d.d_hw = make_div32((uint32_t)(p.H * p.W));
-    d.d_w = make_div32((uint32_t)p.W);
+    d.OH = p.OH; d.OW = p.OW; d.stride = st_;
+    if (N * H * W > 0x7fffffff) return no("input too large for 32-bit pixel indices");
+    d.in_px = (int32_t)(N * H * W);
+    d.d_hw = make_div32((uint32_t)(p.OH * p.OW));
+    d.d_w = make_div32((uint32_t)p.OW);
     d.d_tm = make_div32((uint32_t)tiles_m);
     d.d_tn = make_div32((uint32_t)tiles_n);
     int l2 = 0;

@@ -98,33 +98,37 @@ DIRECT_CASES = [
     dict(N=1, C=64, H=11, W=12, K=32, R=5, S=5, pad=2),      # two-pixel halo, K below one tile
     dict(N=5, C=512, H=3, W=3, K=64, R=3, S=3, pad=1),       # images smaller than the halo of a tile
     dict(N=1, C=128, H=8, W=9, K=72, R=5, S=5, pad=2),       # run-time tap walk with K groups
+    dict(N=3, C=64, H=12, W=10, K=96, R=3, S=3, pad=1, stride=2),    # stride 2: tiles over rows and images of half size
+    dict(N=2, C=128, H=14, W=18, K=64, R=1, S=1, pad=0, stride=2),   # the strided 1x1 of a projection shortcut
+    dict(N=2, C=256, H=6, W=8, K=64, R=5, S=5, pad=2, stride=2),     # run-time tap walk at stride 2
 ]
 
 
-@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"]))
+@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1)))
 def test_direct_kernel_exact_integers_every_variant(h, case):
-    """The patch-resident direct kernels (NHWC / OHWI / NHWC, same-size padding):
+    """The patch-resident direct kernels (NHWC / OHWI / NHWC, same-size padding, stride 1 or 2):
     every tile shape, pipeline depth and channel-slice count, bit for bit; fp32
     and bf16 output, bias and ReLU through the fused split-K tail as well."""
     c = case
     x = small_ints_f32(61, (c["N"], c["C"], c["H"], c["W"]), -3, 3)
     w = small_ints_f32(62, (c["K"], c["C"], c["R"], c["S"]), -3, 3)
     b = small_ints_f32(63, (c["K"],), -50, 50)
-    cfg = dict(stride=1, pad=c["pad"])
-    ref = oracle.conv2d(x, w, stride=1, pad=c["pad"])
-    ref_br = oracle.conv2d(x, w, stride=1, pad=c["pad"], bias=b, relu=True)
+    st = c.get("stride", 1)
+    cfg = dict(stride=st, pad=c["pad"])
+    ref = oracle.conv2d(x, w, stride=st, pad=c["pad"])
+    ref_br = oracle.conv2d(x, w, stride=st, pad=c["pad"], bias=b, relu=True)
     xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
-    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=1, pad=c["pad"],
+    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=st, pad=c["pad"],
                        in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
     variants = [(v, n) for v, n in applicable_variants(h, d0) if "direct" in n]
-    assert len(variants) >= 20, "direct kernels should cover this case"
+    assert len(variants) >= (20 if st == 1 else 6), "direct kernels should cover this case"
     assert any(not n.endswith("_k1") for _, n in variants) or c["C"] == 64
     for v, name in variants:
         got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, variant=v)
         assert np.array_equal(got, ref), name
     # kernels whose waves form several K groups (name: w<rows>x<cols>x<groups>)
     grouped = [vn for vn in variants if re.search(r"_w\d+x\d+x\d+_", vn[1])]
-    assert grouped or c["C"] == 64
+    assert grouped or c["C"] == 64 or st == 2            # (at stride 2 the wide patch leaves room for few of them)
     # the epilogue variants on a few kernels, split and unsplit, with and without K groups
     picks = ([variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
              + grouped[:2] + [vn for vn in grouped if not vn[1].endswith("_k1")][:2])
