@@ -200,6 +200,18 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
                         const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
 
+/* alt_conv2d with a sum fused into its epilogue (the fused loop nest of Fig. 6; a residual
+ * join whose other operand is already in the convolution's output layout):
+ *   y = act(conv(x, w) + bias + addend),
+ * the sum in fp32 before the one rounding of the output.  `addend` (device, 16-byte aligned)
+ * has y's layout and element type and may not alias y.  Built into the tile kernels (dense
+ * NHWC activations and output, OHWI weights, bf16 inputs: the direct and streaming kernels);
+ * descriptors only the implicit-GEMM kernels cover, grouped and depth-wise ones fail with
+ * ALT_UNSUPPORTED (run alt_conv2d and alt_eltwise_add instead).  Everything else as alt_conv2d. */
+alt_status_t alt_conv2d_add(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
+                            const float *bias, const void *addend, void *y, void *workspace, size_t ws_bytes,
+                            void *stream);
+
 /* One alt_conv2d call's arguments, for alt_conv2d_multi. */
 typedef struct {
     const alt_conv_desc_t *d;

@@ -144,7 +144,7 @@ def exported_symbols():
     return ["alt_create", "alt_destroy", "alt_last_error", "alt_status_string", "alt_version",
             "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
-            "alt_conv2d", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
+            "alt_conv2d", "alt_conv2d_add", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
             "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
@@ -313,6 +313,10 @@ class Handle:
     def conv2d(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
         _ck(lib().alt_conv2d(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
                              _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv2d_add(self, d, x, w, addend, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_conv2d_add(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(addend), _ptr(y),
+                                 _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
 
     def conv2d_prepared(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
         """The same call as conv2d with its arguments marshalled once: returns a

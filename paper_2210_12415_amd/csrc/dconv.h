@@ -83,6 +83,7 @@ struct DconvParams {
     // direct kernel only: output image size and stride (H, W above are the input's; M counts
     // output pixels), and the number of input pixels
     int32_t OH, OW, stride, in_px;
+    const void *addend;           // added before the activation: same layout and element type as y, or null
 };
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -287,12 +288,36 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
             bv[v * 4 + 0] = b4.x; bv[v * 4 + 1] = b4.y; bv[v * 4 + 2] = b4.z; bv[v * 4 + 3] = b4.w;
         }
     }
+    const __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc((void *)p.addend, 0, (int)p.y_bytes, 0x00020000);
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const bool ok = offs[it] != kOutOfRange / 4u;
+        float ad[CW];                                      // the fused sum's other operand (zeros without one)
+#pragma unroll
+        for (int q = 0; q < CW; ++q) ad[q] = 0.f;
+        if (!p.addend) {
+        } else if (CW == 8 || out_bf16) {
+            // bf16: element 2j is the low half of dword j, element 2j+1 the high half (whole-vector
+            // shifts and masks; an out-of-range offset reads zeros)
+            u32x4_t av = {0u, 0u, 0u, 0u};
+            if constexpr (CW == 8) av = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+            else {
+                typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+                const u32x2_t a2 = __builtin_amdgcn_raw_buffer_load_b64(ar, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+                av = __builtin_shufflevector(a2, a2, 0, 1, 0, 1);
+            }
+            const f32x4_t lo = __builtin_bit_cast(f32x4_t, av << 16), hi = __builtin_bit_cast(f32x4_t, av & 0xffff0000u);
+#pragma unroll
+            for (int q = 0; q < CW / 2; ++q) { ad[2 * q] = lo[q]; ad[2 * q + 1] = hi[q]; }
+        } else {
+            const f32x4_t a4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0));
+            const f32x4_t z = a4 + (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ad[q] = z[q];
+        }
         float o[CW];
 #pragma unroll
-        for (int q = 0; q < CW; ++q) o[q] = fmaxf(vs[it][q / 4][q % 4] + bv[q], relu_floor);
+        for (int q = 0; q < CW; ++q) o[q] = fmaxf(vs[it][q / 4][q % 4] + bv[q] + ad[q], relu_floor);
         if (CW == 8 || out_bf16) {                         // (eight columns per lane are only used for bf16 output)
             uint32_t w[CW / 2];
 #pragma unroll

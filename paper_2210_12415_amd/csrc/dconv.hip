@@ -102,6 +102,7 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     if (p.batch > 1 && ((p.x_bstride * 2) % 16 || (p.w_bstride * 2) % 16 || (p.y_bstride * osz) % 16))
         return no("batch entries are not 16-byte aligned");
     if (p.batch > 65535) return no("too many batch entries for one launch");
+    if (p.addend && p.batch > 1) return no("the fused sum is not built for batched problems");
     if (splitk < 1 || (splitk > 1 && p.batch > 1)) return no("split-K is not built for batched problems");
     if (C % ((int64_t)k.BK * splitk * k.kw)) return no("K does not split into whole steps per slice and K group");
     if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0)
@@ -116,7 +117,7 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     if (!out) return true;
     DconvParams d;
     std::memset(&d, 0, sizeof d);
-    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
+    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y; d.addend = p.addend;
     d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
     d.partial_bytes = (uint32_t)((int64_t)p.M * K * 4);
     d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = (int32_t)(C / splitk);
@@ -187,7 +188,7 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if (!out) return true;
     DconvParams d;
     std::memset(&d, 0, sizeof d);
-    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
+    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y; d.addend = p.addend;
     d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
     d.partial_bytes = (uint32_t)((int64_t)p.M * K * 4);
     d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = (int32_t)Cs;

@@ -55,6 +55,7 @@ struct IgemmParams {
     Dim2 xn, xc, xh, xw;      // activations (N, C, H, W)
     Dim2 wo, wi, wr, ws;      // weights (O, I, R, S)
     Dim2 yn, yk, yh, yw;      // output (N, K, OH, OW)
+    const void *addend;       // tensor added before the activation (same layout and type as y), or null
 };
 
 struct KEntry {               // one K step: what is uniform over the tile

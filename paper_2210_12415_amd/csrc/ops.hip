@@ -101,6 +101,7 @@ bool igemm_applicable(const Problem &pb, const IgemmLaunch &k, int splitk, Igemm
     auto no = [&](const char *m) { if (why) *why = m; return false; };
     const IgemmParams &p0 = pb.p;
     if (k.dtype != pb.dtype) return no("element type");
+    if (p0.addend && !k.launch_direct) return no("the fused sum is built into the tile kernels only");
     if (k.launch_direct) {
         if (!dconv_setup(pb, k, splitk, nullptr, nullptr, why)) return false;
         if (out) {
@@ -482,26 +483,45 @@ static int pick_variant(alt_handle_t h, const Problem &pb, int requested, const 
     return igemm_default_variant(pb, ws_limit);
 }
 
-alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
-                        void *y, void *workspace, size_t ws_bytes, void *stream)
+static alt_status_t conv2d_impl(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
+                                const void *addend, void *y, void *workspace, size_t ws_bytes, void *stream, const char *who)
 {
     if (!h) return ALT_INVALID_ARG;
-    if (!d || !x || !w || !y) return fail(h, ALT_INVALID_ARG, "alt_conv2d: null argument");
-    if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv2d: bias flag without bias");
+    if (!d || !x || !w || !y) return fail(h, ALT_INVALID_ARG, "%s: null argument", who);
+    if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "%s: bias flag without bias", who);
     const size_t ws_limit = workspace ? ws_bytes : 0;
-    const unsigned sig = align_sig(x, w, bias, y);
+    const unsigned sig = align_sig(x, w, bias, y) | (addend ? 1u << 17 : 0u) | ((unsigned)((uintptr_t)addend & 15) << 18);
     if (MemoEntry *m = memo_find(h, d, sizeof *d, sig, ws_limit)) {
-        m->pb.p.x = x; m->pb.p.w = w; m->pb.p.bias = bias; m->pb.p.y = y;
+        m->pb.p.x = x; m->pb.p.w = w; m->pb.p.bias = bias; m->pb.p.y = y; m->pb.p.addend = addend;
         return igemm_run(h, m->pb, m->variant, workspace, ws_bytes, (hipStream_t)stream);
     }
     Problem pb;
     alt_status_t s = conv_problem(h, d, x, w, bias, y, &pb);
     if (s != ALT_OK) return s;
+    if (addend) {
+        if (pb.depthwise || pb.groups > 1) return fail(h, ALT_UNSUPPORTED, "%s: no fused sum for grouped convolutions", who);
+        if ((uintptr_t)addend % 16) return fail(h, ALT_INVALID_ARG, "%s: the addend must be 16-byte aligned", who);
+        pb.p.addend = addend;
+    }
     if (pb.depthwise) return depthwise_run(h, pb, d->N, d->C, (hipStream_t)stream);
+    // (a tuned choice for the same problem without the sum is a good one with it, if it applies)
     int v = pick_variant(h, pb, d->variant, d->variant >= 0 ? std::string() : conv_key(h, d), ws_limit);
-    if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_conv2d: no kernel variant applies");
+    if (v < 0) return fail(h, ALT_UNSUPPORTED, "%s: no kernel variant applies", who);
     memo_store(h, d, sizeof *d, sig, ws_limit, pb, v);
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
+                        void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    return conv2d_impl(h, d, x, w, bias, nullptr, y, workspace, ws_bytes, stream, "alt_conv2d");
+}
+
+alt_status_t alt_conv2d_add(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
+                            const void *addend, void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (h && !addend) return fail(h, ALT_INVALID_ARG, "alt_conv2d_add: null addend");
+    return conv2d_impl(h, d, x, w, bias, addend, y, workspace, ws_bytes, stream, "alt_conv2d_add");
 }
 
 alt_status_t alt_conv2d_multi(alt_handle_t h, const alt_conv_call_t *calls, int32_t n)

@@ -606,3 +606,52 @@ def test_conv3d_by_unfolding_the_depth(h, stride, pad):
     assert canary_ok(whole, n_out)
     got = host(yd, np.float32).reshape(N, OD, ref.shape[3], ref.shape[4], K).transpose(0, 4, 1, 2, 3)
     assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("out_dtype", [alt.F32, alt.BF16])
+def test_conv2d_add_fused_sum_exact_integers(h, out_dtype):
+    """alt_conv2d_add: y = relu(conv + bias + addend) in one launch, every tile-kernel variant
+    (direct, streaming, K groups, split-K), ragged tiles; integers, so bit for bit the oracle's
+    convolution followed by its element-wise sum.  Descriptors the tile kernels do not cover fail."""
+    for (N, C, H, W, K, R, cfg) in [(2, 64, 11, 9, 72, 3, dict(stride=1, pad=1)), (2, 128, 10, 7, 64, 1, dict(stride=1, pad=0)),
+                                    (3, 64, 12, 10, 96, 3, dict(stride=2, pad=1))]:
+        x = small_ints_f32(1001, (N, C, H, W), -3, 3)
+        w = small_ints_f32(1002, (K, C, R, R), -3, 3)
+        b = small_ints_f32(1003, (K,), -20, 20)
+        conv = oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], bias=b)
+        a = small_ints_f32(1004, conv.shape, -64, 64)
+        ref = np.maximum(conv + a, np.float32(0))                       # integers: every step exact
+        d0 = alt.conv_desc(N, C, H, W, K, R, R, stride=cfg["stride"], pad=cfg["pad"], in_dtype=alt.BF16, out_dtype=out_dtype,
+                           epilogue=alt.EPI_BIAS | alt.EPI_RELU, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+        oshape = h.conv2d_output_shape(d0)
+        n_out = int(np.prod(oshape))
+        ydt = np.float32 if out_dtype == alt.F32 else np.uint16
+        a_l = to_layout(a if out_dtype == alt.F32 else f32_to_bf16_bits(a), "NCHW", "NHWC")
+        xd, wd = dev(to_layout(f32_to_bf16_bits(x), "NCHW", "NHWC")), dev(to_layout(f32_to_bf16_bits(w), "OIHW", "OHWI"))
+        ad, bd = dev(a_l), dev(b)
+        ws = torch.empty(36 * n_out, dtype=torch.float32, device="cuda")
+        variants = [(v, n) for v, n in applicable_variants(h, d0) if "direct" in n or "stream" in n]
+        assert len(variants) >= 6
+        for v, name in variants:
+            import copy
+            d = copy.copy(d0)
+            d.variant = v
+            whole, yd = canary_dev(n_out, ydt)
+            h.conv2d_add(d, xd, wd, ad, yd, bias=bd, workspace=ws, ws_bytes=ws.numel() * 4)
+            got = from_layout(host(yd, ydt), oshape, "NCHW", "NHWC")
+            assert canary_ok(whole, n_out), name
+            want = ref if out_dtype == alt.F32 else f32_to_bf16_bits(ref)
+            assert np.array_equal(got, want), name
+        generic = [v for v, n in applicable_variants(h, d0) if "direct" not in n and "stream" not in n]
+        d = copy.copy(d0)
+        d.variant = generic[0]
+        whole, yd = canary_dev(n_out, ydt)
+        with pytest.raises(alt.AltError) as e:
+            h.conv2d_add(d, xd, wd, ad, yd, bias=bd, workspace=ws, ws_bytes=ws.numel() * 4)
+        assert e.value.status == 4
+    # a layout only the implicit-GEMM kernels take: no variant applies
+    d = alt.conv_desc(1, 32, 8, 8, 32, 3, 3, pad=1, in_dtype=alt.BF16)
+    z = torch.zeros(1 << 14, dtype=torch.float32, device="cuda")
+    with pytest.raises(alt.AltError) as e:
+        h.conv2d_add(d, z, z, z, z)
+    assert e.value.status == 4
