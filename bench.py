@@ -644,10 +644,10 @@ def main():
             measurements=gp.trials,
             add_relu_us=round(add_us, 2), add_relu_GBps=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6), 1),
             add_relu_frac_hbm_peak=round(3.0 * numel * 2 / 1e9 / (add_us * 1e-6) / PEAK_HBM_GBPS, 4))
+        rb = extra["residual_block"]
+        rb["sum_fused_into_node"] = int(gp.fused_into[2])        # -1: the planner kept the sum as a launch of its own
         if fused is not None:
-            rb = extra["residual_block"]
             rb["conv_with_fused_sum_us"] = round(fused, 2)
-            rb["total_with_fused_sum_us"] = round(float(gp.total_us) - float(gp.node_us[1]) - float(gp.node_us[2]) + fused, 2)
 
     if want("groups"):
         # --------------------------- depth-wise and group-wise convolution ----

@@ -438,6 +438,10 @@ typedef struct {
     float node_us[ALT_MAX_GRAPH];
     float total_us;                                 /* planned latency of the graph */
     float default_total_us;                         /* the same graph with NCHW on every tensor */
+    int32_t fused_into[ALT_MAX_GRAPH];              /* ALT_NODE_ADD node i: index of the convolution node whose
+                                                       epilogue computes it (alt_conv2d_add; conv[] of that node then
+                                                       carries the sum's ReLU and node_us the fused time, node_us[i]
+                                                       is 0), or -1: the sum runs as alt_eltwise_add */
 } alt_graph_plan_t;
 
 /* Layout choice for a small graph of convolutions and element-wise sums, e.g.
@@ -451,7 +455,11 @@ typedef struct {
  * outputs of nodes before it; the last node's output is the graph's.  Measures
  * every convolution under every (input, output) layout pair, every conversion
  * of every consumed tensor and every sum, then takes the cheapest assignment.
- * Synchronises. */
+ * Last, a sum one of whose operands is the output of a convolution without ReLU
+ * that nothing else reads, read as stored, while the other operand (possibly a
+ * converted copy) exists before that convolution runs, is measured
+ * fused into that convolution's epilogue (alt_conv2d_add) and fused in the plan
+ * if that is faster than the two launches.  Synchronises. */
 alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int nnodes,
                             const alt_layout_t *in_layout, const alt_tune_opts_t *opts,
                             alt_graph_plan_t *plan);

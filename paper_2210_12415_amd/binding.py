@@ -107,7 +107,8 @@ class GraphPlan(ctypes.Structure):
                 ("conv", ConvDesc * MAX_GRAPH), ("tensor_layout", Layout * (MAX_GRAPH + 1)),
                 ("read_layout", (Layout * 2) * MAX_GRAPH), ("convert", (ctypes.c_int32 * 2) * MAX_GRAPH),
                 ("convert_us", (ctypes.c_float * 2) * MAX_GRAPH), ("node_us", ctypes.c_float * MAX_GRAPH),
-                ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float)]
+                ("total_us", ctypes.c_float), ("default_total_us", ctypes.c_float),
+                ("fused_into", ctypes.c_int32 * MAX_GRAPH)]
 
 
 class Peaks(ctypes.Structure):

@@ -931,6 +931,49 @@ alt_status_t alt_tune_graph(alt_handle_t h, const alt_graph_node_t *nodes, int n
     }
     if (in_idx != 0) dflt += CC(0, in_idx, 0);     // the all-NCHW graph converts its input once
     plan->default_total_us = (float)dflt;
+
+    // sums that a convolution's epilogue can compute (Fig. 6's fused nest)
+    for (int i = 0; i < nnodes; ++i) plan->fused_into[i] = -1;
+    for (int i = 0; i < nnodes; ++i) {
+        if (nodes[i].kind != ALT_NODE_ADD) continue;
+        for (int j = 0; j < 2 && plan->fused_into[i] < 0; ++j) {
+            if (plan->convert[i][j]) continue;                           // the sum reads the convolution's output as stored
+                                                                         // (the other operand may be a converted copy)
+            const int t = j == 0 ? i0[i] : i1[i], other = j == 0 ? i1[i] : i0[i];
+            const int c = t - 1;                                         // the node that produces tensor t
+            if (c < 0 || nodes[c].kind != ALT_NODE_CONV || (nodes[c].conv.epilogue & ALT_EPI_RELU) || other >= t) continue;   // (the other operand exists before the convolution runs)
+            if (T[other].dtype != T[t].dtype) continue;
+            int readers = 0;
+            for (int i2 = 0; i2 < nnodes; ++i2)
+                readers += (i0[i2] == t) + (nodes[i2].kind == ALT_NODE_ADD && i1[i2] == t);
+            bool already = false;                                        // one sum per epilogue
+            for (int i2 = 0; i2 < nnodes; ++i2) already = already || plan->fused_into[i2] == c;
+            if (readers != 1 || already) continue;
+            alt_conv_desc_t d = plan->conv[c];
+            if (nodes[i].relu) d.epilogue |= ALT_EPI_RELU;
+            const alt_conv_desc_t &op = nodes[c].conv;
+            const int64_t xs[4] = {op.N, op.C, op.H, op.W};
+            BoundLayout bs, bd;
+            if ((s = bind_layout(&plain_x, 4, xs, &bs, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+            if ((s = bind_layout(&d.x_layout, 4, xs, &bd, &err)) != ALT_OK) return fail(h, s, "%s", err.c_str());
+            if ((s = transform_bound(h, (int)dtype_size(op.in_dtype), bs, x0, bd, x1, st)) != ALT_OK) return s;
+            if ((s = alt_pack_weights(h, &d, w0, w1, st)) != ALT_OK) return s;
+            float us = INFINITY;
+            // (x0 serves as the addend: any buffer of the output's size does for timing)
+            s = measure(h, tm, st, opt_warmup(opts), opt_reps(opts),
+                        [&] { return alt_conv2d_add(h, &d, x1, w1, bias, x0, y, ws, ws_bytes, st); }, &us);
+            ++plan->trials;
+            if (s == ALT_UNSUPPORTED) continue;                          // not a tile-kernel problem
+            if (s != ALT_OK) return s;
+            if (us < plan->node_us[c] + plan->node_us[i]) {
+                plan->total_us -= plan->node_us[c] + plan->node_us[i] - us;
+                plan->node_us[c] = us;
+                plan->node_us[i] = 0.f;
+                plan->conv[c] = d;
+                plan->fused_into[i] = c;
+            }
+        }
+    }
     return ALT_OK;
 }
 

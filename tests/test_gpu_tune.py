@@ -149,34 +149,52 @@ def run_graph_plan(h, plan, nodes, x, weights, biases, arena, in_layout="NCHW->N
     tensor (device, bf16 bits), its logical shape and its layout."""
     tensors = [(dev(x.reshape(-1)), x.shape)]
     copies = {}                                   # (tensor, layout) -> converted copy, shared by its consumers
+
+    def read(i, j):
+        """Input j of node i as the plan has the node read it."""
+        t = nodes[i].in0 if j == 0 else nodes[i].in1
+        buf, shape = tensors[t]
+        if plan.convert[i][j]:
+            key = (t, _phys_name(plan.read_layout[i][j], "NCHW"))
+            if key not in copies:
+                copies[key] = torch.empty_like(buf)
+                h.layout_transform(alt.BF16, shape, plan.tensor_layout[t], buf, plan.read_layout[i][j], copies[key])
+            buf = copies[key]
+        return buf, shape
+
+    charged = set()
     for i, nd in enumerate(nodes):
-        ins = []
         for j in range(2 if nd.kind == alt.NODE_ADD else 1):
-            t = nd.in0 if j == 0 else nd.in1
-            buf, shape = tensors[t]
-            if plan.convert[i][j]:
-                key = (t, _phys_name(plan.read_layout[i][j], "NCHW"))
-                if key not in copies:
-                    assert plan.convert_us[i][j] > 0
-                    copies[key] = torch.empty_like(buf)
-                    h.layout_transform(alt.BF16, shape, plan.tensor_layout[t], buf, plan.read_layout[i][j], copies[key])
-                else:
-                    assert plan.convert_us[i][j] == 0      # charged once
-                buf = copies[key]
-            ins.append((buf, shape))
+            if plan.convert[i][j]:                  # a converted copy is charged to its first reader only
+                key = (nd.in0 if j == 0 else nd.in1, _phys_name(plan.read_layout[i][j], "NCHW"))
+                assert (plan.convert_us[i][j] > 0) == (key not in charged)
+                charged.add(key)
+    for i, nd in enumerate(nodes):
         if nd.kind == alt.NODE_CONV:
+            xin, _ = read(i, 0)
             d = plan.conv[i]
             wd = torch.empty_like(dev(weights[i].reshape(-1)))
             h.pack_weights(d, dev(weights[i].reshape(-1)), wd)
             oshape = h.conv2d_output_shape(d)
             y = torch.empty(int(np.prod(oshape)), dtype=torch.int16, device="cuda")
-            h.conv2d(d, ins[0][0], wd, y, bias=dev(biases[i]) if biases[i] is not None else None, workspace=arena,
-                     ws_bytes=arena.numel())
+            bias = dev(biases[i]) if biases[i] is not None else None
+            fused = [k for k in range(len(nodes)) if nodes[k].kind == alt.NODE_ADD and plan.fused_into[k] == i]
+            if fused:                                   # the sum of node fused[0] runs in this convolution's epilogue
+                k = fused[0]
+                jo = 1 if nodes[k].in0 == i + 1 else 0
+                other = nodes[k].in1 if jo == 1 else nodes[k].in0
+                assert other <= i and not plan.convert[k][1 - jo] and plan.node_us[k] == 0
+                h.conv2d_add(d, xin, wd, read(k, jo)[0], y, bias=bias, workspace=arena, ws_bytes=arena.numel())
+            else:
+                h.conv2d(d, xin, wd, y, bias=bias, workspace=arena, ws_bytes=arena.numel())
             tensors.append((y, oshape))
+        elif plan.fused_into[i] >= 0:                   # computed by its convolution already
+            tensors.append(tensors[plan.fused_into[i] + 1])
         else:
-            y = torch.empty_like(ins[0][0])
-            h.eltwise_add(alt.BF16, y.numel(), ins[0][0], ins[1][0], y, relu=bool(nd.relu))
-            tensors.append((y, ins[0][1]))
+            (a, shape), (b2, _) = read(i, 0), read(i, 1)
+            y = torch.empty_like(a)
+            h.eltwise_add(alt.BF16, y.numel(), a, b2, y, relu=bool(nd.relu))
+            tensors.append((y, shape))
     return tensors[-1][0], tensors[-1][1], plan.tensor_layout[len(nodes)]
 
 
@@ -213,6 +231,12 @@ def test_residual_block_plan_executes_to_oracle_result(h, arena):
     got = from_layout(host(out, np.uint16), oshape, "NCHW", name(olayout))
     assert rel_err(bf16_bits_to_f32(got), bf16_bits_to_f32(ref)) <= TOL[alt.BF16]
     assert (bf16_bits_to_f32(got) >= 0).all()
+    assert plan.fused_into[0] == plan.fused_into[1] == -1 and plan.fused_into[2] in (-1, 1)
+    if plan.fused_into[2] == 1:
+        # fused: the fp32 sum is rounded once (the unfused reference above rounds the convolution first)
+        assert plan.conv[1].epilogue & alt.EPI_RELU and plan.node_us[2] == 0
+        once = np.maximum(oracle.conv2d(t1, ws[1], stride=1, pad=1, bias=bs[1]) + bf16_bits_to_f32(x), np.float32(0))
+        assert rel_err(bf16_bits_to_f32(got), once) <= 2.0 ** -8
 
 
 @pytest.mark.parametrize("dtype", [alt.BF16, alt.F32])
