@@ -214,6 +214,19 @@ def test_calls_without_gpu_fail_loudly_not_silently():
     with pytest.raises(alt.AltError) as e:
         h.conv2d(bad, 16, 16, 16, stream=0)
     assert e.value.status == 3
+    # the other compute entry points refuse too (no host fallback anywhere)
+    nhwc = alt.conv_desc(1, 64, 8, 8, 64, 3, 3, pad=1, in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI",
+                         y_layout="NCHW->NHWC")
+    for call in (lambda: h.conv2d_add(nhwc, 16, 16, 16, 16, stream=0),
+                 lambda: h.conv2d_transpose(alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=1), 16, 16, 16, workspace=16,
+                                            ws_bytes=1 << 20, stream=0),
+                 lambda: h.pack_weights_transpose(d, 16, 16, stream=0),
+                 lambda: h.tune_conv2d_multi([dict(d=nhwc, x=16, w=16, y=16, stream=0)]),
+                 lambda: h.eltwise_add(alt.BF16, 64, 16, 16, 16, stream=0),
+                 lambda: h.unfold(alt.BF16, (4, 8), 0, 2, 1, 16, 4096, stream=0)):
+        with pytest.raises(alt.AltError) as e:
+            call()
+        assert e.value.status == 6
 
 
 def test_conv_transpose_host_side(oracle):
