@@ -518,8 +518,8 @@ def main():
         extra["conv_on_unfolded_tiles_c64_56x56_b16"] = dict(
             tiles=[N_ * TH * TH, BH, BH, C_], unfold_reorder_and_conv_us=round(us_all, 2), tile_conv_alone_us=round(us_conv, 2),
             direct_kernel_us=round(direct["us"], 2),
-            note="the tile convolution runs on the implicit-GEMM kernels (default variant); the direct kernel's "
-                 "figure is the same layer with same-size padding")
+            note="the tile convolution has no padding and runs on the direct kernel too (default variant); "
+                 "direct_kernel_us is the un-tiled layer with same-size padding under its tuned variant")
         del xs, wsd2, t1, t2, t3, yt
 
     if want("gemm"):

@@ -13,8 +13,8 @@
 // the weights stream through a ring of LDS stages (direct-to-LDS loads as in
 // igemm_dma.h).
 //
-// Covers: bf16, stride 1 or 2 (image sizes a multiple of the stride), dilation 1,
-// "same" padding (2*pad = R-1, S-1; so 1x1 pad 0 too), activations NHWC,
+// Covers: bf16, stride 1 or 2, dilation 1, padding from none to "same"
+// (2*pad <= R-1, S-1, so the output is no larger than the input), activations NHWC,
 // weights OHWI, output NHWC (fp32 or bf16), all dense, 64, 128, 256 or 512
 // channels per split, output channels a multiple of 4.  The input pixel under
 // an output pixel then grows monotonically with the output's linear index,
@@ -484,7 +484,8 @@ void dconv_kernel(const DconvParams p)
     // the pixel an instruction offset, with no per-read address arithmetic.
     // Output pixel m of image img at (oh, ow) sits over input pixel img*H*W + oh*stride*W + ow*stride
     // (its tap (pad_h, pad_w)); the tile's patch runs from the first row's to the last row's.
-    const int halo = p.pad_h * p.W + p.pad_w;
+    const int halo = p.pad_h * p.W + p.pad_w;                                  // pixels before the first tap's anchor
+    const int halo_hi = (p.R - 1 - p.pad_h) * p.W + (p.S - 1 - p.pad_w);       // and behind the last one's
     const int ohw = p.OH * p.OW;
     auto anchor = [&](int m) {
         const int img = (int)div32((uint32_t)m, p.d_hw), rem = m - img * ohw;
@@ -492,7 +493,7 @@ void dconv_kernel(const DconvParams p)
         return img * (p.H * p.W) + (oh * p.W + ow) * p.stride;
     };
     const int a0 = anchor(m0);
-    const int np = anchor(min(m0 + BM, p.M) - 1) - a0 + 1 + 2 * halo;
+    const int np = anchor(min(m0 + BM, p.M) - 1) - a0 + 1 + halo + halo_hi;
     const int spp = (1 << p.log2_cpp) + 1;                 // 16-byte slots per patch pixel
     const int pitch_b = spp * 16;
     const int nwl = (np * spp + 63) >> 6;                  // wave-loads (the region is padded to whole ones)
@@ -765,16 +766,33 @@ void dconv_kernel(const DconvParams p)
 #endif
 }
 
+// Pixels of the largest patch over the tiles of BM output pixels: the span of input pixels
+// under a tile's first and last output pixel (found tile by tile: it depends on where rows and
+// images end inside the tile) plus the taps' reach before and behind.
+inline size_t dconv_patch_pixels(int BM, int64_t M, int H, int W, int OH, int OW, int R, int S, int pad_h, int pad_w,
+                                 int stride)
+{
+    auto anchor = [&](int64_t m) {
+        const int64_t img = m / ((int64_t)OH * OW), rem = m - img * OH * OW, oh = rem / OW, ow = rem - oh * OW;
+        return img * H * W + (oh * W + ow) * stride;
+    };
+    int64_t span = 1;
+    if (stride == 1 && OH == H && OW == W) span = BM;      // output and input indices coincide
+    else
+        for (int64_t m0 = 0; m0 < M; m0 += BM) {
+            const int64_t m1 = (m0 + BM < M ? m0 + BM : M) - 1;
+            const int64_t d = anchor(m1) - anchor(m0) + 1;
+            if (d > span) span = d;
+        }
+    return (size_t)span + (size_t)pad_h * W + pad_w + (size_t)(R - 1 - pad_h) * W + (S - 1 - pad_w);
+}
+
 // LDS bytes of one workgroup: the K groups' weight rings, the patch rounded up to
 // whole wave-loads, the all-zero row.
-inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, int W, int pad_h, int pad_w,
-                              int stride)
+// np = the largest patch of any tile, in pixels (dconv_patch_pixels).
+inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, size_t np)
 {
     const size_t spp = (size_t)Cs / 8 + 1;                 // 16-byte slots per patch pixel (one unused)
-    // BM consecutive output pixels sit over at most stride^2 * BM input pixels, plus one step
-    // from an output row (or image) to the next
-    const size_t span = stride == 1 ? (size_t)BM : (size_t)stride * stride * BM + (size_t)stride * W;
-    const size_t np = span + 2 * ((size_t)pad_h * W + pad_w);
     const size_t nwl = (np * spp + 63) / 64;
     const size_t pz = (nwl * 64 + spp - 1) / spp;          // the zero row sits behind the whole wave-loads
     const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + (pz + 1) * spp * 16;

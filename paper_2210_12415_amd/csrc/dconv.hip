@@ -154,9 +154,11 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if (p.batch != 1) return no("direct kernel takes no batch");
     if (p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2) || p.dil_h != 1 || p.dil_w != 1)
         return no("direct kernel needs stride 1 or 2, dilation 1");
-    if (2 * p.pad_h != p.R - 1 || 2 * p.pad_w != p.S - 1) return no("direct kernel needs same-size padding");
+    if (p.pad_h < 0 || p.pad_w < 0 || 2 * p.pad_h > p.R - 1 || 2 * p.pad_w > p.S - 1)
+        return no("direct kernel needs padding between none and same-size");
     const int st_ = p.stride_h;
-    if (p.H % st_ || p.W % st_ || p.OH != p.H / st_ || p.OW != p.W / st_) return no("direct kernel needs output size = input size / stride");
+    // (then OH <= ceil(H / stride) and likewise OW: the input pixel under an output pixel never moves backwards)
+    if ((int64_t)(p.OH - 1) * st_ >= p.H || (int64_t)(p.OW - 1) * st_ >= p.W) return no("output larger than the strided input");
     const int64_t C = p.C, H = p.H, W = p.W, OH = p.OH, OW = p.OW, K = p.Nc, R = p.R, S = p.S, N = p.M / (OH * OW);
     if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
         return no("activations are not dense NHWC");
@@ -180,7 +182,8 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
     if (K % 4 || (uintptr_t)p.y % 16 || ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 16))
         return no("direct kernel stores four output channels at a time");
-    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs, p.W, p.pad_h, p.pad_w, st_);
+    const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs,
+                                       dconv_patch_pixels(k.BM, p.M, p.H, p.W, p.OH, p.OW, p.R, p.S, p.pad_h, p.pad_w, st_));
     if (lds > 160 * 1024) return no("patch does not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");

@@ -101,12 +101,15 @@ DIRECT_CASES = [
     dict(N=3, C=64, H=12, W=10, K=96, R=3, S=3, pad=1, stride=2),    # stride 2: tiles over rows and images of half size
     dict(N=2, C=128, H=14, W=18, K=64, R=1, S=1, pad=0, stride=2),   # the strided 1x1 of a projection shortcut
     dict(N=2, C=256, H=6, W=8, K=64, R=5, S=5, pad=2, stride=2),     # run-time tap walk at stride 2
+    dict(N=3, C=64, H=12, W=11, K=64, R=3, S=3, pad=0),              # no padding: the output is smaller than the input
+    dict(N=2, C=128, H=13, W=11, K=64, R=3, S=3, pad=0, stride=2),   # the same at stride 2, odd image sizes
+    dict(N=2, C=64, H=10, W=12, K=32, R=5, S=5, pad=1),              # less than same-size padding
 ]
 
 
-@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1)))
+@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d_p%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1), c["pad"]))
 def test_direct_kernel_exact_integers_every_variant(h, case):
-    """The patch-resident direct kernels (NHWC / OHWI / NHWC, same-size padding, stride 1 or 2):
+    """The patch-resident direct kernels (NHWC / OHWI / NHWC, padding from none to same-size, stride 1 or 2):
     every tile shape, pipeline depth and channel-slice count, bit for bit; fp32
     and bf16 output, bias and ReLU through the fused split-K tail as well."""
     c = case
