@@ -687,6 +687,17 @@ def main():
             tflops=round(gfl / float(grep_.best_us) / 1e6, 1), trials=grep_.trials,
             layout_us=dict(zip(gnames, [round(float(grep_.layout_best_us[i]), 2) for i in range(grep_.n_layouts)])))
 
+        # a segmentation-style dilated 3x3 layer (256 channels, 28x28, taps two pixels apart), tuned like the others
+        dshape = alt.conv_desc(16, 256, 28, 28, 256, 3, 3, stride=1, pad=2, dil=2, in_dtype=alt.BF16, out_dtype=alt.BF16)
+        dbest, drep = h.tune_conv2d(dshape, arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        dfl = 2.0 * 16 * 256 * 28 * 28 * 256 * 9
+        dnames = [drep.layout_name[i].value.decode() for i in range(drep.n_layouts)]
+        extra["dilated_c256_3x3_d2_28x28_b16"] = dict(
+            variant=h.conv2d_variant_name(dbest, dbest.variant), layout=dnames[int(np.argmin([drep.layout_best_us[i] for i in range(drep.n_layouts)]))],
+            tuned_us=round(float(drep.best_us), 2), default_layout_us=round(float(drep.default_us), 2),
+            tflops=round(dfl / float(drep.best_us) / 1e6, 1), trials=drep.trials,
+            layout_us=dict(zip(dnames, [round(float(drep.layout_best_us[i]), 2) for i in range(drep.n_layouts)])))
+
         # a decoder-style transposed convolution (128 -> 64 channels, 4x4, stride 2, 28x28 -> 56x56, batch 16):
         # zero insertion + the forward kernels, per activation layout
         t2d = {}

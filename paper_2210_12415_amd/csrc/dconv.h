@@ -13,8 +13,8 @@
 // the weights stream through a ring of LDS stages (direct-to-LDS loads as in
 // igemm_dma.h).
 //
-// Covers: bf16, stride 1 or 2, dilation 1, padding from none to "same"
-// (2*pad <= R-1, S-1, so the output is no larger than the input), activations NHWC,
+// Covers: bf16, stride 1 or 2, any dilation, padding from none to "same"
+// (2*pad <= dil*(R-1), dil*(S-1), so the output is no larger than the input), activations NHWC,
 // weights OHWI, output NHWC (fp32 or bf16), all dense, 64, 128, 256 or 512
 // channels per split, output channels a multiple of 4.  The input pixel under
 // an output pixel then grows monotonically with the output's linear index,
@@ -83,6 +83,7 @@ struct DconvParams {
     // direct kernel only: output image size and stride (H, W above are the input's; M counts
     // output pixels), and the number of input pixels
     int32_t OH, OW, stride, in_px;
+    int32_t dil;                  // distance between filter taps, in input pixels (both directions)
     const void *addend;           // added before the activation: same layout and element type as y, or null
 };
 
@@ -485,7 +486,7 @@ void dconv_kernel(const DconvParams p)
     // Output pixel m of image img at (oh, ow) sits over input pixel img*H*W + oh*stride*W + ow*stride
     // (its tap (pad_h, pad_w)); the tile's patch runs from the first row's to the last row's.
     const int halo = p.pad_h * p.W + p.pad_w;                                  // pixels before the first tap's anchor
-    const int halo_hi = (p.R - 1 - p.pad_h) * p.W + (p.S - 1 - p.pad_w);       // and behind the last one's
+    const int halo_hi = ((p.R - 1) * p.dil - p.pad_h) * p.W + ((p.S - 1) * p.dil - p.pad_w);   // and behind the last one's
     const int ohw = p.OH * p.OW;
     auto anchor = [&](int m) {
         const int img = (int)div32((uint32_t)m, p.d_hw), rem = m - img * ohw;
@@ -597,11 +598,11 @@ void dconv_kernel(const DconvParams p)
         uint32_t a_row[TM], c_off, st_off;
     };
     auto set_tap = [&](StepAddr &sa, int r, int s) {
-        const int shift = (r - p.pad_h) * p.W + (s - p.pad_w);
+        const int dr = r * p.dil - p.pad_h, ds = s * p.dil - p.pad_w;          // the tap's offset from the anchor
+        const int shift = dr * p.W + ds;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const bool ok = (unsigned)(row_oh[i] + r - p.pad_h) < (unsigned)p.H &&
-                            (unsigned)(row_ow[i] + s - p.pad_w) < (unsigned)p.W;
+            const bool ok = (unsigned)(row_oh[i] + dr) < (unsigned)p.H && (unsigned)(row_ow[i] + ds) < (unsigned)p.W;
             const int px = ok ? row_px[i] + shift : pz;
             sa.a_row[i] = patch0 + (uint32_t)(px * pitch_b) + khalf;
         }
@@ -770,7 +771,7 @@ void dconv_kernel(const DconvParams p)
 // under a tile's first and last output pixel (found tile by tile: it depends on where rows and
 // images end inside the tile) plus the taps' reach before and behind.
 inline size_t dconv_patch_pixels(int BM, int64_t M, int H, int W, int OH, int OW, int R, int S, int pad_h, int pad_w,
-                                 int stride)
+                                 int stride, int dil)
 {
     auto anchor = [&](int64_t m) {
         const int64_t img = m / ((int64_t)OH * OW), rem = m - img * OH * OW, oh = rem / OW, ow = rem - oh * OW;
@@ -784,7 +785,7 @@ inline size_t dconv_patch_pixels(int BM, int64_t M, int H, int W, int OH, int OW
             const int64_t d = anchor(m1) - anchor(m0) + 1;
             if (d > span) span = d;
         }
-    return (size_t)span + (size_t)pad_h * W + pad_w + (size_t)(R - 1 - pad_h) * W + (S - 1 - pad_w);
+    return (size_t)span + (size_t)pad_h * W + pad_w + (size_t)((R - 1) * dil - pad_h) * W + ((S - 1) * dil - pad_w);
 }
 
 // LDS bytes of one workgroup: the K groups' weight rings, the patch rounded up to

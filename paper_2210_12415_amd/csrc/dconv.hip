@@ -152,9 +152,9 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     const IgemmParams &p = pb.p;
     if (pb.dtype != ALT_BF16) return no("direct kernel is bf16 only");
     if (p.batch != 1) return no("direct kernel takes no batch");
-    if (p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2) || p.dil_h != 1 || p.dil_w != 1)
-        return no("direct kernel needs stride 1 or 2, dilation 1");
-    if (p.pad_h < 0 || p.pad_w < 0 || 2 * p.pad_h > p.R - 1 || 2 * p.pad_w > p.S - 1)
+    if (p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2) || p.dil_h != p.dil_w || p.dil_h < 1)
+        return no("direct kernel needs stride 1 or 2 and one dilation for both directions");
+    if (p.pad_h < 0 || p.pad_w < 0 || 2 * p.pad_h > p.dil_h * (p.R - 1) || 2 * p.pad_w > p.dil_w * (p.S - 1))
         return no("direct kernel needs padding between none and same-size");
     const int st_ = p.stride_h;
     // (then OH <= ceil(H / stride) and likewise OW: the input pixel under an output pixel never moves backwards)
@@ -183,7 +183,7 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     if (K % 4 || (uintptr_t)p.y % 16 || ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 16))
         return no("direct kernel stores four output channels at a time");
     const size_t lds = dconv_lds_bytes(k.BM, k.BN, k.prefetch + 1, k.wgn, kw, bk, (int)Cs,
-                                       dconv_patch_pixels(k.BM, p.M, p.H, p.W, p.OH, p.OW, p.R, p.S, p.pad_h, p.pad_w, st_));
+                                       dconv_patch_pixels(k.BM, p.M, p.H, p.W, p.OH, p.OW, p.R, p.S, p.pad_h, p.pad_w, st_, p.dil_h));
     if (lds > 160 * 1024) return no("patch does not fit LDS");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
@@ -198,7 +198,7 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     d.H = p.H; d.W = p.W; d.R = p.R; d.S = p.S; d.pad_h = p.pad_h; d.pad_w = p.pad_w;
     d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = splitk;
     d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
-    d.OH = p.OH; d.OW = p.OW; d.stride = st_;
+    d.OH = p.OH; d.OW = p.OW; d.stride = st_; d.dil = p.dil_h;
     if (N * H * W > 0x7fffffff) return no("input too large for 32-bit pixel indices");
     d.in_px = (int32_t)(N * H * W);
     d.d_hw = make_div32((uint32_t)(p.OH * p.OW));

@@ -104,10 +104,12 @@ DIRECT_CASES = [
     dict(N=3, C=64, H=12, W=11, K=64, R=3, S=3, pad=0),              # no padding: the output is smaller than the input
     dict(N=2, C=128, H=13, W=11, K=64, R=3, S=3, pad=0, stride=2),   # the same at stride 2, odd image sizes
     dict(N=2, C=64, H=10, W=12, K=32, R=5, S=5, pad=1),              # less than same-size padding
+    dict(N=2, C=64, H=13, W=12, K=64, R=3, S=3, pad=2, dil=2),       # dilated, same-size
+    dict(N=2, C=128, H=14, W=10, K=32, R=3, S=3, pad=1, dil=3, stride=2),   # dilated and strided, partial padding
 ]
 
 
-@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d_p%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1), c["pad"]))
+@pytest.mark.parametrize("case", DIRECT_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d_p%d_d%d" % (c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1), c["pad"], c.get("dil", 1)))
 def test_direct_kernel_exact_integers_every_variant(h, case):
     """The patch-resident direct kernels (NHWC / OHWI / NHWC, padding from none to same-size, stride 1 or 2):
     every tile shape, pipeline depth and channel-slice count, bit for bit; fp32
@@ -116,22 +118,22 @@ def test_direct_kernel_exact_integers_every_variant(h, case):
     x = small_ints_f32(61, (c["N"], c["C"], c["H"], c["W"]), -3, 3)
     w = small_ints_f32(62, (c["K"], c["C"], c["R"], c["S"]), -3, 3)
     b = small_ints_f32(63, (c["K"],), -50, 50)
-    st = c.get("stride", 1)
-    cfg = dict(stride=st, pad=c["pad"])
-    ref = oracle.conv2d(x, w, stride=st, pad=c["pad"])
-    ref_br = oracle.conv2d(x, w, stride=st, pad=c["pad"], bias=b, relu=True)
+    st, dil = c.get("stride", 1), c.get("dil", 1)
+    cfg = dict(stride=st, pad=c["pad"], dil=dil)
+    ref = oracle.conv2d(x, w, stride=st, pad=c["pad"], dil=dil)
+    ref_br = oracle.conv2d(x, w, stride=st, pad=c["pad"], dil=dil, bias=b, relu=True)
     xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
-    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=st, pad=c["pad"],
+    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=st, pad=c["pad"], dil=dil,
                        in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
     variants = [(v, n) for v, n in applicable_variants(h, d0) if "direct" in n]
-    assert len(variants) >= (20 if st == 1 else 6), "direct kernels should cover this case"
+    assert len(variants) >= (20 if st == 1 and dil == 1 else 6), "direct kernels should cover this case"
     assert any(not n.endswith("_k1") for _, n in variants) or c["C"] == 64
     for v, name in variants:
         got, _ = run_conv(h, xb, wb, cfg, "NHWC", "OHWI", "NHWC", alt.BF16, variant=v)
         assert np.array_equal(got, ref), name
     # kernels whose waves form several K groups (name: w<rows>x<cols>x<groups>)
     grouped = [vn for vn in variants if re.search(r"_w\d+x\d+x\d+_", vn[1])]
-    assert grouped or c["C"] == 64 or st == 2            # (at stride 2 the wide patch leaves room for few of them)
+    assert grouped or c["C"] == 64 or st == 2 or dil > 1  # (a wide patch leaves room for few of them)
     # the epilogue variants on a few kernels, split and unsplit, with and without K groups
     picks = ([variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
              + grouped[:2] + [vn for vn in grouped if not vn[1].endswith("_k1")][:2])
