@@ -719,6 +719,30 @@ def main():
             per_layout=t2d, speedup_vs_nchw=round(t2d["NCHW"]["us"] / min(v["us"] for v in t2d.values()), 2),
             note="two launches per call (input expansion, forward kernel with default variant choice)")
 
+        # a ResNet3D-18-shaped layer (the C3D of the operator list): 128 -> 128 channels, 3x3x3, 8 slices of 28x28,
+        # batch 2; depth unfolded into the channels per call, then the 2-D kernels on 16 images of 384 channels
+        c3d = {}
+        c3fl = 2.0 * 2 * 8 * 28 * 28 * 128 * 128 * 27         # nominal: padding taps counted
+        # tune the equivalent 2-D problem first: the 3-D call finds the winners in the cache
+        h.tune_conv2d(alt.conv_desc(16, 384, 28, 28, 128, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16),
+                      arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
+            d = alt.conv3d_desc(2, 128, 8, 28, 28, 128, 3, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
+            osh = h.conv3d_output_shape(d)
+            xb = torch.randint(-200, 200, (2 * 8 * 128 * 28 * 28,), dtype=torch.int16, device=dev)
+            wb = torch.randint(-200, 200, (128 * 128 * 27,), dtype=torch.int16, device=dev)
+            yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)
+            wsb = h.conv3d_workspace_size(d)
+            wsd = torch.empty(wsb + 16, dtype=torch.uint8, device=dev)
+            gr = capture(lambda st: h.conv3d(d, xb, wb, yb, workspace=wsd, ws_bytes=wsb, stream=st), 20)
+            us = graph_timed(gr, 20)
+            del gr, xb, wb, yb, wsd
+            c3d[xl] = dict(us=round(us, 2), nominal_tflops=round(c3fl / us / 1e6, 1))
+        extra["conv3d_c128_3x3x3_8x28x28_b2"] = dict(
+            per_layout=c3d, speedup_vs_nchw=round(c3d["NCHW"]["us"] / min(v["us"] for v in c3d.values()), 2),
+            note="two launches per call (depth unfolding into the workspace, tuned forward kernel)")
+
     if want("budget"):
         # ------------------------------- budgeted search against the full one ----
         # the tuner with 48 measurements per layer (variants ranked by the cost estimate, measured best first)

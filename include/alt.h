@@ -263,6 +263,43 @@ alt_status_t alt_conv2d_transpose_output_shape(const alt_conv_desc_t *d, int64_t
 alt_status_t alt_pack_weights_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *w_ckrs,
                                         void *w_packed, void *stream);
 
+/* 3-D convolution (C3D in the operator list of Section 6.1):
+ *   y[n,k,od,oh,ow] = sum_{c,t,r,s} x[n,c,od*stride_d-pad_d+t*dil_d, oh*stride_h-pad_h+r*dil_h, ow*stride_w-pad_w+s*dil_w] * w[k,c,t,r,s],
+ *   zeros outside the input, OD = floor((D+2pad_d-dil_d(T-1)-1)/stride_d)+1 (OH, OW as for alt_conv2d).
+ * `plane` is the 2-D part of the problem: N, C, H, W, K, R, S, the strides, padding and dilation
+ * of the two directions of a depth slice, dtypes, epilogue, variant, and the layouts of ONE depth
+ * slice; D, T and the *_d fields are the depth part.  Tensors are stacks of depth slices, batch
+ * index outermost (every layout alt_layout_parse accepts keeps it there):
+ *   x is logical (N*D,  C, H,  W)  under plane.x_layout, slice (n, d)  at batch index n*D  + d,
+ *   y is logical (N*OD, K, OH, OW) under plane.y_layout, slice (n, od) at batch index n*OD + od,
+ * so "NCHW->NHWC" here is the NDHWC tensor and "NCHW->NCHW" the NDCHW one (a tensor with the
+ * channels outside the depth is brought there by alt_layout_transform on its five dimensions).
+ * It runs as a 2-D convolution: unfolding the depth (Section 4.1.2, Eq. 1) into tiles of T slices
+ * every stride_d and placing the tile index beside the channels gives
+ *   x'[(n,od), t*C + c, h, w] = x[(n, od*stride_d - pad_d + t*dil_d), c, h, w]   (zero outside the depth),
+ * logical (N*OD, T*C, H, W) under plane.x_layout, which a kernel of its own writes into the
+ * workspace per call; alt_conv2d's kernels (variants, tuning cache, epilogue as there) convolve it
+ * with w'[k, t*C + c, r, s] = w[k,c,t,r,s], logical (K, T*C, R, S) under plane.w_layout, which
+ * alt_pack_weights3d writes once, offline, from the dense (K,C,T,R,S) filter.  Blocked layouts
+ * must divide T*C as they would C.  T = 1 with stride_d = 1 and pad_d = 0 is alt_conv2d on x itself.
+ * `workspace` (device, 16-byte aligned) holds x' followed by what alt_conv2d wants;
+ * alt_conv3d_workspace_size reports the sum, less than x' fails with ALT_WORKSPACE_TOO_SMALL.
+ * groups > 1 is ALT_UNSUPPORTED.  alt_conv3d_output_shape writes (N, K, OD, OH, OW).
+ * Asynchronous on `stream`. */
+typedef struct {
+    alt_conv_desc_t plane;
+    int64_t D, T;                 /* input depth, filter depth */
+    int32_t stride_d, pad_d, dil_d;
+    int32_t reserved;             /* 0 */
+} alt_conv3d_desc_t;
+
+alt_status_t alt_conv3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
+                        const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
+alt_status_t alt_conv3d_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes);
+alt_status_t alt_conv3d_output_shape(const alt_conv3d_desc_t *d, int64_t *out_nkdhw);
+alt_status_t alt_pack_weights3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_kctrs,
+                                void *w_packed, void *stream);
+
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and
  * operand loader).  Variant numbers are stable within one library build. */

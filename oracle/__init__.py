@@ -394,14 +394,15 @@ def conv2d_transpose(x, w, stride=1, pad=0, dil=1, out_bf16=False, bias=None, re
     return f32_to_bf16_bits(y) if out_bf16 else y
 
 
-def conv3d(x, w, stride=1, pad=0):
+def conv3d(x, w, stride=1, pad=0, dil=1):
     """3-D convolution (the C3D of Section 6.1's operator list) from its definition:
 
-        y[n, k, od, oh, ow] = sum_{c,t,r,s} x[n, c, od*stride - pad + t, oh*stride - pad + r, ow*stride - pad + s] * w[k, c, t, r, s]
+        y[n, k, od, oh, ow] = sum_{c,t,r,s} x[n, c, od*sd - pd + t*dd, oh*sh - ph + r*dh, ow*sw - pw + s*dw] * w[k, c, t, r, s]
 
     with zeros outside the input.  x: (N,C,D,H,W), w: (K,C,T,R,S), float32 or uint16 bf16
-    bits; sums in float64, one rounding to float32.  Pure numpy: one channel contraction
-    per filter tap over a strided view of the zero-padded input."""
+    bits; stride, pad, dil: one number for all three directions or (depth, height, width);
+    sums in float64, one rounding to float32.  Pure numpy: one channel contraction per
+    filter tap over a strided view of the zero-padded input."""
     x = np.asarray(x)
     w = np.asarray(w)
     xf = bf16_bits_to_f64(x) if x.dtype == np.uint16 else x.astype(np.float64)
@@ -410,16 +411,20 @@ def conv3d(x, w, stride=1, pad=0):
     K, C2, T, R, S = wf.shape
     if C2 != C:
         raise ValueError("conv3d: w is (K, C, T, R, S)")
-    OD, OH, OW = (D + 2 * pad - T) // stride + 1, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    three = lambda v: tuple(int(e) for e in v) if isinstance(v, (tuple, list)) else (int(v),) * 3
+    (sd, sh, sw), (pd, ph, pw), (dd, dh, dw) = three(stride), three(pad), three(dil)
+    OD = (D + 2 * pd - dd * (T - 1) - 1) // sd + 1
+    OH = (H + 2 * ph - dh * (R - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (S - 1) - 1) // sw + 1
     if min(OD, OH, OW) < 1:
         raise ValueError("conv3d: empty output")
-    xp = np.pad(xf, ((0, 0), (0, 0), (pad, pad), (pad, pad), (pad, pad)))
+    xp = np.pad(xf, ((0, 0), (0, 0), (pd, pd), (ph, ph), (pw, pw)))
     y = np.zeros((N, K, OD, OH, OW), dtype=np.float64)
     for t in range(T):
         for r in range(R):
             for s_ in range(S):
-                win = xp[:, :, t:t + (OD - 1) * stride + 1:stride, r:r + (OH - 1) * stride + 1:stride,
-                         s_:s_ + (OW - 1) * stride + 1:stride]
+                win = xp[:, :, t * dd:t * dd + (OD - 1) * sd + 1:sd, r * dh:r * dh + (OH - 1) * sh + 1:sh,
+                         s_ * dw:s_ * dw + (OW - 1) * sw + 1:sw]
                 y += np.einsum("ncdhw,kc->nkdhw", win, wf[:, :, t, r, s_])
     return y.astype(np.float32)
 

@@ -11,8 +11,8 @@ import os as _os
 # Only effective if set before the HIP runtime starts in this process.
 _os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 
-from .binding import (AltError, Handle, Layout, ConvDesc, ConvCall, GemmDesc, TuneOpts, TuneReport,
+from .binding import (AltError, Handle, Layout, ConvDesc, Conv3dDesc, ConvCall, GemmDesc, TuneOpts, TuneReport,
                       ChainPlan, GraphNode, GraphPlan, NODE_CONV, NODE_ADD, Prim, Peaks, F32, BF16, EPI_BIAS, EPI_RELU,
                       layout_parse, layout_from_prims, layout_physical_shape, layout_offset,
                       layout_index_of, plan_chain, plan_graph, graph_node, unfold_shape, split, reorder, fuse, version, lib,
-                      conv_desc, gemm_desc, exported_symbols, library_path)
+                      conv_desc, conv3d_desc, gemm_desc, exported_symbols, library_path)

@@ -59,6 +59,12 @@ class ConvDesc(ctypes.Structure):
                 ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
+class Conv3dDesc(ctypes.Structure):
+    _fields_ = [("plane", ConvDesc), ("D", ctypes.c_int64), ("T", ctypes.c_int64),
+                ("stride_d", ctypes.c_int32), ("pad_d", ctypes.c_int32), ("dil_d", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
 class GemmDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("batch", "M", "N", "K")] + \
                [(n, ctypes.c_int32) for n in ("in_dtype", "out_dtype", "variant", "reserved")] + \
@@ -146,7 +152,8 @@ def exported_symbols():
             "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
             "alt_conv2d", "alt_conv2d_add", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
-            "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose",
+            "alt_conv3d", "alt_conv3d_workspace_size", "alt_conv3d_output_shape", "alt_pack_weights3d", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
@@ -274,6 +281,18 @@ def conv_desc(N, C, H, W, K, R, S, stride=1, pad=0, dil=1, in_dtype=BF16, out_dt
     return d
 
 
+def _triple(v):
+    return tuple(v) if isinstance(v, (tuple, list)) else (v, v, v)
+
+
+def conv3d_desc(N, C, D, H, W, K, T, R, S, stride=1, pad=0, dil=1, **plane):
+    """stride, pad, dil: one number or (depth, height, width); the rest as conv_desc."""
+    (sd, sh, sw), (pd, ph, pw), (dd, dh, dw) = _triple(stride), _triple(pad), _triple(dil)
+    q = conv_desc(N, C, H, W, K, R, S, **plane)
+    q.stride_h, q.stride_w, q.pad_h, q.pad_w, q.dil_h, q.dil_w = sh, sw, ph, pw, dh, dw
+    return Conv3dDesc(q, D, T, sd, pd, dd, 0)
+
+
 def gemm_desc(M, N, K, batch=1, in_dtype=BF16, out_dtype=F32, variant=-1,
               a_layout="MK->MK", b_layout="KN->KN", c_layout="MN->MN"):
     d = GemmDesc(batch, M, N, K, in_dtype, out_dtype, variant, 0)
@@ -392,6 +411,24 @@ class Handle:
     def pack_weights_transpose(self, d, w_ckrs, w_packed, stream=None):
         _ck(lib().alt_pack_weights_transpose(self._h, ctypes.byref(d), _ptr(w_ckrs), _ptr(w_packed),
                                              _stream(stream)), self._h)
+
+    def conv3d(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_conv3d(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
+                             _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv3d_workspace_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_conv3d_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def conv3d_output_shape(self, d):
+        out = (ctypes.c_int64 * 5)()
+        _ck(lib().alt_conv3d_output_shape(ctypes.byref(d), out))
+        return tuple(out)
+
+    def pack_weights3d(self, d, w_kctrs, w_packed, stream=None):
+        _ck(lib().alt_pack_weights3d(self._h, ctypes.byref(d), _ptr(w_kctrs), _ptr(w_packed),
+                                     _stream(stream)), self._h)
 
     def pack_weights(self, d, w_oihw, w_packed, stream=None):
         _ck(lib().alt_pack_weights(self._h, ctypes.byref(d), _ptr(w_oihw), _ptr(w_packed),

@@ -11,6 +11,7 @@
 #include <string>
 
 #include "common.h"
+#include "fast_layout.h"
 #include "layout_eval.h"
 #include "ops.h"
 
@@ -61,14 +62,6 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_spread_kernel(SpreadParams p)
 // 16 bytes of a channel run when both layouts end in the same contiguous channel block),
 // recovers their logical index from the offset digit by digit and gathers from x.  All
 // index arithmetic is 32-bit with divisions by multiplication.
-struct FastAtom {
-    uint32_t dim, div, ext, stride;
-    FastDiv by_div, by_ext, by_stride;
-};
-struct FastLayout {
-    int32_t n, pad_;
-    FastAtom a[ALT_MAX_RANK];
-};
 struct SpreadFastParams {
     const void *src;
     void *dst;
@@ -76,8 +69,6 @@ struct SpreadFastParams {
     FastDiv by_sh, by_sw;
     uint32_t nvec, pad_;
 };
-
-__device__ __forceinline__ uint32_t fast_mod(uint32_t n, const FastDiv &f) { return n - fast_div(n, f) * f.d; }
 
 template <int ELSZ, int VEC>
 __global__ __launch_bounds__(kT2dThreads) void t2d_spread_fast_kernel(SpreadFastParams p)
@@ -105,21 +96,6 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_spread_fast_kernel(SpreadFast
         }
         *(V *)((char *)p.dst + (size_t)o * ELSZ) = w;
     }
-}
-
-bool fast_layout(const BoundLayout &b, FastLayout *out)
-{
-    if (!b.separable || b.ndim != 4 || b.numel >= ((int64_t)1 << 31) || b.nsub > ALT_MAX_RANK) return false;
-    out->n = b.nsub;
-    out->pad_ = 0;
-    for (int j = 0; j < b.nsub; ++j) {
-        const Atom &a = b.atom[j];
-        if (a.div >= ((int64_t)1 << 31) || a.ext >= ((int64_t)1 << 31) || a.stride >= ((int64_t)1 << 31) || a.stride < 1) return false;
-        FastAtom &f = out->a[j];
-        f.dim = (uint32_t)a.dim; f.div = (uint32_t)a.div; f.ext = (uint32_t)a.ext; f.stride = (uint32_t)a.stride;
-        f.by_div = make_fastdiv(f.div); f.by_ext = make_fastdiv(f.ext); f.by_stride = make_fastdiv(f.stride);
-    }
-    return true;
 }
 
 // Elements per thread: eight (16 bytes of bf16) or four (of fp32) when both layouts end in

@@ -221,12 +221,39 @@ def test_calls_without_gpu_fail_loudly_not_silently():
                  lambda: h.conv2d_transpose(alt.conv_desc(1, 16, 8, 8, 16, 3, 3, stride=2, pad=1), 16, 16, 16, workspace=16,
                                             ws_bytes=1 << 20, stream=0),
                  lambda: h.pack_weights_transpose(d, 16, 16, stream=0),
+                 lambda: h.conv3d(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1), 16, 16, 16, workspace=16, ws_bytes=1 << 20,
+                                  stream=0),
+                 lambda: h.conv3d(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 1, 3, 3, pad=(0, 1, 1)), 16, 16, 16, stream=0),
+                 lambda: h.pack_weights3d(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1), 16, 16, stream=0),
                  lambda: h.tune_conv2d_multi([dict(d=nhwc, x=16, w=16, y=16, stream=0)]),
                  lambda: h.eltwise_add(alt.BF16, 64, 16, 16, 16, stream=0),
                  lambda: h.unfold(alt.BF16, (4, 8), 0, 2, 1, 16, 4096, stream=0)):
         with pytest.raises(alt.AltError) as e:
             call()
         assert e.value.status == 6
+
+
+def test_conv3d_host_side(oracle):
+    """Output shape of the 3-D convolution against the shape of the oracle's result, and the argument
+    checks that need no device."""
+    h = alt.Handle()
+    for (D, H, W, T, R, S, stride, pad, dil) in [(7, 9, 8, 3, 3, 3, 1, 1, 1), (6, 7, 5, 3, 2, 3, (2, 1, 1), (1, 0, 2), (1, 1, 1)),
+                                                 (9, 8, 7, 2, 3, 3, (1, 2, 1), (2, 1, 0), (3, 1, 2))]:
+        d = alt.conv3d_desc(2, 4, D, H, W, 8, T, R, S, stride=stride, pad=pad, dil=dil)
+        ref = oracle.conv3d(np.zeros((2, 4, D, H, W), np.float32), np.zeros((8, 4, T, R, S), np.float32), stride=stride, pad=pad, dil=dil)
+        assert h.conv3d_output_shape(d) == ref.shape
+    with pytest.raises(alt.AltError) as e:
+        h.conv3d_workspace_size(alt.conv3d_desc(1, 16, 3, 8, 8, 16, 5, 3, 3, pad=(0, 1, 1)))   # filter deeper than the input
+    assert e.value.status == 1
+    with pytest.raises(alt.AltError) as e:
+        h.conv3d_workspace_size(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1, groups=2))
+    assert e.value.status == 4
+    with pytest.raises(alt.AltError) as e:
+        h.conv3d_workspace_size(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, stride=(0, 1, 1), pad=1))
+    assert e.value.status == 1
+    # the unfolded input is counted: T*C channels for every output slice
+    d = alt.conv3d_desc(2, 16, 6, 8, 8, 16, 3, 3, 3, stride=(2, 1, 1), pad=1, in_dtype=alt.BF16)
+    assert h.conv3d_workspace_size(d) >= 2 * 3 * (3 * 16) * 8 * 8 * 2
 
 
 def test_conv_transpose_host_side(oracle):

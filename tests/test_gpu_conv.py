@@ -613,6 +613,122 @@ def test_conv3d_by_unfolding_the_depth(h, stride, pad):
     assert np.array_equal(got, ref)
 
 
+def run_conv3d(h, x, w, stride, pad, dil, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False, variant=-1,
+               ws_slack=0):
+    """x (N,C,D,H,W), w (K,C,T,R,S): float32 or uint16 bf16 bits, logical.  Puts x under `xl` slice by
+    slice with the oracle's conversion, packs w with the library, returns the logical (N,K,OD,OH,OW) result."""
+    N, C, D, H, W = x.shape
+    K, _, T, R, S = w.shape
+    epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
+    d = alt.conv3d_desc(N, C, D, H, W, K, T, R, S, stride=stride, pad=pad, dil=dil, in_dtype=in_dtype, out_dtype=out_dtype,
+                        epilogue=epi, variant=variant, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+    oshape = h.conv3d_output_shape(d)
+    _, _, OD, OH, OW = oshape
+    xs = np.ascontiguousarray(x.transpose(0, 2, 1, 3, 4)).reshape(N * D, C, H, W)
+    xd = dev(to_layout(xs, "NCHW", xl))
+    wd = torch.empty_like(dev(w.reshape(-1)))
+    h.pack_weights3d(d, dev(w.reshape(-1)), wd)
+    # the packed filter is the one the header states, under w_layout
+    w2 = np.ascontiguousarray(w.transpose(0, 2, 1, 3, 4)).reshape(K, T * C, R, S)
+    assert np.array_equal(host(wd, w.dtype), to_layout(w2, "OIHW", wl).reshape(-1))
+    ydt = np.float32 if out_dtype == alt.F32 else np.uint16
+    n_out = int(np.prod(oshape))
+    whole, yd = canary_dev(n_out, ydt)
+    need = h.conv3d_workspace_size(d)
+    ws_bytes = need + 36 * n_out * 4 + ws_slack
+    ws = torch.empty(ws_bytes // 4 + 4, dtype=torch.float32, device="cuda")
+    bd = dev(bias) if bias is not None else None
+    h.conv3d(d, xd, wd, yd, bias=bd, workspace=ws, ws_bytes=ws_bytes)
+    got = host(yd, ydt)
+    assert canary_ok(whole, n_out), "wrote outside y"
+    got = from_layout(got, (N * OD, K, OH, OW), "NCHW", yl).reshape(N, OD, K, OH, OW).transpose(0, 2, 1, 3, 4)
+    return got, d
+
+
+CONV3D_GEOMETRY = [(1, 1, 1), (2, 1, 1), (1, 0, 1), ((2, 1, 1), (1, 0, 1), (1, 1, 1)), ((1, 2, 2), (2, 1, 1), (2, 1, 1)),
+                   ((3, 1, 1), (0, 1, 1), (1, 1, 1))]
+
+
+@pytest.mark.parametrize("layouts", [("NHWC", "OHWI", "NHWC"), ("NCHW", "OIHW", "NCHW"), ("NCHW16c", "OIHW16o16i", "NCHW16c"),
+                                     ("NHWC", "OIHW16i16o", "NCHW"), ("NCHW8c", "OHWI", "NHWC")])
+@pytest.mark.parametrize("geometry", CONV3D_GEOMETRY, ids=lambda g: "s%s_p%s_d%s" % g)
+def test_conv3d_exact_integers(h, layouts, geometry):
+    """alt_conv3d (the C3D of Section 6.1): bf16 integers, every sum exact, so the result is the
+    oracle's 3-D definition bit for bit: per-direction strides, padding (zero slices before and
+    behind the depth) and dilation, depth-slice layouts with the channels innermost, outermost
+    and blocked, fp32 and bf16 output with bias and ReLU."""
+    stride, pad, dil = geometry
+    xl, wl, yl = layouts
+    N, C, D, H, W, K, T, R, S = 2, 16, 7, 9, 8, 32, 3, 3, 3
+    x = small_ints_f32(911, (N, C, D, H, W), -3, 3)
+    w = small_ints_f32(912, (K, C, T, R, S), -3, 3)
+    b = small_ints_f32(913, (K,), -20, 20)
+    ref = oracle.conv3d(x, w, stride=stride, pad=pad, dil=dil)
+    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    got, d = run_conv3d(h, xb, wb, stride, pad, dil, xl, wl, yl, alt.BF16)
+    assert got.shape == ref.shape
+    assert np.array_equal(got, ref)
+    got, _ = run_conv3d(h, xb, wb, stride, pad, dil, xl, wl, yl, alt.BF16, out_dtype=alt.BF16, bias=b, relu=True)
+    ref_br = np.maximum(ref + b[None, :, None, None, None], np.float32(0))
+    assert np.array_equal(got, f32_to_bf16_bits(ref_br))
+    # every kernel variant of the equivalent 2-D problem
+    f = alt.conv_desc(N * ref.shape[2], T * C, H, W, K, R, S, in_dtype=alt.BF16, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
+                      y_layout="NCHW->" + yl)
+    f.stride_h, f.stride_w, f.pad_h, f.pad_w, f.dil_h, f.dil_w = (d.plane.stride_h, d.plane.stride_w, d.plane.pad_h,
+                                                                   d.plane.pad_w, d.plane.dil_h, d.plane.dil_w)
+    variants = applicable_variants(h, f)
+    assert variants
+    for v, name in variants[::3]:
+        got, _ = run_conv3d(h, xb, wb, stride, pad, dil, xl, wl, yl, alt.BF16, variant=v)
+        assert np.array_equal(got, ref), name
+
+
+def test_conv3d_fp32_and_gaussian_inputs_within_tolerance(h):
+    """Gaussian operands: fp32 within 1e-5, bf16 within 2e-2 of the oracle's float64 sums (a ResNet3D-shaped
+    3x3x3 layer at reduced size; 64 channels, so the direct kernel's 192-channel patch is among the candidates)."""
+    N, C, D, H, W, K, T = 2, 64, 6, 14, 12, 64, 3
+    x = normal_f32(921, (N, C, D, H, W))
+    w = normal_f32(922, (K, C, T, 3, 3), 0.05)
+    ref = oracle.conv3d(x, w, stride=1, pad=1)
+    got, _ = run_conv3d(h, x, w, 1, 1, 1, "NHWC", "OHWI", "NHWC", alt.F32)
+    assert rel_err(got, ref) <= TOL[alt.F32]
+    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    refb = oracle.conv3d(xb, wb, stride=1, pad=1)
+    for xl, wl, yl in [("NHWC", "OHWI", "NHWC"), ("NCHW32c", "OIHW32o32i", "NCHW32c")]:
+        got, _ = run_conv3d(h, xb, wb, 1, 1, 1, xl, wl, yl, alt.BF16)
+        assert rel_err(got, refb) <= TOL[alt.BF16], (xl, rel_err(got, refb))
+
+
+def test_conv3d_one_tap_is_the_2d_call_and_errors(h):
+    """T = 1, stride_d = 1, pad_d = 0 needs no workspace (the 2-D kernels run on x itself); a workspace
+    below the unfolded input, groups and a filter deeper than the padded input are refused."""
+    N, C, D, H, W, K = 2, 16, 3, 6, 5, 16
+    x = small_ints_f32(931, (N, C, D, H, W), -3, 3)
+    w1 = small_ints_f32(932, (K, C, 1, 3, 3), -3, 3)
+    d1 = alt.conv3d_desc(N, C, D, H, W, K, 1, 3, 3, stride=1, pad=(0, 1, 1), in_dtype=alt.F32)
+    assert h.conv3d_workspace_size(d1) == h.conv2d_workspace_size(alt.conv_desc(N * D, C, H, W, K, 3, 3, pad=1, in_dtype=alt.F32))
+    xs = np.ascontiguousarray(x.transpose(0, 2, 1, 3, 4))
+    yd = torch.empty(N * D * K * H * W, dtype=torch.float32, device="cuda")
+    h.conv3d(d1, dev(xs.reshape(-1)), dev(w1.reshape(-1)), yd)
+    got = host(yd, np.float32).reshape(N, D, K, H, W).transpose(0, 2, 1, 3, 4)
+    assert np.array_equal(got, oracle.conv3d(x, w1, stride=1, pad=(0, 1, 1)))
+    d3 = alt.conv3d_desc(N, C, D, H, W, K, 3, 3, 3, stride=1, pad=1, in_dtype=alt.F32)
+    need = h.conv3d_workspace_size(d3)
+    assert need >= N * D * 3 * C * H * W * 4
+    ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
+    w3 = dev(small_ints_f32(933, (K, C, 3, 3, 3), -3, 3).reshape(-1))
+    with pytest.raises(alt.AltError, match="workspace"):
+        h.conv3d(d3, dev(xs.reshape(-1)), w3, yd, workspace=ws, ws_bytes=1024)
+    with pytest.raises(alt.AltError, match="workspace"):
+        h.conv3d(d3, dev(xs.reshape(-1)), w3, yd)
+    dg = alt.conv3d_desc(N, C, D, H, W, K, 3, 3, 3, stride=1, pad=1, in_dtype=alt.F32, groups=2)
+    with pytest.raises(alt.AltError, match="groups"):
+        h.conv3d(dg, dev(xs.reshape(-1)), w3, yd, workspace=ws, ws_bytes=need)
+    dd = alt.conv3d_desc(N, C, D, H, W, K, 5, 3, 3, stride=1, pad=(0, 1, 1), in_dtype=alt.F32)
+    with pytest.raises(alt.AltError):
+        h.conv3d_workspace_size(dd)
+
+
 @pytest.mark.parametrize("out_dtype", [alt.F32, alt.BF16])
 def test_conv2d_add_fused_sum_exact_integers(h, out_dtype):
     """alt_conv2d_add: y = relu(conv + bias + addend) in one launch, every tile-kernel variant

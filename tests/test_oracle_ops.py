@@ -411,6 +411,20 @@ def test_conv_transpose_stride1_is_conv_with_flipped_filter(oracle):
     assert np.array_equal(y[0, 0], exp)
 
 
+@pytest.mark.parametrize("stride,pad,dil", [((2, 1, 1), (1, 0, 2), (1, 1, 1)), ((1, 2, 1), (2, 1, 0), (2, 1, 2)),
+                                            ((1, 1, 2), (0, 2, 1), (1, 3, 1))])
+def test_conv3d_with_different_stride_padding_dilation_per_direction(oracle, stride, pad, dil):
+    """Each direction takes its own stride, padding and dilation: against torch's conv3d in float64
+    (values that differ per direction, so an exchanged pair of directions shows)."""
+    x = normal_f32(111, (2, 3, 7, 8, 9))
+    w = normal_f32(112, (4, 3, 3, 2, 3))
+    got = oracle.conv3d(x, w, stride=stride, pad=pad, dil=dil)
+    ref = torch.nn.functional.conv3d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), stride=stride,
+                                     padding=pad, dilation=dil).numpy()
+    assert got.shape == ref.shape
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+
+
 @pytest.mark.parametrize("stride,pad", [(1, 0), (1, 1), (2, 1), (2, 0)])
 def test_conv3d_vs_library_routine_and_2d_special_case(oracle, stride, pad):
     """Against torch's conv3d in float64; with a depth of one tap and one slice it is the C2D."""
