@@ -300,6 +300,27 @@ alt_status_t alt_conv3d_output_shape(const alt_conv3d_desc_t *d, int64_t *out_nk
 alt_status_t alt_pack_weights3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_kctrs,
                                 void *w_packed, void *stream);
 
+/* Transposed 3-D convolution (T3D in the operator list of Section 6.1), the adjoint of the C3D
+ * that maps K channels to C with the same filter:
+ *   y[n,k, id*stride_d-pad_d+t*dil_d, ih*stride_h-pad_h+r*dil_h, iw*stride_w-pad_w+s*dil_w] += x[n,c,id,ih,iw] * w[c,k,t,r,s],
+ *   OD = (D-1)*stride_d - 2*pad_d + dil_d*(T-1) + 1 (likewise OH, OW); needs pad <= dil*(taps-1) in
+ *   each direction, groups = 1.
+ * The descriptor reads as for alt_conv3d with N, C, D, H, W describing x, K the output channels and
+ * the strides, padding and dilation those of the transposed operator; tensors are stacks of depth
+ * slices as there.  It runs as the forward operator at stride 1 and padding dil*(taps-1)-pad over x
+ * with stride-1 zeros between its elements in all three directions, with the mirrored,
+ * channel-swapped filter: the depth-unfolding kernel of alt_conv3d reads x where all three
+ * indices are multiples of the strides and writes zeros elsewhere (one pass, into the workspace),
+ * alt_pack_weights3d_transpose writes w'[k, t*C + c, r, s] = w[c, k, T-1-t, R-1-r, S-1-s], logical
+ * (K, T*C, R, S) under plane.w_layout, once from the dense (C,K,T,R,S) filter, and alt_conv2d's
+ * kernels do the rest.  Workspace and errors as for alt_conv3d.  Asynchronous on `stream`. */
+alt_status_t alt_conv3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
+                                  const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
+alt_status_t alt_conv3d_transpose_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes);
+alt_status_t alt_conv3d_transpose_output_shape(const alt_conv3d_desc_t *d, int64_t *out_nkdhw);
+alt_status_t alt_pack_weights3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_cktrs,
+                                          void *w_packed, void *stream);
+
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and
  * operand loader).  Variant numbers are stable within one library build. */

@@ -429,6 +429,40 @@ def conv3d(x, w, stride=1, pad=0, dil=1):
     return y.astype(np.float32)
 
 
+def conv3d_transpose(x, w, stride=1, pad=0, dil=1):
+    """Transposed 3-D convolution (the T3D of Section 6.1's operator list): the adjoint of the
+    C3D that maps K channels to C with the same filter, written out as a scatter:
+
+        y[n, k, id*sd - pd + t*dd, ih*sh - ph + r*dh, iw*sw - pw + s*dw] += x[n, c, id, ih, iw] * w[c, k, t, r, s]
+
+    over all terms whose target lies inside the output of extents (D-1)*sd - 2*pd + dd*(T-1) + 1
+    (likewise for the other two).  x: (N,C,D,H,W), w: (C,K,T,R,S), float32 or uint16 bf16 bits;
+    stride, pad, dil: one number or (depth, height, width); sums in float64, one rounding to
+    float32.  Pure numpy: one channel contraction per filter tap, added into a strided view of
+    the uncropped output."""
+    x = np.asarray(x)
+    w = np.asarray(w)
+    xf = bf16_bits_to_f64(x) if x.dtype == np.uint16 else x.astype(np.float64)
+    wf = bf16_bits_to_f64(w) if w.dtype == np.uint16 else w.astype(np.float64)
+    N, C, D, H, W = xf.shape
+    C2, K, T, R, S = wf.shape
+    if C2 != C:
+        raise ValueError("conv3d_transpose: w is (C, K, T, R, S)")
+    three = lambda v: tuple(int(e) for e in v) if isinstance(v, (tuple, list)) else (int(v),) * 3
+    (sd, sh, sw), (pd, ph, pw), (dd, dh, dw) = three(stride), three(pad), three(dil)
+    FD, FH, FW = (D - 1) * sd + dd * (T - 1) + 1, (H - 1) * sh + dh * (R - 1) + 1, (W - 1) * sw + dw * (S - 1) + 1
+    OD, OH, OW = FD - 2 * pd, FH - 2 * ph, FW - 2 * pw
+    if min(OD, OH, OW) < 1:
+        raise ValueError("conv3d_transpose: empty output")
+    full = np.zeros((N, K, FD, FH, FW), dtype=np.float64)
+    for t in range(T):
+        for r in range(R):
+            for s_ in range(S):
+                full[:, :, t * dd:t * dd + (D - 1) * sd + 1:sd, r * dh:r * dh + (H - 1) * sh + 1:sh,
+                     s_ * dw:s_ * dw + (W - 1) * sw + 1:sw] += np.einsum("ncdhw,ck->nkdhw", xf, wf[:, :, t, r, s_])
+    return full[:, :, pd:pd + OD, ph:ph + OH, pw:pw + OW].astype(np.float32)
+
+
 def conv_out_shape(x_shape, w_shape, stride=1, pad=0, dil=1):
     d = _Conv(*x_shape, w_shape[0], w_shape[2], w_shape[3], stride, stride, pad, pad, dil, dil,
               0, 0, 0, 0)

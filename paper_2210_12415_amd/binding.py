@@ -153,7 +153,9 @@ def exported_symbols():
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
             "alt_conv2d", "alt_conv2d_add", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
             "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose",
-            "alt_conv3d", "alt_conv3d_workspace_size", "alt_conv3d_output_shape", "alt_pack_weights3d", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_conv3d", "alt_conv3d_workspace_size", "alt_conv3d_output_shape", "alt_pack_weights3d",
+            "alt_conv3d_transpose", "alt_conv3d_transpose_workspace_size", "alt_conv3d_transpose_output_shape",
+            "alt_pack_weights3d_transpose", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
@@ -429,6 +431,24 @@ class Handle:
     def pack_weights3d(self, d, w_kctrs, w_packed, stream=None):
         _ck(lib().alt_pack_weights3d(self._h, ctypes.byref(d), _ptr(w_kctrs), _ptr(w_packed),
                                      _stream(stream)), self._h)
+
+    def conv3d_transpose(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
+        _ck(lib().alt_conv3d_transpose(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
+                                       _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv3d_transpose_workspace_size(self, d):
+        n = ctypes.c_size_t()
+        _ck(lib().alt_conv3d_transpose_workspace_size(self._h, ctypes.byref(d), ctypes.byref(n)), self._h)
+        return n.value
+
+    def conv3d_transpose_output_shape(self, d):
+        out = (ctypes.c_int64 * 5)()
+        _ck(lib().alt_conv3d_transpose_output_shape(ctypes.byref(d), out))
+        return tuple(out)
+
+    def pack_weights3d_transpose(self, d, w_cktrs, w_packed, stream=None):
+        _ck(lib().alt_pack_weights3d_transpose(self._h, ctypes.byref(d), _ptr(w_cktrs), _ptr(w_packed),
+                                               _stream(stream)), self._h)
 
     def pack_weights(self, d, w_oihw, w_packed, stream=None):
         _ck(lib().alt_pack_weights(self._h, ctypes.byref(d), _ptr(w_oihw), _ptr(w_packed),

@@ -8,6 +8,12 @@
 //   w'[k,(t,c),r,s]      = w[k,c,t,r,s].
 // One kernel writes x' under the activation layout into the workspace per call, one writes
 // w' once, offline (a weight tensor is a constant, Section 4.2); alt_conv2d does the work.
+//
+// The transposed 3-D convolution (T3D of the same list) is the forward one at stride 1 over x
+// with stride-1 zeros between its elements in all three directions, with the filter mirrored,
+// its channel dimensions exchanged and padding dil*(T-1)-pad: the same two kernels, the
+// first reading x[.., d/stride_d, h/stride_h, w/stride_w] where all three divide and zero
+// elsewhere, the second reading the filter back to front.
 #include <hip/hip_runtime.h>
 
 #include <string>
@@ -30,9 +36,10 @@ template <> struct Word<16> { using type = uint4; };
 struct GatherParams {
     const void *src;
     void *dst;
-    BoundLayout ls, ld;           // x over (N*D, C, H, W); x' over (N*OD, T*C, H, W)
+    BoundLayout ls, ld;           // x over (N*D, C, H, W); x' over (N*OD, T*C, He, We)
     int64_t D, OD, C;
-    int32_t sd, pd, dd, pad_;
+    int32_t sd, pd, dd;           // depth stride, padding, dilation of the forward problem
+    int32_t zd, zh, zw;           // x sits at every zd-th slice, zh-th row, zw-th column of the tensor convolved (1: x itself)
 };
 
 // One thread per element of x', any pair of layouts.
@@ -48,11 +55,13 @@ __global__ __launch_bounds__(kC3dThreads) void c3d_gather_kernel(GatherParams p)
         const int64_t out = eval_offset(p.ld, idx);
         const int64_t img = idx[0] / p.OD, od = idx[0] - img * p.OD;
         const int64_t t = idx[1] / p.C, c = idx[1] - t * p.C;
-        const int64_t d = od * p.sd - p.pd + t * p.dd;
+        const int64_t de = od * p.sd - p.pd + t * p.dd;
         E v = 0;
-        if (d >= 0 && d < p.D) {
-            idx[0] = img * p.D + d;
+        if (de >= 0 && de % p.zd == 0 && de / p.zd < p.D && idx[2] % p.zh == 0 && idx[3] % p.zw == 0) {
+            idx[0] = img * p.D + de / p.zd;
             idx[1] = c;
+            idx[2] /= p.zh;
+            idx[3] /= p.zw;
             v = ((const E *)p.src)[eval_offset(p.ls, idx)];
         }
         ((E *)p.dst)[out] = v;
@@ -63,7 +72,7 @@ struct GatherFastParams {
     const void *src;
     void *dst;
     FastLayout ls, ld;
-    FastDiv by_od, by_c;
+    FastDiv by_od, by_c, by_zd, by_zh, by_zw;
     uint32_t D, nvec;
     int32_t sd, pd, dd, pad_;
 };
@@ -86,12 +95,15 @@ __global__ __launch_bounds__(kC3dThreads) void c3d_gather_fast_kernel(GatherFast
         }
         const uint32_t img = fast_div(idx[0], p.by_od), od = idx[0] - img * p.by_od.d;
         const uint32_t t = fast_div(idx[1], p.by_c), c = idx[1] - t * p.by_c.d;
-        const int32_t d = (int32_t)od * p.sd - p.pd + (int32_t)t * p.dd;
+        const int32_t de = (int32_t)od * p.sd - p.pd + (int32_t)t * p.dd;
+        const uint32_t d = fast_div((uint32_t)de, p.by_zd), qh = fast_div(idx[2], p.by_zh), qw = fast_div(idx[3], p.by_zw);
         V w;
         __builtin_memset(&w, 0, sizeof w);
-        if ((uint32_t)d < p.D) {
-            idx[0] = img * p.D + (uint32_t)d;
+        if (de >= 0 && d * p.by_zd.d == (uint32_t)de && d < p.D && qh * p.by_zh.d == idx[2] && qw * p.by_zw.d == idx[3]) {
+            idx[0] = img * p.D + d;
             idx[1] = c;
+            idx[2] = qh;
+            idx[3] = qw;
             uint32_t so = 0;
             for (int j = 0; j < p.ls.n; ++j) {
                 const FastAtom &a = p.ls.a[j];
@@ -107,24 +119,27 @@ __global__ __launch_bounds__(kC3dThreads) void c3d_gather_fast_kernel(GatherFast
 // logical dimension (channels or width), whole in that dimension's innermost piece, with
 // extents (and, for channels, C itself: a run may not cross from one depth tap to the next)
 // that are multiples of it; else one.
-int gather_vec(const BoundLayout &ls, const BoundLayout &ld, int elsz, int64_t C, const void *src, const void *dst)
+int gather_vec(const BoundLayout &ls, const BoundLayout &ld, int elsz, int64_t C, int zw, const void *src, const void *dst)
 {
     const int want = 16 / elsz;
     const Atom *is = unit_stride_atom(ls), *id = unit_stride_atom(ld);
     if (!is || !id || is->dim != id->dim || (is->dim != 1 && is->dim != 3) || is->div != 1 || id->div != 1) return 1;
+    if (is->dim == 3 && zw != 1) return 1;                 // zeros between the elements of a row: no common run
     if (is->ext % want || id->ext % want || (is->dim == 1 && C % want)) return 1;
     if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return 1;
     return want;
 }
 
 struct PackParams {
-    const void *src;              // dense (K, C, T, R, S)
+    const void *src;              // dense (K, C, T, R, S); (C, K, T, R, S) for the transposed operator
     void *dst;
     BoundLayout ld;               // w' over (K, T*C, R, S) under w_layout
     int64_t C, T;
+    int32_t mirrored, pad_;
 };
 
-// w'[k, t*C + c, r, s] = w[k, c, t, r, s], one thread per element.
+// w'[k, t*C + c, r, s] = w[k, c, t, r, s], or w[c, k, T-1-t, R-1-r, S-1-s] for the transposed operator;
+// one thread per element.
 template <int ELSZ>
 __global__ __launch_bounds__(kC3dThreads) void c3d_pack_kernel(PackParams p)
 {
@@ -136,7 +151,9 @@ __global__ __launch_bounds__(kC3dThreads) void c3d_pack_kernel(PackParams p)
         int64_t r = e;
         for (int d = 3; d >= 0; --d) { idx[d] = r % p.ld.shape[d]; r /= p.ld.shape[d]; }
         const int64_t t = idx[1] / p.C, c = idx[1] - t * p.C;
-        const int64_t src = (((idx[0] * p.C + c) * p.T + t) * R + idx[2]) * S + idx[3];
+        const int64_t K = p.ld.shape[0];
+        const int64_t src = p.mirrored ? ((((c * K + idx[0]) * p.T + (p.T - 1 - t)) * R + (R - 1 - idx[2])) * S + (S - 1 - idx[3]))
+                                       : ((((idx[0] * p.C + c) * p.T + t) * R + idx[2]) * S + idx[3]);
         ((E *)p.dst)[eval_offset(p.ld, idx)] = ((const E *)p.src)[src];
     }
 }
@@ -155,20 +172,168 @@ int64_t out_depth(const alt_conv3d_desc_t *d)
     return span < 0 ? 0 : span / d->stride_d + 1;
 }
 
-// The equivalent 2-D problem of a 3-D descriptor; *gather says whether x' differs from x.
-alt_status_t plane_desc(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *f, bool *gather)
+// What the two kernels and alt_conv2d need to know of a 3-D problem.
+struct Problem3d {
+    alt_conv_desc_t f;            // the 2-D problem: batch N*OD, T*C channels
+    int64_t xs[4];                // x as a stack of slices: (N*D, C, H, W)
+    int64_t D, OD, C;
+    int32_t sd, pd, dd;           // depth stride, padding, dilation of the forward problem
+    int32_t zd, zh, zw;           // zero-insertion strides (1 for the forward operator)
+    bool gather;                  // false: the 2-D problem reads x itself
+};
+
+// The forward operator.
+alt_status_t forward_problem(alt_handle_t h, const alt_conv3d_desc_t *d, Problem3d *out)
 {
     const alt_conv_desc_t &q = d->plane;
-    if (q.N < 1 || q.C < 1 || d->D < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: extents must be positive");
+    if (q.N < 1 || q.C < 1 || q.H < 1 || q.W < 1 || d->D < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: extents must be positive");
     if (d->stride_d < 1 || d->dil_d < 1 || d->pad_d < 0) return fail(h, ALT_INVALID_ARG, "alt_conv3d: bad depth stride, padding or dilation");
     if (q.groups > 1) return fail(h, ALT_UNSUPPORTED, "alt_conv3d: groups are not supported");
     const int64_t OD = out_depth(d);
     if (OD < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: the filter is deeper than the padded input");
-    *f = q;
-    f->N = q.N * OD;
-    f->C = q.C * d->T;
-    *gather = !(d->T == 1 && d->stride_d == 1 && d->pad_d == 0);
+    Problem3d &p = *out;
+    p.f = q;
+    p.f.N = q.N * OD;
+    p.f.C = q.C * d->T;
+    p.xs[0] = q.N * d->D; p.xs[1] = q.C; p.xs[2] = q.H; p.xs[3] = q.W;
+    p.D = d->D; p.OD = OD; p.C = q.C;
+    p.sd = d->stride_d; p.pd = d->pad_d; p.dd = d->dil_d;
+    p.zd = p.zh = p.zw = 1;
+    p.gather = !(d->T == 1 && d->stride_d == 1 && d->pad_d == 0);
     return ALT_OK;
+}
+
+int64_t transposed_extent(int64_t in, int stride, int pad, int dil, int64_t taps)
+{
+    return (in - 1) * stride - 2 * (int64_t)pad + (int64_t)dil * (taps - 1) + 1;
+}
+
+// The transposed operator as the forward one over the zero-inserted input.
+alt_status_t transposed_problem(alt_handle_t h, const alt_conv3d_desc_t *d, Problem3d *out)
+{
+    const alt_conv_desc_t &q = d->plane;
+    if (q.N < 1 || q.C < 1 || q.H < 1 || q.W < 1 || q.K < 1 || q.R < 1 || q.S < 1 || d->D < 1 || d->T < 1)
+        return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: extents must be positive");
+    if (d->stride_d < 1 || q.stride_h < 1 || q.stride_w < 1 || d->dil_d < 1 || q.dil_h < 1 || q.dil_w < 1 || d->pad_d < 0 ||
+        q.pad_h < 0 || q.pad_w < 0)
+        return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: bad stride, padding or dilation");
+    if (q.groups > 1) return fail(h, ALT_UNSUPPORTED, "alt_conv3d_transpose: groups are not supported");
+    if (d->pad_d > d->dil_d * (d->T - 1) || q.pad_h > q.dil_h * (q.R - 1) || q.pad_w > q.dil_w * (q.S - 1))
+        return fail(h, ALT_UNSUPPORTED, "alt_conv3d_transpose: padding beyond dil*(taps-1) is not supported");
+    Problem3d &p = *out;
+    p.OD = transposed_extent(d->D, d->stride_d, d->pad_d, d->dil_d, d->T);
+    if (p.OD < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: empty output");
+    p.f = q;
+    p.f.N = q.N * p.OD;
+    p.f.C = q.C * d->T;
+    p.f.H = (q.H - 1) * q.stride_h + 1;
+    p.f.W = (q.W - 1) * q.stride_w + 1;
+    p.f.stride_h = p.f.stride_w = 1;
+    p.f.pad_h = q.dil_h * (int32_t)(q.R - 1) - q.pad_h;
+    p.f.pad_w = q.dil_w * (int32_t)(q.S - 1) - q.pad_w;
+    p.xs[0] = q.N * d->D; p.xs[1] = q.C; p.xs[2] = q.H; p.xs[3] = q.W;
+    p.D = d->D; p.C = q.C;
+    p.sd = 1; p.pd = d->dil_d * (int32_t)(d->T - 1) - d->pad_d; p.dd = d->dil_d;
+    p.zd = d->stride_d; p.zh = q.stride_h; p.zw = q.stride_w;
+    p.gather = !(d->T == 1 && d->stride_d == 1 && d->pad_d == 0 && q.stride_h == 1 && q.stride_w == 1);
+    return ALT_OK;
+}
+
+size_t gathered_bytes(const Problem3d &p)
+{
+    return round256((size_t)(p.f.N * p.f.C * p.f.H * p.f.W) * dtype_size(p.f.in_dtype));
+}
+
+alt_status_t workspace_size(alt_handle_t h, const Problem3d &p, size_t *bytes)
+{
+    size_t conv_ws = 0;
+    const alt_status_t s = alt_conv2d_workspace_size(h, &p.f, &conv_ws);
+    if (s != ALT_OK) return s;
+    *bytes = (p.gather ? gathered_bytes(p) : 0) + conv_ws;
+    return ALT_OK;
+}
+
+alt_status_t pack3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w, void *w_packed, void *stream, bool mirrored,
+                    const char *who)
+{
+    if (!d || !w || !w_packed) return fail(h, ALT_INVALID_ARG, "%s: null argument", who);
+    const alt_conv_desc_t &q = d->plane;
+    if (q.in_dtype != ALT_F32 && q.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "%s: bad dtype", who);
+    if (q.K < 1 || q.C < 1 || q.R < 1 || q.S < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "%s: extents must be positive", who);
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const int64_t wsh[4] = {q.K, q.C * d->T, q.R, q.S};
+    PackParams p;
+    std::string err;
+    const alt_status_t s = bind_layout(&q.w_layout, 4, wsh, &p.ld, &err);
+    if (s != ALT_OK) return fail(h, s, "w_layout: %s", err.c_str());
+    p.src = w;
+    p.dst = w_packed;
+    p.C = q.C;
+    p.T = d->T;
+    p.mirrored = mirrored ? 1 : 0;
+    p.pad_ = 0;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype_size(q.in_dtype) == 2) hipLaunchKernelGGL(c3d_pack_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
+    else hipLaunchKernelGGL(c3d_pack_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+alt_status_t run3d(alt_handle_t h, const Problem3d &pr, const void *x, const void *w_packed, const float *bias, void *y,
+                   void *workspace, size_t ws_bytes, void *stream, const char *who)
+{
+    if (!pr.gather) return alt_conv2d(h, &pr.f, x, w_packed, bias, y, workspace, ws_bytes, stream);
+
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const alt_conv_desc_t &f = pr.f;
+    const int elsz = (int)dtype_size(f.in_dtype);
+    const size_t xu_bytes = gathered_bytes(pr);
+    if (!workspace || ws_bytes < xu_bytes)
+        return fail(h, ALT_WORKSPACE_TOO_SMALL, "%s: the workspace must hold the depth-unfolded input (%zu bytes)", who, xu_bytes);
+    if ((uintptr_t)workspace % 16) return fail(h, ALT_INVALID_ARG, "%s: workspace must be 16-byte aligned", who);
+    GatherParams p;
+    const int64_t us[4] = {f.N, f.C, f.H, f.W};
+    std::string err;
+    alt_status_t s;
+    if ((s = bind_layout(&f.x_layout, 4, pr.xs, &p.ls, &err)) != ALT_OK) return fail(h, s, "x_layout: %s", err.c_str());
+    if ((s = bind_layout(&f.x_layout, 4, us, &p.ld, &err)) != ALT_OK) return fail(h, s, "x_layout (depth-unfolded input): %s", err.c_str());
+    p.src = x;
+    p.dst = workspace;
+    p.D = pr.D; p.OD = pr.OD; p.C = pr.C;
+    p.sd = pr.sd; p.pd = pr.pd; p.dd = pr.dd;
+    p.zd = pr.zd; p.zh = pr.zh; p.zw = pr.zw;
+    hipStream_t st = (hipStream_t)stream;
+    GatherFastParams g;
+    const int64_t T = f.C / pr.C;
+    const bool small = pr.D < ((int64_t)1 << 20) && pr.OD < ((int64_t)1 << 20) && T < ((int64_t)1 << 10) &&
+                       (int64_t)pr.sd * pr.OD + (int64_t)pr.dd * T + pr.pd < ((int64_t)1 << 30);
+    if (small && fast_layout(p.ls, &g.ls) && fast_layout(p.ld, &g.ld)) {
+        const int vec = gather_vec(p.ls, p.ld, elsz, pr.C, pr.zw, x, workspace);
+        g.src = x;
+        g.dst = workspace;
+        g.by_od = make_fastdiv((uint32_t)pr.OD);
+        g.by_c = make_fastdiv((uint32_t)pr.C);
+        g.by_zd = make_fastdiv((uint32_t)pr.zd);
+        g.by_zh = make_fastdiv((uint32_t)pr.zh);
+        g.by_zw = make_fastdiv((uint32_t)pr.zw);
+        g.D = (uint32_t)pr.D;
+        g.nvec = (uint32_t)(p.ld.numel / vec);
+        g.sd = pr.sd;
+        g.pd = pr.pd;
+        g.dd = pr.dd;
+        g.pad_ = 0;
+        const dim3 grid(blocks_for(g.nvec)), block(kC3dThreads);
+        if (elsz == 2 && vec == 8) hipLaunchKernelGGL((c3d_gather_fast_kernel<2, 8>), grid, block, 0, st, g);
+        else if (elsz == 2) hipLaunchKernelGGL((c3d_gather_fast_kernel<2, 1>), grid, block, 0, st, g);
+        else if (vec == 4) hipLaunchKernelGGL((c3d_gather_fast_kernel<4, 4>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((c3d_gather_fast_kernel<4, 1>), grid, block, 0, st, g);
+    } else if (elsz == 2) {
+        hipLaunchKernelGGL(c3d_gather_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
+    } else {
+        hipLaunchKernelGGL(c3d_gather_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
+    }
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return alt_conv2d(h, &f, workspace, w_packed, bias, y, (char *)workspace + xu_bytes, ws_bytes - xu_bytes, stream);
 }
 
 }  // namespace
@@ -197,39 +362,16 @@ extern "C" alt_status_t alt_conv3d_workspace_size(alt_handle_t h, const alt_conv
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
-    alt_conv_desc_t f;
-    bool gather;
-    alt_status_t s = plane_desc(h, d, &f, &gather);
-    if (s != ALT_OK) return s;
-    size_t conv_ws = 0;
-    if ((s = alt_conv2d_workspace_size(h, &f, &conv_ws)) != ALT_OK) return s;
-    *bytes = (gather ? round256((size_t)(f.N * f.C * f.H * f.W) * dtype_size(f.in_dtype)) : 0) + conv_ws;
-    return ALT_OK;
+    Problem3d p;
+    const alt_status_t s = forward_problem(h, d, &p);
+    return s != ALT_OK ? s : workspace_size(h, p, bytes);
 }
 
 extern "C" alt_status_t alt_pack_weights3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_kctrs,
                                            void *w_packed, void *stream)
 {
     if (!h) return ALT_INVALID_ARG;
-    if (!d || !w_kctrs || !w_packed) return fail(h, ALT_INVALID_ARG, "alt_pack_weights3d: null argument");
-    const alt_conv_desc_t &q = d->plane;
-    if (q.in_dtype != ALT_F32 && q.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_pack_weights3d: bad dtype");
-    if (q.K < 1 || q.C < 1 || q.R < 1 || q.S < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "alt_pack_weights3d: extents must be positive");
-    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
-    const int64_t wsh[4] = {q.K, q.C * d->T, q.R, q.S};
-    PackParams p;
-    std::string err;
-    alt_status_t s = bind_layout(&q.w_layout, 4, wsh, &p.ld, &err);
-    if (s != ALT_OK) return fail(h, s, "w_layout: %s", err.c_str());
-    p.src = w_kctrs;
-    p.dst = w_packed;
-    p.C = q.C;
-    p.T = d->T;
-    hipStream_t st = (hipStream_t)stream;
-    if (dtype_size(q.in_dtype) == 2) hipLaunchKernelGGL(c3d_pack_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
-    else hipLaunchKernelGGL(c3d_pack_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
-    ALT_CHECK_HIP(h, hipGetLastError());
-    return ALT_OK;
+    return pack3d(h, d, w_kctrs, w_packed, stream, false, "alt_pack_weights3d");
 }
 
 extern "C" alt_status_t alt_conv3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
@@ -237,62 +379,48 @@ extern "C" alt_status_t alt_conv3d(alt_handle_t h, const alt_conv3d_desc_t *d, c
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !x || !w_packed || !y) return fail(h, ALT_INVALID_ARG, "alt_conv3d: null argument");
-    const alt_conv_desc_t &q = d->plane;
-    if (q.in_dtype != ALT_F32 && q.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_conv3d: bad dtype");
-    alt_conv_desc_t f;
-    bool gather;
-    alt_status_t s = plane_desc(h, d, &f, &gather);
-    if (s != ALT_OK) return s;
-    if (!gather) return alt_conv2d(h, &f, x, w_packed, bias, y, workspace, ws_bytes, stream);
+    if (d->plane.in_dtype != ALT_F32 && d->plane.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_conv3d: bad dtype");
+    Problem3d p;
+    const alt_status_t s = forward_problem(h, d, &p);
+    return s != ALT_OK ? s : run3d(h, p, x, w_packed, bias, y, workspace, ws_bytes, stream, "alt_conv3d");
+}
 
-    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
-    if (q.H < 1 || q.W < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: extents must be positive");
-    const int elsz = (int)dtype_size(q.in_dtype);
-    const size_t xu_bytes = round256((size_t)(f.N * f.C * f.H * f.W) * elsz);
-    if (!workspace || ws_bytes < xu_bytes)
-        return fail(h, ALT_WORKSPACE_TOO_SMALL, "alt_conv3d: the workspace must hold the depth-unfolded input (%zu bytes)", xu_bytes);
-    if ((uintptr_t)workspace % 16) return fail(h, ALT_INVALID_ARG, "alt_conv3d: workspace must be 16-byte aligned");
-    GatherParams p;
-    const int64_t OD = out_depth(d);
-    const int64_t xs[4] = {q.N * d->D, q.C, q.H, q.W}, us[4] = {f.N, f.C, f.H, f.W};
-    std::string err;
-    if ((s = bind_layout(&q.x_layout, 4, xs, &p.ls, &err)) != ALT_OK) return fail(h, s, "x_layout: %s", err.c_str());
-    if ((s = bind_layout(&q.x_layout, 4, us, &p.ld, &err)) != ALT_OK) return fail(h, s, "x_layout (depth-unfolded input): %s", err.c_str());
-    p.src = x;
-    p.dst = workspace;
-    p.D = d->D;
-    p.OD = OD;
-    p.C = q.C;
-    p.sd = d->stride_d;
-    p.pd = d->pad_d;
-    p.dd = d->dil_d;
-    p.pad_ = 0;
-    hipStream_t st = (hipStream_t)stream;
-    GatherFastParams g;
-    const bool small = d->D < ((int64_t)1 << 20) && OD < ((int64_t)1 << 20) && d->T < ((int64_t)1 << 10) &&
-                       (int64_t)d->stride_d * OD + (int64_t)d->dil_d * d->T + d->pad_d < ((int64_t)1 << 30);
-    if (small && fast_layout(p.ls, &g.ls) && fast_layout(p.ld, &g.ld)) {
-        const int vec = gather_vec(p.ls, p.ld, elsz, q.C, x, workspace);
-        g.src = x;
-        g.dst = workspace;
-        g.by_od = make_fastdiv((uint32_t)OD);
-        g.by_c = make_fastdiv((uint32_t)q.C);
-        g.D = (uint32_t)d->D;
-        g.nvec = (uint32_t)(p.ld.numel / vec);
-        g.sd = d->stride_d;
-        g.pd = d->pad_d;
-        g.dd = d->dil_d;
-        g.pad_ = 0;
-        const dim3 grid(blocks_for(g.nvec)), block(kC3dThreads);
-        if (elsz == 2 && vec == 8) hipLaunchKernelGGL((c3d_gather_fast_kernel<2, 8>), grid, block, 0, st, g);
-        else if (elsz == 2) hipLaunchKernelGGL((c3d_gather_fast_kernel<2, 1>), grid, block, 0, st, g);
-        else if (vec == 4) hipLaunchKernelGGL((c3d_gather_fast_kernel<4, 4>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((c3d_gather_fast_kernel<4, 1>), grid, block, 0, st, g);
-    } else if (elsz == 2) {
-        hipLaunchKernelGGL(c3d_gather_kernel<2>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
-    } else {
-        hipLaunchKernelGGL(c3d_gather_kernel<4>, dim3(blocks_for(p.ld.numel)), dim3(kC3dThreads), 0, st, p);
-    }
-    ALT_CHECK_HIP(h, hipGetLastError());
-    return alt_conv2d(h, &f, workspace, w_packed, bias, y, (char *)workspace + xu_bytes, ws_bytes - xu_bytes, stream);
+extern "C" alt_status_t alt_conv3d_transpose_output_shape(const alt_conv3d_desc_t *d, int64_t *out)
+{
+    if (!d || !out) return ALT_INVALID_ARG;
+    const alt_conv_desc_t &q = d->plane;
+    if (d->stride_d < 1 || q.stride_h < 1 || q.stride_w < 1 || d->dil_d < 1 || q.dil_h < 1 || q.dil_w < 1) return ALT_INVALID_ARG;
+    out[0] = q.N;
+    out[1] = q.K;
+    out[2] = transposed_extent(d->D, d->stride_d, d->pad_d, d->dil_d, d->T);
+    out[3] = transposed_extent(q.H, q.stride_h, q.pad_h, q.dil_h, q.R);
+    out[4] = transposed_extent(q.W, q.stride_w, q.pad_w, q.dil_w, q.S);
+    return (out[2] < 1 || out[3] < 1 || out[4] < 1) ? ALT_INVALID_ARG : ALT_OK;
+}
+
+extern "C" alt_status_t alt_conv3d_transpose_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem3d p;
+    const alt_status_t s = transposed_problem(h, d, &p);
+    return s != ALT_OK ? s : workspace_size(h, p, bytes);
+}
+
+extern "C" alt_status_t alt_pack_weights3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_cktrs,
+                                                     void *w_packed, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    return pack3d(h, d, w_cktrs, w_packed, stream, true, "alt_pack_weights3d_transpose");
+}
+
+extern "C" alt_status_t alt_conv3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
+                                             const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !x || !w_packed || !y) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: null argument");
+    if (d->plane.in_dtype != ALT_F32 && d->plane.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: bad dtype");
+    Problem3d p;
+    const alt_status_t s = transposed_problem(h, d, &p);
+    return s != ALT_OK ? s : run3d(h, p, x, w_packed, bias, y, workspace, ws_bytes, stream, "alt_conv3d_transpose");
 }

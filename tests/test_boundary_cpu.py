@@ -225,6 +225,9 @@ def test_calls_without_gpu_fail_loudly_not_silently():
                                   stream=0),
                  lambda: h.conv3d(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 1, 3, 3, pad=(0, 1, 1)), 16, 16, 16, stream=0),
                  lambda: h.pack_weights3d(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1), 16, 16, stream=0),
+                 lambda: h.conv3d_transpose(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, stride=2, pad=1), 16, 16, 16, workspace=16,
+                                            ws_bytes=1 << 24, stream=0),
+                 lambda: h.pack_weights3d_transpose(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1), 16, 16, stream=0),
                  lambda: h.tune_conv2d_multi([dict(d=nhwc, x=16, w=16, y=16, stream=0)]),
                  lambda: h.eltwise_add(alt.BF16, 64, 16, 16, 16, stream=0),
                  lambda: h.unfold(alt.BF16, (4, 8), 0, 2, 1, 16, 4096, stream=0)):
@@ -251,6 +254,14 @@ def test_conv3d_host_side(oracle):
     with pytest.raises(alt.AltError) as e:
         h.conv3d_workspace_size(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, stride=(0, 1, 1), pad=1))
     assert e.value.status == 1
+    for (D, H, W, T, R, S, stride, pad, dil) in [(4, 5, 6, 3, 2, 3, 2, 1, 1), (3, 4, 5, 3, 3, 2, (2, 1, 3), (1, 0, 1), (1, 2, 1))]:
+        d = alt.conv3d_desc(2, 4, D, H, W, 8, T, R, S, stride=stride, pad=pad, dil=dil)
+        ref = oracle.conv3d_transpose(np.zeros((2, 4, D, H, W), np.float32), np.zeros((4, 8, T, R, S), np.float32), stride=stride,
+                                      pad=pad, dil=dil)
+        assert h.conv3d_transpose_output_shape(d) == ref.shape
+    with pytest.raises(alt.AltError) as e:
+        h.conv3d_transpose_workspace_size(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, stride=2, pad=(3, 1, 1)))
+    assert e.value.status == 4
     # the unfolded input is counted: T*C channels for every output slice
     d = alt.conv3d_desc(2, 16, 6, 8, 8, 16, 3, 3, 3, stride=(2, 1, 1), pad=1, in_dtype=alt.BF16)
     assert h.conv3d_workspace_size(d) >= 2 * 3 * (3 * 16) * 8 * 8 * 2

@@ -729,6 +729,74 @@ def test_conv3d_one_tap_is_the_2d_call_and_errors(h):
         h.conv3d_workspace_size(dd)
 
 
+@pytest.mark.parametrize("layouts", [("NHWC", "OHWI", "NHWC"), ("NCHW", "OIHW", "NCHW"), ("NCHW16c", "OIHW16o16i", "NCHW16c")])
+@pytest.mark.parametrize("geometry", [(1, 1, 1), (2, 1, 1), ((2, 1, 3), (1, 0, 2), (1, 1, 1)), ((1, 2, 2), (2, 1, 0), (2, 1, 2)),
+                                      ((2, 2, 2), (0, 0, 0), (1, 1, 1))], ids=lambda g: "s%s_p%s_d%s" % g)
+def test_conv3d_transpose_exact_integers(h, layouts, geometry):
+    """alt_conv3d_transpose (the T3D of Section 6.1) against the oracle's scatter definition, bf16 integers,
+    bit for bit: per-direction strides, padding and dilation, three slice layouts, fp32 output and bf16 output
+    with bias and ReLU; the packed filter is the mirrored, channel-swapped one."""
+    stride, pad, dil = geometry
+    xl, wl, yl = layouts
+    N, C, D, H, W, K, T, R, S = 2, 16, 4, 5, 6, 32, 3, 2, 3
+    x = small_ints_f32(941, (N, C, D, H, W), -3, 3)
+    w = small_ints_f32(942, (C, K, T, R, S), -3, 3)
+    b = small_ints_f32(943, (K,), -20, 20)
+    ref = oracle.conv3d_transpose(x, w, stride=stride, pad=pad, dil=dil)
+    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    xs = np.ascontiguousarray(xb.transpose(0, 2, 1, 3, 4)).reshape(N * D, C, H, W)
+    xd = dev(to_layout(xs, "NCHW", xl))
+    for out_dtype, bias, relu in [(alt.F32, None, False), (alt.BF16, b, True)]:
+        epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
+        d = alt.conv3d_desc(N, C, D, H, W, K, T, R, S, stride=stride, pad=pad, dil=dil, in_dtype=alt.BF16, out_dtype=out_dtype,
+                            epilogue=epi, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+        oshape = h.conv3d_transpose_output_shape(d)
+        assert oshape == ref.shape
+        _, _, OD, OH, OW = oshape
+        wd = torch.empty_like(dev(wb.reshape(-1)))
+        h.pack_weights3d_transpose(d, dev(wb.reshape(-1)), wd)
+        w2 = np.ascontiguousarray(wb[:, :, ::-1, ::-1, ::-1].transpose(1, 2, 0, 3, 4)).reshape(K, T * C, R, S)
+        assert np.array_equal(host(wd, np.uint16), to_layout(w2, "OIHW", wl).reshape(-1))
+        ydt = np.float32 if out_dtype == alt.F32 else np.uint16
+        n_out = int(np.prod(oshape))
+        whole, yd = canary_dev(n_out, ydt)
+        need = h.conv3d_transpose_workspace_size(d)
+        ws = torch.empty((need + 36 * n_out * 4) // 4 + 4, dtype=torch.float32, device="cuda")
+        h.conv3d_transpose(d, xd, wd, yd, bias=dev(bias) if bias is not None else None, workspace=ws, ws_bytes=need + 36 * n_out * 4)
+        got = host(yd, ydt)
+        assert canary_ok(whole, n_out), "wrote outside y"
+        got = from_layout(got, (N * OD, K, OH, OW), "NCHW", yl).reshape(N, OD, K, OH, OW).transpose(0, 2, 1, 3, 4)
+        want = ref if bias is None else f32_to_bf16_bits(np.maximum(ref + b[None, :, None, None, None], np.float32(0)))
+        assert np.array_equal(got, want)
+
+
+def test_conv3d_transpose_gaussian_within_tolerance_and_errors(h):
+    """Gaussian bf16 operands within 2e-2 of the oracle (a decoder-shaped 4x4x4 stride-2 layer at reduced size);
+    padding beyond dil*(taps-1), groups and a short workspace are refused."""
+    N, C, D, H, W, K = 1, 64, 3, 6, 5, 32
+    x = f32_to_bf16_bits(normal_f32(951, (N, C, D, H, W)))
+    w = f32_to_bf16_bits(normal_f32(952, (C, K, 4, 4, 4), 0.05))
+    ref = oracle.conv3d_transpose(x, w, stride=2, pad=1)
+    d = alt.conv3d_desc(N, C, D, H, W, K, 4, 4, 4, stride=2, pad=1, in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI",
+                        y_layout="NCHW->NHWC")
+    assert h.conv3d_transpose_output_shape(d) == ref.shape == (1, 32, 6, 12, 10)
+    xd = dev(np.ascontiguousarray(x.transpose(0, 2, 3, 4, 1)).reshape(-1))
+    wd = torch.empty_like(dev(w.reshape(-1)))
+    h.pack_weights3d_transpose(d, dev(w.reshape(-1)), wd)
+    need = h.conv3d_transpose_workspace_size(d)
+    ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
+    yd = torch.empty(ref.size, dtype=torch.float32, device="cuda")
+    h.conv3d_transpose(d, xd, wd, yd, workspace=ws, ws_bytes=need)
+    got = host(yd, np.float32).reshape(1, 6, 12, 10, 32).transpose(0, 4, 1, 2, 3)
+    assert rel_err(got, ref) <= TOL[alt.BF16]
+    with pytest.raises(alt.AltError, match="workspace"):
+        h.conv3d_transpose(d, xd, wd, yd, workspace=ws, ws_bytes=4096)
+    with pytest.raises(alt.AltError, match="padding"):
+        h.conv3d_transpose_workspace_size(alt.conv3d_desc(N, C, D, H, W, K, 3, 3, 3, stride=2, pad=(3, 1, 1)))
+    with pytest.raises(alt.AltError, match="groups"):
+        h.conv3d_transpose_workspace_size(alt.conv3d_desc(N, C, D, H, W, K, 3, 3, 3, stride=2, pad=1, groups=2))
+
+
 @pytest.mark.parametrize("out_dtype", [alt.F32, alt.BF16])
 def test_conv2d_add_fused_sum_exact_integers(h, out_dtype):
     """alt_conv2d_add: y = relu(conv + bias + addend) in one launch, every tile-kernel variant

@@ -425,6 +425,33 @@ def test_conv3d_with_different_stride_padding_dilation_per_direction(oracle, str
     assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
 
 
+@pytest.mark.parametrize("stride,pad,dil", [(1, 0, 1), (2, 1, 1), ((2, 1, 3), (1, 0, 2), (1, 1, 1)), ((1, 2, 2), (2, 1, 0), (2, 1, 2))])
+def test_conv3d_transpose_vs_library_routine_adjoint_and_2d_special_case(oracle, stride, pad, dil):
+    """The transposed C3D against torch's conv_transpose3d in float64; as the adjoint of the oracle's own
+    C3D (<conv3d(u), v> = <u, conv3d_transpose(v)> for the same filter, in exact integers); and with one
+    slice and one depth tap it is the transposed C2D."""
+    x = normal_f32(121, (2, 3, 4, 5, 6))
+    w = normal_f32(122, (3, 4, 3, 2, 3))
+    got = oracle.conv3d_transpose(x, w, stride=stride, pad=pad, dil=dil)
+    ref = torch.nn.functional.conv_transpose3d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), stride=stride,
+                                               padding=pad, dilation=dil).numpy()
+    assert got.shape == ref.shape
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+    # adjoint: v has the shape of x, u the shape of the transposed result when the forward sizes cover it
+    v = small_ints_f32(123, (2, 3, 4, 5, 6), -4, 4)
+    wi = small_ints_f32(124, (3, 4, 3, 2, 3), -4, 4)
+    tv = oracle.conv3d_transpose(v, wi, stride=stride, pad=pad, dil=dil)
+    u = small_ints_f32(125, tv.shape, -4, 4)
+    fu = oracle.conv3d(u, wi, stride=stride, pad=pad, dil=dil)          # the filter (C,K,..) read as (K'=C, C'=K, ..)
+    assert fu.shape == v.shape
+    assert float(np.sum(fu.astype(np.float64) * v)) == float(np.sum(u.astype(np.float64) * tv))
+    if not isinstance(stride, tuple):
+        x1 = small_ints_f32(126, (2, 3, 1, 5, 6), -4, 4)
+        w1 = small_ints_f32(127, (3, 4, 1, 2, 3), -4, 4)
+        assert np.array_equal(oracle.conv3d_transpose(x1, w1, stride=(1, stride, stride), pad=(0, pad, pad))[:, :, 0],
+                              oracle.conv2d_transpose(x1[:, :, 0], w1[:, :, 0], stride=stride, pad=pad))
+
+
 @pytest.mark.parametrize("stride,pad", [(1, 0), (1, 1), (2, 1), (2, 0)])
 def test_conv3d_vs_library_routine_and_2d_special_case(oracle, stride, pad):
     """Against torch's conv3d in float64; with a depth of one tap and one slice it is the C2D."""
