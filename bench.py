@@ -701,13 +701,18 @@ def main():
         # a decoder-style transposed convolution (128 -> 64 channels, 4x4, stride 2, 28x28 -> 56x56, batch 16):
         # zero insertion + the forward kernels, per activation layout
         t2d = {}
+        # tune the merged stride-1 problem of the sub-pixel form first: the call finds the winners in the cache
+        h.tune_conv2d(alt.conv_desc(16, 128, 28, 28, 256, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16),
+                      arena, arena.numel(), max_trials=0, warmup=3, reps=20)
         tfl = 2.0 * 16 * 128 * 64 * 16 * 28 * 28              # nominal: every input pixel meets every filter tap
         for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
             d = alt.conv_desc(16, 128, 28, 28, 64, 4, 4, stride=2, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
                               x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
             osh = h.conv2d_transpose_output_shape(d)
             xb = torch.randint(-200, 200, (16 * 128 * 28 * 28,), dtype=torch.int16, device=dev)
-            wb = torch.randint(-200, 200, (128 * 64 * 16,), dtype=torch.int16, device=dev)
+            wsrc = torch.randint(-200, 200, (128 * 64 * 16,), dtype=torch.int16, device=dev)
+            wb = torch.empty(int(np.prod(h.conv2d_transpose_weight_shape(d))), dtype=torch.int16, device=dev)
+            h.pack_weights_transpose(d, wsrc, wb, stream=stream)
             yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)
             wsb = h.conv2d_transpose_workspace_size(d)
             wsd = torch.empty(wsb + 16, dtype=torch.uint8, device=dev)
@@ -717,7 +722,9 @@ def main():
             t2d[xl] = dict(us=round(us, 2), nominal_tflops=round(tfl / us / 1e6, 1))
         extra["conv_transpose_c128_k64_4x4_s2_28x28_b16"] = dict(
             per_layout=t2d, speedup_vs_nchw=round(t2d["NCHW"]["us"] / min(v["us"] for v in t2d.values()), 2),
-            note="two launches per call (input expansion, forward kernel with default variant choice)")
+            form="sub-pixel" if h.conv2d_transpose_weight_shape(d)[0] != 64 else "zero insertion",
+            note="sub-pixel form: one stride-1 convolution of x with 4*K output channels into the workspace, then the kernel that "
+                 "moves the four phases into place (and one that replicates the bias when there is one); tuned forward kernel")
 
         # a ResNet3D-18-shaped layer (the C3D of the operator list): 128 -> 128 channels, 3x3x3, 8 slices of 28x28,
         # batch 2; depth unfolded into the channels per call, then the 2-D kernels on 16 images of 384 channels

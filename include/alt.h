@@ -252,14 +252,26 @@ alt_status_t alt_pack_weights(alt_handle_t h, const alt_conv_desc_t *d, const vo
  * It runs as the equivalent forward convolution: x with stride-1 zeros between its pixels
  * (written into the workspace under x_layout by a kernel of its own; skipped for stride 1)
  * convolved with w' at stride 1 and padding dil*(R-1)-pad by alt_conv2d's kernels (variant,
- * epilogue, dtypes and tuning cache as for alt_conv2d).  `workspace` (device) holds the
- * expanded input followed by what alt_conv2d wants; alt_conv2d_transpose_workspace_size
- * reports the sum, and less than the expanded input's size fails with
+ * epilogue, dtypes and tuning cache as for alt_conv2d).
+ * Sub-pixel form: where both output extents are multiples of the strides and the taps of the
+ * stride_h*stride_w output phases fit one symmetric window (4x4 at stride 2 with padding 1, 2x2
+ * at stride 2, 6x6 at stride 2 with padding 2, 8x8 at stride 4 with padding 2, ...) the library
+ * instead runs ONE stride-1 convolution of x itself with stride_h*stride_w*K output channels,
+ *   y'[n, (ph*stride_w + pw)*K + k, q, p] = y[n, k, q*stride_h + ph, p*stride_w + pw],
+ * into the workspace (no inserted zeros are multiplied) and moves y' into place under y_layout
+ * with a kernel of its own; the packed filter is then the merged one, logical
+ * (stride_h*stride_w*K, C, R', S') under w_layout with R', S' the common window of the phases.
+ * Which form a descriptor takes depends on the descriptor alone;
+ * alt_conv2d_transpose_weight_shape reports the logical shape of the packed filter (so its
+ * size), alt_pack_weights_transpose writes it, alt_conv2d_transpose_workspace_size counts the
+ * form's needs.  `workspace` (device, 16-byte aligned) holds the expanded input (or y' and a
+ * bias vector) followed by what alt_conv2d wants; less than the first part fails with
  * ALT_WORKSPACE_TOO_SMALL.  Asynchronous on `stream`. */
 alt_status_t alt_conv2d_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w_packed,
                                   const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv2d_transpose_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
 alt_status_t alt_conv2d_transpose_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw);
+alt_status_t alt_conv2d_transpose_weight_shape(const alt_conv_desc_t *d, int64_t *out_kcrs);
 alt_status_t alt_pack_weights_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *w_ckrs,
                                         void *w_packed, void *stream);
 

@@ -152,7 +152,7 @@ def exported_symbols():
             "alt_layout_parse", "alt_layout_from_prims", "alt_layout_physical_shape",
             "alt_layout_offset", "alt_layout_index_of", "alt_layout_transform",
             "alt_conv2d", "alt_conv2d_add", "alt_conv2d_multi", "alt_conv2d_transpose", "alt_conv2d_transpose_workspace_size",
-            "alt_conv2d_transpose_output_shape", "alt_pack_weights_transpose",
+            "alt_conv2d_transpose_output_shape", "alt_conv2d_transpose_weight_shape", "alt_pack_weights_transpose",
             "alt_conv3d", "alt_conv3d_workspace_size", "alt_conv3d_output_shape", "alt_pack_weights3d",
             "alt_conv3d_transpose", "alt_conv3d_transpose_workspace_size", "alt_conv3d_transpose_output_shape",
             "alt_pack_weights3d_transpose", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
@@ -408,6 +408,11 @@ class Handle:
     def conv2d_transpose_output_shape(self, d):
         out = (ctypes.c_int64 * 4)()
         _ck(lib().alt_conv2d_transpose_output_shape(ctypes.byref(d), out))
+        return tuple(out)
+
+    def conv2d_transpose_weight_shape(self, d):
+        out = (ctypes.c_int64 * 4)()
+        _ck(lib().alt_conv2d_transpose_weight_shape(ctypes.byref(d), out))
         return tuple(out)
 
     def pack_weights_transpose(self, d, w_ckrs, w_packed, stream=None):

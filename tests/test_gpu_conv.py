@@ -481,8 +481,12 @@ def run_conv_transpose(h, x, w, cfg, xl, wl, yl, in_dtype, out_dtype=alt.F32, bi
     d = alt.conv_desc(N, C, H, W, K, R, S, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), in_dtype=in_dtype,
                       out_dtype=out_dtype, epilogue=epi, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
     oshape = h.conv2d_transpose_output_shape(d)
-    wd = torch.empty_like(dev(w.reshape(-1)))
+    wshape = h.conv2d_transpose_weight_shape(d)
+    whole_w, wd = canary_dev(int(np.prod(wshape)), w.dtype)
     h.pack_weights_transpose(d, dev(w.reshape(-1)), wd)
+    assert canary_ok(whole_w, int(np.prod(wshape))), "wrote outside the packed filter"
+    if wshape == (K, C, R, S):          # zero-insertion form: the mirrored, channel-swapped filter
+        assert np.array_equal(host(wd, w.dtype), to_layout(np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3)), "OIHW", wl).reshape(-1))
     ydt = np.float32 if out_dtype == alt.F32 else np.uint16
     n_out = int(np.prod(oshape))
     whole, yd = canary_dev(n_out, ydt)
@@ -502,9 +506,17 @@ def test_conv_transpose_exact_integers(h, layouts, in_dtype):
     bit for bit against the oracle's scatter definition: strides 1-3, padding up to dil*(R-1),
     dilation, ragged sizes, bias and ReLU."""
     xl, wl, yl = layouts
+    forms = set()
     for (N, C, H, W, K, R, S, cfg) in [(2, 32, 7, 9, 48, 3, 3, dict(stride=2, pad=1)), (1, 64, 5, 6, 32, 3, 3, dict(stride=1, pad=1)),
                                        (2, 16, 6, 5, 32, 4, 4, dict(stride=2, pad=1)), (1, 32, 4, 7, 16, 3, 2, dict(stride=3, pad=0)),
-                                       (2, 16, 8, 5, 16, 3, 3, dict(stride=2, pad=2, dil=2))]:
+                                       (2, 16, 8, 5, 16, 3, 3, dict(stride=2, pad=2, dil=2)),
+                                       # sub-pixel form: 2x2 and 6x6 at stride 2, 8x8 at stride 4, a phase without taps, dilated taps
+                                       (2, 32, 5, 7, 16, 2, 2, dict(stride=2, pad=0)), (1, 16, 6, 5, 32, 6, 6, dict(stride=2, pad=2)),
+                                       (1, 16, 4, 5, 16, 8, 8, dict(stride=4, pad=2)), (2, 16, 5, 4, 16, 2, 2, dict(stride=3, pad=0)),
+                                       (1, 32, 6, 7, 16, 2, 2, dict(stride=2, pad=1, dil=3))]:
+        dsc = alt.conv_desc(N, C, H, W, K, R, S, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), in_dtype=in_dtype,
+                            x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+        forms.add("zero insertion" if h.conv2d_transpose_weight_shape(dsc) == (K, C, R, S) else "sub-pixel")
         x = small_ints_f32(601, (N, C, H, W), -3, 3)
         w = small_ints_f32(602, (C, K, R, S), -3, 3)
         b = small_ints_f32(603, (K,), -20, 20)
@@ -513,6 +525,7 @@ def test_conv_transpose_exact_integers(h, layouts, in_dtype):
         got, _ = run_conv_transpose(h, xi, wi, cfg, xl, wl, yl, in_dtype, bias=b, relu=True)
         assert got.shape == ref.shape
         assert np.array_equal(got, ref), (N, C, H, W, K, R, S, cfg)
+    assert forms == {"zero insertion", "sub-pixel"}
 
 
 def test_conv_transpose_tolerance_and_errors(h):
