@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 import paper_2210_12415_amd as alt
+from workloads import small_ints_f32
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -234,6 +235,49 @@ def test_calls_without_gpu_fail_loudly_not_silently():
         with pytest.raises(alt.AltError) as e:
             call()
         assert e.value.status == 6
+
+
+def test_conv_transpose_sub_pixel_form_host_side(oracle):
+    """Which descriptors take the sub-pixel form and the shape of their packed filter; and the identity the form
+    rests on, checked with the oracle alone: the stride-1 convolution of x with the merged filter gives
+    y'[n, (ph*sw + pw)*K + k, q, p] = y[n, k, q*sh + ph, p*sw + pw] of the transposed convolution."""
+    h = alt.Handle()
+    K, C = 8, 4
+    for (H, W, R, S, stride, pad, dil, want) in [(6, 5, 4, 4, 2, 1, 1, (4 * K, C, 3, 3)), (5, 7, 2, 2, 2, 0, 1, (4 * K, C, 1, 1)),
+                                                 (6, 5, 6, 6, 2, 2, 1, (4 * K, C, 3, 3)), (4, 5, 8, 8, 4, 2, 1, (16 * K, C, 3, 3)),
+                                                 (6, 7, 2, 2, 2, 1, 3, (4 * K, C, 3, 3)), (5, 4, 2, 2, 3, 1, 1, (9 * K, C, 2, 2)),
+                                                 (7, 9, 3, 3, 2, 1, 1, (K, C, 3, 3)), (5, 6, 3, 3, 1, 1, 1, (K, C, 3, 3)),
+                                                 (8, 5, 3, 3, 2, 2, 2, (K, C, 3, 3))]:
+        d = alt.conv_desc(2, C, H, W, K, R, S, stride=stride, pad=pad, dil=dil)
+        got = h.conv2d_transpose_weight_shape(d)
+        assert got == want, (R, S, stride, pad, dil, got)
+        if got[0] == K:
+            continue
+        Rm, Sm = got[2], got[3]
+        x = small_ints_f32(701, (2, C, H, W), -3, 3)
+        w = small_ints_f32(702, (C, K, R, S), -3, 3)
+        y = oracle.conv2d_transpose(x, w, stride=stride, pad=pad, dil=dil)
+        # the window of tap offsets (ph + pad - r*dil)/stride over all phases, and the merged filter over it
+        deltas = [(ph + pad - r * dil) // stride for ph in range(stride) for r in range(R) if (ph + pad - r * dil) % stride == 0]
+        pm = -min(deltas)
+        assert max(deltas) - min(deltas) + 1 == Rm == Sm
+        wm = np.zeros((stride * stride * K, C, Rm, Sm), np.float32)
+        for ph in range(stride):
+            for pw in range(stride):
+                for a in range(Rm):
+                    for b in range(Sm):
+                        nr, ns = ph + pad - stride * (a - pm), pw + pad - stride * (b - pm)
+                        if nr >= 0 and ns >= 0 and nr % dil == 0 and ns % dil == 0 and nr // dil < R and ns // dil < S:
+                            wm[(ph * stride + pw) * K:(ph * stride + pw + 1) * K, :, a, b] = w[:, :, nr // dil, ns // dil].T
+        yq = oracle.conv2d(x, wm, stride=1, pad=pm)
+        assert yq.shape == (2, stride * stride * K, y.shape[2] // stride, y.shape[3] // stride)
+        back = yq.reshape(2, stride, stride, K, yq.shape[2], yq.shape[3]).transpose(0, 3, 4, 1, 5, 2).reshape(y.shape)
+        assert np.array_equal(back, y)
+    # blocked layouts: the merged extents must fit them (24*4 channels in blocks of 8 do), else the zero-insertion form
+    d = alt.conv_desc(2, 16, 6, 5, 24, 4, 4, stride=2, pad=1, y_layout="NCHW->NCHW8c")
+    assert h.conv2d_transpose_weight_shape(d) == (96, 16, 3, 3)
+    d = alt.conv_desc(2, 16, 6, 5, 8, 2, 2, stride=3, pad=1, w_layout="OIHW->OIHW16o16i", x_layout="NCHW->NCHW16c")
+    assert h.conv2d_transpose_weight_shape(d) == (8, 16, 2, 2)          # 9*8 output channels are no multiple of 16
 
 
 def test_conv3d_host_side(oracle):
