@@ -626,6 +626,63 @@ def test_conv3d_by_unfolding_the_depth(h, stride, pad):
     assert np.array_equal(got, ref)
 
 
+def random_geometry(seed, square):
+    """A seeded convolution geometry with a non-empty output: filter extents, strides, dilations and padding
+    drawn per direction (`square`: one stride and one dilation for both, as the direct kernel wants;
+    padding from none to same-size), image sizes that leave ragged tiles."""
+    rng = np.random.default_rng(seed)
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+    dh, dw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    if square:
+        sw, dw = sh, dh
+    ph, pw = int(rng.integers(0, dh * (R - 1) // 2 + 1)), int(rng.integers(0, dw * (S - 1) // 2 + 1))
+    H = int(rng.integers(dh * (R - 1) + 1, dh * (R - 1) + 14))
+    W = int(rng.integers(dw * (S - 1) + 1, dw * (S - 1) + 14))
+    return dict(N=int(rng.integers(1, 4)), C=int(rng.choice([64, 128, 192])), K=int(rng.choice([32, 64, 96, 160])), H=H, W=W, R=R, S=S,
+                stride=(sh, sw), pad=(ph, pw), dil=(dh, dw))
+
+
+def conv_desc_of(g, **kw):
+    d = alt.conv_desc(g["N"], g["C"], g["H"], g["W"], g["K"], g["R"], g["S"], **kw)
+    (d.stride_h, d.stride_w), (d.pad_h, d.pad_w), (d.dil_h, d.dil_w) = g["stride"], g["pad"], g["dil"]
+    return d
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_geometries_exact_integers(h, seed):
+    """Seeded sweep over filter extents 1-5, strides 1-2, dilations 1-3 and padding from none to same-size,
+    each drawn per direction, on ragged images: bf16 integers, so every variant of every kernel family that
+    takes the geometry must give the oracle's result bit for bit.  NHWC/OHWI with one stride and dilation
+    (the direct and streaming kernels must be among the variants when their conditions hold) and a blocked
+    layout with fully independent directions (implicit-GEMM kernels)."""
+    for square, (xl, wl, yl) in [(True, ("NHWC", "OHWI", "NHWC")), (False, ("NCHW32c", "OIHW32o32i", "NHWC"))]:
+        g = random_geometry(1000 + seed, square)
+        x = small_ints_f32(2000 + seed, (g["N"], g["C"], g["H"], g["W"]), -3, 3)
+        w = small_ints_f32(3000 + seed, (g["K"], g["C"], g["R"], g["S"]), -3, 3)
+        b = small_ints_f32(4000 + seed, (g["K"],), -20, 20)
+        ref = oracle.conv2d(x, w, stride=g["stride"], pad=g["pad"], dil=g["dil"], bias=b, relu=True)
+        xd, wd, bd = dev(to_layout(f32_to_bf16_bits(x), "NCHW", xl)), dev(to_layout(f32_to_bf16_bits(w), "OIHW", wl)), dev(b)
+        d0 = conv_desc_of(g, in_dtype=alt.BF16, epilogue=alt.EPI_BIAS | alt.EPI_RELU, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl,
+                          y_layout="NCHW->" + yl)
+        oshape = h.conv2d_output_shape(d0)
+        assert oshape == ref.shape, g
+        n_out = int(np.prod(oshape))
+        ws = torch.empty(36 * n_out, dtype=torch.float32, device="cuda")
+        variants = applicable_variants(h, d0)
+        assert variants, g
+        if square:
+            assert any("direct" in n or "stream" in n for _, n in variants), g
+        for v, name in variants:
+            d = conv_desc_of(g, in_dtype=alt.BF16, epilogue=alt.EPI_BIAS | alt.EPI_RELU, variant=v, x_layout="NCHW->" + xl,
+                             w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+            whole, yd = canary_dev(n_out, np.float32)
+            h.conv2d(d, xd, wd, yd, bias=bd, workspace=ws, ws_bytes=ws.numel() * 4)
+            got = from_layout(host(yd, np.float32), oshape, "NCHW", yl)
+            assert canary_ok(whole, n_out), (g, name)
+            assert np.array_equal(got, ref), (g, name)
+
+
 def run_conv3d(h, x, w, stride, pad, dil, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False, variant=-1,
                ws_slack=0):
     """x (N,C,D,H,W), w (K,C,T,R,S): float32 or uint16 bf16 bits, logical.  Puts x under `xl` slice by
