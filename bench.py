@@ -701,14 +701,13 @@ def main():
         # a decoder-style transposed convolution (128 -> 64 channels, 4x4, stride 2, 28x28 -> 56x56, batch 16):
         # zero insertion + the forward kernels, per activation layout
         t2d = {}
-        # tune the merged stride-1 problem of the sub-pixel form first: the call finds the winners in the cache
-        h.tune_conv2d(alt.conv_desc(16, 128, 28, 28, 256, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16),
-                      arena, arena.numel(), max_trials=0, warmup=3, reps=20)
         tfl = 2.0 * 16 * 128 * 64 * 16 * 28 * 28              # nominal: every input pixel meets every filter tap
         for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
             d = alt.conv_desc(16, 128, 28, 28, 64, 4, 4, stride=2, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
                               x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
             osh = h.conv2d_transpose_output_shape(d)
+            # tune(op, shape) for the transposed operator: the variants of the forward problem it runs as
+            h.tune_conv2d_variants(h.conv2d_transpose_problem(d), arena, arena.numel(), max_trials=0, warmup=3, reps=20)
             xb = torch.randint(-200, 200, (16 * 128 * 28 * 28,), dtype=torch.int16, device=dev)
             wsrc = torch.randint(-200, 200, (128 * 64 * 16,), dtype=torch.int16, device=dev)
             wb = torch.empty(int(np.prod(h.conv2d_transpose_weight_shape(d))), dtype=torch.int16, device=dev)
@@ -730,13 +729,12 @@ def main():
         # batch 2; depth unfolded into the channels per call, then the 2-D kernels on 16 images of 384 channels
         c3d = {}
         c3fl = 2.0 * 2 * 8 * 28 * 28 * 128 * 128 * 27         # nominal: padding taps counted
-        # tune the equivalent 2-D problem first: the 3-D call finds the winners in the cache
-        h.tune_conv2d(alt.conv_desc(16, 384, 28, 28, 128, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16),
-                      arena, arena.numel(), max_trials=0, warmup=3, reps=20)
         for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
             d = alt.conv3d_desc(2, 128, 8, 28, 28, 128, 3, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
                                 x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
             osh = h.conv3d_output_shape(d)
+            # tune(op, shape) for the 3-D operator: the variants of the 2-D problem it runs as
+            h.tune_conv2d_variants(h.conv3d_problem(d), arena, arena.numel(), max_trials=0, warmup=3, reps=20)
             xb = torch.randint(-200, 200, (2 * 8 * 128 * 28 * 28,), dtype=torch.int16, device=dev)
             wb = torch.randint(-200, 200, (128 * 128 * 27,), dtype=torch.int16, device=dev)
             yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)

@@ -272,6 +272,11 @@ alt_status_t alt_conv2d_transpose(alt_handle_t h, const alt_conv_desc_t *d, cons
 alt_status_t alt_conv2d_transpose_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
 alt_status_t alt_conv2d_transpose_output_shape(const alt_conv_desc_t *d, int64_t *out_nkhw);
 alt_status_t alt_conv2d_transpose_weight_shape(const alt_conv_desc_t *d, int64_t *out_kcrs);
+/* The 2-D forward problem alt_conv2d_transpose hands to alt_conv2d's kernels for this descriptor
+ * (extents, padding and layouts of the form it takes; epilogue, dtypes and variant as given):
+ * tune(op, shape) for the transposed operator is alt_tune_conv2d on it, after which the call
+ * finds the winning variant in the cache. */
+alt_status_t alt_conv2d_transpose_problem(alt_handle_t h, const alt_conv_desc_t *d, alt_conv_desc_t *out);
 alt_status_t alt_pack_weights_transpose(alt_handle_t h, const alt_conv_desc_t *d, const void *w_ckrs,
                                         void *w_packed, void *stream);
 
@@ -311,6 +316,9 @@ alt_status_t alt_conv3d_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *
 alt_status_t alt_conv3d_output_shape(const alt_conv3d_desc_t *d, int64_t *out_nkdhw);
 alt_status_t alt_pack_weights3d(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_kctrs,
                                 void *w_packed, void *stream);
+/* The 2-D problem (batch N*OD, T*C channels) that alt_conv3d hands to alt_conv2d's kernels: tune(op, shape)
+ * for the 3-D operator is alt_tune_conv2d on it. */
+alt_status_t alt_conv3d_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *out);
 
 /* Transposed 3-D convolution (T3D in the operator list of Section 6.1), the adjoint of the C3D
  * that maps K channels to C with the same filter:
@@ -332,6 +340,7 @@ alt_status_t alt_conv3d_transpose_workspace_size(alt_handle_t h, const alt_conv3
 alt_status_t alt_conv3d_transpose_output_shape(const alt_conv3d_desc_t *d, int64_t *out_nkdhw);
 alt_status_t alt_pack_weights3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_cktrs,
                                           void *w_packed, void *stream);
+alt_status_t alt_conv3d_transpose_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *out);
 
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and

@@ -358,6 +358,26 @@ extern "C" alt_status_t alt_conv3d_output_shape(const alt_conv3d_desc_t *d, int6
     return ALT_OK;
 }
 
+extern "C" alt_status_t alt_conv3d_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *out)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !out) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem3d p;
+    const alt_status_t s = forward_problem(h, d, &p);
+    if (s == ALT_OK) *out = p.f;
+    return s;
+}
+
+extern "C" alt_status_t alt_conv3d_transpose_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *out)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !out) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem3d p;
+    const alt_status_t s = transposed_problem(h, d, &p);
+    if (s == ALT_OK) *out = p.f;
+    return s;
+}
+
 extern "C" alt_status_t alt_conv3d_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes)
 {
     if (!h) return ALT_INVALID_ARG;

@@ -436,6 +436,18 @@ extern "C" alt_status_t alt_conv2d_transpose_weight_shape(const alt_conv_desc_t 
     return ALT_OK;
 }
 
+extern "C" alt_status_t alt_conv2d_transpose_problem(alt_handle_t h, const alt_conv_desc_t *d, alt_conv_desc_t *out)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !out) return fail(h, ALT_INVALID_ARG, "null argument");
+    alt_conv_desc_t f;
+    const alt_status_t s = forward_desc(h, d, &f);
+    if (s != ALT_OK) return s;
+    SubPixelPlan sp;
+    *out = subpixel_plan(d, &sp) ? sp.f : f;
+    return ALT_OK;
+}
+
 extern "C" alt_status_t alt_conv2d_transpose_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes)
 {
     if (!h) return ALT_INVALID_ARG;

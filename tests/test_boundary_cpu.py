@@ -306,6 +306,15 @@ def test_conv3d_host_side(oracle):
     with pytest.raises(alt.AltError) as e:
         h.conv3d_transpose_workspace_size(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, stride=2, pad=(3, 1, 1)))
     assert e.value.status == 4
+    # the 2-D problems behind the 3-D operators (what alt_tune_conv2d is given to tune them)
+    f = h.conv3d_problem(alt.conv3d_desc(2, 16, 6, 8, 7, 32, 3, 3, 3, stride=(2, 1, 1), pad=1))
+    assert (f.N, f.C, f.H, f.W, f.K, f.R, f.S, f.stride_h, f.pad_h) == (2 * 3, 3 * 16, 8, 7, 32, 3, 3, 1, 1)
+    f = h.conv3d_transpose_problem(alt.conv3d_desc(2, 16, 3, 4, 5, 32, 3, 3, 3, stride=2, pad=1))
+    assert (f.N, f.C, f.H, f.W, f.K, f.stride_h, f.stride_w, f.pad_h, f.pad_w) == (2 * 5, 3 * 16, 7, 9, 32, 1, 1, 1, 1)
+    f = h.conv2d_transpose_problem(alt.conv_desc(2, 16, 6, 5, 8, 4, 4, stride=2, pad=1))
+    assert (f.N, f.C, f.H, f.W, f.K, f.R, f.S, f.stride_h, f.pad_h) == (2, 16, 6, 5, 32, 3, 3, 1, 1)
+    f = h.conv2d_transpose_problem(alt.conv_desc(2, 16, 6, 5, 8, 3, 3, stride=2, pad=1))
+    assert (f.N, f.C, f.H, f.W, f.K, f.R, f.S, f.stride_h, f.pad_h) == (2, 16, 11, 9, 8, 3, 3, 1, 1)
     # the unfolded input is counted: T*C channels for every output slice
     d = alt.conv3d_desc(2, 16, 6, 8, 8, 16, 3, 3, 3, stride=(2, 1, 1), pad=1, in_dtype=alt.BF16)
     assert h.conv3d_workspace_size(d) >= 2 * 3 * (3 * 16) * 8 * 8 * 2

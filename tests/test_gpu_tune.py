@@ -299,3 +299,59 @@ def test_tune_conv2d_multi_returns_a_valid_launch(h):
     with pytest.raises(alt.AltError) as e:
         h.tune_conv2d_multi([])
     assert e.value.status == 1
+
+
+def test_tuning_the_problem_behind_the_transposed_and_3d_operators(h):
+    """tune(op, shape) for T2D, C3D and T3D: the library reports the 2-D problem it runs them as, alt_tune_conv2d_variants
+    tunes it, and the operator's call (variant -1) then runs the cached winner: results stay the oracle's bit for bit."""
+    arena = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    lay = dict(in_dtype=alt.BF16, x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC")
+    # transposed C2D, sub-pixel form
+    N, C, H, W, K = 2, 64, 9, 7, 32
+    d = alt.conv_desc(N, C, H, W, K, 4, 4, stride=2, pad=1, **lay)
+    f = h.conv2d_transpose_problem(d)
+    assert (f.N, f.C, f.H, f.W, f.K, f.R, f.S, f.stride_h, f.pad_h) == (N, C, H, W, 4 * K, 3, 3, 1, 1)
+    us, trials = h.tune_conv2d_variants(f, arena, arena.numel(), max_trials=12, warmup=1, reps=3)
+    assert us > 0 and trials >= 1
+    x = small_ints_f32(1201, (N, C, H, W), -3, 3)
+    w = small_ints_f32(1202, (C, K, 4, 4), -3, 3)
+    ref = oracle.conv2d_transpose(x, w, stride=2, pad=1)
+    wd = torch.empty(int(np.prod(h.conv2d_transpose_weight_shape(d))), dtype=torch.int16, device="cuda")
+    h.pack_weights_transpose(d, dev(f32_to_bf16_bits(w).reshape(-1)), wd)
+    need = h.conv2d_transpose_workspace_size(d)
+    ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
+    yd = torch.empty(ref.size, dtype=torch.float32, device="cuda")
+    h.conv2d_transpose(d, dev(to_layout(f32_to_bf16_bits(x), "NCHW", "NHWC")), wd, yd, workspace=ws, ws_bytes=need)
+    assert np.array_equal(from_layout(host(yd, np.float32), ref.shape, "NCHW", "NHWC"), ref)
+    # C3D and T3D
+    D, T = 5, 3
+    d3 = alt.conv3d_desc(N, C, D, H, W, K, T, 3, 3, stride=1, pad=1, **lay)
+    f3 = h.conv3d_problem(d3)
+    assert (f3.N, f3.C, f3.K, f3.H, f3.W) == (N * D, T * C, K, H, W)
+    h.tune_conv2d_variants(f3, arena, arena.numel(), max_trials=12, warmup=1, reps=3)
+    x3 = small_ints_f32(1203, (N, C, D, H, W), -3, 3)
+    w3 = small_ints_f32(1204, (K, C, T, 3, 3), -3, 3)
+    ref3 = oracle.conv3d(x3, w3, stride=1, pad=1)
+    wd3 = torch.empty(w3.size, dtype=torch.int16, device="cuda")
+    h.pack_weights3d(d3, dev(f32_to_bf16_bits(w3).reshape(-1)), wd3)
+    need = h.conv3d_workspace_size(d3)
+    ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
+    yd = torch.empty(ref3.size, dtype=torch.float32, device="cuda")
+    xs = np.ascontiguousarray(f32_to_bf16_bits(x3).transpose(0, 2, 3, 4, 1))
+    h.conv3d(d3, dev(xs.reshape(-1)), wd3, yd, workspace=ws, ws_bytes=need)
+    assert np.array_equal(host(yd, np.float32).reshape(N, D, H, W, K).transpose(0, 4, 1, 2, 3), ref3)
+    dt = alt.conv3d_desc(N, C, D, H, W, K, T, 3, 3, stride=2, pad=1, **lay)
+    ft = h.conv3d_transpose_problem(dt)
+    od, oh, ow = h.conv3d_transpose_output_shape(dt)[2:]
+    assert (ft.N, ft.C, ft.K, ft.H, ft.W, ft.stride_h, ft.pad_h) == (N * od, T * C, K, 2 * H - 1, 2 * W - 1, 1, 1)
+    h.tune_conv2d_variants(ft, arena, arena.numel(), max_trials=12, warmup=1, reps=3)
+    wt = small_ints_f32(1205, (C, K, T, 3, 3), -3, 3)
+    reft = oracle.conv3d_transpose(x3, wt, stride=2, pad=1)
+    wdt = torch.empty(wt.size, dtype=torch.int16, device="cuda")
+    h.pack_weights3d_transpose(dt, dev(f32_to_bf16_bits(wt).reshape(-1)), wdt)
+    need = h.conv3d_transpose_workspace_size(dt)
+    ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
+    yd = torch.empty(reft.size, dtype=torch.float32, device="cuda")
+    h.conv3d_transpose(dt, dev(xs.reshape(-1)), wdt, yd, workspace=ws, ws_bytes=need)
+    assert np.array_equal(host(yd, np.float32).reshape(N, od, oh, ow, K).transpose(0, 4, 1, 2, 3), reft)
+
