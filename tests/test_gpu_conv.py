@@ -683,6 +683,39 @@ def test_seeded_random_geometries_exact_integers(h, seed):
             assert np.array_equal(got, ref), (g, name)
 
 
+def test_operands_of_2_gib_and_more(h):
+    """Maximum sizes: an input and an output just over 2 GiB each (beyond the reach of the 32-bit buffer
+    offsets the fast loaders and stores use): the library must take the kernels with 64-bit addressing, and
+    the result must still be the oracle's, bit for bit on integers, at sampled outputs that include both
+    ends of the tensor and the neighbourhood of the 2 GiB boundary."""
+    N, C, H, W, K = 2, 16, 5800, 5800, 8
+    numel = N * C * H * W
+    assert numel * 2 > 2 ** 31 and N * K * H * W * 4 > 2 ** 31
+    lut = f32_to_bf16_bits(np.array([-3, -2, -1, 0, 1, 2, 3, 0], dtype=np.float32))    # a hash of the offset picks the value
+    x = np.empty(numel, dtype=np.uint16)
+    step = 1 << 26
+    for a in range(0, numel, step):
+        e = min(numel, a + step)
+        i = np.arange(a, e, dtype=np.uint32)
+        x[a:e] = lut[((i * np.uint32(2654435761)) >> np.uint32(13)) & np.uint32(7)]
+    x = x.reshape(N, C, H, W)
+    w = f32_to_bf16_bits(small_ints_f32(1301, (K, C, 3, 3), -3, 3))
+    b = small_ints_f32(1302, (K,), -20, 20)
+    d = alt.conv_desc(N, C, H, W, K, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.F32, epilogue=alt.EPI_BIAS | alt.EPI_RELU)
+    n_out = N * K * H * W
+    xd = torch.from_numpy(x.reshape(-1).view(np.int16)).cuda()
+    whole, yd = canary_dev(n_out, np.float32)
+    h.conv2d(d, xd, dev(w.reshape(-1)), yd, bias=dev(b))
+    torch.cuda.synchronize()
+    assert canary_ok(whole, n_out), "wrote outside y"
+    rng = np.random.default_rng(1303)
+    flat = np.concatenate([np.arange(0, 2048), np.arange(n_out - 2048, n_out), np.arange(2 ** 29 - 1024, 2 ** 29 + 1024),
+                           rng.integers(0, n_out, 6000)]).astype(np.int64)
+    ref = oracle.conv2d_at(x, w, flat, stride=1, pad=1, bias=b, relu=True)
+    got = yd[torch.from_numpy(flat).cuda()].cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
 def run_conv3d(h, x, w, stride, pad, dil, xl, wl, yl, in_dtype, out_dtype=alt.F32, bias=None, relu=False, variant=-1,
                ws_slack=0):
     """x (N,C,D,H,W), w (K,C,T,R,S): float32 or uint16 bf16 bits, logical.  Puts x under `xl` slice by

@@ -131,3 +131,33 @@ def test_bert_shapes_sampled(h, g):
         got = host(Cd, np.float32)[flat].astype(np.float64)
         err = float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
         assert err <= 1e-4, (bl, err)
+
+
+@pytest.mark.parametrize("b_layout", ["NK", "KN"])
+def test_operand_of_2_gib_and_more(h, b_layout):
+    """Maximum sizes: A just over 2 GiB (1,050,000 x 1024 bf16), beyond the 32-bit buffer offsets of the fast
+    loaders: the product must still be the oracle's, bit for bit on integers, on sampled rows that include
+    both ends of A and the rows around the 2 GiB boundary."""
+    M, K, N = 1050000, 1024, 64
+    assert M * K * 2 > 2 ** 31
+    lut = f32_to_bf16_bits(np.array([-3, -2, -1, 0, 1, 2, 3, 0], dtype=np.float32))      # a hash of the offset picks the value
+    A = np.empty(M * K, dtype=np.uint16)
+    step = 1 << 26
+    for a in range(0, M * K, step):
+        e = min(M * K, a + step)
+        i = np.arange(a, e, dtype=np.uint32)
+        A[a:e] = lut[((i * np.uint32(2654435761)) >> np.uint32(13)) & np.uint32(7)]
+    A = A.reshape(M, K)
+    B = f32_to_bf16_bits(small_ints_f32(1401, (K, N), -3, 3))
+    d = alt.gemm_desc(M, N, K, in_dtype=alt.BF16, out_dtype=alt.F32, a_layout="MK->MK", b_layout="KN->" + b_layout, c_layout="MN->MN")
+    whole, Cd = canary_dev(M * N, np.float32)
+    h.gemm(d, torch.from_numpy(A.reshape(-1).view(np.int16)).cuda(), dev(to_layout(B, "KN", b_layout)), Cd)
+    torch.cuda.synchronize()
+    assert canary_ok(whole, M * N)
+    rng = np.random.default_rng(1402)
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(M - 300, M), np.arange(2 ** 20 - 150, 2 ** 20 + 150),
+                                     rng.integers(0, M, 1500)]))
+    ref = oracle.gemm(A[rows], B)
+    got = Cd.view(M, N)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(got, ref)
+

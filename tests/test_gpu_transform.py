@@ -164,3 +164,38 @@ def test_unfold_rejects_bad_arguments(h):
     with pytest.raises(alt.AltError) as e:
         h.unfold(alt.F32, (4, 4), 0, 2, 1, a, a)                         # overlapping buffers
     assert e.value.status == 1
+
+
+def test_transform_of_more_than_2_to_the_31_elements(h):
+    """Maximum sizes: a bf16 tensor of 2.2e9 elements (4.4 GB, offsets beyond 32 bits) from NCHW to NHWC.
+    Every element of dst must be the element of src with the same logical index; checked on the
+    first and last 4096 elements of dst and on four million sampled indices, offsets from the
+    closed forms of the two layouts (the source holds a hash of its own offset)."""
+    N, C, H, W = 33, 64, 1024, 1024
+    numel = N * C * H * W
+    assert numel > 2 ** 31
+    def pattern(off):                                   # int64 offsets -> int16 values
+        return (((off * 2654435761) >> 13) & 0xFFFF).to(torch.int16)
+    src = torch.empty(numel, dtype=torch.int16, device="cuda")
+    step = 1 << 27
+    for a in range(0, numel, step):
+        b = min(numel, a + step)
+        src[a:b] = pattern(torch.arange(a, b, dtype=torch.int64, device="cuda"))
+    dst = torch.full((numel + 128,), 0x5A5A, dtype=torch.int16, device="cuda")
+    h.layout_transform(alt.BF16, (N, C, H, W), "NCHW->NCHW", src, "NCHW->NHWC", dst[64:64 + numel])
+    torch.cuda.synchronize()
+    assert bool((dst[:64] == 0x5A5A).all()) and bool((dst[64 + numel:] == 0x5A5A).all()), "wrote outside dst"
+    out = dst[64:64 + numel]
+    def src_off_of_dst(o):                              # NHWC offset -> NCHW offset of the same logical index
+        c = o % C; r = o // C
+        w = r % W; r = r // W
+        hh = r % H; n = r // H
+        return ((n * C + c) * H + hh) * W + w
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    sample = torch.randint(0, numel, (1 << 22,), dtype=torch.int64, device="cuda", generator=gen)
+    edges = torch.cat([torch.arange(0, 4096, dtype=torch.int64, device="cuda"),
+                       torch.arange(numel - 4096, numel, dtype=torch.int64, device="cuda"),
+                       torch.arange(2 ** 31 - 2048, 2 ** 31 + 2048, dtype=torch.int64, device="cuda")])
+    for o in (edges, sample):
+        assert torch.equal(out[o], pattern(src_off_of_dst(o)))
+
