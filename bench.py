@@ -748,6 +748,44 @@ def main():
             per_layout=c3d, speedup_vs_nchw=round(c3d["NCHW"]["us"] / min(v["us"] for v in c3d.values()), 2),
             note="two launches per call (depth unfolding into the workspace, tuned forward kernel)")
 
+        # the transposed 3-D operator (T3D): a decoder-shaped 4x4x4 stride-2 layer, 128 -> 64 channels,
+        # 4 slices of 14x14 -> 8 slices of 28x28, batch 2
+        t3d = {}
+        t3fl = 2.0 * 2 * 128 * 64 * 64 * 4 * 14 * 14          # nominal: every input element meets every filter tap
+        for xl, wl in [("NCHW", "OIHW"), ("NHWC", "OHWI"), ("NCHW32c", "OIHW32o32i")]:
+            d = alt.conv3d_desc(2, 128, 4, 14, 14, 64, 4, 4, 4, stride=2, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + xl)
+            osh = h.conv3d_transpose_output_shape(d)
+            h.tune_conv2d_variants(h.conv3d_transpose_problem(d), arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+            xb = torch.randint(-200, 200, (2 * 4 * 128 * 14 * 14,), dtype=torch.int16, device=dev)
+            wsrc = torch.randint(-200, 200, (128 * 64 * 64,), dtype=torch.int16, device=dev)
+            wb = torch.empty(int(np.prod(h.conv3d_transpose_weight_shape(d))), dtype=torch.int16, device=dev)
+            h.pack_weights3d_transpose(d, wsrc, wb, stream=stream)
+            yb = torch.empty(int(np.prod(osh)), dtype=torch.int16, device=dev)
+            wsb = h.conv3d_transpose_workspace_size(d)
+            wsd = torch.empty(wsb + 16, dtype=torch.uint8, device=dev)
+            gr = capture(lambda st: h.conv3d_transpose(d, xb, wb, yb, workspace=wsd, ws_bytes=wsb, stream=st), 20)
+            us = graph_timed(gr, 20)
+            del gr, xb, wb, yb, wsd
+            t3d[xl] = dict(us=round(us, 2), nominal_tflops=round(t3fl / us / 1e6, 1))
+        extra["conv3d_transpose_c128_k64_4x4x4_s2_4x14x14_b2"] = dict(
+            per_layout=t3d, speedup_vs_nchw=round(t3d["NCHW"]["us"] / min(v["us"] for v in t3d.values()), 2),
+            form="sub-pixel" if h.conv3d_transpose_weight_shape(d)[0] != 64 else "zero insertion",
+            note="sub-pixel form: one forward 3-D convolution of x with 8*K output channels over the merged 3x3x3 window, then the "
+                 "kernel that moves the eight phases into place")
+
+        # a 1-D convolution (C1D: the C2D with H = R = 1): 256 channels, 9 taps, 2048 samples, batch 16, tuned like the others
+        c1shape = alt.conv_desc(16, 256, 1, 2048, 256, 1, 9, in_dtype=alt.BF16, out_dtype=alt.BF16)
+        c1shape.pad_h, c1shape.pad_w = 0, 4
+        c1best, c1rep = h.tune_conv2d(c1shape, arena, arena.numel(), max_trials=0, warmup=3, reps=20)
+        c1fl = 2.0 * 16 * 2048 * 256 * 256 * 9
+        c1names = [c1rep.layout_name[i].value.decode() for i in range(c1rep.n_layouts)]
+        extra["conv1d_c256_k9_l2048_b16"] = dict(
+            variant=h.conv2d_variant_name(c1best, c1best.variant), layout=c1names[int(np.argmin([c1rep.layout_best_us[i] for i in range(c1rep.n_layouts)]))],
+            tuned_us=round(float(c1rep.best_us), 2), default_layout_us=round(float(c1rep.default_us), 2),
+            tflops=round(c1fl / float(c1rep.best_us) / 1e6, 1), trials=c1rep.trials,
+            layout_us=dict(zip(c1names, [round(float(c1rep.layout_best_us[i]), 2) for i in range(c1rep.n_layouts)])))
+
     if want("budget"):
         # ------------------------------- budgeted search against the full one ----
         # the tuner with 48 measurements per layer (variants ranked by the cost estimate, measured best first)

@@ -333,7 +333,15 @@ alt_status_t alt_conv3d_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_
  * indices are multiples of the strides and writes zeros elsewhere (one pass, into the workspace),
  * alt_pack_weights3d_transpose writes w'[k, t*C + c, r, s] = w[c, k, T-1-t, R-1-r, S-1-s], logical
  * (K, T*C, R, S) under plane.w_layout, once from the dense (C,K,T,R,S) filter, and alt_conv2d's
- * kernels do the rest.  Workspace and errors as for alt_conv3d.  Asynchronous on `stream`. */
+ * kernels do the rest.
+ * Sub-pixel form, as for alt_conv2d_transpose: where the output extents are multiples of the strides
+ * and the taps of the stride_d*stride_h*stride_w output phases fit one symmetric window per direction
+ * (4x4x4 at stride 2 with padding 1, 2x2x2 at stride 2, ...), the library instead runs one forward
+ * 3-D convolution of x itself (stride 1) with that many times K output channels into the workspace
+ * and moves the phases into place with a kernel of its own; the packed filter is then the merged
+ * one.  alt_conv3d_transpose_weight_shape reports the logical shape (K', T'*C, R', S') of the packed
+ * filter of the form the descriptor takes (so its size).
+ * Workspace and errors as for alt_conv3d.  Asynchronous on `stream`. */
 alt_status_t alt_conv3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
                                   const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv3d_transpose_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes);
@@ -341,6 +349,7 @@ alt_status_t alt_conv3d_transpose_output_shape(const alt_conv3d_desc_t *d, int64
 alt_status_t alt_pack_weights3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_cktrs,
                                           void *w_packed, void *stream);
 alt_status_t alt_conv3d_transpose_problem(alt_handle_t h, const alt_conv3d_desc_t *d, alt_conv_desc_t *out);
+alt_status_t alt_conv3d_transpose_weight_shape(alt_handle_t h, const alt_conv3d_desc_t *d, int64_t *out_kcrs);
 
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and

@@ -155,7 +155,7 @@ def exported_symbols():
             "alt_conv2d_transpose_output_shape", "alt_conv2d_transpose_weight_shape", "alt_pack_weights_transpose",
             "alt_conv3d", "alt_conv3d_workspace_size", "alt_conv3d_output_shape", "alt_pack_weights3d",
             "alt_conv3d_transpose", "alt_conv3d_transpose_workspace_size", "alt_conv3d_transpose_output_shape",
-            "alt_pack_weights3d_transpose", "alt_conv2d_transpose_problem", "alt_conv3d_problem", "alt_conv3d_transpose_problem", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
+            "alt_pack_weights3d_transpose", "alt_conv2d_transpose_problem", "alt_conv3d_problem", "alt_conv3d_transpose_problem", "alt_conv3d_transpose_weight_shape", "alt_conv2d_workspace_size", "alt_conv2d_output_shape", "alt_pack_weights",
             "alt_conv2d_variant_count", "alt_conv2d_variant_name",
             "alt_gemm", "alt_gemm_workspace_size", "alt_gemm_variant_count", "alt_gemm_variant_name",
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
@@ -424,6 +424,11 @@ class Handle:
         out = ConvDesc()
         _ck(lib().alt_conv3d_transpose_problem(self._h, ctypes.byref(d), ctypes.byref(out)), self._h)
         return out
+
+    def conv3d_transpose_weight_shape(self, d):
+        out = (ctypes.c_int64 * 4)()
+        _ck(lib().alt_conv3d_transpose_weight_shape(self._h, ctypes.byref(d), out), self._h)
+        return tuple(out)
 
     def conv2d_transpose_weight_shape(self, d):
         out = (ctypes.c_int64 * 4)()

@@ -13,7 +13,12 @@
 // with stride-1 zeros between its elements in all three directions, with the filter mirrored,
 // its channel dimensions exchanged and padding dil*(T-1)-pad: the same two kernels, the
 // first reading x[.., d/stride_d, h/stride_h, w/stride_w] where all three divide and zero
-// elsewhere, the second reading the filter back to front.
+// elsewhere, the second reading the filter back to front.  Where the output extents are multiples
+// of the strides and the taps of the stride_d*stride_h*stride_w output phases fit one symmetric
+// window per direction (4x4x4 at stride 2 with padding 1, 2x2x2 at stride 2, ...) it takes the
+// sub-pixel form instead: the phases are stride-1 convolutions of x itself, merged into one
+// forward 3-D convolution with that many times K output channels over the common window, whose
+// result a last kernel moves into place; no inserted zeros are multiplied.
 #include <hip/hip_runtime.h>
 
 #include <string>
@@ -22,6 +27,7 @@
 #include "fast_layout.h"
 #include "layout_eval.h"
 #include "ops.h"
+#include "subpixel.h"
 
 namespace alt {
 namespace {
@@ -158,6 +164,39 @@ __global__ __launch_bounds__(kC3dThreads) void c3d_pack_kernel(PackParams p)
     }
 }
 
+struct Merge3dParams {
+    const void *src;              // dense (C, K, T, R, S)
+    void *dst;
+    BoundLayout ld;               // the merged filter over (K', Tm*C, Rm, Sm) under w_layout
+    int64_t C, K, T, R, S;
+    int32_t sd, sh, sw, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, pm_d, pm_h, pm_w;
+};
+
+// w_m[((pd*sh + ph)*sw + pw)*K + k, a_d*C + c, a, b] = w[c, k, t, r, s] for the tap with
+// t*dil_d = pd + pad_d - sd*(a_d - pm_d), r*dil_h = ph + pad_h - sh*(a - pm_h), s*dil_w = pw + pad_w - sw*(b - pm_w);
+// zero if there is none.  One thread per element.
+template <int ELSZ>
+__global__ __launch_bounds__(kC3dThreads) void c3d_merge_kernel(Merge3dParams p)
+{
+    using E = typename Word<ELSZ>::type;
+    const int64_t n = p.ld.numel;
+    for (int64_t e = blockIdx.x * (int64_t)kC3dThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kC3dThreads) {
+        int64_t idx[ALT_MAX_RANK];
+        int64_t rem = e;
+        for (int d = 3; d >= 0; --d) { idx[d] = rem % p.ld.shape[d]; rem /= p.ld.shape[d]; }
+        const int64_t phase = idx[0] / p.K, k = idx[0] - phase * p.K;
+        const int64_t pd = phase / (p.sh * p.sw), phw = phase - pd * (p.sh * p.sw), ph = phw / p.sw, pw = phw - ph * p.sw;
+        const int64_t ad = idx[1] / p.C, c = idx[1] - ad * p.C;
+        const int64_t nt = pd + p.pad_d - p.sd * (ad - p.pm_d), nr = ph + p.pad_h - p.sh * (idx[2] - p.pm_h),
+                      ns = pw + p.pad_w - p.sw * (idx[3] - p.pm_w);
+        E v = 0;
+        if (nt >= 0 && nr >= 0 && ns >= 0 && nt % p.dil_d == 0 && nr % p.dil_h == 0 && ns % p.dil_w == 0 && nt / p.dil_d < p.T &&
+            nr / p.dil_h < p.R && ns / p.dil_w < p.S)
+            v = ((const E *)p.src)[(((c * p.K + k) * p.T + nt / p.dil_d) * p.R + nr / p.dil_h) * p.S + ns / p.dil_w];
+        ((E *)p.dst)[eval_offset(p.ld, idx)] = v;
+    }
+}
+
 unsigned blocks_for(int64_t n)
 {
     const int64_t b = (n + kC3dThreads - 1) / kC3dThreads;
@@ -237,6 +276,47 @@ alt_status_t transposed_problem(alt_handle_t h, const alt_conv3d_desc_t *d, Prob
     p.zd = d->stride_d; p.zh = q.stride_h; p.zw = q.stride_w;
     p.gather = !(d->T == 1 && d->stride_d == 1 && d->pad_d == 0 && q.stride_h == 1 && q.stride_w == 1);
     return ALT_OK;
+}
+
+// The sub-pixel form of the transposed operator: the merged forward 3-D problem on x itself.
+struct SubPixel3d {
+    alt_conv3d_desc_t m;          // forward descriptor: K' output channels, merged filter extents, stride 1
+    Problem3d pr;                 // its 2-D problem
+    PhaseAxis ad, ah, aw;
+};
+
+// Whether the descriptor takes the sub-pixel form (decided from the descriptor alone, so the weight pack,
+// the workspace size and the call agree).
+bool subpixel3d_plan(alt_handle_t h, const alt_conv3d_desc_t *d, SubPixel3d *out)
+{
+    const alt_conv_desc_t &q = d->plane;
+    if (d->stride_d == 1 && q.stride_h == 1 && q.stride_w == 1) return false;
+    if (d->stride_d > 8 || q.stride_h > 8 || q.stride_w > 8) return false;
+    SubPixel3d &s = *out;
+    s.ad = phase_axis(d->D, d->T, d->stride_d, d->pad_d, d->dil_d);
+    s.ah = phase_axis(q.H, q.R, q.stride_h, q.pad_h, q.dil_h);
+    s.aw = phase_axis(q.W, q.S, q.stride_w, q.pad_w, q.dil_w);
+    if (!s.ad.ok || !s.ah.ok || !s.aw.ok) return false;
+    s.m = *d;
+    s.m.plane.K = q.K * d->stride_d * q.stride_h * q.stride_w;
+    s.m.plane.R = s.ah.taps;
+    s.m.plane.S = s.aw.taps;
+    s.m.plane.stride_h = s.m.plane.stride_w = 1;
+    s.m.plane.dil_h = s.m.plane.dil_w = 1;
+    s.m.plane.pad_h = s.ah.pad;
+    s.m.plane.pad_w = s.aw.pad;
+    s.m.T = s.ad.taps;
+    s.m.stride_d = 1;
+    s.m.dil_d = 1;
+    s.m.pad_d = s.ad.pad;
+    // the filter and output layouts must take the merged extents
+    BoundLayout b;
+    std::string err;
+    const int64_t ws[4] = {s.m.plane.K, q.C * s.m.T, s.m.plane.R, s.m.plane.S};
+    const int64_t ys[4] = {q.N * s.ad.outq, s.m.plane.K, s.ah.outq, s.aw.outq};
+    if (bind_layout(&q.w_layout, 4, ws, &b, &err) != ALT_OK) return false;
+    if (bind_layout(&q.y_layout, 4, ys, &b, &err) != ALT_OK) return false;
+    return forward_problem(h, &s.m, &s.pr) == ALT_OK && s.pr.OD == s.ad.outq;
 }
 
 size_t gathered_bytes(const Problem3d &p)
@@ -336,6 +416,35 @@ alt_status_t run3d(alt_handle_t h, const Problem3d &pr, const void *x, const voi
     return alt_conv2d(h, &f, workspace, w_packed, bias, y, (char *)workspace + xu_bytes, ws_bytes - xu_bytes, stream);
 }
 
+size_t subpixel3d_y_bytes(const SubPixel3d &s)
+{
+    return round256((size_t)(s.pr.f.N * s.pr.f.K * s.ah.outq * s.aw.outq) * dtype_size(s.pr.f.out_dtype));
+}
+size_t subpixel3d_bias_bytes(const SubPixel3d &s) { return round256((size_t)s.pr.f.K * sizeof(float)); }
+
+// Workspace: the phase-major output y', the replicated bias, then what the forward 3-D problem wants.
+alt_status_t run_subpixel3d(alt_handle_t h, const alt_conv3d_desc_t *d, const SubPixel3d &s, const void *x, const void *w_packed,
+                            const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const alt_conv_desc_t &q = d->plane;
+    const size_t yb = subpixel3d_y_bytes(s), bb = subpixel3d_bias_bytes(s);
+    if (!workspace || ws_bytes < yb + bb)
+        return fail(h, ALT_WORKSPACE_TOO_SMALL, "alt_conv3d_transpose: the workspace must hold the phase-major output (%zu bytes)", yb + bb);
+    if ((uintptr_t)workspace % 16 || (uintptr_t)y % 16) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: workspace and y must be 16-byte aligned");
+    if ((q.epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: ALT_EPI_BIAS without a bias");
+    hipStream_t st = (hipStream_t)stream;
+    float *bias_m = (float *)((char *)workspace + yb);
+    alt_status_t st_;
+    if (q.epilogue & ALT_EPI_BIAS)
+        if ((st_ = phase_bias(h, bias, bias_m, q.K, s.pr.f.K, st)) != ALT_OK) return st_;
+    st_ = run3d(h, s.pr, x, w_packed, (q.epilogue & ALT_EPI_BIAS) ? bias_m : nullptr, workspace, (char *)workspace + yb + bb,
+                ws_bytes - yb - bb, stream, "alt_conv3d_transpose");
+    if (st_ != ALT_OK) return st_;
+    return phase_shuffle(h, &q.y_layout, q.N, q.K, s.ad.outq, s.ah.outq, s.aw.outq, d->stride_d, q.stride_h, q.stride_w,
+                         (int)dtype_size(q.out_dtype), workspace, y, st);
+}
+
 }  // namespace
 }  // namespace alt
 
@@ -374,8 +483,10 @@ extern "C" alt_status_t alt_conv3d_transpose_problem(alt_handle_t h, const alt_c
     if (!d || !out) return fail(h, ALT_INVALID_ARG, "null argument");
     Problem3d p;
     const alt_status_t s = transposed_problem(h, d, &p);
-    if (s == ALT_OK) *out = p.f;
-    return s;
+    if (s != ALT_OK) return s;
+    SubPixel3d sp;
+    *out = subpixel3d_plan(h, d, &sp) ? sp.pr.f : p.f;
+    return ALT_OK;
 }
 
 extern "C" alt_status_t alt_conv3d_workspace_size(alt_handle_t h, const alt_conv3d_desc_t *d, size_t *bytes)
@@ -424,14 +535,64 @@ extern "C" alt_status_t alt_conv3d_transpose_workspace_size(alt_handle_t h, cons
     if (!d || !bytes) return fail(h, ALT_INVALID_ARG, "null argument");
     Problem3d p;
     const alt_status_t s = transposed_problem(h, d, &p);
-    return s != ALT_OK ? s : workspace_size(h, p, bytes);
+    if (s != ALT_OK) return s;
+    SubPixel3d sp;
+    if (subpixel3d_plan(h, d, &sp)) {
+        size_t inner = 0;
+        const alt_status_t s2 = workspace_size(h, sp.pr, &inner);
+        if (s2 != ALT_OK) return s2;
+        *bytes = subpixel3d_y_bytes(sp) + subpixel3d_bias_bytes(sp) + inner;
+        return ALT_OK;
+    }
+    return workspace_size(h, p, bytes);
 }
 
 extern "C" alt_status_t alt_pack_weights3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *w_cktrs,
                                                      void *w_packed, void *stream)
 {
     if (!h) return ALT_INVALID_ARG;
-    return pack3d(h, d, w_cktrs, w_packed, stream, true, "alt_pack_weights3d_transpose");
+    if (!d || !w_cktrs || !w_packed) return fail(h, ALT_INVALID_ARG, "alt_pack_weights3d_transpose: null argument");
+    if (d->plane.in_dtype != ALT_F32 && d->plane.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_pack_weights3d_transpose: bad dtype");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    Problem3d chk;
+    const alt_status_t cs = transposed_problem(h, d, &chk);
+    if (cs != ALT_OK) return cs;
+    SubPixel3d sp;
+    if (!subpixel3d_plan(h, d, &sp)) return pack3d(h, d, w_cktrs, w_packed, stream, true, "alt_pack_weights3d_transpose");
+    const alt_conv_desc_t &q = d->plane;
+    Merge3dParams m;
+    const int64_t msh[4] = {sp.m.plane.K, q.C * sp.m.T, sp.m.plane.R, sp.m.plane.S};
+    std::string err;
+    const alt_status_t ms = bind_layout(&q.w_layout, 4, msh, &m.ld, &err);
+    if (ms != ALT_OK) return fail(h, ms, "w_layout: %s", err.c_str());
+    m.src = w_cktrs;
+    m.dst = w_packed;
+    m.C = q.C; m.K = q.K; m.T = d->T; m.R = q.R; m.S = q.S;
+    m.sd = d->stride_d; m.sh = q.stride_h; m.sw = q.stride_w;
+    m.pad_d = d->pad_d; m.pad_h = q.pad_h; m.pad_w = q.pad_w;
+    m.dil_d = d->dil_d; m.dil_h = q.dil_h; m.dil_w = q.dil_w;
+    m.pm_d = sp.ad.pad; m.pm_h = sp.ah.pad; m.pm_w = sp.aw.pad;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype_size(q.in_dtype) == 2) hipLaunchKernelGGL(c3d_merge_kernel<2>, dim3(blocks_for(m.ld.numel)), dim3(kC3dThreads), 0, st, m);
+    else hipLaunchKernelGGL(c3d_merge_kernel<4>, dim3(blocks_for(m.ld.numel)), dim3(kC3dThreads), 0, st, m);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+extern "C" alt_status_t alt_conv3d_transpose_weight_shape(alt_handle_t h, const alt_conv3d_desc_t *d, int64_t *out)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!d || !out) return fail(h, ALT_INVALID_ARG, "null argument");
+    Problem3d p;
+    const alt_status_t s = transposed_problem(h, d, &p);
+    if (s != ALT_OK) return s;
+    SubPixel3d sp;
+    if (subpixel3d_plan(h, d, &sp)) {
+        out[0] = sp.m.plane.K; out[1] = d->plane.C * sp.m.T; out[2] = sp.m.plane.R; out[3] = sp.m.plane.S;
+    } else {
+        out[0] = d->plane.K; out[1] = d->plane.C * d->T; out[2] = d->plane.R; out[3] = d->plane.S;
+    }
+    return ALT_OK;
 }
 
 extern "C" alt_status_t alt_conv3d_transpose(alt_handle_t h, const alt_conv3d_desc_t *d, const void *x, const void *w_packed,
@@ -442,5 +603,8 @@ extern "C" alt_status_t alt_conv3d_transpose(alt_handle_t h, const alt_conv3d_de
     if (d->plane.in_dtype != ALT_F32 && d->plane.in_dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_conv3d_transpose: bad dtype");
     Problem3d p;
     const alt_status_t s = transposed_problem(h, d, &p);
-    return s != ALT_OK ? s : run3d(h, p, x, w_packed, bias, y, workspace, ws_bytes, stream, "alt_conv3d_transpose");
+    if (s != ALT_OK) return s;
+    SubPixel3d sp;
+    if (subpixel3d_plan(h, d, &sp)) return run_subpixel3d(h, d, sp, x, w_packed, bias, y, workspace, ws_bytes, stream);
+    return run3d(h, p, x, w_packed, bias, y, workspace, ws_bytes, stream, "alt_conv3d_transpose");
 }

@@ -46,6 +46,11 @@ alt_status_t conv_problem(alt_handle_t h, const alt_conv_desc_t *d, const void *
 alt_status_t gemm_problem(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, const void *B, void *C,
                           Problem *pb);
 
+// t2d.hip: the kernels that put the output phases of a sub-pixel transposed convolution into place
+alt_status_t phase_shuffle(alt_handle_t h, const alt_layout_t *layout, int64_t N, int64_t K, int64_t ODq, int64_t OHq, int64_t OWq,
+                           int sd, int sh, int sw, int elsz, const void *src, void *dst, hipStream_t st);
+alt_status_t phase_bias(alt_handle_t h, const float *bias, float *out, int64_t K, int64_t n, hipStream_t st);
+
 alt_status_t transform_bound(alt_handle_t h, int elsz, const BoundLayout &ls, const void *src,
                              const BoundLayout &ld, void *dst, hipStream_t st);
 

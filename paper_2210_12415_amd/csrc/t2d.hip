@@ -14,6 +14,7 @@
 #include "fast_layout.h"
 #include "layout_eval.h"
 #include "ops.h"
+#include "subpixel.h"
 
 namespace alt {
 namespace {
@@ -172,36 +173,6 @@ alt_status_t forward_desc(alt_handle_t h, const alt_conv_desc_t *d, alt_conv_des
 // when the output extents are multiples of the strides and the symmetric padding -delta_min
 // yields exactly OH/stride_h by OW/stride_w outputs (4x4 at stride 2 with padding 1, 2x2 at
 // stride 2, 6x6 at stride 2 with padding 2, 8x8 at stride 4 with padding 2, ...).
-struct PhaseAxis {
-    int32_t taps, pad;            // extent and padding of the merged filter along this axis
-    int64_t outq;                 // outputs per phase
-    bool ok;
-};
-
-PhaseAxis phase_axis(int64_t in, int64_t taps, int stride, int pad, int dil)
-{
-    PhaseAxis a{0, 0, 0, false};
-    const int64_t out = (in - 1) * stride - 2 * (int64_t)pad + (int64_t)dil * (taps - 1) + 1;
-    if (out < 1 || out % stride) return a;
-    int64_t lo = 0, hi = 0;
-    bool any = false;
-    for (int ph = 0; ph < stride; ++ph)
-        for (int64_t r = 0; r < taps; ++r) {
-            const int64_t num = ph + pad - r * dil;
-            if (((num % stride) + stride) % stride) continue;
-            const int64_t delta = (num - (((num % stride) + stride) % stride)) / stride;
-            lo = any ? (delta < lo ? delta : lo) : delta;
-            hi = any ? (delta > hi ? delta : hi) : delta;
-            any = true;
-        }
-    if (!any || lo > 0 || hi - lo + 1 > 64) return a;
-    a.taps = (int32_t)(hi - lo + 1);
-    a.pad = (int32_t)-lo;
-    a.outq = out / stride;
-    a.ok = in + 2 * (int64_t)a.pad - a.taps + 1 == a.outq;
-    return a;
-}
-
 struct SubPixelPlan {
     alt_conv_desc_t f;            // the merged stride-1 problem on x: K' = stride_h*stride_w*K channels out
     PhaseAxis ah, aw;
@@ -271,11 +242,11 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_bias_kernel(const float *bias
 }
 
 struct ShuffleParams {
-    const void *src;              // y' over (N, K', OH/sh, OW/sw) under y_layout
-    void *dst;                    // y over (N, K, OH, OW) under y_layout
+    const void *src;              // y' over (N*OD/sd, K', OH/sh, OW/sw) under y_layout
+    void *dst;                    // y over (N*OD, K, OH, OW) under y_layout (OD = sd = 1 for the 2-D operator)
     BoundLayout ls, ld;
-    int32_t sh, sw;
-    int64_t K;
+    int32_t sd, sh, sw, pad_;
+    int64_t K, OD;
 };
 
 // One thread per element of y, any layout.
@@ -290,7 +261,9 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_shuffle_kernel(ShuffleParams 
         for (int d = 3; d >= 0; --d) { idx[d] = r % p.ld.shape[d]; r /= p.ld.shape[d]; }
         const int64_t out = eval_offset(p.ld, idx);
         const int64_t q = idx[2] / p.sh, ph = idx[2] - q * p.sh, c = idx[3] / p.sw, pw = idx[3] - c * p.sw;
-        idx[1] += (ph * p.sw + pw) * p.K;
+        const int64_t img = idx[0] / p.OD, od = idx[0] - img * p.OD, qd = od / p.sd, pd = od - qd * p.sd;
+        idx[0] = img * (p.OD / p.sd) + qd;
+        idx[1] += ((pd * p.sh + ph) * p.sw + pw) * p.K;
         idx[2] = q;
         idx[3] = c;
         ((E *)p.dst)[out] = ((const E *)p.src)[eval_offset(p.ls, idx)];
@@ -301,8 +274,8 @@ struct ShuffleFastParams {
     const void *src;
     void *dst;
     FastLayout ls, ld;
-    FastDiv by_sh, by_sw;
-    uint32_t K, nvec;
+    FastDiv by_sh, by_sw, by_sd, by_od;
+    uint32_t K, nvec, ODq, pad_;
 };
 
 // The same for separable layouts with fewer than 2^31 elements, walked in the order of y's
@@ -320,7 +293,10 @@ __global__ __launch_bounds__(kT2dThreads) void t2d_shuffle_fast_kernel(ShuffleFa
         }
         const uint32_t q = fast_div(idx[2], p.by_sh), ph = idx[2] - q * p.by_sh.d;
         const uint32_t c = fast_div(idx[3], p.by_sw), pw = idx[3] - c * p.by_sw.d;
-        idx[1] += (ph * p.by_sw.d + pw) * p.K;
+        const uint32_t img = fast_div(idx[0], p.by_od), od = idx[0] - img * p.by_od.d;
+        const uint32_t qd = fast_div(od, p.by_sd), pd = od - qd * p.by_sd.d;
+        idx[0] = img * p.ODq + qd;
+        idx[1] += ((pd * p.by_sh.d + ph) * p.by_sw.d + pw) * p.K;
         idx[2] = q;
         idx[3] = c;
         uint32_t so = 0;
@@ -350,46 +326,37 @@ size_t subpixel_y_bytes(const SubPixelPlan &s)
 }
 size_t subpixel_bias_bytes(const SubPixelPlan &s) { return round256((size_t)s.f.K * sizeof(float)); }
 
-alt_status_t run_subpixel(alt_handle_t h, const alt_conv_desc_t *d, const SubPixelPlan &s, const void *x, const void *w_packed,
-                          const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream)
+}  // namespace
+
+// y[(n, qd*sd + pd), k, q*sh + ph, p*sw + pw] = y'[(n, qd), ((pd*sh + ph)*sw + pw)*K + k, q, p], both under `layout`
+// (y' over (N*ODq, sd*sh*sw*K, OHq, OWq); ODq = sd = 1 for the 2-D operator).
+alt_status_t phase_shuffle(alt_handle_t h, const alt_layout_t *layout, int64_t N, int64_t K, int64_t ODq, int64_t OHq, int64_t OWq,
+                           int sd, int sh, int sw, int elsz, const void *src, void *dst, hipStream_t st)
 {
-    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
-    const size_t yb = subpixel_y_bytes(s), bb = subpixel_bias_bytes(s);
-    if (!workspace || ws_bytes < yb + bb)
-        return fail(h, ALT_WORKSPACE_TOO_SMALL, "alt_conv2d_transpose: the workspace must hold the phase-major output (%zu bytes)", yb + bb);
-    if ((uintptr_t)workspace % 16 || (uintptr_t)y % 16) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: workspace and y must be 16-byte aligned");
-    if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: ALT_EPI_BIAS without a bias");
     ShuffleParams p;
-    const int64_t qs[4] = {s.f.N, s.f.K, s.ah.outq, s.aw.outq};
-    const int64_t os[4] = {d->N, d->K, s.ah.outq * d->stride_h, s.aw.outq * d->stride_w};
+    const int64_t qs[4] = {N * ODq, K * sd * sh * sw, OHq, OWq};
+    const int64_t os[4] = {N * ODq * sd, K, OHq * sh, OWq * sw};
     std::string err;
     alt_status_t st_;
-    if ((st_ = bind_layout(&d->y_layout, 4, qs, &p.ls, &err)) != ALT_OK) return fail(h, st_, "y_layout (phase-major output): %s", err.c_str());
-    if ((st_ = bind_layout(&d->y_layout, 4, os, &p.ld, &err)) != ALT_OK) return fail(h, st_, "y_layout: %s", err.c_str());
-    hipStream_t st = (hipStream_t)stream;
-    float *bias_m = (float *)((char *)workspace + yb);
-    if (d->epilogue & ALT_EPI_BIAS) {
-        const int n = (int)s.f.K;
-        hipLaunchKernelGGL(t2d_bias_kernel, dim3((n + kT2dThreads - 1) / kT2dThreads), dim3(kT2dThreads), 0, st, bias, bias_m, (int)d->K, n);
-        ALT_CHECK_HIP(h, hipGetLastError());
-    }
-    st_ = alt_conv2d(h, &s.f, x, w_packed, (d->epilogue & ALT_EPI_BIAS) ? bias_m : nullptr, workspace,
-                     (char *)workspace + yb + bb, ws_bytes - yb - bb, stream);
-    if (st_ != ALT_OK) return st_;
-    p.src = workspace;
-    p.dst = y;
-    p.sh = d->stride_h;
-    p.sw = d->stride_w;
-    p.K = d->K;
-    const int elsz = (int)dtype_size(d->out_dtype);
+    if ((st_ = bind_layout(layout, 4, qs, &p.ls, &err)) != ALT_OK) return fail(h, st_, "y_layout (phase-major output): %s", err.c_str());
+    if ((st_ = bind_layout(layout, 4, os, &p.ld, &err)) != ALT_OK) return fail(h, st_, "y_layout: %s", err.c_str());
+    p.src = src;
+    p.dst = dst;
+    p.sd = sd; p.sh = sh; p.sw = sw; p.pad_ = 0;
+    p.K = K;
+    p.OD = ODq * sd;
     ShuffleFastParams q;
     if (fast_layout(p.ls, &q.ls) && fast_layout(p.ld, &q.ld)) {
-        const int vec = shuffle_vec(p.ls, p.ld, elsz, d->K, workspace, y);
-        q.src = workspace;
-        q.dst = y;
-        q.by_sh = make_fastdiv((uint32_t)d->stride_h);
-        q.by_sw = make_fastdiv((uint32_t)d->stride_w);
-        q.K = (uint32_t)d->K;
+        const int vec = shuffle_vec(p.ls, p.ld, elsz, K, src, dst);
+        q.src = src;
+        q.dst = dst;
+        q.by_sh = make_fastdiv((uint32_t)sh);
+        q.by_sw = make_fastdiv((uint32_t)sw);
+        q.by_sd = make_fastdiv((uint32_t)sd);
+        q.by_od = make_fastdiv((uint32_t)p.OD);
+        q.K = (uint32_t)K;
+        q.ODq = (uint32_t)ODq;
+        q.pad_ = 0;
         q.nvec = (uint32_t)(p.ld.numel / vec);
         const dim3 grid(blocks_for(q.nvec)), block(kT2dThreads);
         if (elsz == 2 && vec == 8) hipLaunchKernelGGL((t2d_shuffle_fast_kernel<2, 8>), grid, block, 0, st, q);
@@ -403,6 +370,38 @@ alt_status_t run_subpixel(alt_handle_t h, const alt_conv_desc_t *d, const SubPix
     }
     ALT_CHECK_HIP(h, hipGetLastError());
     return ALT_OK;
+}
+
+// bias'[j*K + k] = bias[k] for the n = phases*K entries of `out`
+alt_status_t phase_bias(alt_handle_t h, const float *bias, float *out, int64_t K, int64_t n, hipStream_t st)
+{
+    hipLaunchKernelGGL(t2d_bias_kernel, dim3((unsigned)((n + kT2dThreads - 1) / kT2dThreads)), dim3(kT2dThreads), 0, st, bias, out,
+                       (int)K, (int)n);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
+
+namespace {
+
+alt_status_t run_subpixel(alt_handle_t h, const alt_conv_desc_t *d, const SubPixelPlan &s, const void *x, const void *w_packed,
+                          const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    const size_t yb = subpixel_y_bytes(s), bb = subpixel_bias_bytes(s);
+    if (!workspace || ws_bytes < yb + bb)
+        return fail(h, ALT_WORKSPACE_TOO_SMALL, "alt_conv2d_transpose: the workspace must hold the phase-major output (%zu bytes)", yb + bb);
+    if ((uintptr_t)workspace % 16 || (uintptr_t)y % 16) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: workspace and y must be 16-byte aligned");
+    if ((d->epilogue & ALT_EPI_BIAS) && !bias) return fail(h, ALT_INVALID_ARG, "alt_conv2d_transpose: ALT_EPI_BIAS without a bias");
+    hipStream_t st = (hipStream_t)stream;
+    float *bias_m = (float *)((char *)workspace + yb);
+    alt_status_t st_;
+    if (d->epilogue & ALT_EPI_BIAS)
+        if ((st_ = phase_bias(h, bias, bias_m, d->K, s.f.K, st)) != ALT_OK) return st_;
+    st_ = alt_conv2d(h, &s.f, x, w_packed, (d->epilogue & ALT_EPI_BIAS) ? bias_m : nullptr, workspace,
+                     (char *)workspace + yb + bb, ws_bytes - yb - bb, stream);
+    if (st_ != ALT_OK) return st_;
+    return phase_shuffle(h, &d->y_layout, d->N, d->K, 1, s.ah.outq, s.aw.outq, 1, d->stride_h, d->stride_w,
+                         (int)dtype_size(d->out_dtype), workspace, y, st);
 }
 
 }  // namespace

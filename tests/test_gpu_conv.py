@@ -834,7 +834,9 @@ def test_conv3d_one_tap_is_the_2d_call_and_errors(h):
 
 @pytest.mark.parametrize("layouts", [("NHWC", "OHWI", "NHWC"), ("NCHW", "OIHW", "NCHW"), ("NCHW16c", "OIHW16o16i", "NCHW16c")])
 @pytest.mark.parametrize("geometry", [(1, 1, 1), (2, 1, 1), ((2, 1, 3), (1, 0, 2), (1, 1, 1)), ((1, 2, 2), (2, 1, 0), (2, 1, 2)),
-                                      ((2, 2, 2), (0, 0, 0), (1, 1, 1))], ids=lambda g: "s%s_p%s_d%s" % g)
+                                      ((2, 2, 2), (0, 0, 0), (1, 1, 1)), ((1, 2, 1), (1, 0, 1), (1, 1, 1)), ((3, 2, 3), (0, 0, 0), (1, 1, 1)),
+                                      ((1, 2, 1), (1, 1, 1), (1, 3, 1))],
+                         ids=lambda g: "s%s_p%s_d%s" % g)
 def test_conv3d_transpose_exact_integers(h, layouts, geometry):
     """alt_conv3d_transpose (the T3D of Section 6.1) against the oracle's scatter definition, bf16 integers,
     bit for bit: per-direction strides, padding and dilation, three slice layouts, fp32 output and bf16 output
@@ -849,6 +851,7 @@ def test_conv3d_transpose_exact_integers(h, layouts, geometry):
     xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
     xs = np.ascontiguousarray(xb.transpose(0, 2, 1, 3, 4)).reshape(N * D, C, H, W)
     xd = dev(to_layout(xs, "NCHW", xl))
+    forms = set()
     for out_dtype, bias, relu in [(alt.F32, None, False), (alt.BF16, b, True)]:
         epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
         d = alt.conv3d_desc(N, C, D, H, W, K, T, R, S, stride=stride, pad=pad, dil=dil, in_dtype=alt.BF16, out_dtype=out_dtype,
@@ -856,10 +859,14 @@ def test_conv3d_transpose_exact_integers(h, layouts, geometry):
         oshape = h.conv3d_transpose_output_shape(d)
         assert oshape == ref.shape
         _, _, OD, OH, OW = oshape
-        wd = torch.empty_like(dev(wb.reshape(-1)))
+        wshape = h.conv3d_transpose_weight_shape(d)
+        whole_w, wd = canary_dev(int(np.prod(wshape)), np.uint16)
         h.pack_weights3d_transpose(d, dev(wb.reshape(-1)), wd)
-        w2 = np.ascontiguousarray(wb[:, :, ::-1, ::-1, ::-1].transpose(1, 2, 0, 3, 4)).reshape(K, T * C, R, S)
-        assert np.array_equal(host(wd, np.uint16), to_layout(w2, "OIHW", wl).reshape(-1))
+        assert canary_ok(whole_w, int(np.prod(wshape))), "wrote outside the packed filter"
+        forms.add("zero insertion" if wshape == (K, T * C, R, S) else "sub-pixel")
+        if wshape == (K, T * C, R, S):      # zero-insertion form: the mirrored, channel-swapped filter
+            w2 = np.ascontiguousarray(wb[:, :, ::-1, ::-1, ::-1].transpose(1, 2, 0, 3, 4)).reshape(K, T * C, R, S)
+            assert np.array_equal(host(wd, np.uint16), to_layout(w2, "OIHW", wl).reshape(-1))
         ydt = np.float32 if out_dtype == alt.F32 else np.uint16
         n_out = int(np.prod(oshape))
         whole, yd = canary_dev(n_out, ydt)
@@ -871,6 +878,9 @@ def test_conv3d_transpose_exact_integers(h, layouts, geometry):
         got = from_layout(got, (N * OD, K, OH, OW), "NCHW", yl).reshape(N, OD, K, OH, OW).transpose(0, 2, 1, 3, 4)
         want = ref if bias is None else f32_to_bf16_bits(np.maximum(ref + b[None, :, None, None, None], np.float32(0)))
         assert np.array_equal(got, want)
+    # filter 3 x 2 x 3: the sub-pixel form needs extents that the strides divide in every direction
+    sub = stride in ((1, 2, 1), (3, 2, 3))
+    assert forms == ({"sub-pixel"} if sub else {"zero insertion"}), (geometry, forms)
 
 
 def test_conv3d_transpose_gaussian_within_tolerance_and_errors(h):
@@ -884,7 +894,8 @@ def test_conv3d_transpose_gaussian_within_tolerance_and_errors(h):
                         y_layout="NCHW->NHWC")
     assert h.conv3d_transpose_output_shape(d) == ref.shape == (1, 32, 6, 12, 10)
     xd = dev(np.ascontiguousarray(x.transpose(0, 2, 3, 4, 1)).reshape(-1))
-    wd = torch.empty_like(dev(w.reshape(-1)))
+    assert h.conv3d_transpose_weight_shape(d) == (8 * K, 3 * C, 3, 3)          # the sub-pixel form
+    wd = torch.empty(8 * K * 3 * C * 9, dtype=torch.int16, device="cuda")
     h.pack_weights3d_transpose(d, dev(w.reshape(-1)), wd)
     need = h.conv3d_transpose_workspace_size(d)
     ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")

@@ -347,7 +347,7 @@ def test_tuning_the_problem_behind_the_transposed_and_3d_operators(h):
     h.tune_conv2d_variants(ft, arena, arena.numel(), max_trials=12, warmup=1, reps=3)
     wt = small_ints_f32(1205, (C, K, T, 3, 3), -3, 3)
     reft = oracle.conv3d_transpose(x3, wt, stride=2, pad=1)
-    wdt = torch.empty(wt.size, dtype=torch.int16, device="cuda")
+    wdt = torch.empty(int(np.prod(h.conv3d_transpose_weight_shape(dt))), dtype=torch.int16, device="cuda")
     h.pack_weights3d_transpose(dt, dev(f32_to_bf16_bits(wt).reshape(-1)), wdt)
     need = h.conv3d_transpose_workspace_size(dt)
     ws = torch.empty(need // 4 + 4, dtype=torch.float32, device="cuda")
