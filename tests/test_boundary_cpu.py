@@ -280,6 +280,37 @@ def test_conv_transpose_sub_pixel_form_host_side(oracle):
     assert h.conv2d_transpose_weight_shape(d) == (8, 16, 2, 2)          # 9*8 output channels are no multiple of 16
 
 
+def test_conv3d_transpose_sub_pixel_form_host_side(oracle):
+    """The 3-D sub-pixel form: which descriptors take it, and, with the oracle alone, that the forward 3-D
+    convolution of x with the merged filter holds the transposed result phase by phase."""
+    h = alt.Handle()
+    K, C = 4, 3
+    assert h.conv3d_transpose_weight_shape(alt.conv3d_desc(2, C, 3, 4, 5, K, 3, 3, 3, stride=2, pad=1)) == (K, 3 * C, 3, 3)
+    assert h.conv3d_transpose_weight_shape(alt.conv3d_desc(2, C, 3, 4, 5, K, 2, 2, 2, stride=2, pad=0)) == (8 * K, C, 1, 1)
+    D, H, W, T, R, S, stride, pad = 3, 4, 5, 4, 4, 4, 2, 1
+    d = alt.conv3d_desc(2, C, D, H, W, K, T, R, S, stride=stride, pad=pad)
+    assert h.conv3d_transpose_weight_shape(d) == (8 * K, 3 * C, 3, 3)
+    x = small_ints_f32(711, (2, C, D, H, W), -3, 3)
+    w = small_ints_f32(712, (C, K, T, R, S), -3, 3)
+    y = oracle.conv3d_transpose(x, w, stride=stride, pad=pad)
+    pm, Tm = 1, 3
+    wm = np.zeros((8 * K, C, Tm, Tm, Tm), np.float32)
+    for pd in range(2):
+        for ph in range(2):
+            for pw in range(2):
+                for a in range(Tm):
+                    for b in range(Tm):
+                        for c in range(Tm):
+                            nt, nr, ns = pd + pad - stride * (a - pm), ph + pad - stride * (b - pm), pw + pad - stride * (c - pm)
+                            if 0 <= nt < T and 0 <= nr < R and 0 <= ns < S:
+                                j = (pd * 2 + ph) * 2 + pw
+                                wm[j * K:(j + 1) * K, :, a, b, c] = w[:, :, nt, nr, ns].T
+    yq = oracle.conv3d(x, wm, stride=1, pad=pm)
+    assert yq.shape == (2, 8 * K, D, H, W)
+    back = yq.reshape(2, 2, 2, 2, K, D, H, W).transpose(0, 4, 5, 1, 6, 2, 7, 3).reshape(y.shape)
+    assert np.array_equal(back, y)
+
+
 def test_conv3d_host_side(oracle):
     """Output shape of the 3-D convolution against the shape of the oracle's result, and the argument
     checks that need no device."""
