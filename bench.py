@@ -37,7 +37,9 @@ PEAK_HBM_GBPS = 8000.0
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    # (a step is ~27 us: 2000 of them keep the fixed costs of a timed region, a few hundred us of runtime
+    # housekeeping after the launches before it, below one percent)
+    ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="skip the extra sections")
     ap.add_argument("--sections", default="all",
