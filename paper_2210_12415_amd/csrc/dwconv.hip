@@ -11,6 +11,11 @@
 //    channel-last weights): a thread owns eight channels of one output pixel,
 //    every access is 16 bytes;
 //    (3x3 filters without dilation get a register-tiled version of it);
+//  * row kernel: bf16 tensors whose width is contiguous on activations and
+//    output (NCHW), 3x3 filters with padding 1 along the width: a thread owns
+//    four consecutive outputs of one row of one channel plane, reads the
+//    input columns under them as 8-byte vectors (plus the two edge columns)
+//    and stores 8 bytes;
 //  * element kernel: any separable layout; a thread owns one output element,
 //    threads run along the output's contiguous dimension.
 #include <hip/hip_runtime.h>
@@ -222,6 +227,82 @@ __global__ __launch_bounds__(kDwThreads, STRIDE == 1 ? 4 : 3) void dwconv_vec8_3
     }
 }
 
+// bf16 in and out, width contiguous, 3x3 without dilation, padding 1 along the width, W and OW multiples of four
+// (checked by the host together with the alignment of every plane and row).  A thread computes outputs
+// (oh, ow0 .. ow0+3) of one (n, c) plane from input columns ow0*STRIDE - 1 .. : the columns from ow0*STRIDE on come
+// as aligned 8-byte vectors (wholly inside or wholly outside the row), the one before them as a scalar.
+template <int STRIDE>
+__global__ __launch_bounds__(kDwThreads) void dwconv_rows_3x3_kernel(const DwParams p)
+{
+    typedef uint32_t w2_t __attribute__((ext_vector_type(2)));
+    constexpr int TW = 4, NCOL = (TW - 1) * STRIDE + 3;    // 6 columns at stride 1, 9 at stride 2
+    constexpr int NV = (NCOL - 1 + 3) / 4;                 // vectors that cover columns 1 .. NCOL-1
+    const uint32_t OWB = (uint32_t)p.OW / TW;
+    const int64_t total = (int64_t)p.N * p.C * p.OH * OWB;
+    const int64_t sxh = p.xh.si, syh = p.yh.si;
+    for (int64_t e = blockIdx.x * (int64_t)kDwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kDwThreads) {
+        int c, ow0, oh, n;
+        if (total <= 0x7fffffff) {
+            uint32_t r = (uint32_t)e;
+            ow0 = (int)(r % OWB) * TW; r /= OWB;
+            oh = (int)(r % (uint32_t)p.OH); r /= (uint32_t)p.OH;
+            c = (int)(r % (uint32_t)p.C);
+            n = (int)(r / (uint32_t)p.C);
+        } else {
+            int64_t r = e;
+            ow0 = (int)(r % OWB) * TW; r /= OWB;
+            oh = (int)(r % p.OH); r /= p.OH;
+            c = (int)(r % p.C);
+            n = (int)(r / p.C);
+        }
+        const uint16_t *xb = (const uint16_t *)p.x + dim2_off(p.xn, n) + dim2_off(p.xc, c);
+        const uint16_t *wb = (const uint16_t *)p.w + dim2_off(p.wo, c);
+        float wq[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            wq[t] = __builtin_bit_cast(float, (uint32_t)wb[(t / 3) * p.wr.si + (t % 3) * p.ws.si] << 16);
+        float acc[TW] = {0.f, 0.f, 0.f, 0.f};
+        const int ih0 = oh * STRIDE - p.pad_h, iw1 = ow0 * STRIDE;      // column 1 of the window: a multiple of four
+#pragma unroll
+        for (int fr = 0; fr < 3; ++fr) {
+            const int ih = ih0 + fr;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            const uint16_t *row = xb + ih * sxh;
+            float xv[1 + 4 * NV];
+            xv[0] = iw1 > 0 ? __builtin_bit_cast(float, (uint32_t)row[iw1 - 1] << 16) : 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                w2_t d = {0u, 0u};
+                if (iw1 + 4 * v < p.W) d = *(const w2_t *)(row + iw1 + 4 * v);
+                xv[1 + 4 * v] = __builtin_bit_cast(float, d[0] << 16);
+                xv[2 + 4 * v] = __builtin_bit_cast(float, d[0] & 0xffff0000u);
+                xv[3 + 4 * v] = __builtin_bit_cast(float, d[1] << 16);
+                xv[4 + 4 * v] = __builtin_bit_cast(float, d[1] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int fs = 0; fs < 3; ++fs)
+#pragma unroll
+                for (int j = 0; j < TW; ++j) acc[j] += xv[j * STRIDE + fs] * wq[fr * 3 + fs];
+        }
+        const float bias = (p.epilogue & ALT_EPI_BIAS) ? p.bias[c] : 0.f;
+        const float floor_ = (p.epilogue & ALT_EPI_RELU) ? 0.f : -INFINITY;
+        float o[TW];
+#pragma unroll
+        for (int j = 0; j < TW; ++j) o[j] = fmaxf(acc[j] + bias, floor_);
+        uint16_t *yb = (uint16_t *)p.y + dim2_off(p.yn, n) + dim2_off(p.yk, c) + oh * syh + ow0;
+        const w2_t out = {f32x2_to_bf16x2(o[0], o[1]), f32x2_to_bf16x2(o[2], o[3])};
+        *(w2_t *)yb = out;
+    }
+}
+
+// every offset of a plane or row start is a multiple of four elements (8 bytes of bf16)
+bool rows_of_4(const Dim2 *d, int n)
+{
+    for (int i = 0; i < n; ++i)
+        if (d[i].so % 4 || d[i].si % 4) return false;
+    return true;
+}
+
 // eight consecutive channels from a multiple of eight are one contiguous, 16-byte aligned run
 bool chan_runs_of_8(const Dim2 &c, int64_t C, const Dim2 *others, int n_others)
 {
@@ -260,9 +341,18 @@ alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t
     const bool k3x3 = vec && q.R == 3 && q.S == 3 && q.dil_h == 1 && q.dil_w == 1 && q.stride_h == q.stride_w &&
                       (q.stride_h == 1 || q.stride_h == 2) && q.xh.f >= q.H && q.xw.f >= q.W && q.yh.f >= q.OH &&
                       q.yw.f >= q.OW;
-    const int64_t work = k3x3 ? N * q.OH * ((q.OW + kTW - 1) / kTW) * (C / 8) : N * q.OH * q.OW * (vec ? C / 8 : C);
+    const Dim2 xr[3] = {q.xn, q.xc, q.xh}, yr[3] = {q.yn, q.yk, q.yh};
+    const bool rows = !vec && p.in_bf16 && p.out_bf16 && q.R == 3 && q.S == 3 && q.dil_h == 1 && q.dil_w == 1 &&
+                      q.stride_h == q.stride_w && (q.stride_h == 1 || q.stride_h == 2) && q.pad_w == 1 && q.xw.si == 1 &&
+                      q.xw.f >= q.W && q.xh.f >= q.H && q.yw.si == 1 && q.yw.f >= q.OW && q.yh.f >= q.OH && q.wr.f >= 3 &&
+                      q.ws.f >= 3 && q.W % 4 == 0 && q.OW % 4 == 0 && rows_of_4(xr, 3) && rows_of_4(yr, 3) &&
+                      (uintptr_t)q.x % 8 == 0 && (uintptr_t)q.y % 8 == 0;
+    const int64_t work = rows ? N * C * q.OH * (q.OW / 4)
+                       : k3x3 ? N * q.OH * ((q.OW + kTW - 1) / kTW) * (C / 8) : N * q.OH * q.OW * (vec ? C / 8 : C);
     const unsigned blocks = (unsigned)std::min<int64_t>((work + kDwThreads - 1) / kDwThreads, 256 * 64);
-    if (k3x3 && q.stride_h == 1) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<1, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    if (rows && q.stride_h == 1) hipLaunchKernelGGL(dwconv_rows_3x3_kernel<1>, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (rows) hipLaunchKernelGGL(dwconv_rows_3x3_kernel<2>, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (k3x3 && q.stride_h == 1) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<1, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
     else if (k3x3) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<2, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
     else if (vec) hipLaunchKernelGGL(dwconv_vec8_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);
     else hipLaunchKernelGGL(dwconv_elem_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);

@@ -396,6 +396,30 @@ def test_depthwise_conv_exact_integers(h, layouts, in_dtype):
         assert np.array_equal(got, oracle.conv2d(x, w, stride=cfg["stride"], pad=cfg["pad"], dil=cfg.get("dil", 1), groups=C))
 
 
+def test_depthwise_conv_width_contiguous_kernel_exact_integers(h):
+    """The depth-wise kernel for width-contiguous bf16 tensors (NCHW in and out, 3x3, padding 1 along the width,
+    W and OW multiples of four): strides 1 and 2, with and without padding along the height, images one vector
+    wide, bias and ReLU; bit for bit the oracle's.  Geometries just outside its conditions run on the other kernels
+    and must agree as well."""
+    for (N, C, H, W, st, pad) in [(2, 24, 12, 16, 1, (1, 1)), (2, 10, 16, 24, 2, (1, 1)), (3, 7, 9, 8, 1, (0, 1)), (1, 5, 6, 4, 1, (1, 1)),
+                                  (2, 6, 11, 8, 2, (0, 1)), (1, 3, 10, 56, 1, (1, 1)), (2, 4, 9, 10, 1, (1, 1)), (2, 4, 8, 12, 1, (1, 0))]:
+        x = small_ints_f32(331, (N, C, H, W), -3, 3)
+        w = small_ints_f32(332, (C, 1, 3, 3), -3, 3)
+        b = small_ints_f32(333, (C,), -20, 20)
+        ref = oracle.conv2d(x, w, stride=st, pad=pad, groups=C, bias=b, relu=True, out_bf16=True)
+        d = alt.conv_desc(N, C, H, W, C, 3, 3, stride=st, in_dtype=alt.BF16, out_dtype=alt.BF16, epilogue=alt.EPI_BIAS | alt.EPI_RELU,
+                          groups=C)
+        d.pad_h, d.pad_w = pad
+        oshape = h.conv2d_output_shape(d)
+        assert oshape == ref.shape
+        n_out = int(np.prod(oshape))
+        whole, yd = canary_dev(n_out, np.uint16)
+        h.conv2d(d, dev(f32_to_bf16_bits(x).reshape(-1)), dev(f32_to_bf16_bits(w).reshape(-1)), yd, bias=dev(b))
+        got = host(yd, np.uint16).reshape(oshape)
+        assert canary_ok(whole, n_out), "wrote outside y"
+        assert np.array_equal(got, ref), (N, C, H, W, st, pad)
+
+
 def test_depthwise_conv_tolerance(h):
     x = f32_to_bf16_bits(normal_f32(321, (2, 64, 28, 28)))
     w = f32_to_bf16_bits(normal_f32(322, (64, 1, 3, 3), std=0.3))
