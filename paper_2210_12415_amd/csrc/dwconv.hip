@@ -13,9 +13,9 @@
 //    (3x3 filters without dilation get a register-tiled version of it);
 //  * row kernel: bf16 tensors whose width is contiguous on activations and
 //    output (NCHW), 3x3 filters with padding 1 along the width: a thread owns
-//    four consecutive outputs of one row of one channel plane, reads the
-//    input columns under them as 8-byte vectors (plus the two edge columns)
-//    and stores 8 bytes;
+//    four or eight consecutive outputs of one row of one channel plane,
+//    reads the input columns under them as 8- or 16-byte vectors (plus the
+//    column before them) and stores one such vector;
 //  * element kernel: any separable layout; a thread owns one output element,
 //    threads run along the output's contiguous dimension.
 #include <hip/hip_runtime.h>
@@ -227,16 +227,17 @@ __global__ __launch_bounds__(kDwThreads, STRIDE == 1 ? 4 : 3) void dwconv_vec8_3
     }
 }
 
-// bf16 in and out, width contiguous, 3x3 without dilation, padding 1 along the width, W and OW multiples of four
-// (checked by the host together with the alignment of every plane and row).  A thread computes outputs
-// (oh, ow0 .. ow0+3) of one (n, c) plane from input columns ow0*STRIDE - 1 .. : the columns from ow0*STRIDE on come
-// as aligned 8-byte vectors (wholly inside or wholly outside the row), the one before them as a scalar.
-template <int STRIDE>
+// bf16 in and out, width contiguous, 3x3 without dilation, padding 1 along the width, W and OW multiples of TW
+// (four or eight; checked by the host together with the alignment of every plane and row).  A thread computes
+// outputs (oh, ow0 .. ow0+TW-1) of one (n, c) plane from input columns ow0*STRIDE - 1 .. : the columns from
+// ow0*STRIDE on come as aligned vectors of TW elements (wholly inside or wholly outside the row), the one before
+// them as a scalar.
+template <int STRIDE, int TW>
 __global__ __launch_bounds__(kDwThreads) void dwconv_rows_3x3_kernel(const DwParams p)
 {
-    typedef uint32_t w2_t __attribute__((ext_vector_type(2)));
-    constexpr int TW = 4, NCOL = (TW - 1) * STRIDE + 3;    // 6 columns at stride 1, 9 at stride 2
-    constexpr int NV = (NCOL - 1 + 3) / 4;                 // vectors that cover columns 1 .. NCOL-1
+    typedef uint32_t wv_t __attribute__((ext_vector_type(TW / 2)));     // TW bf16: 8 bytes (TW = 4) or 16 (TW = 8)
+    constexpr int NCOL = (TW - 1) * STRIDE + 3;            // input columns under TW outputs
+    constexpr int NV = (NCOL - 1 + TW - 1) / TW;           // vectors that cover columns 1 .. NCOL-1
     const uint32_t OWB = (uint32_t)p.OW / TW;
     const int64_t total = (int64_t)p.N * p.C * p.OH * OWB;
     const int64_t sxh = p.xh.si, syh = p.yh.si;
@@ -261,23 +262,27 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_rows_3x3_kernel(const DwPar
 #pragma unroll
         for (int t = 0; t < 9; ++t)
             wq[t] = __builtin_bit_cast(float, (uint32_t)wb[(t / 3) * p.wr.si + (t % 3) * p.ws.si] << 16);
-        float acc[TW] = {0.f, 0.f, 0.f, 0.f};
-        const int ih0 = oh * STRIDE - p.pad_h, iw1 = ow0 * STRIDE;      // column 1 of the window: a multiple of four
+        float acc[TW];
+#pragma unroll
+        for (int j = 0; j < TW; ++j) acc[j] = 0.f;
+        const int ih0 = oh * STRIDE - p.pad_h, iw1 = ow0 * STRIDE;      // column 1 of the window: a multiple of TW
 #pragma unroll
         for (int fr = 0; fr < 3; ++fr) {
             const int ih = ih0 + fr;
             if ((unsigned)ih >= (unsigned)p.H) continue;
             const uint16_t *row = xb + ih * sxh;
-            float xv[1 + 4 * NV];
+            float xv[1 + TW * NV];
             xv[0] = iw1 > 0 ? __builtin_bit_cast(float, (uint32_t)row[iw1 - 1] << 16) : 0.f;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                w2_t d = {0u, 0u};
-                if (iw1 + 4 * v < p.W) d = *(const w2_t *)(row + iw1 + 4 * v);
-                xv[1 + 4 * v] = __builtin_bit_cast(float, d[0] << 16);
-                xv[2 + 4 * v] = __builtin_bit_cast(float, d[0] & 0xffff0000u);
-                xv[3 + 4 * v] = __builtin_bit_cast(float, d[1] << 16);
-                xv[4 + 4 * v] = __builtin_bit_cast(float, d[1] & 0xffff0000u);
+                wv_t d;
+                __builtin_memset(&d, 0, sizeof d);
+                if (iw1 + TW * v < p.W) d = *(const wv_t *)(row + iw1 + TW * v);
+#pragma unroll
+                for (int q = 0; q < TW / 2; ++q) {
+                    xv[1 + TW * v + 2 * q] = __builtin_bit_cast(float, d[q] << 16);
+                    xv[2 + TW * v + 2 * q] = __builtin_bit_cast(float, d[q] & 0xffff0000u);
+                }
             }
 #pragma unroll
             for (int fs = 0; fs < 3; ++fs)
@@ -286,20 +291,20 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_rows_3x3_kernel(const DwPar
         }
         const float bias = (p.epilogue & ALT_EPI_BIAS) ? p.bias[c] : 0.f;
         const float floor_ = (p.epilogue & ALT_EPI_RELU) ? 0.f : -INFINITY;
-        float o[TW];
+        wv_t out;
 #pragma unroll
-        for (int j = 0; j < TW; ++j) o[j] = fmaxf(acc[j] + bias, floor_);
+        for (int q = 0; q < TW / 2; ++q)
+            out[q] = f32x2_to_bf16x2(fmaxf(acc[2 * q] + bias, floor_), fmaxf(acc[2 * q + 1] + bias, floor_));
         uint16_t *yb = (uint16_t *)p.y + dim2_off(p.yn, n) + dim2_off(p.yk, c) + oh * syh + ow0;
-        const w2_t out = {f32x2_to_bf16x2(o[0], o[1]), f32x2_to_bf16x2(o[2], o[3])};
-        *(w2_t *)yb = out;
+        *(wv_t *)yb = out;
     }
 }
 
-// every offset of a plane or row start is a multiple of four elements (8 bytes of bf16)
-bool rows_of_4(const Dim2 *d, int n)
+// every offset of a plane or row start is a multiple of m elements
+bool rows_of(int m, const Dim2 *d, int n)
 {
     for (int i = 0; i < n; ++i)
-        if (d[i].so % 4 || d[i].si % 4) return false;
+        if (d[i].so % m || d[i].si % m) return false;
     return true;
 }
 
@@ -345,13 +350,18 @@ alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t
     const bool rows = !vec && p.in_bf16 && p.out_bf16 && q.R == 3 && q.S == 3 && q.dil_h == 1 && q.dil_w == 1 &&
                       q.stride_h == q.stride_w && (q.stride_h == 1 || q.stride_h == 2) && q.pad_w == 1 && q.xw.si == 1 &&
                       q.xw.f >= q.W && q.xh.f >= q.H && q.yw.si == 1 && q.yw.f >= q.OW && q.yh.f >= q.OH && q.wr.f >= 3 &&
-                      q.ws.f >= 3 && q.W % 4 == 0 && q.OW % 4 == 0 && rows_of_4(xr, 3) && rows_of_4(yr, 3) &&
+                      q.ws.f >= 3 && q.W % 4 == 0 && q.OW % 4 == 0 && rows_of(4, xr, 3) && rows_of(4, yr, 3) &&
                       (uintptr_t)q.x % 8 == 0 && (uintptr_t)q.y % 8 == 0;
-    const int64_t work = rows ? N * C * q.OH * (q.OW / 4)
+    // eight outputs per thread in 16-byte accesses where the rows allow it
+    const bool rows8 = rows && q.W % 8 == 0 && q.OW % 8 == 0 && rows_of(8, xr, 3) && rows_of(8, yr, 3) &&
+                       (uintptr_t)q.x % 16 == 0 && (uintptr_t)q.y % 16 == 0;
+    const int64_t work = rows ? N * C * q.OH * (q.OW / (rows8 ? 8 : 4))
                        : k3x3 ? N * q.OH * ((q.OW + kTW - 1) / kTW) * (C / 8) : N * q.OH * q.OW * (vec ? C / 8 : C);
     const unsigned blocks = (unsigned)std::min<int64_t>((work + kDwThreads - 1) / kDwThreads, 256 * 64);
-    if (rows && q.stride_h == 1) hipLaunchKernelGGL(dwconv_rows_3x3_kernel<1>, dim3(blocks), dim3(kDwThreads), 0, st, p);
-    else if (rows) hipLaunchKernelGGL(dwconv_rows_3x3_kernel<2>, dim3(blocks), dim3(kDwThreads), 0, st, p);
+    if (rows8 && q.stride_h == 1) hipLaunchKernelGGL((dwconv_rows_3x3_kernel<1, 8>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (rows8) hipLaunchKernelGGL((dwconv_rows_3x3_kernel<2, 8>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (rows && q.stride_h == 1) hipLaunchKernelGGL((dwconv_rows_3x3_kernel<1, 4>), dim3(blocks), dim3(kDwThreads), 0, st, p);
+    else if (rows) hipLaunchKernelGGL((dwconv_rows_3x3_kernel<2, 4>), dim3(blocks), dim3(kDwThreads), 0, st, p);
     else if (k3x3 && q.stride_h == 1) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<1, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
     else if (k3x3) hipLaunchKernelGGL((dwconv_vec8_3x3_kernel<2, kTW>), dim3(blocks), dim3(kDwThreads), 0, st, p);
     else if (vec) hipLaunchKernelGGL(dwconv_vec8_kernel, dim3(blocks), dim3(kDwThreads), 0, st, p);

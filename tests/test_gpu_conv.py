@@ -398,11 +398,12 @@ def test_depthwise_conv_exact_integers(h, layouts, in_dtype):
 
 def test_depthwise_conv_width_contiguous_kernel_exact_integers(h):
     """The depth-wise kernel for width-contiguous bf16 tensors (NCHW in and out, 3x3, padding 1 along the width,
-    W and OW multiples of four): strides 1 and 2, with and without padding along the height, images one vector
-    wide, bias and ReLU; bit for bit the oracle's.  Geometries just outside its conditions run on the other kernels
+    W and OW multiples of four, eight outputs per thread where they are multiples of eight): strides 1 and 2, with and
+    without padding along the height, images one vector wide, bias and ReLU; bit for bit the oracle's.  Geometries just outside its conditions run on the other kernels
     and must agree as well."""
     for (N, C, H, W, st, pad) in [(2, 24, 12, 16, 1, (1, 1)), (2, 10, 16, 24, 2, (1, 1)), (3, 7, 9, 8, 1, (0, 1)), (1, 5, 6, 4, 1, (1, 1)),
-                                  (2, 6, 11, 8, 2, (0, 1)), (1, 3, 10, 56, 1, (1, 1)), (2, 4, 9, 10, 1, (1, 1)), (2, 4, 8, 12, 1, (1, 0))]:
+                                  (2, 6, 11, 8, 2, (0, 1)), (1, 3, 10, 56, 1, (1, 1)), (2, 4, 9, 10, 1, (1, 1)), (2, 4, 8, 12, 1, (1, 0)),
+                                  (2, 6, 10, 32, 2, (1, 1)), (3, 5, 7, 8, 1, (1, 1)), (2, 3, 9, 16, 2, (0, 1))]:
         x = small_ints_f32(331, (N, C, H, W), -3, 3)
         w = small_ints_f32(332, (C, 1, 3, 3), -3, 3)
         b = small_ints_f32(333, (C,), -20, 20)
