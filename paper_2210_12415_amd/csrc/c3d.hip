@@ -222,14 +222,14 @@ struct Problem3d {
 };
 
 // The forward operator.
-alt_status_t forward_problem(alt_handle_t h, const alt_conv3d_desc_t *d, Problem3d *out)
+alt_status_t forward_problem(alt_handle_t h, const alt_conv3d_desc_t *d, Problem3d *out, const char *who = "alt_conv3d")
 {
     const alt_conv_desc_t &q = d->plane;
-    if (q.N < 1 || q.C < 1 || q.H < 1 || q.W < 1 || d->D < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: extents must be positive");
-    if (d->stride_d < 1 || d->dil_d < 1 || d->pad_d < 0) return fail(h, ALT_INVALID_ARG, "alt_conv3d: bad depth stride, padding or dilation");
-    if (q.groups > 1) return fail(h, ALT_UNSUPPORTED, "alt_conv3d: groups are not supported");
+    if (q.N < 1 || q.C < 1 || q.H < 1 || q.W < 1 || d->D < 1 || d->T < 1) return fail(h, ALT_INVALID_ARG, "%s: extents must be positive", who);
+    if (d->stride_d < 1 || d->dil_d < 1 || d->pad_d < 0) return fail(h, ALT_INVALID_ARG, "%s: bad depth stride, padding or dilation", who);
+    if (q.groups > 1) return fail(h, ALT_UNSUPPORTED, "%s: groups are not supported", who);
     const int64_t OD = out_depth(d);
-    if (OD < 1) return fail(h, ALT_INVALID_ARG, "alt_conv3d: the filter is deeper than the padded input");
+    if (OD < 1) return fail(h, ALT_INVALID_ARG, "%s: the filter is deeper than the padded input", who);
     Problem3d &p = *out;
     p.f = q;
     p.f.N = q.N * OD;
@@ -316,7 +316,7 @@ bool subpixel3d_plan(alt_handle_t h, const alt_conv3d_desc_t *d, SubPixel3d *out
     const int64_t ys[4] = {q.N * s.ad.outq, s.m.plane.K, s.ah.outq, s.aw.outq};
     if (bind_layout(&q.w_layout, 4, ws, &b, &err) != ALT_OK) return false;
     if (bind_layout(&q.y_layout, 4, ys, &b, &err) != ALT_OK) return false;
-    return forward_problem(h, &s.m, &s.pr) == ALT_OK && s.pr.OD == s.ad.outq;
+    return forward_problem(h, &s.m, &s.pr, "alt_conv3d_transpose") == ALT_OK && s.pr.OD == s.ad.outq;
 }
 
 size_t gathered_bytes(const Problem3d &p)
