@@ -873,25 +873,25 @@ def test_conv3d_transpose_exact_integers(h, layouts, geometry):
     w = small_ints_f32(942, (C, K, T, R, S), -3, 3)
     b = small_ints_f32(943, (K,), -20, 20)
     ref = oracle.conv3d_transpose(x, w, stride=stride, pad=pad, dil=dil)
-    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
-    xs = np.ascontiguousarray(xb.transpose(0, 2, 1, 3, 4)).reshape(N * D, C, H, W)
-    xd = dev(to_layout(xs, "NCHW", xl))
     forms = set()
-    for out_dtype, bias, relu in [(alt.F32, None, False), (alt.BF16, b, True)]:
+    for in_dtype, out_dtype, bias, relu in [(alt.BF16, alt.F32, None, False), (alt.BF16, alt.BF16, b, True), (alt.F32, alt.F32, b, True)]:
+        xb, wb = (f32_to_bf16_bits(x), f32_to_bf16_bits(w)) if in_dtype == alt.BF16 else (x, w)
+        xs = np.ascontiguousarray(xb.transpose(0, 2, 1, 3, 4)).reshape(N * D, C, H, W)
+        xd = dev(to_layout(xs, "NCHW", xl))
         epi = (alt.EPI_BIAS if bias is not None else 0) | (alt.EPI_RELU if relu else 0)
-        d = alt.conv3d_desc(N, C, D, H, W, K, T, R, S, stride=stride, pad=pad, dil=dil, in_dtype=alt.BF16, out_dtype=out_dtype,
+        d = alt.conv3d_desc(N, C, D, H, W, K, T, R, S, stride=stride, pad=pad, dil=dil, in_dtype=in_dtype, out_dtype=out_dtype,
                             epilogue=epi, x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
         oshape = h.conv3d_transpose_output_shape(d)
         assert oshape == ref.shape
         _, _, OD, OH, OW = oshape
         wshape = h.conv3d_transpose_weight_shape(d)
-        whole_w, wd = canary_dev(int(np.prod(wshape)), np.uint16)
+        whole_w, wd = canary_dev(int(np.prod(wshape)), wb.dtype)
         h.pack_weights3d_transpose(d, dev(wb.reshape(-1)), wd)
         assert canary_ok(whole_w, int(np.prod(wshape))), "wrote outside the packed filter"
         forms.add("zero insertion" if wshape == (K, T * C, R, S) else "sub-pixel")
         if wshape == (K, T * C, R, S):      # zero-insertion form: the mirrored, channel-swapped filter
             w2 = np.ascontiguousarray(wb[:, :, ::-1, ::-1, ::-1].transpose(1, 2, 0, 3, 4)).reshape(K, T * C, R, S)
-            assert np.array_equal(host(wd, np.uint16), to_layout(w2, "OIHW", wl).reshape(-1))
+            assert np.array_equal(host(wd, wb.dtype), to_layout(w2, "OIHW", wl).reshape(-1))
         ydt = np.float32 if out_dtype == alt.F32 else np.uint16
         n_out = int(np.prod(oshape))
         whole, yd = canary_dev(n_out, ydt)
@@ -901,7 +901,9 @@ def test_conv3d_transpose_exact_integers(h, layouts, geometry):
         got = host(yd, ydt)
         assert canary_ok(whole, n_out), "wrote outside y"
         got = from_layout(got, (N * OD, K, OH, OW), "NCHW", yl).reshape(N, OD, K, OH, OW).transpose(0, 2, 1, 3, 4)
-        want = ref if bias is None else f32_to_bf16_bits(np.maximum(ref + b[None, :, None, None, None], np.float32(0)))
+        want = ref if bias is None else np.maximum(ref + b[None, :, None, None, None], np.float32(0))
+        if out_dtype == alt.BF16:
+            want = f32_to_bf16_bits(want)
         assert np.array_equal(got, want)
     # filter 3 x 2 x 3: the sub-pixel form needs extents that the strides divide in every direction
     sub = stride in ((1, 2, 1), (3, 2, 3))
