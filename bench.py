@@ -32,6 +32,9 @@ os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBPS = 8000.0
+MIN_TIMED_MS = 50.0          # every timed region of the headline step runs at least this long
+MAX_LINE_BYTES = 2000        # the final stdout line stays below this; everything else goes to EXTRA_PATH
+EXTRA_PATH = os.path.join(ROOT, "gpurun_out", "bench_extra.json")
 
 
 def main():
@@ -46,6 +49,8 @@ def main():
                     help="comma-separated extra sections to run besides the headline step: f32, transforms, gemm, b1, "
                          "scaled, chain, graph, groups, budget, peaks (default all; --quick runs none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--default-trials", type=int, default=32,
+                    help="measurements spent per layer on the default layout's own kernel variants (0 = all)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
                          "which gives a hardware-counter run its scale")
@@ -256,15 +261,25 @@ def main():
             if not torch.equal(l["y"], ye):
                 raise SystemExit("bench.py: graph replay of %s differs from the eager launch" % l["L"]["name"])
         def timed_steps(one_step):
+            # --steps is a floor: a step is tens of microseconds and a timed region carries a fixed
+            # cost of a few hundred, so every way is timed for at least MIN_TIMED_MS of device work.
+            # A short probe region sizes the count; the steps actually timed are reported.
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
+            for _ in range(20):
+                one_step()
+            torch.cuda.synchronize()
+            probe_ms = (time.perf_counter() - t0) * 1000.0 / 20
+            n = max(args.steps, int(math.ceil(MIN_TIMED_MS / max(probe_ms, 1e-3))))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
             e0.record(stream)
-            for _ in range(args.steps):
+            for _ in range(n):
                 one_step()
             e1.record(stream)
             torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1000.0 / args.steps, e0.elapsed_time(e1) / args.steps
+            return (time.perf_counter() - t0) * 1000.0 / n, e0.elapsed_time(e1) / n, n
 
         # Three ways to issue the same five launches: one graph replay per step, five
         # launches on one stream through calls marshalled once, or one alt_conv2d_multi
@@ -276,8 +291,8 @@ def main():
         # three figures are kept.
         for _ in range(args.warmup):
             step()
-        g_ms, g_dev = timed_steps(g_step.replay)
-        s_ms, s_dev = timed_steps(step)
+        g_ms, g_dev, g_n = timed_steps(g_step.replay)
+        s_ms, s_dev, s_n = timed_steps(step)
         def timed_multi(descs, order=None):
             # reference: the same kernels launched one after the other on the default stream
             # (another variant may sum in another order and round a bf16 output differently)
@@ -295,41 +310,60 @@ def main():
             for l, ye in zip(layers, serial_y):
                 if not torch.equal(l["y"], ye):
                     raise SystemExit("bench.py: multi-stream launch of %s differs from the same kernel launched alone" % l["L"]["name"])
-            return timed_steps(multi)[0]
-        m_ms = timed_multi([l["desc"] for l in layers])
-        ways = [(g_ms, g_dev, "one HIP graph replay per step (5 kernel nodes, one stream)"),
-                (s_ms, s_dev, "5 launches per step on one stream (arguments marshalled once)"),
-                (m_ms, m_ms, "one alt_conv2d_multi call per step: the 5 independent layers on 5 streams")]
+            r = timed_steps(multi)
+            return r[0], r[2]
+        m_ms, m_n = timed_multi([l["desc"] for l in layers])
+        ways = [(g_ms, g_dev, "one HIP graph replay per step (5 kernel nodes, one stream)", g_n),
+                (s_ms, s_dev, "5 launches per step on one stream (arguments marshalled once)", s_n),
+                (m_ms, m_ms, "one alt_conv2d_multi call per step: the 5 independent layers on 5 streams", m_n)]
         res = dict(graph_ms_per_step=g_ms, stream_ms_per_step=s_ms, multi_stream_ms_per_step=m_ms)
         if co_descs is not None:
             # the same launch with the kernel variants chosen jointly for it (see co_tune)
-            c_ms = timed_multi(co_descs, co_order)
+            c_ms, c_n = timed_multi(co_descs, co_order)
             res["multi_stream_cotuned_ms_per_step"] = c_ms
             res["cotuned_variants"] = [h.conv2d_variant_name(d, d.variant) for d in co_descs]
             res["cotuned_issue_order"] = [layers[i]["L"]["name"] for i in (co_order or range(len(layers)))]
             ways.append((c_ms, c_ms, "one alt_conv2d_multi call per step: the 5 independent layers on 5 streams, "
-                                     "kernel variants chosen jointly under that launch"))
+                                     "kernel variants chosen jointly under that launch", c_n))
         best = min(ways, key=lambda t: t[0])
-        res.update(ms_per_step=best[0], dev_ms_per_step=best[1], launch=best[2])
+        res.update(ms_per_step=best[0], dev_ms_per_step=best[1], launch=best[2], steps_timed=best[3])
         del eager_y
         del g_step
-        # per-layer kernel durations, live: 20 launches of the layer per graph replay
+        # per-layer kernel durations, live: 20 launches of the layer per graph replay; the default
+        # layout (NCHW activations, OIHW weights) is measured in the same run, under the best of its own
+        # kernel variants (a short search on the device); what comes from the stored plan says so
         per_layer = []
         for l in layers:
             g = capture(lambda st, l=l: run_layer(l, st), 20)
             us = graph_timed(g, 20)
             del g
             l["us"] = us
-            per_layer.append(dict(layer=l["L"]["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
+            L = l["L"]
+            d0 = alt.conv_desc(16, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"], pad=L["pad"],
+                               in_dtype=alt.BF16, out_dtype=l["desc"].out_dtype)
+            try:
+                def_us, def_trials = h.tune_conv2d_variants(d0, arena, arena.numel(), max_trials=args.default_trials,
+                                                            warmup=3, reps=20)
+                def_us = float(def_us)
+            except alt.AltError:
+                def_us, def_trials = float("nan"), 0
+            stored = not tuned_now
+            per_layer.append(dict(layer=L["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
                                   tflops=round(l["flops"] / us / 1e6, 1),
                                   frac_mfma_peak=round(l["flops"] / us / 1e6 / PEAK_BF16_TFLOPS, 4),
+                                  frac_own_ceiling=round(l["flops"] / us / 1e6 / own_ceiling_tflops(l), 4),
                                   compulsory_GBps=round(l["bytes"] / us / 1e3, 1),
-                                  tuner_trials=l["trials"], default_layout_us=round(l["default_us"], 2),
-                                  tuned_us=round(l["best_us"], 2),
-                                  speedup_vs_default_layout=round(l["default_us"] / l["best_us"], 2),
-                                  layout_us=l["layout_us"]))
+                                  default_layout_us_live=round(def_us, 2), default_layout_trials_live=int(def_trials),
+                                  speedup_vs_default_layout_live=round(def_us / us, 2),
+                                  plan_is_stored=stored,
+                                  plan=dict(tuner_trials=l["trials"], default_layout_us=round(l["default_us"], 2),
+                                            tuned_us=round(l["best_us"], 2), layout_us=l["layout_us"])))
         res["per_layer"] = per_layer
         return res
+
+    def own_ceiling_tflops(l):
+        """min(MFMA peak, arithmetic intensity x HBM peak) of a layer, from its compulsory bytes."""
+        return min(PEAK_BF16_TFLOPS, l["flops"] / l["bytes"] * PEAK_HBM_GBPS / 1e3)
 
     def load_traffic():
         """HBM bytes per launch from a stored pair of hardware-counter runs
@@ -391,6 +425,15 @@ def main():
     per_layer = head["per_layer"]
     dom = max(layers, key=lambda l: l["us"])
     achieved = dom["flops"] / dom["us"] / 1e6
+    attainable = None
+    if want("peaks"):
+        pk = h.get_peak(arena, arena.numel())
+        attainable = dict(copy_GBps=round(float(pk.copy_gbps), 1), read_GBps=round(float(pk.read_gbps), 1),
+                          write_GBps=round(float(pk.write_gbps), 1),
+                          mfma_bf16_TFLOPs=round(float(pk.mfma_bf16_tflops), 1),
+                          compute_units=pk.compute_units, clock_mhz=pk.clock_mhz, arch=pk.arch.decode(),
+                          note="streams over a 1 GiB arena (copy: 512 MiB read + 512 MiB written per launch); "
+                               "register-resident bf16 MFMA loop")
     traffic_doc = load_traffic()
     for l, pl in zip(layers, per_layer):
         tr = kernel_traffic(traffic_doc, l, 16)
@@ -400,8 +443,11 @@ def main():
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_BF16_TFLOPS, 4),
                     traffic=(dom_tr["fetch_bytes"] + dom_tr["write_bytes"]) if dom_tr else None,
+                    traffic_source="stored rocprofv3 --pmc runs of this kernel and grid" if dom_tr else None,
                     kernel=dom["variant"], layer=dom["L"]["name"],
-                    us_per_launch=round(dom["us"], 3), flops_per_launch=dom["flops"])
+                    us_per_launch=round(dom["us"], 3), flops_per_launch=dom["flops"],
+                    frac_vs_attainable=round(achieved / attainable["mfma_bf16_TFLOPs"], 4) if attainable else None,
+                    frac_own_ceiling=round(achieved / own_ceiling_tflops(dom), 4))
 
     extra = dict(per_layer_b16=per_layer, device_ms_per_step=round(dev_ms_per_step, 4), launch=head["launch"],
                  graph_replay_ms_per_step=round(head["graph_ms_per_step"], 5),
@@ -436,45 +482,51 @@ def main():
 
     if want("transforms"):
         # -------------------------------------------------- conversion operator ----
-        tr = []
-        for shp in TRANSFORM_SHAPES:
-            numel = int(np.prod(shp))
-            for dt, tdt, es in [(alt.F32, torch.float32, 4), (alt.BF16, torch.int16, 2)]:
-                # a ring of distinct buffers larger than the last-level cache, so every launch streams from HBM
-                nring = max(2, int(math.ceil((768 << 20) / (numel * es * 2))))
-                srcs = [torch.randn(numel, device=dev).to(tdt) if tdt == torch.float32 else
-                        torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev) for _ in range(nring)]
-                dsts = [torch.empty(numel, dtype=tdt, device=dev) for _ in range(nring)]
-                for a, b in [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
-                             ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW", "NCHW->NCHW32c")]:
-                    la, lb = alt.layout_parse(a), alt.layout_parse(b)
-                    def ring(st):
-                        for i in range(nring):
-                            h.layout_transform(dt, shp, la, srcs[i], lb, dsts[i], stream=st)
+        # Cold figures: a ring of distinct source and destination buffers of at least 1 GiB in total,
+        # four times the 256 MB last-level cache, so every launch reads from and writes to HBM.  Warm
+        # figures: the same pair of buffers again and again (cache-resident at the configured sizes).
+        # Both are per launch inside a HIP graph on one stream, i.e. they include the gap between
+        # consecutive kernels of a stream.
+        RING_BYTES = 1 << 30
+        pairs = [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"),
+                 ("NCHW->NCHW", "NCHW->NCHW16c"), ("NCHW->NCHW", "NCHW->NCHW32c")]
 
-                    g = capture(ring, 1)
-                    us_cold = graph_timed(g, nring, replays=4, batches=3)
-                    g = capture(lambda st: h.layout_transform(dt, shp, la, srcs[0], lb, dsts[0], stream=st), 20)
-                    us_warm = graph_timed(g, 20, replays=5, batches=3)
-                    del g
-                    gb = 2.0 * numel * es / 1e9
-                    tr.append(dict(shape=list(shp), dtype="f32" if dt == alt.F32 else "bf16",
-                                   src=a.split(">")[1], dst=b.split(">")[1], us_hbm=round(us_cold, 2),
+        def transform_rows(shapes, warm):
+            rows = []
+            for shp in shapes:
+                numel = int(np.prod(shp))
+                for dt, tdt, es in [(alt.F32, torch.float32, 4), (alt.BF16, torch.int16, 2)]:
+                    nring = max(2, int(math.ceil(RING_BYTES / (numel * es * 2))))
+                    srcs = [torch.randint(-30000, 30000, (numel,), dtype=torch.int16 if es == 2 else torch.int32,
+                                          device=dev).view(tdt) for _ in range(nring)]
+                    dsts = [torch.empty(numel, dtype=tdt, device=dev) for _ in range(nring)]
+                    for a, b in pairs:
+                        la, lb = alt.layout_parse(a), alt.layout_parse(b)
+                        def ring(st):
+                            for i in range(nring):
+                                h.layout_transform(dt, shp, la, srcs[i], lb, dsts[i], stream=st)
+
+                        g = capture(ring, 1)
+                        us_cold = graph_timed(g, nring, replays=4, batches=3)
+                        gb = 2.0 * numel * es / 1e9
+                        row = dict(shape=list(shp), dtype="f32" if dt == alt.F32 else "bf16",
+                                   src=a.split(">")[1], dst=b.split(">")[1], ring_buffers=2 * nring,
+                                   ring_MB=round(2 * nring * numel * es / 1e6), us_hbm=round(us_cold, 2),
                                    GBps_hbm=round(gb / (us_cold * 1e-6), 1),
-                                   frac_hbm_peak=round(gb / (us_cold * 1e-6) / PEAK_HBM_GBPS, 4),
-                                   us_cache_resident=round(us_warm, 2), GBps_cache_resident=round(gb / (us_warm * 1e-6), 1)))
-                del srcs, dsts
-        extra["layout_transform"] = tr
-        # scaled beyond the configs: 16x the batch, to show the kernel away from launch overhead
-        big = (256, 64, 56, 56)
-        numel = int(np.prod(big))
-        s0 = torch.randint(-30000, 30000, (numel,), dtype=torch.int16, device=dev)
-        s1 = torch.empty_like(s0)
-        us = median_timed(lambda: h.layout_transform(alt.BF16, big, "NCHW->NCHW", s0, "NCHW->NHWC", s1, stream=stream), 20, 3)
-        extra["layout_transform_scaled_256x64x56x56_bf16_nchw_to_nhwc"] = dict(
-            us=round(us, 1), GBps=round(2.0 * numel * 2 / 1e9 / (us * 1e-6), 1),
-            frac_hbm_peak=round(2.0 * numel * 2 / 1e9 / (us * 1e-6) / PEAK_HBM_GBPS, 4))
-        del s0, s1
+                                   frac_hbm_peak=round(gb / (us_cold * 1e-6) / PEAK_HBM_GBPS, 4))
+                        if warm:
+                            g = capture(lambda st: h.layout_transform(dt, shp, la, srcs[0], lb, dsts[0], stream=st), 20)
+                            us_warm = graph_timed(g, 20, replays=5, batches=3)
+                            row.update(us_cache_resident=round(us_warm, 2),
+                                       GBps_cache_resident=round(gb / (us_warm * 1e-6), 1))
+                        del g
+                        rows.append(row)
+                    del srcs, dsts
+            return rows
+
+        extra["layout_transform"] = transform_rows(TRANSFORM_SHAPES, warm=True)
+        # scaled beyond the configs: 16x the batch of each shape, cold, to show the kernels away from launch overhead
+        extra["layout_transform_scaled"] = transform_rows([(16 * s[0],) + tuple(s[1:]) for s in TRANSFORM_SHAPES], warm=False)
         # the unfold primitive (overlapped tiles of 14 + 2 rows along H of an NHWC tensor, Section 4.1.2): expands the data
         ushape = (16, 56, 56, 64)
         oshape = alt.unfold_shape(ushape, 1, 16, 14)
@@ -549,6 +601,21 @@ def main():
                            speedup_vs_default_layout=round(float(rep.default_us) / float(rep.best_us), 2),
                            tuner_trials=rep.trials, layout_us=dict(zip(names, [round(u, 2) for u in lus]))))
         extra["gemm_bert"] = gm
+        # scaled beyond the configs: one 4096^3 product, bf16 output, tuned with a budget
+        d0 = alt.gemm_desc(4096, 4096, 4096, in_dtype=alt.BF16, out_dtype=alt.BF16, b_layout="KN->NK")
+        us_best, trials = None, 0
+        A = torch.randint(-200, 200, (4096 * 4096,), dtype=torch.int16, device=dev)
+        B = torch.randint(-200, 200, (4096 * 4096,), dtype=torch.int16, device=dev)
+        Cd = torch.empty(4096 * 4096, dtype=torch.int16, device=dev)
+        best, rep = h.tune_gemm(d0, arena, arena.numel(), max_trials=64, warmup=2, reps=5, layout_mask=0)
+        wsb = h.gemm_workspace_size(best)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+        us = median_timed(lambda: h.gemm(best, A, B, Cd, workspace=ws, ws_bytes=wsb, stream=stream), 20, 3)
+        fl = 2.0 * 4096 ** 3
+        extra["gemm_4096"] = dict(variant=h.gemm_variant_name(best, best.variant), us=round(us, 1),
+                                  tflops=round(fl / us / 1e6, 1), frac_mfma_peak=round(fl / us / 1e6 / PEAK_BF16_TFLOPS, 4),
+                                  tuner_trials=rep.trials)
+        del A, B, Cd
 
     if want("b1"):
         # ------------------------------------------------------- batch-1 layers ----
@@ -807,12 +874,8 @@ def main():
         h.cache_clear()
         extra["budgeted_search_b16"] = bud
 
-    if want("peaks"):
-        pk = h.get_peak(arena, arena.numel())
-        extra["attainable"] = dict(copy_GBps=round(float(pk.copy_gbps), 1),
-                                   mfma_bf16_TFLOPs=round(float(pk.mfma_bf16_tflops), 1),
-                                   compute_units=pk.compute_units, clock_mhz=pk.clock_mhz,
-                                   arch=pk.arch.decode())
+    if attainable:
+        extra["attainable"] = attainable
 
     # ------------------------------------------------------------ cpu baseline ----
     cpu = None
@@ -837,15 +900,75 @@ def main():
                    kind="oracle", sample="the whole step (five layers, batch 16), %d passes, %.1f s" % (passes, t_total))
 
     out = dict(metric="conv2d/GEMM TFLOP/s (% bf16 MFMA peak); layout_transform GB/s (% HBM)",
-               value=round(value, 2), unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               value=round(value, 2), unit="TFLOP/s", n_gpus=1, steps=int(head["steps_timed"]), warmup=args.warmup,
                ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="bf16", data="synthetic",
-               config=dict(workload="ResNet-50-style conv layers (C64 56x56 3x3, C128 28x28 3x3, C256 14x14 3x3, "
-                                    "C512 7x7 3x3, C256->64 56x56 1x1), batch 16, bf16 in / fp32 accumulate / bf16 out, "
-                                    "tuned layout per layer, inputs resident in the tuned layout",
-                           flops_per_step=step_flops, frac_bf16_mfma_peak=round(value / PEAK_BF16_TFLOPS, 4)),
-               roofline=roofline, cpu_baseline=cpu, extra=extra)
-    print(json.dumps(out))
+               config=dict(workload="ResNet-50-style conv layers C64/56x56/3x3, C128/28x28/3x3, C256/14x14/3x3, "
+                                    "C512/7x7/3x3, C256->64/56x56/1x1 at batch 16, bf16 in, fp32 accumulate, bf16 out, "
+                                    "tuned layout per layer, inputs resident in HBM",
+                           flops_per_step=step_flops, frac_bf16_mfma_peak=round(value / PEAK_BF16_TFLOPS, 4),
+                           steps_requested=args.steps, launch=head["launch"][:60],
+                           plan="tuned in this run" if tuned_now else "stored: " + os.path.relpath(args.plan, ROOT)),
+               roofline=roofline, cpu_baseline=cpu, summary=summarise(extra))
+    emit(out, extra)
+
+
+def summarise(extra):
+    """A few figures of each section for the final line (the sections themselves go to EXTRA_PATH)."""
+    s = dict(layer_us=[p["us"] for p in extra["per_layer_b16"]],
+             layer_frac_mfma=[p["frac_mfma_peak"] for p in extra["per_layer_b16"]],
+             layer_speedup_vs_default_layout=[p["speedup_vs_default_layout_live"] for p in extra["per_layer_b16"]],
+             one_stream_ms_per_step=extra["graph_replay_ms_per_step"])
+    tr = extra.get("layout_transform")
+    if tr:
+        s["transform_cold_GBps_min_max"] = [min(t["GBps_hbm"] for t in tr), max(t["GBps_hbm"] for t in tr)]
+    sc = extra.get("layout_transform_scaled")
+    if sc:
+        s["transform_16x_cold_GBps"] = [t["GBps_hbm"] for t in sc]
+    gm = extra.get("gemm_bert")
+    if gm:
+        s["gemm_frac_mfma"] = [g["frac_mfma_peak"] for g in gm]
+    big = extra.get("gemm_4096")
+    if big:
+        s["gemm_4096_frac_mfma"] = big["frac_mfma_peak"]
+    cs = extra.get("conv_scaled_batch256_nhwc_bf16out")
+    if cs:
+        s["conv_b256_frac_mfma"] = [c["frac_mfma_peak"] for c in cs]
+    ch = extra.get("chain")
+    if ch:
+        s["chain_us"] = ch["planned_total_us"]
+    at = extra.get("attainable")
+    if at:
+        s["attainable"] = {k: at[k] for k in at if k.endswith("GBps") or k.endswith("TFLOPs")}
+    s["extra_file"] = os.path.relpath(EXTRA_PATH, ROOT)
+    return s
+
+
+def final_line(out):
+    """The one JSON line that ends the run: compact separators, below MAX_LINE_BYTES (whatever a
+    summary list grows to, the headline fields survive: the summary is what gets dropped)."""
+    line = json.dumps(out, separators=(",", ":"))
+    if len(line) >= MAX_LINE_BYTES:
+        out = dict(out)
+        out["summary"] = dict(extra_file=out.get("summary", {}).get("extra_file"), dropped="line too long")
+        line = json.dumps(out, separators=(",", ":"))
+    if len(line) >= MAX_LINE_BYTES:
+        raise SystemExit("bench.py: final line is %d bytes" % len(line))
+    return line
+
+
+def emit(out, extra):
+    """Writes the sections to EXTRA_PATH (and to stdout, each on a line of its own, before the final line)."""
+    try:
+        os.makedirs(os.path.dirname(EXTRA_PATH), exist_ok=True)
+        with open(EXTRA_PATH, "w") as f:
+            json.dump(dict(headline=out, extra=extra), f, indent=1)
+    except OSError:
+        pass
+    for k, v in extra.items():
+        print("# extra.%s %s" % (k, json.dumps(v, separators=(",", ":"))))
+    sys.stdout.flush()
+    print(final_line(out))
 
 
 if __name__ == "__main__":

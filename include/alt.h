@@ -581,10 +581,13 @@ typedef struct {
     int32_t compute_units;
     int32_t clock_mhz;
     char arch[32];
+    float read_gbps;              /* measured read-only pass over half the arena, bytes read per second / 1e9 */
+    float write_gbps;             /* measured write-only pass over the arena, bytes written per second / 1e9 */
 } alt_peaks_t;
 
 /* Measures attainable peaks on the handle's device using `arena` (device,
- * >= 512 MiB recommended) as copy buffer.  Synchronises. */
+ * >= 1 GiB recommended: the passes must not fit the 256 MiB last-level cache)
+ * as copy buffer; the arena's contents are overwritten.  Synchronises. */
 alt_status_t alt_get_peak(alt_handle_t h, void *arena, size_t arena_bytes, alt_peaks_t *out);
 
 #if defined(__GNUC__)

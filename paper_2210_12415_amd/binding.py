@@ -121,7 +121,7 @@ class Peaks(ctypes.Structure):
     _fields_ = [("copy_gbps", ctypes.c_float), ("mfma_bf16_tflops", ctypes.c_float),
                 ("nominal_hbm_gbps", ctypes.c_float), ("nominal_bf16_tflops", ctypes.c_float),
                 ("compute_units", ctypes.c_int32), ("clock_mhz", ctypes.c_int32),
-                ("arch", ctypes.c_char * 32)]
+                ("arch", ctypes.c_char * 32), ("read_gbps", ctypes.c_float), ("write_gbps", ctypes.c_float)]
 
 
 _lib = None

@@ -64,6 +64,34 @@ def rel_err(got, ref):
     return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
 
 
+def err_measures(got, ref, absdot=None):
+    """The three error figures the parity tests report, as a dict:
+    scaled    max_i |g_i - r_i| / (|r_i| + rms(r))             (the measure the thresholds are asserted on for fp32 sums)
+    floored   max_i |g_i - r_i| / max(|r_i|, 1e-3 * rms(r))    (relative error with a small floor)
+    component max_i |g_i - r_i| / sum_j |a_ij| |b_j|           (scale-free; absdot = the operator applied to |a|, |b|)
+    A sum of Kg fp32 roundings has an absolute error near sqrt(Kg) * 2^-25 * rms whatever the
+    order of summation, so outputs that happen to fall near zero carry relative errors of
+    1e-4 and more under `floored` even when every addition is correctly rounded: the 1e-5
+    threshold for fp32 operands can only be met under `scaled`, the 2e-2 threshold for
+    bf16 operands is asserted under `floored`, and `component` is held against the textbook
+    bound Kg * 2^-24."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    rms = float(np.sqrt(np.mean(ref * ref))) or 1.0
+    diff = np.abs(got - ref)
+    out = dict(scaled=float(np.max(diff / (np.abs(ref) + rms))),
+               floored=float(np.max(diff / np.maximum(np.abs(ref), 1e-3 * rms))))
+    if absdot is not None:
+        ad = np.asarray(absdot, dtype=np.float64).reshape(-1)
+        out["component"] = float(np.max(diff / np.maximum(ad, np.finfo(np.float64).tiny)))
+    return out
+
+
+def abs_bits(bits):
+    """|x| of bf16 bit patterns."""
+    return (np.asarray(bits, dtype=np.uint16) & np.uint16(0x7fff)).astype(np.uint16)
+
+
 TOL = {alt.F32: 1e-5, alt.BF16: 2e-2}
 
 
