@@ -25,6 +25,12 @@
  *    B (K, N), C (M, N), with an optional dense outermost batch.
  *  - Element types: ALT_F32 (IEEE binary32) and ALT_BF16 (bfloat16 bit
  *    patterns in 16-bit words).  Products are accumulated in fp32.
+ *  - Kernel arguments: these kernels run for a few microseconds, and with the
+ *    HIP runtime's default (kernel arguments in host memory) every workgroup's
+ *    first loads cross the host link, which costs each launch 2-5 us.  Set
+ *    HIP_FORCE_DEV_KERNARG=1 in the environment before the process makes its
+ *    first HIP call; the library cannot do it (the runtime reads the variable
+ *    once, when it starts).  The Python binding sets it on import if unset.
  */
 #ifndef ALT_H_
 #define ALT_H_
@@ -199,6 +205,30 @@ typedef struct {
 alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
                         const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
+
+/* Split-K variants of the tile kernels (names ending _k2, _k4, ...: the reduction over input
+ * channels of the Fig. 3 program cut into slices that run as separate workgroups) sum their
+ * slices inside the one launch: every slice writes its partial tile to `workspace`, the last
+ * slice to arrive at the tile's counter adds them in slice order.  The counters live in a
+ * static device array of ALT_SPLITK_MAX_STREAMS sets; a set is bound to the stream that first
+ * launches a split-K variant and serves that stream from then on, so launches on different
+ * streams never share one.  Limits that follow:
+ *  - when more than ALT_SPLITK_MAX_STREAMS streams have launched split-K variants on a device,
+ *    the next new stream makes the library wait for the device to go idle and release the
+ *    sets (those that a graph capture has seen stay bound for good); while a stream is being
+ *    captured that wait is not possible and the call returns ALT_UNSUPPORTED;
+ *  - a captured graph carries the set of the stream it was captured on: do not replay it
+ *    while other split-K launches issued or captured on that same stream are in flight;
+ *  - partial tiles and counters are exchanged with device scope (written through to the
+ *    memory all XCDs share): the result does not depend on where workgroups run. */
+#define ALT_SPLITK_MAX_STREAMS 64
+typedef struct {
+    int32_t streams_bound;        /* counter sets bound to a stream */
+    int32_t max_streams;          /* ALT_SPLITK_MAX_STREAMS */
+    int32_t counters_nonzero;     /* arrival counters that are not zero with the device idle (always 0 unless a launch failed) */
+} alt_splitk_status_t;
+/* Waits for the device to go idle, then reports the above. */
+alt_status_t alt_splitk_status(alt_handle_t h, alt_splitk_status_t *out);
 
 /* alt_conv2d with a sum fused into its epilogue (the fused loop nest of Fig. 6; a residual
  * join whose other operand is already in the convolution's output layout):

@@ -117,6 +117,10 @@ class GraphPlan(ctypes.Structure):
                 ("fused_into", ctypes.c_int32 * MAX_GRAPH)]
 
 
+class SplitkStatus(ctypes.Structure):
+    _fields_ = [("streams_bound", ctypes.c_int32), ("max_streams", ctypes.c_int32), ("counters_nonzero", ctypes.c_int32)]
+
+
 class Peaks(ctypes.Structure):
     _fields_ = [("copy_gbps", ctypes.c_float), ("mfma_bf16_tflops", ctypes.c_float),
                 ("nominal_hbm_gbps", ctypes.c_float), ("nominal_bf16_tflops", ctypes.c_float),
@@ -161,7 +165,7 @@ def exported_symbols():
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_conv2d_multi", "alt_tune_chain", "alt_plan_chain",
             "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
-            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak"]
+            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_splitk_status"]
 
 
 def version():
@@ -588,6 +592,11 @@ class Handle:
 
     def cache_clear(self):
         _ck(lib().alt_cache_clear(self._h), self._h)
+
+    def splitk_status(self):
+        out = SplitkStatus()
+        _ck(lib().alt_splitk_status(self._h, ctypes.byref(out)), self._h)
+        return out
 
     def get_peak(self, arena, arena_bytes):
         p = Peaks()

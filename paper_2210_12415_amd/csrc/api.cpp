@@ -41,7 +41,6 @@ alt_status_t alt_create(alt_handle_t *out)
         (void)hipGetLastError();
     }
     if (!c->has_gpu) c->arch = "none";
-    else (void)alt::dconv_round_robin_xcds();      // probes the device once
     *out = c;
     return ALT_OK;
 }

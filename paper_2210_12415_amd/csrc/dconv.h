@@ -75,7 +75,7 @@ struct DconvParams {
     Div32 d_slots;                // division by Cs / 8 + 1, the 16-byte slots of a patch pixel in LDS
     int32_t ncc;                  // K steps per tap: (Cs / K groups) / channels per K step
     int32_t bk;                   // channels per K step: 64, or 32 for narrow K groups
-    int32_t xcd_local;            // split-K: the slices of a tile run on one XCD and meet in its L2
+    int32_t pad0_;
     Div32 d_sk;                   // division by splitk
     // streaming kernel (dstream.h) only: batch entries and the byte strides between them
     int32_t batch, pad1_;
@@ -91,13 +91,12 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kDconvOutBf16 = 4;
 constexpr int kAgentScope = 16;          // cache-policy operand of buffer loads/stores: sc1 = device (agent) scope
-constexpr int kBypassL1 = 1;             // sc0: served by the XCD's L2, never by the CU's own L1
 // Output stores carry sc0 + sc1: the lines go through to memory as they are written instead of
 // staying dirty in the XCD's L2 until the write-back at the end of the kernel, which
 // shortens the gap before the next kernel on the stream (measured: 5 % of a five-layer step).
 constexpr int kWriteThrough = 17;
 constexpr int kDconvMaxTiles = 4096;     // output tiles a split-K launch may have (one counter each)
-constexpr int kDconvSlots = 8;           // counter sets, handed to launches round-robin
+constexpr int kDconvSlots = 64;          // counter sets, one per stream that has issued a split-K launch
 
 // Wave-wide 16-byte-per-lane load into LDS at `lds` (+ 16 * lane); the byte
 // offset is voff (per lane) + soff (wave-uniform).
@@ -211,31 +210,24 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const u32x4_t w = __builtin_bit_cast(u32x4_t, vs[it][v]);
-                if (p.xcd_local) __builtin_amdgcn_raw_buffer_store_b128(w, pr, (int)(offs[it] * 4u), v * 16, 0);
-                else __builtin_amdgcn_raw_buffer_store_b128(w, pr, (int)(offs[it] * 4u), v * 16, kAgentScope);
+                __builtin_amdgcn_raw_buffer_store_b128(w, pr, (int)(offs[it] * 4u), v * 16, kAgentScope);
             }
-        // Release half.  Across XCDs: the partial sums were stored with device (agent) scope,
-        // i.e. written through to memory all XCDs share; once the stores are acknowledged
-        // they are visible to device-scope loads anywhere (a full device-scope fence would
-        // write back the whole L2 and costs tens of microseconds here).  Within one XCD:
-        // plain stores are acknowledged by the XCD's L2, which every CU of the XCD reads.
+        // Release half: the partial sums were stored with device (agent) scope, i.e. written
+        // through to memory all XCDs share; once the stores are acknowledged they are
+        // visible to device-scope loads anywhere (a full device-scope fence would write
+        // back the whole L2 and costs tens of microseconds here).
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         uint32_t *flag = (uint32_t *)smem_u4 + NW * (WTM * SP);
         if (t == 0) {
-            // (the XCD-local counter is an atomic executed in that XCD's L2: no device-scope bits)
-            const uint32_t old = p.xcd_local
-                ? __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
-                : __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t old = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             *flag = old == (uint32_t)(p.splitk - 1);
-            if (*flag) {                           // ready for the next launch
-                if (p.xcd_local) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                else __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if (*flag)                             // ready for the next launch
+                __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         if (*flag == 0) return false;                   // another workgroup finishes this tile
-        // acquire half: the loads below have device scope (or bypass the CU's L1) and so do not hit stale cache lines
+        // acquire half: the loads below have device scope and so do not hit stale cache lines
 
         // Sum of the slices in slice order.  All loads of a slice are issued before any of
         // them is consumed (one dependent load per access would cost a device-scope memory
@@ -263,9 +255,7 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
                 for (int it = 0; it < NIT; ++it)
 #pragma unroll
                     for (int v = 0; v < V; ++v)
-                        w4[g][it][v] = p.xcd_local
-                            ? __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), v * 16, kBypassL1)
-                            : __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), v * 16, kAgentScope);
+                        w4[g][it][v] = __builtin_amdgcn_raw_buffer_load_b128(sr, (int)(offs[it] * 4u), v * 16, kAgentScope);
             }
 #pragma unroll
             for (int g = 0; g < G; ++g)
@@ -351,7 +341,7 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
 template <int BM, int BN, int WGM, int WGN, int KW>
 __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
                                                uint4 *smem_u4, int t, int lane, int wave, int kg, int wq, int wm, int wn,
-                                               int m0, int n0, int mt, int nt, int split, char *y, uint64_t *epi_clk)
+                                               int m0, int n0, int mt, int nt, int split, char *y)
 {
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -366,9 +356,6 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
     // channels per lane, consecutive lanes side by side.
     constexpr int SP = WTN + 4;                            // staging pitch in floats
     __syncthreads();                                       // every wave is done with the stages and the patch
-#ifdef ALT_PHASE_TIMING
-    epi_clk[0] = __builtin_amdgcn_s_memtime();
-#endif
     float *stg = (float *)smem_u4 + wave * (WTM * SP);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -380,10 +367,6 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
                     make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     // (with one K group a wave reads back only what it wrote itself; the compiler orders these LDS accesses)
     if constexpr (KW > 1) __syncthreads();
-#ifdef ALT_PHASE_TIMING
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    epi_clk[1] = __builtin_amdgcn_s_memtime();
-#endif
     bool mine;
     constexpr bool kWideFits = WTM % ((64 / (WTN / 8)) * KW) == 0;     // eight columns per lane divide the tile evenly
     if (kWideFits && (p.flags & kDconvOutBf16) && p.Nc % 8 == 0) {
@@ -392,9 +375,6 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
     } else {
         mine = dconv_epilogue_tail<BM, BN, WGM, WGN, KW, 4>(p, smem_u4, t, lane, kg, wq, wm, wn, m0, n0, mt, nt, split, y);
     }
-#ifdef ALT_PHASE_TIMING
-    epi_clk[2] = __builtin_amdgcn_s_memtime();
-#endif
     return mine;
 }
 
@@ -422,10 +402,6 @@ template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK, int KR, int 
 __global__ __launch_bounds__(64 * WGM * WGN * KW, ALT_DCONV_MIN_WAVES((BM / WGM) * (BN / WGN) / 64, WGM * WGN * KW))
 void dconv_kernel(const DconvParams p)
 {
-#ifdef ALT_PHASE_TIMING
-    uint64_t stamps[5] = {0, 0, 0, 0, 0};
-#endif
-    ALT_STAMP(0);
     constexpr int NWG = WGM * WGN, NW = NWG * KW;          // waves per group, per workgroup
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -452,18 +428,7 @@ void dconv_kernel(const DconvParams p)
 
     // workgroup -> (m tile, n tile, channel slice)
     int mt, nt, split;
-    if (p.xcd_local) {
-        // Workgroup ids are dealt round-robin to the 8 XCDs, so ids that agree modulo 8 share an
-        // XCD and its L2: the slices of one tile are given such ids (the host has checked the
-        // dealing order on this device), tiles go round the XCDs, the grid is padded to whole rounds.
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int tl = (int)div32((uint32_t)slot, p.d_sk);
-        split = slot - tl * p.splitk;
-        const int tile_id = tl * 8 + xcd;
-        if (tile_id >= p.tiles_m * p.tiles_n) return;
-        nt = (int)div32((uint32_t)tile_id, p.d_tm);
-        mt = tile_id - nt * p.tiles_m;
-    } else {
+    {
         // consecutive logical ids share an XCD
         const int ntot = p.tiles_m * p.tiles_n * p.splitk;
         const int logical = igemm_logical_tile(ntot);
@@ -622,10 +587,6 @@ void dconv_kernel(const DconvParams p)
         for (int j = 0; j < TN; ++j) lds_read16_async(bf[kc][j], b_rd[j][kc] + sa.st_off);
     };
 
-    ALT_STAMP(1);
-#ifdef ALT_PHASE_TIMING
-    const uint64_t core_clk0 = __builtin_amdgcn_s_memtime();
-#endif
     // ---- main loop -------------------------------------------------------------------------------------
     // K steps walk the taps, 64-channel chunks of the slice innermost.  Step t's weights
     // sit in stage t % NS.  At the barrier that opens step t every wave has its share of
@@ -653,7 +614,6 @@ void dconv_kernel(const DconvParams p)
         }
         wait_vmcnt<(NS - 2) * NLB>();                      // the patch and stage 0
         lds_barrier();
-        ALT_STAMP(2);
         // reads of k chunk g (counted over all steps); past the last step they repeat it (never used)
         auto reads = [&](auto gc) {
             constexpr int g = decltype(gc)::value;
@@ -693,7 +653,6 @@ void dconv_kernel(const DconvParams p)
         cur.st_off = 0;
         wait_vmcnt<(NS - 2) * NLB>();                          // the patch and stage 0
         lds_barrier();
-        ALT_STAMP(2);
     #pragma unroll
         for (int kc = 0; kc < D; ++kc) read_frags(kc, cur);
         for (int step = 0; step < nsteps; ++step) {
@@ -741,30 +700,8 @@ void dconv_kernel(const DconvParams p)
 #pragma unroll
         for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bf[kc][j]));
     }
-    ALT_STAMP(3);
-#ifdef ALT_PHASE_TIMING
-    const uint64_t core_clk1 = __builtin_amdgcn_s_memtime();
-#endif
 
-    uint64_t epi_clk[3] = {0, 0, 0};
-    if (!dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
-                                              (char *)p.y, epi_clk))
-        return;
-#ifdef ALT_PHASE_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ALT_STAMP(4);
-    if (threadIdx.x == 0 && p.partial) {
-        // (developer builds) timestamps behind the partial sums; with split-K only the reducing workgroups get here
-        uint64_t *out = (uint64_t *)((char *)p.partial + (p.splitk > 1 ? (size_t)p.splitk * p.partial_bytes : 0)) + (size_t)blockIdx.x * 8;
-        for (int i = 0; i < 5; ++i) out[i] = stamps[i];
-        out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
-        out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
-        out[7] = core_clk1 - core_clk0;                                // core clocks spent in the main loop
-        out[4] = stamps[4] | ((epi_clk[1] - epi_clk[0]) << 48);         // top 16 bits: clocks barrier -> staged
-        out[3] = stamps[3] | ((epi_clk[2] - epi_clk[1]) << 48);         // clocks staged -> stores issued
-        out[2] = stamps[2] | ((epi_clk[0] - core_clk1) << 48);          // clocks main loop end -> past the barrier
-    }
-#endif
+    dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split, (char *)p.y);
 }
 
 // Pixels of the largest patch over the tiles of BM output pixels: the span of input pixels
@@ -813,7 +750,7 @@ hipError_t dconv_launch_kr(const DconvParams &p, size_t lds, hipStream_t st)
         attr_set = true;
     }
     const int tiles = p.tiles_m * p.tiles_n;
-    const unsigned grid = p.xcd_local ? (unsigned)((tiles + 7) / 8 * 8 * p.splitk) : (unsigned)(tiles * p.splitk);
+    const unsigned grid = (unsigned)(tiles * p.splitk);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WGM * WGN * KW), lds, st, p);
     return hipGetLastError();
 }

@@ -1,7 +1,7 @@
 // Host side of the patch-resident direct convolution (dconv.h) and of the
 // streaming kernel (dstream.h): which problems each covers, their launch
 // parameters, and the arrival counters of the fused split-K reduction.
-#include <atomic>
+#include <mutex>
 
 #include "dstream.h"
 #include "ops.h"
@@ -11,25 +11,35 @@ namespace alt {
 namespace {
 
 // Arrival counters of the fused split-K reduction: zero when the module is
-// loaded, and every launch leaves them zero again.  kDconvSlots sets are
-// handed out round-robin so that launches in flight on different streams do
-// not share one (more than kDconvSlots overlapping split-K launches would).
+// loaded, and every launch leaves them zero again.  There are kDconvSlots sets;
+// a set is bound to the first stream that issues a split-K launch and stays
+// with it (launches on one stream run one after the other, so they can share
+// a set; launches on different streams never do).
 __device__ __align__(256) uint32_t g_dconv_counters[kDconvSlots * kDconvMaxTiles];
-
 constexpr int kMaxDevices = 16;
-uint32_t *g_counter_ptr[kMaxDevices];
-int g_round_robin[kMaxDevices];      // 0 = not probed, 1 = workgroup ids go round the XCDs in order, -1 = they do not
 
-// Each workgroup reports the XCD it runs on.
-__global__ void xcd_probe_kernel(uint32_t *out)
-{
-    if (threadIdx.x == 0) out[blockIdx.x] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20)) & 0xf;   // XCC_ID
-}
-std::atomic<unsigned> g_next_slot{0};
+struct SlotTable {
+    hipStream_t stream[kDconvSlots];
+    bool used[kDconvSlots], pinned[kDconvSlots];   // pinned: a captured graph carries this set's address
+};
+
+struct DeviceState {
+    uint32_t *counters = nullptr;
+    SlotTable slots{};
+};
+DeviceState g_dev[kMaxDevices];
+std::mutex g_mutex;
 
 bool dense(const Dim2 &d, int64_t extent, int64_t stride)
 {
     return extent == 1 || (d.f >= extent && d.si == stride);
+}
+
+DeviceState *device_state()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    return &g_dev[dev];
 }
 
 }  // namespace
@@ -37,47 +47,71 @@ bool dense(const Dim2 &d, int64_t extent, int64_t stride)
 // Device address of the counters on the current device (looked up once per device).
 hipError_t dconv_counters(uint32_t **out)
 {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (!g_counter_ptr[dev]) {
+    DeviceState *ds = device_state();
+    if (!ds) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!ds->counters) {
         void *ptr = nullptr;
-        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_dconv_counters));
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_dconv_counters));
         if (e != hipSuccess) return e;
-        g_counter_ptr[dev] = (uint32_t *)ptr;
+        ds->counters = (uint32_t *)ptr;
     }
-    *out = g_counter_ptr[dev];
+    *out = ds->counters;
     return hipSuccess;
 }
 
-// Whether workgroup i of a launch runs on the same XCD as every workgroup j with
-// j = i (mod 8), which lets the slices of a split-K tile meet in one L2.  Probed once per
-// device with a small launch whose workgroups report their XCD, using the counter array
-// as scratch (it is zeroed again); synchronises, so it runs when a handle is created.
-bool dconv_round_robin_xcds()
+// Counter sets bound to streams on the current device, and how many counters are not zero once
+// the device is idle (-1 if they cannot be read): waits for the device.
+void dconv_splitk_state(int *slots_bound, int *counters_nonzero)
 {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
-    if (g_round_robin[dev] != 0) return g_round_robin[dev] > 0;
-    g_round_robin[dev] = -1;
-    if (const char *e = std::getenv("ALT_SPLITK_SCOPE"))
-        if (std::strcmp(e, "device") == 0) return false;
-    uint32_t *buf = nullptr;
-    if (dconv_counters(&buf) != hipSuccess) return false;
-    constexpr int kBlocks = 1024;
-    static_assert(kBlocks <= kDconvSlots * kDconvMaxTiles, "probe scratch");
-    uint32_t host[kBlocks];
-    bool ok = true;
-    for (int rep = 0; rep < 3 && ok; ++rep) {
-        hipLaunchKernelGGL(xcd_probe_kernel, dim3(kBlocks), dim3(64), 0, 0, buf);
-        if (hipMemcpy(host, buf, sizeof host, hipMemcpyDeviceToHost) != hipSuccess) { ok = false; break; }
-        for (int b = 8; b < kBlocks; ++b) ok = ok && host[b] == host[b & 7];
+    DeviceState *ds = device_state();
+    *slots_bound = 0;
+    *counters_nonzero = -1;
+    if (!ds) return;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        for (int i = 0; i < kDconvSlots; ++i) *slots_bound += ds->slots.used[i] ? 1 : 0;
     }
-    (void)hipMemset(buf, 0, sizeof host);
-    (void)hipDeviceSynchronize();
-    if (ok) g_round_robin[dev] = 1;
-    return ok;
+    uint32_t *base = nullptr;
+    if (dconv_counters(&base) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return;
+    std::vector<uint32_t> host((size_t)kDconvSlots * kDconvMaxTiles);
+    if (hipMemcpy(host.data(), base, host.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) return;
+    int nz = 0;
+    for (uint32_t v : host) nz += v != 0;
+    *counters_nonzero = nz;
+}
+
+// The counter set of `st` on the current device: the one bound to it, else a free one.  When
+// every set is bound the host waits until the device is idle and releases all sets except
+// those a captured graph carries the address of.  hipErrorNotReady if that leaves none, or
+// if the wait would be needed while `st` is being captured.
+static hipError_t counter_slot(DeviceState *ds, hipStream_t st, int *slot)
+{
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (st) (void)hipStreamIsCapturing(st, &cap);
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    SlotTable &t = ds->slots;
+    int free_slot = -1;
+    for (int i = 0; i < kDconvSlots; ++i) {
+        if (t.used[i] && t.stream[i] == st) { t.pinned[i] |= capturing; *slot = i; return hipSuccess; }
+        if (!t.used[i] && free_slot < 0) free_slot = i;
+    }
+    if (free_slot < 0) {
+        // Every set is bound.  Sets whose address a captured graph carries stay; the others are
+        // released once nothing is in flight on the device.
+        if (capturing) return hipErrorNotReady;
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return e;
+        for (int i = 0; i < kDconvSlots; ++i)
+            if (!t.pinned[i]) { t.used[i] = false; if (free_slot < 0) free_slot = i; }
+        if (free_slot < 0) return hipErrorNotReady;
+    }
+    t.used[free_slot] = true;
+    t.pinned[free_slot] = capturing;
+    t.stream[free_slot] = st;
+    *slot = free_slot;
+    return hipSuccess;
 }
 
 // The same for a streaming kernel (dstream.h): 1x1 filters, stride 1, no padding (a GEMM
@@ -133,11 +167,6 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     d.d_sk = make_div32((uint32_t)splitk);
     d.batch = p.batch;
     d.x_bstride = p.x_bstride * 2; d.w_bstride = p.w_bstride * 2; d.y_bstride = p.y_bstride * osz;
-    {
-        int dev = 0;
-        d.xcd_local = splitk > 1 && hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices &&
-                      g_round_robin[dev] > 0 && (int64_t)(tiles_m * tiles_n + 7) / 8 * 8 * splitk <= 0x7fffffff;
-    }
     *out = d;
     *lds_bytes = lds;
     return true;
@@ -212,11 +241,6 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     d.ncc = (int32_t)(Csg / bk);
     d.bk = bk;
     d.d_sk = make_div32((uint32_t)splitk);
-    {
-        int dev = 0;
-        d.xcd_local = splitk > 1 && hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices &&
-                      g_round_robin[dev] > 0 && (int64_t)(tiles_m * tiles_n + 7) / 8 * 8 * splitk <= 0x7fffffff;
-    }
     *out = d;
     *lds_bytes = lds;
     return true;
@@ -228,12 +252,13 @@ hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *par
         uint32_t *base = nullptr;
         hipError_t e = dconv_counters(&base);
         if (e != hipSuccess) return e;
-        d.counters = base + (size_t)(g_next_slot.fetch_add(1) % kDconvSlots) * kDconvMaxTiles;
+        DeviceState *ds = device_state();
+        int slot = 0;
+        e = counter_slot(ds, st, &slot);
+        if (e != hipSuccess) return e;
+        d.counters = base + (size_t)slot * kDconvMaxTiles;
         d.partial = partial;
     }
-#ifdef ALT_PHASE_TIMING
-    if (d.splitk == 1) d.partial = partial;    // developer builds: workgroup timestamps go to the workspace
-#endif
     return k.launch_direct(d, lds, st);
 }
 

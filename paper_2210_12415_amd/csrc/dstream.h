@@ -20,10 +20,6 @@ template <int BM, int BN, int WGM, int WGN, int KW, int NS, int BK>
 __global__ __launch_bounds__(64 * WGM * WGN * KW, ALT_DCONV_MIN_WAVES((BM / WGM) * (BN / WGN) / 64, WGM * WGN * KW))
 void dstream_kernel(const DconvParams p)
 {
-#ifdef ALT_PHASE_TIMING
-    uint64_t stamps[5] = {0, 0, 0, 0, 0};
-#endif
-    ALT_STAMP(0);
     constexpr int NWG = WGM * WGN;                         // waves per K group
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -53,15 +49,7 @@ void dstream_kernel(const DconvParams p)
 
     // workgroup -> (m tile, n tile, channel slice), as in the direct convolution
     int mt, nt, split;
-    if (p.xcd_local) {
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int tl = (int)div32((uint32_t)slot, p.d_sk);
-        split = slot - tl * p.splitk;
-        const int tile_id = tl * 8 + xcd;
-        if (tile_id >= p.tiles_m * p.tiles_n) return;
-        nt = (int)div32((uint32_t)tile_id, p.d_tm);
-        mt = tile_id - nt * p.tiles_m;
-    } else {
+    {
         const int ntot = p.tiles_m * p.tiles_n * p.splitk;
         const int logical = igemm_logical_tile(ntot);
         const int rest = (int)div32((uint32_t)logical, p.d_tm);
@@ -157,10 +145,8 @@ void dstream_kernel(const DconvParams p)
         for (int j = 0; j < TN; ++j) lds_read16_async_at<off>(bf[buf][j], b_rd[j][kc]);
     };
 
-    ALT_STAMP(1);
     wait_vmcnt<(NS - 2) * LPS>();                          // stage 0 (this wave's share)
     lds_barrier();
-    ALT_STAMP(2);
     static_for<D>(reads);
 
     // One K step in stage st.  At its barrier every wave has its share of the next stage
@@ -203,23 +189,9 @@ void dstream_kernel(const DconvParams p)
 #pragma unroll
         for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bf[kc][j]));
     }
-    ALT_STAMP(3);
 
-    uint64_t epi_clk[3] = {0, 0, 0};
-    if (!dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
-                                              (char *)p.y + (int64_t)bz * p.y_bstride, epi_clk))
-        return;
-#ifdef ALT_PHASE_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ALT_STAMP(4);
-    if (threadIdx.x == 0 && p.partial && gridDim.y == 1) {
-        uint64_t *out = (uint64_t *)((char *)p.partial + (p.splitk > 1 ? (size_t)p.splitk * p.partial_bytes : 0)) + (size_t)blockIdx.x * 8;
-        for (int i = 0; i < 5; ++i) out[i] = stamps[i];
-        out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
-        out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
-        out[7] = 0;
-    }
-#endif
+    dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
+                                         (char *)p.y + (int64_t)bz * p.y_bstride);
 }
 
 // LDS bytes of one workgroup: the K groups' operand rings, or the output staging.
@@ -242,7 +214,7 @@ hipError_t dstream_launch(const DconvParams &p, size_t lds, hipStream_t st)
         attr_set = true;
     }
     const int tiles = p.tiles_m * p.tiles_n;
-    const unsigned grid = p.xcd_local ? (unsigned)((tiles + 7) / 8 * 8 * p.splitk) : (unsigned)(tiles * p.splitk);
+    const unsigned grid = (unsigned)(tiles * p.splitk);
     hipLaunchKernelGGL(kern, dim3(grid, (unsigned)p.batch), dim3(64 * WGM * WGN * KW), lds, st, p);
     return hipGetLastError();
 }

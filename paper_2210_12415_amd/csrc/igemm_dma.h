@@ -64,22 +64,9 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void *base, uint32_t bytes)
     return r;
 }
 
-// Built with -DALT_PHASE_TIMING (developer builds only), every workgroup writes
-// five 100 MHz timestamps (start, prologue done, first stage landed, main loop
-// done, epilogue done) to the split-K workspace instead of using it.
-#ifdef ALT_PHASE_TIMING
-#define ALT_STAMP(i) do { if (threadIdx.x == 0) stamps[i] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define ALT_STAMP(i) do { } while (0)
-#endif
-
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int NS>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmParams p)
 {
-#ifdef ALT_PHASE_TIMING
-    uint64_t stamps[5] = {0, 0, 0, 0, 0};
-#endif
-    ALT_STAMP(0);
     using TR = ElemTraits<T>;
     constexpr int EPV = TR::EPV;
     constexpr int ES = TR::SIZE;
@@ -217,7 +204,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
     if (nk > 0) {
         fill_ktab(0);
         lds_barrier();
-        ALT_STAMP(1);
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
             if (s < nk) issue(ktab[s], s, 0, LPS);
@@ -227,9 +213,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
             if (ks + NS - 2 < nk) wait_vmcnt<(NS - 2) * LPS>();
             else wait_vmcnt<0>();
             lds_barrier();                             // everyone's part of step ks is in LDS; step ks-1 is consumed
-#ifdef ALT_PHASE_TIMING
-            if (ks == 0) ALT_STAMP(2);
-#endif
             const int nf = ks + NS - 1;
             const bool more = nf < nk;
             if (more && nf % kKTab == 0) {             // next window of the K-step table
@@ -271,18 +254,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_dma_kernel(const IgemmPa
             if (ks0 + st < nk) do_step(ks0 + st, st);
         lds_barrier();                                 // last reads done before the stages are reused
     }
-    ALT_STAMP(3);
     igemm_epilogue<BM, TM, TN, WTM, WTN, NT>(p, acc, (void *)smem_u4, m0, n0, wm, wn, split, bz);
-#ifdef ALT_PHASE_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ALT_STAMP(4);
-    if (threadIdx.x == 0 && p.partial && p.splitk == 1) {
-        uint64_t *out = (uint64_t *)p.partial + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
-        for (int i = 0; i < 5; ++i) out[i] = stamps[i];
-        out[5] = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, 4));    // HW_ID
-        out[6] = __builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, 20));    // XCC_ID
-    }
-#endif
 }
 
 template <typename T, int BM, int BN, int BK, int NS>

@@ -31,7 +31,7 @@ alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *wor
 // dconv.hip
 bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes,
                  std::string *why);
-bool dconv_round_robin_xcds();
+void dconv_splitk_state(int *slots_bound, int *counters_nonzero);
 hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st);
 
 // dwconv.hip

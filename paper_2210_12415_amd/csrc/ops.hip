@@ -230,12 +230,12 @@ alt_status_t igemm_run(alt_handle_t h, const Problem &pb, int variant, void *wor
         if (!dconv_setup(pb, k, splitk, &dp, &lds, &why))
             return fail(h, ALT_UNSUPPORTED, "variant %s/splitk%d not applicable: %s", k.name, splitk, why.c_str());
         hipError_t e = dconv_run(k, dp, lds, (float *)workspace, st);
+        if (e == hipErrorNotReady)
+            return fail(h, ALT_UNSUPPORTED, "%s: no split-K counter set is free for this stream (%d streams hold one; sets "
+                                            "that captured graphs use are never released)", k.name, kDconvSlots);
         if (e != hipSuccess) return fail(h, ALT_HIP_ERROR, "launch of %s failed: %s", k.name, hipGetErrorString(e));
         return ALT_OK;
     }
-#ifdef ALT_PHASE_TIMING
-    if (need == 0 && workspace) p.partial = (float *)workspace;
-#endif
     if (need > 0) {
         if (!workspace || ws_bytes < need)
             return fail(h, ALT_WORKSPACE_TOO_SMALL, "split-K needs %zu workspace bytes, got %zu", need, ws_bytes);
@@ -612,6 +612,20 @@ alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, c
     if (v < 0) return fail(h, ALT_UNSUPPORTED, "alt_gemm: no kernel variant applies");
     memo_store(h, d, sizeof *d, sig, ws_limit, pb, v);
     return igemm_run(h, pb, v, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+alt_status_t alt_splitk_status(alt_handle_t h, alt_splitk_status_t *out)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!out) return fail(h, ALT_INVALID_ARG, "alt_splitk_status: null argument");
+    std::memset(out, 0, sizeof *out);
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    int bound = 0, nonzero = 0;
+    dconv_splitk_state(&bound, &nonzero);
+    out->streams_bound = bound; out->counters_nonzero = nonzero;
+    out->max_streams = kDconvSlots;
+    if (nonzero < 0) return fail(h, ALT_HIP_ERROR, "alt_splitk_status: could not read the counters");
+    return ALT_OK;
 }
 
 alt_status_t alt_gemm_workspace_size(alt_handle_t h, const alt_gemm_desc_t *d, size_t *bytes)
