@@ -163,6 +163,29 @@ alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, int ndim, c
                                   const alt_layout_t *src_layout, const void *src,
                                   const alt_layout_t *dst_layout, void *dst, void *stream);
 
+/* What alt_layout_transform would launch for a conversion, without launching it (host only: works
+ * without a GPU).  src_misalign / dst_misalign: the buffers' addresses modulo 16, which decide the
+ * vector widths.  kind: 0 plain copy, 1 one thread per element (layouts whose blocks do not nest,
+ * non-separable fuse sequences), 2 contiguous runs copied as they are, 3 tiles through LDS (the
+ * contiguous piece differs between the two layouts).  With replay != 0 and kind = 3 the call also
+ * replays every workgroup's index arithmetic on the host and counts, in `mismatches`, destination
+ * elements not written exactly once from the source element that the two layouts' index maps
+ * (Table 1) name, plus LDS indices out of range: 0 means the plan is the conversion operator of
+ * Section 4.2; -1 means not replayed. */
+typedef struct {
+    int32_t kind;
+    int32_t src_flat, dst_flat;   /* kind 3: that side of a tile is one contiguous run, moved in 16-byte vectors */
+    int32_t load_bytes, store_bytes;
+    int32_t tile_a, tile_b, tile_g;
+    int64_t workgroups;
+    int64_t lds_bytes;
+    int64_t mismatches;
+} alt_transform_plan_t;
+alt_status_t alt_layout_transform_plan(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape,
+                                       const alt_layout_t *src_layout, int src_misalign,
+                                       const alt_layout_t *dst_layout, int dst_misalign, int replay,
+                                       alt_transform_plan_t *out);
+
 /* ---- C2D (program of Fig. 3; zero padding as in Section 4.2; fused bias and
  *      ReLU as in Fig. 6; producer writes the consumer's layout, Section 4.2) */
 
@@ -611,7 +634,7 @@ typedef struct {
     int32_t compute_units;
     int32_t clock_mhz;
     char arch[32];
-    float read_gbps;              /* measured read-only pass over half the arena, bytes read per second / 1e9 */
+    float read_gbps;              /* measured read-only pass over the arena, bytes read per second / 1e9 */
     float write_gbps;             /* measured write-only pass over the arena, bytes written per second / 1e9 */
 } alt_peaks_t;
 

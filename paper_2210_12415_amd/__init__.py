@@ -13,6 +13,6 @@ _os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 
 from .binding import (AltError, Handle, Layout, ConvDesc, Conv3dDesc, ConvCall, GemmDesc, TuneOpts, TuneReport,
                       ChainPlan, GraphNode, GraphPlan, NODE_CONV, NODE_ADD, Prim, Peaks, F32, BF16, EPI_BIAS, EPI_RELU,
-                      SplitkStatus, layout_parse, layout_from_prims, layout_physical_shape, layout_offset,
+                      SplitkStatus, TransformPlan, layout_parse, layout_from_prims, layout_physical_shape, layout_offset,
                       layout_index_of, plan_chain, plan_graph, graph_node, unfold_shape, split, reorder, fuse, version, lib,
                       conv_desc, conv3d_desc, gemm_desc, exported_symbols, library_path)

@@ -117,6 +117,13 @@ class GraphPlan(ctypes.Structure):
                 ("fused_into", ctypes.c_int32 * MAX_GRAPH)]
 
 
+class TransformPlan(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("src_flat", ctypes.c_int32), ("dst_flat", ctypes.c_int32),
+                ("load_bytes", ctypes.c_int32), ("store_bytes", ctypes.c_int32),
+                ("tile_a", ctypes.c_int32), ("tile_b", ctypes.c_int32), ("tile_g", ctypes.c_int32),
+                ("workgroups", ctypes.c_int64), ("lds_bytes", ctypes.c_int64), ("mismatches", ctypes.c_int64)]
+
+
 class SplitkStatus(ctypes.Structure):
     _fields_ = [("streams_bound", ctypes.c_int32), ("max_streams", ctypes.c_int32), ("counters_nonzero", ctypes.c_int32)]
 
@@ -165,7 +172,7 @@ def exported_symbols():
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_conv2d_multi", "alt_tune_chain", "alt_plan_chain",
             "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
-            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_splitk_status"]
+            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_layout_transform_plan", "alt_splitk_status"]
 
 
 def version():
@@ -334,6 +341,13 @@ class Handle:
                                        ctypes.byref(_as_layout(src_layout)), _ptr(src),
                                        ctypes.byref(_as_layout(dst_layout)), _ptr(dst),
                                        _stream(stream)), self._h)
+
+    def layout_transform_plan(self, dtype, shape, src_layout, dst_layout, src_misalign=0, dst_misalign=0, replay=False):
+        out = TransformPlan()
+        _ck(lib().alt_layout_transform_plan(self._h, dtype, len(shape), _i64(shape), ctypes.byref(_as_layout(src_layout)),
+                                            int(src_misalign), ctypes.byref(_as_layout(dst_layout)), int(dst_misalign),
+                                            int(bool(replay)), ctypes.byref(out)), self._h)
+        return out
 
     # conv
     def conv2d(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):

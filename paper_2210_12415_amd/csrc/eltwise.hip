@@ -48,7 +48,9 @@ __global__ __launch_bounds__(kEltThreads) void eltwise_add_kernel(const void *a,
             for (int q = 0; q < 4; ++q) out[q] = f32x2_to_bf16x2(lo[q], hi[q]);
         }
         char *dst = (char *)y + v * 16;
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(dst), "v"(out) : "memory");
+        // (s_nop: the store reads its four data registers up to two cycles after it issues, and the
+        // compiler does not guard registers of an asm statement against the next VALU write)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(dst), "v"(out) : "memory");
     }
     // tail
     const int64_t t0 = n16 * EPV;

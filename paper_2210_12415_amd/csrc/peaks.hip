@@ -6,40 +6,52 @@
 namespace alt {
 namespace {
 
-// Plain streams over a large buffer.  A thread keeps four independent 16-byte accesses in
-// flight per trip; consecutive threads touch consecutive 16-byte pieces, the four accesses of a
-// trip are one grid-wide stride apart.
-__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4 *src, uint4 *dst, size_t n)
+// Plain streams over a large buffer.  A workgroup moves one contiguous chunk of kChunk 16-byte
+// vectors, eight per thread, all of them in flight before the first store, with the non-temporal
+// hint on both sides; the grid walks the buffer front to back.  (A grid-stride loop over the same
+// buffer, whose workgroups touch addresses megabytes apart at any one time, measured 4.4-4.7 TB/s
+// on this machine against 6.2-6.5 for this shape.)
+typedef uint32_t vec4_t __attribute__((ext_vector_type(4)));
+constexpr int kPerThread = 8, kChunk = kPerThread * 256;
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(const vec4_t *src, vec4_t *dst, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    const size_t base = (size_t)blockIdx.x * kChunk + threadIdx.x;
+    vec4_t r[kPerThread];
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const size_t i = base + (size_t)k * 256;
+        r[k] = __builtin_nontemporal_load(src + (i < n ? i : 0));
     }
-    for (; i < n; i += stride) dst[i] = src[i];
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const size_t i = base + (size_t)k * 256;
+        if (i < n) __builtin_nontemporal_store(r[k], dst + i);
+    }
 }
 
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src, uint4 *sink, size_t n)
+__global__ __launch_bounds__(256) void stream_read_kernel(const vec4_t *src, vec4_t *sink, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
-    uint4 s = make_uint4(0, 0, 0, 0);
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        s.x ^= a.x ^ b.x ^ c.x ^ d.x; s.y ^= a.y ^ b.y ^ c.y ^ d.y;
-        s.z ^= a.z ^ b.z ^ c.z ^ d.z; s.w ^= a.w ^ b.w ^ c.w ^ d.w;
+    const size_t base = (size_t)blockIdx.x * kChunk + threadIdx.x;
+    vec4_t s = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const size_t i = base + (size_t)k * 256;
+        s ^= __builtin_nontemporal_load(src + (i < n ? i : 0));
     }
-    for (; i < n; i += stride) { const uint4 a = src[i]; s.x ^= a.x; s.y ^= a.y; s.z ^= a.z; s.w ^= a.w; }
-    // one 16-byte store per thread: 1/(trips*4) of the bytes read, and it keeps the loads alive
-    sink[blockIdx.x * (size_t)256 + threadIdx.x] = s;
+    // (a store that in practice never happens keeps the loads alive)
+    if (s.x == 0x12345678u && s.y == 0x9abcdef0u && s.z == 0x0fedcba9u) sink[threadIdx.x] = s;
 }
 
-__global__ __launch_bounds__(256) void stream_write_kernel(uint4 *dst, size_t n, uint32_t v)
+__global__ __launch_bounds__(256) void stream_write_kernel(vec4_t *dst, size_t n, uint32_t v)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    const uint4 w = make_uint4(v, v + 1, v + 2, v + 3);
-    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += stride) dst[i] = w;
+    const size_t base = (size_t)blockIdx.x * kChunk + threadIdx.x;
+    const vec4_t w = {v, v + 1, v + 2, v + 3};
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const size_t i = base + (size_t)k * 256;
+        if (i < n) __builtin_nontemporal_store(w, dst + i);
+    }
 }
 
 __global__ __launch_bounds__(256) void mfma_loop_kernel(float *sink, int iters)
@@ -87,36 +99,33 @@ extern "C" alt_status_t alt_get_peak(alt_handle_t h, void *arena, size_t arena_b
     const size_t n = half / 16;
     const int cus = h->compute_units > 0 ? h->compute_units : 256;
     float ms = 0.f;
-    const int blocks = cus * 8;
+    const unsigned blocks = (unsigned)((n + kChunk - 1) / kChunk);
     for (int pass = 0; pass < 2; ++pass) {
         ALT_CHECK_HIP(h, hipEventRecord(e0, 0));
         for (int r = 0; r < 10; ++r)
-            hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, 0, (const uint4 *)arena,
-                               (uint4 *)((char *)arena + half), n);
+            hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, 0, (const vec4_t *)arena,
+                               (vec4_t *)((char *)arena + half), n);
         ALT_CHECK_HIP(h, hipEventRecord(e1, 0));
         ALT_CHECK_HIP(h, hipEventSynchronize(e1));
         ALT_CHECK_HIP(h, hipEventElapsedTime(&ms, e0, e1));
     }
     out->copy_gbps = (float)(2.0 * half * 10 / (ms * 1e-3) / 1e9);
-    // read-only and write-only streams over the whole arena (the reader's sink is the first
-    // blocks * 4 KiB of the upper half, which the writer then overwrites)
+    // read-only and write-only passes over the whole arena
     const size_t whole = (arena_bytes & ~(size_t)255), nw = whole / 16;
-    if ((size_t)blocks * 4096 <= half) {
-        for (int pass = 0; pass < 2; ++pass) {
-            ALT_CHECK_HIP(h, hipEventRecord(e0, 0));
-            for (int r = 0; r < 10; ++r)
-                hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, 0, (const uint4 *)arena,
-                                   (uint4 *)((char *)arena + half), n);
-            ALT_CHECK_HIP(h, hipEventRecord(e1, 0));
-            ALT_CHECK_HIP(h, hipEventSynchronize(e1));
-            ALT_CHECK_HIP(h, hipEventElapsedTime(&ms, e0, e1));
-        }
-        out->read_gbps = (float)(1.0 * half * 10 / (ms * 1e-3) / 1e9);
-    }
+    const unsigned wblocks = (unsigned)((nw + kChunk - 1) / kChunk);
     for (int pass = 0; pass < 2; ++pass) {
         ALT_CHECK_HIP(h, hipEventRecord(e0, 0));
         for (int r = 0; r < 10; ++r)
-            hipLaunchKernelGGL(stream_write_kernel, dim3(blocks), dim3(256), 0, 0, (uint4 *)arena, nw, (uint32_t)r);
+            hipLaunchKernelGGL(stream_read_kernel, dim3(wblocks), dim3(256), 0, 0, (const vec4_t *)arena, (vec4_t *)arena, nw);
+        ALT_CHECK_HIP(h, hipEventRecord(e1, 0));
+        ALT_CHECK_HIP(h, hipEventSynchronize(e1));
+        ALT_CHECK_HIP(h, hipEventElapsedTime(&ms, e0, e1));
+    }
+    out->read_gbps = (float)(1.0 * whole * 10 / (ms * 1e-3) / 1e9);
+    for (int pass = 0; pass < 2; ++pass) {
+        ALT_CHECK_HIP(h, hipEventRecord(e0, 0));
+        for (int r = 0; r < 10; ++r)
+            hipLaunchKernelGGL(stream_write_kernel, dim3(wblocks), dim3(256), 0, 0, (vec4_t *)arena, nw, (uint32_t)r);
         ALT_CHECK_HIP(h, hipEventRecord(e1, 0));
         ALT_CHECK_HIP(h, hipEventSynchronize(e1));
         ALT_CHECK_HIP(h, hipEventElapsedTime(&ms, e0, e1));
