@@ -229,6 +229,22 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
                         const float *bias, void *y, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_conv2d_workspace_size(alt_handle_t h, const alt_conv_desc_t *d, size_t *bytes);
 
+/* alt_conv2d for callers that cannot bring a workspace or allocate one: code under HIP
+ * graph capture, serving loops and harnesses where hipMalloc is forbidden.  Same operation,
+ * same kernels and same variant choice as alt_conv2d, but the split-K partial tiles go to a
+ * static device array of ALT_STATIC_WORKSPACE_BYTES that the library's code object holds on
+ * every device it is loaded on, from load to process end.  The call allocates and frees no
+ * device memory.  With variant = -1 only variants whose partial tiles fit the array are
+ * picked (none are needed without split-K); an explicit split-K variant that needs more
+ * fails with ALT_WORKSPACE_TOO_SMALL and a message giving both sizes.  Nothing in the array
+ * has to be zero between calls (every partial tile is written before it is read; the
+ * arrival counters reset themselves).  All calls on one device share the one array: two
+ * calls that may run at the same time (different streams, or a replayed graph beside eager
+ * calls) race on it and must be ordered by the caller; calls on one stream are ordered. */
+#define ALT_STATIC_WORKSPACE_BYTES (32u << 20)
+alt_status_t alt_conv2d_static(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w,
+                               const float *bias, void *y, void *stream);
+
 /* Split-K variants of the tile kernels (names ending _k2, _k4, ...: the reduction over input
  * channels of the Fig. 3 program cut into slices that run as separate workgroups) sum their
  * slices inside the one launch: every slice writes its partial tile to `workspace`, the last

@@ -172,7 +172,7 @@ def exported_symbols():
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_conv2d_multi", "alt_tune_chain", "alt_plan_chain",
             "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
-            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_layout_transform_plan", "alt_splitk_status"]
+            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_layout_transform_plan", "alt_splitk_status", "alt_conv2d_static"]
 
 
 def version():
@@ -353,6 +353,9 @@ class Handle:
     def conv2d(self, d, x, w, y, bias=None, workspace=None, ws_bytes=0, stream=None):
         _ck(lib().alt_conv2d(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
                              _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream(stream)), self._h)
+
+    def conv2d_static(self, d, x, w, y, bias=None, stream=None):
+        _ck(lib().alt_conv2d_static(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _stream(stream)), self._h)
 
     def conv2d_add(self, d, x, w, addend, y, bias=None, workspace=None, ws_bytes=0, stream=None):
         _ck(lib().alt_conv2d_add(self._h, ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(addend), _ptr(y),

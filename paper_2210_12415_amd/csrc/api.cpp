@@ -41,6 +41,10 @@ alt_status_t alt_create(alt_handle_t *out)
         (void)hipGetLastError();
     }
     if (!c->has_gpu) c->arch = "none";
+    else {
+        void *ws = nullptr;
+        (void)alt::static_scratch(&ws);            // address of alt_conv2d_static's array on this device (kept per device)
+    }
     *out = c;
     return ALT_OK;
 }

@@ -34,6 +34,9 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
 void dconv_splitk_state(int *slots_bound, int *counters_nonzero);
 hipError_t dconv_run(const IgemmLaunch &k, DconvParams d, size_t lds, float *partial, hipStream_t st);
 
+// ops.hip: device address of alt_conv2d_static's workspace array on the current device
+hipError_t static_scratch(void **out);
+
 // dwconv.hip
 alt_status_t depthwise_run(alt_handle_t h, const Problem &pb, int64_t N, int64_t C, hipStream_t st);
 

@@ -517,6 +517,52 @@ alt_status_t alt_conv2d(alt_handle_t h, const alt_conv_desc_t *d, const void *x,
     return conv2d_impl(h, d, x, w, bias, nullptr, y, workspace, ws_bytes, stream, "alt_conv2d");
 }
 
+// ---- alt_conv2d without a caller's workspace ---------------------------------------------
+// The split-K partial tiles of alt_conv2d_static live in this array instead of a workspace
+// the caller brings.  The name below is a host-side stand-in: the array's device address is
+// looked up once per device (static_scratch) and that pointer is what kernels get.
+constexpr size_t kStaticScratchBytes = ALT_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void *g_scratch_ptr[16];
+static std::mutex g_scratch_mutex;
+
+}  // extern "C"
+
+namespace alt {
+// Device address of `scratch` on the current device; first use on a device asks the runtime.
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace alt
+
+extern "C" {
+
+alt_status_t alt_conv2d_static(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
+                               void *y, void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    void *ws = nullptr;
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return fail(h, ALT_HIP_ERROR, "alt_conv2d_static: no address for the static workspace: %s", hipGetErrorString(e));
+    // (an explicitly requested variant whose partial tiles exceed the array fails in igemm_run with
+    // ALT_WORKSPACE_TOO_SMALL and the two sizes; variant = -1 only picks variants that fit)
+    return conv2d_impl(h, d, x, w, bias, nullptr, y, ws, kStaticScratchBytes, stream, "alt_conv2d_static");
+}
+
 alt_status_t alt_conv2d_add(alt_handle_t h, const alt_conv_desc_t *d, const void *x, const void *w, const float *bias,
                             const void *addend, void *y, void *workspace, size_t ws_bytes, void *stream)
 {
