@@ -372,3 +372,51 @@ def test_conv_transpose_host_side(oracle):
     import ctypes
     assert alt.lib().alt_conv2d_multi(h._h, None, ctypes.c_int32(2)) == 1
     assert alt.lib().alt_conv2d_multi(h._h, None, ctypes.c_int32(-1)) == 1
+
+
+# ---- the conversion operator's launch plan, replayed on the host -------------------------------------
+
+_PLAN_PAIRS = [("NCHW->NCHW", "NCHW->NHWC"), ("NCHW->NHWC", "NCHW->NCHW"), ("NCHW->NCHW", "NCHW->NCHW16c"),
+               ("NCHW->NCHW16c", "NCHW->NCHW"), ("NCHW->NCHW", "NCHW->NCHW32c"), ("NCHW->NCHW", "NCHW->HWNC"),
+               ("NCHW->CNHW", "NCHW->NCHW4c"), ("NCHW->NCHW32c", "NCHW->NHWC")]
+_PLAN_SHAPES = [(2, 32, 5, 7), (3, 64, 14, 14), (1, 32, 1, 1), (2, 96, 7, 7), (1, 32, 9, 40), (2, 64, 56, 56),
+                (4, 256, 14, 14), (8, 512, 7, 7), (40, 512, 7, 7), (5, 32, 49, 1)]
+
+
+@pytest.mark.parametrize("shape", _PLAN_SHAPES)
+def test_transform_plan_replays_to_the_index_maps(shape):
+    """Every workgroup of the tile kernel's launch plan, replayed on the host (alt_layout_transform_plan):
+    each destination element is written exactly once, from the source element that the two layouts' index
+    maps name; every LDS index lies inside the tile; every vector access is aligned and inside its buffer.
+    Both element sizes, aligned buffers and buffers off by one element or by eight bytes."""
+    h = alt.Handle()
+    tiles = 0
+    for a, b in _PLAN_PAIRS:
+        for dt, es in ((alt.F32, 4), (alt.BF16, 2)):
+            for sm, dm in ((0, 0), (es, 0), (0, es), (8, 8)):
+                p = h.layout_transform_plan(dt, shape, a, b, sm, dm, replay=True)
+                assert p.kind in (0, 1, 2, 3)
+                if p.kind == 3:
+                    tiles += 1
+                    assert p.mismatches == 0, (shape, a, b, dt, sm, dm, p.mismatches, p.src_flat, p.dst_flat,
+                                               p.tile_a, p.tile_b, p.tile_g)
+                    assert p.lds_bytes <= 64 * 1024 and p.workgroups >= 1
+    assert tiles > 0 or shape[2] * shape[3] == 1        # (a 1x1 image leaves nothing to transpose)
+
+
+def test_transform_plan_takes_contiguous_runs_where_rows_are_odd():
+    """49-element rows (7x7 images) take no 16-byte vectors on their own; the plan moves them as part of
+    one contiguous run per tile (a flat side) with 16-byte accesses, on the side where they are contiguous."""
+    h = alt.Handle()
+    for dt in (alt.F32, alt.BF16):
+        p = h.layout_transform_plan(dt, (64, 512, 7, 7), "NCHW->NCHW", "NCHW->NHWC")
+        assert p.kind == 3 and p.src_flat == 1 and p.load_bytes == 16 and p.store_bytes == 16 and p.tile_a == 49
+        p = h.layout_transform_plan(dt, (64, 512, 7, 7), "NCHW->NHWC", "NCHW->NCHW")
+        assert p.kind == 3 and p.dst_flat == 1 and p.load_bytes == 16 and p.store_bytes == 16 and p.tile_b == 49
+        p = h.layout_transform_plan(dt, (64, 512, 7, 7), "NCHW->NCHW", "NCHW->NCHW16c")
+        assert p.kind == 3 and p.src_flat == 1 and p.load_bytes == 16 and p.store_bytes == 16
+    # buffers that are not 16-byte aligned cannot be flat
+    p = h.layout_transform_plan(alt.BF16, (64, 512, 7, 7), "NCHW->NCHW", "NCHW->NHWC", 2, 0)
+    assert p.kind == 3 and p.src_flat == 0 and p.load_bytes == 2
+    with pytest.raises(alt.AltError):
+        h.layout_transform_plan(alt.F32, (2, 4, 2, 2), "NCHW->NCHW", "NCHW->NHWC", 2, 0)     # not a multiple of the element size
