@@ -378,6 +378,115 @@ __device__ __forceinline__ bool dconv_epilogue(const DconvParams &p, floatx16_t 
     return mine;
 }
 
+// Whether a tile kernel's output staging (every wave's whole tile at once) exceeds LDS; such
+// kernels stage and store their tiles 32 rows at a time instead (dconv_epilogue_banded).
+template <int BM, int BN, int WGN, int KW>
+constexpr bool kBandedEpilogue = (size_t)KW * BM * (BN + 8 * WGN) * 4 + 16 > 160 * 1024;
+
+// The end of a tile kernel whose wave tiles are too large to stage whole (128 x 128 per wave):
+// each wave takes its tile through a private LDS region one band of 32 rows at a time, then
+// stores the band with 16-byte accesses (four fp32 or eight bf16 columns per lane) exactly as
+// dconv_epilogue_tail does.  One K group and no split-K (the host does not offer these
+// kernels with either); a wave only reads back what it wrote, so after the opening
+// barrier (all waves done with the operand stages) no further one is needed.
+template <int BM, int BN, int WGM, int WGN>
+__device__ __forceinline__ void dconv_epilogue_banded(const DconvParams &p, floatx16_t (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                                      uint4 *smem_u4, int lane, int wave, int wm, int wn, int m0, int n0,
+                                                      char *y)
+{
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int SP = WTN + 4;                            // staging pitch in floats
+    __syncthreads();
+    float *stg = (float *)smem_u4 + wave * (32 * SP);
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)p.y_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc((void *)p.addend, 0, (int)p.y_bytes, 0x00020000);
+    const float relu_floor = (p.flags & ALT_EPI_RELU) ? 0.f : -INFINITY;
+    const bool wide = (p.flags & kDconvOutBf16) && p.Nc % 8 == 0;      // eight bf16 columns per lane
+    auto band = [&](auto cw, int i) {
+        constexpr int CW = decltype(cw)::value;
+        constexpr int V = CW / 4, CPRW = WTN / CW, RPI = 64 / CPRW, NIT = 32 / RPI;
+        const int cl = lane % CPRW, rl = lane / CPRW;
+        const int n = n0 + wn * WTN + cl * CW;
+        const bool n_ok = n < p.Nc;
+        float bv[CW];
+#pragma unroll
+        for (int q = 0; q < CW; ++q) bv[q] = 0.f;
+        if (n_ok && (p.flags & ALT_EPI_BIAS)) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float4 b4 = *(const float4 *)(p.bias + n + v * 4);
+                bv[v * 4 + 0] = b4.x; bv[v * 4 + 1] = b4.y; bv[v * 4 + 2] = b4.z; bv[v * 4 + 3] = b4.w;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int row = it * RPI + rl;
+            const int m = m0 + wm * WTM + i * 32 + row;
+            const bool ok = n_ok && m < p.M;
+            float o[CW];
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float4 f = *(const float4 *)(stg + row * SP + cl * CW + v * 4);
+                o[v * 4 + 0] = f.x; o[v * 4 + 1] = f.y; o[v * 4 + 2] = f.z; o[v * 4 + 3] = f.w;
+            }
+            const uint32_t el = (uint32_t)(m * p.Nc + n);
+            float ad[CW];                                  // the fused sum's other operand: y's layout and element type
+#pragma unroll
+            for (int q = 0; q < CW; ++q) ad[q] = 0.f;
+            if (!p.addend) {
+            } else if (CW == 8 || (p.flags & kDconvOutBf16)) {
+                u32x4_t av = {0u, 0u, 0u, 0u};
+                if constexpr (CW == 8) av = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? el * 2u : kOutOfRange), 0, 0);
+                else {
+                    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+                    const u32x2_t a2 = __builtin_amdgcn_raw_buffer_load_b64(ar, (int)(ok ? el * 2u : kOutOfRange), 0, 0);
+                    av = __builtin_shufflevector(a2, a2, 0, 1, 0, 1);
+                }
+                const f32x4_t lo = __builtin_bit_cast(f32x4_t, av << 16), hi = __builtin_bit_cast(f32x4_t, av & 0xffff0000u);
+#pragma unroll
+                for (int q = 0; q < CW / 2; ++q) { ad[2 * q] = lo[q]; ad[2 * q + 1] = hi[q]; }
+            } else {
+                const f32x4_t a4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? el * 4u : kOutOfRange), 0, 0));
+                const f32x4_t z = a4 + (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ad[q] = z[q];
+            }
+#pragma unroll
+            for (int q = 0; q < CW; ++q) o[q] = fmaxf(o[q] + bv[q] + ad[q], relu_floor);
+            if (CW == 8 || (p.flags & kDconvOutBf16)) {
+                uint32_t w[CW / 2];
+#pragma unroll
+                for (int q = 0; q < CW / 2; ++q) w[q] = f32x2_to_bf16x2(o[2 * q], o[2 * q + 1]);
+                if constexpr (CW == 8) {
+                    u32x4_t ov = {w[0], w[1], w[2], w[3]};
+                    __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? el * 2u : kOutOfRange), 0, kWriteThrough);
+                } else {
+                    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+                    u32x2_t ov = {w[0], w[1]};
+                    __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? el * 2u : kOutOfRange), 0, kWriteThrough);
+                }
+            } else {
+                u32x4_t ov = {__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                              __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])};
+                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? el * 4u : kOutOfRange), 0, kWriteThrough);
+            }
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        // band i of the wave's tile to row-major order (same element mapping as in dconv_epilogue)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(float4 *)(stg + (lane & 31) * SP + j * 32 + 8 * q + 4 * (lane >> 5)) =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        if (wide) band(std::integral_constant<int, 8>{}, i);
+        else band(std::integral_constant<int, 4>{}, i);
+    }
+}
+
 // Waves per SIMD the register allocation must leave room for (a SIMD has 512 registers per
 // lane, accumulators included).  Without a bound the allocator spreads the accumulators
 // over the second register file and takes what it likes: one wave per SIMD for 64x64 wave

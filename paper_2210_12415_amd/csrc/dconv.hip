@@ -143,8 +143,9 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
         return no("operand of 2 GiB or more");
     if ((int64_t)p.M * K * 4 >= 0x7fffffff) return no("output too large for 32-bit offsets");
     if (K % 4 || (p.epilogue & ALT_EPI_BIAS && (uintptr_t)p.bias % 16)) return no("streaming kernel stores four output columns at a time");
-    const size_t lds = dstream_lds_bytes(k.BM, k.BN, k.BK, k.prefetch + 1, k.wgn, k.kw);
+    const size_t lds = dstream_lds_bytes(k.BM, k.BN, k.BK, k.prefetch + 1, k.wgm, k.wgn, k.kw);
     if (lds > 160 * 1024) return no("stages do not fit LDS");
+    if (dstream_banded(k.BM, k.BN, k.wgn, k.kw) && splitk > 1) return no("tiles this large take no split-K");
     const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
     if (splitk > 1 && (int64_t)tiles_m * tiles_n > kDconvMaxTiles) return no("too many output tiles for the split-K counters");
     if ((int64_t)tiles_m * tiles_n * splitk > 0x7fffffff) return no("grid too large");

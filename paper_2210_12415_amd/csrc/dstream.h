@@ -130,7 +130,9 @@ void dstream_kernel(const DconvParams p)
 
     // Operand reads run D k-chunks ahead of the MFMAs that use them; k chunk g (counted
     // from the start of a round over the stages) uses register buffer g % NBUF.
-    constexpr int D0 = (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
+    // (wave tiles of eight or more MFMAs per k chunk run a hand-pinned schedule, one chunk ahead: see do_step)
+    constexpr bool kPinned = KW == 1 && TM * TN >= 8 && TM >= 2 && LPS <= NKC * TM;
+    constexpr int D0 = kPinned ? 1 : (TM + TN) * 3 <= 15 ? 3 : (TM + TN) * 2 <= 15 ? 2 : 1;
     constexpr int D = D0 < NKC ? D0 : NKC;                 // the look-ahead stays within the next step
     constexpr int NBUF = 4;
     static_assert(D < NBUF && NBUF % NKC == 0, "fragment buffers");
@@ -147,30 +149,71 @@ void dstream_kernel(const DconvParams p)
 
     wait_vmcnt<(NS - 2) * LPS>();                          // stage 0 (this wave's share)
     lds_barrier();
-    static_for<D>(reads);
+    static_for<D>(reads);                                  // (D = 1 for the wave tiles with a pinned schedule)
 
     // One K step in stage st.  At its barrier every wave has its share of the next stage
     // landed, so both are complete for everybody afterwards and the look-ahead may run into
     // the next stage; the barrier also says the previous stage is consumed, and its refill
     // is issued right after it.  Past the last step the look-ahead reads whatever the
     // repeated loads left in the next stage (never used).
+    //
+    // Large wave tiles (kPinned: at least eight MFMAs per k chunk, one wave per SIMD) fix the
+    // instruction order by hand: with nobody else on the SIMD to fill a gap, whatever stands
+    // between two MFMAs and does not fit the first one's shadow is lost.  After each row of
+    // TN MFMAs come a few of the next chunk's operand reads (all of them within the first
+    // TM - 1 rows, so that the last row's MFMAs cover their latency) and one of the step's
+    // direct-to-LDS loads; scheduling barriers keep the compiler from regrouping them.
+    auto issue_one = [&](int i) {                          // load i of the stage the cursor is on
+        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * (BK * 2);
+        const uint32_t dst = ldsW + lstage * STAGE;
+        if (i < NLA) dma_load16_s(x_rsrc, a_voff[i], soff, dst + i * (NWG * 1024));
+        else dma_load16_s(w_rsrc, b_voff[i - NLA], soff, dst + A_STAGE + (i - NLA) * (NWG * 1024));
+    };
     auto do_step = [&](auto ST) {
         constexpr int st = decltype(ST)::value;
         wait_vmcnt<(NS - 3) * LPS>();
         if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");
-        issue_stage();
-        static_for<NKC>([&](auto KC) {
-            constexpr int g = st * NKC + decltype(KC)::value, buf = g % NBUF;
-            reads(std::integral_constant<int, g + D>{});
-            lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
+        if constexpr (!kPinned) {
+            issue_stage();
+            static_for<NKC>([&](auto KC) {
+                constexpr int g = st * NKC + decltype(KC)::value, buf = g % NBUF;
+                reads(std::integral_constant<int, g + D>{});
+                lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
-                                                                        __builtin_bit_cast(bf16x8_t, af[buf][i]),
-                                                                        acc[i][j], 0, 0, 0);
-        });
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                            __builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                            acc[i][j], 0, 0, 0);
+            });
+        } else {
+            static_for<NKC>([&](auto KC) {
+                constexpr int kc = decltype(KC)::value, g = st * NKC + kc, buf = g % NBUF;
+                // the chunk this one's rows read ahead for: D = 1 here (TM + TN reads fill the counter's range)
+                constexpr int gn = g + 1, stn = (gn / NKC) % NS, kcn = gn % NKC, bufn = gn % NBUF, offn = stn * STAGE;
+                constexpr int RPS = (TM + TN + TM - 2) / (TM - 1);             // reads per row slot, rows 0 .. TM - 2
+                lds_wait<0>(af[buf], bf[buf]);
+                static_for<TM>([&](auto IR) {
+                    constexpr int i = decltype(IR)::value;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                            __builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                            acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<RPS>([&](auto RR) {
+                        constexpr int r = i * RPS + decltype(RR)::value;
+                        if constexpr (r < TM) lds_read16_async_at<offn>(af[bufn][r], a_rd[r][kcn]);
+                        else if constexpr (r < TM + TN) lds_read16_async_at<offn>(bf[bufn][r - TM], b_rd[r - TM][kcn]);
+                    });
+                    if constexpr (kc * TM + i < LPS) issue_one(kc * TM + i);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
+            ++lstep;
+            lstage = lstage + 1 == NS ? 0 : lstage + 1;
+        }
     };
     int ks0 = 0;
     for (; ks0 + NS <= nk; ks0 += NS)                      // whole rounds over the stages, no exit inside
@@ -190,15 +233,29 @@ void dstream_kernel(const DconvParams p)
         for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bf[kc][j]));
     }
 
-    dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
-                                         (char *)p.y + (int64_t)bz * p.y_bstride);
+    if constexpr (kBandedEpilogue<BM, BN, WGN, KW>) {
+        static_assert(KW == 1, "banded epilogue: one K group");
+        dconv_epilogue_banded<BM, BN, WGM, WGN>(p, acc, smem_u4, lane, wave, wm, wn, m0, n0,
+                                                (char *)p.y + (int64_t)bz * p.y_bstride);
+    } else {
+        dconv_epilogue<BM, BN, WGM, WGN, KW>(p, acc, smem_u4, t, lane, wave, kg, wq, wm, wn, m0, n0, mt, nt, split,
+                                             (char *)p.y + (int64_t)bz * p.y_bstride);
+    }
 }
 
 // LDS bytes of one workgroup: the K groups' operand rings, or the output staging.
-inline size_t dstream_lds_bytes(int BM, int BN, int bk, int NS, int waves_n, int kw)
+// (kernels whose whole-tile staging exceeds LDS stage 32 rows per wave at a time: see kBandedEpilogue)
+inline bool dstream_banded(int BM, int BN, int waves_n, int kw)
+{
+    return (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16 > 160 * 1024;
+}
+
+inline size_t dstream_lds_bytes(int BM, int BN, int bk, int NS, int waves_m, int waves_n, int kw)
 {
     const size_t main_loop = (size_t)kw * NS * (BM + BN) * bk * 2;
-    const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
+    const size_t staging = dstream_banded(BM, BN, waves_n, kw)
+        ? (size_t)waves_m * waves_n * 32 * (BN / waves_n + 4) * 4
+        : (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
     return main_loop > staging ? main_loop : staging;
 }
 
