@@ -643,7 +643,7 @@ def main():
             wsd = torch.randint(-200, 200, (L["K"] * L["C"] * L["R"] * L["S"],), dtype=torch.int16, device=dev)
             oh, ow = conv_out_hw(L["H"], L["W"], L["R"], L["S"], L["stride"], L["pad"])
             ys = torch.empty(batch * L["K"] * oh * ow, dtype=torch.int16, device=dev)
-            us_best, _ = h.tune_conv2d_variants(shape, arena, arena.numel(), max_trials=24, warmup=2, reps=10)
+            us_best, _ = h.tune_conv2d_variants(shape, arena, arena.numel(), max_trials=96, warmup=2, reps=10)
             us = median_timed(lambda: h.conv2d(shape, xs, wsd, ys, workspace=arena, ws_bytes=arena.numel(), stream=stream), 20, 3)
             fl = conv_flops(batch, **L)
             scaled.append(dict(layer=L["name"], batch=batch, variant=h.conv2d_variant_name(shape, shape.variant),

@@ -422,7 +422,11 @@ alt_status_t alt_conv3d_transpose_weight_shape(alt_handle_t h, const alt_conv3d_
 
 /* Kernel variants applicable to a descriptor (loop-tuning space of Section
  * 4.3 realised as tile shapes, K-depth per LDS stage, split-K factor and
- * operand loader).  Variant numbers are stable within one library build. */
+ * operand loader).  Variant numbers are stable within one library build.
+ * alt_conv2d_variant_name with variant = -1 names the variant alt_conv2d picks for
+ * the descriptor when it is left to choose (the tuned one if the cache has it, else
+ * the best by the library's cost estimate); ALT_UNSUPPORTED if `variant` does not
+ * apply to the descriptor. */
 alt_status_t alt_conv2d_variant_count(alt_handle_t h, const alt_conv_desc_t *d, int *count);
 alt_status_t alt_conv2d_variant_name(alt_handle_t h, const alt_conv_desc_t *d, int variant,
                                      char *buf, size_t buflen);

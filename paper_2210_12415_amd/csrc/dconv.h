@@ -724,34 +724,70 @@ void dconv_kernel(const DconvParams p)
         wait_vmcnt<(NS - 2) * NLB>();                      // the patch and stage 0
         lds_barrier();
         // reads of k chunk g (counted over all steps); past the last step they repeat it (never used)
-        auto reads = [&](auto gc) {
-            constexpr int g = decltype(gc)::value;
+        auto read_one = [&](auto gc, auto rc) {            // operand read r of chunk g: the TM patch rows, then the TN weight rows
+            constexpr int g = decltype(gc)::value, r = decltype(rc)::value;
             constexpr int step = g / NKC < NSTEPS ? g / NKC : NSTEPS - 1, kc = g % NKC, buf = g % NBUF;
             constexpr int tap = step / NCC, cc = step % NCC, st = step % NS;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) lds_read16_async_at<cc * (BK * 2) + kc * 32>(af[buf][i], t_row[tap][i]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) lds_read16_async_at<st * B_STAGE>(bf[buf][j], b_rd[j][kc]);
+            if constexpr (r < TM) lds_read16_async_at<cc * (BK * 2) + kc * 32>(af[buf][r], t_row[tap][r]);
+            else lds_read16_async_at<st * B_STAGE>(bf[buf][r - TM], b_rd[r - TM][kc]);
         };
-        static_for<D>([&](auto gc) { reads(gc); });
+        auto reads = [&](auto gc) {
+            static_for<TM + TN>([&](auto rc) { read_one(gc, rc); });
+        };
+        // Large wave tiles run a hand-pinned instruction order (see the streaming kernel, dstream.h):
+        // after each row of TN MFMAs a few of the next chunk's operand reads and one weight load.
+        constexpr bool kPinned = KW == 1 && TM * TN >= 8 && TM >= 2 && NLB <= NKC * TM;
+        constexpr int DP = kPinned ? 1 : D;
+        static_for<DP>([&](auto gc) { reads(gc); });
         static_for<NSTEPS>([&](auto sc) {
             constexpr int step = decltype(sc)::value;
             wait_vmcnt<(NS - 3) * NLB>();                  // stage step+1 has landed (this wave's share)
             if constexpr (NWG > 1) asm volatile("s_barrier" ::: "memory");   // (a one-wave group loads its ring alone)
-            issue_b();
-            static_for<NKC>([&](auto kcc) {
-                constexpr int kc = decltype(kcc)::value;
-                constexpr int buf = (step * NKC + kc) % NBUF;
-                reads(std::integral_constant<int, step * NKC + kc + D>{});
-                lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
+            if constexpr (!kPinned) {
+                issue_b();
+                static_for<NKC>([&](auto kcc) {
+                    constexpr int kc = decltype(kcc)::value;
+                    constexpr int buf = (step * NKC + kc) % NBUF;
+                    reads(std::integral_constant<int, step * NKC + kc + D>{});
+                    lds_wait<D * (TM + TN)>(af[buf], bf[buf]);
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
-                                                                            __builtin_bit_cast(bf16x8_t, af[buf][i]),
-                                                                            acc[i][j], 0, 0, 0);
-            });
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                                __builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                                acc[i][j], 0, 0, 0);
+                });
+            } else {
+                static_for<NKC>([&](auto kcc) {
+                    constexpr int kc = decltype(kcc)::value, g = step * NKC + kc, buf = g % NBUF;
+                    constexpr int RPS = (TM + TN + TM - 2) / (TM - 1);         // reads per row slot, rows 0 .. TM - 2
+                    lds_wait<0>(af[buf], bf[buf]);
+                    static_for<TM>([&](auto IR) {
+                        constexpr int i = decltype(IR)::value;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bf[buf][j]),
+                                                                                __builtin_bit_cast(bf16x8_t, af[buf][i]),
+                                                                                acc[i][j], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        static_for<RPS>([&](auto RR) {
+                            constexpr int r = i * RPS + decltype(RR)::value;
+                            if constexpr (r < TM + TN) read_one(std::integral_constant<int, g + 1>{}, std::integral_constant<int, r>{});
+                        });
+                        if constexpr (kc * TM + i < NLB)
+                            dma_load16_s(w_rsrc, b_voff[kc * TM + i], lsoff, ldsB + lstage * B_STAGE + (kc * TM + i) * (NWG * 1024));
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                });
+                // the cursor moves on as in issue_b
+                ++lstep;
+                lstage = lstage + 1 == NS ? 0 : lstage + 1;
+                const bool more = lstep < nsteps;
+                const bool wrap = lcc + 1 == ncc;
+                lsoff += more ? (uint32_t)(BK * 2) + (wrap ? (uint32_t)(p.C - csg) * 2u : 0u) : 0u;
+                lcc = more ? (wrap ? 0 : lcc + 1) : lcc;
+            }
         });
     } else {
         static_assert(KR > 0 || NKC == NBUF, "the run-time path takes 64-channel steps");

@@ -184,6 +184,9 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
     if (k.bmode == LOAD_TRANS) mode_cost *= 1.5;
     if (k.prefetch > 1) mode_cost *= 0.8;
     if (k.launch_direct) mode_cost *= 0.5;
+    // (a 1x1 filter leaves the patch-resident kernel nothing to reuse: the streaming kernel runs the same
+    // problem without staging the patch first, and has measured faster wherever both apply)
+    if (k.launch_direct && p.R == 1 && p.S == 1) mode_cost *= 1.5;
     const double blocks = (double)p.tiles_m * p.tiles_n * p.splitk * p.batch;
     const double rounds = std::ceil(blocks / 512.0);
     const double step = (double)k.BM * k.BN * k.BK / 16384.0 + 3.0 * (k.BM + k.BN) * k.BK / 8192.0 + 2.0;
@@ -609,13 +612,17 @@ alt_status_t alt_conv2d_variant_name(alt_handle_t h, const alt_conv_desc_t *d, i
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !buf || buflen == 0) return fail(h, ALT_INVALID_ARG, "null argument");
-    std::string n = igemm_variant_name(variant);
-    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
-    std::snprintf(buf, buflen, "%s", n.c_str());
     Problem pb;
     alt_status_t s = conv_problem(h, d, (void *)16, (void *)16, nullptr, (void *)16, &pb);
     if (s != ALT_OK) return s;
     if (pb.depthwise) return fail(h, ALT_UNSUPPORTED, "depth-wise convolutions have no kernel variants");
+    if (variant < 0) {                               // the variant alt_conv2d would run with variant = -1 and any workspace
+        variant = pick_variant(h, pb, -1, conv_key(h, d), (size_t)-1);
+        if (variant < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
+    }
+    std::string n = igemm_variant_name(variant);
+    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
+    std::snprintf(buf, buflen, "%s", n.c_str());
     std::string why;
     const auto &tab = igemm_table();
     if (!igemm_applicable(pb, tab[variant / kNumSplits], kSplits[variant % kNumSplits], nullptr, &why))

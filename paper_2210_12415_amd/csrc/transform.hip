@@ -74,34 +74,57 @@ __device__ inline void locate_tile(const PermuteParams &p, int64_t &src_base, in
     }
 }
 
-// Streaming accesses.  A conversion reads every source element once and writes every destination
-// element once, so both carry the non-temporal hint: the lines are not kept in the caches at the
-// expense of data somebody will read again.  Measured on 1 GiB rings against plain loads with
-// write-through stores: +25 % on a 12.8 MB tensor, +10 % on a 205 MB one.
-template <typename V>
-__device__ __forceinline__ void store_through(char *addr, const V &w)
+// Two access policies.  Streaming (NT = true): a conversion reads every source element once and
+// writes every destination element once, so both sides carry the non-temporal hint and the lines
+// do not displace data somebody will read again; on tensors that exceed the caches this measured
+// +25 % (12.8 MB tensor, cold) and +10 % (205 MB) against the other policy.  Cached (NT = false):
+// plain loads, stores that go through to memory as they are written (sc0 sc1) but stay in the L2:
+// a tensor that an operator has just produced is read from the cache, and the converted tensor is
+// there for the operator that consumes it (7.2 -> 5.5 us for a 12.8 MB tensor between two layers).
+// The host takes the cached policy for tensors of up to kStreamingBytes.
+constexpr size_t kStreamingBytes = (size_t)16 << 20;
+
+template <bool NT, typename V>
+__device__ __forceinline__ void store_vec(char *addr, const V &w)
 {
     typedef uint32_t n4_t __attribute__((ext_vector_type(4)));
     typedef uint32_t n2_t __attribute__((ext_vector_type(2)));
-    if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(__builtin_bit_cast(n4_t, w), (n4_t *)addr);
-    else if constexpr (sizeof(V) == 8) __builtin_nontemporal_store(__builtin_bit_cast(n2_t, w), (n2_t *)addr);
-    else if constexpr (sizeof(V) == 4) __builtin_nontemporal_store(__builtin_bit_cast(uint32_t, w), (uint32_t *)addr);
-    else __builtin_nontemporal_store(__builtin_bit_cast(uint16_t, w), (uint16_t *)addr);
+    if constexpr (NT) {
+        if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(__builtin_bit_cast(n4_t, w), (n4_t *)addr);
+        else if constexpr (sizeof(V) == 8) __builtin_nontemporal_store(__builtin_bit_cast(n2_t, w), (n2_t *)addr);
+        else if constexpr (sizeof(V) == 4) __builtin_nontemporal_store(__builtin_bit_cast(uint32_t, w), (uint32_t *)addr);
+        else __builtin_nontemporal_store(__builtin_bit_cast(uint16_t, w), (uint16_t *)addr);
+    } else if constexpr (sizeof(V) == 16) {
+        // (a store of more than 64 bits reads its data registers up to two cycles after it issues, and
+        // the compiler, which keeps VALU writes to them away from its own stores, does not look inside
+        // an asm statement: the wait states stand here)
+        const n4_t v = __builtin_bit_cast(n4_t, w);
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(addr), "v"(v) : "memory");
+    } else if constexpr (sizeof(V) == 8) {
+        const n2_t v = __builtin_bit_cast(n2_t, w);
+        asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(addr), "v"(v) : "memory");
+    } else if constexpr (sizeof(V) == 4) {
+        const uint32_t v = __builtin_bit_cast(uint32_t, w);
+        asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(addr), "v"(v) : "memory");
+    } else {
+        *(V *)addr = w;
+    }
 }
 
-template <typename V>
-__device__ __forceinline__ V load_streaming(const char *addr)
+template <bool NT, typename V>
+__device__ __forceinline__ V load_vec(const char *addr)
 {
     typedef uint32_t n4_t __attribute__((ext_vector_type(4)));
     typedef uint32_t n2_t __attribute__((ext_vector_type(2)));
-    if constexpr (sizeof(V) == 16) return __builtin_bit_cast(V, __builtin_nontemporal_load((const n4_t *)addr));
+    if constexpr (!NT) return *(const V *)addr;
+    else if constexpr (sizeof(V) == 16) return __builtin_bit_cast(V, __builtin_nontemporal_load((const n4_t *)addr));
     else if constexpr (sizeof(V) == 8) return __builtin_bit_cast(V, __builtin_nontemporal_load((const n2_t *)addr));
     else if constexpr (sizeof(V) == 4) return __builtin_bit_cast(V, __builtin_nontemporal_load((const uint32_t *)addr));
     else return __builtin_bit_cast(V, __builtin_nontemporal_load((const uint16_t *)addr));
 }
 
 // Piece a is contiguous on both sides: copy TB runs of TA elements.
-template <int ELSZ, int VBYTES>
+template <int ELSZ, int VBYTES, bool NT>
 __global__ __launch_bounds__(kThreads) void permute_rows_kernel(PermuteParams p)
 {
     using V = typename Word<VBYTES>::type;
@@ -115,8 +138,8 @@ __global__ __launch_bounds__(kThreads) void permute_rows_kernel(PermuteParams p)
     char *dst = (char *)p.dst;
     for (int v = threadIdx.x; v < ra * tb; v += kThreads) {
         int ib = v / ra, ia = (v - ib * ra) * VL;
-        V w = load_streaming<V>(src + (sb + ib * p.ss_b + ia) * ELSZ);
-        store_through(dst + (db + ib * p.ds_b + ia) * ELSZ, w);
+        V w = load_vec<NT, V>(src + (sb + ib * p.ss_b + ia) * ELSZ);
+        store_vec<NT>(dst + (db + ib * p.ds_b + ia) * ELSZ, w);
     }
 }
 
@@ -239,7 +262,7 @@ __host__ __device__ inline bool tile_store_slot(const TileParams &p, const TileO
 
 constexpr int kTrip = 4;                   // vectors a thread has in flight per trip
 
-template <int ELSZ, int LBYTES, int SBYTES, bool SF, bool DF>
+template <int ELSZ, int LBYTES, int SBYTES, bool SF, bool DF, bool NT>
 __global__ __launch_bounds__(kThreads) void permute_tile_kernel(TileParams p)
 {
     using E = typename Word<ELSZ>::type;
@@ -263,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void permute_tile_kernel(TileParams p)
             int64_t so;
             ok[k] = tile_load_slot<VL, SF>(p, o, v, &so, &li[k]) && v < nvl;
             // (a vector outside the tile reads the tile's first vector instead: always in bounds, never stored)
-            w[k] = load_streaming<VLd>(src + (ok[k] ? so : 0) * ELSZ);
+            w[k] = load_vec<NT, VLd>(src + (ok[k] ? so : 0) * ELSZ);
         }
 #pragma unroll
         for (int k = 0; k < kTrip; ++k) {
@@ -289,7 +312,7 @@ __global__ __launch_bounds__(kThreads) void permute_tile_kernel(TileParams p)
             E *e = (E *)&w;
 #pragma unroll
             for (int j = 0; j < VS; ++j) e[j] = tile[li[j]];
-            store_through(dst + dof * ELSZ, w);
+            store_vec<NT>(dst + dof * ELSZ, w);
         }
     }
 }
@@ -332,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void unfold_kernel(const char *src, char 
         V w;
         std::memset(&w, 0, sizeof w);
         if (e < D) w = *(const V *)(src + ((o * D + e) * vec_inner + i) * VB);
-        store_through(dst + v * VB, w);
+        store_vec<false>(dst + v * VB, w);
     }
 }
 
@@ -397,36 +420,44 @@ int pick_vector_bytes(int elsz, int64_t run, const std::vector<int64_t> &strides
     return elsz;
 }
 
-template <int ELSZ>
-void launch_rows(int vb, const PermuteParams &p, dim3 grid, hipStream_t st)
+template <int ELSZ, bool NT>
+void launch_rows_nt(int vb, const PermuteParams &p, dim3 grid, hipStream_t st)
 {
-    if (vb == 16) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 16>), grid, dim3(kThreads), 0, st, p);
-    else if (vb == 8) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 8>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((permute_rows_kernel<ELSZ, ELSZ>), grid, dim3(kThreads), 0, st, p);
+    if (vb == 16) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 16, NT>), grid, dim3(kThreads), 0, st, p);
+    else if (vb == 8) hipLaunchKernelGGL((permute_rows_kernel<ELSZ, 8, NT>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((permute_rows_kernel<ELSZ, ELSZ, NT>), grid, dim3(kThreads), 0, st, p);
+}
+
+template <int ELSZ>
+void launch_rows(int vb, bool nt, const PermuteParams &p, dim3 grid, hipStream_t st)
+{
+    if (nt) launch_rows_nt<ELSZ, true>(vb, p, grid, st);
+    else launch_rows_nt<ELSZ, false>(vb, p, grid, st);
 }
 
 template <int ELSZ, int LB, int SB, bool SF, bool DF>
-void launch_tile_k(const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
+void launch_tile_k(bool nt, const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((permute_tile_kernel<ELSZ, LB, SB, SF, DF>), grid, dim3(kThreads), lds, st, p);
+    if (nt) hipLaunchKernelGGL((permute_tile_kernel<ELSZ, LB, SB, SF, DF, true>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((permute_tile_kernel<ELSZ, LB, SB, SF, DF, false>), grid, dim3(kThreads), lds, st, p);
 }
 
 template <int ELSZ, int LB, bool SF>
-void launch_tile_s(int sb, bool df, const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
+void launch_tile_s(int sb, bool df, bool nt, const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (df) launch_tile_k<ELSZ, LB, 16, SF, true>(p, grid, lds, st);          // a flat side moves 16-byte vectors
-    else if (sb == 16) launch_tile_k<ELSZ, LB, 16, SF, false>(p, grid, lds, st);
-    else if (sb == 8) launch_tile_k<ELSZ, LB, 8, SF, false>(p, grid, lds, st);
-    else launch_tile_k<ELSZ, LB, ELSZ, SF, false>(p, grid, lds, st);
+    if (df) launch_tile_k<ELSZ, LB, 16, SF, true>(nt, p, grid, lds, st);      // a flat side moves 16-byte vectors
+    else if (sb == 16) launch_tile_k<ELSZ, LB, 16, SF, false>(nt, p, grid, lds, st);
+    else if (sb == 8) launch_tile_k<ELSZ, LB, 8, SF, false>(nt, p, grid, lds, st);
+    else launch_tile_k<ELSZ, LB, ELSZ, SF, false>(nt, p, grid, lds, st);
 }
 
 template <int ELSZ>
-void launch_tile(int lb, int sb, bool sf, bool df, const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
+void launch_tile(int lb, int sb, bool sf, bool df, bool nt, const TileParams &p, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (sf) launch_tile_s<ELSZ, 16, true>(sb, df, p, grid, lds, st);
-    else if (lb == 16) launch_tile_s<ELSZ, 16, false>(sb, df, p, grid, lds, st);
-    else if (lb == 8) launch_tile_s<ELSZ, 8, false>(sb, df, p, grid, lds, st);
-    else launch_tile_s<ELSZ, ELSZ, false>(sb, df, p, grid, lds, st);
+    if (sf) launch_tile_s<ELSZ, 16, true>(sb, df, nt, p, grid, lds, st);
+    else if (lb == 16) launch_tile_s<ELSZ, 16, false>(sb, df, nt, p, grid, lds, st);
+    else if (lb == 8) launch_tile_s<ELSZ, 8, false>(sb, df, nt, p, grid, lds, st);
+    else launch_tile_s<ELSZ, ELSZ, false>(sb, df, nt, p, grid, lds, st);
 }
 
 // Host replay of the tile kernel's index arithmetic for one workgroup: calls visit(src element
@@ -523,7 +554,7 @@ alt_status_t plan_tile(alt_handle_t h, int elsz, const std::vector<Piece> &pcs, 
     // small tensors so that the launch still has several workgroups per compute unit, each with its
     // whole tile in flight; a flat side may take up to 32 KB to leave the other side runs of 128 bytes.
     int64_t budget = 16384;
-    while (budget > 4096 && numel * elsz / budget < 1536) budget /= 2;
+    while (budget > 4096 && numel * elsz / budget < 768) budget /= 2;
     const int64_t E = budget / elsz;
     constexpr int64_t kEdge = 64;                             // edge of the square tile, elements
     const int64_t run = std::max<int64_t>(budget / 128 / elsz, 1);      // elements in 128 bytes (in 32 for the smallest tiles)
@@ -698,13 +729,13 @@ alt_status_t run_transform(alt_handle_t h, TransformPlan &t, const void *src, vo
             break;
         case TransformPlan::ROWS:
             t.p.src = src; t.p.dst = dst;
-            if (t.elsz == 2) launch_rows<2>(t.vb, t.p, dim3(t.blocks), st);
-            else launch_rows<4>(t.vb, t.p, dim3(t.blocks), st);
+            if (t.elsz == 2) launch_rows<2>(t.vb, t.bytes > kStreamingBytes, t.p, dim3(t.blocks), st);
+            else launch_rows<4>(t.vb, t.bytes > kStreamingBytes, t.p, dim3(t.blocks), st);
             break;
         case TransformPlan::TRANSPOSE:
             t.tp.src = src; t.tp.dst = dst;
-            if (t.elsz == 2) launch_tile<2>(t.lb, t.sb, t.sf, t.df, t.tp, dim3(t.blocks), t.lds, st);
-            else launch_tile<4>(t.lb, t.sb, t.sf, t.df, t.tp, dim3(t.blocks), t.lds, st);
+            if (t.elsz == 2) launch_tile<2>(t.lb, t.sb, t.sf, t.df, t.bytes > kStreamingBytes, t.tp, dim3(t.blocks), t.lds, st);
+            else launch_tile<4>(t.lb, t.sb, t.sf, t.df, t.bytes > kStreamingBytes, t.tp, dim3(t.blocks), t.lds, st);
             break;
     }
     ALT_CHECK_HIP(h, hipGetLastError());
