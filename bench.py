@@ -54,6 +54,11 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel (256 MiB read + 256 MiB written per launch), "
                          "which gives a hardware-counter run its scale")
+    ap.add_argument("--only", default="",
+                    help="profiling target: run just one prepared launch loop (no tuning, no timing sections) and exit. "
+                         "step = the five batch-16 layers under the stored plan; gemm4096 = the 4096^3 product under the "
+                         "256x256 streaming tile; conv_b256 = the 64-channel 56x56 layer at batch 256; transform = the "
+                         "NCHW->NHWC conversion of (256,64,56,56) fp32 and of (16,64,56,56) fp32 over rings of 1 GiB")
     ap.add_argument("--plan", default=os.path.join(ROOT, "workloads", "tuned_plan_gfx950.json"),
                     help="tuned layouts and kernel variants of the batch-16 layers (a previous run's choice)")
     ap.add_argument("--retune", action="store_true",
@@ -195,6 +200,75 @@ def main():
             e1.synchronize()
             out.append(e0.elapsed_time(e1) * 1000.0 / (replays * launches_per_replay))
         return float(np.median(out))
+
+    if args.only:
+        # ---------------------------------------------------- profiling targets ----
+        def named(d, name, kind="conv"):
+            count = h.conv2d_variant_count(d) if kind == "conv" else h.gemm_variant_count(d)
+            for v in range(count):
+                try:
+                    if (h.conv2d_variant_name(d, v) if kind == "conv" else h.gemm_variant_name(d, v)) == name:
+                        d.variant = v
+                        return d
+                except alt.AltError:
+                    pass
+            raise SystemExit("bench.py: this build has no variant %s" % name)
+
+        reps = max(args.steps, 1)
+        if args.only == "gemm4096":
+            d = named(alt.gemm_desc(4096, 4096, 4096, in_dtype=alt.BF16, out_dtype=alt.BF16, b_layout="KN->NK"),
+                      "bf16_256x256x32_stream_w2x4x1_s4_k1", "gemm")
+            A = torch.randint(-200, 200, (4096 * 4096,), dtype=torch.int16, device=dev)
+            B = torch.randint(-200, 200, (4096 * 4096,), dtype=torch.int16, device=dev)
+            Cd = torch.empty(4096 * 4096, dtype=torch.int16, device=dev)
+            us = timed(lambda: h.gemm(d, A, B, Cd, stream=stream), reps)
+            print(json.dumps(dict(target=args.only, variant=h.gemm_variant_name(d, d.variant), us=round(us, 2),
+                                  tflops=round(2.0 * 4096 ** 3 / us / 1e6, 1))))
+        elif args.only == "conv_b256":
+            d = named(alt.conv_desc(256, 64, 56, 56, 64, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                                    x_layout="NCHW->NHWC", w_layout="OIHW->OHWI", y_layout="NCHW->NHWC"),
+                      "bf16_256x64x64_direct_w4x1_s3_k1")
+            xs = torch.randint(-200, 200, (256 * 64 * 56 * 56,), dtype=torch.int16, device=dev)
+            wsd = torch.randint(-200, 200, (64 * 64 * 9,), dtype=torch.int16, device=dev)
+            ys = torch.empty(256 * 64 * 56 * 56, dtype=torch.int16, device=dev)
+            us = timed(lambda: h.conv2d(d, xs, wsd, ys, stream=stream), reps)
+            print(json.dumps(dict(target=args.only, variant=h.conv2d_variant_name(d, d.variant), us=round(us, 2),
+                                  tflops=round(conv_flops(256, **RESNET_LAYERS[0]) / us / 1e6, 1))))
+        elif args.only == "transform":
+            out = {}
+            for shp in [(256, 64, 56, 56), (16, 64, 56, 56)]:
+                numel = int(np.prod(shp))
+                nring = max(2, int(math.ceil((1 << 30) / (numel * 8))))
+                srcs = [torch.randint(-30000, 30000, (numel,), dtype=torch.int32, device=dev).view(torch.float32) for _ in range(nring)]
+                dsts = [torch.empty(numel, dtype=torch.float32, device=dev) for _ in range(nring)]
+                la, lb = alt.layout_parse("NCHW->NCHW"), alt.layout_parse("NCHW->NHWC")
+                k = [0]
+
+                def one():
+                    h.layout_transform(alt.F32, shp, la, srcs[k[0] % nring], lb, dsts[k[0] % nring], stream=stream)
+                    k[0] += 1
+                us = timed(one, max(reps, 2 * nring), warm=nring)
+                out["x".join(map(str, shp))] = dict(us=round(us, 2), GBps=round(2.0 * numel * 4 / 1e3 / us, 1), ring_buffers=2 * nring)
+                del srcs, dsts
+            print(json.dumps(dict(target=args.only, fp32_nchw_to_nhwc=out)))
+        elif args.only == "step":
+            with open(args.plan) as f:
+                plan = json.load(f)["bf16_out"]
+            layers = prepare_layers(16, alt.BF16, 0, plan)
+            torch.cuda.synchronize()
+
+            def step():
+                for l in layers:
+                    run_layer(l)
+            us = timed(step, reps)
+            print(json.dumps(dict(target=args.only, us_per_step_one_stream=round(us, 2),
+                                  variants=[l["variant"] for l in layers])))
+        else:
+            raise SystemExit("bench.py: unknown --only target %s" % args.only)
+        if args.calib_copy:
+            h.get_peak(arena[:512 << 20], 512 << 20)
+        torch.cuda.synchronize()
+        return
 
     all_plans = {}
     if not args.retune and os.path.exists(args.plan):
