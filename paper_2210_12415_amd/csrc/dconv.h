@@ -85,6 +85,7 @@ struct DconvParams {
     int32_t OH, OW, stride, in_px;
     int32_t dil;                  // distance between filter taps, in input pixels (both directions)
     const void *addend;           // added before the activation: same layout and element type as y, or null
+    Div32 d_ihw;                  // channel-planar kernel (dplanar.h) only: division by H*W
 };
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));

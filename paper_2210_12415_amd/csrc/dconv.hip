@@ -3,6 +3,7 @@
 // parameters, and the arrival counters of the fused split-K reduction.
 #include <mutex>
 
+#include "dplanar.h"
 #include "dstream.h"
 #include "ops.h"
 
@@ -173,10 +174,70 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     return true;
 }
 
+// The same for a channel-planar kernel (dplanar.h): NCHW activations, OIHW weights, NCHW output, all dense.
+static bool dplanar_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes,
+                          std::string *why)
+{
+    auto no = [&](const char *m) { if (why) *why = m; return false; };
+    const IgemmParams &p = pb.p;
+    if (pb.dtype != ALT_BF16) return no("planar kernel is bf16 only");
+    if (p.batch != 1) return no("planar kernel takes no batch");
+    if (splitk != 1) return no("planar kernel takes no split-K");
+    if (p.addend) return no("planar kernel has no fused sum");
+    if (!((p.R == 3 && p.S == 3) || (p.R == 1 && p.S == 1))) return no("planar kernel is built for 1x1 and 3x3 filters");
+    if (p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2) || p.dil_h != p.dil_w || p.dil_h < 1)
+        return no("planar kernel needs stride 1 or 2 and one dilation for both directions");
+    if (p.pad_h < 0 || p.pad_w < 0 || 2 * p.pad_h > p.dil_h * (p.R - 1) || 2 * p.pad_w > p.dil_w * (p.S - 1))
+        return no("planar kernel needs padding between none and same-size");
+    const int st_ = p.stride_h;
+    if ((int64_t)(p.OH - 1) * st_ >= p.H || (int64_t)(p.OW - 1) * st_ >= p.W) return no("output larger than the strided input");
+    const int64_t C = p.C, H = p.H, W = p.W, OH = p.OH, OW = p.OW, K = p.Nc, R = p.R, S = p.S, N = p.M / (OH * OW);
+    if (!(dense(p.xw, W, 1) && dense(p.xh, H, W) && dense(p.xc, C, H * W) && dense(p.xn, N, C * H * W)))
+        return no("activations are not dense NCHW");
+    if (!(dense(p.ws, S, 1) && dense(p.wr, R, S) && dense(p.wi, C, R * S) && dense(p.wo, K, C * R * S)))
+        return no("weights are not dense OIHW");
+    if (!(dense(p.yw, OW, 1) && dense(p.yh, OH, OW) && dense(p.yk, K, OH * OW) && dense(p.yn, N, K * OH * OW)))
+        return no("output is not dense NCHW");
+    if (C % 64) return no("channels must be a multiple of 64");
+    if (H * W < 8) return no("images of fewer than eight pixels");
+    if ((uintptr_t)p.w % 16 || (uintptr_t)p.x % 2) return no("weights are not 16-byte aligned");
+    if ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 4) return no("bias is not aligned");
+    if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0 || (int64_t)p.M * K * 4 >= 0x7fffffff)
+        return no("operand of 2 GiB or more");
+    if (N * H * W > 0x7fffffff) return no("input too large for 32-bit pixel indices");
+    const size_t lds = dplanar_lds_bytes(k.BM, k.BN, k.kw, (int)(R * S), (int)C,
+                                         dconv_patch_pixels(k.BM, p.M, p.H, p.W, p.OH, p.OW, p.R, p.S, p.pad_h, p.pad_w, st_, p.dil_h));
+    if (lds > 160 * 1024) return no("patch and weight stages do not fit LDS");
+    const int tiles_m = (p.M + k.BM - 1) / k.BM, tiles_n = (p.Nc + k.BN - 1) / k.BN;
+    if ((int64_t)tiles_m * tiles_n > 0x7fffffff) return no("grid too large");
+    if (!out) return true;
+    DconvParams d;
+    std::memset(&d, 0, sizeof d);
+    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
+    d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
+    d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = p.C;
+    d.H = p.H; d.W = p.W; d.R = p.R; d.S = p.S; d.pad_h = p.pad_h; d.pad_w = p.pad_w;
+    d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = 1;
+    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
+    d.OH = p.OH; d.OW = p.OW; d.stride = st_; d.dil = p.dil_h;
+    d.in_px = (int32_t)(N * H * W);
+    d.d_hw = make_div32((uint32_t)(p.OH * p.OW));
+    d.d_w = make_div32((uint32_t)p.OW);
+    d.d_tm = make_div32((uint32_t)tiles_m);
+    d.d_tn = make_div32((uint32_t)tiles_n);
+    d.d_ihw = make_div32((uint32_t)(H * W));
+    d.d_sk = make_div32(1);
+    d.bk = 64;
+    *out = d;
+    *lds_bytes = lds;
+    return true;
+}
+
 // Fills the launch parameters of direct kernel `k` for `pb` split into `splitk`
 // channel slices, or says why the kernel does not cover the problem.
 bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes, std::string *why)
 {
+    if (k.stream == 2) return dplanar_setup(pb, k, splitk, out, lds_bytes, why);
     if (k.stream) return dstream_setup(pb, k, splitk, out, lds_bytes, why);
     auto no = [&](const char *m) { if (why) *why = m; return false; };
     const IgemmParams &p = pb.p;

@@ -25,3 +25,11 @@
                                     ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
                                     &dstream_launch<BM, BN, WGM, WGN, KW, NS, BK>, WGM, WGN, KW, 1}),            \
          true)
+
+// channel-planar kernel (dplanar.h): BM x BN tile, KW K groups of WGM x WGN waves
+#define ALT_DPLANAR(BM, BN, WGM, WGN, KW)                                                                        \
+    const bool reg_dplanar_##BM##x##BN##_w##WGM##x##WGN##x##KW =                                                 \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x64_planar_w" #WGM "x" #WGN "x" #KW, ALT_BF16, BM, BN,   \
+                                    64, LOAD_VEC, LOAD_VEC, 0, 0, 0, nullptr,                                    \
+                                    &dplanar_launch<BM, BN, WGM, WGN, KW>, WGM, WGN, KW, 2}),                    \
+         true)

@@ -657,7 +657,8 @@ struct IgemmLaunch {
     hipError_t (*launch_direct)(const DconvParams &p, size_t lds_bytes, hipStream_t st) = nullptr;
     int wgm = 0, wgn = 0;     // wave grid of a direct kernel
     int kw = 1;               // its K groups (each a wave grid of its own over a share of the channels)
-    int stream = 0;           // 1: both operands stream through LDS (dstream.h: 1x1 filters and GEMMs of any depth)
+    int stream = 0;           // 1: both operands stream through LDS (dstream.h: 1x1 filters and GEMMs of any depth);
+                              // 2: channel-planar operands converted on the way into LDS (dplanar.h)
 };
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int AMODE, int BMODE, int PF>

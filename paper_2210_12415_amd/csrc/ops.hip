@@ -156,7 +156,7 @@ size_t igemm_workspace(const Problem &pb, int splitk)
 double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams &p)
 {
     (void)pb;
-    if (k.launch_direct && k.stream) {
+    if (k.launch_direct && k.stream == 1) {
         // Streaming kernel: all K groups take one K step each in the larger of their matrix-core
         // time (at the efficiency these kernels reach: less with fewer than eight waves) and the
         // time to bring their operand tiles into LDS (about 45 bytes per clock per CU), plus a
@@ -176,6 +176,26 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
         // (halved like the direct kernels' estimate below: wherever one of these kernels applies it
         // has beaten the implicit-GEMM kernels, whose estimate is optimistic)
         return 0.5 * (clk / 2200.0 * 45.0 + (p.splitk > 1 ? 140.0 : 0.0));
+    }
+    if (k.launch_direct && k.stream == 2) {
+        // Channel-planar kernel: a workgroup converts its patch on the way in (about 20 bytes per clock
+        // after a start-up latency), then per 64 channels runs all taps out of LDS (matrix-core time of
+        // the tile, or the time to bring the weights in) between two barriers and a weight scatter, then
+        // stores its tile plane by plane.  As many workgroups share a CU as their LDS allows.
+        const int taps = p.R * p.S, st = p.stride_h;
+        const double halo = (double)(p.dil_h * (p.R - 1)) * p.W + p.dil_w * (p.S - 1);
+        const double np = (double)k.BM * st * st + halo + 8;
+        const double lds = std::max((double)taps * (k.BN * 144 + 16) + np * (p.C * 2 + 16), (double)k.kw * k.BN * (k.BM + 4) * 4);
+        const int per_cu = std::max(1, (int)(160.0 * 1024 / lds));
+        // (workgroups that share a CU overlap their latencies, not their traffic or their matrix-core time)
+        const double blocks = (double)p.tiles_m * p.tiles_n;
+        const double per_cu_work = std::ceil(blocks / 256.0), rounds = std::ceil(blocks / (256.0 * per_cu));
+        const double wload = (double)k.BN * 64 * taps * 2 / 40.0;      // the super-step's weights through L2
+        const double busy = np * p.C * 2 / 20.0 + (p.C / 64) * std::max(taps * (double)k.BM * k.BN / 32.0 * 1.2, wload) +
+                            (double)k.BM * k.BN / 8.0;
+        const double latency = 3000.0 + (p.C / 64) * 800.0 + 1500.0;
+        const double clk = per_cu_work * busy + rounds * latency + 5000.0;
+        return 0.5 * (clk / 2200.0 * 45.0);
     }
     double mode_cost = 1.0;
     if (k.amode == LOAD_GATHER) mode_cost *= 6.0;

@@ -221,8 +221,11 @@ def test_residual_block_plan_executes_to_oracle_result(h, arena, N, H):
     for i in (0, 1):
         assert name(plan.conv[i].x_layout) == name(plan.read_layout[i][0])
         assert name(plan.conv[i].y_layout) == name(plan.tensor_layout[i + 1])
-    # the direct kernels make channel-contiguous layouts the choice for these convolutions
-    assert name(plan.conv[0].x_layout) != "NCHW"
+    # at the benchmark's size the patch-resident kernels make channel-contiguous layouts the choice for
+    # these convolutions (the small case is launch-bound: the channel-planar kernel without a conversion
+    # may measure as fast)
+    if N == 16:
+        assert name(plan.conv[0].x_layout) != "NCHW"
     x = f32_to_bf16_bits(normal_f32(181, (N, C, H, H)))
     ws = [f32_to_bf16_bits(normal_f32(182 + i, (C, C, 3, 3), std=0.05)) for i in range(2)] + [None]
     bs = [normal_f32(190 + i, (C,), std=0.1) for i in range(2)] + [None]
