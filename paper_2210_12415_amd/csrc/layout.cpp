@@ -68,6 +68,48 @@ alt_status_t bind_layout(const alt_layout_t *l, int ndim, const int64_t *shape, 
         for (int d = 0; d < ndim; ++d)
             if (l->shape[d] != shape[d])
                 return bad(ALT_SHAPE_MISMATCH, "primitive sequence was built for another shape");
+        // A caller may have filled the descriptor by hand: walk the sequence with the same checks as
+        // alt_layout_from_prims (dimension and count in range, split factors that multiply to the extent,
+        // reorders that are permutations, fuses of adjacent dimensions), so that evaluating it never
+        // indexes outside its arrays.
+        std::vector<int64_t> cur(shape, shape + ndim);
+        for (int q = 0; q < l->nprims; ++q) {
+            const alt_prim_t &pr = l->prims[q];
+            const int rank = (int)cur.size();
+            std::vector<int64_t> ns;
+            if (pr.kind == ALT_PRIM_SPLIT) {
+                if (pr.dim < 0 || pr.dim >= rank || pr.count < 1 || pr.count > ALT_MAX_RANK || rank + pr.count - 1 > ALT_MAX_RANK)
+                    return bad(ALT_INVALID_LAYOUT, "split outside the tensor's rank");
+                int64_t prod = 1;
+                for (int j = 0; j < pr.count; ++j) {
+                    if (pr.v[j] < 1) return bad(ALT_INVALID_LAYOUT, "non-positive split factor");
+                    prod *= pr.v[j];
+                }
+                if (prod != cur[pr.dim]) return bad(ALT_SHAPE_MISMATCH, "split factors do not multiply to the extent");
+                for (int d = 0; d < rank; ++d) {
+                    if (d != pr.dim) { ns.push_back(cur[d]); continue; }
+                    for (int j = 0; j < pr.count; ++j) ns.push_back(pr.v[j]);
+                }
+            } else if (pr.kind == ALT_PRIM_REORDER) {
+                if (pr.count != rank) return bad(ALT_INVALID_LAYOUT, "reorder of another rank");
+                std::vector<int> seen(rank, 0);
+                for (int j = 0; j < rank; ++j) {
+                    const int64_t o = pr.v[j];
+                    if (o < 0 || o >= rank || seen[o]) return bad(ALT_INVALID_LAYOUT, "reorder is not a permutation");
+                    seen[o] = 1;
+                    ns.push_back(cur[o]);
+                }
+            } else if (pr.kind == ALT_PRIM_FUSE) {
+                if (pr.dim < 0 || pr.count < 1 || pr.dim + pr.count > rank) return bad(ALT_INVALID_LAYOUT, "fuse outside the tensor's rank");
+                for (int d = 0; d < rank; ++d) {
+                    if (d <= pr.dim || d >= pr.dim + pr.count) ns.push_back(cur[d]);
+                    else ns.back() *= cur[d];
+                }
+            } else {
+                return bad(ALT_INVALID_LAYOUT, "unknown primitive");
+            }
+            cur.swap(ns);
+        }
         out->separable = 0;
         out->nprims = l->nprims;
         std::memcpy(out->prims, l->prims, sizeof(alt_prim_t) * l->nprims);

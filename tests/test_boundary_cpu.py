@@ -96,6 +96,49 @@ def test_layout_errors():
     assert e.value.status == 2
 
 
+def test_hand_filled_general_layouts_are_checked_before_use():
+    """A descriptor whose primitive list a caller wrote by hand (not through alt_layout_from_prims) is walked
+    with the same checks before anything evaluates it: every corruption below used to index outside the
+    descriptor's arrays; now each is an error status."""
+    N, H, W, O = 2, 3, 5, 8
+    shape = (N, H, W, O)
+    good = alt.layout_from_prims(shape, [alt.fuse(1, 3), alt.split(1, [O // 4, 4, H * W]), alt.reorder([0, 1, 3, 2])])
+    assert good.separable == 0
+    assert alt.layout_offset(good, shape, (1, 2, 4, 7)) >= 0
+
+    def broken(edit):
+        L = alt.Layout.from_buffer_copy(bytes(good))
+        edit(L)
+        return L
+
+    def set_v(q, j, val):
+        def f(L):
+            L.prims[q].v[j] = val
+        return f
+
+    def set_field(q, name, val):
+        def f(L):
+            setattr(L.prims[q], name, val)
+        return f
+
+    cases = [(set_v(2, 1, 9), 2),                 # reorder entry outside the rank
+             (set_v(2, 1, 0), 2),                 # reorder repeats a dimension
+             (set_field(2, "count", 7), 2),       # reorder of another rank
+             (set_field(1, "dim", 5), 2),         # split of a dimension that does not exist
+             (set_field(1, "count", 9), 2),       # more factors than the descriptor holds
+             (set_v(1, 0, 3), 3),                 # factors no longer multiply to the extent
+             (set_v(1, 1, -4), 2),                # negative factor
+             (set_field(0, "count", 6), 2),       # fuse beyond the last dimension
+             (set_field(0, "kind", 17), 2)]       # unknown primitive
+    for edit, status in cases:
+        L = broken(edit)
+        for call in (lambda: alt.layout_offset(L, shape, (0, 0, 0, 0)), lambda: alt.layout_index_of(L, shape, 0),
+                     lambda: alt.layout_physical_shape(L, shape)):
+            with pytest.raises(alt.AltError) as e:
+                call()
+            assert e.value.status == status
+
+
 def test_plan_chain_known_shortest_paths():
     inf = float("inf")
     # two layouts; op0 is fast only when writing layout 1, op1 only when reading layout 1
