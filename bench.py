@@ -177,6 +177,39 @@ def main():
 
     side = torch.cuda.Stream()
 
+    def cold_layer_us(l):
+        """Microseconds per launch of layer l with activations and output that no cache holds: the launches of
+        one graph walk a ring of (x, y) pairs carved out of the arena, at least 400 MB apart before a pair comes
+        round again (the last-level cache is 256 MB); the weights stay where they are."""
+        xb, yb = l["x"].numel() * l["x"].element_size(), l["y"].numel() * l["y"].element_size()
+        pitch = (xb + yb + 511) // 256 * 256
+        nring = int(min(256, arena.numel() // pitch))
+        if nring * pitch < (400 << 20) and nring < 256:
+            return None
+        arena.view(torch.int16).random_(-200, 200)
+        torch.cuda.synchronize()
+        pairs = []
+        for i in range(nring):
+            base = i * pitch
+            xoff = (xb + 255) // 256 * 256
+            pairs.append((arena[base:base + xb].view(l["x"].dtype), arena[base + xoff:base + xoff + yb].view(l["y"].dtype)))
+        it = [0]
+
+        def one(st):
+            x, y = pairs[it[0] % nring]
+            it[0] += 1
+            h.conv2d(l["desc"], x, l["w"], y, workspace=l["ws"], ws_bytes=l["ws_bytes"], stream=st)
+        one(side)
+        side.synchronize()
+        it[0] = 0
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(nring):
+                one(side)
+        us = graph_timed(g, nring, replays=3, batches=3)
+        del g
+        return us
+
     def capture(fn, n):
         """A HIP graph of n back-to-back calls of fn(stream), recorded on a side stream."""
         fn(side)                                # first use of a kernel (module load, attributes) stays outside the capture
@@ -412,6 +445,7 @@ def main():
             us = graph_timed(g, 20)
             del g
             l["us"] = us
+            cold_us = cold_layer_us(l)
             L = l["L"]
             d0 = alt.conv_desc(16, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"], pad=L["pad"],
                                in_dtype=alt.BF16, out_dtype=l["desc"].out_dtype)
@@ -423,6 +457,7 @@ def main():
                 def_us, def_trials = float("nan"), 0
             stored = not tuned_now
             per_layer.append(dict(layer=L["name"], layout=l["layout"], variant=l["variant"], us=round(us, 3),
+                                  us_cold_inputs=None if cold_us is None else round(cold_us, 3),
                                   tflops=round(l["flops"] / us / 1e6, 1),
                                   frac_mfma_peak=round(l["flops"] / us / 1e6 / PEAK_BF16_TFLOPS, 4),
                                   frac_own_ceiling=round(l["flops"] / us / 1e6 / own_ceiling_tflops(l), 4),
@@ -990,6 +1025,7 @@ def main():
 def summarise(extra):
     """A few figures of each section for the final line (the sections themselves go to EXTRA_PATH)."""
     s = dict(layer_us=[p["us"] for p in extra["per_layer_b16"]],
+             layer_us_cold_inputs=[p.get("us_cold_inputs") for p in extra["per_layer_b16"]],
              layer_frac_mfma=[p["frac_mfma_peak"] for p in extra["per_layer_b16"]],
              layer_speedup_vs_default_layout=[p["speedup_vs_default_layout_live"] for p in extra["per_layer_b16"]],
              one_stream_ms_per_step=extra["graph_replay_ms_per_step"])
