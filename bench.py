@@ -296,6 +296,24 @@ def main():
             us = timed(step, reps)
             print(json.dumps(dict(target=args.only, us_per_step_one_stream=round(us, 2),
                                   variants=[l["variant"] for l in layers])))
+        elif args.only == "step_nchw":
+            # the five layers in the default layouts (NCHW activations and output, OIHW weights): the
+            # channel-planar kernels, each layer under the library's own choice of tile
+            ls = []
+            for L in RESNET_LAYERS:
+                d = alt.conv_desc(16, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], stride=L["stride"], pad=L["pad"],
+                                  in_dtype=alt.BF16, out_dtype=alt.BF16)
+                oh, ow = conv_out_hw(L["H"], L["W"], L["R"], L["S"], L["stride"], L["pad"])
+                ls.append((d, torch.randint(-200, 200, (16 * L["C"] * L["H"] * L["W"],), dtype=torch.int16, device=dev),
+                           torch.randint(-200, 200, (L["K"] * L["C"] * L["R"] * L["S"],), dtype=torch.int16, device=dev),
+                           torch.empty(16 * L["K"] * oh * ow, dtype=torch.int16, device=dev)))
+
+            def step():
+                for d, x, w, y in ls:
+                    h.conv2d(d, x, w, y, stream=stream)
+            us = timed(step, reps)
+            print(json.dumps(dict(target=args.only, us_per_step_one_stream=round(us, 2),
+                                  variants=[h.conv2d_variant_name(d, -1) for d, _, _, _ in ls])))
         else:
             raise SystemExit("bench.py: unknown --only target %s" % args.only)
         if args.calib_copy:
