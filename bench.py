@@ -1052,7 +1052,8 @@ def summarise(extra):
         s["transform_cold_GBps_min_max"] = [min(t["GBps_hbm"] for t in tr), max(t["GBps_hbm"] for t in tr)]
     sc = extra.get("layout_transform_scaled")
     if sc:
-        s["transform_16x_cold_GBps"] = [t["GBps_hbm"] for t in sc]
+        s["transform_16x_cold_GBps_min_max"] = [min(t["GBps_hbm"] for t in sc), max(t["GBps_hbm"] for t in sc)]
+        s["transform_16x_cold_GBps_56x56"] = [t["GBps_hbm"] for t in sc if tuple(t.get("shape", ())[2:]) == (56, 56)][:4]
     gm = extra.get("gemm_bert")
     if gm:
         s["gemm_frac_mfma"] = [g["frac_mfma_peak"] for g in gm]
