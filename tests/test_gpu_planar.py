@@ -89,3 +89,28 @@ def test_planar_kernels_on_the_benchmark_layers(h, layer):
         got, _ = run_conv(h, x, w, cfg, "NCHW", "OIHW", "NCHW", alt.BF16, out_dtype=alt.BF16, variant=v)
         e = err_measures(bf16_bits_to_f32(got), ref)
         assert e["floored"] <= 2e-2, (name, e)
+
+
+@pytest.mark.parametrize("x_shift,y_shift", [(1, 0), (0, 3), (5, 7)])
+def test_planar_kernels_take_buffers_at_any_element_offset(h, x_shift, y_shift):
+    """Activations and output that start at an odd element of an allocation (2-byte aligned, nothing more):
+    the 16-byte runs the kernel loads and stores are then misaligned everywhere, and must still be exact."""
+    import torch
+    from gpu_util import dev, host, to_layout, from_layout
+    N, C, H, W, K = 3, 64, 14, 14, 64
+    x = small_ints_f32(101, (N, C, H, W), -3, 3)
+    w = small_ints_f32(102, (K, C, 3, 3), -3, 3)
+    ref = f32_to_bf16_bits(oracle.conv2d(x, w, stride=1, pad=1, relu=True))
+    d0 = alt.conv_desc(N, C, H, W, K, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.BF16, epilogue=alt.EPI_RELU,
+                       x_layout="NCHW->NCHW", w_layout="OIHW->OIHW", y_layout="NCHW->NCHW")
+    xb = f32_to_bf16_bits(x).reshape(-1)
+    xd_whole = dev(np.concatenate([np.zeros(x_shift, np.uint16), xb, np.zeros(8, np.uint16)]))
+    wd = dev(f32_to_bf16_bits(w).reshape(-1))
+    n_out = N * K * H * W
+    for v, name in [(v, n) for v, n in applicable_variants(h, d0) if "planar" in n]:
+        d0.variant = v
+        y_whole = torch.full((n_out + y_shift + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
+        h.conv2d(d0, xd_whole[x_shift:], wd, y_whole[y_shift:])
+        got = host(y_whole, np.uint16)
+        assert np.array_equal(got[y_shift:y_shift + n_out].reshape(ref.shape), ref), name
+        assert (got[:y_shift] == 0x5A5A).all() and (got[y_shift + n_out:] == 0x5A5A).all(), name
