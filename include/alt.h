@@ -448,6 +448,7 @@ alt_status_t alt_gemm(alt_handle_t h, const alt_gemm_desc_t *d, const void *A, c
                       void *C, void *workspace, size_t ws_bytes, void *stream);
 alt_status_t alt_gemm_workspace_size(alt_handle_t h, const alt_gemm_desc_t *d, size_t *bytes);
 alt_status_t alt_gemm_variant_count(alt_handle_t h, const alt_gemm_desc_t *d, int *count);
+/* (variant = -1 names the variant alt_gemm picks for the descriptor, as alt_conv2d_variant_name does) */
 alt_status_t alt_gemm_variant_name(alt_handle_t h, const alt_gemm_desc_t *d, int variant,
                                    char *buf, size_t buflen);
 

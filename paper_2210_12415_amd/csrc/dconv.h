@@ -128,6 +128,32 @@ __device__ __forceinline__ void lds_read16_async_at(u32x4_t &dst, uint32_t addr)
     else lds_read16_async(dst, addr + (uint32_t)OFF);
 }
 
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+// LDS transpose read of gfx950, 64 bits per lane, 16-bit elements (completion not tracked by the compiler,
+// like lds_read16_async): within each group of 16 lanes, lane i receives element i % 4 of the 8 bytes
+// that lanes 4j + i / 4 (j = 0..3) address, i.e. with lanes 4j .. 4j+3 on row j of a matrix, column i of rows 0..3.
+template <int OFF>
+__device__ __forceinline__ void lds_read8_tr_async_at(u32x2_t &dst, uint32_t addr)
+{
+    if constexpr (OFF >= 0 && OFF < 65536) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    else asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(dst) : "v"(addr + (uint32_t)OFF) : "memory");
+}
+
+// lds_wait for fragments whose B halves are read separately.
+template <int N, int NA, int NB>
+__device__ __forceinline__ void lds_wait_tr(u32x4_t (&a)[NA], u32x2_t (&b)[NB][2])
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a[0]) : "n"(N) : "memory");
+#pragma unroll
+    for (int i = 1; i < NA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        asm volatile("" : "+v"(b[j][0]));
+        asm volatile("" : "+v"(b[j][1]));
+    }
+}
+
 // f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>), in order.
 template <typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)

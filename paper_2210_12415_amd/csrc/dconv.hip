@@ -129,7 +129,12 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, N = p.M / (H * W);
     if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
         return no("A is not dense with K contiguous");
-    if (!(dense(p.wi, C, 1) && dense(p.wo, K, C))) return no("B is not dense with K contiguous");
+    if (k.bt) {
+        if (!(dense(p.wo, K, 1) && dense(p.wi, C, K))) return no("B is not dense with N contiguous");
+        if (K % 8) return no("row-major B is loaded eight columns at a time");
+    } else if (!(dense(p.wi, C, 1) && dense(p.wo, K, C))) {
+        return no("B is not dense with K contiguous");
+    }
     if (!(dense(p.yk, K, 1) && dense(p.yw, W, K) && dense(p.yh, H, W * K) && dense(p.yn, N, H * W * K)))
         return no("output is not dense with N contiguous");
     const int64_t osz = p.out_bf16 ? 2 : 4;

@@ -33,3 +33,11 @@
                                     64, LOAD_VEC, LOAD_VEC, 0, 0, 0, nullptr,                                    \
                                     &dplanar_launch<BM, BN, WGM, WGN, KW>, WGM, WGN, KW, 2}),                    \
          true)
+
+// the streaming kernel for B stored [K][N] (row-major): the same tiles, B read through LDS transpose reads
+#define ALT_DSTREAM_KN(BM, BN, WGM, WGN, KW, NS, BK)                                                             \
+    const bool reg_dstream_kn_##BM##x##BN##x##BK##_w##WGM##x##WGN##x##KW##_s##NS =                               \
+        (igemm_register(IgemmLaunch{"bf16_" #BM "x" #BN "x" #BK "_streamkn_w" #WGM "x" #WGN "x" #KW "_s" #NS,     \
+                                    ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
+                                    &dstream_launch<BM, BN, WGM, WGN, KW, NS, BK, true>, WGM, WGN, KW, 1, 1}),   \
+         true)

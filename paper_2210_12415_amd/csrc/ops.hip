@@ -726,12 +726,16 @@ alt_status_t alt_gemm_variant_name(alt_handle_t h, const alt_gemm_desc_t *d, int
 {
     if (!h) return ALT_INVALID_ARG;
     if (!d || !buf || buflen == 0) return fail(h, ALT_INVALID_ARG, "null argument");
-    std::string n = igemm_variant_name(variant);
-    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
-    std::snprintf(buf, buflen, "%s", n.c_str());
     Problem pb;
     alt_status_t s = gemm_problem(h, d, (void *)16, (void *)16, (void *)16, &pb);
     if (s != ALT_OK) return s;
+    if (variant < 0) {                               // the variant alt_gemm would run with variant = -1 and any workspace
+        variant = pick_variant(h, pb, -1, gemm_key(h, d), (size_t)-1);
+        if (variant < 0) return fail(h, ALT_UNSUPPORTED, "no kernel variant applies");
+    }
+    std::string n = igemm_variant_name(variant);
+    if (n.empty()) return fail(h, ALT_INVALID_ARG, "variant %d out of range", variant);
+    std::snprintf(buf, buflen, "%s", n.c_str());
     std::string why;
     const auto &tab = igemm_table();
     if (!igemm_applicable(pb, tab[variant / kNumSplits], kSplits[variant % kNumSplits], nullptr, &why))

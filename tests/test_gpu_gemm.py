@@ -58,26 +58,32 @@ def test_exact_integers_every_variant(h, layouts, in_dtype):
         assert np.array_equal(got, ref), name
 
 
-@pytest.mark.parametrize("shape", [(2, 160, 256, 192), (1, 300, 768, 200), (3, 128, 64, 128), (1, 70, 1536, 36)],
+@pytest.mark.parametrize("shape", [(2, 160, 256, 192), (1, 300, 768, 200), (3, 128, 64, 128), (1, 70, 1536, 36),
+                                   (1, 70, 1536, 40), (2, 260, 320, 264)],
                          ids=lambda s: "b%d_%dx%dx%d" % s)
-def test_streaming_kernels_exact_integers(h, shape):
-    """The streaming kernels (A as MK, B as NK, K a multiple of 64): every tile shape,
-    K-group count and split factor, bit for bit; batched, ragged M and N, deep K."""
+@pytest.mark.parametrize("bl", ["NK", "KN"])
+def test_streaming_kernels_exact_integers(h, shape, bl):
+    """The streaming kernels (A as MK, B as NK or, read through LDS transpose reads, as KN; K a multiple of
+    64): every tile shape, K-group count and split factor, bit for bit; batched, ragged M and N, deep K."""
     batch, M, K, N = shape
+    if bl == "KN" and N % 8:
+        pytest.skip("row-major B is loaded eight columns at a time")
     A = small_ints_f32(71, (batch, M, K), -3, 3)
     B = small_ints_f32(72, (batch, K, N), -3, 3)
     ref = oracle.gemm(A, B)
     Ab, Bb = f32_to_bf16_bits(A), f32_to_bf16_bits(B)
-    d0 = alt.gemm_desc(M, N, K, batch=batch, in_dtype=alt.BF16, a_layout="MK->MK", b_layout="KN->NK", c_layout="MN->MN")
+    d0 = alt.gemm_desc(M, N, K, batch=batch, in_dtype=alt.BF16, a_layout="MK->MK", b_layout="KN->" + bl, c_layout="MN->MN")
     variants = [(v, n) for v, n in applicable_variants(h, d0, "gemm") if "stream" in n]
+    assert all(("streamkn" in n) == (bl == "KN") for _, n in variants)
     assert len(variants) >= 6, "streaming kernels should cover this case"
     assert batch > 1 or K < 128 or any(not n.endswith("_k1") for _, n in variants)
     for v, name in variants:
-        got, _ = run_gemm(h, Ab, Bb, "MK", "NK", "MN", alt.BF16, variant=v)
+        print(name, flush=True)
+        got, _ = run_gemm(h, Ab, Bb, "MK", bl, "MN", alt.BF16, variant=v)
         assert np.array_equal(got, ref), name
     picks = [variants[0], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:2]
     for v, name in picks:
-        got16, _ = run_gemm(h, Ab, Bb, "MK", "NK", "MN", alt.BF16, out_dtype=alt.BF16, variant=v)
+        got16, _ = run_gemm(h, Ab, Bb, "MK", bl, "MN", alt.BF16, out_dtype=alt.BF16, variant=v)
         assert np.array_equal(got16[0], f32_to_bf16_bits(ref[0])), name
 
 
