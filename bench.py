@@ -742,6 +742,11 @@ def main():
         extra["gemm_4096"] = dict(variant=h.gemm_variant_name(best, best.variant), us=round(us, 1),
                                   tflops=round(fl / us / 1e6, 1), frac_mfma_peak=round(fl / us / 1e6 / PEAK_BF16_TFLOPS, 4),
                                   tuner_trials=rep.trials)
+        # the same product with B row-major ([K][N], the default layout), under the library's own choice of tile
+        dk = alt.gemm_desc(4096, 4096, 4096, in_dtype=alt.BF16, out_dtype=alt.BF16)
+        us_kn = median_timed(lambda: h.gemm(dk, A, B, Cd, stream=stream), 20, 3)
+        extra["gemm_4096"]["row_major_b"] = dict(variant=h.gemm_variant_name(dk, -1), us=round(us_kn, 1),
+                                                 tflops=round(fl / us_kn / 1e6, 1))
         del A, B, Cd
 
     if want("b1"):

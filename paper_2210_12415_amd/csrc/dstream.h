@@ -165,7 +165,7 @@ void dstream_kernel(const DconvParams p)
     // Operand reads run D k-chunks ahead of the MFMAs that use them; k chunk g (counted
     // from the start of a round over the stages) uses register buffer g % NBUF.
     // (wave tiles of eight or more MFMAs per k chunk run a hand-pinned schedule, one chunk ahead: see do_step)
-    constexpr bool kPinned = !BT && KW == 1 && TM * TN >= 8 && TM >= 2 && LPS <= NKC * TM;
+    constexpr bool kPinned = KW == 1 && TM * TN >= 8 && TM >= 2 && LPS <= NKC * TM;
     constexpr int D0 = kPinned ? 1 : (TM + RB * TN) * 3 <= 15 ? 3 : (TM + RB * TN) * 2 <= 15 ? 2 : 1;
     constexpr int D = D0 < NKC ? D0 : NKC;                 // the look-ahead stays within the next step
     constexpr int NBUF = 4;
@@ -262,6 +262,8 @@ void dstream_kernel(const DconvParams p)
                 // the chunk this one's rows read ahead for: D = 1 here (TM + TN reads fill the counter's range)
                 constexpr int gn = g + 1, stn = (gn / NKC) % NS, kcn = gn % NKC, bufn = gn % NBUF, offn = stn * STAGE;
                 constexpr int RPS = (TM + TN + TM - 2) / (TM - 1);             // reads per row slot, rows 0 .. TM - 2
+                constexpr bool look = GEND == 0 || gn < GEND;
+                if constexpr (FIRST && kc == 0) reads(std::integral_constant<int, g>{});
                 frag_wait(std::integral_constant<int, 0>{}, std::integral_constant<int, buf>{});
                 static_for<TM>([&](auto IR) {
                     constexpr int i = decltype(IR)::value;
@@ -273,7 +275,8 @@ void dstream_kernel(const DconvParams p)
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<RPS>([&](auto RR) {
                         constexpr int r = i * RPS + decltype(RR)::value;
-                        if constexpr (r < TM) lds_read16_async_at<offn>(af[bufn][r], a_rd[r][kcn]);
+                        if constexpr (!look) {
+                        } else if constexpr (r < TM) lds_read16_async_at<offn>(af[bufn][r], a_rd[r][kcn]);
                         else if constexpr (r < TM + TN)
                             read_b(std::integral_constant<int, bufn>{}, std::integral_constant<int, r - TM>{},
                                    std::integral_constant<int, offn>{}, b_rd[r - TM][kcn]);
