@@ -208,6 +208,23 @@ def layout_transform(src, shape, seq_src, seq_dst):
     return dst
 
 
+def pad_transform(src, src_shape, seq_src, dst_shape, seq_dst):
+    """The pad primitive (Section 4.1.2: zeros appended to selected dimensions) and its inverse,
+    unpad, carried by the conversion operator (Section 4.2: a padding operator with a propagated
+    layout pads and converts in one pass).  `src` is the flat buffer of a tensor of logical
+    src_shape under seq_src; the result is the flat buffer of the tensor of logical dst_shape
+    under seq_dst whose element at index i is the source's where i lies inside both shapes and
+    zero (all bits clear) elsewhere.  Written as its definition: to logical order, copy the
+    common box into zeros, to the destination layout."""
+    src_shape, dst_shape = tuple(int(v) for v in src_shape), tuple(int(v) for v in dst_shape)
+    assert len(src_shape) == len(dst_shape)
+    logical = layout_transform(src, src_shape, seq_src, []).reshape(src_shape)
+    out = np.zeros(dst_shape, dtype=logical.dtype)
+    box = tuple(slice(0, min(a, b)) for a, b in zip(src_shape, dst_shape))
+    out[box] = logical[box]
+    return layout_transform(out.reshape(-1), dst_shape, [], seq_dst)
+
+
 # ----------------------------------------------------------------- unfold ----
 
 def unfold_tiles(D, B, S):

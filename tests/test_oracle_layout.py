@@ -229,6 +229,33 @@ def test_transform_gemm_operand_is_matrix_transpose(oracle):
     assert np.array_equal(got.reshape(10, 6), A.T)
 
 
+@pytest.mark.parametrize("bits", [16, 32])
+def test_pad_transform_against_an_index_loop_and_its_inverse(oracle, bits):
+    """pad (Section 4.1.2) carried by the conversion operator: against a per-element loop written out
+    here (channel-blocked destination, closed-form offset), zeros exactly where the index leaves the
+    source, unpad as the inverse bit for bit, and the plain conversion when the shapes agree."""
+    N, C, H, W, x = 2, 5, 3, 4, 8
+    src_shape, dst_shape = (N, C, H, W), (N, 8, H, W + 2)       # channels padded to one block of 8, width by 2
+    src = special_bit_patterns(21, src_shape, bits)
+    nhwc = oracle.seq_from_string("NCHW->NHWC", src_shape)
+    c8 = oracle.seq_from_string("NCHW->NCHW8c", dst_shape)
+    stored = oracle.layout_transform(src, src_shape, [], nhwc)
+    got = oracle.pad_transform(stored, src_shape, nhwc, dst_shape, c8)
+    want = np.zeros(int(np.prod(dst_shape)), dtype=src.dtype)
+    Wp = W + 2
+    for n in range(N):
+        for c in range(C):
+            for h in range(H):
+                for w in range(W):
+                    want[(((n * 1 + c // x) * H + h) * Wp + w) * x + c % x] = src[n, c, h, w]
+    assert np.array_equal(got, want)
+    assert np.count_nonzero(got) <= src.size                    # everything else is all-bits-zero
+    back = oracle.pad_transform(got, dst_shape, c8, src_shape, nhwc)
+    assert np.array_equal(back, stored)
+    same = oracle.pad_transform(stored, src_shape, nhwc, src_shape, oracle.seq_from_string("NCHW->NCHW", src_shape))
+    assert np.array_equal(same, src.reshape(-1))
+
+
 def test_unfold_nd_against_sliding_windows(oracle):
     """N-D unfold against numpy's sliding windows (written independently of the oracle):
     tile t of a dimension is the window starting at t*S; the ragged last tile is zero-filled."""
