@@ -163,6 +163,20 @@ alt_status_t alt_layout_transform(alt_handle_t h, alt_dtype_t dtype, int ndim, c
                                   const alt_layout_t *src_layout, const void *src,
                                   const alt_layout_t *dst_layout, void *dst, void *stream);
 
+/* The pad primitive and its inverse (Section 4.1.2: zeros appended to selected dimensions) carried by the
+ * conversion operator (Section 4.2: a padding operator with a propagated layout pads and converts in one
+ * pass).  src holds a tensor of logical `src_shape` under `src_layout`, dst receives the tensor of logical
+ * `dst_shape` under `dst_layout` (each layout is bound to its own shape; this is how a channel count that a
+ * block factor does not divide reaches a blocked layout: pad it to the next multiple).  dst's element at
+ * index i is src's where i lies inside both shapes and zero (all bits clear) elsewhere: extents may grow
+ * (pad), shrink (unpad) or both.  Device pointers to numel(src_shape) and numel(dst_shape) elements, no
+ * overlap.  One thread per element (this form is for operands prepared once, not for the hot path).
+ * Asynchronous on `stream`; launches kernels only (safe under stream capture). */
+alt_status_t alt_layout_transform_pad(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *src_shape,
+                                      const alt_layout_t *src_layout, const void *src,
+                                      const int64_t *dst_shape, const alt_layout_t *dst_layout, void *dst,
+                                      void *stream);
+
 /* What alt_layout_transform would launch for a conversion, without launching it (host only: works
  * without a GPU).  src_misalign / dst_misalign: the buffers' addresses modulo 16, which decide the
  * vector widths.  kind: 0 plain copy, 1 one thread per element (layouts whose blocks do not nest,

@@ -172,7 +172,7 @@ def exported_symbols():
             "alt_tune_conv2d_arena_size", "alt_tune_gemm_arena_size", "alt_tune_conv2d", "alt_tune_gemm",
             "alt_tune_conv2d_variants", "alt_tune_conv2d_multi", "alt_tune_chain", "alt_plan_chain",
             "alt_eltwise_add", "alt_tune_graph", "alt_plan_graph", "alt_unfold", "alt_unfold_shape",
-            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_layout_transform_plan", "alt_splitk_status", "alt_conv2d_static"]
+            "alt_cache_save", "alt_cache_load", "alt_cache_clear", "alt_get_peak", "alt_layout_transform_plan", "alt_splitk_status", "alt_conv2d_static", "alt_layout_transform_pad"]
 
 
 def version():
@@ -403,6 +403,11 @@ class Handle:
                 _ck(status, hh)
             return keep is None
         return run
+
+    def layout_transform_pad(self, dtype, src_shape, src_layout, src, dst_shape, dst_layout, dst, stream=None):
+        _ck(lib().alt_layout_transform_pad(self._h, dtype, len(src_shape), _i64(src_shape),
+                                           ctypes.byref(_as_layout(src_layout)), _ptr(src), _i64(dst_shape),
+                                           ctypes.byref(_as_layout(dst_layout)), _ptr(dst), _stream(stream)), self._h)
 
     def conv2d_multi(self, calls):
         self.conv2d_multi_prepared(calls)()

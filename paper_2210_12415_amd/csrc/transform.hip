@@ -317,23 +317,38 @@ __global__ __launch_bounds__(kThreads) void permute_tile_kernel(TileParams p)
     }
 }
 
+// One thread per logical index of the box `it_shape` (the tensor's shape; for the pad form the
+// part of the index space both tensors have): each layout is evaluated under its own shape.
 struct GeneralParams {
     const void *src;
     void *dst;
     BoundLayout ls, ld;
+    int64_t it_shape[ALT_MAX_RANK], it_numel;
 };
 
 template <int ELSZ>
 __global__ __launch_bounds__(kThreads) void permute_general_kernel(GeneralParams p)
 {
     using E = typename Word<ELSZ>::type;
-    const int64_t n = p.ls.numel;
+    const int64_t n = p.it_numel;
     for (int64_t e = blockIdx.x * (int64_t)kThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kThreads) {
         int64_t idx[ALT_MAX_RANK];
         int64_t r = e;
-        for (int d = p.ls.ndim - 1; d >= 0; --d) { idx[d] = r % p.ls.shape[d]; r /= p.ls.shape[d]; }
+        for (int d = p.ls.ndim - 1; d >= 0; --d) { idx[d] = r % p.it_shape[d]; r /= p.it_shape[d]; }
         ((E *)p.dst)[eval_offset(p.ld, idx)] = ((const E *)p.src)[eval_offset(p.ls, idx)];
     }
+}
+
+// Zeros over `bytes` bytes (a multiple of 2) at a 2-byte-aligned address: 16-byte stores over the
+// aligned middle, 2-byte stores at the ends.  (A kernel, not a memset: callers may be under graph capture.)
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(char *dst, int64_t bytes)
+{
+    const int64_t head = std::min<int64_t>(bytes, (16 - ((uintptr_t)dst & 15)) & 15);
+    const int64_t nvec = (bytes - head) / 16, tail0 = head + nvec * 16;
+    const int64_t tid = blockIdx.x * (int64_t)kThreads + threadIdx.x, nth = (int64_t)gridDim.x * kThreads;
+    for (int64_t v = tid; v < nvec; v += nth) *(uint4 *)(dst + head + v * 16) = make_uint4(0, 0, 0, 0);
+    for (int64_t b = tid * 2; b < head; b += nth * 2) *(uint16_t *)(dst + b) = 0;
+    for (int64_t b = tail0 + tid * 2; b < bytes; b += nth * 2) *(uint16_t *)(dst + b) = 0;
 }
 
 // The unfold primitive on one dimension of a row-major tensor seen as [outer][D][inner]:
@@ -658,6 +673,8 @@ alt_status_t plan_transform(alt_handle_t h, int elsz, const BoundLayout &ls, con
     if (!permutable) {
         t.kind = TransformPlan::GENERAL;
         t.gp.src = src; t.gp.dst = dst; t.gp.ls = ls; t.gp.ld = ld;
+        for (int d = 0; d < ls.ndim; ++d) t.gp.it_shape[d] = ls.shape[d];
+        t.gp.it_numel = numel;
         t.blocks = (unsigned)std::min<int64_t>((numel + kThreads - 1) / kThreads, 256 * 32);
         return ALT_OK;
     }
@@ -872,6 +889,52 @@ bool replay_any(int vl, int vs, bool sf, bool df, const TileParams &p, uint32_t 
 
 }  // namespace
 }  // namespace alt
+
+extern "C" alt_status_t alt_layout_transform_pad(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *src_shape,
+                                                 const alt_layout_t *src_layout, const void *src,
+                                                 const int64_t *dst_shape, const alt_layout_t *dst_layout, void *dst,
+                                                 void *stream)
+{
+    if (!h) return ALT_INVALID_ARG;
+    if (!src_shape || !dst_shape || !src_layout || !dst_layout || !src || !dst)
+        return fail(h, ALT_INVALID_ARG, "alt_layout_transform_pad: null argument");
+    if (dtype != ALT_F32 && dtype != ALT_BF16) return fail(h, ALT_INVALID_ARG, "alt_layout_transform_pad: bad dtype");
+    if (ndim < 1 || ndim > ALT_MAX_RANK) return fail(h, ALT_INVALID_ARG, "alt_layout_transform_pad: bad rank");
+    BoundLayout ls, ld;
+    std::string err;
+    alt_status_t s = bind_layout(src_layout, ndim, src_shape, &ls, &err);
+    if (s != ALT_OK) return fail(h, s, "source layout: %s", err.c_str());
+    s = bind_layout(dst_layout, ndim, dst_shape, &ld, &err);
+    if (s != ALT_OK) return fail(h, s, "destination layout: %s", err.c_str());
+    const size_t elsz = dtype_size(dtype);
+    const char *a = (const char *)src, *b = (const char *)dst;
+    if ((a < b + (size_t)ld.numel * elsz) && (b < a + (size_t)ls.numel * elsz))
+        return fail(h, ALT_INVALID_ARG, "alt_layout_transform_pad: src and dst must not overlap");
+    if ((uintptr_t)src % elsz || (uintptr_t)dst % elsz)
+        return fail(h, ALT_INVALID_ARG, "alt_layout_transform_pad: buffers are not aligned to the element size");
+    if (!h->has_gpu) return fail(h, ALT_HIP_ERROR, "no GPU device available");
+    GeneralParams gp;
+    gp.src = src; gp.dst = dst; gp.ls = ls; gp.ld = ld;
+    gp.it_numel = 1;
+    bool grows = false;
+    for (int d = 0; d < ndim; ++d) {
+        gp.it_shape[d] = std::min(src_shape[d], dst_shape[d]);
+        gp.it_numel *= gp.it_shape[d];
+        grows |= dst_shape[d] > src_shape[d];
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (grows) {
+        const int64_t bytes = ld.numel * (int64_t)elsz;
+        const unsigned blocks = (unsigned)std::min<int64_t>((bytes / 16 + kThreads) / kThreads, 256 * 16);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(kThreads), 0, st, (char *)dst, bytes);
+        ALT_CHECK_HIP(h, hipGetLastError());
+    }
+    const unsigned blocks = (unsigned)std::min<int64_t>((gp.it_numel + kThreads - 1) / kThreads, 256 * 32);
+    if (elsz == 2) hipLaunchKernelGGL(permute_general_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, gp);
+    else hipLaunchKernelGGL(permute_general_kernel<4>, dim3(blocks), dim3(kThreads), 0, st, gp);
+    ALT_CHECK_HIP(h, hipGetLastError());
+    return ALT_OK;
+}
 
 extern "C" alt_status_t alt_layout_transform_plan(alt_handle_t h, alt_dtype_t dtype, int ndim, const int64_t *shape,
                                                   const alt_layout_t *src_layout, int src_misalign,

@@ -254,6 +254,13 @@ def test_calls_without_gpu_fail_loudly_not_silently():
     with pytest.raises(alt.AltError) as e:
         h.layout_transform(alt.F32, (2, 4), "MK->MK", 16, "MK->KM", 16, stream=0)
     assert e.value.status == 1
+    # the pad form checks its layouts against their own shapes and refuses overlapping buffers before any device work
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform_pad(alt.BF16, (2, 12, 3, 3), "NCHW->NCHW", 16, (2, 12, 3, 3), "NCHW->NCHW16c", 8192, stream=0)
+    assert e.value.status == 3                           # 16 does not divide the destination's 12 channels
+    with pytest.raises(alt.AltError) as e:
+        h.layout_transform_pad(alt.BF16, (2, 12, 3, 3), "NCHW->NCHW", 16, (2, 16, 3, 3), "NCHW->NCHW16c", 64, stream=0)
+    assert e.value.status == 1
     bad = alt.conv_desc(1, 24, 8, 8, 16, 3, 3, pad=1, x_layout="NCHW->NCHW16c")
     with pytest.raises(alt.AltError) as e:
         h.conv2d(bad, 16, 16, 16, stream=0)
@@ -274,6 +281,8 @@ def test_calls_without_gpu_fail_loudly_not_silently():
                  lambda: h.pack_weights3d_transpose(alt.conv3d_desc(1, 16, 4, 8, 8, 16, 3, 3, 3, pad=1), 16, 16, stream=0),
                  lambda: h.tune_conv2d_multi([dict(d=nhwc, x=16, w=16, y=16, stream=0)]),
                  lambda: h.eltwise_add(alt.BF16, 64, 16, 16, 16, stream=0),
+                 lambda: h.layout_transform_pad(alt.BF16, (2, 12, 3, 3), "NCHW->NCHW", 16, (2, 16, 3, 3), "NCHW->NCHW16c", 8192,
+                                                stream=0),
                  lambda: h.unfold(alt.BF16, (4, 8), 0, 2, 1, 16, 4096, stream=0)):
         with pytest.raises(alt.AltError) as e:
             call()

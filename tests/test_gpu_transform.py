@@ -199,3 +199,52 @@ def test_transform_of_more_than_2_to_the_31_elements(h):
     for o in (edges, sample):
         assert torch.equal(out[o], pattern(src_off_of_dst(o)))
 
+
+
+@pytest.mark.parametrize("dtype", [alt.F32, alt.BF16])
+@pytest.mark.parametrize("case", [
+    ((3, 60, 7, 5), "NCHW->NCHW", (3, 64, 7, 5), "NCHW->NCHW16c"),      # channels padded to the next block
+    ((3, 60, 7, 5), "NCHW->NHWC", (3, 64, 9, 5), "NCHW->NCHW32c"),      # channels and height, blocked destination
+    ((2, 64, 6, 7), "NCHW->NCHW16c", (2, 50, 6, 7), "NCHW->NHWC"),      # unpad
+    ((4, 10, 3, 3), "NCHW->NCHW", (2, 16, 3, 5), "NCHW->NCHW8c"),       # one extent shrinks, others grow
+], ids=["pad_c", "pad_ch", "unpad_c", "mixed"])
+def test_pad_transform_bit_exact(h, dtype, case):
+    """alt_layout_transform_pad against the oracle's pad transform: NaN payloads, -0 and denormals move
+    unchanged, everything outside the source is all-bits-zero, nothing outside the destination is touched."""
+    src_shape, src_name, dst_shape, dst_name = case
+    bits = 32 if dtype == alt.F32 else 16
+    data = special_bit_patterns(17, src_shape, bits).reshape(-1)
+    s_seq = oracle.seq_from_string(src_name, src_shape)
+    d_seq = oracle.seq_from_string(dst_name, dst_shape)
+    want = oracle.pad_transform(data, src_shape, s_seq, dst_shape, d_seq)
+    src = dev(data)
+    n_out = int(np.prod(dst_shape))
+    for shift in (0, 1):                                   # destination at an aligned and at an odd element offset
+        whole, dst = canary_dev(n_out, NP[dtype], pad=64 + shift)
+        h.layout_transform_pad(dtype, src_shape, src_name, src, dst_shape, dst_name, dst)
+        got = host(dst, NP[dtype])
+        assert canary_ok(whole, n_out, pad=64 + shift), "wrote outside the destination"
+        assert np.array_equal(got, want), (case, shift)
+
+
+def test_convolution_over_padded_channels_equals_the_unpadded_one(h):
+    """C = 60 does not divide into blocks of 16: padded to 64 (activations and weights) the blocked layouts
+    apply, and the zeros add nothing: the result equals the oracle's convolution of the unpadded tensors."""
+    from workloads import small_ints_f32, f32_to_bf16_bits
+    from gpu_util import from_layout
+    N, C, Cp, H, W, K = 2, 60, 64, 9, 8, 32
+    x = small_ints_f32(301, (N, C, H, W), -3, 3)
+    w = small_ints_f32(302, (K, C, 3, 3), -3, 3)
+    ref = oracle.conv2d(x, w, stride=1, pad=1)
+    xd, wd = dev(f32_to_bf16_bits(x).reshape(-1)), dev(f32_to_bf16_bits(w).reshape(-1))
+    xp = torch.empty(N * Cp * H * W, dtype=torch.int16, device="cuda")
+    wp = torch.empty(K * Cp * 9, dtype=torch.int16, device="cuda")
+    h.layout_transform_pad(alt.BF16, (N, C, H, W), "NCHW->NCHW", xd, (N, Cp, H, W), "NCHW->NCHW16c", xp)
+    h.layout_transform_pad(alt.BF16, (K, C, 3, 3), "OIHW->OIHW", wd, (K, Cp, 3, 3), "OIHW->OIHW16o16i", wp)
+    d = alt.conv_desc(N, Cp, H, W, K, 3, 3, stride=1, pad=1, in_dtype=alt.BF16, out_dtype=alt.F32,
+                      x_layout="NCHW->NCHW16c", w_layout="OIHW->OIHW16o16i", y_layout="NCHW->NCHW16c")
+    y = torch.empty(N * K * H * W, dtype=torch.float32, device="cuda")
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    h.conv2d(d, xp, wp, y, workspace=ws, ws_bytes=ws.numel())
+    got = from_layout(host(y, np.float32), (N, K, H, W), "NCHW", "NCHW16c")
+    assert np.array_equal(got, ref)
