@@ -85,8 +85,28 @@ struct DconvParams {
     int32_t OH, OW, stride, in_px;
     int32_t dil;                  // distance between filter taps, in input pixels (both directions)
     const void *addend;           // added before the activation: same layout and element type as y, or null
-    Div32 d_ihw;                  // channel-planar kernel (dplanar.h) only: division by H*W
+    Div32 d_ihw;                  // division by H*W (channel-planar kernel, blocked activations)
+    // Channel-blocked tensors (N C/b H W b, b = 1 << blk, at least 8): 0 = channels contiguous per pixel (NHWC)
+    int32_t x_blk, y_blk;
 };
+
+// Element offset of channel `ch` of input pixel g (= img * H*W + hw) under the activations' layout.
+__device__ __forceinline__ uint32_t dconv_in_elem(const DconvParams &p, int g, int ch)
+{
+    if (p.x_blk == 0) return (uint32_t)(g * p.C + ch);
+    const int hw_all = p.H * p.W;
+    const int img = (int)div32((uint32_t)g, p.d_ihw), hw = g - img * hw_all;
+    return (uint32_t)(img * (p.C * hw_all) + ((((ch >> p.x_blk) * hw_all + hw) << p.x_blk) | (ch & ((1 << p.x_blk) - 1))));
+}
+
+// Element offset of channel n of output pixel m (= img * OH*OW + q) under the output's layout.
+__device__ __forceinline__ uint32_t dconv_out_elem(const DconvParams &p, int m, int n)
+{
+    if (p.y_blk == 0) return (uint32_t)(m * p.Nc + n);
+    const int ohw = p.OH * p.OW;
+    const int img = (int)div32((uint32_t)m, p.d_hw), q = m - img * ohw;
+    return (uint32_t)(img * (p.Nc * ohw) + ((((n >> p.y_blk) * ohw + q) << p.y_blk) | (n & ((1 << p.y_blk) - 1))));
+}
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
@@ -221,11 +241,14 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
                     vs[it][v] += (f32x4_t){f.x, f.y, f.z, f.w};
                 }
     }
-    uint32_t offs[NIT];                                    // element offsets in the output (and a partial-sum plane)
+    uint32_t offs[NIT];                                    // element offsets in a partial-sum plane ([M][Nc]) ...
+    uint32_t yoffs[NIT];                                   // ... and in the output under its layout
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int m = mrow0 + it * RPI;
-        offs[it] = (n_ok && m < p.M) ? (uint32_t)(m * p.Nc + n) : kOutOfRange / 4u;
+        const bool in = n_ok && m < p.M;
+        offs[it] = in ? (uint32_t)(m * p.Nc + n) : kOutOfRange / 4u;
+        yoffs[it] = in ? dconv_out_elem(p, m, n) : kOutOfRange / 4u;
     }
 
     if (p.splitk > 1) {
@@ -309,7 +332,7 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
     const __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc((void *)p.addend, 0, (int)p.y_bytes, 0x00020000);
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const bool ok = offs[it] != kOutOfRange / 4u;
+        const bool ok = yoffs[it] != kOutOfRange / 4u;
         float ad[CW];                                      // the fused sum's other operand (zeros without one)
 #pragma unroll
         for (int q = 0; q < CW; ++q) ad[q] = 0.f;
@@ -318,17 +341,17 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
             // bf16: element 2j is the low half of dword j, element 2j+1 the high half (whole-vector
             // shifts and masks; an out-of-range offset reads zeros)
             u32x4_t av = {0u, 0u, 0u, 0u};
-            if constexpr (CW == 8) av = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+            if constexpr (CW == 8) av = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? yoffs[it] * 2u : kOutOfRange), 0, 0);
             else {
                 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-                const u32x2_t a2 = __builtin_amdgcn_raw_buffer_load_b64(ar, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, 0);
+                const u32x2_t a2 = __builtin_amdgcn_raw_buffer_load_b64(ar, (int)(ok ? yoffs[it] * 2u : kOutOfRange), 0, 0);
                 av = __builtin_shufflevector(a2, a2, 0, 1, 0, 1);
             }
             const f32x4_t lo = __builtin_bit_cast(f32x4_t, av << 16), hi = __builtin_bit_cast(f32x4_t, av & 0xffff0000u);
 #pragma unroll
             for (int q = 0; q < CW / 2; ++q) { ad[2 * q] = lo[q]; ad[2 * q + 1] = hi[q]; }
         } else {
-            const f32x4_t a4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, 0));
+            const f32x4_t a4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok ? yoffs[it] * 4u : kOutOfRange), 0, 0));
             const f32x4_t z = a4 + (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int q = 0; q < 4; ++q) ad[q] = z[q];
@@ -343,16 +366,16 @@ __device__ __forceinline__ bool dconv_epilogue_tail(const DconvParams &p, uint4 
                 w[q] = f32x2_to_bf16x2(o[2 * q], o[2 * q + 1]);
             if constexpr (CW == 8) {
                 u32x4_t ov = {w[0], w[1], w[2], w[3]};
-                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, kWriteThrough);
+                __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? yoffs[it] * 2u : kOutOfRange), 0, kWriteThrough);
             } else {
                 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
                 u32x2_t ov = {w[0], w[1]};
-                __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? offs[it] * 2u : kOutOfRange), 0, kWriteThrough);
+                __builtin_amdgcn_raw_buffer_store_b64(ov, yr, (int)(ok ? yoffs[it] * 2u : kOutOfRange), 0, kWriteThrough);
             }
         } else {
             u32x4_t ov = {__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
                           __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3])};
-            __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? offs[it] * 4u : kOutOfRange), 0, kWriteThrough);
+            __builtin_amdgcn_raw_buffer_store_b128(ov, yr, (int)(ok ? yoffs[it] * 4u : kOutOfRange), 0, kWriteThrough);
         }
     }
     return true;
@@ -457,7 +480,7 @@ __device__ __forceinline__ void dconv_epilogue_banded(const DconvParams &p, floa
                 const float4 f = *(const float4 *)(stg + row * SP + cl * CW + v * 4);
                 o[v * 4 + 0] = f.x; o[v * 4 + 1] = f.y; o[v * 4 + 2] = f.z; o[v * 4 + 3] = f.w;
             }
-            const uint32_t el = (uint32_t)(m * p.Nc + n);
+            const uint32_t el = ok ? dconv_out_elem(p, m, n) : 0u;
             float ad[CW];                                  // the fused sum's other operand: y's layout and element type
 #pragma unroll
             for (int q = 0; q < CW; ++q) ad[q] = 0.f;
@@ -602,13 +625,12 @@ void dconv_kernel(const DconvParams p)
     const int pz = (int)div32((uint32_t)((nwl << 6) + spp - 1), p.d_slots);   // the all-zero pixel row behind the patch
     {
         const int g0 = a0 - halo;
-        const uint32_t lane_off = (uint32_t)(split * p.Cs) * 2u;
         auto load_one = [&](int j) {
             const int slot = j * 64 + lane;
             const int px = (int)div32((uint32_t)slot, p.d_slots), c = slot - px * spp;
             const int g = g0 + px;
             const bool ok = c < spp - 1 && px < np && (unsigned)g < (unsigned)p.in_px;
-            const uint32_t voff = ok ? (uint32_t)(g * p.C) * 2u + lane_off + (uint32_t)c * 16u : kOutOfRange;
+            const uint32_t voff = ok ? dconv_in_elem(p, g, split * p.Cs + c * 8) * 2u : kOutOfRange;
             dma_load16(x_rsrc, voff, patch0 + j * 1024);
         };
         int j = wave;

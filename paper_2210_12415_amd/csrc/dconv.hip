@@ -36,6 +36,21 @@ bool dense(const Dim2 &d, int64_t extent, int64_t stride)
     return extent == 1 || (d.f >= extent && d.si == stride);
 }
 
+// Whether four per-dimension maps describe a dense activation tensor with the channels of a pixel contiguous
+// (NHWC: *blk = 0) or in blocks of b = 2^*blk >= 8 channels (N C/b H W b, b dividing C).
+bool nhwc_or_blocked(const Dim2 &c, const Dim2 &w, const Dim2 &h, const Dim2 &n, int64_t C, int64_t H, int64_t W, int64_t N,
+                     int *blk)
+{
+    if (dense(c, C, 1) && dense(w, W, C) && dense(h, H, W * C) && dense(n, N, H * W * C)) { *blk = 0; return true; }
+    const int64_t b = c.f;
+    if (c.si != 1 || b < 8 || b >= C || (b & (b - 1)) || C % b || c.so != H * W * b) return false;
+    if (!(dense(w, W, b) && dense(h, H, W * b) && dense(n, N, C * H * W))) return false;
+    int l = 0;
+    while (((int64_t)1 << l) < b) ++l;
+    *blk = l;
+    return true;
+}
+
 DeviceState *device_state()
 {
     int dev = 0;
@@ -127,16 +142,17 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
         return no("streaming kernel needs a 1x1 filter, stride 1, no padding");
     if (p.OH != p.H || p.OW != p.W) return no("streaming kernel needs output size = input size");
     const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, N = p.M / (H * W);
-    if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
-        return no("A is not dense with K contiguous");
+    int x_blk = 0, y_blk = 0;
+    if (!nhwc_or_blocked(p.xc, p.xw, p.xh, p.xn, C, H, W, N, &x_blk)) return no("A is not dense with K contiguous (whole or in blocks)");
+    if (x_blk && k.BK % (1 << x_blk)) return no("channel blocks larger than a K step");
     if (k.bt) {
         if (!(dense(p.wo, K, 1) && dense(p.wi, C, K))) return no("B is not dense with N contiguous");
         if (K % 8) return no("row-major B is loaded eight columns at a time");
     } else if (!(dense(p.wi, C, 1) && dense(p.wo, K, C))) {
         return no("B is not dense with K contiguous");
     }
-    if (!(dense(p.yk, K, 1) && dense(p.yw, W, K) && dense(p.yh, H, W * K) && dense(p.yn, N, H * W * K)))
-        return no("output is not dense with N contiguous");
+    if (!nhwc_or_blocked(p.yk, p.yw, p.yh, p.yn, K, H, W, N, &y_blk)) return no("output is not dense with N contiguous (whole or in blocks)");
+    if ((x_blk || y_blk) && p.batch > 1) return no("blocked tensors are not built for batched problems");
     const int64_t osz = p.out_bf16 ? 2 : 4;
     if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16 || (uintptr_t)p.y % 16) return no("operands are not 16-byte aligned");
     if (p.batch > 1 && ((p.x_bstride * 2) % 16 || (p.w_bstride * 2) % 16 || (p.y_bstride * osz) % 16))
@@ -173,6 +189,8 @@ static bool dstream_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     d.bk = k.BK;
     d.d_sk = make_div32((uint32_t)splitk);
     d.batch = p.batch;
+    d.OH = p.H; d.OW = p.W; d.x_blk = x_blk; d.y_blk = y_blk;
+    d.d_ihw = make_div32((uint32_t)(p.H * p.W));
     d.x_bstride = p.x_bstride * 2; d.w_bstride = p.w_bstride * 2; d.y_bstride = p.y_bstride * osz;
     *out = d;
     *lds_bytes = lds;
@@ -256,12 +274,11 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     // (then OH <= ceil(H / stride) and likewise OW: the input pixel under an output pixel never moves backwards)
     if ((int64_t)(p.OH - 1) * st_ >= p.H || (int64_t)(p.OW - 1) * st_ >= p.W) return no("output larger than the strided input");
     const int64_t C = p.C, H = p.H, W = p.W, OH = p.OH, OW = p.OW, K = p.Nc, R = p.R, S = p.S, N = p.M / (OH * OW);
-    if (!(dense(p.xc, C, 1) && dense(p.xw, W, C) && dense(p.xh, H, W * C) && dense(p.xn, N, H * W * C)))
-        return no("activations are not dense NHWC");
+    int x_blk = 0, y_blk = 0;
+    if (!nhwc_or_blocked(p.xc, p.xw, p.xh, p.xn, C, H, W, N, &x_blk)) return no("activations are not dense NHWC or N C/b H W b");
     if (!(dense(p.wi, C, 1) && dense(p.ws, S, C) && dense(p.wr, R, S * C) && dense(p.wo, K, R * S * C)))
         return no("weights are not dense OHWI");
-    if (!(dense(p.yk, K, 1) && dense(p.yw, OW, K) && dense(p.yh, OH, OW * K) && dense(p.yn, N, OH * OW * K)))
-        return no("output is not dense NHWC");
+    if (!nhwc_or_blocked(p.yk, p.yw, p.yh, p.yn, K, OH, OW, N, &y_blk)) return no("output is not dense NHWC or N K/b H W b");
     if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16) return no("operands are not 16-byte aligned");
     if (splitk < 1 || C % splitk) return no("split factor does not divide the channels");
     const int64_t Cs = C / splitk;
@@ -308,6 +325,8 @@ bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParam
     d.ncc = (int32_t)(Csg / bk);
     d.bk = bk;
     d.d_sk = make_div32((uint32_t)splitk);
+    d.x_blk = x_blk; d.y_blk = y_blk;
+    d.d_ihw = make_div32((uint32_t)(H * W));
     *out = d;
     *lds_bytes = lds;
     return true;

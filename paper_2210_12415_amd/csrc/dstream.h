@@ -89,7 +89,9 @@ void dstream_kernel(const DconvParams p)
         const int s = (i * NWG + wq) * 64 + lane;
         const int row = s / CPR, c = (s % CPR) ^ ((row / RP) & (CPR - 1));
         const int m = m0 + row;
-        a_voff[i] = m < p.M ? (uint32_t)(m * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
+        // (blocked activations: a K step is BK / block whole blocks, so the chunk's place inside the step and the
+        // step's distance are both fixed)
+        a_voff[i] = m < p.M ? dconv_in_elem(p, m, split * p.Cs + kg * (nk * BK) + c * 8) * 2u : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
@@ -105,15 +107,17 @@ void dstream_kernel(const DconvParams p)
             b_voff[i] = n < p.Nc ? (uint32_t)(n * p.C) * 2u + k_off0 + (uint32_t)c * 16u : kOutOfRange;
         }
     }
-    // byte distance between consecutive K steps of B: BK columns of a row, or BK rows
+    // byte distance between consecutive K steps of B: BK columns of a row, or BK rows; of A: BK channels of a
+    // pixel, or BK / block channel blocks (planes of H*W pixels)
     const uint32_t b_step = BT ? (uint32_t)(BK * p.Nc) * 2u : (uint32_t)(BK * 2);
+    const uint32_t a_step = p.x_blk ? (uint32_t)(BK * p.H * p.W) * 2u : (uint32_t)(BK * 2);
     const uint32_t ring0 = lds0 + kg * RING;
     const uint32_t ldsW = ring0 + wq * 1024;
     // load cursor: K step `lstep` goes to stage `lstage`; past the last step the last one is
     // loaded again (into stages nobody reads any more), which keeps the load count per step fixed
     int lstep = 0, lstage = 0;
     auto issue_stage = [&]() {
-        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * (BK * 2), soff_b = (uint32_t)min(lstep, nk - 1) * b_step;
+        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * a_step, soff_b = (uint32_t)min(lstep, nk - 1) * b_step;
         const uint32_t dst = ldsW + lstage * STAGE;
 #pragma unroll
         for (int i = 0; i < NLA; ++i) dma_load16_s(x_rsrc, a_voff[i], soff, dst + i * (NWG * 1024));
@@ -226,7 +230,7 @@ void dstream_kernel(const DconvParams p)
     // TM - 1 rows, so that the last row's MFMAs cover their latency) and one of the step's
     // direct-to-LDS loads; scheduling barriers keep the compiler from regrouping them.
     auto issue_one = [&](int i) {                          // load i of the stage the cursor is on
-        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * (BK * 2), soff_b = (uint32_t)min(lstep, nk - 1) * b_step;
+        const uint32_t soff = (uint32_t)min(lstep, nk - 1) * a_step, soff_b = (uint32_t)min(lstep, nk - 1) * b_step;
         const uint32_t dst = ldsW + lstage * STAGE;
         if (i < NLA) dma_load16_s(x_rsrc, a_voff[i], soff, dst + i * (NWG * 1024));
         else dma_load16_s(w_rsrc, b_voff[i - NLA], soff_b, dst + A_STAGE + (i - NLA) * (NWG * 1024));

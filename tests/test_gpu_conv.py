@@ -985,3 +985,45 @@ def test_conv2d_add_fused_sum_exact_integers(h, out_dtype):
     with pytest.raises(alt.AltError) as e:
         h.conv2d_add(d, z, z, z, z)
     assert e.value.status == 4
+
+
+BLOCKED_CASES = [
+    # (case, x layout, y layout)
+    (dict(N=3, C=128, H=9, W=10, K=96, R=3, S=3, pad=1), "NCHW16c", "NCHW32c"),
+    (dict(N=2, C=64, H=20, W=17, K=64, R=3, S=3, pad=1), "NCHW8c", "NHWC"),
+    (dict(N=2, C=256, H=13, W=6, K=160, R=1, S=1, pad=0), "NCHW64c", "NCHW16c"),       # 1x1: the streaming kernels too
+    (dict(N=2, C=128, H=14, W=18, K=64, R=1, S=1, pad=0), "NCHW32c", "NCHW8c"),
+    (dict(N=5, C=512, H=3, W=3, K=64, R=3, S=3, pad=1), "NHWC", "NCHW64c"),
+    (dict(N=3, C=64, H=12, W=10, K=96, R=3, S=3, pad=1, stride=2), "NCHW32c", "NCHW32c"),
+    (dict(N=2, C=64, H=13, W=12, K=64, R=3, S=3, pad=2, dil=2), "NCHW16c", "NCHW16c"),
+]
+
+
+@pytest.mark.parametrize("case,xl,yl", BLOCKED_CASES, ids=lambda v: v if isinstance(v, str) else "c%d_%dx%d_k%d_%dx%d" % (
+    v["C"], v["H"], v["W"], v["K"], v["R"], v["S"]))
+def test_tile_kernels_on_channel_blocked_tensors(h, case, xl, yl):
+    """The patch-resident and streaming kernels with activations and output as N C/b H W b (b = 8 .. 64) and weights
+    OHWI: the patch loader and the epilogue address 16-byte channel runs under the blocked layout; every variant,
+    bit for bit, fp32 and bf16 output, bias and ReLU (split-K tails included)."""
+    c = case
+    x = small_ints_f32(111, (c["N"], c["C"], c["H"], c["W"]), -3, 3)
+    w = small_ints_f32(112, (c["K"], c["C"], c["R"], c["S"]), -3, 3)
+    b = small_ints_f32(113, (c["K"],), -50, 50)
+    st, dil = c.get("stride", 1), c.get("dil", 1)
+    cfg = dict(stride=st, pad=c["pad"], dil=dil)
+    ref = oracle.conv2d(x, w, stride=st, pad=c["pad"], dil=dil)
+    ref_br = oracle.conv2d(x, w, stride=st, pad=c["pad"], dil=dil, bias=b, relu=True)
+    xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=st, pad=c["pad"], dil=dil,
+                       in_dtype=alt.BF16, x_layout="NCHW->" + xl, w_layout="OIHW->OHWI", y_layout="NCHW->" + yl)
+    variants = [(v, n) for v, n in applicable_variants(h, d0) if "_direct_" in n or "_stream_" in n]
+    assert len(variants) >= 6, "tile kernels should cover this case"
+    for v, name in variants:
+        got, _ = run_conv(h, xb, wb, cfg, xl, "OHWI", yl, alt.BF16, variant=v)
+        assert np.array_equal(got, ref), name
+    picks = [variants[0], variants[len(variants) // 2], variants[-1]] + [vn for vn in variants if not vn[1].endswith("_k1")][:3]
+    for v, name in picks:
+        got, _ = run_conv(h, xb, wb, cfg, xl, "OHWI", yl, alt.BF16, bias=b, relu=True, variant=v)
+        assert np.array_equal(got, ref_br), name
+        got16, _ = run_conv(h, xb, wb, cfg, xl, "OHWI", yl, alt.BF16, out_dtype=alt.BF16, bias=b, relu=True, variant=v)
+        assert np.array_equal(got16, f32_to_bf16_bits(ref_br)), name
