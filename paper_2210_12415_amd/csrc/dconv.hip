@@ -219,8 +219,10 @@ static bool dplanar_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
         return no("activations are not dense NCHW");
     if (!(dense(p.ws, S, 1) && dense(p.wr, R, S) && dense(p.wi, C, R * S) && dense(p.wo, K, C * R * S)))
         return no("weights are not dense OIHW");
-    if (!(dense(p.yw, OW, 1) && dense(p.yh, OH, OW) && dense(p.yk, K, OH * OW) && dense(p.yn, N, K * OH * OW)))
-        return no("output is not dense NCHW");
+    const bool y_nchw = dense(p.yw, OW, 1) && dense(p.yh, OH, OW) && dense(p.yk, K, OH * OW) && dense(p.yn, N, K * OH * OW);
+    const bool y_nhwc = dense(p.yk, K, 1) && dense(p.yw, OW, K) && dense(p.yh, OH, OW * K) && dense(p.yn, N, OH * OW * K);
+    if (!y_nchw && !y_nhwc) return no("output is neither dense NCHW nor dense NHWC");
+    if (!y_nchw && (K % 8 || (uintptr_t)p.y % 16)) return no("NHWC output is stored eight channels at a time");
     if (C % 64) return no("channels must be a multiple of 64");
     if (H * W < 8) return no("images of fewer than eight pixels");
     if ((uintptr_t)p.w % 16 || (uintptr_t)p.x % 2) return no("weights are not 16-byte aligned");
@@ -241,7 +243,7 @@ static bool dplanar_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = p.C;
     d.H = p.H; d.W = p.W; d.R = p.R; d.S = p.S; d.pad_h = p.pad_h; d.pad_w = p.pad_w;
     d.tiles_m = tiles_m; d.tiles_n = tiles_n; d.splitk = 1;
-    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
+    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0) | (y_nchw ? 0 : kPlanarOutNhwc);
     d.OH = p.OH; d.OW = p.OW; d.stride = st_; d.dil = p.dil_h;
     d.in_px = (int32_t)(N * H * W);
     d.d_hw = make_div32((uint32_t)(p.OH * p.OW));

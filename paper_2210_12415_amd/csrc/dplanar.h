@@ -22,6 +22,10 @@
 // K groups: KW groups of waves each take every KW-th 16-channel chunk of a tap's 64
 // channels; their tiles are summed in group order when the staged output is read back.
 //
+// The output may also be NHWC (eight output channels per store): the layer then converts the
+// layout for an NHWC consumer by itself, which is how layout propagation (Section 4.2) lets a
+// chain that starts in NCHW do without a conversion operator.
+//
 // Covers: bf16, 1x1 and 3x3 filters, stride 1 or 2, any dilation, padding from none to
 // same-size, channels a multiple of 64, images of at least eight pixels, fp32 or bf16
 // output, bias and ReLU.  No split-K and no fused addend.
@@ -46,6 +50,8 @@ struct __attribute__((packed, aligned(4))) PlanarRunF {
     f32x4_t v;
 };
 
+constexpr int kPlanarOutNhwc = 8;                // flag: the output is NHWC, not NCHW
+
 constexpr int kPlanarWP = 144;                   // bytes of a weight row in LDS: 64 channels and one unused 16-byte slot
 
 // LDS bytes of one tap's weight stage: BN rows, then 16 bytes that skew consecutive taps over the banks.
@@ -55,7 +61,8 @@ inline size_t dplanar_lds_bytes(int BM, int BN, int kw, int taps, int C, size_t 
 {
     const size_t npr = (np + 7) / 8 * 8;
     const size_t main_loop = (size_t)taps * planar_stage_bytes(BN) + (npr + 1) * ((size_t)C * 2 + 16);
-    const size_t staging = (size_t)kw * BN * (BM + 4) * 4;
+    // output staging: [channel][pixel] (NCHW output) or [pixel][channel] (NHWC output), the larger of the two
+    const size_t staging = std::max((size_t)kw * BN * (BM + 4) * 4, (size_t)kw * BM * (BN + 4) * 4);
     return main_loop > staging ? main_loop : staging;
 }
 
@@ -344,10 +351,58 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dplanar_kernel(const Dcon
         }
     }
 
-    // ---- output: [K group][channel][pixel] through LDS, then plane by plane ------------------------------
-    constexpr int SPM = BM + 4;                            // staging pitch in floats
     __syncthreads();
     float *stg = (float *)smem;
+    if (p.flags & kPlanarOutNhwc) {
+        // ---- output with the channels of a pixel contiguous (the consumer's layout: no conversion operator
+        // between this layer and an NHWC one): [K group][pixel][channel] through LDS, then eight channels
+        // (16 bytes of bf16, two 16-byte stores of fp32) per thread ----------------------------------------
+        constexpr int SPN = BN + 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    stg[((size_t)kg * BM + wm * WTM + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + e % 4) * SPN + wn * WTN + j * 32 +
+                        (lane & 31)] = acc[i][j][e];
+        __syncthreads();
+        constexpr int N8 = BN / 8;
+        const bool relu = p.flags & ALT_EPI_RELU, bias = p.flags & ALT_EPI_BIAS, obf = p.flags & kDconvOutBf16;
+        for (int idx = t; idx < BM * N8; idx += NT) {
+            const int ml = idx / N8, nl = (idx % N8) * 8;
+            const int m = m0 + ml, n = n0 + nl;
+            if (m >= p.M || n >= p.Nc) continue;
+            float v[8];
+            {
+                const float *sg = stg + (size_t)ml * SPN + nl;
+                const float4 lo = *(const float4 *)sg, hi = *(const float4 *)(sg + 4);
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+            }
+#pragma unroll
+            for (int g = 1; g < KW; ++g) {
+                const float *sg = stg + ((size_t)g * BM + ml) * SPN + nl;
+                const float4 lo = *(const float4 *)sg, hi = *(const float4 *)(sg + 4);
+                v[0] += lo.x; v[1] += lo.y; v[2] += lo.z; v[3] += lo.w; v[4] += hi.x; v[5] += hi.y; v[6] += hi.z; v[7] += hi.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (bias) v[e] += p.bias[n + e];
+                if (relu) v[e] = fmaxf(v[e], 0.f);
+            }
+            const size_t off = (size_t)m * p.Nc + n;       // (Nc is a multiple of 8 and y is 16-byte aligned here)
+            if (obf) {
+                *(uint4 *)((uint16_t *)p.y + off) = make_uint4(f32x2_to_bf16x2(v[0], v[1]), f32x2_to_bf16x2(v[2], v[3]),
+                                                               f32x2_to_bf16x2(v[4], v[5]), f32x2_to_bf16x2(v[6], v[7]));
+            } else {
+                *(float4 *)((float *)p.y + off) = make_float4(v[0], v[1], v[2], v[3]);
+                *(float4 *)((float *)p.y + off + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            }
+        }
+        return;
+    }
+    // ---- output: [K group][channel][pixel] through LDS, then plane by plane ------------------------------
+    constexpr int SPM = BM + 4;                            // staging pitch in floats
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -35,9 +35,11 @@ PLANAR_CASES = [
 ]
 
 
+@pytest.mark.parametrize("yl", ["NCHW", "NHWC"])
 @pytest.mark.parametrize("case", PLANAR_CASES, ids=lambda c: "c%d_%dx%d_k%d_%dx%d_s%d_p%d_d%d" % (
     c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], c.get("stride", 1), c["pad"], c.get("dil", 1)))
-def test_planar_kernels_exact_integers_every_variant(h, case):
+def test_planar_kernels_exact_integers_every_variant(h, case, yl):
+    """(yl = NHWC: the layer converts the layout for an NHWC consumer by itself.)"""
     c = case
     x = small_ints_f32(71, (c["N"], c["C"], c["H"], c["W"]), -3, 3)
     w = small_ints_f32(72, (c["K"], c["C"], c["R"], c["S"]), -3, 3)
@@ -48,16 +50,16 @@ def test_planar_kernels_exact_integers_every_variant(h, case):
     ref_br = oracle.conv2d(x, w, stride=st, pad=c["pad"], dil=dil, bias=b, relu=True)
     xb, wb = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
     d0 = alt.conv_desc(c["N"], c["C"], c["H"], c["W"], c["K"], c["R"], c["S"], stride=st, pad=c["pad"], dil=dil,
-                       in_dtype=alt.BF16, x_layout="NCHW->NCHW", w_layout="OIHW->OIHW", y_layout="NCHW->NCHW")
+                       in_dtype=alt.BF16, x_layout="NCHW->NCHW", w_layout="OIHW->OIHW", y_layout="NCHW->" + yl)
     variants = [(v, n) for v, n in applicable_variants(h, d0) if "planar" in n]
     assert len(variants) >= 2, "planar kernels should cover this case"
     for v, name in variants:
         print(name, flush=True)
-        got, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", "NCHW", alt.BF16, variant=v)
+        got, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", yl, alt.BF16, variant=v)
         assert np.array_equal(got, ref), name
-        got, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", "NCHW", alt.BF16, bias=b, relu=True, variant=v)
+        got, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", yl, alt.BF16, bias=b, relu=True, variant=v)
         assert np.array_equal(got, ref_br), name
-        got16, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", "NCHW", alt.BF16, out_dtype=alt.BF16, bias=b, relu=True,
+        got16, _ = run_conv(h, xb, wb, cfg, "NCHW", "OIHW", yl, alt.BF16, out_dtype=alt.BF16, bias=b, relu=True,
                             variant=v)
         assert np.array_equal(got16, f32_to_bf16_bits(ref_br)), name
 
