@@ -472,3 +472,49 @@ def test_transform_plan_takes_contiguous_runs_where_rows_are_odd():
     assert p.kind == 3 and p.src_flat == 0 and p.load_bytes == 2
     with pytest.raises(alt.AltError):
         h.layout_transform_plan(alt.F32, (2, 4, 2, 2), "NCHW->NCHW", "NCHW->NHWC", 2, 0)     # not a multiple of the element size
+
+
+def test_kernel_families_follow_the_layouts():
+    """Which kernel family covers which layouts (host-side applicability only, no GPU needed): the patch-resident
+    and streaming kernels take NHWC or channel-blocked activations and output with OHWI weights, the
+    channel-planar kernels NCHW activations and OIHW weights with NCHW or NHWC output, the transpose-read
+    streaming kernels row-major B; and without a tuned entry the library picks from the family written for the layout."""
+    h = alt.Handle()
+
+    def families(d, kind="conv"):
+        count = h.conv2d_variant_count(d) if kind == "conv" else h.gemm_variant_count(d)
+        fam = set()
+        for v in range(count):
+            try:
+                name = h.conv2d_variant_name(d, v) if kind == "conv" else h.gemm_variant_name(d, v)
+            except alt.AltError as e:
+                assert e.status == 4
+                continue
+            for key in ("_direct_", "_stream_", "_streamkn_", "_planar_"):
+                if key in name:
+                    fam.add(key.strip("_"))
+        return fam
+
+    def conv(xl, wl, yl, R=3, C=128, K=128):
+        return alt.conv_desc(16, C, 28, 28, K, R, R, stride=1, pad=R // 2, in_dtype=alt.BF16, out_dtype=alt.BF16,
+                             x_layout="NCHW->" + xl, w_layout="OIHW->" + wl, y_layout="NCHW->" + yl)
+
+    assert families(conv("NHWC", "OHWI", "NHWC")) == {"direct"}
+    assert families(conv("NCHW16c", "OHWI", "NCHW32c")) == {"direct"}
+    assert families(conv("NCHW64c", "OHWI", "NHWC", R=1)) == {"direct", "stream"}
+    assert families(conv("NCHW", "OIHW", "NCHW")) == {"planar"}
+    assert families(conv("NCHW", "OIHW", "NHWC")) == {"planar"}
+    assert families(conv("NCHW", "OHWI", "NCHW")) == set()            # planar kernels scatter OIHW rows
+    assert families(conv("NCHW16c", "OIHW16o16i", "NCHW16c")) == set()        # blocked weights: implicit-GEMM kernels
+    assert families(conv("NCHW", "OIHW", "NCHW", C=96)) == set()      # channels not a multiple of 64
+    assert "_planar_" in h.conv2d_variant_name(conv("NCHW", "OIHW", "NCHW"), -1)
+    assert "_direct_" in h.conv2d_variant_name(conv("NCHW32c", "OHWI", "NCHW32c"), -1)
+
+    def gemm(bl, N=768):
+        return alt.gemm_desc(2048, N, 768, in_dtype=alt.BF16, out_dtype=alt.F32, b_layout="KN->" + bl)
+
+    assert families(gemm("NK"), "gemm") == {"stream", "direct"}       # (a product is a 1x1 convolution to the patch kernels)
+    assert families(gemm("KN"), "gemm") == {"streamkn"}
+    assert families(gemm("KN", N=772), "gemm") == set()               # row-major B is loaded eight columns at a time
+    assert "_streamkn_" in h.gemm_variant_name(gemm("KN"), -1)
+    assert "_stream_" in h.gemm_variant_name(gemm("NK"), -1)
