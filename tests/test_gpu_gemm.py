@@ -167,3 +167,24 @@ def test_operand_of_2_gib_and_more(h, b_layout):
     got = Cd.view(M, N)[torch.from_numpy(rows).cuda()].cpu().numpy()
     assert np.array_equal(got, ref)
 
+
+
+@pytest.mark.parametrize("bl", ["NK", "KN"])
+def test_streaming_kernels_every_step_count(h, bl):
+    """Every number of K steps from 1 to 12, and 16, 17, 24 (whole and partial rounds over rings of 3 to 8 stages,
+    with and without K groups and split-K), on every streaming variant: the fragment reads of these kernels
+    complete behind the compiler's back, and a register copy the compiler places at a branch while such a
+    read is in flight would show as a wrong sum for exactly some step counts."""
+    M, N = 96, 136
+    for steps in list(range(1, 13)) + [16, 17, 24]:
+        K = 64 * steps
+        A = small_ints_f32(131 + steps, (1, M, K), -3, 3)
+        B = small_ints_f32(231 + steps, (1, K, N), -3, 3)
+        ref = oracle.gemm(A, B)
+        Ab, Bb = f32_to_bf16_bits(A), f32_to_bf16_bits(B)
+        d0 = alt.gemm_desc(M, N, K, in_dtype=alt.BF16, a_layout="MK->MK", b_layout="KN->" + bl, c_layout="MN->MN")
+        variants = [(v, n) for v, n in applicable_variants(h, d0, "gemm") if "stream" in n]
+        assert len(variants) >= 9
+        for v, name in variants:
+            got, _ = run_gemm(h, Ab, Bb, "MK", bl, "MN", alt.BF16, variant=v)
+            assert np.array_equal(got, ref), (name, steps)
