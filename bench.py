@@ -522,7 +522,7 @@ def main():
             kr = L["R"] if (L["R"] == L["S"] and ((L["R"] == 3 and ncc in (1, 2)) or (L["R"] == 1 and ncc in (1, 2, 4, 8)))) else 0
             key = "dconv_kernel<%d, %d, %d, %d, %d, %d, %d, %d, %d>|%d" % (BM, BN, wgm, wgn, kw, ns, BK, kr, ncc if kr else 0, grid)
         else:
-            key = "dstream_kernel<%d, %d, %d, %d, %d, %d, %d>|%d" % (BM, BN, wgm, wgn, kw, ns, BK, grid)
+            key = "dstream_kernel<%d, %d, %d, %d, %d, %d, %d, false>|%d" % (BM, BN, wgm, wgn, kw, ns, BK, grid)
         e = doc["kernels"].get(key)
         if not e or "fetch_bytes" not in e or "write_bytes" not in e:
             return None
