@@ -493,8 +493,8 @@ def main():
         return min(PEAK_BF16_TFLOPS, l["flops"] / l["bytes"] * PEAK_HBM_GBPS / 1e3)
 
     def load_traffic():
-        """HBM bytes per launch from a stored pair of hardware-counter runs
-        (workloads/traffic_from_rocprof.py writes the file), or None."""
+        """HBM bytes per launch from a stored pair of hardware-counter runs (FETCH_SIZE and
+        WRITE_SIZE averages per dispatch, scaled by the plain copy kernel's reading), or None."""
         path = os.path.join(ROOT, "workloads", "measured_traffic_gfx950.json")
         if not os.path.exists(path):
             return None
