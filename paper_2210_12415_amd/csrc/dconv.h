@@ -75,11 +75,10 @@ struct DconvParams {
     Div32 d_slots;                // division by Cs / 8 + 1, the 16-byte slots of a patch pixel in LDS
     int32_t ncc;                  // K steps per tap: (Cs / K groups) / channels per K step
     int32_t bk;                   // channels per K step: 64, or 32 for narrow K groups
-    int32_t regw_grid;            // register-weights kernel (dregw.h): resident workgroups of the launch
+    int32_t pad0_;
     Div32 d_sk;                   // division by splitk
     // streaming kernel (dstream.h) only: batch entries and the byte strides between them
-    int32_t batch;
-    int32_t regw_ring_px;         // register-weights kernel: pixels of the LDS ring
+    int32_t batch, pad1_;
     int64_t x_bstride, w_bstride, y_bstride;
     // direct kernel only: output image size and stride (H, W above are the input's; M counts
     // output pixels), and the number of input pixels
@@ -89,8 +88,6 @@ struct DconvParams {
     Div32 d_ihw;                  // division by H*W (channel-planar kernel, blocked activations)
     // Channel-blocked tensors (N C/b H W b, b = 1 << blk, at least 8): 0 = channels contiguous per pixel (NHWC)
     int32_t x_blk, y_blk;
-    int32_t regw_bias_off;        // register-weights kernel: where the bias sits in LDS, bytes
-    int32_t regw_ahead;           // register-weights kernel: tiles the loads run ahead
 };
 
 // Element offset of channel `ch` of input pixel g (= img * H*W + hw) under the activations' layout.

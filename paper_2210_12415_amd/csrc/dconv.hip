@@ -4,7 +4,6 @@
 #include <mutex>
 
 #include "dplanar.h"
-#include "dregw.h"
 #include "dstream.h"
 #include "ops.h"
 
@@ -259,86 +258,10 @@ static bool dplanar_setup(const Problem &pb, const IgemmLaunch &k, int splitk, D
     return true;
 }
 
-// The same for a register-weights kernel (dregw.h): a 3x3 filter over 32 or 64 channels into at most 64, stride 1,
-// output size = input size; activations and output NHWC or channel-blocked, weights OHWI.
-static bool dregw_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes,
-                        std::string *why)
-{
-    auto no = [&](const char *m) { if (why) *why = m; return false; };
-    const IgemmParams &p = pb.p;
-    if (pb.dtype != ALT_BF16) return no("register-weights kernel is bf16 only");
-    if (p.batch != 1) return no("register-weights kernel takes no batch");
-    if (splitk != 1) return no("register-weights kernel takes no split-K");
-    if (p.addend) return no("register-weights kernel has no fused sum");
-    if (p.R != 3 || p.S != 3) return no("register-weights kernel is built for 3x3 filters");
-    if (p.stride_h != 1 || p.stride_w != 1 || p.dil_h != 1 || p.dil_w != 1) return no("register-weights kernel needs stride 1, no dilation");
-    if (p.OH != p.H || p.OW != p.W || p.pad_h != 1 || p.pad_w != 1) return no("register-weights kernel needs output size = input size");
-    const int64_t C = p.C, H = p.H, W = p.W, K = p.Nc, N = p.M / (H * W);
-    if (C != 64 && C != 32) return no("register-weights kernel takes 32 or 64 input channels");
-    if (K > 64) return no("register-weights kernel takes at most 64 output channels");
-    int x_blk = 0, y_blk = 0;
-    if (!nhwc_or_blocked(p.xc, p.xw, p.xh, p.xn, C, H, W, N, &x_blk)) return no("activations are not dense NHWC or N C/b H W b");
-    if (!(dense(p.wi, C, 1) && dense(p.ws, 3, C) && dense(p.wr, 3, 3 * C) && dense(p.wo, K, 9 * C)))
-        return no("weights are not dense OHWI");
-    if (!nhwc_or_blocked(p.yk, p.yw, p.yh, p.yn, K, H, W, N, &y_blk)) return no("output is not dense NHWC or N K/b H W b");
-    if ((uintptr_t)p.x % 16 || (uintptr_t)p.w % 16 || (uintptr_t)p.y % 16) return no("operands are not 16-byte aligned");
-    if (K % 8) return no("register-weights kernel stores eight output channels at a time");
-    if ((p.epilogue & ALT_EPI_BIAS) && (uintptr_t)p.bias % 4) return no("bias is not aligned");
-    if (pb.x_elems * 2 >= 0x7fffffff || pb.w_elems * 2 >= 0x7fffffff || p.y_bytes == 0 || (int64_t)p.M * K * 4 >= 0x7fffffff)
-        return no("operand of 2 GiB or more");
-    if (N * H * W > 0x7fffffff - (1 << 20)) return no("input too large for 32-bit pixel indices");
-    if (k.BM != kRegwBM) return no("tile height");
-    int ring_px = 0, ahead = 0;
-    uint32_t bias_off = 0;
-    size_t lds = 0;
-    if (W > 4096 || !dregw_plan((int)C, (int)W, &ring_px, &ahead, &bias_off, &lds)) return no("no pixel ring for this image width fits LDS");
-    const int tiles_m = (p.M + k.BM - 1) / k.BM;
-    if (!out) return true;
-    // one resident workgroup per compute unit (its registers leave room for no second one)
-    static int cus[kMaxDevices] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return no("no current device");
-    if (cus[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return no("device query failed");
-        cus[dev] = n;
-    }
-    DconvParams d;
-    std::memset(&d, 0, sizeof d);
-    d.x = p.x; d.w = p.w; d.bias = p.bias; d.y = p.y;
-    d.x_bytes = p.x_bytes; d.w_bytes = p.w_bytes; d.y_bytes = p.y_bytes;
-    d.M = p.M; d.Nc = p.Nc; d.C = p.C; d.Cs = p.C;
-    d.H = p.H; d.W = p.W; d.R = 3; d.S = 3; d.pad_h = 1; d.pad_w = 1;
-    d.tiles_m = tiles_m; d.tiles_n = 1; d.splitk = 1;
-    d.flags = (p.epilogue & (ALT_EPI_BIAS | ALT_EPI_RELU)) | (p.out_bf16 ? kDconvOutBf16 : 0);
-    d.OH = p.H; d.OW = p.W; d.stride = 1; d.dil = 1;
-    d.in_px = (int32_t)(N * H * W);
-    d.d_hw = make_div32((uint32_t)(H * W));
-    d.d_w = make_div32((uint32_t)W);
-    d.d_tm = make_div32((uint32_t)tiles_m);
-    d.d_tn = make_div32(1);
-    d.d_ihw = make_div32((uint32_t)(H * W));
-    d.d_sk = make_div32(1);
-    int l2 = 0;
-    while ((8 << l2) < C) ++l2;
-    d.log2_cpp = l2;
-    d.d_slots = make_div32((uint32_t)(C / 8 + 1));
-    d.ncc = 1; d.bk = 64;
-    d.x_blk = x_blk; d.y_blk = y_blk;
-    d.regw_grid = tiles_m < cus[dev] ? tiles_m : cus[dev];
-    d.regw_ring_px = ring_px;
-    d.regw_ahead = ahead;
-    d.regw_bias_off = (int32_t)bias_off;
-    *out = d;
-    *lds_bytes = lds;
-    return true;
-}
-
 // Fills the launch parameters of direct kernel `k` for `pb` split into `splitk`
 // channel slices, or says why the kernel does not cover the problem.
 bool dconv_setup(const Problem &pb, const IgemmLaunch &k, int splitk, DconvParams *out, size_t *lds_bytes, std::string *why)
 {
-    if (k.stream == 3) return dregw_setup(pb, k, splitk, out, lds_bytes, why);
     if (k.stream == 2) return dplanar_setup(pb, k, splitk, out, lds_bytes, why);
     if (k.stream) return dstream_setup(pb, k, splitk, out, lds_bytes, why);
     auto no = [&](const char *m) { if (why) *why = m; return false; };

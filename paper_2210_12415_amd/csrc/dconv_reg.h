@@ -41,10 +41,3 @@
                                     ALT_BF16, BM, BN, BK, LOAD_VEC, LOAD_VEC, NS - 1, 1, 0, nullptr,             \
                                     &dstream_launch<BM, BN, WGM, WGN, KW, NS, BK, true>, WGM, WGN, KW, 1, 1}),   \
          true)
-
-// register-weights kernel (dregw.h): 128 x 64 tile, two pixel halves by two channel halves of waves, 3x3 filters
-#define ALT_DREGW()                                                                                              \
-    const bool reg_dregw_128 =                                                                                   \
-        (igemm_register(IgemmLaunch{"bf16_128x64x64_regw_w2x1x2", ALT_BF16, 128, 64, 64, LOAD_VEC, LOAD_VEC, 0,   \
-                                    0, 0, nullptr, &dregw_launch, 2, 1, 2, 3}),                                  \
-         true)

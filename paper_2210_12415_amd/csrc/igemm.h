@@ -659,7 +659,6 @@ struct IgemmLaunch {
     int kw = 1;               // its K groups (each a wave grid of its own over a share of the channels)
     int stream = 0;           // 1: both operands stream through LDS (dstream.h: 1x1 filters and GEMMs of any depth);
                               // 2: channel-planar operands converted on the way into LDS (dplanar.h)
-                              // 3: weights resident in registers, workgroups resident on the compute units (dregw.h)
     int bt = 0;               // streaming kernel: 1 = B stored [K][N] (row-major), read through LDS transpose reads
 };
 

@@ -197,14 +197,6 @@ double igemm_estimate(const Problem &pb, const IgemmLaunch &k, const IgemmParams
         const double clk = per_cu_work * busy + rounds * latency + 5000.0;
         return 0.5 * (clk / 2200.0 * 45.0);
     }
-    if (k.launch_direct && k.stream == 3) {
-        // Register-weights kernel: one resident workgroup per CU walks its tiles, after a prologue that brings
-        // the weights into registers.  Measured slower than the tile kernels so far: ranked behind them.
-        const double per_cu = std::ceil((double)p.tiles_m / 256.0);
-        const double tile = (double)k.BM * 64 * p.R * p.S * p.C / 16384.0 * 8.0 * 3.5;
-        const double clk = per_cu * tile + 20000.0;
-        return clk / 2200.0 * 45.0;
-    }
     double mode_cost = 1.0;
     if (k.amode == LOAD_GATHER) mode_cost *= 6.0;
     if (k.bmode == LOAD_GATHER) mode_cost *= 3.0;
