@@ -69,5 +69,5 @@ def test_bench_quick_run_ends_in_a_parsable_line():
     last = r.stdout.strip().splitlines()[-1]
     back = json.loads(last)
     assert len(last) < bench.MAX_LINE_BYTES
-    assert back["steps"] >= 20 and back["ms_per_step"] * back["steps"] >= 40.0      # timed for at least ~50 ms
+    assert back["steps"] >= 20 and back["ms_per_step"] * back["steps"] >= 45.0      # timed for at least ~50 ms
     assert back["roofline"]["bound"] == "mfma" and 0 < back["roofline"]["frac"] < 1
