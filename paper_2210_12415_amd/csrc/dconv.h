@@ -622,7 +622,14 @@ void dconv_kernel(const DconvParams p)
     const int spp = (1 << p.log2_cpp) + 1;                 // 16-byte slots per patch pixel
     const int pitch_b = spp * 16;
     const int nwl = (np * spp + 63) >> 6;                  // wave-loads (the region is padded to whole ones)
-    const int pz = (int)div32((uint32_t)((nwl << 6) + spp - 1), p.d_slots);   // the all-zero pixel row behind the patch
+    const int pz = (int)div32((uint32_t)((nwl << 6) + spp - 1), p.d_slots);   // the first pixel row behind the patch
+    // Behind the patch, at a multiple of 256 bytes (one pass over all banks), sits the zero area that taps
+    // outside the image read: 256 bytes and a pixel's channels of zeros.  A lane whose tap is outside reads it at
+    // the same offset modulo 256 as the pixel it would have read, i.e. from the same banks, so the lanes of an
+    // operand read stay on distinct banks as they are without padding (one zero pixel shared by all such lanes
+    // sits on the banks of some other lane's pixel: measured 170 against 245 bytes per clock with eight lanes
+    // on it).
+    const uint32_t zero0 = (patch0 + (uint32_t)(pz * pitch_b) + 255u) & ~255u;
     {
         const int g0 = a0 - halo;
         auto load_one = [&](int j) {
@@ -638,7 +645,8 @@ void dconv_kernel(const DconvParams p)
             load_one(j); load_one(j + NW); load_one(j + 2 * NW); load_one(j + 3 * NW);
         }
         for (; j < nwl; j += NW) load_one(j);
-        if (t < spp - 1) ((uint4 *)((char *)smem_u4 + KW * B_RING + pz * pitch_b))[t] = make_uint4(0, 0, 0, 0);
+        for (int i = t; i < 16 + (p.Cs >> 3) + 2; i += 64 * NW)
+            *(uint4 *)((char *)smem_u4 + (zero0 - lds0) + i * 16) = make_uint4(0, 0, 0, 0);
     }
 
     // ---- weights: slot s = (i*NWG + wq)*64 + lane of a stage holds chunk (s % CPR) ^ swz(row) of row s / CPR
@@ -726,8 +734,8 @@ void dconv_kernel(const DconvParams p)
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const bool ok = (unsigned)(row_oh[i] + dr) < (unsigned)p.H && (unsigned)(row_ow[i] + ds) < (unsigned)p.W;
-            const int px = ok ? row_px[i] + shift : pz;
-            sa.a_row[i] = patch0 + (uint32_t)(px * pitch_b) + khalf;
+            const uint32_t at = patch0 + (uint32_t)((row_px[i] + shift) * pitch_b);
+            sa.a_row[i] = (ok ? at : zero0 + (at & 255u)) + khalf;
         }
     };
     // Operand reads run D k-chunks ahead of the MFMAs that use them, each k-chunk in a
@@ -920,14 +928,15 @@ inline size_t dconv_patch_pixels(int BM, int64_t M, int H, int W, int OH, int OW
 }
 
 // LDS bytes of one workgroup: the K groups' weight rings, the patch rounded up to
-// whole wave-loads, the all-zero row.
+// whole wave-loads, the zero area.
 // np = the largest patch of any tile, in pixels (dconv_patch_pixels).
 inline size_t dconv_lds_bytes(int BM, int BN, int NS, int waves_n, int kw, int bk, int Cs, size_t np)
 {
     const size_t spp = (size_t)Cs / 8 + 1;                 // 16-byte slots per patch pixel (one unused)
     const size_t nwl = (np * spp + 63) / 64;
-    const size_t pz = (nwl * 64 + spp - 1) / spp;          // the zero row sits behind the whole wave-loads
-    const size_t main_loop = (size_t)kw * NS * BN * bk * 2 + (pz + 1) * spp * 16;
+    const size_t pz = (nwl * 64 + spp - 1) / spp;          // the zero area sits behind the whole wave-loads,
+    // at the next multiple of 256 bytes: 256 bytes, a pixel's channels and the two K halves' reach
+    const size_t main_loop = ((size_t)kw * NS * BN * bk * 2 + pz * spp * 16 + 255) / 256 * 256 + 512 + (size_t)Cs * 2 + 32;
     // output staging: per K group [BM][BN + 8 floats per wave column], + the split-K flag
     const size_t staging = (size_t)kw * BM * (BN + 8 * waves_n) * 4 + 16;
     return main_loop > staging ? main_loop : staging;
