@@ -60,7 +60,8 @@ constexpr int planar_stage_bytes(int BN) { return BN * kPlanarWP + 16; }
 inline size_t dplanar_lds_bytes(int BM, int BN, int kw, int taps, int C, size_t np)
 {
     const size_t npr = (np + 7) / 8 * 8;
-    const size_t main_loop = (size_t)taps * planar_stage_bytes(BN) + (npr + 1) * ((size_t)C * 2 + 16);
+    // (the zero area behind the patch: at the next multiple of 256 bytes, 256 bytes and a pixel's channels)
+    const size_t main_loop = ((size_t)taps * planar_stage_bytes(BN) + npr * ((size_t)C * 2 + 16) + 255) / 256 * 256 + 512 + (size_t)C * 2 + 32;
     // output staging: [channel][pixel] (NCHW output) or [pixel][channel] (NHWC output), the larger of the two
     const size_t staging = std::max((size_t)kw * BN * (BM + 4) * 4, (size_t)kw * BM * (BN + 4) * 4);
     return main_loop > staging ? main_loop : staging;
@@ -146,9 +147,12 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dplanar_kernel(const Dcon
     const int a0 = anchor(m0);
     const int np = anchor(min(m0 + BM, p.M) - 1) - a0 + 1 + halo + halo_hi;
     const int npr = (np + 7) & ~7;                         // whole blocks of eight pixels
-    const int pz = npr;                                    // the all-zero pixel behind them
     const int pitch_b = p.C * 2 + 16;
     char *patch = smem + RS * WST;
+    // behind the patch, at a multiple of 256 bytes: the zero area that taps outside the image read, each lane at
+    // the offset modulo 256 (i.e. on the banks) of the pixel it would have read (see dconv.h)
+    const uint32_t patch_a = (uint32_t)(uintptr_t)patch;
+    const uint32_t zero0 = (patch_a + (uint32_t)(npr * pitch_b) + 255u) & ~255u;
     {
         // Work items: (pixel block of eight, channel block of eight), one per lane: the lane loads its eight
         // planes' runs, transposes them 8x8 in registers and writes eight 16-byte channel chunks.  A set of 64
@@ -257,7 +261,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dplanar_kernel(const Dcon
                 item_store(a, blk, nx, str_a);
             }
         }
-        if (t < (p.C >> 3)) *(uint4 *)(patch + (size_t)pz * pitch_b + t * 16) = make_uint4(0, 0, 0, 0);
+        for (int i = t; i < 16 + (p.C >> 3) + 2; i += NT)
+            *(uint4 *)(patch + (zero0 - patch_a) + i * 16) = make_uint4(0, 0, 0, 0);
     }
     scatter_w();
     const int nsb = p.C >> 6;
@@ -282,7 +287,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dplanar_kernel(const Dcon
         }
     }
     // LDS byte addresses of the operand rows: the patch row under every tap (rows whose tap falls
-    // outside the image use the zero pixel) and the weight rows, both at this lane's eight channels
+    // outside the image use the zero area) and the weight rows, both at this lane's eight channels
     // of this K group's first 16-channel chunk.
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const uint32_t khalf = (lane >> 5) * 16 + kg * 32;
@@ -294,8 +299,8 @@ __global__ __launch_bounds__(64 * WGM * WGN * KW) void dplanar_kernel(const Dcon
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const bool ok = (unsigned)(row_oh[i] + dr) < (unsigned)p.H && (unsigned)(row_ow[i] + ds) < (unsigned)p.W;
-            const int px = ok ? row_px[i] + shift : pz;
-            t_row[tap][i] = lds0 + RS * WST + (uint32_t)(px * pitch_b) + khalf;
+            const uint32_t at = lds0 + RS * WST + (uint32_t)((row_px[i] + shift) * pitch_b);
+            t_row[tap][i] = (ok ? at : zero0 + (at & 255u)) + khalf;
         }
     }
     uint32_t b_rd[TN];
